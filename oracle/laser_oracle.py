@@ -1,0 +1,171 @@
+"""Plain fp64 CPU checker for the STA + GSTA forward pass of LASER (arxiv 2602.11562).
+
+TEST INFRASTRUCTURE ONLY. This module is the slow, obviously-correct statement
+of what the path computes. It is imported by the tests, by the smoke check and
+by the benchmark's CPU-baseline leg, never by the product package, and it shares
+no code with the HIP kernels. All arithmetic is float64 numpy; `numpy.dot` /
+`@` serve as the matmul step, everything else is written out.
+
+Notation (paper, Sec. 3.1, 3.4.2, 3.4.3): one user has a history of L items; item j
+has key K[j] in R^{d_q} and value V[j] in R^{d}; a candidate (target item) has query
+Q in R^{d_q} (Q = t W_q) and target vector t in R^{d}; w is the segment length,
+L' = S = ceil(L / w) segments, gamma the STA score scale, M = L_stack GSTA layers.
+
+Readings where the paper is silent (listed in full in the design notes):
+  * valid length: items j >= len are tail padding; their gate is exactly 0;
+  * L not a multiple of w: the last segment is short;
+  * GSTA: segments with no valid item are left out of the softmax; when no
+    segment is valid the layer output is 0 (so z = t);
+  * GSTA scale is sqrt(d) with d the embedding dim; single head; H' is the same
+    in every layer; weights differ per layer; y = x @ W.
+
+Pin status: every function below is pinned by tests/test_oracle_pins.py (brute
+force written independently, closed forms, invariants, and reduction to library
+softmax / matmul calls). No function here is "parity unpinned".
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+
+def num_segments(L: int, w: int) -> int:
+    """L' of split_seq (Sec. 3.4.2, first equation): windows of w consecutive items."""
+    return -(-int(L) // int(w))
+
+
+def segment_counts(lens, L: int, w: int) -> np.ndarray:
+    """cnt[u, i] = number of valid items (j < len[u]) inside segment i = [i*w, min((i+1)*w, L))."""
+    lens = np.asarray(lens, dtype=np.int64).reshape(-1)
+    S = num_segments(L, w)
+    cnt = np.zeros((lens.shape[0], S), dtype=np.int32)
+    for u in range(lens.shape[0]):
+        n = min(max(int(lens[u]), 0), L)
+        for i in range(S):
+            lo = i * w
+            hi = min((i + 1) * w, L)
+            cnt[u, i] = max(0, min(hi, n) - lo)
+    return cnt
+
+
+def sigmoid(x: np.ndarray) -> np.ndarray:
+    """Logistic function 1 / (1 + exp(-x)), evaluated without overflow on either side."""
+    x = np.asarray(x, dtype=np.float64)
+    out = np.empty_like(x)
+    pos = x >= 0
+    out[pos] = 1.0 / (1.0 + np.exp(-x[pos]))
+    ex = np.exp(x[~pos])
+    out[~pos] = ex / (1.0 + ex)
+    return out
+
+
+def sta_segment(Q: np.ndarray, K_seg: np.ndarray, V_seg: np.ndarray, gamma: float) -> np.ndarray:
+    """s_i = Sigmoid(Q K^T / gamma) V for one segment (Sec. 3.4.2, STA equation).
+
+    Q [d_q], K_seg [n, d_q], V_seg [n, d] hold only the valid items of the segment.
+    """
+    d = V_seg.shape[1]
+    if K_seg.shape[0] == 0:
+        return np.zeros(d, dtype=np.float64)
+    alpha = sigmoid((K_seg @ Q) / gamma)          # one independent gate per item
+    return alpha @ V_seg
+
+
+def sta_pair(Q: np.ndarray, K: np.ndarray, V: np.ndarray, length: int, w: int, gamma: float) -> np.ndarray:
+    """H' [S, d] of one (user, candidate): the segment loop of Sec. 3.4.2 in its naive form."""
+    L = K.shape[0]
+    S = num_segments(L, w)
+    n = min(max(int(length), 0), L)
+    Hp = np.zeros((S, V.shape[1]), dtype=np.float64)
+    for i in range(S):
+        lo = i * w
+        hi = min(min((i + 1) * w, L), n)
+        if hi > lo:
+            Hp[i] = sta_segment(Q, K[lo:hi], V[lo:hi], gamma)
+    return Hp
+
+
+def sta_pair_global(Q: np.ndarray, K: np.ndarray, V: np.ndarray, length: int, w: int, gamma: float) -> np.ndarray:
+    """Same H', in the deployment form of Sec. 3.5.1: global gates alpha in R^{1 x L},
+    reshape R(.) to (L' x 1 x w) and (L' x w x d), one batched matmul, squeeze.
+    Rows past the end of the history (and past the valid length) enter with gate 0."""
+    L, d = V.shape
+    S = num_segments(L, w)
+    n = min(max(int(length), 0), L)
+    alpha = sigmoid((Q @ K.T) / gamma)            # [L]
+    alpha[n:] = 0.0
+    A_hat = np.zeros((S * w,), dtype=np.float64)
+    A_hat[:L] = alpha
+    V_hat = np.zeros((S * w, d), dtype=np.float64)
+    V_hat[:L] = V
+    V_hat[n:L] = 0.0                              # gate 0 must also silence non-finite padding
+    A_hat = A_hat.reshape(S, 1, w)
+    V_hat = V_hat.reshape(S, w, d)
+    return np.matmul(A_hat, V_hat).reshape(S, d)
+
+
+def gsta_pair(Hp: np.ndarray, t: np.ndarray, Wq: np.ndarray, Wk: np.ndarray, Wv: np.ndarray,
+              seg_valid: np.ndarray) -> np.ndarray:
+    """z = t_M for one (user, candidate) (Sec. 3.4.3, attention equation and residual update).
+
+    Hp [S, d]; t [d]; Wq, Wk, Wv [M, d, d]; seg_valid [S] bool (segment has >= 1 valid item).
+    """
+    S, d = Hp.shape
+    M = Wq.shape[0]
+    t_l = np.array(t, dtype=np.float64)
+    idx = np.flatnonzero(np.asarray(seg_valid))
+    for l in range(M):
+        if idx.size == 0:
+            continue                                # o_l = 0
+        Hv = Hp[idx]                                # valid segments only
+        qp = t_l @ Wq[l]                            # t_{l-1} W_q^l
+        Kp = Hv @ Wk[l]                             # H' W_k^l
+        Vp = Hv @ Wv[l]                             # H' W_v^l
+        e = (Kp @ qp) / math.sqrt(d)
+        e = e - e.max()
+        p = np.exp(e)
+        a = p / p.sum()                             # softmax over segments
+        o = a @ Vp
+        t_l = t_l + o                               # t_l = t_{l-1} + o_l
+    return t_l
+
+
+def sta_forward(q, k, v, lens, w: int, gamma: float, global_form: bool = False):
+    """H' [U, C, S, d] and cnt [U, S] for a batch. q [U,C,d_q], k [U,L,d_q], v [U,L,d], lens [U] or None."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    U, C, _ = q.shape
+    L, d = v.shape[1], v.shape[2]
+    lens = np.full(U, L, dtype=np.int64) if lens is None else np.asarray(lens, dtype=np.int64)
+    S = num_segments(L, w)
+    one = sta_pair_global if global_form else sta_pair
+    Hp = np.zeros((U, C, S, d), dtype=np.float64)
+    for u in range(U):
+        for c in range(C):
+            Hp[u, c] = one(q[u, c], k[u], v[u], int(lens[u]), w, gamma)
+    return Hp, segment_counts(lens, L, w)
+
+
+def gsta_forward(Hp, t0, wq, wk, wv, cnt) -> np.ndarray:
+    """z [U, C, d] for a batch. Hp [U,C,S,d], t0 [U,C,d], w* [M,d,d], cnt [U,S]."""
+    Hp = np.asarray(Hp, dtype=np.float64)
+    t0 = np.asarray(t0, dtype=np.float64)
+    wq = np.asarray(wq, dtype=np.float64)
+    wk = np.asarray(wk, dtype=np.float64)
+    wv = np.asarray(wv, dtype=np.float64)
+    U, C, S, d = Hp.shape
+    z = np.zeros((U, C, d), dtype=np.float64)
+    for u in range(U):
+        valid = np.asarray(cnt[u]) > 0
+        for c in range(C):
+            z[u, c] = gsta_pair(Hp[u, c], t0[u, c], wq, wk, wv, valid)
+    return z
+
+
+def laser_forward(q, k, v, t0, wq, wk, wv, lens, w: int, gamma: float):
+    """STA followed by GSTA. Returns (H' [U,C,S,d], cnt [U,S], z [U,C,d])."""
+    Hp, cnt = sta_forward(q, k, v, lens, w, gamma)
+    z = gsta_forward(Hp, t0, wq, wk, wv, cnt)
+    return Hp, cnt, z

@@ -1,0 +1,321 @@
+"""Pins for the fp64 checker: it is compared with things other than itself.
+
+  P1  brute force written here element by element with math.exp (no numpy arithmetic)
+  P2  the paper's own equivalence: per-segment loop (Sec. 3.4.2) == global gates + reshape + bmm (Sec. 3.5.1)
+  P3  invariants that follow from the STA equation: permutation inside a segment, locality, silence,
+      single segment == plain gated target attention
+  P4  closed forms (Q=0 -> half-sum, V=1 -> sum of gates, saturated gates -> sum pooling, W_q=0 -> mean, ...)
+  P5  reduction to library routines (torch softmax / scaled_dot_product_attention, scipy expit)
+  P6  exact re-association of the GSTA products
+  P8  planted mistakes in the checker are caught by P1 (shows the pins have teeth)
+"""
+import math
+import types
+
+import numpy as np
+import pytest
+import scipy.special
+import torch
+
+import oracle
+from oracle import laser_oracle as lo
+
+
+def _rand(shape, seed, scale=1.0):
+    return np.random.default_rng(seed).standard_normal(shape) * scale
+
+
+# --------------------------------------------------------------------------- P1
+def brute_force(q, k, v, t0, wq, wk, wv, lens, w, gamma):
+    """Every output element from scalar Python arithmetic; follows Sec. 3.4.2 / 3.4.3 directly."""
+    U, C, dq = len(q), len(q[0]), len(q[0][0])
+    L, d = len(v[0]), len(v[0][0])
+    M = len(wq)
+    S = (L + w - 1) // w
+    Hp = [[[[0.0] * d for _ in range(S)] for _ in range(C)] for _ in range(U)]
+    cnt = [[0] * S for _ in range(U)]
+    z = [[[0.0] * d for _ in range(C)] for _ in range(U)]
+    for u in range(U):
+        for i in range(S):
+            cnt[u][i] = sum(1 for j in range(i * w, min((i + 1) * w, L)) if j < lens[u])
+        for c in range(C):
+            for i in range(S):
+                for j in range(i * w, min((i + 1) * w, L)):
+                    if j >= lens[u]:
+                        continue
+                    e = sum(q[u][c][a] * k[u][j][a] for a in range(dq)) / gamma
+                    g = 1.0 / (1.0 + math.exp(-e))
+                    for b in range(d):
+                        Hp[u][c][i][b] += g * v[u][j][b]
+            t = list(t0[u][c])
+            for l in range(M):
+                segs = [i for i in range(S) if cnt[u][i] > 0]
+                if not segs:
+                    continue
+                qp = [sum(t[a] * wq[l][a][b] for a in range(d)) for b in range(d)]
+                sc = []
+                vals = []
+                for i in segs:
+                    kp = [sum(Hp[u][c][i][a] * wk[l][a][b] for a in range(d)) for b in range(d)]
+                    vp = [sum(Hp[u][c][i][a] * wv[l][a][b] for a in range(d)) for b in range(d)]
+                    sc.append(sum(qp[b] * kp[b] for b in range(d)) / math.sqrt(d))
+                    vals.append(vp)
+                mx = max(sc)
+                ex = [math.exp(s - mx) for s in sc]
+                den = sum(ex)
+                for b in range(d):
+                    t[b] = t[b] + sum(ex[n] / den * vals[n][b] for n in range(len(segs)))
+            z[u][c] = t
+    return np.array(Hp), np.array(cnt), np.array(z)
+
+
+TINY = [
+    # U, C, L, w, dq, d, M, lens
+    (1, 2, 5, 2, 3, 2, 2, [4]),        # short last segment + one masked tail item
+    (2, 3, 7, 3, 2, 4, 1, [7, 2]),     # second user: only first segment (partly) valid
+    (2, 1, 6, 6, 4, 3, 3, [0, 6]),     # one user with no history at all; single segment
+    (1, 2, 9, 4, 5, 5, 2, [9]),        # full length, L % w != 0
+]
+
+
+def _tiny_inputs(case, seed):
+    U, C, L, w, dq, d, M, lens = case
+    q = _rand((U, C, dq), seed + 1)
+    k = _rand((U, L, dq), seed + 2)
+    v = _rand((U, L, d), seed + 3)
+    t0 = _rand((U, C, d), seed + 4)
+    wq = _rand((M, d, d), seed + 5, 0.8)
+    wk = _rand((M, d, d), seed + 6, 0.8)
+    wv = _rand((M, d, d), seed + 7, 0.8)
+    return q, k, v, t0, wq, wk, wv, np.array(lens), w
+
+
+@pytest.mark.parametrize("case", TINY)
+@pytest.mark.parametrize("gamma", [1.0, 1.7])
+def test_p1_brute_force(case, gamma):
+    q, k, v, t0, wq, wk, wv, lens, w = _tiny_inputs(case, 11)
+    Hb, cb, zb = brute_force(q.tolist(), k.tolist(), v.tolist(), t0.tolist(), wq.tolist(), wk.tolist(),
+                             wv.tolist(), lens.tolist(), w, gamma)
+    Ho, co, zo = oracle.laser_forward(q, k, v, t0, wq, wk, wv, lens, w, gamma)
+    assert np.array_equal(cb, co)
+    np.testing.assert_allclose(Ho, Hb, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(zo, zb, rtol=1e-11, atol=1e-12)
+
+
+def test_segment_counts_by_enumeration():
+    for L, w in [(10, 3), (8, 4), (7, 10), (1, 1), (10000, 256), (33, 32)]:
+        lens = np.minimum(np.array([0, 1, w - 1 if w > 1 else 0, w, w + 1, L - 1, L]), L)
+        cnt = oracle.segment_counts(lens, L, w)
+        S = oracle.num_segments(L, w)
+        assert cnt.shape == (len(lens), S)
+        for u, n in enumerate(lens):
+            exp = [sum(1 for j in range(i * w, min((i + 1) * w, L)) if j < n) for i in range(S)]
+            assert cnt[u].tolist() == exp
+            assert cnt[u].sum() == n
+    # out-of-range lengths are clamped to [0, L]
+    assert oracle.segment_counts([-3, 99], 8, 4).tolist() == [[0, 0], [4, 4]]
+
+
+# --------------------------------------------------------------------------- P2
+@pytest.mark.parametrize("L,w,n", [(64, 8, 64), (70, 8, 70), (70, 8, 37), (50, 64, 50), (33, 1, 20)])
+def test_p2_naive_equals_global_reshape_form(L, w, n):
+    dq, d = 6, 10
+    Q, K, V = _rand(dq, 1), _rand((L, dq), 2), _rand((L, d), 3)
+    a = oracle.sta_pair(Q, K, V, n, w, 1.3)
+    b = oracle.sta_pair_global(Q, K, V, n, w, 1.3)
+    np.testing.assert_allclose(a, b, rtol=1e-13, atol=1e-13)
+
+
+# --------------------------------------------------------------------------- P3
+def test_p3_permutation_inside_a_segment_leaves_output_unchanged():
+    L, w, dq, d = 48, 16, 5, 7
+    Q, K, V = _rand(dq, 4), _rand((L, dq), 5), _rand((L, d), 6)
+    base = oracle.sta_pair(Q, K, V, L, w, 2.0)
+    perm = np.arange(L)
+    perm[16:32] = 16 + np.random.default_rng(0).permutation(16)
+    out = oracle.sta_pair(Q, K[perm], V[perm], L, w, 2.0)
+    np.testing.assert_allclose(out, base, rtol=1e-12, atol=1e-13)
+    # a permutation that moves items ACROSS segments must change the result (the test can fail)
+    perm2 = np.arange(L)
+    perm2[[0, 40]] = [40, 0]
+    out2 = oracle.sta_pair(Q, K[perm2], V[perm2], L, w, 2.0)
+    assert np.abs(out2 - base).max() > 1e-3
+
+
+def test_p3_perturbing_one_segment_changes_only_that_segment():
+    L, w, dq, d = 40, 8, 4, 6
+    Q, K, V = _rand(dq, 7), _rand((L, dq), 8), _rand((L, d), 9)
+    base = oracle.sta_pair(Q, K, V, L, w, 1.0)
+    K2, V2 = K.copy(), V.copy()
+    K2[16:24] += 1.0
+    V2[16:24] *= -2.0
+    out = oracle.sta_pair(Q, K2, V2, L, w, 1.0)
+    changed = np.abs(out - base).max(axis=1) > 0
+    assert changed.tolist() == [False, False, True, False, False]
+
+
+def test_p3_gate_driven_to_zero_silences_the_segment():
+    L, w, dq, d = 24, 8, 4, 5
+    Q, K, V = _rand(dq, 10), _rand((L, dq), 11), _rand((L, d), 12)
+    qhat = Q / np.linalg.norm(Q)
+    K[8:16] = -200.0 * qhat
+    out = oracle.sta_pair(Q, K, V, L, w, 1.0)
+    assert np.abs(out[1]).max() < 1e-30
+    assert np.abs(out[0]).max() > 1e-2 and np.abs(out[2]).max() > 1e-2
+
+
+def test_p3_single_segment_is_plain_gated_target_attention():
+    L, dq, d = 30, 6, 4
+    Q, K, V = _rand(dq, 13), _rand((L, dq), 14), _rand((L, d), 15)
+    for w in (30, 31, 1000):
+        out = oracle.sta_pair(Q, K, V, L, w, 1.5)
+        assert out.shape == (1, d)
+        ref = scipy.special.expit(Q @ K.T / 1.5) @ V
+        np.testing.assert_allclose(out[0], ref, rtol=1e-13, atol=1e-14)
+
+
+# --------------------------------------------------------------------------- P4
+def test_p4_zero_query_gives_half_sum():
+    L, w, dq, d = 20, 6, 3, 4
+    K, V = _rand((L, dq), 16), _rand((L, d), 17)
+    n = 15
+    out = oracle.sta_pair(np.zeros(dq), K, V, n, w, 1.0)
+    for i in range(4):
+        lo, hi = i * w, min((i + 1) * w, n)
+        np.testing.assert_allclose(out[i], 0.5 * V[lo:hi].sum(0) if hi > lo else 0.0, rtol=1e-14, atol=1e-15)
+
+
+def test_p4_unit_values_give_sum_of_gates_and_gamma_divides_the_score():
+    L, w, dq, d = 12, 4, 3, 5
+    Q, K = _rand(dq, 18), _rand((L, dq), 19)
+    gamma = 2.5
+    out = oracle.sta_pair(Q, K, np.ones((L, d)), L, w, gamma)
+    for i in range(3):
+        g = sum(1.0 / (1.0 + math.exp(-float(Q @ K[j]) / gamma)) for j in range(i * w, (i + 1) * w))
+        np.testing.assert_allclose(out[i], g, rtol=1e-14)
+
+
+def test_p4_saturated_gates_give_sum_pooling():
+    L, w, dq, d = 16, 8, 4, 3
+    Q = _rand(dq, 20)
+    K = np.tile(100.0 * Q / (Q @ Q), (L, 1))
+    V = _rand((L, d), 21)
+    out = oracle.sta_pair(Q, K, V, L, w, 1.0)
+    np.testing.assert_allclose(out, V.reshape(2, 8, d).sum(1), rtol=1e-13, atol=1e-13)
+
+
+def test_p4_gsta_closed_forms():
+    S, d, M = 6, 5, 3
+    Hp, t = _rand((S, d), 22), _rand(d, 23)
+    Wq, Wk, Wv = _rand((M, d, d), 24), _rand((M, d, d), 25), _rand((M, d, d), 26)
+    valid = np.array([True, True, True, True, False, False])
+    # W_q = 0 -> uniform softmax -> o_l = mean over valid segments of H' W_v^l; residuals add up
+    z = oracle.gsta_pair(Hp, t, np.zeros_like(Wq), Wk, Wv, valid)
+    np.testing.assert_allclose(z, t + sum(Hp[:4].mean(0) @ Wv[l] for l in range(M)), rtol=1e-13, atol=1e-13)
+    # exactly one valid segment -> a = 1 -> z = t + sum_l H'_0 W_v^l
+    one = np.array([True] + [False] * 5)
+    z = oracle.gsta_pair(Hp, t, Wq, Wk, Wv, one)
+    np.testing.assert_allclose(z, t + sum(Hp[0] @ Wv[l] for l in range(M)), rtol=1e-13, atol=1e-13)
+    # W_v = 0 -> z = t ; no valid segment -> z = t
+    np.testing.assert_array_equal(oracle.gsta_pair(Hp, t, Wq, Wk, np.zeros_like(Wv), valid), t)
+    np.testing.assert_array_equal(oracle.gsta_pair(Hp, t, Wq, Wk, Wv, np.zeros(S, bool)), t)
+    # invalid segments never matter, whatever they hold
+    Hp2 = Hp.copy()
+    Hp2[4:] = 1e6
+    np.testing.assert_array_equal(oracle.gsta_pair(Hp2, t, Wq, Wk, Wv, valid),
+                                  oracle.gsta_pair(Hp, t, Wq, Wk, Wv, valid))
+
+
+def test_p4_empty_history_gives_zero_segments_and_z_equals_t():
+    q, k, v = _rand((1, 2, 3), 27), _rand((1, 9, 3), 28), _rand((1, 9, 4), 29)
+    t0 = _rand((1, 2, 4), 30)
+    W = _rand((2, 4, 4), 31)
+    Hp, cnt, z = oracle.laser_forward(q, k, v, t0, W, W, W, np.array([0]), 4, 1.0)
+    assert not Hp.any() and not cnt.any()
+    np.testing.assert_array_equal(z, t0)
+
+
+# --------------------------------------------------------------------------- P5
+@pytest.mark.parametrize("sharp", [1.0, 30.0])
+def test_p5_one_gsta_layer_is_masked_single_query_sdpa(sharp):
+    S, d = 9, 8
+    Hp, t = _rand((S, d), 32), _rand(d, 33)
+    Wq, Wk, Wv = _rand((1, d, d), 34) * sharp, _rand((1, d, d), 35), _rand((1, d, d), 36)
+    valid = np.array([True] * 6 + [False] * 3)
+    z = oracle.gsta_pair(Hp, t, Wq, Wk, Wv, valid)
+    tq = torch.from_numpy(t @ Wq[0]).reshape(1, 1, 1, d)
+    tk = torch.from_numpy(Hp @ Wk[0]).reshape(1, 1, S, d)
+    tv = torch.from_numpy(Hp @ Wv[0]).reshape(1, 1, S, d)
+    mask = torch.from_numpy(valid).reshape(1, 1, 1, S)
+    o = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask, scale=1.0 / math.sqrt(d))
+    np.testing.assert_allclose(z, t + o.reshape(d).numpy(), rtol=1e-12, atol=1e-12)
+    # and the explicit softmax call
+    logits = torch.from_numpy((Hp[:6] @ Wk[0]) @ (t @ Wq[0]) / math.sqrt(d))
+    a = torch.softmax(logits, dim=0).numpy()
+    np.testing.assert_allclose(z, t + a @ (Hp[:6] @ Wv[0]), rtol=1e-12, atol=1e-12)
+
+
+def test_p5_sigmoid_matches_library_expit_over_a_wide_range():
+    x = np.concatenate([np.linspace(-700, 700, 4001), _rand(1000, 37, 5.0)])
+    np.testing.assert_allclose(oracle.sigmoid(x), scipy.special.expit(x), rtol=4e-16, atol=0)
+    assert oracle.sigmoid(np.array([0.0]))[0] == 0.5
+
+
+def test_p5_batch_sta_with_one_segment_is_two_matmuls_and_expit():
+    U, C, L, dq, d = 2, 3, 17, 4, 6
+    q, k, v = _rand((U, C, dq), 38), _rand((U, L, dq), 39), _rand((U, L, d), 40)
+    Hp, cnt = oracle.sta_forward(q, k, v, None, L, 2.0)
+    ref = scipy.special.expit(np.einsum("uca,uja->ucj", q, k) / 2.0) @ v
+    np.testing.assert_allclose(Hp[:, :, 0], ref, rtol=1e-13, atol=1e-13)
+    assert cnt.tolist() == [[L], [L]]
+
+
+# --------------------------------------------------------------------------- P6
+def test_p6_gsta_products_can_be_reassociated():
+    S, d = 12, 16
+    Hp, t = _rand((S, d), 41), _rand(d, 42)
+    Wq, Wk, Wv = _rand((d, d), 43), _rand((d, d), 44), _rand((d, d), 45)
+    e1 = (Hp @ Wk) @ (t @ Wq)
+    e2 = Hp @ (Wk @ (t @ Wq))
+    np.testing.assert_allclose(e1, e2, rtol=1e-12, atol=1e-12)
+    a = scipy.special.softmax(e1 / math.sqrt(d))
+    np.testing.assert_allclose(a @ (Hp @ Wv), (a @ Hp) @ Wv, rtol=1e-12, atol=1e-12)
+
+
+# --------------------------------------------------------------------------- P8
+def _p1_error(monkeypatch_fn):
+    """max abs difference between (possibly sabotaged) checker and the brute force over the tiny cases."""
+    worst = 0.0
+    for case in TINY:
+        q, k, v, t0, wq, wk, wv, lens, w = _tiny_inputs(case, 11)
+        Hb, cb, zb = brute_force(q.tolist(), k.tolist(), v.tolist(), t0.tolist(), wq.tolist(), wk.tolist(),
+                                 wv.tolist(), lens.tolist(), w, 1.7)
+        Ho, co, zo = lo.laser_forward(q, k, v, t0, wq, wk, wv, lens, w, 1.7)
+        worst = max(worst, np.abs(Ho - Hb).max(), np.abs(zo - zb).max(), float(np.abs(co - cb).max()))
+    return worst
+
+
+def test_p8_planted_mistakes_are_caught(monkeypatch):
+    assert _p1_error(None) < 1e-11
+    real_sigmoid, real_sqrt, real_segment, real_gsta = lo.sigmoid, math.sqrt, lo.sta_segment, lo.gsta_pair
+
+    mutants = {
+        "softmax instead of sigmoid": ("sigmoid", lambda x: np.exp(x - x.max()) / np.exp(x - x.max()).sum()),
+        "sign of the score": ("sigmoid", lambda x: real_sigmoid(-x)),
+        "gamma dropped": ("sta_segment", lambda Q, K, V, g: real_segment(Q, K, V, 1.0)),
+        "gamma multiplies": ("sta_segment", lambda Q, K, V, g: real_segment(Q, K, V, 1.0 / g)),
+        "transposed W_q": ("gsta_pair", lambda H, t, a, b, c, m: real_gsta(H, t, a.transpose(0, 2, 1), b, c, m)),
+        "transposed W_v": ("gsta_pair", lambda H, t, a, b, c, m: real_gsta(H, t, a, b, c.transpose(0, 2, 1), m)),
+        "W_k and W_v swapped": ("gsta_pair", lambda H, t, a, b, c, m: real_gsta(H, t, a, c, b, m)),
+        "residual dropped": ("gsta_pair", lambda H, t, a, b, c, m: real_gsta(H, t, a, b, c, m) - t),
+        "mask ignored in GSTA": ("gsta_pair", lambda H, t, a, b, c, m: real_gsta(H, t, a, b, c, np.ones_like(m))),
+    }
+    for name, (attr, fn) in mutants.items():
+        with monkeypatch.context() as mp:
+            mp.setattr(lo, attr, fn)
+            assert _p1_error(None) > 1e-4, f"planted mistake not detected: {name}"
+    # scale sqrt(d) -> d
+    with monkeypatch.context() as mp:
+        mp.setattr(lo, "math", types.SimpleNamespace(sqrt=lambda x: x))
+        assert _p1_error(None) > 1e-4
+    assert _p1_error(None) < 1e-11
