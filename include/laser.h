@@ -1,0 +1,139 @@
+/*
+ * laser.h - C ABI of the MI355X (gfx950) implementation of LASER's hot path
+ * (arxiv 2602.11562): Segmented Target Attention (STA) over a long per-user
+ * behaviour history, then Global Stacked Target Attention (GSTA) over the
+ * compressed segments.
+ *
+ * Problem statement (paper Sec. 3.1, generalised from one target item to the C
+ * candidates a ranking request scores for one user): a user u has a history of
+ * up to L items; item j carries a key K[u,j,:] in R^{d_q} and a value V[u,j,:]
+ * in R^{d} (K = H W_k, V = H W_v, already projected); candidate c carries a
+ * query Q[u,c,:] in R^{d_q} (Q = t W_q) and a target vector t[u,c,:] in R^{d}.
+ *
+ * Conventions for every entry point
+ *   - Every data pointer is a DEVICE pointer (HBM), caller-owned, row-major,
+ *     contiguous, 16-byte aligned. Nothing is copied to or from the host.
+ *   - The library allocates nothing, keeps no state and never synchronises: work
+ *     is enqueued on `stream` (a hipStream_t; NULL = the default stream).
+ *   - Outputs are overwritten in full, including exact zeros for empty segments.
+ *   - Return value only; no exception or abort crosses the ABI. Arguments are
+ *     validated on the host before anything is launched, so an error return means
+ *     no kernel ran. `lens` is device data and cannot be checked on the host: each
+ *     value is clamped to [0, L] on the device.
+ *   - dtype `dt` is the storage type of q, k, v, t0, the GSTA weights and H'
+ *     (LASER_F32 or LASER_BF16). Arithmetic accumulates in fp32. z is always fp32.
+ *   - Segment i covers items [i*w, min((i+1)*w, L)); S = ceil(L / w).
+ *     Item j of user u is valid iff j < lens[u]. Padded rows are never multiplied
+ *     in, so they may hold anything, including NaN or Inf.
+ */
+#ifndef LASER_H_
+#define LASER_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LASER_OK = 0,
+  LASER_ERR_NULL = 1,        /* a required pointer is NULL                       */
+  LASER_ERR_SHAPE = 2,       /* a size is <= 0, too large, or inconsistent       */
+  LASER_ERR_DTYPE = 3,       /* dt is not a laser_dtype                          */
+  LASER_ERR_UNSUPPORTED = 4, /* valid request that no kernel here implements     */
+  LASER_ERR_LAUNCH = 5,      /* the HIP runtime refused a launch                 */
+  LASER_ERR_ALIGN = 6        /* a pointer is not 16-byte aligned                 */
+} laser_status;
+
+typedef enum { LASER_F32 = 0, LASER_BF16 = 1 } laser_dtype;
+
+/* Which STA kernel runs. AUTO picks by (dt, C, d_q, d, w); the others force one
+ * and return LASER_ERR_UNSUPPORTED when the shape is outside that kernel's range. */
+typedef enum {
+  LASER_STA_AUTO = 0,
+  LASER_STA_GENERIC = 1, /* fp32 FMA, any shape, either dtype                        */
+  LASER_STA_MFMA = 2,    /* bf16 MFMA, many candidates per user                      */
+  LASER_STA_STREAM = 3   /* bf16, few candidates per user, HBM streaming             */
+} laser_sta_variant;
+
+/* Which GSTA kernel runs. */
+typedef enum {
+  LASER_GSTA_AUTO = 0,
+  LASER_GSTA_GENERIC = 1, /* fp32 FMA, one workgroup per pair, any shape              */
+  LASER_GSTA_TILED = 2    /* bf16 storage, a tile of pairs per workgroup, MFMA        */
+} laser_gsta_variant;
+
+/*
+ * Segmented Target Attention, forward (paper Sec. 3.4.2, the STA equation
+ *   s_i = Sigmoid(Q K_i^T / gamma) V_i,
+ * in the "global scores, then per-segment aggregation" form of Sec. 3.5.1):
+ *   seg_out[u,c,i,:] = sum over valid j in segment i of
+ *                      sigmoid(dot(q[u,c,:], k[u,j,:]) / gamma) * v[u,j,:]
+ *   seg_cnt[u,i]     = number of valid items in segment i
+ *
+ *   q       [U,C,d_q]  candidate queries
+ *   k       [U,L,d_q]  history keys
+ *   v       [U,L,d]    history values
+ *   lens    [U] int32  valid lengths; NULL means every user has L valid items
+ *   gamma   score scale (> 0); the paper leaves its value open
+ *   seg_out [U,C,S,d]  H', dtype dt (fp32 sums rounded once to dt)
+ *   seg_cnt [U,S] int32, may be NULL
+ * Limits: U,C,L,d_q,d,w >= 1; d_q, d <= 1024 and multiples of 8; every tensor < 2^31 elements.
+ */
+laser_status laser_sta_forward(const void* q, const void* k, const void* v, const int32_t* lens,
+                               int U, int C, int L, int d_q, int d, int w, float gamma, laser_dtype dt,
+                               void* seg_out, int32_t* seg_cnt, void* stream);
+
+/* Same operation with the kernel chosen by the caller (tests and benchmarks). */
+laser_status laser_sta_forward_variant(const void* q, const void* k, const void* v, const int32_t* lens,
+                                       int U, int C, int L, int d_q, int d, int w, float gamma, laser_dtype dt,
+                                       void* seg_out, int32_t* seg_cnt, void* stream, laser_sta_variant variant);
+
+/*
+ * Global Stacked Target Attention, forward (paper Sec. 3.4.3): for l = 1..M
+ *   a_l = softmax((t_{l-1} W_q^l)(H' W_k^l)^T / sqrt(d)),  o_l = a_l (H' W_v^l),  t_l = t_{l-1} + o_l
+ * with t_0 = t0 and z = t_M. The softmax runs over the segments of user u that hold at
+ * least one valid item (the first ceil(lens[u] / w)); with none, z = t0.
+ *
+ *   seg   [U,C,S,d]  H' (dtype dt), S = ceil(L / w)
+ *   t0    [U,C,d]    target vectors (dtype dt)
+ *   wq, wk, wv [M,d,d] each (dtype dt), applied as y = x W (row vector times matrix)
+ *   lens  [U] int32 or NULL (all L)
+ *   z_out [U,C,d] fp32
+ * Limits: d <= 1024 and a multiple of 8; S <= 4096; M >= 1.
+ */
+laser_status laser_gsta_forward(const void* seg, const void* t0, const void* wq, const void* wk, const void* wv,
+                                const int32_t* lens, int U, int C, int L, int d, int w, int M, laser_dtype dt,
+                                float* z_out, void* stream);
+
+laser_status laser_gsta_forward_variant(const void* seg, const void* t0, const void* wq, const void* wk,
+                                        const void* wv, const int32_t* lens, int U, int C, int L, int d, int w,
+                                        int M, laser_dtype dt, float* z_out, void* stream,
+                                        laser_gsta_variant variant);
+
+/*
+ * The whole path: STA, then GSTA on the segment vectors it produced (paper Sec. 3.2,
+ * "compress-then-refine"; the per-segment FFN + LayerNorm of Sec. 3.4.2 is not applied,
+ * which is the paper's "-FFN+LayerNorm" ablation variant). Arguments as above; seg_out
+ * [U,C,S,d] is required (it is the buffer GSTA reads), seg_cnt may be NULL.
+ * GSTA consumes H' as stored in seg_out, i.e. after rounding to dt.
+ */
+laser_status laser_forward(const void* q, const void* k, const void* v, const void* t0,
+                           const void* wq, const void* wk, const void* wv, const int32_t* lens,
+                           int U, int C, int L, int d_q, int d, int w, float gamma, int M, laser_dtype dt,
+                           void* seg_out, int32_t* seg_cnt, float* z_out, void* stream);
+
+/* Name of the STA / GSTA kernel AUTO would pick for a shape (static strings; host only, no GPU needed). */
+const char* laser_sta_kernel_name(int C, int d_q, int d, int w, laser_dtype dt);
+const char* laser_gsta_kernel_name(int C, int S, int d, laser_dtype dt);
+
+/* Static, human-readable name of a status code. Never NULL. */
+const char* laser_status_string(laser_status s);
+
+/* Library version as major * 10000 + minor * 100 + patch. */
+int laser_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LASER_H_ */

@@ -1,0 +1,189 @@
+"""Thin ctypes binding over liblaser.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (include/laser.h).
+Tensors are PyTorch device tensors used purely as owners of HBM allocations; the
+current torch stream is handed to the library. There is no fallback: if the
+shared library is missing or an entry point reports an error, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblaser.so")
+
+LASER_F32, LASER_BF16 = 0, 1
+STA_AUTO, STA_GENERIC, STA_MFMA, STA_STREAM = 0, 1, 2, 3
+GSTA_AUTO, GSTA_GENERIC, GSTA_TILED = 0, 1, 2
+
+EXPORTS = [
+    "laser_sta_forward", "laser_sta_forward_variant", "laser_gsta_forward", "laser_gsta_forward_variant",
+    "laser_forward", "laser_sta_kernel_name", "laser_gsta_kernel_name", "laser_status_string", "laser_version",
+]
+
+
+class LaserError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {status_string(code)} (status {code})")
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """dlopen liblaser.so (built by paper_2602_11562_amd.build) and declare the prototypes."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2602_11562_amd.build` "
+                          "(there is no CPU or PyTorch fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, ip, i32, f32 = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+    lib.laser_sta_forward.argtypes = [vp, vp, vp, ip, i32, i32, i32, i32, i32, i32, f32, i32, vp, ip, vp]
+    lib.laser_sta_forward_variant.argtypes = lib.laser_sta_forward.argtypes + [i32]
+    lib.laser_gsta_forward.argtypes = [vp, vp, vp, vp, vp, ip, i32, i32, i32, i32, i32, i32, i32, vp, vp]
+    lib.laser_gsta_forward_variant.argtypes = lib.laser_gsta_forward.argtypes + [i32]
+    lib.laser_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, ip, i32, i32, i32, i32, i32, i32, f32, i32, i32,
+                                  vp, ip, vp, vp]
+    for name in ("laser_sta_forward", "laser_sta_forward_variant", "laser_gsta_forward",
+                 "laser_gsta_forward_variant", "laser_forward", "laser_version"):
+        getattr(lib, name).restype = i32
+    lib.laser_sta_kernel_name.argtypes = [i32, i32, i32, i32, i32]
+    lib.laser_sta_kernel_name.restype = ctypes.c_char_p
+    lib.laser_gsta_kernel_name.argtypes = [i32, i32, i32, i32]
+    lib.laser_gsta_kernel_name.restype = ctypes.c_char_p
+    lib.laser_status_string.argtypes = [i32]
+    lib.laser_status_string.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def status_string(code: int) -> str:
+    return load_library().laser_status_string(int(code)).decode()
+
+
+def laser_version() -> int:
+    return int(load_library().laser_version())
+
+
+def laser_sta_kernel_name(C: int, d_q: int, d: int, w: int, dt: int) -> str:
+    return load_library().laser_sta_kernel_name(C, d_q, d, w, dt).decode()
+
+
+def laser_gsta_kernel_name(C: int, S: int, d: int, dt: int) -> str:
+    return load_library().laser_gsta_kernel_name(C, S, d, dt).decode()
+
+
+# ----------------------------------------------------------------------------- tensor marshalling
+def _torch():
+    import torch
+    return torch
+
+
+def _dt(t) -> int:
+    torch = _torch()
+    if t.dtype == torch.float32:
+        return LASER_F32
+    if t.dtype == torch.bfloat16:
+        return LASER_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t, name: str, dtype=None) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live in device memory")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    torch = _torch()
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream or None
+
+
+def _check(code: int, where: str) -> None:
+    if code != 0:
+        raise LaserError(code, where)
+
+
+def laser_sta_forward(q, k, v, lens, w: int, gamma: float, seg_out=None, seg_cnt=None, stream=None,
+                      variant: int = STA_AUTO, want_cnt: bool = True):
+    """q [U,C,d_q], k [U,L,d_q], v [U,L,d], lens int32 [U] or None -> (H' [U,C,S,d], cnt [U,S] or None)."""
+    torch = _torch()
+    U, C, d_q = q.shape
+    L, d = v.shape[1], v.shape[2]
+    if k.shape != (U, L, d_q) or v.shape[0] != U:
+        raise ValueError("q, k, v shapes disagree")
+    if k.dtype != q.dtype or v.dtype != q.dtype:
+        raise TypeError("q, k, v must share a dtype")
+    S = -(-L // w)
+    if seg_out is None:
+        seg_out = torch.empty((U, C, S, d), dtype=q.dtype, device=q.device)
+    elif tuple(seg_out.shape) != (U, C, S, d) or seg_out.dtype != q.dtype:
+        raise ValueError("seg_out must be [U,C,S,d] in the input dtype")
+    if seg_cnt is None and want_cnt:
+        seg_cnt = torch.empty((U, S), dtype=torch.int32, device=q.device)
+    if lens is not None and tuple(lens.shape) != (U,):
+        raise ValueError("lens must be [U]")
+    code = load_library().laser_sta_forward_variant(
+        _ptr(q, "q"), _ptr(k, "k"), _ptr(v, "v"), _ptr(lens, "lens", torch.int32), U, C, L, d_q, d, int(w),
+        float(gamma), _dt(q), _ptr(seg_out, "seg_out"), _ptr(seg_cnt, "seg_cnt", torch.int32), _stream(stream),
+        int(variant))
+    _check(code, "laser_sta_forward")
+    return seg_out, seg_cnt
+
+
+def laser_gsta_forward(seg, t0, wq, wk, wv, lens, L: int, w: int, z_out=None, stream=None,
+                       variant: int = GSTA_AUTO):
+    """seg [U,C,S,d], t0 [U,C,d], w* [M,d,d], lens int32 [U] or None -> z [U,C,d] fp32."""
+    torch = _torch()
+    U, C, S, d = seg.shape
+    M = wq.shape[0]
+    if S != -(-L // w):
+        raise ValueError("seg.shape[2] must be ceil(L / w)")
+    if tuple(t0.shape) != (U, C, d) or any(tuple(x.shape) != (M, d, d) for x in (wq, wk, wv)):
+        raise ValueError("t0 / weight shapes disagree with seg")
+    if any(x.dtype != seg.dtype for x in (t0, wq, wk, wv)):
+        raise TypeError("seg, t0 and the weights must share a dtype")
+    if z_out is None:
+        z_out = torch.empty((U, C, d), dtype=torch.float32, device=seg.device)
+    code = load_library().laser_gsta_forward_variant(
+        _ptr(seg, "seg"), _ptr(t0, "t0"), _ptr(wq, "wq"), _ptr(wk, "wk"), _ptr(wv, "wv"),
+        _ptr(lens, "lens", torch.int32), U, C, int(L), d, int(w), M, _dt(seg), _ptr(z_out, "z_out", torch.float32),
+        _stream(stream), int(variant))
+    _check(code, "laser_gsta_forward")
+    return z_out
+
+
+def laser_forward(q, k, v, t0, wq, wk, wv, lens, w: int, gamma: float, seg_out=None, seg_cnt=None, z_out=None,
+                  stream=None, want_cnt: bool = True):
+    """The whole path. Returns (H' [U,C,S,d], cnt [U,S] or None, z [U,C,d] fp32)."""
+    torch = _torch()
+    U, C, d_q = q.shape
+    L, d = v.shape[1], v.shape[2]
+    M = wq.shape[0]
+    S = -(-L // w)
+    if seg_out is None:
+        seg_out = torch.empty((U, C, S, d), dtype=q.dtype, device=q.device)
+    if seg_cnt is None and want_cnt:
+        seg_cnt = torch.empty((U, S), dtype=torch.int32, device=q.device)
+    if z_out is None:
+        z_out = torch.empty((U, C, d), dtype=torch.float32, device=q.device)
+    if any(x.dtype != q.dtype for x in (k, v, t0, wq, wk, wv, seg_out)):
+        raise TypeError("all inputs and seg_out must share a dtype")
+    code = load_library().laser_forward(
+        _ptr(q, "q"), _ptr(k, "k"), _ptr(v, "v"), _ptr(t0, "t0"), _ptr(wq, "wq"), _ptr(wk, "wk"), _ptr(wv, "wv"),
+        _ptr(lens, "lens", torch.int32), U, C, L, d_q, d, int(w), float(gamma), M, _dt(q), _ptr(seg_out, "seg_out"),
+        _ptr(seg_cnt, "seg_cnt", torch.int32), _ptr(z_out, "z_out", torch.float32), _stream(stream))
+    _check(code, "laser_forward")
+    return seg_out, seg_cnt, z_out

@@ -1,0 +1,173 @@
+// Host side of the C ABI: argument validation (GPU-free), kernel selection, launches.
+#include "laser_internal.h"
+
+namespace laser {
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static laser_status check_dims(int U, int C, int L, int d_q, int d, int w) {
+  if (U <= 0 || C <= 0 || L <= 0 || d_q <= 0 || d <= 0 || w <= 0) return LASER_ERR_SHAPE;
+  if (d_q > 1024 || d > 1024 || (d_q % 8) != 0 || (d % 8) != 0) return LASER_ERR_SHAPE;
+  const long long S = ((long long)L + w - 1) / w;
+  const long long lim = 0x7fffffffLL;
+  if ((long long)U * C * d_q > lim || (long long)U * L * d_q > lim || (long long)U * L * d > lim ||
+      (long long)U * C * S * d > lim || (long long)U * S > lim)
+    return LASER_ERR_SHAPE;
+  return LASER_OK;
+}
+
+static laser_status validate_sta(const void* q, const void* k, const void* v, const int32_t* lens, int U, int C,
+                                 int L, int d_q, int d, int w, float gamma, laser_dtype dt, void* seg_out,
+                                 int32_t* seg_cnt, void* stream, StaArgs* out) {
+  if (!q || !k || !v || !seg_out) return LASER_ERR_NULL;
+  if (dt != LASER_F32 && dt != LASER_BF16) return LASER_ERR_DTYPE;
+  laser_status s = check_dims(U, C, L, d_q, d, w);
+  if (s != LASER_OK) return s;
+  if (!(gamma > 0.0f) || !(gamma < INFINITY)) return LASER_ERR_SHAPE;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(seg_out)) return LASER_ERR_ALIGN;
+  if ((lens && (reinterpret_cast<uintptr_t>(lens) & 3u)) || (seg_cnt && (reinterpret_cast<uintptr_t>(seg_cnt) & 3u)))
+    return LASER_ERR_ALIGN;
+  *out = StaArgs{q, k, v, lens, U, C, L, d_q, d, w, (L + w - 1) / w, gamma, dt, seg_out, seg_cnt,
+                 static_cast<hipStream_t>(stream)};
+  return LASER_OK;
+}
+
+static laser_status validate_gsta(const void* seg, const void* t0, const void* wq, const void* wk, const void* wv,
+                                  const int32_t* lens, int U, int C, int L, int d, int w, int M, laser_dtype dt,
+                                  float* z_out, void* stream, GstaArgs* out) {
+  if (!seg || !t0 || !wq || !wk || !wv || !z_out) return LASER_ERR_NULL;
+  if (dt != LASER_F32 && dt != LASER_BF16) return LASER_ERR_DTYPE;
+  laser_status s = check_dims(U, C, L, d, d, w);
+  if (s != LASER_OK) return s;
+  const int S = (L + w - 1) / w;
+  if (M <= 0 || M > 64 || S > 4096) return LASER_ERR_SHAPE;
+  if (!aligned16(seg) || !aligned16(t0) || !aligned16(wq) || !aligned16(wk) || !aligned16(wv) || !aligned16(z_out))
+    return LASER_ERR_ALIGN;
+  if (lens && (reinterpret_cast<uintptr_t>(lens) & 3u)) return LASER_ERR_ALIGN;
+  *out = GstaArgs{seg, t0, wq, wk, wv, lens, U, C, L, d, w, S, M, dt, z_out, static_cast<hipStream_t>(stream)};
+  return LASER_OK;
+}
+
+static laser_sta_variant pick_sta(const StaArgs& a) {
+  if (sta_stream_supports(a)) return LASER_STA_STREAM;
+  if (sta_mfma_supports(a)) return LASER_STA_MFMA;
+  return LASER_STA_GENERIC;
+}
+
+static laser_gsta_variant pick_gsta(const GstaArgs& a) {
+  return gsta_tiled_supports(a) ? LASER_GSTA_TILED : LASER_GSTA_GENERIC;
+}
+
+static laser_status run_sta(const StaArgs& a, laser_sta_variant variant) {
+  if (variant == LASER_STA_AUTO) variant = pick_sta(a);
+  laser_status s;
+  switch (variant) {
+    case LASER_STA_GENERIC: s = sta_generic_launch(a); break;
+    case LASER_STA_MFMA: s = sta_mfma_launch(a); break;
+    case LASER_STA_STREAM: s = sta_stream_launch(a); break;
+    default: return LASER_ERR_UNSUPPORTED;
+  }
+  if (s != LASER_OK) return s;
+  if (a.seg_cnt) s = seg_cnt_launch(a.lens, a.U, a.L, a.w, a.S, a.seg_cnt, a.stream);
+  return s;
+}
+
+static laser_status run_gsta(const GstaArgs& a, laser_gsta_variant variant) {
+  if (variant == LASER_GSTA_AUTO) variant = pick_gsta(a);
+  switch (variant) {
+    case LASER_GSTA_GENERIC: return gsta_generic_launch(a);
+    case LASER_GSTA_TILED: return gsta_tiled_launch(a);
+    default: return LASER_ERR_UNSUPPORTED;
+  }
+}
+
+}  // namespace laser
+
+using namespace laser;
+
+extern "C" {
+
+laser_status laser_sta_forward_variant(const void* q, const void* k, const void* v, const int32_t* lens, int U,
+                                       int C, int L, int d_q, int d, int w, float gamma, laser_dtype dt,
+                                       void* seg_out, int32_t* seg_cnt, void* stream, laser_sta_variant variant) {
+  StaArgs a;
+  laser_status s = validate_sta(q, k, v, lens, U, C, L, d_q, d, w, gamma, dt, seg_out, seg_cnt, stream, &a);
+  if (s != LASER_OK) return s;
+  if (variant < LASER_STA_AUTO || variant > LASER_STA_STREAM) return LASER_ERR_UNSUPPORTED;
+  return run_sta(a, variant);
+}
+
+laser_status laser_sta_forward(const void* q, const void* k, const void* v, const int32_t* lens, int U, int C,
+                               int L, int d_q, int d, int w, float gamma, laser_dtype dt, void* seg_out,
+                               int32_t* seg_cnt, void* stream) {
+  return laser_sta_forward_variant(q, k, v, lens, U, C, L, d_q, d, w, gamma, dt, seg_out, seg_cnt, stream,
+                                   LASER_STA_AUTO);
+}
+
+laser_status laser_gsta_forward_variant(const void* seg, const void* t0, const void* wq, const void* wk,
+                                        const void* wv, const int32_t* lens, int U, int C, int L, int d, int w,
+                                        int M, laser_dtype dt, float* z_out, void* stream,
+                                        laser_gsta_variant variant) {
+  GstaArgs a;
+  laser_status s = validate_gsta(seg, t0, wq, wk, wv, lens, U, C, L, d, w, M, dt, z_out, stream, &a);
+  if (s != LASER_OK) return s;
+  if (variant < LASER_GSTA_AUTO || variant > LASER_GSTA_TILED) return LASER_ERR_UNSUPPORTED;
+  return run_gsta(a, variant);
+}
+
+laser_status laser_gsta_forward(const void* seg, const void* t0, const void* wq, const void* wk, const void* wv,
+                                const int32_t* lens, int U, int C, int L, int d, int w, int M, laser_dtype dt,
+                                float* z_out, void* stream) {
+  return laser_gsta_forward_variant(seg, t0, wq, wk, wv, lens, U, C, L, d, w, M, dt, z_out, stream,
+                                    LASER_GSTA_AUTO);
+}
+
+laser_status laser_forward(const void* q, const void* k, const void* v, const void* t0, const void* wq,
+                           const void* wk, const void* wv, const int32_t* lens, int U, int C, int L, int d_q, int d,
+                           int w, float gamma, int M, laser_dtype dt, void* seg_out, int32_t* seg_cnt, float* z_out,
+                           void* stream) {
+  StaArgs sa;
+  GstaArgs ga;
+  laser_status s = validate_sta(q, k, v, lens, U, C, L, d_q, d, w, gamma, dt, seg_out, seg_cnt, stream, &sa);
+  if (s != LASER_OK) return s;
+  s = validate_gsta(seg_out, t0, wq, wk, wv, lens, U, C, L, d, w, M, dt, z_out, stream, &ga);
+  if (s != LASER_OK) return s;   // both validated before the first launch
+  s = run_sta(sa, LASER_STA_AUTO);
+  if (s != LASER_OK) return s;
+  return run_gsta(ga, LASER_GSTA_AUTO);
+}
+
+const char* laser_sta_kernel_name(int C, int d_q, int d, int w, laser_dtype dt) {
+  StaArgs a{};
+  a.U = 1; a.C = C; a.L = w > 0 ? w : 1; a.d_q = d_q; a.d = d; a.w = w; a.S = 1; a.gamma = 1.0f; a.dt = dt;
+  if (C <= 0 || d_q <= 0 || d <= 0 || w <= 0 || (dt != LASER_F32 && dt != LASER_BF16)) return "invalid";
+  switch (pick_sta(a)) {
+    case LASER_STA_MFMA: return "sta_mfma_bf16";
+    case LASER_STA_STREAM: return "sta_stream_bf16";
+    default: return "sta_generic";
+  }
+}
+
+const char* laser_gsta_kernel_name(int C, int S, int d, laser_dtype dt) {
+  GstaArgs a{};
+  a.U = 1; a.C = C; a.L = S; a.w = 1; a.S = S; a.d = d; a.M = 1; a.dt = dt;
+  if (C <= 0 || S <= 0 || d <= 0 || (dt != LASER_F32 && dt != LASER_BF16)) return "invalid";
+  return pick_gsta(a) == LASER_GSTA_TILED ? "gsta_tiled_bf16" : "gsta_generic";
+}
+
+const char* laser_status_string(laser_status s) {
+  switch (s) {
+    case LASER_OK: return "ok";
+    case LASER_ERR_NULL: return "required pointer is NULL";
+    case LASER_ERR_SHAPE: return "invalid or inconsistent size";
+    case LASER_ERR_DTYPE: return "unknown dtype";
+    case LASER_ERR_UNSUPPORTED: return "shape not supported by the requested kernel";
+    case LASER_ERR_LAUNCH: return "HIP launch failed";
+    case LASER_ERR_ALIGN: return "pointer not sufficiently aligned";
+  }
+  return "unknown status";
+}
+
+int laser_version(void) { return 100; }
+
+}  // extern "C"

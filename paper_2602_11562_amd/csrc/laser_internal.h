@@ -1,0 +1,96 @@
+// Internal declarations shared by the host entry points and the kernel launchers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "laser.h"
+
+namespace laser {
+
+// Problem sizes after validation. S = ceil(L / w).
+struct StaArgs {
+  const void* q;
+  const void* k;
+  const void* v;
+  const int32_t* lens;
+  int U, C, L, d_q, d, w, S;
+  float gamma;
+  laser_dtype dt;
+  void* seg_out;
+  int32_t* seg_cnt;
+  hipStream_t stream;
+};
+
+struct GstaArgs {
+  const void* seg;
+  const void* t0;
+  const void* wq;
+  const void* wk;
+  const void* wv;
+  const int32_t* lens;
+  int U, C, L, d, w, S, M;
+  laser_dtype dt;
+  float* z_out;
+  hipStream_t stream;
+};
+
+// Each launcher returns LASER_ERR_UNSUPPORTED (launching nothing) when the shape is outside its range.
+bool sta_generic_supports(const StaArgs& a);
+laser_status sta_generic_launch(const StaArgs& a);
+bool sta_mfma_supports(const StaArgs& a);
+laser_status sta_mfma_launch(const StaArgs& a);
+bool sta_stream_supports(const StaArgs& a);
+laser_status sta_stream_launch(const StaArgs& a);
+
+bool gsta_generic_supports(const GstaArgs& a);
+laser_status gsta_generic_launch(const GstaArgs& a);
+bool gsta_tiled_supports(const GstaArgs& a);
+laser_status gsta_tiled_launch(const GstaArgs& a);
+
+// seg_cnt[u, i] (integer, exact); used by every STA variant.
+laser_status seg_cnt_launch(const int32_t* lens, int U, int L, int w, int S, int32_t* seg_cnt, hipStream_t stream);
+
+inline laser_status launch_status() { return hipGetLastError() == hipSuccess ? LASER_OK : LASER_ERR_LAUNCH; }
+
+// ---------------------------------------------------------------- device helpers
+__device__ __forceinline__ float bf16_bits_to_f32(unsigned short b) { return __uint_as_float(((unsigned int)b) << 16); }
+
+// Round-to-nearest-even float -> bfloat16 bits (hardware conversion on gfx950).
+__device__ __forceinline__ unsigned short f32_to_bf16_bits(float x) {
+  __bf16 h = (__bf16)x;
+  return __builtin_bit_cast(unsigned short, h);
+}
+
+template <typename T>
+__device__ __forceinline__ float load_as_f32(const T* p, size_t i);
+template <>
+__device__ __forceinline__ float load_as_f32<float>(const float* p, size_t i) { return p[i]; }
+template <>
+__device__ __forceinline__ float load_as_f32<unsigned short>(const unsigned short* p, size_t i) {
+  return bf16_bits_to_f32(p[i]);
+}
+
+template <typename T>
+__device__ __forceinline__ void store_from_f32(T* p, size_t i, float x);
+template <>
+__device__ __forceinline__ void store_from_f32<float>(float* p, size_t i, float x) { p[i] = x; }
+template <>
+__device__ __forceinline__ void store_from_f32<unsigned short>(unsigned short* p, size_t i, float x) {
+  p[i] = f32_to_bf16_bits(x);
+}
+
+// Valid length of user u, clamped to [0, L]; lens == nullptr means full length.
+__device__ __forceinline__ int valid_len(const int32_t* lens, int u, int L) {
+  if (lens == nullptr) return L;
+  int n = lens[u];
+  return n < 0 ? 0 : (n > L ? L : n);
+}
+
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
+  return x;
+}
+
+}  // namespace laser

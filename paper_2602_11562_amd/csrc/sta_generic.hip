@@ -1,0 +1,149 @@
+// Generic STA kernel: fp32 FMA arithmetic, any shape, fp32 or bf16 storage.
+//
+// Computes the STA equation of Sec. 3.4.2 in the global form of Sec. 3.5.1:
+//   H'[u,c,i,:] = sum_{valid j in segment i} sigmoid(q[u,c,:] . k[u,j,:] / gamma) * v[u,j,:]
+// One workgroup owns (user u, segment i, four candidates); each of its four waves owns one
+// candidate. The segment is walked in chunks of TI items that the workgroup stages in LDS as
+// fp32 (coalesced global reads, shared by the four candidates). Per chunk a wave first gives
+// one lane per item the score dot product and the gate, then gives one lane per value column
+// the gated sum over the chunk. Sums run over items in ascending order in fp32, so results
+// are deterministic. This is the correctness path (fp32 tolerance) and the fallback for shapes
+// the MFMA and streaming kernels do not take.
+#include "laser_internal.h"
+
+namespace laser {
+
+constexpr int GEN_WAVES = 4;
+constexpr int GEN_MAX_COLS = 16;  // d <= 64 * 16
+
+template <typename T>
+__global__ __launch_bounds__(256) void sta_generic_kernel(const T* __restrict__ q, const T* __restrict__ k,
+                                                          const T* __restrict__ v, const int32_t* __restrict__ lens,
+                                                          int C, int L, int dq, int d, int w, int S, int TI,
+                                                          float inv_gamma, T* __restrict__ seg_out) {
+  extern __shared__ float smem[];
+  const int kpitch = dq + 1;                   // +1: lanes read different rows at the same column
+  float* Ks = smem;                            // [TI][dq + 1]
+  float* Vs = Ks + (size_t)TI * kpitch;        // [TI][d]
+  float* qs = Vs + (size_t)TI * d;             // [4][dq]
+  float* gs = qs + GEN_WAVES * dq;             // [4][TI]
+
+  const int cblocks = (C + GEN_WAVES - 1) / GEN_WAVES;
+  int bid = blockIdx.x;
+  const int i = bid % S;
+  bid /= S;
+  const int cb = bid % cblocks;
+  const int u = bid / cblocks;
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int c = cb * GEN_WAVES + wave;
+  const bool active = c < C;
+
+  const int n = valid_len(lens, u, L);
+  const int lo = i * w;
+  int hi = lo + w;
+  if (hi > L) hi = L;
+  if (hi > n) hi = n;
+
+  for (int a = lane; a < dq; a += 64)
+    qs[wave * dq + a] = active ? load_as_f32(q, ((size_t)u * C + c) * dq + a) : 0.0f;
+
+  float acc[GEN_MAX_COLS];
+#pragma unroll
+  for (int b = 0; b < GEN_MAX_COLS; ++b) acc[b] = 0.0f;
+
+  const T* kU = k + (size_t)u * L * dq;
+  const T* vU = v + (size_t)u * L * d;
+
+  for (int j0 = lo; j0 < hi; j0 += TI) {
+    const int nj = (hi - j0) < TI ? (hi - j0) : TI;
+    __syncthreads();
+    for (int e = tid; e < nj * dq; e += 256) {
+      const int r = e / dq, a = e - r * dq;
+      Ks[r * kpitch + a] = load_as_f32(kU, (size_t)(j0 + r) * dq + a);
+    }
+    for (int e = tid; e < nj * d; e += 256) Vs[e] = load_as_f32(vU, (size_t)j0 * d + e);
+    __syncthreads();
+    if (lane < nj) {
+      float e = 0.0f;
+      const float* kr = Ks + lane * kpitch;
+      const float* qr = qs + wave * dq;
+      for (int a = 0; a < dq; ++a) e = fmaf(qr[a], kr[a], e);
+      gs[wave * TI + lane] = 1.0f / (1.0f + expf(-e * inv_gamma));   // independent gate per item
+    }
+    __syncthreads();
+    for (int jj = 0; jj < nj; ++jj) {
+      const float g = gs[wave * TI + jj];
+#pragma unroll
+      for (int b = 0; b < GEN_MAX_COLS; ++b) {
+        const int col = lane + 64 * b;
+        if (col < d) acc[b] = fmaf(g, Vs[jj * d + col], acc[b]);
+      }
+    }
+  }
+
+  if (active) {
+    const size_t base = (((size_t)u * C + c) * S + i) * d;
+#pragma unroll
+    for (int b = 0; b < GEN_MAX_COLS; ++b) {
+      const int col = lane + 64 * b;
+      if (col < d) store_from_f32(seg_out, base + col, acc[b]);
+    }
+  }
+}
+
+__global__ void seg_cnt_kernel(const int32_t* __restrict__ lens, int U, int L, int w, int S,
+                               int32_t* __restrict__ seg_cnt) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= U * S) return;
+  const int u = idx / S, i = idx - u * S;
+  const int n = valid_len(lens, u, L);
+  const int lo = i * w;
+  int hi = lo + w;
+  if (hi > L) hi = L;
+  if (hi > n) hi = n;
+  seg_cnt[idx] = hi > lo ? hi - lo : 0;
+}
+
+laser_status seg_cnt_launch(const int32_t* lens, int U, int L, int w, int S, int32_t* seg_cnt, hipStream_t stream) {
+  const int total = U * S;
+  hipLaunchKernelGGL(seg_cnt_kernel, dim3((total + 255) / 256), dim3(256), 0, stream, lens, U, L, w, S, seg_cnt);
+  return launch_status();
+}
+
+static size_t gen_lds_bytes(int TI, int dq, int d) {
+  return sizeof(float) * ((size_t)TI * (dq + 1) + (size_t)TI * d + GEN_WAVES * dq + GEN_WAVES * TI);
+}
+
+static int gen_pick_ti(int dq, int d) {
+  for (int ti = 64; ti >= 1; ti >>= 1)
+    if (gen_lds_bytes(ti, dq, d) <= 60 * 1024) return ti;
+  return 0;
+}
+
+bool sta_generic_supports(const StaArgs& a) {
+  if (a.d > 64 * GEN_MAX_COLS || a.d_q > 1024) return false;
+  if (gen_pick_ti(a.d_q, a.d) == 0) return false;
+  const long long blocks = (long long)a.U * ((a.C + GEN_WAVES - 1) / GEN_WAVES) * a.S;
+  return blocks <= 0x7fffffffLL;
+}
+
+laser_status sta_generic_launch(const StaArgs& a) {
+  if (!sta_generic_supports(a)) return LASER_ERR_UNSUPPORTED;
+  const int TI = gen_pick_ti(a.d_q, a.d);
+  const size_t lds = gen_lds_bytes(TI, a.d_q, a.d);
+  const unsigned blocks = (unsigned)((long long)a.U * ((a.C + GEN_WAVES - 1) / GEN_WAVES) * a.S);
+  const float inv_gamma = 1.0f / a.gamma;
+  if (a.dt == LASER_F32) {
+    hipLaunchKernelGGL(sta_generic_kernel<float>, dim3(blocks), dim3(256), lds, a.stream, (const float*)a.q,
+                       (const float*)a.k, (const float*)a.v, a.lens, a.C, a.L, a.d_q, a.d, a.w, a.S, TI, inv_gamma,
+                       (float*)a.seg_out);
+  } else {
+    hipLaunchKernelGGL(sta_generic_kernel<unsigned short>, dim3(blocks), dim3(256), lds, a.stream,
+                       (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens,
+                       a.C, a.L, a.d_q, a.d, a.w, a.S, TI, inv_gamma, (unsigned short*)a.seg_out);
+  }
+  return launch_status();
+}
+
+}  // namespace laser

@@ -1,0 +1,5 @@
+#include "laser_internal.h"
+namespace laser {
+bool sta_mfma_supports(const StaArgs&) { return false; }
+laser_status sta_mfma_launch(const StaArgs&) { return LASER_ERR_UNSUPPORTED; }
+}  // namespace laser

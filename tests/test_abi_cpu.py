@@ -1,0 +1,107 @@
+"""The C-ABI library without a GPU: it loads, exports every declared symbol, and rejects bad arguments
+on the host before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2602_11562_amd as laser
+from paper_2602_11562_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2602_11562_amd.build import build_library
+        build_library()
+    return laser.load_library()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "laser.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(laser_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_status_strings(lib):
+    assert laser.laser_version() >= 100
+    seen = {laser.status_string(c) for c in range(7)}
+    assert len(seen) == 7 and "ok" in seen
+    assert laser.status_string(99) == "unknown status"
+
+
+A = 0x10000  # any 16-byte aligned non-NULL value: validation fails before it could be dereferenced
+
+
+def _sta(lib, q=A, k=A, v=A, lens=None, U=2, C=3, L=64, dq=16, d=16, w=8, gamma=1.0, dt=1, out=A, cnt=None,
+         variant=0):
+    return lib.laser_sta_forward_variant(q, k, v, lens, U, C, L, dq, d, w, gamma, dt, out, cnt, None, variant)
+
+
+def _gsta(lib, seg=A, t0=A, wq=A, wk=A, wv=A, lens=None, U=2, C=3, L=64, d=16, w=8, M=1, dt=1, z=A, variant=0):
+    return lib.laser_gsta_forward_variant(seg, t0, wq, wk, wv, lens, U, C, L, d, w, M, dt, z, None, variant)
+
+
+def test_sta_argument_validation(lib):
+    NULL, SHAPE, DTYPE, UNSUP, ALIGN = 1, 2, 3, 4, 6
+    assert _sta(lib, q=None) == NULL and _sta(lib, k=None) == NULL and _sta(lib, v=None) == NULL
+    assert _sta(lib, out=None) == NULL
+    assert _sta(lib, dt=2) == DTYPE and _sta(lib, dt=-1) == DTYPE
+    for kw in ({"U": 0}, {"C": 0}, {"L": 0}, {"dq": 0}, {"d": 0}, {"w": 0}, {"w": -4}, {"U": -1},
+               {"d": 12}, {"dq": 20}, {"d": 2048}, {"gamma": 0.0}, {"gamma": -1.0}, {"gamma": float("nan")},
+               {"gamma": float("inf")},
+               {"U": 1 << 20, "L": 1 << 20},                 # element count overflows int32
+               {"U": 4096, "C": 4096, "L": 4096, "w": 1}):   # H' would overflow
+        assert _sta(lib, **kw) == SHAPE, kw
+    assert _sta(lib, q=A + 8) == ALIGN and _sta(lib, out=A + 2) == ALIGN and _sta(lib, lens=A + 2) == ALIGN
+    assert _sta(lib, cnt=A + 1) == ALIGN
+    assert _sta(lib, variant=7) == UNSUP and _sta(lib, variant=-1) == UNSUP
+    # the plain entry point validates the same way
+    assert lib.laser_sta_forward(None, A, A, None, 2, 3, 64, 16, 16, 8, 1.0, 1, A, None, None) == NULL
+
+
+def test_gsta_argument_validation(lib):
+    NULL, SHAPE, DTYPE, UNSUP, ALIGN = 1, 2, 3, 4, 6
+    for name in ("seg", "t0", "wq", "wk", "wv", "z"):
+        assert _gsta(lib, **{name: None}) == NULL
+    assert _gsta(lib, dt=5) == DTYPE
+    for kw in ({"M": 0}, {"M": 65}, {"d": 0}, {"d": 4}, {"w": 0}, {"L": 0}, {"U": 0}, {"C": -2},
+               {"L": 8192, "w": 1}):                         # S > 4096
+        assert _gsta(lib, **kw) == SHAPE, kw
+    assert _gsta(lib, wk=A + 4) == ALIGN and _gsta(lib, lens=A + 1) == ALIGN
+    assert _gsta(lib, variant=9) == UNSUP
+    assert lib.laser_gsta_forward(A, A, A, A, None, None, 2, 3, 64, 16, 8, 1, 1, A, None) == NULL
+
+
+def test_forward_validates_both_stages_before_launching(lib):
+    f = lib.laser_forward
+    ok_tail = (None, 2, 3, 64, 16, 16, 8, 1.0)
+    assert f(A, A, A, None, A, A, A, *ok_tail, 1, 1, A, None, A, None) == 1      # t0 NULL
+    assert f(A, A, A, A, A, A, A, *ok_tail, 1, 1, None, None, A, None) == 1      # seg_out NULL
+    assert f(A, A, A, A, A, A, A, *ok_tail, 1, 1, A, None, None, None) == 1      # z_out NULL
+    assert f(A, A, A, A, A, A, A, *ok_tail, 0, 1, A, None, A, None) == 2         # M = 0
+    assert f(A, A, A, A, A, A, A, *ok_tail, 1, 3, A, None, A, None) == 3         # dtype
+
+
+def test_kernel_names(lib):
+    assert laser.laser_sta_kernel_name(16, 64, 64, 64, laser.LASER_F32) == "sta_generic"
+    assert laser.laser_sta_kernel_name(0, 64, 64, 64, laser.LASER_F32) == "invalid"
+    assert laser.laser_gsta_kernel_name(16, 16, 64, laser.LASER_F32) == "gsta_generic"
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    x = torch.zeros(1, 2, 8)
+    with pytest.raises(ValueError):
+        laser.laser_sta_forward(x, torch.zeros(1, 4, 8), torch.zeros(1, 4, 8), None, 2, 1.0,
+                                seg_out=torch.zeros(1, 2, 2, 8), want_cnt=False)

@@ -1,0 +1,286 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 checker, element by element.
+
+Reduced copies of the five benchmark workloads (same dtype, d, w, C and structure, fewer users / shorter
+histories so the checker finishes in seconds, still several tiles and ragged tails), every kernel variant
+that accepts the shape, plus the edge cases of the method.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from workloads.configs import WorkloadSpec, make_workload
+
+from parity_util import TOL, DeviceWorkload, oracle_batch, round_like, to_device, to_host_f64, vec_rel_err
+
+pytestmark = pytest.mark.gpu
+
+laser = pytest.importorskip("paper_2602_11562_amd")
+
+STA_VARIANTS = {"auto": 0, "generic": 1, "mfma": 2, "stream": 3}
+GSTA_VARIANTS = {"auto": 0, "generic": 1, "tiled": 2}
+
+C = workloads.CONFIGS
+REDUCED = {
+    "cfg1": C["cfg1_tiny_f32"],                                            # full size
+    "cfg2": C["cfg2_bf16"].replace(U=6),
+    "cfg3": C["cfg3_high_fanout"].replace(U=2, L=1024 + 128),
+    "cfg4": C["cfg4_low_fanout"].replace(U=48),
+    "cfg5": C["cfg5_lifelong"].replace(U=1, L=2 * 256 + 16),               # short last segment of 16 items
+}
+
+
+def _run_sta(dw, variant, gamma=None, lens="wl"):
+    s = dw.spec
+    g = s.gamma if gamma is None else gamma
+    lens_t = dw.lens if lens == "wl" else lens
+    try:
+        return laser.laser_sta_forward(dw.q, dw.k, dw.v, lens_t, s.w, g, variant=variant)
+    except laser.LaserError as e:
+        if e.code == 4 and variant not in (0, 1):
+            pytest.skip("variant does not take this shape")
+        raise
+
+
+def _run_gsta(dw, seg, variant, lens="wl"):
+    s = dw.spec
+    lens_t = dw.lens if lens == "wl" else lens
+    try:
+        return laser.laser_gsta_forward(seg, dw.t0, dw.wq, dw.wk, dw.wv, lens_t, s.L, s.w, variant=variant)
+    except laser.LaserError as e:
+        if e.code == 4 and variant not in (0, 1):
+            pytest.skip("variant does not take this shape")
+        raise
+
+
+@pytest.fixture(scope="module")
+def cases():
+    cache = {}
+
+    def get(name):
+        if name not in cache:
+            wl = make_workload(REDUCED[name])
+            cache[name] = (wl, DeviceWorkload(wl), oracle_batch(wl))
+        return cache[name]
+    return get
+
+
+@pytest.mark.parametrize("variant", list(STA_VARIANTS))
+@pytest.mark.parametrize("name", list(REDUCED))
+def test_sta_matches_checker(cases, name, variant):
+    import torch
+    wl, dw, (Hp_ref, cnt_ref, _) = cases(name)
+    print(f"case {name} variant {variant} spec {wl.spec}", flush=True)
+    seg, cnt = _run_sta(dw, STA_VARIANTS[variant])
+    torch.cuda.synchronize()
+    assert np.array_equal(cnt.cpu().numpy(), cnt_ref)                       # integer work: bit-exact
+    err = vec_rel_err(to_host_f64(seg), Hp_ref)
+    print(f"  max vector-relative error {err:.3e}", flush=True)
+    assert err <= TOL[wl.spec.dtype]
+
+
+@pytest.mark.parametrize("variant", list(GSTA_VARIANTS))
+@pytest.mark.parametrize("name", list(REDUCED))
+def test_gsta_matches_checker_on_the_same_segments(cases, name, variant):
+    """GSTA alone: both sides start from the same stored H' (the checker's H' rounded to the storage type)."""
+    import torch
+    wl, dw, (Hp_ref, cnt_ref, _) = cases(name)
+    s = wl.spec
+    print(f"case {name} gsta variant {variant}", flush=True)
+    Hs = round_like(Hp_ref, s.dtype)
+    if s.dtype == "bf16":
+        seg_store = workloads.f32_to_bf16_bits(Hs.astype(np.float32))
+    else:
+        seg_store = Hs.astype(np.float32)
+    z = _run_gsta(dw, to_device(seg_store), GSTA_VARIANTS[variant])
+    torch.cuda.synchronize()
+    z_ref = oracle.gsta_forward(Hs, wl.f64("t0"), wl.f64("wq"), wl.f64("wk"), wl.f64("wv"), cnt_ref)
+    err = vec_rel_err(to_host_f64(z), z_ref)
+    print(f"  max vector-relative error {err:.3e}", flush=True)
+    assert err <= TOL[s.dtype]
+
+
+@pytest.mark.parametrize("name", list(REDUCED))
+def test_whole_path_matches_checker(cases, name):
+    import torch
+    wl, dw, (Hp_ref, cnt_ref, z_ref) = cases(name)
+    s = wl.spec
+    print(f"case {name} laser_forward", flush=True)
+    seg, cnt, z = laser.laser_forward(dw.q, dw.k, dw.v, dw.t0, dw.wq, dw.wk, dw.wv, dw.lens, s.w, s.gamma)
+    torch.cuda.synchronize()
+    assert np.array_equal(cnt.cpu().numpy(), cnt_ref)
+    e_seg = vec_rel_err(to_host_f64(seg), Hp_ref)
+    e_z = vec_rel_err(to_host_f64(z), z_ref)
+    print(f"  H' err {e_seg:.3e}  z err {e_z:.3e}", flush=True)
+    assert e_seg <= TOL[s.dtype] and e_z <= TOL[s.dtype]
+
+
+def test_results_are_bit_identical_run_to_run(cases):
+    import torch
+    for name in ("cfg1", "cfg2", "cfg3", "cfg4"):
+        wl, dw, _ = cases(name)
+        s = wl.spec
+        a = laser.laser_forward(dw.q, dw.k, dw.v, dw.t0, dw.wq, dw.wk, dw.wv, dw.lens, s.w, s.gamma)
+        b = laser.laser_forward(dw.q, dw.k, dw.v, dw.t0, dw.wq, dw.wk, dw.wv, dw.lens, s.w, s.gamma)
+        torch.cuda.synchronize()
+        assert torch.equal(a[0].view(torch.int16 if s.dtype == "bf16" else torch.int32),
+                           b[0].view(torch.int16 if s.dtype == "bf16" else torch.int32))
+        assert torch.equal(a[2].view(torch.int32), b[2].view(torch.int32))
+
+
+# ----------------------------------------------------------------------------------------- edge cases
+def _spec(dtype, U, Cn, L, d, dq, w, M, seed, **kw):
+    return WorkloadSpec(f"edge_{seed}", dtype, U=U, C=Cn, L=L, d=d, d_q=dq, w=w, M=M, lens_kind="full", seed=seed,
+                        **kw)
+
+
+EDGE_SPECS = {
+    "paper_default_w10": _spec("bf16", 2, 5, 1000, 128, 32, 10, 2, 2001),      # Sec. 4.1.2: L=1000, w=10, M=2
+    "paper_default_w10_f32": _spec("f32", 1, 3, 1000, 128, 32, 10, 2, 2002),
+    "w_equals_1": _spec("f32", 1, 2, 40, 16, 8, 1, 1, 2003),
+    "w_larger_than_L": _spec("bf16", 2, 7, 100, 64, 64, 256, 1, 2004),         # a single segment
+    "one_candidate": _spec("bf16", 5, 1, 700, 64, 64, 128, 1, 2005),
+    "odd_candidate_count": _spec("bf16", 2, 67, 640, 128, 128, 128, 1, 2006),
+    "dq_differs_from_d": _spec("bf16", 2, 64, 512, 128, 64, 128, 1, 2007),
+    "small_dims": _spec("f32", 2, 3, 50, 8, 8, 7, 3, 2008),
+    "three_layers_long_tail": _spec("bf16", 3, 33, 1300, 64, 64, 256, 3, 2009),
+}
+
+EDGE_LENS = {
+    "one_candidate": [0, 1, 127, 128, 700],
+    "three_layers_long_tail": [1299, 257, 0],
+    "odd_candidate_count": [640, 129],
+    "small_dims": [50, 13],
+}
+
+
+@pytest.mark.parametrize("sta_variant", list(STA_VARIANTS))
+@pytest.mark.parametrize("name", list(EDGE_SPECS))
+def test_edge_cases(name, sta_variant):
+    import torch
+    spec = EDGE_SPECS[name]
+    wl = make_workload(spec)
+    if name in EDGE_LENS:
+        wl.lens = np.array(EDGE_LENS[name], dtype=np.int32)
+    dw = DeviceWorkload(wl)
+    print(f"edge {name} sta variant {sta_variant} spec {spec} lens {wl.lens.tolist()}", flush=True)
+    Hp_ref, cnt_ref, z_ref = oracle_batch(wl)
+    seg, cnt = _run_sta(dw, STA_VARIANTS[sta_variant])
+    z = _run_gsta(dw, seg, 0)
+    torch.cuda.synchronize()
+    assert np.array_equal(cnt.cpu().numpy(), cnt_ref)
+    e_seg = vec_rel_err(to_host_f64(seg), Hp_ref)
+    e_z = vec_rel_err(to_host_f64(z), z_ref)
+    print(f"  H' err {e_seg:.3e}  z err {e_z:.3e}", flush=True)
+    assert e_seg <= TOL[spec.dtype] and e_z <= TOL[spec.dtype]
+
+
+@pytest.mark.parametrize("sta_variant", list(STA_VARIANTS))
+def test_padding_may_hold_nan_and_lens_are_clamped(sta_variant):
+    """Rows past lens[u] are never multiplied in; lens outside [0, L] behave as clamped; lens=NULL means full."""
+    import torch
+    spec = _spec("bf16", 4, 64, 512, 64, 64, 128, 1, 2010)
+    wl = make_workload(spec)
+    wl.lens = np.array([200, 512, 0, 300], dtype=np.int32)
+    nan_bits = np.uint16(0x7FC0)
+    for r, n in enumerate(wl.lens):
+        wl.k[r, n:] = nan_bits
+        wl.v[r, n:] = nan_bits
+    dw = DeviceWorkload(wl)
+    print(f"nan padding, variant {sta_variant}", flush=True)
+    k64, v64 = wl.f64("k"), wl.f64("v")
+    Hp_ref, cnt_ref = oracle.sta_forward(wl.f64("q"), np.nan_to_num(k64), np.nan_to_num(v64), wl.lens, spec.w,
+                                         spec.gamma)
+    seg, cnt = _run_sta(dw, STA_VARIANTS[sta_variant])
+    torch.cuda.synchronize()
+    assert np.array_equal(cnt.cpu().numpy(), cnt_ref)
+    assert vec_rel_err(to_host_f64(seg), Hp_ref) <= TOL["bf16"]
+    # out-of-range lengths: -5 -> 0, 10**6 -> L
+    wl2 = make_workload(spec)
+    dw2 = DeviceWorkload(wl2)
+    weird = to_device(np.array([-5, 10 ** 6, 512, 17], dtype=np.int32))
+    seg2, cnt2 = _run_sta(dw2, STA_VARIANTS[sta_variant], lens=weird)
+    Hp2, cnt2_ref = oracle.sta_forward(wl2.f64("q"), wl2.f64("k"), wl2.f64("v"), np.array([0, 512, 512, 17]),
+                                       spec.w, spec.gamma)
+    seg3, cnt3 = _run_sta(dw2, STA_VARIANTS[sta_variant], lens=None)
+    Hp3, cnt3_ref = oracle.sta_forward(wl2.f64("q"), wl2.f64("k"), wl2.f64("v"), None, spec.w, spec.gamma)
+    torch.cuda.synchronize()
+    assert np.array_equal(cnt2.cpu().numpy(), cnt2_ref) and np.array_equal(cnt3.cpu().numpy(), cnt3_ref)
+    assert vec_rel_err(to_host_f64(seg2), Hp2) <= TOL["bf16"]
+    assert vec_rel_err(to_host_f64(seg3), Hp3) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("gamma", [1.0, 0.25])
+def test_gating_extremes_and_gamma(gamma):
+    """Saturated and silenced gates (scores far from zero) on the bf16 path, and gamma != sqrt(d_q)."""
+    import torch
+    spec = _spec("bf16", 2, 64, 512, 64, 64, 128, 1, 2011)
+    wl = make_workload(spec)
+    q = wl.f64("q")
+    k = wl.f64("k")
+    # segment 1 of user 0: keys strongly anti-aligned with candidate 0 (silenced); segment 2: strongly aligned
+    q0 = q[0, 0] / np.linalg.norm(q[0, 0])
+    k[0, 128:256] = -40.0 * q0
+    k[0, 256:384] = +40.0 * q0
+    wl.k = workloads.f32_to_bf16_bits(k.astype(np.float32))
+    dw = DeviceWorkload(wl)
+    Hp_ref, _ = oracle.sta_forward(wl.f64("q"), wl.f64("k"), wl.f64("v"), wl.lens, spec.w, gamma)
+    assert np.abs(Hp_ref[0, 0, 1]).max() < 1e-6                     # the checker agrees the segment is silent
+    for variant in STA_VARIANTS.values():
+        try:
+            seg, _ = laser.laser_sta_forward(dw.q, dw.k, dw.v, dw.lens, spec.w, gamma, variant=variant)
+        except laser.LaserError as e:
+            assert e.code == 4
+            continue
+        torch.cuda.synchronize()
+        got = to_host_f64(seg)
+        assert vec_rel_err(np.delete(got, 1, axis=2), np.delete(Hp_ref, 1, axis=2)) <= TOL["bf16"]
+        # the silenced segment of (user 0, candidate 0): tiny next to its neighbours
+        assert np.abs(got[0, 0, 1]).max() <= 1e-5
+        assert vec_rel_err(got[1, :, 1], Hp_ref[1, :, 1]) <= TOL["bf16"]
+        assert vec_rel_err(got[0, 1:, 1], Hp_ref[0, 1:, 1]) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_gsta_with_a_sharp_softmax(dtype):
+    """Scaled-up W_q makes the softmax concentrate on few segments (default weights give it near-uniform)."""
+    import torch
+    scale = 40.0 if dtype == "f32" else 6.0
+    spec = _spec(dtype, 2, 16, 1024, 64, 64, 64, 2, 2012)
+    wl = make_workload(spec)
+    wq = wl.f64("wq") * scale
+    wl.wq = wq.astype(np.float32) if dtype == "f32" else workloads.f32_to_bf16_bits(wq.astype(np.float32))
+    dw = DeviceWorkload(wl)
+    Hp_ref, cnt_ref, _ = oracle_batch(wl)
+    Hs = round_like(Hp_ref, dtype)
+    seg_store = Hs.astype(np.float32) if dtype == "f32" else workloads.f32_to_bf16_bits(Hs.astype(np.float32))
+    z_ref = oracle.gsta_forward(Hs, wl.f64("t0"), wl.f64("wq"), wl.f64("wk"), wl.f64("wv"), cnt_ref)
+    for variant in GSTA_VARIANTS.values():
+        try:
+            z = laser.laser_gsta_forward(to_device(seg_store), dw.t0, dw.wq, dw.wk, dw.wv, dw.lens, spec.L, spec.w,
+                                         variant=variant)
+        except laser.LaserError as e:
+            assert e.code == 4
+            continue
+        torch.cuda.synchronize()
+        err = vec_rel_err(to_host_f64(z), z_ref)
+        print(f"sharp softmax {dtype} variant {variant}: err {err:.3e}", flush=True)
+        assert err <= TOL[dtype]
+
+
+def test_permutation_inside_a_segment_on_the_gpu():
+    """Items of one segment permuted (keys and values together): H' changes only by rounding order."""
+    import torch
+    spec = _spec("bf16", 1, 64, 512, 64, 64, 128, 1, 2013)
+    wl = make_workload(spec)
+    dw = DeviceWorkload(wl)
+    base, _ = laser.laser_sta_forward(dw.q, dw.k, dw.v, dw.lens, spec.w, spec.gamma)
+    perm = np.arange(512)
+    perm[128:256] = 128 + np.random.default_rng(3).permutation(128)
+    wl.k, wl.v = wl.k[:, perm].copy(), wl.v[:, perm].copy()
+    dw2 = DeviceWorkload(wl)
+    out, _ = laser.laser_sta_forward(dw2.q, dw2.k, dw2.v, dw2.lens, spec.w, spec.gamma)
+    torch.cuda.synchronize()
+    a, b = to_host_f64(base), to_host_f64(out)
+    assert np.array_equal(np.delete(a, 1, axis=2), np.delete(b, 1, axis=2))     # other segments: bit-identical
+    assert vec_rel_err(b[:, :, 1], a[:, :, 1]) <= 2 * 2.0 ** -8                  # one bf16 rounding each side
