@@ -1,5 +1,236 @@
+// STA on the bf16 matrix cores (many candidates per user).
+//
+// Operation (Sec. 3.4.2 STA equation, global-score form of Sec. 3.5.1): for a user, the scores of all
+// candidates against all history items are one [C x d_q].[d_q x L] contraction, the gated aggregation is a
+// [C x L].[L x d] contraction whose accumulator is flushed at every segment boundary.
+//
+// Mapping. A workgroup owns (user, tile of 64*NW candidates, a run of consecutive segments); each of its NW
+// waves owns 64 candidates (two 32-wide MFMA column blocks) and keeps their queries in registers as the
+// B operand for the whole run. History items are staged through LDS 64 at a time with coalesced 16-byte
+// global loads shared by all waves; rows past the valid length (or past the end of the segment) are stored as
+// zeros, so a padded item contributes gate(0) * 0 = 0 and needs no mask in the epilogue, and padding that
+// holds NaN never reaches the arithmetic.
+//
+// Both products are computed transposed so that nothing has to be shuffled between them:
+//   Sc^T[item, cand] = K_tile . Q^T            v_mfma_f32_32x32x16_bf16, A = K rows from LDS (16 B per lane)
+//   P^T = bf16(sigmoid(Sc^T / gamma))          in the accumulator registers
+//   acc^T[dcol, cand] += V_tile^T . P^T        A = V^T via the LDS transpose load, B = P^T as it already sits
+// The accumulator layout of the first product (lane = candidate, registers = items 8(r/4)+4(lane/32)+r%4) is,
+// per 16-item step, exactly a B operand whose k-slots are the items {4h..4h+3, 8+4h..8+4h+3}; V^T is fetched
+// with the same slot order by two ds_read_b64_tr_b16 per step.
 #include "laser_internal.h"
+
 namespace laser {
-bool sta_mfma_supports(const StaArgs&) { return false; }
-laser_status sta_mfma_launch(const StaArgs&) { return LASER_ERR_UNSUPPORTED; }
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int TI = 64;   // history items staged per step
+
+// LDS row pitches in bytes. K rows are read 16 B per lane by 32 consecutive items: pitch = 16 mod 256 spreads
+// them over all banks. V rows are read by the transpose load, four consecutive items x 64 B: pitch = 64 mod 256.
+template <int DQ> struct KPitch { static constexpr int v = DQ * 2 + 16; };
+template <int D> struct VPitch { static constexpr int v = (D * 2) % 256 == 64 ? D * 2 : D * 2 + 64; };
+
+__device__ __forceinline__ float gate(float score, float neg_scale_log2e) {
+  // sigmoid(x) = 1 / (1 + 2^(-x log2 e)); x = score / gamma
+  return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(score * neg_scale_log2e));
+}
+
+template <int DQ, int D, int NW>
+__global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short* __restrict__ q,
+                                                           const unsigned short* __restrict__ k,
+                                                           const unsigned short* __restrict__ v,
+                                                           const int32_t* __restrict__ lens, int C, int L, int w,
+                                                           int S, int spw, int ctiles, int sruns,
+                                                           float neg_scale_log2e, unsigned short* __restrict__ seg_out) {
+  constexpr int KP = KPitch<DQ>::v, VP = VPitch<D>::v;
+  constexpr int NT = 64 * NW;
+  constexpr int KSTEPS = DQ / 16, DB = D / 32;
+  __shared__ __attribute__((aligned(16))) unsigned char Ks[TI * KP];
+  __shared__ __attribute__((aligned(16))) unsigned char Vs[TI * VP];
+
+  int bid = blockIdx.x;
+  const int srun = bid % sruns;
+  bid /= sruns;
+  const int ct = bid % ctiles;
+  const int u = bid / ctiles;
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int l32 = lane & 31, h = lane >> 5;
+  const int cbase = ct * (64 * NW) + wave * 64;     // first candidate of this wave
+  const int n = valid_len(lens, u, L);
+
+  // queries: B operand of the score product, lane = candidate, 8 consecutive d_q elements per k-step half
+  bf16x8 qreg[2][KSTEPS];
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb) {
+    const int c = cbase + nb * 32 + l32;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+      u32x4 raw = {0u, 0u, 0u, 0u};
+      if (c < C) raw = *reinterpret_cast<const u32x4*>(q + ((size_t)u * C + c) * DQ + ks * 16 + h * 8);
+      qreg[nb][ks] = __builtin_bit_cast(bf16x8, raw);
+    }
+  }
+
+  const unsigned short* kU = k + (size_t)u * L * DQ;
+  const unsigned short* vU = v + (size_t)u * L * D;
+
+  const int seg_lo = srun * spw;
+  const int seg_hi = (seg_lo + spw) < S ? (seg_lo + spw) : S;
+  for (int i = seg_lo; i < seg_hi; ++i) {
+    const int lo = i * w;
+    int hi = lo + w;
+    if (hi > L) hi = L;
+    if (hi > n) hi = n;
+
+    f32x16 acc[DB][2];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[db][nb][r] = 0.0f;
+
+    for (int t0 = lo; t0 < hi; t0 += TI) {
+      __syncthreads();   // previous tile fully consumed
+      // stage K and V rows t0 .. t0+TI-1 (zeros past hi), 16 B per thread per step
+      constexpr int KCH = DQ / 8, VCH = D / 8;   // 16-byte chunks per row
+      for (int e = tid; e < TI * KCH; e += NT) {
+        const int r = e / KCH, ch = e - r * KCH;
+        u32x4 val = {0u, 0u, 0u, 0u};
+        if (t0 + r < hi) val = *reinterpret_cast<const u32x4*>(kU + (size_t)(t0 + r) * DQ + ch * 8);
+        *reinterpret_cast<u32x4*>(Ks + r * KP + ch * 16) = val;
+      }
+      for (int e = tid; e < TI * VCH; e += NT) {
+        const int r = e / VCH, ch = e - r * VCH;
+        u32x4 val = {0u, 0u, 0u, 0u};
+        if (t0 + r < hi) val = *reinterpret_cast<const u32x4*>(vU + (size_t)(t0 + r) * D + ch * 8);
+        *reinterpret_cast<u32x4*>(Vs + r * VP + ch * 16) = val;
+      }
+      __syncthreads();
+
+#pragma unroll
+      for (int ib = 0; ib < TI / 32; ++ib) {
+        if (t0 + ib * 32 >= hi) break;   // uniform: the rest of the tile is padding
+        // ---- Sc^T = K . Q^T for 32 items x 64 candidates
+        f32x16 sc[2];
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sc[nb][r] = 0.0f;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+          const bf16x8 a = *reinterpret_cast<const bf16x8*>(Ks + (ib * 32 + l32) * KP + (ks * 16 + h * 8) * 2);
+          sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[0][ks], sc[0], 0, 0, 0);
+          sc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[1][ks], sc[1], 0, 0, 0);
+        }
+        // ---- gates, rounded to bf16: they become the B operand of the second product as they sit
+        bf16x8 p[2][2];
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+          for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) p[nb][s][e] = (__bf16)gate(sc[nb][s * 8 + e], neg_scale_log2e);
+        // ---- acc^T += V^T . P^T
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+          const int item0 = ib * 32 + s * 16 + h * 4;   // k-slots 0..3; slots 4..7 are 8 items further
+#pragma unroll
+          for (int db = 0; db < DB; ++db) {
+            // transpose load: lane i of a 16-lane group supplies the address of V[item0 + i/4][dc0 + 4 (i%4)]
+            // and receives V[item0 + 0..3][dc0 + i]
+            const int dc0 = db * 32 + (l32 & 16);
+            const int i16 = lane & 15;
+            const unsigned char* src = Vs + (item0 + (i16 >> 2)) * VP + (dc0 + 4 * (i16 & 3)) * 2;
+            const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) s16x4*)(src));
+            const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) s16x4*)(src + 8 * VP));
+            typedef short s16x8 __attribute__((ext_vector_type(8)));
+            const s16x8 both = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+            const bf16x8 a = __builtin_bit_cast(bf16x8, both);
+            acc[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p[0][s], acc[db][0], 0, 0, 0);
+            acc[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p[1][s], acc[db][1], 0, 0, 0);
+          }
+        }
+      }
+    }
+
+    // ---- H'[u, c, i, :]: lane = candidate, registers = 4 consecutive value columns per group of four
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+      const int c = cbase + nb * 32 + l32;
+      if (c < C) {
+        unsigned short* dst = seg_out + (((size_t)u * C + c) * S + i) * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            bf16x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[db][nb][g * 4 + e];
+            *reinterpret_cast<u32x2*>(dst + db * 32 + g * 8 + h * 4) = __builtin_bit_cast(u32x2, o);
+          }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------ host side
+static int pick_nw(int C) { return C > 128 ? 4 : (C > 64 ? 2 : 1); }
+
+bool sta_mfma_supports(const StaArgs& a) {
+  if (a.dt != LASER_BF16) return false;
+  if (!(a.d_q == 32 || a.d_q == 64 || a.d_q == 128)) return false;
+  if (!(a.d == 64 || a.d == 128)) return false;
+  if (a.C < 9) return false;   // fewer candidates than that: the streaming kernel's range
+  const int nw = pick_nw(a.C);
+  const long long ctiles = (a.C + 64 * nw - 1) / (64 * nw);
+  return (long long)a.U * ctiles * a.S <= 0x7fffffffLL;
+}
+
+template <int DQ, int D, int NW>
+static void launch_one(const StaArgs& a, int spw, int ctiles, int sruns, float nsl) {
+  const unsigned blocks = (unsigned)((long long)a.U * ctiles * sruns);
+  hipLaunchKernelGGL((sta_mfma_kernel<DQ, D, NW>), dim3(blocks), dim3(64 * NW), 0, a.stream,
+                     (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens, a.C,
+                     a.L, a.w, a.S, spw, ctiles, sruns, nsl, (unsigned short*)a.seg_out);
+}
+
+template <int DQ, int D>
+static void launch_nw(const StaArgs& a, int nw, int spw, int ctiles, int sruns, float nsl) {
+  if (nw == 4) launch_one<DQ, D, 4>(a, spw, ctiles, sruns, nsl);
+  else if (nw == 2) launch_one<DQ, D, 2>(a, spw, ctiles, sruns, nsl);
+  else launch_one<DQ, D, 1>(a, spw, ctiles, sruns, nsl);
+}
+
+laser_status sta_mfma_launch(const StaArgs& a) {
+  if (!sta_mfma_supports(a)) return LASER_ERR_UNSUPPORTED;
+  const int nw = pick_nw(a.C);
+  const int ctiles = (a.C + 64 * nw - 1) / (64 * nw);
+  // consecutive segments per workgroup: as many as still leave about two workgroups per compute unit
+  int spw = 1;
+  while (spw < 8 && (long long)a.U * ctiles * ((a.S + 2 * spw - 1) / (2 * spw)) >= 512) spw *= 2;
+  const int sruns = (a.S + spw - 1) / spw;
+  const float nsl = -1.4426950408889634f / a.gamma;
+  const int key = a.d_q * 1000 + a.d;
+  switch (key) {
+    case 32064: launch_nw<32, 64>(a, nw, spw, ctiles, sruns, nsl); break;
+    case 32128: launch_nw<32, 128>(a, nw, spw, ctiles, sruns, nsl); break;
+    case 64064: launch_nw<64, 64>(a, nw, spw, ctiles, sruns, nsl); break;
+    case 64128: launch_nw<64, 128>(a, nw, spw, ctiles, sruns, nsl); break;
+    case 128064: launch_nw<128, 64>(a, nw, spw, ctiles, sruns, nsl); break;
+    case 128128: launch_nw<128, 128>(a, nw, spw, ctiles, sruns, nsl); break;
+    default: return LASER_ERR_UNSUPPORTED;
+  }
+  return launch_status();
+}
+
 }  // namespace laser
