@@ -1,0 +1,232 @@
+#!/usr/bin/env python3
+"""Benchmark of the STA + GSTA forward path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A step is one pass of the whole hot path (STA, segment counts, GSTA: `laser_forward`) over one batch of
+seeded synthetic input already resident in HBM. Prints ONE JSON line (see the design doc for the fields).
+Order of work: (1) the fp64 CPU checker is timed on a bounded sample of the same workload, before the GPU
+is touched; (2) inputs are generated on the host and uploaded (several distinct copies so the working set
+exceeds the 256 MB last-level cache); (3) warm-up, then K timed steps; (4) the dominant kernel (STA) and GSTA
+are timed on their own with HIP events over K back-to-back launches each; (5) sampled outputs are compared
+with the checker.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+import numpy as np  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16
+DEFAULT_WORKLOAD = "cfg3_high_fanout"   # the configuration the metric is quoted on (L=4096, 256 candidates)
+
+
+def _oracle_pairs(args):
+    """Worker: checker on a list of (row, candidate) pairs of a workload (CPU only)."""
+    wl, pairs = args
+    from parity_util import oracle_pair
+    for (r, c) in pairs:
+        oracle_pair(wl, r, c)
+    return len(pairs)
+
+
+def cpu_baseline(spec, budget_s: float = 12.0):
+    """Time the fp64 checker, as it stands, on a bounded sample of the workload. Returns the JSON object."""
+    import workloads
+    from parity_util import oracle_pair
+    try:
+        from threadpoolctl import threadpool_limits
+    except Exception:  # pragma: no cover
+        threadpool_limits = None
+    # enough users that the sample can fill the time budget (sized from a one-pair calibration)
+    probe = workloads.make_workload(spec, users=[0])
+    t = time.perf_counter()
+    oracle_pair(probe, 0, 0)
+    per_pair = max(time.perf_counter() - t, 1e-5)
+    n_users = int(min(spec.U, 64, max(2, math.ceil(budget_s / per_pair / spec.C))))
+    wl = workloads.make_workload(spec, users=list(range(n_users)))
+    import contextlib
+    with (threadpool_limits(limits=1) if threadpool_limits else contextlib.nullcontext()):
+        return _cpu_baseline_timed(spec, wl, n_users, budget_s)
+
+
+def _cpu_baseline_timed(spec, wl, n_users, budget_s):
+    from parity_util import oracle_pair
+    # calibrate on two pairs, then size the sample to the budget
+    t = time.perf_counter()
+    oracle_pair(wl, 0, 0)
+    oracle_pair(wl, n_users - 1, spec.C - 1)
+    per_pair = (time.perf_counter() - t) / 2
+    n = int(max(4, min(n_users * spec.C, budget_s / max(per_pair, 1e-6))))
+    pairs = [(i % n_users, (i // n_users) % spec.C) for i in range(n)]
+    t = time.perf_counter()
+    for (r, c) in pairs:
+        oracle_pair(wl, r, c)
+    one_core = time.perf_counter() - t
+    out = {"value": n / one_core, "unit": "pairs/s", "cores": 1, "kind": "oracle",
+           "sample": f"{n} (user, candidate) pairs of {spec.name} (users 0..{n_users - 1}), fp64 numpy, "
+                     f"BLAS pinned to 1 thread, {one_core:.1f} s"}
+    # the same code over all host cores (one process per core, before any GPU initialisation)
+    try:
+        import multiprocessing as mp
+        cores = len(os.sched_getaffinity(0))
+        cores = min(cores, 16)
+        if cores > 1:
+            chunks = [pairs[i::cores] for i in range(cores)]
+            with mp.get_context("fork").Pool(cores) as pool:
+                t = time.perf_counter()
+                done = sum(pool.map(_oracle_pairs, [(wl, ch) for ch in chunks]))
+                allc = time.perf_counter() - t
+            out["all_cores"] = {"value": done / allc, "cores": cores, "seconds": round(allc, 2)}
+    except Exception as e:  # pragma: no cover
+        out["all_cores"] = {"error": str(e)}
+    return out
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copies", type=int, default=0, help="distinct input/output copies to rotate through (0 = auto)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (users shard across GPUs with no exchange; see DESIGN.md); "
+              "--gpus must be 1", file=sys.stderr)
+        return 2
+
+    import workloads
+    from paper_2602_11562_amd import cost_model as cm
+    spec = workloads.CONFIGS[args.workload]
+
+    cpu = None if args.no_cpu_baseline else cpu_baseline(spec)
+
+    import torch
+    import paper_2602_11562_amd as laser
+    from parity_util import TOL, DeviceWorkload, oracle_pair, to_host_f64, vec_rel_err
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    laser.load_library()   # fails loudly if liblaser.so is missing
+
+    wl = workloads.make_workload(spec)
+    esz = 4 if spec.dtype == "f32" else 2
+    tdt = torch.float32 if spec.dtype == "f32" else torch.bfloat16
+    sta_b = cm.sta_bytes(wl.lens, spec.U, spec.C, spec.L, spec.d_q, spec.d, spec.w, spec.dtype)
+    sta_f = cm.sta_flops(wl.lens, spec.C, spec.d_q, spec.d)
+    gsta_b = cm.gsta_bytes(wl.lens, spec.U, spec.C, spec.L, spec.d, spec.w, spec.M, spec.dtype)
+    gsta_f = cm.gsta_flops(wl.lens, spec.C, spec.d, spec.w, spec.M)
+    footprint = (wl.q.nbytes + wl.k.nbytes + wl.v.nbytes + wl.t0.nbytes + spec.U * spec.C * spec.S * spec.d * esz
+                 + spec.U * spec.C * spec.d * 4)
+    copies = args.copies or int(min(8, max(1, math.ceil(600e6 / footprint))))
+
+    sets = []
+    for _ in range(copies):
+        dw = DeviceWorkload(wl)   # a fresh allocation of every input
+        seg = torch.empty((spec.U, spec.C, spec.S, spec.d), dtype=tdt, device="cuda")
+        cnt = torch.empty((spec.U, spec.S), dtype=torch.int32, device="cuda")
+        z = torch.empty((spec.U, spec.C, spec.d), dtype=torch.float32, device="cuda")
+        sets.append((dw, seg, cnt, z))
+
+    def step(i):
+        dw, seg, cnt, z = sets[i % copies]
+        laser.laser_forward(dw.q, dw.k, dw.v, dw.t0, dw.wq, dw.wk, dw.wv, dw.lens, spec.w, spec.gamma,
+                            seg_out=seg, seg_cnt=cnt, z_out=z)
+
+    def sta_only(i):
+        dw, seg, cnt, z = sets[i % copies]
+        laser.laser_sta_forward(dw.q, dw.k, dw.v, dw.lens, spec.w, spec.gamma, seg_out=seg, want_cnt=False)
+
+    def gsta_only(i):
+        dw, seg, cnt, z = sets[i % copies]
+        laser.laser_gsta_forward(seg, dw.t0, dw.wq, dw.wk, dw.wv, dw.lens, spec.L, spec.w, z_out=z)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+
+    def event_time(fn):
+        """Average duration (ms) of K back-to-back launches, HIP events on the launch stream."""
+        for i in range(min(args.warmup, 10)):
+            fn(i)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for i in range(args.steps):
+            fn(i)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / args.steps
+
+    sta_ms = event_time(sta_only)
+    gsta_ms = event_time(gsta_only)
+
+    # sampled parity against the checker (one-by-one pairs), in this launch configuration
+    step(0)
+    torch.cuda.synchronize()
+    dw, seg, cnt, z = sets[0]
+    rng = np.random.default_rng(0)
+    worst = 0.0
+    for _ in range(4):
+        r, c = int(rng.integers(spec.U)), int(rng.integers(spec.C))
+        Hp_ref, z_ref = oracle_pair(wl, r, c)
+        worst = max(worst, vec_rel_err(to_host_f64(seg[r, c]), Hp_ref), vec_rel_err(to_host_f64(z[r, c]), z_ref))
+    parity_ok = worst <= TOL[spec.dtype]
+
+    dtl = laser.LASER_F32 if spec.dtype == "f32" else laser.LASER_BF16
+    sta_kernel = laser.laser_sta_kernel_name(spec.C, spec.d_q, spec.d, spec.w, dtl)
+    gsta_kernel = laser.laser_gsta_kernel_name(spec.C, spec.S, spec.d, dtl)
+    t_hbm = sta_b / (HBM_PEAK_GBS * 1e9)
+    t_mfma = sta_f / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    if t_hbm >= t_mfma or spec.dtype == "f32":
+        roof = {"bound": "hbm", "achieved": sta_b / (sta_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    else:
+        roof = {"bound": "mfma", "achieved": sta_f / (sta_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof.update({"kernel": sta_kernel, "kernel_ms": sta_ms, "algorithmic_bytes": sta_b, "algorithmic_flops": sta_f,
+                 "tflops": sta_f / (sta_ms * 1e-3) / 1e12, "gbps": sta_b / (sta_ms * 1e-3) / 1e9})
+
+    rec = {
+        "metric": "STA+GSTA (user,candidate) pairs/sec",
+        "value": spec.pairs / (ms_per_step * 1e-3),
+        "unit": "pairs/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": spec.dtype, "data": "synthetic",
+        "config": {"workload": spec.name, "U": spec.U, "C": spec.C, "L": spec.L, "d": spec.d, "d_q": spec.d_q,
+                   "w": spec.w, "S": spec.S, "M": spec.M, "pairs": spec.pairs, "input_copies": copies,
+                   "footprint_mb": footprint / 1e6, "seg_out_written": True},
+        "roofline": roof,
+        "cpu_baseline": cpu,
+        "kernels": {"sta": {"name": sta_kernel, "ms": sta_ms}, "gsta": {
+            "name": gsta_kernel, "ms": gsta_ms, "algorithmic_bytes": gsta_b, "algorithmic_flops": gsta_f,
+            "gbps": gsta_b / (gsta_ms * 1e-3) / 1e9}},
+        "parity": {"max_vector_rel_err": worst, "tolerance": TOL[spec.dtype], "ok": bool(parity_ok),
+                   "sampled_pairs": 4},
+    }
+    print(json.dumps(rec))
+    return 0 if parity_ok else 1
+
+
+if __name__ == "__main__":
+    sys.exit(main())
