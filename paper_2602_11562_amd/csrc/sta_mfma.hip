@@ -4,12 +4,13 @@
 // candidates against all history items are one [C x d_q].[d_q x L] contraction, the gated aggregation is a
 // [C x L].[L x d] contraction whose accumulator is flushed at every segment boundary.
 //
-// Mapping. A workgroup owns (user, tile of 64*NW candidates, a run of consecutive segments); each of its NW
-// waves owns 64 candidates (two 32-wide MFMA column blocks) and keeps their queries in registers as the
-// B operand for the whole run. History items are staged through LDS 64 at a time with coalesced 16-byte
-// global loads shared by all waves; rows past the valid length (or past the end of the segment) are stored as
-// zeros, so a padded item contributes gate(0) * 0 = 0 and needs no mask in the epilogue, and padding that
-// holds NaN never reaches the arithmetic.
+// Mapping. A workgroup owns (user, tile of 32*NW candidates, a run of consecutive segments); each of its NW
+// waves owns 32 candidates (one MFMA column block) and keeps their queries in registers as the B operand for
+// the whole run. History items are staged through LDS 64 at a time with coalesced 16-byte global loads shared
+// by all waves; rows past the valid length (or past the end of the segment) are stored as zeros, so a padded
+// item contributes gate(0) * 0 = 0 and needs no mask in the epilogue, and padding that holds NaN never reaches
+// the arithmetic. With NBUF = 2 the loads of the next tile are issued before the current tile is computed and
+// land in the other LDS buffer afterwards: one barrier per tile, memory latency behind the MFMA work.
 //
 // Both products are computed transposed so that nothing has to be shuffled between them:
 //   Sc^T[item, cand] = K_tile . Q^T            v_mfma_f32_32x32x16_bf16, A = K rows from LDS (16 B per lane)
@@ -18,6 +19,11 @@
 // The accumulator layout of the first product (lane = candidate, registers = items 8(r/4)+4(lane/32)+r%4) is,
 // per 16-item step, exactly a B operand whose k-slots are the items {4h..4h+3, 8+4h..8+4h+3}; V^T is fetched
 // with the same slot order by two ds_read_b64_tr_b16 per step.
+//
+// H' leaves through a wave-private LDS patch, 64 value columns at a time, so that global stores are whole
+// 128-byte row pieces instead of 8-byte fragments of 32 different rows.
+#include <cstdlib>
+
 #include "laser_internal.h"
 
 namespace laser {
@@ -25,11 +31,14 @@ namespace laser {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int TI = 64;   // history items staged per step
+constexpr int TI = 64;    // history items staged per step
+constexpr int CW = 32;    // candidates per wave
+constexpr int OP = 136;   // output patch row pitch in bytes: 64 bf16 + 8 (write side spreads over all banks)
 
 // LDS row pitches in bytes. K rows are read 16 B per lane by 32 consecutive items: pitch = 16 mod 256 spreads
 // them over all banks. V rows are read by the transpose load, four consecutive items x 64 B: pitch = 64 mod 256.
@@ -41,7 +50,44 @@ __device__ __forceinline__ float gate(float score, float neg_scale_log2e) {
   return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(score * neg_scale_log2e));
 }
 
-template <int DQ, int D, int NW>
+template <int DQ, int D, int NT>
+struct Stage {
+  static constexpr int KCH = DQ / 8, VCH = D / 8;   // 16-byte chunks per row
+  static constexpr int KIT = (TI * KCH + NT - 1) / NT, VIT = (TI * VCH + NT - 1) / NT;
+  u32x4 kr[KIT], vr[VIT];
+
+  // global -> registers; rows at or past `hi` (absolute item index) come back as zeros
+  __device__ __forceinline__ void load(const unsigned short* kU, const unsigned short* vU, int t0, int hi, int tid) {
+#pragma unroll
+    for (int it = 0; it < KIT; ++it) {
+      const int e = tid + it * NT, r = e / KCH, ch = e % KCH;
+      kr[it] = u32x4{0u, 0u, 0u, 0u};
+      if (e < TI * KCH && t0 + r < hi) kr[it] = *reinterpret_cast<const u32x4*>(kU + (size_t)(t0 + r) * DQ + ch * 8);
+    }
+#pragma unroll
+    for (int it = 0; it < VIT; ++it) {
+      const int e = tid + it * NT, r = e / VCH, ch = e % VCH;
+      vr[it] = u32x4{0u, 0u, 0u, 0u};
+      if (e < TI * VCH && t0 + r < hi) vr[it] = *reinterpret_cast<const u32x4*>(vU + (size_t)(t0 + r) * D + ch * 8);
+    }
+  }
+  // registers -> LDS
+  __device__ __forceinline__ void store(unsigned char* Ks, unsigned char* Vs, int tid) const {
+    constexpr int KP = KPitch<DQ>::v, VP = VPitch<D>::v;
+#pragma unroll
+    for (int it = 0; it < KIT; ++it) {
+      const int e = tid + it * NT, r = e / KCH, ch = e % KCH;
+      if (e < TI * KCH) *reinterpret_cast<u32x4*>(Ks + r * KP + ch * 16) = kr[it];
+    }
+#pragma unroll
+    for (int it = 0; it < VIT; ++it) {
+      const int e = tid + it * NT, r = e / VCH, ch = e % VCH;
+      if (e < TI * VCH) *reinterpret_cast<u32x4*>(Vs + r * VP + ch * 16) = vr[it];
+    }
+  }
+};
+
+template <int DQ, int D, int NW, int NBUF>
 __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short* __restrict__ q,
                                                            const unsigned short* __restrict__ k,
                                                            const unsigned short* __restrict__ v,
@@ -51,8 +97,8 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short*
   constexpr int KP = KPitch<DQ>::v, VP = VPitch<D>::v;
   constexpr int NT = 64 * NW;
   constexpr int KSTEPS = DQ / 16, DB = D / 32;
-  __shared__ __attribute__((aligned(16))) unsigned char Ks[TI * KP];
-  __shared__ __attribute__((aligned(16))) unsigned char Vs[TI * VP];
+  constexpr int KBYTES = TI * KP, VBYTES = TI * VP, OBYTES = CW * OP;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[NBUF * (KBYTES + VBYTES) + NW * OBYTES];
 
   int bid = blockIdx.x;
   const int srun = bid % sruns;
@@ -62,19 +108,19 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short*
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int l32 = lane & 31, h = lane >> 5;
-  const int cbase = ct * (64 * NW) + wave * 64;     // first candidate of this wave
+  const int cbase = ct * (CW * NW) + wave * CW;     // first candidate of this wave
   const int n = valid_len(lens, u, L);
+  unsigned char* opatch = smem + NBUF * (KBYTES + VBYTES) + wave * OBYTES;
 
   // queries: B operand of the score product, lane = candidate, 8 consecutive d_q elements per k-step half
-  bf16x8 qreg[2][KSTEPS];
-#pragma unroll
-  for (int nb = 0; nb < 2; ++nb) {
-    const int c = cbase + nb * 32 + l32;
+  bf16x8 qreg[KSTEPS];
+  {
+    const int c = cbase + l32;
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) {
       u32x4 raw = {0u, 0u, 0u, 0u};
       if (c < C) raw = *reinterpret_cast<const u32x4*>(q + ((size_t)u * C + c) * DQ + ks * 16 + h * 8);
-      qreg[nb][ks] = __builtin_bit_cast(bf16x8, raw);
+      qreg[ks] = __builtin_bit_cast(bf16x8, raw);
     }
   }
 
@@ -83,61 +129,65 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short*
 
   const int seg_lo = srun * spw;
   const int seg_hi = (seg_lo + spw) < S ? (seg_lo + spw) : S;
-  for (int i = seg_lo; i < seg_hi; ++i) {
-    const int lo = i * w;
-    int hi = lo + w;
-    if (hi > L) hi = L;
-    if (hi > n) hi = n;
+  // valid items are a prefix of the history, so the non-empty segments of the run are a prefix of the run
+  int seg_ne = seg_lo;
+  while (seg_ne < seg_hi && seg_ne * w < n) ++seg_ne;
 
-    f32x16 acc[DB][2];
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[db][nb][r] = 0.0f;
+  // tile cursor over the non-empty segments of the run: (segment, first item, end of valid items in the segment)
+  auto seg_end = [&](int i) {
+    int e = i * w + w;
+    if (e > L) e = L;
+    if (e > n) e = n;
+    return e;
+  };
 
-    for (int t0 = lo; t0 < hi; t0 += TI) {
-      __syncthreads();   // previous tile fully consumed
-      // stage K and V rows t0 .. t0+TI-1 (zeros past hi), 16 B per thread per step
-      constexpr int KCH = DQ / 8, VCH = D / 8;   // 16-byte chunks per row
-      for (int e = tid; e < TI * KCH; e += NT) {
-        const int r = e / KCH, ch = e - r * KCH;
-        u32x4 val = {0u, 0u, 0u, 0u};
-        if (t0 + r < hi) val = *reinterpret_cast<const u32x4*>(kU + (size_t)(t0 + r) * DQ + ch * 8);
-        *reinterpret_cast<u32x4*>(Ks + r * KP + ch * 16) = val;
-      }
-      for (int e = tid; e < TI * VCH; e += NT) {
-        const int r = e / VCH, ch = e - r * VCH;
-        u32x4 val = {0u, 0u, 0u, 0u};
-        if (t0 + r < hi) val = *reinterpret_cast<const u32x4*>(vU + (size_t)(t0 + r) * D + ch * 8);
-        *reinterpret_cast<u32x4*>(Vs + r * VP + ch * 16) = val;
-      }
-      __syncthreads();
+  Stage<DQ, D, NT> st;
+  int ci = seg_lo, ct0 = seg_lo * w, chi = seg_ne > seg_lo ? seg_end(seg_lo) : 0;   // current tile
+  int buf = 0;
+  if (seg_ne > seg_lo) {
+    st.load(kU, vU, ct0, chi, tid);
+    st.store(smem, smem + KBYTES, tid);
+  }
+  __syncthreads();
+
+  f32x16 acc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[db][r] = 0.0f;
+
+  while (ci < seg_ne) {
+    // next tile in the run (same segment, or the first tile of the next non-empty segment)
+    int ni = ci, nt0 = ct0 + TI, nhi = chi;
+    if (nt0 >= chi) {
+      ni = ci + 1;
+      nt0 = ni * w;
+      nhi = ni < seg_ne ? seg_end(ni) : 0;
+    }
+    const bool has_next = ni < seg_ne;
+    unsigned char* Ks = smem + buf * (KBYTES + VBYTES);
+    unsigned char* Vs = Ks + KBYTES;
+    if (NBUF == 2 && has_next) st.load(kU, vU, nt0, nhi, tid);   // in flight during the MFMA work below
 
 #pragma unroll
-      for (int ib = 0; ib < TI / 32; ++ib) {
-        if (t0 + ib * 32 >= hi) break;   // uniform: the rest of the tile is padding
-        // ---- Sc^T = K . Q^T for 32 items x 64 candidates
-        f32x16 sc[2];
+    for (int ib = 0; ib < TI / 32; ++ib) {
+      if (ct0 + ib * 32 < chi) {   // uniform: otherwise the rest of the tile is padding
+        // ---- Sc^T = K . Q^T for 32 items x 32 candidates
+        bf16x8 ka[KSTEPS];
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
+        for (int ks = 0; ks < KSTEPS; ++ks)
+          ka[ks] = *reinterpret_cast<const bf16x8*>(Ks + (ib * 32 + l32) * KP + (ks * 16 + h * 8) * 2);
+        f32x16 sc;
 #pragma unroll
-          for (int r = 0; r < 16; ++r) sc[nb][r] = 0.0f;
+        for (int r = 0; r < 16; ++r) sc[r] = 0.0f;
 #pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(Ks + (ib * 32 + l32) * KP + (ks * 16 + h * 8) * 2);
-          sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[0][ks], sc[0], 0, 0, 0);
-          sc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[1][ks], sc[1], 0, 0, 0);
-        }
+        for (int ks = 0; ks < KSTEPS; ++ks) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[ks], sc, 0, 0, 0);
         // ---- gates, rounded to bf16: they become the B operand of the second product as they sit
-        bf16x8 p[2][2];
+        bf16x8 p[2];
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
+        for (int s = 0; s < 2; ++s)
 #pragma unroll
-          for (int s = 0; s < 2; ++s)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) p[nb][s][e] = (__bf16)gate(sc[nb][s * 8 + e], neg_scale_log2e);
+          for (int e = 0; e < 8; ++e) p[s][e] = (__bf16)gate(sc[s * 8 + e], neg_scale_log2e);
         // ---- acc^T += V^T . P^T
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
@@ -149,42 +199,78 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short*
             const int dc0 = db * 32 + (l32 & 16);
             const int i16 = lane & 15;
             const unsigned char* src = Vs + (item0 + (i16 >> 2)) * VP + (dc0 + 4 * (i16 & 3)) * 2;
-            const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) s16x4*)(src));
-            const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) s16x4*)(src + 8 * VP));
-            typedef short s16x8 __attribute__((ext_vector_type(8)));
+            const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(src));
+            const s16x4 hi4 =
+                __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(src + 8 * VP));
             const s16x8 both = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
-            const bf16x8 a = __builtin_bit_cast(bf16x8, both);
-            acc[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p[0][s], acc[db][0], 0, 0, 0);
-            acc[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p[1][s], acc[db][1], 0, 0, 0);
+            acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), p[s], acc[db], 0, 0, 0);
           }
         }
       }
     }
 
-    // ---- H'[u, c, i, :]: lane = candidate, registers = 4 consecutive value columns per group of four
+    if (ni != ci) {
+      // ---- segment finished: H'[u, c, ci, :] through the wave-private patch, 64 value columns per pass
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-      const int c = cbase + nb * 32 + l32;
-      if (c < C) {
-        unsigned short* dst = seg_out + (((size_t)u * C + c) * S + i) * D;
+      for (int ps = 0; ps < D / 64; ++ps) {
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+        for (int dbl = 0; dbl < 2; ++dbl)
 #pragma unroll
           for (int g = 0; g < 4; ++g) {
             bf16x4 o;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[db][nb][g * 4 + e];
-            *reinterpret_cast<u32x2*>(dst + db * 32 + g * 8 + h * 4) = __builtin_bit_cast(u32x2, o);
+            for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[ps * 2 + dbl][g * 4 + e];
+            *reinterpret_cast<u32x2*>(opatch + l32 * OP + (dbl * 32 + g * 8 + h * 4) * 2) = __builtin_bit_cast(u32x2, o);
           }
+        // read back row-wise: 16 lanes x 8 B = one 128-byte row piece; 4 rows per instruction
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+          const int row = it * 4 + (lane >> 4);
+          const u32x2 val = *reinterpret_cast<const u32x2*>(opatch + row * OP + (lane & 15) * 8);
+          const int cr = cbase + row;
+          if (cr < C)
+            *reinterpret_cast<u32x2*>(seg_out + (((size_t)u * C + cr) * S + ci) * D + ps * 64 + (lane & 15) * 4) = val;
+        }
       }
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[db][r] = 0.0f;
+    }
+
+    if (NBUF == 2) {
+      if (has_next) st.store(smem + (buf ^ 1) * (KBYTES + VBYTES), smem + (buf ^ 1) * (KBYTES + VBYTES) + KBYTES, tid);
+      __syncthreads();
+      buf ^= 1;
+    } else {
+      __syncthreads();   // everyone is done reading the tile
+      if (has_next) {
+        st.load(kU, vU, nt0, nhi, tid);
+        st.store(smem, smem + KBYTES, tid);
+      }
+      __syncthreads();
+    }
+    ci = ni;
+    ct0 = nt0;
+    chi = nhi;
+  }
+
+  // empty segments of the run: exact zeros, 16 bytes per thread
+  if (seg_ne < seg_hi) {
+    const int ncand = (C - ct * (CW * NW)) < CW * NW ? (C - ct * (CW * NW)) : CW * NW;
+    const int per_row = D / 8;
+    const int rows = ncand * (seg_hi - seg_ne);
+    for (int e = tid; e < rows * per_row; e += NT) {
+      const int row = e / per_row, ch = e - row * per_row;
+      const int cc = row / (seg_hi - seg_ne), ii = seg_ne + row % (seg_hi - seg_ne);
+      *reinterpret_cast<u32x4*>(seg_out + (((size_t)u * C + ct * (CW * NW) + cc) * S + ii) * D + ch * 8) =
+          u32x4{0u, 0u, 0u, 0u};
     }
   }
 }
 
 // ------------------------------------------------------------------------------------------ host side
-static int pick_nw(int C) { return C > 128 ? 4 : (C > 64 ? 2 : 1); }
+static int pick_nw(int C) { return C > 128 ? 8 : (C > 64 ? 4 : (C > 32 ? 2 : 1)); }
 
 bool sta_mfma_supports(const StaArgs& a) {
   if (a.dt != LASER_BF16) return false;
@@ -192,32 +278,39 @@ bool sta_mfma_supports(const StaArgs& a) {
   if (!(a.d == 64 || a.d == 128)) return false;
   if (a.C < 9) return false;   // fewer candidates than that: the streaming kernel's range
   const int nw = pick_nw(a.C);
-  const long long ctiles = (a.C + 64 * nw - 1) / (64 * nw);
+  const long long ctiles = (a.C + CW * nw - 1) / (CW * nw);
   return (long long)a.U * ctiles * a.S <= 0x7fffffffLL;
 }
 
-template <int DQ, int D, int NW>
+template <int DQ, int D, int NW, int NBUF>
 static void launch_one(const StaArgs& a, int spw, int ctiles, int sruns, float nsl) {
   const unsigned blocks = (unsigned)((long long)a.U * ctiles * sruns);
-  hipLaunchKernelGGL((sta_mfma_kernel<DQ, D, NW>), dim3(blocks), dim3(64 * NW), 0, a.stream,
+  hipLaunchKernelGGL((sta_mfma_kernel<DQ, D, NW, NBUF>), dim3(blocks), dim3(64 * NW), 0, a.stream,
                      (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens, a.C,
                      a.L, a.w, a.S, spw, ctiles, sruns, nsl, (unsigned short*)a.seg_out);
 }
 
 template <int DQ, int D>
 static void launch_nw(const StaArgs& a, int nw, int spw, int ctiles, int sruns, float nsl) {
-  if (nw == 4) launch_one<DQ, D, 4>(a, spw, ctiles, sruns, nsl);
-  else if (nw == 2) launch_one<DQ, D, 2>(a, spw, ctiles, sruns, nsl);
-  else launch_one<DQ, D, 1>(a, spw, ctiles, sruns, nsl);
+  // eight waves fill a compute unit on their own and prefetch through a second LDS buffer; smaller workgroups
+  // overlap memory and MFMA work across the several workgroups that share a compute unit
+  if (nw == 8) launch_one<DQ, D, 8, 2>(a, spw, ctiles, sruns, nsl);
+  else if (nw == 4) launch_one<DQ, D, 4, 1>(a, spw, ctiles, sruns, nsl);
+  else if (nw == 2) launch_one<DQ, D, 2, 1>(a, spw, ctiles, sruns, nsl);
+  else launch_one<DQ, D, 1, 1>(a, spw, ctiles, sruns, nsl);
 }
 
 laser_status sta_mfma_launch(const StaArgs& a) {
   if (!sta_mfma_supports(a)) return LASER_ERR_UNSUPPORTED;
   const int nw = pick_nw(a.C);
-  const int ctiles = (a.C + 64 * nw - 1) / (64 * nw);
+  const int ctiles = (a.C + CW * nw - 1) / (CW * nw);
   // consecutive segments per workgroup: as many as still leave about two workgroups per compute unit
   int spw = 1;
   while (spw < 8 && (long long)a.U * ctiles * ((a.S + 2 * spw - 1) / (2 * spw)) >= 512) spw *= 2;
+  if (const char* e = getenv("LASER_STA_SPW")) {   // tuning override
+    const int vv = atoi(e);
+    if (vv >= 1 && vv <= 64) spw = vv;
+  }
   const int sruns = (a.S + spw - 1) / spw;
   const float nsl = -1.4426950408889634f / a.gamma;
   const int key = a.d_q * 1000 + a.d;
