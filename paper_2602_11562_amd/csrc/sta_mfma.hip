@@ -38,7 +38,8 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int TI = 64;    // history items staged per step
 constexpr int CW = 32;    // candidates per wave
-constexpr int OP = 136;   // output patch row pitch in bytes: 64 bf16 + 8 (write side spreads over all banks)
+// output patch row pitch in bytes: one H' row + 16 (keeps 16-byte alignment for the row-wise read-back)
+template <int D> struct OPitch { static constexpr int v = D * 2 + 16; };
 
 // LDS row pitches in bytes. K rows are read 16 B per lane by 32 consecutive items: pitch = 16 mod 256 spreads
 // them over all banks. V rows are read by the transpose load, four consecutive items x 64 B: pitch = 64 mod 256.
@@ -54,35 +55,48 @@ template <int DQ, int D, int NT>
 struct Stage {
   static constexpr int KCH = DQ / 8, VCH = D / 8;   // 16-byte chunks per row
   static constexpr int KIT = (TI * KCH + NT - 1) / NT, VIT = (TI * VCH + NT - 1) / NT;
+  static constexpr bool KEXACT = (TI * KCH) % NT == 0, VEXACT = (TI * VCH) % NT == 0;
   u32x4 kr[KIT], vr[VIT];
+  int nvalid;   // rows of the tile that hold valid items
 
-  // global -> registers; rows at or past `hi` (absolute item index) come back as zeros
+  // global -> registers. Straight-line code (no per-lane branches) so that the loads stay in flight while the
+  // caller computes: rows at or past `hi` are fetched from the last valid row instead and zeroed in store().
+  // Requires t0 < hi.
   __device__ __forceinline__ void load(const unsigned short* kU, const unsigned short* vU, int t0, int hi, int tid) {
+    nvalid = hi - t0;
+    const int last = nvalid - 1;
 #pragma unroll
     for (int it = 0; it < KIT; ++it) {
-      const int e = tid + it * NT, r = e / KCH, ch = e % KCH;
-      kr[it] = u32x4{0u, 0u, 0u, 0u};
-      if (e < TI * KCH && t0 + r < hi) kr[it] = *reinterpret_cast<const u32x4*>(kU + (size_t)(t0 + r) * DQ + ch * 8);
+      int e = tid + it * NT;
+      if (!KEXACT) e = e < TI * KCH ? e : TI * KCH - 1;
+      int r = e / KCH;
+      const int ch = e % KCH;
+      r = r < last ? r : last;
+      kr[it] = *reinterpret_cast<const u32x4*>(kU + (size_t)(t0 + r) * DQ + ch * 8);
     }
 #pragma unroll
     for (int it = 0; it < VIT; ++it) {
-      const int e = tid + it * NT, r = e / VCH, ch = e % VCH;
-      vr[it] = u32x4{0u, 0u, 0u, 0u};
-      if (e < TI * VCH && t0 + r < hi) vr[it] = *reinterpret_cast<const u32x4*>(vU + (size_t)(t0 + r) * D + ch * 8);
+      int e = tid + it * NT;
+      if (!VEXACT) e = e < TI * VCH ? e : TI * VCH - 1;
+      int r = e / VCH;
+      const int ch = e % VCH;
+      r = r < last ? r : last;
+      vr[it] = *reinterpret_cast<const u32x4*>(vU + (size_t)(t0 + r) * D + ch * 8);
     }
   }
-  // registers -> LDS
+  // registers -> LDS, padding rows as zeros
   __device__ __forceinline__ void store(unsigned char* Ks, unsigned char* Vs, int tid) const {
     constexpr int KP = KPitch<DQ>::v, VP = VPitch<D>::v;
+    const u32x4 zero = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int it = 0; it < KIT; ++it) {
       const int e = tid + it * NT, r = e / KCH, ch = e % KCH;
-      if (e < TI * KCH) *reinterpret_cast<u32x4*>(Ks + r * KP + ch * 16) = kr[it];
+      if (KEXACT || e < TI * KCH) *reinterpret_cast<u32x4*>(Ks + r * KP + ch * 16) = r < nvalid ? kr[it] : zero;
     }
 #pragma unroll
     for (int it = 0; it < VIT; ++it) {
       const int e = tid + it * NT, r = e / VCH, ch = e % VCH;
-      if (e < TI * VCH) *reinterpret_cast<u32x4*>(Vs + r * VP + ch * 16) = vr[it];
+      if (VEXACT || e < TI * VCH) *reinterpret_cast<u32x4*>(Vs + r * VP + ch * 16) = r < nvalid ? vr[it] : zero;
     }
   }
 };
@@ -97,6 +111,7 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short*
   constexpr int KP = KPitch<DQ>::v, VP = VPitch<D>::v;
   constexpr int NT = 64 * NW;
   constexpr int KSTEPS = DQ / 16, DB = D / 32;
+  constexpr int OP = OPitch<D>::v;
   constexpr int KBYTES = TI * KP, VBYTES = TI * VP, OBYTES = CW * OP;
   __shared__ __attribute__((aligned(16))) unsigned char smem[NBUF * (KBYTES + VBYTES) + NW * OBYTES];
 
@@ -156,6 +171,21 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short*
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[db][r] = 0.0f;
 
+  // patch -> global: 16 lanes x 16 B = one row; LDS operations of a wave execute in order, so the rows written
+  // by this wave above are visible to its own reads here without a barrier
+  constexpr int LPR = D / 8, RPI = 64 / LPR;   // lanes per row, rows per instruction
+  auto flush = [&](int seg) {
+#pragma unroll
+    for (int it = 0; it < CW / RPI; ++it) {
+      const int row = it * RPI + lane / LPR;
+      const u32x4 val = *reinterpret_cast<const u32x4*>(opatch + row * OP + (lane % LPR) * 16);
+      const int cr = cbase + row;
+      if (cr < C)
+        *reinterpret_cast<u32x4*>(seg_out + (((size_t)u * C + cr) * S + seg) * D + (lane % LPR) * 8) = val;
+    }
+  };
+  int out_seg = -1;
+
   while (ci < seg_ne) {
     // next tile in the run (same segment, or the first tile of the next non-empty segment)
     int ni = ci, nt0 = ct0 + TI, nhi = chi;
@@ -167,7 +197,13 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short*
     const bool has_next = ni < seg_ne;
     unsigned char* Ks = smem + buf * (KBYTES + VBYTES);
     unsigned char* Vs = Ks + KBYTES;
-    if (NBUF == 2 && has_next) st.load(kU, vU, nt0, nhi, tid);   // in flight during the MFMA work below
+    // in flight during the MFMA work below; with no next tile the current one is read again (in bounds, unused)
+    // so that the instruction stream stays free of branches around the loads
+    if (NBUF == 2) st.load(kU, vU, has_next ? nt0 : ct0, has_next ? nhi : chi, tid);
+    if (out_seg >= 0) {
+      flush(out_seg);
+      out_seg = -1;
+    }
 
 #pragma unroll
     for (int ib = 0; ib < TI / 32; ++ib) {
@@ -209,29 +245,24 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short*
       }
     }
 
+    // the prefetched tile goes to the other buffer first (its loads were issued a whole tile ago), then the
+    // finished segment is written out; those global stores drain during the next tile
+    if (NBUF == 2 && has_next)
+      st.store(smem + (buf ^ 1) * (KBYTES + VBYTES), smem + (buf ^ 1) * (KBYTES + VBYTES) + KBYTES, tid);
     if (ni != ci) {
-      // ---- segment finished: H'[u, c, ci, :] through the wave-private patch, 64 value columns per pass
+      // ---- segment finished: H'[u, c, ci, :] is parked in the wave-private patch as bf16 rows; it is written
+      // to global memory at the top of the next step, behind that step's prefetch loads, so that waiting for
+      // the prefetch never has to wait for these stores first
 #pragma unroll
-      for (int ps = 0; ps < D / 64; ++ps) {
+      for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int dbl = 0; dbl < 2; ++dbl)
+        for (int g = 0; g < 4; ++g) {
+          bf16x4 o;
 #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            bf16x4 o;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[ps * 2 + dbl][g * 4 + e];
-            *reinterpret_cast<u32x2*>(opatch + l32 * OP + (dbl * 32 + g * 8 + h * 4) * 2) = __builtin_bit_cast(u32x2, o);
-          }
-        // read back row-wise: 16 lanes x 8 B = one 128-byte row piece; 4 rows per instruction
-#pragma unroll
-        for (int it = 0; it < 8; ++it) {
-          const int row = it * 4 + (lane >> 4);
-          const u32x2 val = *reinterpret_cast<const u32x2*>(opatch + row * OP + (lane & 15) * 8);
-          const int cr = cbase + row;
-          if (cr < C)
-            *reinterpret_cast<u32x2*>(seg_out + (((size_t)u * C + cr) * S + ci) * D + ps * 64 + (lane & 15) * 4) = val;
+          for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[db][g * 4 + e];
+          *reinterpret_cast<u32x2*>(opatch + l32 * OP + (db * 32 + g * 8 + h * 4) * 2) = __builtin_bit_cast(u32x2, o);
         }
-      }
+      out_seg = ci;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -239,7 +270,6 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short*
     }
 
     if (NBUF == 2) {
-      if (has_next) st.store(smem + (buf ^ 1) * (KBYTES + VBYTES), smem + (buf ^ 1) * (KBYTES + VBYTES) + KBYTES, tid);
       __syncthreads();
       buf ^= 1;
     } else {
@@ -254,6 +284,8 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short*
     ct0 = nt0;
     chi = nhi;
   }
+
+  if (out_seg >= 0) flush(out_seg);
 
   // empty segments of the run: exact zeros, 16 bytes per thread
   if (seg_ne < seg_hi) {
