@@ -12,8 +12,13 @@
 //
 // fp32 operands of the MFMA steps (t, q', p) are split into a bf16 head and a bf16 remainder and multiplied
 // in two passes, so the products carry ~16 significant bits; weights and H' are bf16 by storage. The running
-// target t stays in fp32 registers in accumulator layout. Weight operands come straight from global memory
-// (L2 resident, 3 d^2 elements per layer). Two fp32 [32 x d] LDS buffers carry the operands between steps.
+// target t stays in fp32 registers in accumulator layout. W_q and W_v (contraction index = row index, the slow
+// one in memory) are staged in LDS with coalesced loads and read with the LDS transpose load; W_k is read in
+// operand order straight from global memory (L2 resident). Two fp32 [32 x d] LDS buffers carry the operands
+// between steps. The H' block of a wave's next pair is requested before the current pair is reduced, and the
+// first one before the projection steps, so the HBM stream runs behind the arithmetic.
+#include <cstdlib>
+
 #include "laser_internal.h"
 
 namespace laser {
@@ -23,7 +28,9 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int GT_PAIRS = 32;
+constexpr int GT_ROWS = 32;     // MFMA row block; a workgroup owns PT <= 32 pairs, the other rows are padding
+constexpr int GT_WAVES = 8;     // waves per workgroup: all of them stream H', the first d/32 also run the MFMA steps
+constexpr int GT_THREADS = 64 * GT_WAVES;
 
 struct HiLo {
   bf16x8 hi, lo;
@@ -44,32 +51,83 @@ __device__ __forceinline__ HiLo split8(const float* p) {
   return o;
 }
 
-// [32 x D] (LDS, fp32, pitch FP) times W (global bf16 [D][D]) -> 32 x 32 block `nb` of the product.
-// TRANSPOSED = false: out = X W      (B operand k = row of W: eight 2-byte loads per lane per step)
-// TRANSPOSED = true : out = X W^T    (B operand k = column of W: one 16-byte load per lane per step)
-template <int D, bool TRANSPOSED>
-__device__ __forceinline__ f32x16 tile_gemm(const float* X, int FP, const unsigned short* __restrict__ W, int nb,
-                                            int l32, int h) {
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+template <int D> struct WPitch { static constexpr int v = (D * 2) % 256 == 64 ? D * 2 : D * 2 + 64; };
+
+// [32 x D] (LDS, fp32, pitch FP) times W^T with W bf16 [D][D] in global memory -> 32 x 32 block `nb`:
+// out[p][n] = sum_k X[p][k] W[n][k]. The B operand (k contiguous per lane) is one 16-byte load per step.
+template <int D>
+__device__ __forceinline__ f32x16 tile_gemm_wt(const float* X, int FP, const unsigned short* __restrict__ W, int nb,
+                                               int l32, int h) {
   f32x16 acc;
 #pragma unroll
   for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
   const int n = nb * 32 + l32;
+  bf16x8 b[D / 16];
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks)
+    b[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(W + (size_t)n * D + ks * 16 + h * 8));
 #pragma unroll
   for (int ks = 0; ks < D / 16; ++ks) {
-    const int k0 = ks * 16 + h * 8;
-    bf16x8 b;
-    if (TRANSPOSED) {
-      b = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(W + (size_t)n * D + k0));
-    } else {
+    const HiLo a = split8(X + l32 * FP + ks * 16 + h * 8);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.hi, b[ks], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.lo, b[ks], acc, 0, 0, 0);
+  }
+  return acc;
+}
+
+// [32 x D] (LDS, fp32, pitch FP) times W with W bf16 [D][D] staged row-major in LDS (pitch WPitch) ->
+// 32 x 32 block `nb`: out[p][n] = sum_k X[p][k] W[k][n]. The B operand wants k contiguous per lane, i.e. a
+// column of W: fetched with the LDS transpose load (lane i of a 16-lane group supplies the address of
+// W[k0 + i/4][n0 + 4 (i%4)] and receives W[k0 .. k0+3][n0 + i]).
+template <int D>
+__device__ __forceinline__ f32x16 tile_gemm_lds(const float* X, int FP, const unsigned char* Wl, int nb, int lane,
+                                                int l32, int h) {
+  constexpr int WP = WPitch<D>::v;
+  f32x16 acc;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) b[i] = __builtin_bit_cast(__bf16, W[(size_t)(k0 + i) * D + n]);
-    }
-    const HiLo a = split8(X + l32 * FP + k0);
+  for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+  const int i16 = lane & 15;
+  const unsigned char* base = Wl + (h * 8 + (i16 >> 2)) * WP + (nb * 32 + (l32 & 16) + 4 * (i16 & 3)) * 2;
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) {
+    const unsigned char* src = base + ks * 16 * WP;
+    const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(src));
+    const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(src + 4 * WP));
+    const bf16x8 b = __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7));
+    const HiLo a = split8(X + l32 * FP + ks * 16 + h * 8);
     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.hi, b, acc, 0, 0, 0);
     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.lo, b, acc, 0, 0, 0);
   }
   return acc;
 }
+
+// W [D][D] bf16: global -> registers (coalesced 16-byte chunks) and registers -> LDS, split so that the loads can
+// be in flight across other work
+template <int D>
+struct WStage {
+  static constexpr int IT = (D * (D / 8) + GT_THREADS - 1) / GT_THREADS;
+  static constexpr bool EXACT = (D * (D / 8)) % GT_THREADS == 0;
+  u32x4 r[IT];
+  __device__ __forceinline__ void load(const unsigned short* __restrict__ W, int tid) {
+#pragma unroll
+    for (int it = 0; it < IT; ++it) {
+      int e = tid + it * GT_THREADS;
+      if (!EXACT) e = e < D * (D / 8) ? e : D * (D / 8) - 1;
+      r[it] = *reinterpret_cast<const u32x4*>(W + (size_t)e * 8);
+    }
+  }
+  __device__ __forceinline__ void store(unsigned char* Wl, int tid) const {
+    constexpr int WP = WPitch<D>::v, CH = D / 8;
+#pragma unroll
+    for (int it = 0; it < IT; ++it) {
+      const int e = tid + it * GT_THREADS, row = e / CH, ch = e % CH;
+      if (EXACT || e < D * CH) *reinterpret_cast<u32x4*>(Wl + row * WP + ch * 16) = r[it];
+    }
+  }
+};
 
 // accumulator layout: lane = column nb*32 + l32, register r = row 8 (r/4) + 4 h + r % 4
 __device__ __forceinline__ void store_acc(float* X, int FP, const f32x16& acc, int nb, int l32, int h, float scale) {
@@ -77,8 +135,8 @@ __device__ __forceinline__ void store_acc(float* X, int FP, const f32x16& acc, i
   for (int r = 0; r < 16; ++r) X[(8 * (r >> 2) + 4 * h + (r & 3)) * FP + nb * 32 + l32] = acc[r] * scale;
 }
 
-template <int D, int ROWS>
-__global__ __launch_bounds__(256) void gsta_tiled_kernel(const unsigned short* __restrict__ seg,
+template <int D, int ROWS, int PT>
+__global__ __launch_bounds__(GT_THREADS) void gsta_tiled_kernel(const unsigned short* __restrict__ seg,
                                                          const unsigned short* __restrict__ t0,
                                                          const unsigned short* __restrict__ wq,
                                                          const unsigned short* __restrict__ wk,
@@ -89,58 +147,81 @@ __global__ __launch_bounds__(256) void gsta_tiled_kernel(const unsigned short* _
   constexpr int DB = D / 32;         // 32-column blocks; waves >= DB idle in the MFMA steps
   constexpr int LPR = D / 8;         // lanes per H' row (16 B each)
   constexpr int RPW = 64 / LPR;      // rows per wave-wide load
-  __shared__ __attribute__((aligned(16))) float bufA[GT_PAIRS * FP];
-  __shared__ __attribute__((aligned(16))) float bufB[GT_PAIRS * FP];
+  constexpr int WP = WPitch<D>::v;
+  constexpr int PPW = PT / GT_WAVES;  // pairs per wave in step 3
+  __shared__ __attribute__((aligned(16))) float bufA[GT_ROWS * FP];
+  __shared__ __attribute__((aligned(16))) float bufB[GT_ROWS * FP];
+  __shared__ __attribute__((aligned(16))) unsigned char Wl[D * WP];
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int l32 = lane & 31, h = lane >> 5;
-  const int pbase = blockIdx.x * GT_PAIRS;
+  const int pbase = blockIdx.x * PT;
   const float scale = 1.0f / sqrtf((float)D);
+  const int grp = lane / LPR, gl = lane % LPR;   // row group and position inside the row
+
+  WStage<D> ws;
+  ws.load(wq, tid);
+
+  // valid segments of the wave's pairs (independent loads, one round trip)
+  int nvs[PPW];
+#pragma unroll
+  for (int it = 0; it < PPW; ++it) {
+    const int pr = pbase + wave + it * GT_WAVES;
+    nvs[it] = 0;
+    if (pr < P) nvs[it] = (valid_len(lens, pr / C, L) + w - 1) / w;
+  }
+  // H' block of one pair: rows j*RPW + grp, 16 bytes per lane; rows of invalid segments are not read.
+  // DEPTH blocks are kept in flight per wave (a ring of register sets).
+  constexpr int DEPTH_WANT = ROWS <= 4 ? 4 : 2;
+  constexpr int DEPTH = DEPTH_WANT < PPW ? DEPTH_WANT : PPW;   // H' blocks in flight per wave (register sets)
+  u32x4 hring[DEPTH][ROWS];
+  auto load_pair = [&](int pi, int nv, u32x4 (&hreg)[ROWS]) {
+    const unsigned short* H = seg + (size_t)(pbase + pi) * S * D;
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j) {
+      const int i = j * RPW + grp;
+      hreg[j] = u32x4{0u, 0u, 0u, 0u};
+      if (i < nv) hreg[j] = *reinterpret_cast<const u32x4*>(H + (size_t)i * D + gl * 8);
+    }
+  };
+#pragma unroll
+  for (int dd = 0; dd < DEPTH; ++dd) load_pair(wave + dd * GT_WAVES, nvs[dd], hring[dd]);   // in flight during steps 1-2
 
   // running target t in accumulator layout (wave = column block)
   f32x16 ts;
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
-    const int pr = pbase + 8 * (r >> 2) + 4 * h + (r & 3);
-    ts[r] = (wave < DB && pr < P) ? bf16_bits_to_f32(t0[(size_t)pr * D + wave * 32 + l32]) : 0.0f;
+    const int row = 8 * (r >> 2) + 4 * h + (r & 3);
+    const int pr = pbase + row;
+    ts[r] = (wave < DB && row < PT && pr < P) ? bf16_bits_to_f32(t0[(size_t)pr * D + wave * 32 + l32]) : 0.0f;
   }
 
-  const int grp = lane / LPR, gl = lane % LPR;   // row group and position inside the row
-
   for (int layer = 0; layer < M; ++layer) {
-    const unsigned short* Wq = wq + (size_t)layer * D * D;
     const unsigned short* Wk = wk + (size_t)layer * D * D;
     const unsigned short* Wv = wv + (size_t)layer * D * D;
 
+    ws.store(Wl, tid);                                 // W_q of this layer
     if (wave < DB) store_acc(bufA, FP, ts, wave, l32, h, 1.0f);
     __syncthreads();
     if (wave < DB) {                                   // step 1: q' = t W_q
-      const f32x16 qp = tile_gemm<D, false>(bufA, FP, Wq, wave, l32, h);
+      const f32x16 qp = tile_gemm_lds<D>(bufA, FP, Wl, wave, lane, l32, h);
       store_acc(bufB, FP, qp, wave, l32, h, 1.0f);
     }
     __syncthreads();
+    ws.load(Wv, tid);                                  // W_v: in flight during step 2, W_q is no longer needed
     if (wave < DB) {                                   // step 2: r = q' W_k^T / sqrt(d)
-      const f32x16 rr = tile_gemm<D, true>(bufB, FP, Wk, wave, l32, h);
+      const f32x16 rr = tile_gemm_wt<D>(bufB, FP, Wk, wave, l32, h);
       store_acc(bufA, FP, rr, wave, l32, h, scale);
     }
+    ws.store(Wl, tid);
     __syncthreads();
 
     // step 3: one pair per wave at a time; its H' block goes through registers once
-    for (int pi = wave; pi < GT_PAIRS; pi += 4) {
-      const int pr = pbase + pi;
-      int nv = 0;
-      if (pr < P) {
-        const int n = valid_len(lens, pr / C, L);
-        nv = (n + w - 1) / w;
-      }
-      u32x4 hreg[ROWS];
-      const unsigned short* H = seg + (size_t)pr * S * D;
+    if (layer > 0) {
 #pragma unroll
-      for (int j = 0; j < ROWS; ++j) {
-        const int i = j * RPW + grp;
-        hreg[j] = u32x4{0u, 0u, 0u, 0u};
-        if (i < nv) hreg[j] = *reinterpret_cast<const u32x4*>(H + (size_t)i * D + gl * 8);
-      }
+      for (int dd = 0; dd < DEPTH; ++dd) load_pair(wave + dd * GT_WAVES, nvs[dd], hring[dd]);
+    }
+    auto reduce_pair = [&](int pi, int nv, u32x4 (&hcur)[ROWS], int refill_pi, int refill_nv) {
       float rs[8];
       {
         const f32x4 a = *reinterpret_cast<const f32x4*>(bufA + pi * FP + gl * 8);
@@ -148,43 +229,46 @@ __global__ __launch_bounds__(256) void gsta_tiled_kernel(const unsigned short* _
 #pragma unroll
         for (int e = 0; e < 4; ++e) { rs[e] = a[e]; rs[4 + e] = b[e]; }
       }
-      float e_[ROWS];
-      float mx = -INFINITY;
-#pragma unroll
-      for (int j = 0; j < ROWS; ++j) {
-        float s = 0.0f;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          s = fmaf(__uint_as_float(hreg[j][e] << 16), rs[2 * e], s);
-          s = fmaf(__uint_as_float(hreg[j][e] & 0xffff0000u), rs[2 * e + 1], s);
-        }
-#pragma unroll
-        for (int off = 1; off < LPR; off <<= 1) s += __shfl_xor(s, off, 64);
-        const bool ok = (j * RPW + grp) < nv;
-        e_[j] = ok ? s : -INFINITY;
-        mx = fmaxf(mx, e_[j]);
-      }
-#pragma unroll
-      for (int off = LPR; off < 64; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
-      float den = 0.0f;
+      // one pass with a running maximum (per lane group, merged across groups afterwards): each row's values
+      // are converted once and used for both the score and the weighted sum
+      float m = -INFINITY, den = 0.0f;
       float pacc[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) pacc[e] = 0.0f;
 #pragma unroll
       for (int j = 0; j < ROWS; ++j) {
-        const float a = (e_[j] == -INFINITY) ? 0.0f : __expf(e_[j] - mx);
-        den += a;
+        float x[8];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          pacc[2 * e] = fmaf(a, __uint_as_float(hreg[j][e] << 16), pacc[2 * e]);
-          pacc[2 * e + 1] = fmaf(a, __uint_as_float(hreg[j][e] & 0xffff0000u), pacc[2 * e + 1]);
+          x[2 * e] = __uint_as_float(hcur[j][e] << 16);
+          x[2 * e + 1] = __uint_as_float(hcur[j][e] & 0xffff0000u);
         }
+        float sdot = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sdot = fmaf(x[e], rs[e], sdot);
+#pragma unroll
+        for (int off = 1; off < LPR; off <<= 1) sdot += __shfl_xor(sdot, off, 64);
+        const bool ok = (j * RPW + grp) < nv;
+        const float m_new = ok ? fmaxf(m, sdot) : m;
+        const float sc = (m == m_new) ? 1.0f : __expf(m - m_new);
+        const float a = ok ? __expf(sdot - m_new) : 0.0f;
+        den = fmaf(den, sc, a);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pacc[e] = fmaf(pacc[e], sc, a * x[e]);
+        m = m_new;
       }
+      if (refill_pi >= 0) load_pair(refill_pi, refill_nv, hcur);   // refill the slot: next block in flight
 #pragma unroll
       for (int off = LPR; off < 64; off <<= 1) {
-        den += __shfl_xor(den, off, 64);
+        const float m_o = __shfl_xor(m, off, 64);
+        const float den_o = __shfl_xor(den, off, 64);
+        const float M2 = fmaxf(m, m_o);
+        const float f = (m == M2) ? 1.0f : __expf(m - M2);
+        const float f_o = (m_o == M2) ? 1.0f : __expf(m_o - M2);
+        den = den * f + den_o * f_o;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) pacc[e] += __shfl_xor(pacc[e], off, 64);
+        for (int e = 0; e < 8; ++e) pacc[e] = pacc[e] * f + __shfl_xor(pacc[e], off, 64) * f_o;
+        m = M2;
       }
       if (grp == 0) {
         const float inv = nv > 0 ? 1.0f / den : 0.0f;
@@ -194,22 +278,38 @@ __global__ __launch_bounds__(256) void gsta_tiled_kernel(const unsigned short* _
         *reinterpret_cast<f32x4*>(bufB + pi * FP + gl * 8) = a;
         *reinterpret_cast<f32x4*>(bufB + pi * FP + gl * 8 + 4) = b;
       }
+    };
+    if constexpr (DEPTH > 1) {
+#pragma unroll
+      for (int it = 0; it < PPW; ++it) {
+        const bool more = it + DEPTH < PPW;
+        reduce_pair(wave + it * GT_WAVES, nvs[it], hring[it % DEPTH], more ? wave + (it + DEPTH) * GT_WAVES : -1,
+                    more ? nvs[(it + DEPTH) % PPW] : 0);
+      }
+    } else {
+#pragma unroll 1
+      for (int it = 0; it < PPW; ++it) {
+        const int pr = pbase + wave + it * GT_WAVES;
+        int nv = 0;
+        if (pr < P) nv = (valid_len(lens, pr / C, L) + w - 1) / w;
+        if (it > 0) load_pair(wave + it * GT_WAVES, nv, hring[0]);
+        reduce_pair(wave + it * GT_WAVES, nv, hring[0], -1, 0);
+      }
     }
     __syncthreads();
     if (wave < DB) {                                   // step 4: o = p W_v ; t += o
-      const f32x16 o = tile_gemm<D, false>(bufB, FP, Wv, wave, l32, h);
+      const f32x16 o = tile_gemm_lds<D>(bufB, FP, Wl, wave, lane, l32, h);
 #pragma unroll
       for (int r = 0; r < 16; ++r) ts[r] += o[r];
     }
-    // bufA is next written after this point only by waves that have passed the barrier above; bufB is next
-    // written in step 1 of the next layer, after the barrier that follows the bufA store.
+    if (layer + 1 < M) ws.load(wq + (size_t)(layer + 1) * D * D, tid);
+    __syncthreads();   // W_v and bufB fully consumed before the next layer overwrites them
   }
 
   // z: through LDS for coalesced fp32 rows
-  __syncthreads();
   if (wave < DB) store_acc(bufA, FP, ts, wave, l32, h, 1.0f);
   __syncthreads();
-  for (int e = tid; e < GT_PAIRS * (D / 4); e += 256) {
+  for (int e = tid; e < PT * (D / 4); e += GT_THREADS) {
     const int row = e / (D / 4), c4 = e - row * (D / 4);
     if (pbase + row < P)
       *reinterpret_cast<f32x4*>(z + (size_t)(pbase + row) * D + c4 * 4) =
@@ -222,16 +322,34 @@ static int rows_needed(int S, int d) { return (S + (64 / (d / 8)) - 1) / (64 / (
 bool gsta_tiled_supports(const GstaArgs& a) {
   if (a.dt != LASER_BF16) return false;
   if (!(a.d == 64 || a.d == 128)) return false;
-  return rows_needed(a.S, a.d) <= 32;
+  return rows_needed(a.S, a.d) <= 10;   // the pair's H' block must fit a wave's registers several times over
+}
+
+template <int D, int ROWS, int PT>
+static void launch_pt(const GstaArgs& a) {
+  const int P = a.U * a.C;
+  hipLaunchKernelGGL((gsta_tiled_kernel<D, ROWS, PT>), dim3((P + PT - 1) / PT), dim3(GT_THREADS), 0, a.stream,
+                     (const unsigned short*)a.seg, (const unsigned short*)a.t0, (const unsigned short*)a.wq,
+                     (const unsigned short*)a.wk, (const unsigned short*)a.wv, a.lens, P, a.C, a.L, a.w, a.S, a.M,
+                     a.z_out);
+}
+
+// pairs per workgroup: fewer when the batch is small, so that every compute unit still gets a few workgroups
+static int pick_pt(int P) {
+  int pt = P >= 8192 ? 32 : 8;   // measured: the per-workgroup set-up cost favours full tiles once every compute unit has one
+  if (const char* e = getenv("LASER_GSTA_PT")) {   // tuning override
+    const int vv = atoi(e);
+    if (vv == 8 || vv == 16 || vv == 32) pt = vv;
+  }
+  return pt;
 }
 
 template <int D, int ROWS>
 static void launch_rows(const GstaArgs& a) {
-  const int P = a.U * a.C;
-  hipLaunchKernelGGL((gsta_tiled_kernel<D, ROWS>), dim3((P + GT_PAIRS - 1) / GT_PAIRS), dim3(256), 0, a.stream,
-                     (const unsigned short*)a.seg, (const unsigned short*)a.t0, (const unsigned short*)a.wq,
-                     (const unsigned short*)a.wk, (const unsigned short*)a.wv, a.lens, P, a.C, a.L, a.w, a.S, a.M,
-                     a.z_out);
+  const int pt = pick_pt(a.U * a.C);
+  if (pt == 32) launch_pt<D, ROWS, 32>(a);
+  else if (pt == 16) launch_pt<D, ROWS, 16>(a);
+  else launch_pt<D, ROWS, 8>(a);
 }
 
 template <int D>
@@ -240,9 +358,7 @@ static void launch_d(const GstaArgs& a) {
   if (rows <= 2) launch_rows<D, 2>(a);
   else if (rows <= 4) launch_rows<D, 4>(a);
   else if (rows <= 8) launch_rows<D, 8>(a);
-  else if (rows <= 10) launch_rows<D, 10>(a);
-  else if (rows <= 16) launch_rows<D, 16>(a);
-  else launch_rows<D, 32>(a);
+  else launch_rows<D, 10>(a);
 }
 
 laser_status gsta_tiled_launch(const GstaArgs& a) {

@@ -301,6 +301,195 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short*
   }
 }
 
+// ------------------------------------------------------------------------------------------ pipelined form
+// Same mapping and arithmetic as above, with the two 32-item blocks of a tile software-pipelined inside each
+// wave so that the sigmoid work (VALU, transcendental unit) of one block runs in the shadow of the MFMAs of
+// another:
+//   phase A   Sc(b1) = K.Q^T            ||  P(b0) = sigmoid(Sc(b0))
+//   phase B   acc += V^T(b0).P(b0)      ||  P(b1) = sigmoid(Sc(b1))
+//   phase C   acc += V^T(b1).P(b1)          then the prefetched tile goes to the other LDS buffer
+//   barrier
+//   phase D   Sc(b0 of the next tile) = K.Q^T
+// Every tile is computed in full (its padding rows are zeros in LDS), so the phases are straight-line code.
+template <int DQ, int D, int NW>
+__global__ __launch_bounds__(64 * NW) void sta_mfma_pipe_kernel(const unsigned short* __restrict__ q,
+                                                                const unsigned short* __restrict__ k,
+                                                                const unsigned short* __restrict__ v,
+                                                                const int32_t* __restrict__ lens, int C, int L,
+                                                                int w, int S, int spw, int ctiles, int sruns,
+                                                                float neg_scale_log2e,
+                                                                unsigned short* __restrict__ seg_out) {
+  constexpr int KP = KPitch<DQ>::v, VP = VPitch<D>::v;
+  constexpr int NT = 64 * NW;
+  constexpr int KSTEPS = DQ / 16, DB = D / 32;
+  constexpr int OP = OPitch<D>::v;
+  constexpr int KBYTES = TI * KP, VBYTES = TI * VP, OBYTES = CW * OP;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * (KBYTES + VBYTES) + NW * OBYTES];
+
+  int bid = blockIdx.x;
+  const int srun = bid % sruns;
+  bid /= sruns;
+  const int ct = bid % ctiles;
+  const int u = bid / ctiles;
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int l32 = lane & 31, h = lane >> 5;
+  const int cbase = ct * (CW * NW) + wave * CW;
+  const int n = valid_len(lens, u, L);
+  unsigned char* opatch = smem + 2 * (KBYTES + VBYTES) + wave * OBYTES;
+
+  bf16x8 qreg[KSTEPS];
+  {
+    const int c = cbase + l32;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+      u32x4 raw = {0u, 0u, 0u, 0u};
+      if (c < C) raw = *reinterpret_cast<const u32x4*>(q + ((size_t)u * C + c) * DQ + ks * 16 + h * 8);
+      qreg[ks] = __builtin_bit_cast(bf16x8, raw);
+    }
+  }
+
+  const unsigned short* kU = k + (size_t)u * L * DQ;
+  const unsigned short* vU = v + (size_t)u * L * D;
+
+  const int seg_lo = srun * spw;
+  const int seg_hi = (seg_lo + spw) < S ? (seg_lo + spw) : S;
+  int seg_ne = seg_lo;
+  while (seg_ne < seg_hi && seg_ne * w < n) ++seg_ne;
+  auto seg_end = [&](int i) {
+    int e = i * w + w;
+    if (e > L) e = L;
+    if (e > n) e = n;
+    return e;
+  };
+
+  // per-lane LDS offsets that do not change: K operand row (block 0) and the transpose-load source
+  const int koff = l32 * KP + h * 16;
+  const int voff = (h * 4 + ((lane & 15) >> 2)) * VP + ((l32 & 16) + 4 * (lane & 3)) * 2;
+
+  auto score = [&](const unsigned char* Ks, int ib) {   // Sc^T of block ib: 32 items x 32 candidates
+    f32x16 sc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sc[r] = 0.0f;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(Ks + ib * 32 * KP + koff + ks * 32);
+      sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], sc, 0, 0, 0);
+    }
+    return sc;
+  };
+  f32x16 acc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[db][r] = 0.0f;
+  auto aggregate = [&](const unsigned char* Vs, int ib, const bf16x8 (&p)[2]) {   // acc^T += V^T . P^T
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const unsigned char* src = Vs + (ib * 32 + s * 16) * VP + voff + db * 64;
+        const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(src));
+        const s16x4 hi4 =
+            __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(src + 8 * VP));
+        const s16x8 both = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), p[s], acc[db], 0, 0, 0);
+      }
+  };
+  auto gates = [&](const f32x16& sc, bf16x8 (&p)[2]) {
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) p[s][e] = (__bf16)gate(sc[s * 8 + e], neg_scale_log2e);
+  };
+
+  constexpr int LPR = D / 8, RPI = 64 / LPR;
+  auto flush = [&](int seg) {
+#pragma unroll
+    for (int it = 0; it < CW / RPI; ++it) {
+      const int row = it * RPI + lane / LPR;
+      const u32x4 val = *reinterpret_cast<const u32x4*>(opatch + row * OP + (lane % LPR) * 16);
+      const int cr = cbase + row;
+      if (cr < C)
+        *reinterpret_cast<u32x4*>(seg_out + (((size_t)u * C + cr) * S + seg) * D + (lane % LPR) * 8) = val;
+    }
+  };
+
+  Stage<DQ, D, NT> st;
+  int ci = seg_lo, ct0 = seg_lo * w, chi = seg_ne > seg_lo ? seg_end(seg_lo) : 0;
+  int buf = 0, out_seg = -1;
+  f32x16 sc0;
+  if (seg_ne > seg_lo) {
+    st.load(kU, vU, ct0, chi, tid);
+    st.store(smem, smem + KBYTES, tid);
+  }
+  __syncthreads();
+  if (seg_ne > seg_lo) sc0 = score(smem, 0);
+
+  while (ci < seg_ne) {
+    int ni = ci, nt0 = ct0 + TI, nhi = chi;
+    if (nt0 >= chi) {
+      ni = ci + 1;
+      nt0 = ni * w;
+      nhi = ni < seg_ne ? seg_end(ni) : 0;
+    }
+    const bool has_next = ni < seg_ne;
+    const unsigned char* Ks = smem + buf * (KBYTES + VBYTES);
+    const unsigned char* Vs = Ks + KBYTES;
+    unsigned char* nKs = smem + (buf ^ 1) * (KBYTES + VBYTES);
+
+    st.load(kU, vU, has_next ? nt0 : ct0, has_next ? nhi : chi, tid);   // lands during phases A-C
+    if (out_seg >= 0) {
+      flush(out_seg);
+      out_seg = -1;
+    }
+
+    bf16x8 p0[2], p1[2];
+    const f32x16 sc1 = score(Ks, 1);   // phase A
+    gates(sc0, p0);
+    aggregate(Vs, 0, p0);              // phase B
+    gates(sc1, p1);
+    aggregate(Vs, 1, p1);              // phase C
+    if (has_next) st.store(nKs, nKs + KBYTES, tid);
+
+    if (ni != ci) {   // segment finished: park H' rows in the patch, stored to global at the top of the next step
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          bf16x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[db][g * 4 + e];
+          *reinterpret_cast<u32x2*>(opatch + l32 * OP + (db * 32 + g * 8 + h * 4) * 2) = __builtin_bit_cast(u32x2, o);
+        }
+      out_seg = ci;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[db][r] = 0.0f;
+    }
+    __syncthreads();
+    buf ^= 1;
+    if (has_next) sc0 = score(nKs, 0);   // phase D
+    ci = ni;
+    ct0 = nt0;
+    chi = nhi;
+  }
+  if (out_seg >= 0) flush(out_seg);
+
+  if (seg_ne < seg_hi) {   // empty segments of the run: exact zeros
+    const int ncand = (C - ct * (CW * NW)) < CW * NW ? (C - ct * (CW * NW)) : CW * NW;
+    const int per_row = D / 8;
+    const int rows = ncand * (seg_hi - seg_ne);
+    for (int e = tid; e < rows * per_row; e += NT) {
+      const int row = e / per_row, ch = e - row * per_row;
+      const int cc = row / (seg_hi - seg_ne), ii = seg_ne + row % (seg_hi - seg_ne);
+      *reinterpret_cast<u32x4*>(seg_out + (((size_t)u * C + ct * (CW * NW) + cc) * S + ii) * D + ch * 8) =
+          u32x4{0u, 0u, 0u, 0u};
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------------------ host side
 static int pick_nw(int C) { return C > 128 ? 8 : (C > 64 ? 4 : (C > 32 ? 2 : 1)); }
 
@@ -326,7 +515,12 @@ template <int DQ, int D>
 static void launch_nw(const StaArgs& a, int nw, int spw, int ctiles, int sruns, float nsl) {
   // eight waves fill a compute unit on their own and prefetch through a second LDS buffer; smaller workgroups
   // overlap memory and MFMA work across the several workgroups that share a compute unit
-  if (nw == 8) launch_one<DQ, D, 8, 2>(a, spw, ctiles, sruns, nsl);
+  if (nw == 8) {
+    const unsigned blocks = (unsigned)((long long)a.U * ctiles * sruns);
+    hipLaunchKernelGGL((sta_mfma_pipe_kernel<DQ, D, 8>), dim3(blocks), dim3(512), 0, a.stream,
+                       (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens,
+                       a.C, a.L, a.w, a.S, spw, ctiles, sruns, nsl, (unsigned short*)a.seg_out);
+  }
   else if (nw == 4) launch_one<DQ, D, 4, 1>(a, spw, ctiles, sruns, nsl);
   else if (nw == 2) launch_one<DQ, D, 2, 1>(a, spw, ctiles, sruns, nsl);
   else launch_one<DQ, D, 1, 1>(a, spw, ctiles, sruns, nsl);
