@@ -1,5 +1,196 @@
+// STA for few candidates per user (C <= 8): an HBM streaming kernel on the vector ALUs.
+//
+// With one or a few candidates the STA equation of Sec. 3.4.2 does about one flop per byte of history read, so
+// the matrix cores have nothing to amortise and the only thing that matters is that K and V are read once, in
+// full 16-byte lanes, with enough loads in flight. One workgroup owns (user, segment); its four waves take
+// alternating chunks of the segment's items. A K row is spread over d_q/8 lanes (16 bytes each), a V row over
+// d/8 lanes: the score is an 8-term dot product per lane plus a shuffle tree over the row's lanes, the gate is
+// evaluated once per (item, candidate), and each lane accumulates gate * v for its 8 value columns. Segment sums
+// are then reduced across the row groups of a wave with shuffles and across the four waves through LDS in a
+// fixed order (deterministic). Items at or past the valid length are neither read nor counted; empty segments
+// are written as zeros.
 #include "laser_internal.h"
+
 namespace laser {
-bool sta_stream_supports(const StaArgs&) { return false; }
-laser_status sta_stream_launch(const StaArgs&) { return LASER_ERR_UNSUPPORTED; }
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void unpack8(const u32x4& r, float (&x)[8]) {
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    x[2 * e] = __uint_as_float(r[e] << 16);
+    x[2 * e + 1] = __uint_as_float(r[e] & 0xffff0000u);
+  }
+}
+
+template <int DQ, int D, int CMAX>
+__global__ __launch_bounds__(256) void sta_stream_kernel(const unsigned short* __restrict__ q,
+                                                         const unsigned short* __restrict__ k,
+                                                         const unsigned short* __restrict__ v,
+                                                         const int32_t* __restrict__ lens, int C, int L, int w, int S,
+                                                         float neg_scale_log2e, unsigned short* __restrict__ seg_out) {
+  constexpr int LQ = DQ / 8, LV = D / 8;           // lanes per K row / V row
+  constexpr int RQ = 64 / LQ, RV = 64 / LV;        // rows per wave-wide load
+  constexpr int IPC = RQ > RV ? RQ : RV;           // items per chunk
+  constexpr int NKL = IPC / RQ, NVL = IPC / RV;    // loads per chunk
+  constexpr bool SAME = (LQ == LV);
+  __shared__ float red[4][CMAX][D];
+  __shared__ float gs[4][CMAX][IPC];
+
+  const int u = blockIdx.x / S, i = blockIdx.x % S;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int n = valid_len(lens, u, L);
+  const int lo = i * w;
+  int hi = lo + w;
+  if (hi > L) hi = L;
+  if (hi > n) hi = n;
+
+  if (hi <= lo) {   // empty segment: exact zeros
+    for (int e = tid; e < C * D; e += 256) {
+      const int c = e / D, col = e - c * D;
+      seg_out[(((size_t)u * C + c) * S + i) * D + col] = 0;
+    }
+    return;
+  }
+
+  const int rq = lane / LQ, cq = lane % LQ;
+  const int rv = lane / LV, cv = lane % LV;
+
+  float qf[CMAX][8];
+#pragma unroll
+  for (int c = 0; c < CMAX; ++c) {
+    u32x4 raw = {0u, 0u, 0u, 0u};
+    if (c < C) raw = *reinterpret_cast<const u32x4*>(q + ((size_t)u * C + c) * DQ + cq * 8);
+    unpack8(raw, qf[c]);
+  }
+  float acc[CMAX][8];
+#pragma unroll
+  for (int c = 0; c < CMAX; ++c)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[c][e] = 0.0f;
+
+  const unsigned short* kU = k + (size_t)u * L * DQ;
+  const unsigned short* vU = v + (size_t)u * L * D;
+
+  // UNR chunks per step: all their loads are issued before the first one is consumed
+  constexpr int UNR = 4;
+  for (int jb = lo + wave * IPC; jb < hi; jb += 4 * IPC * UNR) {
+    u32x4 kreg[UNR][NKL], vreg[UNR][NVL];
+#pragma unroll
+    for (int uu = 0; uu < UNR; ++uu) {
+      const int j0 = jb + uu * 4 * IPC;
+#pragma unroll
+      for (int kl = 0; kl < NKL; ++kl) {
+        const int row = j0 + kl * RQ + rq;
+        kreg[uu][kl] = u32x4{0u, 0u, 0u, 0u};
+        if (row < hi) kreg[uu][kl] = *reinterpret_cast<const u32x4*>(kU + (size_t)row * DQ + cq * 8);
+      }
+#pragma unroll
+      for (int vl = 0; vl < NVL; ++vl) {
+        const int row = j0 + vl * RV + rv;
+        vreg[uu][vl] = u32x4{0u, 0u, 0u, 0u};
+        if (row < hi) vreg[uu][vl] = *reinterpret_cast<const u32x4*>(vU + (size_t)row * D + cv * 8);
+      }
+    }
+#pragma unroll
+    for (int uu = 0; uu < UNR; ++uu) {
+      const int j0 = jb + uu * 4 * IPC;
+      float vf[NVL][8];
+#pragma unroll
+      for (int vl = 0; vl < NVL; ++vl) unpack8(vreg[uu][vl], vf[vl]);
+#pragma unroll
+      for (int c = 0; c < CMAX; ++c) {
+        if (c < C) {
+#pragma unroll
+          for (int kl = 0; kl < NKL; ++kl) {
+            float kf[8];
+            unpack8(kreg[uu][kl], kf);
+            float s = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s = fmaf(kf[e], qf[c][e], s);
+#pragma unroll
+            for (int off = 1; off < LQ; off <<= 1) s += __shfl_xor(s, off, 64);
+            const bool ok = (j0 + kl * RQ + rq) < hi;
+            const float g = ok ? __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(s * neg_scale_log2e)) : 0.0f;
+            if (SAME) {
+#pragma unroll
+              for (int e = 0; e < 8; ++e) acc[c][e] = fmaf(g, vf[kl][e], acc[c][e]);
+            } else if (cq == 0) {
+              gs[wave][c][kl * RQ + rq] = g;
+            }
+          }
+          if (!SAME) {   // LDS operations of one wave execute in order: the gates written above are visible here
+#pragma unroll
+            for (int vl = 0; vl < NVL; ++vl) {
+              const float g = gs[wave][c][vl * RV + rv];
+#pragma unroll
+              for (int e = 0; e < 8; ++e) acc[c][e] = fmaf(g, vf[vl][e], acc[c][e]);
+            }
+          }
+        }
+      }
+    }
+  }
+
+  // sum over the row groups of the wave, then over the four waves (fixed order)
+#pragma unroll
+  for (int c = 0; c < CMAX; ++c) {
+    if (c < C) {
+#pragma unroll
+      for (int off = LV; off < 64; off <<= 1)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[c][e] += __shfl_xor(acc[c][e], off, 64);
+      if (rv == 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) red[wave][c][cv * 8 + e] = acc[c][e];
+      }
+    }
+  }
+  __syncthreads();
+  for (int e = tid; e < C * D; e += 256) {
+    const int c = e / D, col = e - c * D;
+    const float s = ((red[0][c][col] + red[1][c][col]) + red[2][c][col]) + red[3][c][col];
+    seg_out[(((size_t)u * C + c) * S + i) * D + col] = f32_to_bf16_bits(s);
+  }
+}
+
+// ------------------------------------------------------------------------------------------ host side
+bool sta_stream_supports(const StaArgs& a) {
+  if (a.dt != LASER_BF16) return false;
+  if (a.C > 8) return false;
+  if (!(a.d_q == 32 || a.d_q == 64 || a.d_q == 128)) return false;
+  if (!(a.d == 64 || a.d == 128)) return false;
+  return (long long)a.U * a.S <= 0x7fffffffLL;
+}
+
+template <int DQ, int D>
+static void launch_c(const StaArgs& a, float nsl) {
+  const unsigned blocks = (unsigned)((long long)a.U * a.S);
+#define LASER_STREAM_LAUNCH(CM)                                                                                      \
+  hipLaunchKernelGGL((sta_stream_kernel<DQ, D, CM>), dim3(blocks), dim3(256), 0, a.stream,                         \
+                     (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens,   \
+                     a.C, a.L, a.w, a.S, nsl, (unsigned short*)a.seg_out)
+  if (a.C <= 1) LASER_STREAM_LAUNCH(1);
+  else if (a.C <= 2) LASER_STREAM_LAUNCH(2);
+  else if (a.C <= 4) LASER_STREAM_LAUNCH(4);
+  else LASER_STREAM_LAUNCH(8);
+#undef LASER_STREAM_LAUNCH
+}
+
+laser_status sta_stream_launch(const StaArgs& a) {
+  if (!sta_stream_supports(a)) return LASER_ERR_UNSUPPORTED;
+  const float nsl = -1.4426950408889634f / a.gamma;
+  const int key = a.d_q * 1000 + a.d;
+  switch (key) {
+    case 32064: launch_c<32, 64>(a, nsl); break;
+    case 32128: launch_c<32, 128>(a, nsl); break;
+    case 64064: launch_c<64, 64>(a, nsl); break;
+    case 64128: launch_c<64, 128>(a, nsl); break;
+    case 128064: launch_c<128, 64>(a, nsl); break;
+    case 128128: launch_c<128, 128>(a, nsl); break;
+    default: return LASER_ERR_UNSUPPORTED;
+  }
+  return launch_status();
+}
+
 }  // namespace laser
