@@ -101,6 +101,9 @@ def main() -> int:
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copies", type=int, default=0, help="distinct input/output copies to rotate through (0 = auto)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy 5 times (reference reading for the FETCH_SIZE / "
+                         "WRITE_SIZE counters when this command runs under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (users shard across GPUs with no exchange; see DESIGN.md); "
@@ -178,6 +181,14 @@ def main() -> int:
 
     sta_ms = event_time(sta_only)
     gsta_ms = event_time(gsta_only)
+
+    if args.calibration_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # sampled parity against the checker (one-by-one pairs), in this launch configuration
     step(0)

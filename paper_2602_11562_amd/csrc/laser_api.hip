@@ -67,9 +67,7 @@ static laser_status run_sta(const StaArgs& a, laser_sta_variant variant) {
     case LASER_STA_STREAM: s = sta_stream_launch(a); break;
     default: return LASER_ERR_UNSUPPORTED;
   }
-  if (s != LASER_OK) return s;
-  if (a.seg_cnt) s = seg_cnt_launch(a.lens, a.U, a.L, a.w, a.S, a.seg_cnt, a.stream);
-  return s;
+  return s;   // every STA kernel also writes seg_cnt when it is requested
 }
 
 static laser_status run_gsta(const GstaArgs& a, laser_gsta_variant variant) {

@@ -18,7 +18,7 @@ struct StaArgs {
   float gamma;
   laser_dtype dt;
   void* seg_out;
-  int32_t* seg_cnt;
+  int32_t* seg_cnt;   // may be nullptr
   hipStream_t stream;
 };
 
@@ -47,9 +47,6 @@ bool gsta_generic_supports(const GstaArgs& a);
 laser_status gsta_generic_launch(const GstaArgs& a);
 bool gsta_tiled_supports(const GstaArgs& a);
 laser_status gsta_tiled_launch(const GstaArgs& a);
-
-// seg_cnt[u, i] (integer, exact); used by every STA variant.
-laser_status seg_cnt_launch(const int32_t* lens, int U, int L, int w, int S, int32_t* seg_cnt, hipStream_t stream);
 
 inline laser_status launch_status() { return hipGetLastError() == hipSuccess ? LASER_OK : LASER_ERR_LAUNCH; }
 
@@ -85,6 +82,19 @@ __device__ __forceinline__ int valid_len(const int32_t* lens, int u, int L) {
   if (lens == nullptr) return L;
   int n = lens[u];
   return n < 0 ? 0 : (n > L ? L : n);
+}
+
+// seg_cnt[u, i] = number of valid items of user u inside segment i (integer, exact). Called by one workgroup per
+// user inside the STA kernels, so the counts cost no launch of their own.
+__device__ __forceinline__ void write_seg_cnt(int32_t* seg_cnt, int u, int n, int L, int w, int S, int tid, int nt) {
+  if (seg_cnt == nullptr) return;
+  for (int i = tid; i < S; i += nt) {
+    const int lo = i * w;
+    int hi = lo + w;
+    if (hi > L) hi = L;
+    if (hi > n) hi = n;
+    seg_cnt[(size_t)u * S + i] = hi > lo ? hi - lo : 0;
+  }
 }
 
 __device__ __forceinline__ float wave_sum(float x) {

@@ -20,7 +20,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void sta_generic_kernel(const T* __restrict__ q, const T* __restrict__ k,
                                                           const T* __restrict__ v, const int32_t* __restrict__ lens,
                                                           int C, int L, int dq, int d, int w, int S, int TI,
-                                                          float inv_gamma, T* __restrict__ seg_out) {
+                                                          float inv_gamma, T* __restrict__ seg_out,
+                                                          int32_t* __restrict__ seg_cnt) {
   extern __shared__ float smem[];
   const int kpitch = dq + 1;                   // +1: lanes read different rows at the same column
   float* Ks = smem;                            // [TI][dq + 1]
@@ -40,6 +41,7 @@ __global__ __launch_bounds__(256) void sta_generic_kernel(const T* __restrict__ 
   const bool active = c < C;
 
   const int n = valid_len(lens, u, L);
+  if (i == 0 && cb == 0) write_seg_cnt(seg_cnt, u, n, L, w, S, tid, 256);
   const int lo = i * w;
   int hi = lo + w;
   if (hi > L) hi = L;
@@ -92,25 +94,6 @@ __global__ __launch_bounds__(256) void sta_generic_kernel(const T* __restrict__ 
   }
 }
 
-__global__ void seg_cnt_kernel(const int32_t* __restrict__ lens, int U, int L, int w, int S,
-                               int32_t* __restrict__ seg_cnt) {
-  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= U * S) return;
-  const int u = idx / S, i = idx - u * S;
-  const int n = valid_len(lens, u, L);
-  const int lo = i * w;
-  int hi = lo + w;
-  if (hi > L) hi = L;
-  if (hi > n) hi = n;
-  seg_cnt[idx] = hi > lo ? hi - lo : 0;
-}
-
-laser_status seg_cnt_launch(const int32_t* lens, int U, int L, int w, int S, int32_t* seg_cnt, hipStream_t stream) {
-  const int total = U * S;
-  hipLaunchKernelGGL(seg_cnt_kernel, dim3((total + 255) / 256), dim3(256), 0, stream, lens, U, L, w, S, seg_cnt);
-  return launch_status();
-}
-
 static size_t gen_lds_bytes(int TI, int dq, int d) {
   return sizeof(float) * ((size_t)TI * (dq + 1) + (size_t)TI * d + GEN_WAVES * dq + GEN_WAVES * TI);
 }
@@ -137,11 +120,11 @@ laser_status sta_generic_launch(const StaArgs& a) {
   if (a.dt == LASER_F32) {
     hipLaunchKernelGGL(sta_generic_kernel<float>, dim3(blocks), dim3(256), lds, a.stream, (const float*)a.q,
                        (const float*)a.k, (const float*)a.v, a.lens, a.C, a.L, a.d_q, a.d, a.w, a.S, TI, inv_gamma,
-                       (float*)a.seg_out);
+                       (float*)a.seg_out, a.seg_cnt);
   } else {
     hipLaunchKernelGGL(sta_generic_kernel<unsigned short>, dim3(blocks), dim3(256), lds, a.stream,
                        (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens,
-                       a.C, a.L, a.d_q, a.d, a.w, a.S, TI, inv_gamma, (unsigned short*)a.seg_out);
+                       a.C, a.L, a.d_q, a.d, a.w, a.S, TI, inv_gamma, (unsigned short*)a.seg_out, a.seg_cnt);
   }
   return launch_status();
 }

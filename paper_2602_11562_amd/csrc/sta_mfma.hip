@@ -107,7 +107,8 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short*
                                                            const unsigned short* __restrict__ v,
                                                            const int32_t* __restrict__ lens, int C, int L, int w,
                                                            int S, int spw, int ctiles, int sruns,
-                                                           float neg_scale_log2e, unsigned short* __restrict__ seg_out) {
+                                                           float neg_scale_log2e, unsigned short* __restrict__ seg_out,
+                                                           int32_t* __restrict__ seg_cnt) {
   constexpr int KP = KPitch<DQ>::v, VP = VPitch<D>::v;
   constexpr int NT = 64 * NW;
   constexpr int KSTEPS = DQ / 16, DB = D / 32;
@@ -125,6 +126,7 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short*
   const int l32 = lane & 31, h = lane >> 5;
   const int cbase = ct * (CW * NW) + wave * CW;     // first candidate of this wave
   const int n = valid_len(lens, u, L);
+  if (srun == 0 && ct == 0) write_seg_cnt(seg_cnt, u, n, L, w, S, tid, NT);
   unsigned char* opatch = smem + NBUF * (KBYTES + VBYTES) + wave * OBYTES;
 
   // queries: B operand of the score product, lane = candidate, 8 consecutive d_q elements per k-step half
@@ -318,7 +320,8 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_pipe_kernel(const unsigned s
                                                                 const int32_t* __restrict__ lens, int C, int L,
                                                                 int w, int S, int spw, int ctiles, int sruns,
                                                                 float neg_scale_log2e,
-                                                                unsigned short* __restrict__ seg_out) {
+                                                                unsigned short* __restrict__ seg_out,
+                                                                int32_t* __restrict__ seg_cnt) {
   constexpr int KP = KPitch<DQ>::v, VP = VPitch<D>::v;
   constexpr int NT = 64 * NW;
   constexpr int KSTEPS = DQ / 16, DB = D / 32;
@@ -336,6 +339,7 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_pipe_kernel(const unsigned s
   const int l32 = lane & 31, h = lane >> 5;
   const int cbase = ct * (CW * NW) + wave * CW;
   const int n = valid_len(lens, u, L);
+  if (srun == 0 && ct == 0) write_seg_cnt(seg_cnt, u, n, L, w, S, tid, NT);
   unsigned char* opatch = smem + 2 * (KBYTES + VBYTES) + wave * OBYTES;
 
   bf16x8 qreg[KSTEPS];
@@ -508,7 +512,7 @@ static void launch_one(const StaArgs& a, int spw, int ctiles, int sruns, float n
   const unsigned blocks = (unsigned)((long long)a.U * ctiles * sruns);
   hipLaunchKernelGGL((sta_mfma_kernel<DQ, D, NW, NBUF>), dim3(blocks), dim3(64 * NW), 0, a.stream,
                      (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens, a.C,
-                     a.L, a.w, a.S, spw, ctiles, sruns, nsl, (unsigned short*)a.seg_out);
+                     a.L, a.w, a.S, spw, ctiles, sruns, nsl, (unsigned short*)a.seg_out, a.seg_cnt);
 }
 
 template <int DQ, int D>
@@ -519,7 +523,7 @@ static void launch_nw(const StaArgs& a, int nw, int spw, int ctiles, int sruns, 
     const unsigned blocks = (unsigned)((long long)a.U * ctiles * sruns);
     hipLaunchKernelGGL((sta_mfma_pipe_kernel<DQ, D, 8>), dim3(blocks), dim3(512), 0, a.stream,
                        (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens,
-                       a.C, a.L, a.w, a.S, spw, ctiles, sruns, nsl, (unsigned short*)a.seg_out);
+                       a.C, a.L, a.w, a.S, spw, ctiles, sruns, nsl, (unsigned short*)a.seg_out, a.seg_cnt);
   }
   else if (nw == 4) launch_one<DQ, D, 4, 1>(a, spw, ctiles, sruns, nsl);
   else if (nw == 2) launch_one<DQ, D, 2, 1>(a, spw, ctiles, sruns, nsl);
@@ -530,9 +534,11 @@ laser_status sta_mfma_launch(const StaArgs& a) {
   if (!sta_mfma_supports(a)) return LASER_ERR_UNSUPPORTED;
   const int nw = pick_nw(a.C);
   const int ctiles = (a.C + CW * nw - 1) / (CW * nw);
-  // consecutive segments per workgroup: as many as still leave about two workgroups per compute unit
+  // consecutive segments per workgroup (they share the query registers and the prefetch pipeline): as many as
+  // still leave one eight-wave workgroup, or two smaller ones, per compute unit
+  const long long want = nw == 8 ? 256 : 512;
   int spw = 1;
-  while (spw < 8 && (long long)a.U * ctiles * ((a.S + 2 * spw - 1) / (2 * spw)) >= 512) spw *= 2;
+  while (spw < 8 && (long long)a.U * ctiles * ((a.S + 2 * spw - 1) / (2 * spw)) >= want) spw *= 2;
   if (const char* e = getenv("LASER_STA_SPW")) {   // tuning override
     const int vv = atoi(e);
     if (vv >= 1 && vv <= 64) spw = vv;

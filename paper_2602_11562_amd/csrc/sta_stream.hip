@@ -28,7 +28,8 @@ __global__ __launch_bounds__(256) void sta_stream_kernel(const unsigned short* _
                                                          const unsigned short* __restrict__ k,
                                                          const unsigned short* __restrict__ v,
                                                          const int32_t* __restrict__ lens, int C, int L, int w, int S,
-                                                         float neg_scale_log2e, unsigned short* __restrict__ seg_out) {
+                                                         float neg_scale_log2e, unsigned short* __restrict__ seg_out,
+                                                         int32_t* __restrict__ seg_cnt) {
   constexpr int LQ = DQ / 8, LV = D / 8;           // lanes per K row / V row
   constexpr int RQ = 64 / LQ, RV = 64 / LV;        // rows per wave-wide load
   constexpr int IPC = RQ > RV ? RQ : RV;           // items per chunk
@@ -40,6 +41,7 @@ __global__ __launch_bounds__(256) void sta_stream_kernel(const unsigned short* _
   const int u = blockIdx.x / S, i = blockIdx.x % S;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int n = valid_len(lens, u, L);
+  if (i == 0) write_seg_cnt(seg_cnt, u, n, L, w, S, tid, 256);
   const int lo = i * w;
   int hi = lo + w;
   if (hi > L) hi = L;
@@ -169,7 +171,7 @@ static void launch_c(const StaArgs& a, float nsl) {
 #define LASER_STREAM_LAUNCH(CM)                                                                                      \
   hipLaunchKernelGGL((sta_stream_kernel<DQ, D, CM>), dim3(blocks), dim3(256), 0, a.stream,                         \
                      (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens,   \
-                     a.C, a.L, a.w, a.S, nsl, (unsigned short*)a.seg_out)
+                     a.C, a.L, a.w, a.S, nsl, (unsigned short*)a.seg_out, a.seg_cnt)
   if (a.C <= 1) LASER_STREAM_LAUNCH(1);
   else if (a.C <= 2) LASER_STREAM_LAUNCH(2);
   else if (a.C <= 4) LASER_STREAM_LAUNCH(4);
