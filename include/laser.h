@@ -60,7 +60,8 @@ typedef enum {
 typedef enum {
   LASER_GSTA_AUTO = 0,
   LASER_GSTA_GENERIC = 1, /* fp32 FMA, one workgroup per pair, any shape              */
-  LASER_GSTA_TILED = 2    /* bf16 storage, a tile of pairs per workgroup, MFMA        */
+  LASER_GSTA_TILED = 2,   /* bf16 storage, a tile of pairs per workgroup, MFMA, any M */
+  LASER_GSTA_SPLIT = 3    /* bf16 storage, M = 1: projection / streaming / output kernels; z_out is the scratch */
 } laser_gsta_variant;
 
 /*

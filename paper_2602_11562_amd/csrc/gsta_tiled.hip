@@ -58,6 +58,21 @@ template <int D> struct WPitch { static constexpr int v = (D * 2) % 256 == 64 ? 
 
 // [32 x D] (LDS, fp32, pitch FP) times W^T with W bf16 [D][D] in global memory -> 32 x 32 block `nb`:
 // out[p][n] = sum_k X[p][k] W[n][k]. The B operand (k contiguous per lane) is one 16-byte load per step.
+// same product with the B operands already in registers (loaded early by the caller)
+template <int D>
+__device__ __forceinline__ f32x16 tile_gemm_breg(const float* X, int FP, const bf16x8 (&b)[D / 16], int l32, int h) {
+  f32x16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) {
+    const HiLo a = split8(X + l32 * FP + ks * 16 + h * 8);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.hi, b[ks], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.lo, b[ks], acc, 0, 0, 0);
+  }
+  return acc;
+}
+
 template <int D>
 __device__ __forceinline__ f32x16 tile_gemm_wt(const float* X, int FP, const unsigned short* __restrict__ W, int nb,
                                                int l32, int h) {
@@ -65,15 +80,13 @@ __device__ __forceinline__ f32x16 tile_gemm_wt(const float* X, int FP, const uns
 #pragma unroll
   for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
   const int n = nb * 32 + l32;
-  bf16x8 b[D / 16];
-#pragma unroll
-  for (int ks = 0; ks < D / 16; ++ks)
-    b[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(W + (size_t)n * D + ks * 16 + h * 8));
-#pragma unroll
+  // partial unroll: a full unroll makes the scheduler hoist every operand load and costs ~100 registers
+#pragma unroll 2
   for (int ks = 0; ks < D / 16; ++ks) {
+    const bf16x8 b = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(W + (size_t)n * D + ks * 16 + h * 8));
     const HiLo a = split8(X + l32 * FP + ks * 16 + h * 8);
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.hi, b[ks], acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.lo, b[ks], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.hi, b, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.lo, b, acc, 0, 0, 0);
   }
   return acc;
 }
@@ -91,7 +104,7 @@ __device__ __forceinline__ f32x16 tile_gemm_lds(const float* X, int FP, const un
   for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
   const int i16 = lane & 15;
   const unsigned char* base = Wl + (h * 8 + (i16 >> 2)) * WP + (nb * 32 + (l32 & 16) + 4 * (i16 & 3)) * 2;
-#pragma unroll
+#pragma unroll 2
   for (int ks = 0; ks < D / 16; ++ks) {
     const unsigned char* src = base + ks * 16 * WP;
     const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(src));
@@ -317,6 +330,224 @@ __global__ __launch_bounds__(GT_THREADS) void gsta_tiled_kernel(const unsigned s
   }
 }
 
+// ------------------------------------------------------------------------------------------ split form (M = 1)
+// One GSTA layer as three kernels that each have the shape their work wants; the fp32 output buffer z doubles as
+// the only scratch (r, then p, then z live in the same [P x d] fp32 rows, each written by the reader of the last):
+//   gsta_r_kernel     r = (t0 W_q) W_k^T / sqrt(d)        tiles of 32 pairs, MFMA                 -> z rows
+//   gsta_pool_kernel  p = softmax_i(H'_i . r) H'          one wave per pair, H' streamed once     z rows -> z rows
+//   gsta_out_kernel   z = t0 + p W_v                      tiles of 32 pairs, MFMA                 z rows -> z rows
+// The streaming kernel needs ~120 registers and no LDS, so a compute unit holds 16 waves of it and HBM latency is
+// covered by occupancy. The two projection kernels are pure latency chains (one tile per compute unit at the
+// benchmark size), so they are written to need one round trip to memory: every operand is requested in MFMA
+// operand order straight from global memory before anything is waited for.
+constexpr int GS_THREADS = 256;
+
+// B operand of X.W for column block nb: lane n = nb*32 + l32 needs W[k][n] for 8 consecutive k, i.e. a column
+// piece of the row-major matrix: eight 2-byte loads per k-step (consecutive lanes read consecutive addresses).
+template <int D>
+__device__ __forceinline__ void load_b_cols(const unsigned short* __restrict__ W, int nb, int l32, int h,
+                                            bf16x8 (&b)[D / 16]) {
+  const int n = nb * 32 + l32;
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) b[ks][i] = __builtin_bit_cast(__bf16, W[(size_t)(ks * 16 + h * 8 + i) * D + n]);
+}
+
+// B operand of X.W^T: lane n needs W[n][k] for 8 consecutive k: one 16-byte load per k-step
+template <int D>
+__device__ __forceinline__ void load_b_rows(const unsigned short* __restrict__ W, int nb, int l32, int h,
+                                            bf16x8 (&b)[D / 16]) {
+  const int n = nb * 32 + l32;
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks)
+    b[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(W + (size_t)n * D + ks * 16 + h * 8));
+}
+
+template <int D>
+__global__ __launch_bounds__(GS_THREADS) void gsta_r_kernel(const unsigned short* __restrict__ t0,
+                                                            const unsigned short* __restrict__ wq,
+                                                            const unsigned short* __restrict__ wk, int P,
+                                                            float* __restrict__ z) {
+  constexpr int FP = D + 4, DB = D / 32;
+  __shared__ __attribute__((aligned(16))) float bufB[GT_ROWS * FP];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
+  const int pbase = blockIdx.x * GT_ROWS;
+  const int nb = wave < DB ? wave : 0;
+  // everything the two products read from memory is requested here
+  bf16x8 bq[D / 16], bk[D / 16], at[D / 16];
+  load_b_cols<D>(wq, nb, l32, h, bq);
+  load_b_rows<D>(wk, nb, l32, h, bk);
+  {
+    const int pr = (pbase + l32) < P ? (pbase + l32) : (P - 1);   // rows past the batch repeat the last pair
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks)
+      at[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(t0 + (size_t)pr * D + ks * 16 + h * 8));
+  }
+  if (wave < DB) {   // q' = t0 W_q : t0 is bf16 by storage, one pass
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at[ks], bq[ks], acc, 0, 0, 0);
+    store_acc(bufB, FP, acc, wave, l32, h, 1.0f);
+  }
+  __syncthreads();
+  if (wave < DB) {   // r = q' W_k^T / sqrt(d), written from the accumulator layout (64-byte row pieces)
+    const f32x16 rr = tile_gemm_breg<D>(bufB, FP, bk, l32, h);
+    const float scale = 1.0f / sqrtf((float)D);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int pr = pbase + 8 * (r >> 2) + 4 * h + (r & 3);
+      if (pr < P) z[(size_t)pr * D + wave * 32 + l32] = rr[r] * scale;
+    }
+  }
+}
+
+template <int D>
+struct WStage4 {   // W [D][D] bf16 global -> LDS for a 256-thread workgroup
+  static constexpr int IT = D * (D / 8) / GS_THREADS;
+  u32x4 r[IT];
+  __device__ __forceinline__ void load(const unsigned short* __restrict__ W, int tid) {
+#pragma unroll
+    for (int it = 0; it < IT; ++it) r[it] = *reinterpret_cast<const u32x4*>(W + (size_t)(tid + it * GS_THREADS) * 8);
+  }
+  __device__ __forceinline__ void store(unsigned char* Wl, int tid) const {
+    constexpr int WP = WPitch<D>::v, CH = D / 8;
+#pragma unroll
+    for (int it = 0; it < IT; ++it) {
+      const int e = tid + it * GS_THREADS, row = e / CH, ch = e % CH;
+      *reinterpret_cast<u32x4*>(Wl + row * WP + ch * 16) = r[it];
+    }
+  }
+};
+
+// rows of a [32 x D] fp32 LDS tile <- global rows (coalesced pieces); rows >= nrows are zero
+template <int D, typename SrcT>
+__device__ __forceinline__ void tile_load(float* X, int FP, const SrcT* __restrict__ src, int nrows, int tid) {
+  for (int e = tid; e < GT_ROWS * (D / 4); e += GS_THREADS) {
+    const int row = e / (D / 4), c4 = e - row * (D / 4);
+    f32x4 val = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (row < nrows) {
+      if constexpr (sizeof(SrcT) == 4) {
+        val = *reinterpret_cast<const f32x4*>(src + (size_t)row * D + c4 * 4);
+      } else {
+        const unsigned int* p2 = reinterpret_cast<const unsigned int*>(src + (size_t)row * D + c4 * 4);
+        const unsigned int a = p2[0], b = p2[1];
+        val = f32x4{__uint_as_float(a << 16), __uint_as_float(a & 0xffff0000u), __uint_as_float(b << 16),
+                    __uint_as_float(b & 0xffff0000u)};
+      }
+    }
+    *reinterpret_cast<f32x4*>(X + row * FP + c4 * 4) = val;
+  }
+}
+
+// z = t0 + p W_v for a tile of 32 pairs: W_v through LDS and the transpose load, p and t0 through LDS tiles, so
+// every global access is a coalesced row piece; the tile is read completely before the barrier and written after
+template <int D>
+__global__ __launch_bounds__(GS_THREADS) void gsta_out_kernel(const unsigned short* __restrict__ t0,
+                                                              const unsigned short* __restrict__ wv, int P,
+                                                              float* __restrict__ z) {
+  constexpr int FP = D + 4, DB = D / 32, WP = WPitch<D>::v;
+  __shared__ __attribute__((aligned(16))) float bufA[GT_ROWS * FP];
+  __shared__ __attribute__((aligned(16))) float bufB[GT_ROWS * FP];
+  __shared__ __attribute__((aligned(16))) unsigned char Wl[D * WP];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
+  const int pbase = blockIdx.x * GT_ROWS;
+  const int nrows = (P - pbase) < GT_ROWS ? (P - pbase) : GT_ROWS;
+  WStage4<D> ws;
+  ws.load(wv, tid);
+  tile_load<D>(bufB, FP, z + (size_t)pbase * D, nrows, tid);           // p
+  tile_load<D>(bufA, FP, t0 + (size_t)pbase * D, nrows, tid);          // t0
+  ws.store(Wl, tid);
+  __syncthreads();
+  if (wave < DB) {   // each accumulator element adds into its own element of the t0 tile
+    const f32x16 o = tile_gemm_lds<D>(bufB, FP, Wl, wave, lane, l32, h);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) bufA[(8 * (r >> 2) + 4 * h + (r & 3)) * FP + wave * 32 + l32] += o[r];
+  }
+  __syncthreads();
+  for (int e = tid; e < nrows * (D / 4); e += GS_THREADS) {
+    const int row = e / (D / 4), c4 = e - row * (D / 4);
+    *reinterpret_cast<f32x4*>(z + (size_t)(pbase + row) * D + c4 * 4) =
+        *reinterpret_cast<const f32x4*>(bufA + row * FP + c4 * 4);
+  }
+}
+
+// one wave per pair; ROWS register rows of 16 bytes cover the pair's S x D block
+template <int D, int ROWS>
+__global__ __launch_bounds__(GS_THREADS) void gsta_pool_kernel(const unsigned short* __restrict__ seg,
+                                                               const int32_t* __restrict__ lens, int P, int C, int L,
+                                                               int w, int S, float* __restrict__ z) {
+  constexpr int LPR = D / 8, RPW = 64 / LPR;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int pr = blockIdx.x * (GS_THREADS / 64) + wave;
+  if (pr >= P) return;
+  const int grp = lane / LPR, gl = lane % LPR;
+  const int nv = (valid_len(lens, pr / C, L) + w - 1) / w;
+  const unsigned short* H = seg + (size_t)pr * S * D;
+  u32x4 hreg[ROWS];
+#pragma unroll
+  for (int j = 0; j < ROWS; ++j) {
+    const int i = j * RPW + grp;
+    hreg[j] = u32x4{0u, 0u, 0u, 0u};
+    if (i < nv) hreg[j] = *reinterpret_cast<const u32x4*>(H + (size_t)i * D + gl * 8);
+  }
+  float rs[8];
+  {
+    const f32x4 a = *reinterpret_cast<const f32x4*>(z + (size_t)pr * D + gl * 8);
+    const f32x4 b = *reinterpret_cast<const f32x4*>(z + (size_t)pr * D + gl * 8 + 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { rs[e] = a[e]; rs[4 + e] = b[e]; }
+  }
+  float m = -INFINITY, den = 0.0f;
+  float pacc[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) pacc[e] = 0.0f;
+#pragma unroll
+  for (int j = 0; j < ROWS; ++j) {
+    float x[8];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      x[2 * e] = __uint_as_float(hreg[j][e] << 16);
+      x[2 * e + 1] = __uint_as_float(hreg[j][e] & 0xffff0000u);
+    }
+    float sdot = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) sdot = fmaf(x[e], rs[e], sdot);
+#pragma unroll
+    for (int off = 1; off < LPR; off <<= 1) sdot += __shfl_xor(sdot, off, 64);
+    const bool ok = (j * RPW + grp) < nv;
+    const float m_new = ok ? fmaxf(m, sdot) : m;
+    const float sc = (m == m_new) ? 1.0f : __expf(m - m_new);
+    const float a = ok ? __expf(sdot - m_new) : 0.0f;
+    den = fmaf(den, sc, a);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) pacc[e] = fmaf(pacc[e], sc, a * x[e]);
+    m = m_new;
+  }
+#pragma unroll
+  for (int off = LPR; off < 64; off <<= 1) {
+    const float m_o = __shfl_xor(m, off, 64);
+    const float den_o = __shfl_xor(den, off, 64);
+    const float M2 = fmaxf(m, m_o);
+    const float f = (m == M2) ? 1.0f : __expf(m - M2);
+    const float f_o = (m_o == M2) ? 1.0f : __expf(m_o - M2);
+    den = den * f + den_o * f_o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) pacc[e] = pacc[e] * f + __shfl_xor(pacc[e], off, 64) * f_o;
+    m = M2;
+  }
+  if (grp == 0) {   // the row's r has been read by these same lanes above: overwrite it with p
+    const float inv = nv > 0 ? 1.0f / den : 0.0f;
+    f32x4 a, b;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { a[e] = pacc[e] * inv; b[e] = pacc[4 + e] * inv; }
+    *reinterpret_cast<f32x4*>(z + (size_t)pr * D + gl * 8) = a;
+    *reinterpret_cast<f32x4*>(z + (size_t)pr * D + gl * 8 + 4) = b;
+  }
+}
+
 static int rows_needed(int S, int d) { return (S + (64 / (d / 8)) - 1) / (64 / (d / 8)); }
 
 bool gsta_tiled_supports(const GstaArgs& a) {
@@ -359,6 +590,42 @@ static void launch_d(const GstaArgs& a) {
   else if (rows <= 4) launch_rows<D, 4>(a);
   else if (rows <= 8) launch_rows<D, 8>(a);
   else launch_rows<D, 10>(a);
+}
+
+template <int D>
+static void launch_split(const GstaArgs& a) {
+  const int P = a.U * a.C;
+  const unsigned tiles = (unsigned)((P + GT_ROWS - 1) / GT_ROWS);
+  const unsigned short* t0 = (const unsigned short*)a.t0;
+  hipLaunchKernelGGL((gsta_r_kernel<D>), dim3(tiles), dim3(GS_THREADS), 0, a.stream, t0,
+                     (const unsigned short*)a.wq, (const unsigned short*)a.wk, P, a.z_out);
+  const int rows = rows_needed(a.S, a.d);
+  const unsigned pblocks = (unsigned)((P + GS_THREADS / 64 - 1) / (GS_THREADS / 64));
+#define LASER_POOL(R)                                                                                             \
+  hipLaunchKernelGGL((gsta_pool_kernel<D, R>), dim3(pblocks), dim3(GS_THREADS), 0, a.stream,                     \
+                     (const unsigned short*)a.seg, a.lens, P, a.C, a.L, a.w, a.S, a.z_out)
+  if (rows <= 2) LASER_POOL(2);
+  else if (rows <= 4) LASER_POOL(4);
+  else if (rows <= 8) LASER_POOL(8);
+  else if (rows <= 10) LASER_POOL(10);
+  else if (rows <= 16) LASER_POOL(16);
+  else LASER_POOL(32);
+#undef LASER_POOL
+  hipLaunchKernelGGL((gsta_out_kernel<D>), dim3(tiles), dim3(GS_THREADS), 0, a.stream, t0,
+                     (const unsigned short*)a.wv, P, a.z_out);
+}
+
+bool gsta_split_supports(const GstaArgs& a) {
+  if (a.dt != LASER_BF16 || a.M != 1) return false;
+  if (!(a.d == 64 || a.d == 128)) return false;
+  return rows_needed(a.S, a.d) <= 32;
+}
+
+laser_status gsta_split_launch(const GstaArgs& a) {
+  if (!gsta_split_supports(a)) return LASER_ERR_UNSUPPORTED;
+  if (a.d == 64) launch_split<64>(a);
+  else launch_split<128>(a);
+  return launch_status();
 }
 
 laser_status gsta_tiled_launch(const GstaArgs& a) {

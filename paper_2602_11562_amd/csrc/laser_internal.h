@@ -47,6 +47,8 @@ bool gsta_generic_supports(const GstaArgs& a);
 laser_status gsta_generic_launch(const GstaArgs& a);
 bool gsta_tiled_supports(const GstaArgs& a);
 laser_status gsta_tiled_launch(const GstaArgs& a);
+bool gsta_split_supports(const GstaArgs& a);
+laser_status gsta_split_launch(const GstaArgs& a);
 
 inline laser_status launch_status() { return hipGetLastError() == hipSuccess ? LASER_OK : LASER_ERR_LAUNCH; }
 
