@@ -494,6 +494,386 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_pipe_kernel(const unsigned s
   }
 }
 
+// ------------------------------------------------------------------------------------------ direct-to-LDS form
+// d_q = d = 128 and more than 128 candidates per user (the benchmark shape). Same arithmetic and wave mapping as
+// the pipelined form; what changes is how history reaches LDS and how little vector-ALU work surrounds the matrix
+// instructions (a MFMA blocks VALU issue of its SIMD for about half of its own duration, and the gates already
+// need more VALU slots than the MFMAs leave free, so every address computation removed from the loop counts):
+//  * tiles of 32 items are fetched with global_load_lds_dwordx4 (each lane names a 16-byte global chunk, the 64
+//    chunks of a wave land contiguously in LDS), so no register or VALU work is spent on staging; the global
+//    address is a scalar tile base plus a per-lane offset that never changes. Five LDS buffers, up to four tiles
+//    requested ahead. The queries take the same road (through the wave's output patch);
+//  * rows are unpadded; bank conflicts are avoided by an XOR swizzle of the 16-byte chunk index that the fetching
+//    lane applies when it picks its global chunk: K chunk c of row r sits at position c ^ (r & 15), V chunk c at
+//    c ^ 4 (r & 3) (conflict-free for the 16-rows-by-16-bytes operand reads and for the 4-rows-by-64-bytes
+//    transpose loads respectively);
+//  * rows past the valid length cannot be zero-filled by this path: they are fetched from the last valid row and
+//    their gates are forced to 0 in the (rare) partial tile;
+//  * fetches and H' stores are inline assembly without outputs. The compiler's wait-count pass does not see
+//    them, so it never waits for a fetch in flight (a visible load or store would make it wait for everything
+//    outstanding at the next use of a register it cannot prove idle); completion is awaited explicitly with
+//    s_waitcnt vmcnt(n), n = the number of younger fetches allowed to stay outstanding. Operand reads from LDS
+//    are ordinary loads whose waits the compiler places itself;
+//  * H' rows leave with the non-temporal hint: they are not read again by this kernel.
+constexpr int DT_TI = 32, DT_NBUF = 5, DT_AHEAD = 4;
+
+// 16 bytes per lane from global (uniform base + per-lane byte offset) to LDS (uniform address + 16 * lane)
+__device__ __forceinline__ void dma16(const void* gbase, unsigned voff, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n" ::"s"(lds_addr), "v"(voff), "s"(gbase)
+               : "memory");
+}
+
+constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
+
+// waits until at most n (rounded down to even, at most 30) of this wave's vector-memory operations are outstanding
+__device__ __forceinline__ void wait_vm(int n) {
+  switch (n >> 1) {
+#define LASER_VM_CASE(i) case i: __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * i)); break;
+    LASER_VM_CASE(1) LASER_VM_CASE(2) LASER_VM_CASE(3) LASER_VM_CASE(4) LASER_VM_CASE(5) LASER_VM_CASE(6)
+    LASER_VM_CASE(7) LASER_VM_CASE(8) LASER_VM_CASE(9) LASER_VM_CASE(10) LASER_VM_CASE(11) LASER_VM_CASE(12)
+    LASER_VM_CASE(13) LASER_VM_CASE(14)
+#undef LASER_VM_CASE
+    default:
+      if (n >= 30) __builtin_amdgcn_s_waitcnt(vmcnt_imm(30));
+      else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+  }
+}
+
+typedef __attribute__((address_space(3))) unsigned char* lds_bytes;
+// The compiler re-associates "lane offset + buffer offset + constant" into one three-operand add per read; hiding
+// the sum of the first two behind an empty asm leaves it "register + constant", which becomes the read's
+// immediate offset.
+__device__ __forceinline__ lds_bytes lds_at(unsigned addr) { return (lds_bytes)(size_t)addr; }
+__device__ __forceinline__ lds_bytes lds_opaque(unsigned addr) {
+  asm volatile("" : "+v"(addr));
+  return lds_at(addr);
+}
+__device__ __forceinline__ bf16x8 lds_read16(lds_bytes p) {
+  return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(p);
+}
+// items k0..k0+3 and k0+8..k0+11 of one value column per lane (see the file header); p addresses row k0
+__device__ __forceinline__ bf16x8 lds_read_tr(lds_bytes p) {
+  const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
+  const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p + 2048));
+  return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+// Barrier without the fence of __syncthreads(): the compiler neither waits for the wave's outstanding LDS reads
+// (they are awaited where their registers are used) nor moves memory operations across it.
+__device__ __forceinline__ void bare_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned short* __restrict__ q,
+                                                               const unsigned short* __restrict__ k,
+                                                               const unsigned short* __restrict__ v,
+                                                               const int32_t* __restrict__ lens, int C, int L, int w,
+                                                               int S, int spw, int ctiles, int sruns,
+                                                               float neg_scale_log2e,
+                                                               unsigned short* __restrict__ seg_out,
+                                                               int32_t* __restrict__ seg_cnt) {
+  constexpr int DQ = 128, D = 128, KSTEPS = DQ / 16, DB = D / 32;
+  static_assert(DB == 4 && KSTEPS == 8, "operand reads below are written out for d_q = d = 128");
+  static_assert((16 / NW) % 2 == 0, "wait_vm counts in steps of two");
+  constexpr int NT = 64 * NW;
+  constexpr int ROWB = 256;          // bytes per K row and per V row
+  constexpr int KB = DT_TI * ROWB, VB = DT_TI * ROWB, TB = KB + VB;
+  constexpr int OP = OPitch<D>::v, OBYTES = CW * OP;
+  constexpr int IPW = 8 / NW;        // 1 KB fetch groups per wave per matrix per tile (a tile has 8 of each)
+  constexpr int OPT = 2 * IPW;       // fetch instructions per wave per tile
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[DT_NBUF * TB + NW * OBYTES];
+
+  // Workgroups are dealt to the eight XCDs round-robin by index; renumber them so that each XCD gets a contiguous
+  // range: the workgroups that share a user's queries then share an L2 as well
+  int bid = blockIdx.x;
+  if (gridDim.x % 8 == 0) bid = (bid % 8) * (gridDim.x / 8) + bid / 8;
+  const int srun = bid % sruns;
+  bid /= sruns;
+  const int ct = bid % ctiles;
+  const int u = bid / ctiles;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: fetch addresses and cursors stay scalar
+  const int l32 = lane & 31, h = lane >> 5;
+  const int cbase = ct * (CW * NW) + wave * CW;
+  unsigned char* opatch = smem + DT_NBUF * TB + wave * OBYTES;
+  const unsigned lds_base = __builtin_amdgcn_readfirstlane(
+      (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem);
+
+  // Queries first, before anything that depends on the valid length: the wave's 32 rows (8 KB, K swizzle) are
+  // fetched into its output patch, which is idle until the first segment ends, and read into registers once.
+  // Rows past the last candidate repeat it (never stored).
+  const int frow = lane >> 4, fpos = lane & 15;
+  const unsigned qlds = lds_base + DT_NBUF * TB + wave * OBYTES;
+  {
+    const unsigned char* qU = reinterpret_cast<const unsigned char*>(q + (size_t)u * C * DQ);
+#pragma unroll
+    for (int j = 0; j < CW / 4; ++j) {
+      const int row = j * 4 + frow;
+      const int c = cbase + row < C ? cbase + row : C - 1;
+      dma16(qU, (unsigned)c * ROWB + ((fpos ^ (row & 15)) << 4), qlds + j * 1024);
+    }
+  }
+  const int n = __builtin_amdgcn_readfirstlane(valid_len(lens, u, L));
+
+  const unsigned char* kU = reinterpret_cast<const unsigned char*>(k + (size_t)u * L * DQ);
+  const unsigned char* vU = reinterpret_cast<const unsigned char*>(v + (size_t)u * L * D);
+
+  const int seg_lo = srun * spw;
+  const int seg_hi = (seg_lo + spw) < S ? (seg_lo + spw) : S;
+  int seg_ne = seg_lo;
+  while (seg_ne < seg_hi && seg_ne * w < n) ++seg_ne;
+  auto seg_end = [&](int i) {
+    int e = i * w + w;
+    if (e > L) e = L;
+    if (e > n) e = n;
+    return e;
+  };
+
+  // ---- fetch side: this wave moves rows 4 g .. 4 g + 3 of every tile, g = wave * IPW + j
+  unsigned fk[IPW], fv[IPW];   // per-lane byte offsets inside a full tile (row and swizzled chunk)
+#pragma unroll
+  for (int j = 0; j < IPW; ++j) {
+    const int row = (wave * IPW + j) * 4 + frow;
+    fk[j] = row * ROWB + ((fpos ^ (row & 15)) << 4);
+    fv[j] = row * ROWB + ((fpos ^ (4 * (row & 3))) << 4);
+  }
+  auto issue_tile = [&](int t0, int hi, int buf) {   // requires t0 < hi
+    const unsigned char* kT = kU + (size_t)t0 * ROWB;
+    const unsigned char* vT = vU + (size_t)t0 * ROWB;
+    const unsigned dst = lds_base + buf * TB;
+    if (hi - t0 >= DT_TI) {
+#pragma unroll
+      for (int j = 0; j < IPW; ++j) {
+        const int g = wave * IPW + j;
+        dma16(kT, fk[j], dst + g * 1024);
+        dma16(vT, fv[j], dst + KB + g * 1024);
+      }
+    } else {   // partial tile: rows past the last valid one repeat it
+      const int last = hi - t0 - 1;
+#pragma unroll
+      for (int j = 0; j < IPW; ++j) {
+        const int g = wave * IPW + j;
+        const int row = g * 4 + frow;
+        const int back = row > last ? (row - last) * ROWB : 0;
+        dma16(kT, fk[j] - back, dst + g * 1024);
+        dma16(vT, fv[j] - back, dst + KB + g * 1024);
+      }
+    }
+  };
+  // tile cursor: (segment, first item, end of the segment's valid items); advance() moves to the next tile of the run
+  struct Cur { int seg, t0, hi; };
+  auto advance = [&](Cur c) {
+    Cur o = c;
+    o.t0 = c.t0 + DT_TI;
+    if (o.t0 >= c.hi) {
+      o.seg = c.seg + 1;
+      o.t0 = o.seg * w;
+      o.hi = o.seg < seg_ne ? seg_end(o.seg) : 0;
+    }
+    return o;
+  };
+
+  // ---- operand side (constant per lane): swizzled byte offsets inside a tile
+  unsigned kofs[KSTEPS], vofs[DB];
+#pragma unroll
+  for (int ks = 0; ks < KSTEPS; ++ks) kofs[ks] = l32 * ROWB + (((2 * ks + h) ^ (l32 & 15)) << 4);
+  {
+    const int i16 = lane & 15;
+    const int rr = h * 4 + (i16 >> 2);
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      const int c16 = db * 4 + 2 * (l32 >> 4) + ((i16 & 3) >> 1);
+      vofs[db] = KB + rr * ROWB + ((c16 ^ (4 * (rr & 3))) << 4) + (i16 & 1) * 8;
+    }
+  }
+
+  f32x16 acc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[db][r] = 0.0f;
+
+  // ---- output side: the patch is read back 16 bytes per lane, four rows per wave-wide store; the per-lane part
+  // of the global address never changes, the rest is a scalar base
+  constexpr int LPR = D / 8, RPI = 64 / LPR;
+  const unsigned char* opr = opatch + (lane / LPR) * OP + (lane % LPR) * 16;
+  const unsigned ooff = (unsigned)(lane / LPR) * (unsigned)S * (D * 2) + (lane % LPR) * 16;
+  unsigned char* oU = reinterpret_cast<unsigned char*>(seg_out) + ((size_t)u * C + cbase) * S * (D * 2);
+  const bool all_rows = cbase + CW <= C;
+  auto flush = [&](int seg) {
+    u32x4 val[CW / RPI];   // all reads first: one LDS latency per segment instead of one per row group
+#pragma unroll
+    for (int it = 0; it < CW / RPI; ++it) val[it] = *reinterpret_cast<const u32x4*>(opr + it * RPI * OP);
+#pragma unroll
+    for (int it = 0; it < CW / RPI; ++it) {
+      unsigned char* dst = oU + ((size_t)it * RPI * S + seg) * (D * 2);
+      if (all_rows || cbase + it * RPI + lane / LPR < C)
+        asm volatile("global_store_dwordx4 %0, %1, %2 nt" ::"v"(ooff), "v"(val[it]), "s"(dst) : "memory");
+    }
+  };
+
+  const bool any = seg_ne > seg_lo;
+  Cur cur{seg_lo, seg_lo * w, any ? seg_end(seg_lo) : 0};   // tile being computed
+  Cur fet = cur;                                             // next tile to fetch
+  int fetched = 0, done = 0;                                 // tiles requested / tiles finished
+  int fbuf = 0, cbuf = 0;                                    // their LDS buffers
+  auto issue_next = [&]() {
+    if (fet.seg < seg_ne) {
+      issue_tile(fet.t0, fet.hi, fbuf);
+      fet = advance(fet);
+      ++fetched;
+      fbuf = fbuf + 1 == DT_NBUF ? 0 : fbuf + 1;
+    }
+  };
+  // Only fetches may be allowed to stay outstanding in a wait: loads retire in order among themselves but not
+  // relative to stores, so with H' stores allowed for, the count would no longer say which operations are the
+  // outstanding ones. wait_tile(x): this wave's share of tile x has landed (tiles are numbered in request order).
+  auto wait_tile = [&](int x) {
+    const int beyond = fetched - 1 - x;
+    wait_vm(OPT * (beyond > 0 ? beyond : 0));
+  };
+  if (any) {
+#pragma unroll 1
+    for (int a = 0; a < DT_AHEAD; ++a) issue_next();
+  }
+  if (srun == 0 && ct == 0) write_seg_cnt(seg_cnt, u, n, L, w, S, tid, NT);
+  wait_tile(0);   // and the queries, which are older (with no tile requested this waits for everything)
+  __syncthreads();
+
+  bf16x8 qreg[KSTEPS], ka[KSTEPS], va[2][DB];
+  auto read_k = [&](int buf) {
+    const unsigned tb = lds_base + buf * TB;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) ka[ks] = lds_read16(lds_at(kofs[ks] + tb));
+  };
+  auto read_v = [&](int buf) {
+    const unsigned tb = lds_base + buf * TB;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      const lds_bytes a = lds_opaque(vofs[db] + tb);
+      va[0][db] = lds_read_tr(a);
+      va[1][db] = lds_read_tr(a + 4096);
+    }
+  };
+  if (any) {
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) qreg[ks] = lds_read16(lds_at(kofs[ks] + qlds));
+    read_k(0);
+    read_v(0);
+  }
+  int out_seg = -1;
+
+  // One step per tile, one barrier per step, software-pipelined inside the wave so that the matrix pipe always
+  // has work while the vector ALU evaluates gates:
+  //   scores(t+1) [MFMA]  alongside  gates(t) [VALU, on the scores computed one step earlier]
+  //   aggregation(t) [MFMA]
+  // Operand reads run one step ahead of their use: K(t+2) is requested once scores(t+1) has consumed the K
+  // registers, V(t+1) once aggregation(t) has consumed the V registers, and they stay in flight across the
+  // barrier (it carries no fence). When a wave reaches the barrier of step t it has consumed, hence received,
+  // K(t) and V(t-1): after that barrier the buffer of tile t-1 is idle in all waves and takes the fetch of tile
+  // t + NBUF - 1. The same barrier publishes tile t + 2, whose share every wave has awaited just before.
+  auto scores = [&]() {
+    const f32x16 zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+    f32x16 sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0], qreg[0], zero, 0, 0, 0);
+#pragma unroll
+    for (int ks = 1; ks < KSTEPS; ++ks) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[ks], sc, 0, 0, 0);
+    return sc;
+  };
+  f32x16 sc_cur;
+  if (any) {
+    wait_tile(1);
+    __syncthreads();
+    sc_cur = scores();
+    if (advance(cur).seg < seg_ne) read_k(1);
+  }
+  while (cur.seg < seg_ne) {
+    const Cur nxt = advance(cur);
+    const bool has_next = nxt.seg < seg_ne;
+    const bool has_next2 = has_next && advance(nxt).seg < seg_ne;
+    const int nbuf = cbuf + 1 == DT_NBUF ? 0 : cbuf + 1;
+    const int nbuf2 = nbuf + 1 == DT_NBUF ? 0 : nbuf + 1;
+    wait_tile(done + 2);
+    bare_barrier();
+    if (out_seg >= 0) {   // right after the wait: the stores have a whole step to complete before the next one
+      flush(out_seg);
+      out_seg = -1;
+    }
+    issue_next();
+
+    f32x16 sc_nxt;
+    bf16x8 p[2];
+    const int nvt = cur.hi - cur.t0;
+    if (has_next && nvt >= DT_TI) {
+      // steady state, one basic block: the score chain of the next tile with this tile's gates between its links
+      sc_nxt = scores();
+#pragma unroll
+      for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) p[s][e] = (__bf16)gate(sc_cur[s * 8 + e], neg_scale_log2e);
+#pragma unroll
+      for (int i = 0; i < KSTEPS; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+        __builtin_amdgcn_sched_group_barrier(0x002, 9, 0);   // nine vector-ALU instructions
+      }
+    } else {
+      if (has_next) sc_nxt = scores();
+      // partial tile: rows >= nvt are copies of the last valid row, their gates are zero
+#pragma unroll
+      for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int item = s * 16 + 8 * (e >> 2) + 4 * h + (e & 3);
+          p[s][e] = (__bf16)(item < nvt ? gate(sc_cur[s * 8 + e], neg_scale_log2e) : 0.0f);
+        }
+    }
+    if (has_next2) read_k(nbuf2);
+    if (cur.t0 == cur.seg * w) {   // first tile of a segment: start from an inline zero (no clearing pass)
+      const f32x16 zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+      for (int db = 0; db < DB; ++db) acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[0][db], p[0], zero, 0, 0, 0);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[1][db], p[1], acc[db], 0, 0, 0);
+    } else {
+#pragma unroll
+      for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+          acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[s][db], p[s], acc[db], 0, 0, 0);
+    }
+    if (has_next) read_v(nbuf);
+
+    if (nxt.seg != cur.seg) {   // segment finished: park H' rows in the patch
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          bf16x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[db][g * 4 + e];
+          *reinterpret_cast<u32x2*>(opatch + l32 * OP + (db * 32 + g * 8 + h * 4) * 2) = __builtin_bit_cast(u32x2, o);
+        }
+      out_seg = cur.seg;
+    }
+    ++done;
+    cbuf = nbuf;
+    cur = nxt;
+    if (has_next) sc_cur = sc_nxt;
+  }
+  if (out_seg >= 0) flush(out_seg);
+
+  if (seg_ne < seg_hi) {   // empty segments of the run: exact zeros
+    const int ncand = (C - ct * (CW * NW)) < CW * NW ? (C - ct * (CW * NW)) : CW * NW;
+    const int per_row = D / 8;
+    const int rows = ncand * (seg_hi - seg_ne);
+    for (int e = tid; e < rows * per_row; e += NT) {
+      const int row = e / per_row, ch = e - row * per_row;
+      const int cc = row / (seg_hi - seg_ne), ii = seg_ne + row % (seg_hi - seg_ne);
+      *reinterpret_cast<u32x4*>(seg_out + (((size_t)u * C + ct * (CW * NW) + cc) * S + ii) * D + ch * 8) =
+          u32x4{0u, 0u, 0u, 0u};
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------------------ host side
 static int pick_nw(int C) { return C > 128 ? 8 : (C > 64 ? 4 : (C > 32 ? 2 : 1)); }
 
@@ -517,9 +897,15 @@ static void launch_one(const StaArgs& a, int spw, int ctiles, int sruns, float n
 
 template <int DQ, int D>
 static void launch_nw(const StaArgs& a, int nw, int spw, int ctiles, int sruns, float nsl) {
-  // eight waves fill a compute unit on their own and prefetch through a second LDS buffer; smaller workgroups
-  // overlap memory and MFMA work across the several workgroups that share a compute unit
-  if (nw == 8) {
+  // eight waves fill a compute unit on their own and prefetch through LDS buffers of their own (direct-to-LDS
+  // fetches for d_q = d = 128; LASER_STA_NODMA=1 selects the register-staged form there too, for comparison);
+  // smaller workgroups overlap memory and MFMA work across the several workgroups that share a compute unit
+  if (nw == 8 && DQ == 128 && D == 128 && getenv("LASER_STA_NODMA") == nullptr) {
+    const unsigned blocks = (unsigned)((long long)a.U * ctiles * sruns);
+    hipLaunchKernelGGL((sta_mfma_dma_kernel<8>), dim3(blocks), dim3(512), 0, a.stream, (const unsigned short*)a.q,
+                       (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens, a.C, a.L, a.w, a.S, spw,
+                       ctiles, sruns, nsl, (unsigned short*)a.seg_out, a.seg_cnt);
+  } else if (nw == 8) {
     const unsigned blocks = (unsigned)((long long)a.U * ctiles * sruns);
     hipLaunchKernelGGL((sta_mfma_pipe_kernel<DQ, D, 8>), dim3(blocks), dim3(512), 0, a.stream,
                        (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens,
