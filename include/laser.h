@@ -61,7 +61,8 @@ typedef enum {
   LASER_GSTA_AUTO = 0,
   LASER_GSTA_GENERIC = 1, /* fp32 FMA, one workgroup per pair, any shape              */
   LASER_GSTA_TILED = 2,   /* bf16 storage, a tile of pairs per workgroup, MFMA, any M */
-  LASER_GSTA_SPLIT = 3    /* bf16 storage, M = 1: projection / streaming / output kernels; z_out is the scratch */
+  LASER_GSTA_SPLIT = 3,   /* bf16 storage, M = 1: projection / streaming / output kernels; z_out is the scratch */
+  LASER_GSTA_ONE = 4      /* bf16 storage, M = 1: the same three steps in one launch, 32 pairs per workgroup */
 } laser_gsta_variant;
 
 /*

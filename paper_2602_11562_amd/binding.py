@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "liblaser.so")
 
 LASER_F32, LASER_BF16 = 0, 1
 STA_AUTO, STA_GENERIC, STA_MFMA, STA_STREAM = 0, 1, 2, 3
-GSTA_AUTO, GSTA_GENERIC, GSTA_TILED, GSTA_SPLIT = 0, 1, 2, 3
+GSTA_AUTO, GSTA_GENERIC, GSTA_TILED, GSTA_SPLIT, GSTA_ONE = 0, 1, 2, 3, 4
 
 EXPORTS = [
     "laser_sta_forward", "laser_sta_forward_variant", "laser_gsta_forward", "laser_gsta_forward_variant",

@@ -259,8 +259,7 @@ __global__ __launch_bounds__(GT_THREADS) void gsta_tiled_kernel(const unsigned s
         float sdot = 0.0f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) sdot = fmaf(x[e], rs[e], sdot);
-#pragma unroll
-        for (int off = 1; off < LPR; off <<= 1) sdot += __shfl_xor(sdot, off, 64);
+        sdot = row_sum<LPR>(sdot);
         const bool ok = (j * RPW + grp) < nv;
         const float m_new = ok ? fmaxf(m, sdot) : m;
         const float sc = (m == m_new) ? 1.0f : __expf(m - m_new);
@@ -515,8 +514,7 @@ __global__ __launch_bounds__(GS_THREADS) void gsta_pool_kernel(const unsigned sh
     float sdot = 0.0f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) sdot = fmaf(x[e], rs[e], sdot);
-#pragma unroll
-    for (int off = 1; off < LPR; off <<= 1) sdot += __shfl_xor(sdot, off, 64);
+    sdot = row_sum<LPR>(sdot);
     const bool ok = (j * RPW + grp) < nv;
     const float m_new = ok ? fmaxf(m, sdot) : m;
     const float sc = (m == m_new) ? 1.0f : __expf(m - m_new);
@@ -545,6 +543,238 @@ __global__ __launch_bounds__(GS_THREADS) void gsta_pool_kernel(const unsigned sh
     for (int e = 0; e < 4; ++e) { a[e] = pacc[e] * inv; b[e] = pacc[4 + e] * inv; }
     *reinterpret_cast<f32x4*>(z + (size_t)pr * D + gl * 8) = a;
     *reinterpret_cast<f32x4*>(z + (size_t)pr * D + gl * 8 + 4) = b;
+  }
+}
+
+// ------------------------------------------------------------------------------------------ one-kernel form (M = 1)
+// The three steps of the split form in one launch, for a tile of 32 pairs per workgroup (8 waves, 4 pairs each),
+// so that the layer costs one launch and about one round trip to memory plus the H' stream:
+//   * the lower four waves request the three weight matrices and the t0 tile (coalesced 16-byte pieces, a few
+//     registers per lane) and park them in LDS, each matrix in the layout its MFMA operand read wants: W_q and
+//     W_v (contraction index = row) padded for the transpose load, W_k (contraction index = column) padded for
+//     16-byte row reads; waves 0 .. d/32-1 then run q' = t0 W_q and r = q' W_k^T / sqrt(d) from LDS;
+//   * every wave reads the H' blocks of its four pairs into registers (all S rows, unconditionally: rows of empty
+//     segments are replaced by zeros when they are used, so nothing waits for the valid lengths); when each wave
+//     asks for them is explained in the kernel;
+//   * each wave reduces its pairs from registers (scores, softmax, weighted sum);
+//   * z = t0 + p W_v leaves from the accumulator layout (128-byte row pieces).
+template <int D> struct RPitch { static constexpr int v = D * 2 + 16; };   // 16-byte reads of 32 consecutive rows
+
+// [32 x D] (LDS, fp32, pitch FP) times W^T with W bf16 [D][D] in LDS (pitch RPitch): out[p][n] = sum_k X[p][k] W[n][k]
+template <int D>
+__device__ __forceinline__ f32x16 tile_gemm_lds_rows(const float* X, int FP, const unsigned char* Wl, int nb, int l32,
+                                                     int h) {
+  constexpr int RP = RPitch<D>::v;
+  f32x16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+  const unsigned char* base = Wl + (nb * 32 + l32) * RP + h * 16;
+#pragma unroll 2
+  for (int ks = 0; ks < D / 16; ++ks) {
+    const bf16x8 b = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(base + ks * 32));
+    const HiLo a = split8(X + l32 * FP + ks * 16 + h * 8);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.hi, b, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.lo, b, acc, 0, 0, 0);
+  }
+  return acc;
+}
+
+template <int D, int ROWS>
+__global__ __launch_bounds__(GT_THREADS) void gsta_one_kernel(const unsigned short* __restrict__ seg,
+                                                              const unsigned short* __restrict__ t0,
+                                                              const unsigned short* __restrict__ wq,
+                                                              const unsigned short* __restrict__ wk,
+                                                              const unsigned short* __restrict__ wv,
+                                                              const int32_t* __restrict__ lens, int P, int C, int L,
+                                                              int w, int S, float* __restrict__ z) {
+  constexpr int FP = D + 4, DB = D / 32, LPR = D / 8, RPW = 64 / LPR;
+  constexpr int WP = WPitch<D>::v, RP = RPitch<D>::v, CH = D / 8;
+  constexpr int PPW = GT_ROWS / GT_WAVES;   // pairs per wave
+  __shared__ __attribute__((aligned(16))) float bufA[GT_ROWS * FP];
+  __shared__ __attribute__((aligned(16))) float bufB[GT_ROWS * FP];
+  __shared__ __attribute__((aligned(16))) unsigned char Wql[D * WP];
+  __shared__ __attribute__((aligned(16))) unsigned char Wvl[D * WP];
+  __shared__ __attribute__((aligned(16))) unsigned char Wkl[D * RP];
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: the valid lengths become scalar loads
+  const int pbase = blockIdx.x * GT_ROWS;
+  const int grp = lane / LPR, gl = lane % LPR;
+  // (a vector load of a length here would make the compiler wait for every load in flight, the H' stream included)
+  int nvs[PPW];
+#pragma unroll
+  for (int it = 0; it < PPW; ++it) {
+    const int pr = pbase + wave * PPW + it;
+    nvs[it] = pr < P ? (valid_len(lens, pr / C, L) + w - 1) / w : 0;
+  }
+
+  // One register set per pair. A wave issues in order, and a compute unit's memory pipeline accepts requests only
+  // about as fast as the data comes back: a wave that asks for much sits in the issue queue, and would keep its
+  // workgroup waiting at every barrier it has not reached. So the roles are split. The upper four waves ask for
+  // all their blocks at once and meet the others only when r is needed. The lower four waves fetch and park the
+  // small operands and run the projection chain, synchronising among themselves through a counter in LDS (the
+  // hardware barrier counts every wave of the workgroup); they ask for their own blocks once r is written, and
+  // those stream in while the upper waves, which share their SIMDs, reduce.
+  u32x4 hring[PPW][ROWS];
+  auto load_pair = [&](int it, u32x4 (&hreg)[ROWS]) {
+    const int pr = (pbase + wave * PPW + it) < P ? (pbase + wave * PPW + it) : (P - 1);   // past the batch: repeat
+    const unsigned short* H = seg + (size_t)pr * S * D;
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j) {
+      const int i = j * RPW + grp;
+      hreg[j] = *reinterpret_cast<const u32x4*>(H + (size_t)(i < S ? i : S - 1) * D + gl * 8);
+    }
+  };
+  const bool front = wave < GT_WAVES / 2;
+  __shared__ unsigned int arrived[2];
+  if (tid < 2) arrived[tid] = 0u;
+  __syncthreads();   // everyone is here within the first instructions; nothing has been requested yet
+  // arrival counter for the lower waves: LDS operations of a wave execute in order, so what it wrote before its
+  // increment is visible to whoever reads the new count; all four waves are resident, so the wait ends
+  auto lower_sync = [&](int idx) {
+    if (lane == 0) __hip_atomic_fetch_add(&arrived[idx], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+    while (__hip_atomic_load(&arrived[idx], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < GT_WAVES / 2)
+      __builtin_amdgcn_s_sleep(1);
+  };
+  if (!front) {
+#pragma unroll
+    for (int it = 0; it < PPW; ++it) load_pair(it, hring[it]);
+  } else {
+    constexpr int FT = GT_THREADS / 2;
+    constexpr int WIT = D * CH / FT;                   // 16-byte pieces per thread and matrix
+    constexpr int TIT = GT_ROWS * (D / 4) / FT;        // 8-byte pieces of the t0 tile per thread
+    static_assert((D * CH) % FT == 0 && (GT_ROWS * (D / 4)) % FT == 0, "tile sizes divide the loader threads");
+    u32x4 rq[WIT], rk[WIT], rv[WIT];
+    unsigned int traw[TIT][2];
+#pragma unroll
+    for (int it = 0; it < WIT; ++it) rq[it] = *reinterpret_cast<const u32x4*>(wq + (size_t)(tid + it * FT) * 8);
+#pragma unroll
+    for (int it = 0; it < TIT; ++it) {
+      const int e = tid + it * FT, row = e / (D / 4), c4 = e % (D / 4);
+      const int pr = (pbase + row) < P ? (pbase + row) : (P - 1);
+      const unsigned int* p2 = reinterpret_cast<const unsigned int*>(t0 + (size_t)pr * D + c4 * 4);
+      traw[it][0] = p2[0];
+      traw[it][1] = p2[1];
+    }
+#pragma unroll
+    for (int it = 0; it < WIT; ++it) rk[it] = *reinterpret_cast<const u32x4*>(wk + (size_t)(tid + it * FT) * 8);
+#pragma unroll
+    for (int it = 0; it < WIT; ++it) rv[it] = *reinterpret_cast<const u32x4*>(wv + (size_t)(tid + it * FT) * 8);
+    // park them in LDS, each matrix with the pitch its operand read wants
+#pragma unroll
+    for (int it = 0; it < WIT; ++it) {
+      const int e = tid + it * FT, row = e / CH, ch = e % CH;
+      *reinterpret_cast<u32x4*>(Wql + row * WP + ch * 16) = rq[it];
+    }
+#pragma unroll
+    for (int it = 0; it < TIT; ++it) {
+      const int e = tid + it * FT, row = e / (D / 4), c4 = e % (D / 4);
+      *reinterpret_cast<f32x4*>(bufA + row * FP + c4 * 4) =
+          f32x4{__uint_as_float(traw[it][0] << 16), __uint_as_float(traw[it][0] & 0xffff0000u),
+                __uint_as_float(traw[it][1] << 16), __uint_as_float(traw[it][1] & 0xffff0000u)};
+    }
+#pragma unroll
+    for (int it = 0; it < WIT; ++it) {
+      const int e = tid + it * FT, row = e / CH, ch = e % CH;
+      *reinterpret_cast<u32x4*>(Wkl + row * RP + ch * 16) = rk[it];
+      *reinterpret_cast<u32x4*>(Wvl + row * WP + ch * 16) = rv[it];
+    }
+  }
+  if (front) lower_sync(0);
+  f32x16 ts;
+  if (wave < DB) {   // q' = t0 W_q; t0 in accumulator layout is kept for the last step
+#pragma unroll
+    for (int r = 0; r < 16; ++r) ts[r] = bufA[(8 * (r >> 2) + 4 * h + (r & 3)) * FP + wave * 32 + l32];
+    const f32x16 qp = tile_gemm_lds<D>(bufA, FP, Wql, wave, lane, l32, h);
+    store_acc(bufB, FP, qp, wave, l32, h, 1.0f);
+  }
+  if (front) lower_sync(1);
+  if (wave < DB) {   // r = q' W_k^T / sqrt(d)
+    const f32x16 rr = tile_gemm_lds_rows<D>(bufB, FP, Wkl, wave, l32, h);
+    store_acc(bufA, FP, rr, wave, l32, h, 1.0f / sqrtf((float)D));
+  }
+  __syncthreads();   // r complete in bufA; q' in bufB consumed
+  if (front) {
+#pragma unroll
+    for (int it = 0; it < PPW; ++it) load_pair(it, hring[it]);
+  }
+
+#pragma unroll
+  for (int it = 0; it < PPW; ++it) {
+    u32x4 (&hcur)[ROWS] = hring[it];
+    const int pi = wave * PPW + it, nv = nvs[it];
+    float rs[8];
+    {
+      const f32x4 a = *reinterpret_cast<const f32x4*>(bufA + pi * FP + gl * 8);
+      const f32x4 b = *reinterpret_cast<const f32x4*>(bufA + pi * FP + gl * 8 + 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { rs[e] = a[e]; rs[4 + e] = b[e]; }
+    }
+    // Two passes over the register-resident block instead of a running maximum: the rows' scores are independent
+    // of each other (eight dot products in flight instead of one chain of dependent rescalings), and the weighted
+    // sum then needs no rescaling. Rows of empty segments count as zeros whatever they hold.
+    float sd[ROWS];
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j) {
+      const bool ok = (j * RPW + grp) < nv;
+      float sdot = 0.0f;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const unsigned int pk = ok ? hcur[j][e] : 0u;
+        sdot = fmaf(__uint_as_float(pk << 16), rs[2 * e], sdot);
+        sdot = fmaf(__uint_as_float(pk & 0xffff0000u), rs[2 * e + 1], sdot);
+      }
+      sdot = row_sum<LPR>(sdot);
+      sd[j] = ok ? sdot : -INFINITY;
+    }
+    float m = sd[0];
+#pragma unroll
+    for (int j = 1; j < ROWS; ++j) m = fmaxf(m, sd[j]);
+    const float mref = (m == -INFINITY) ? 0.0f : m;   // no valid row in this lane group
+    float den = 0.0f;
+    float pacc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) pacc[e] = 0.0f;
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j) {
+      const bool ok = (j * RPW + grp) < nv;
+      const float a = ok ? __expf(sd[j] - mref) : 0.0f;
+      den += a;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const unsigned int pk = ok ? hcur[j][e] : 0u;
+        pacc[2 * e] = fmaf(a, __uint_as_float(pk << 16), pacc[2 * e]);
+        pacc[2 * e + 1] = fmaf(a, __uint_as_float(pk & 0xffff0000u), pacc[2 * e + 1]);
+      }
+    }
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) {
+      const float m_o = __shfl_xor(m, off, 64);
+      const float den_o = __shfl_xor(den, off, 64);
+      const float M2 = fmaxf(m, m_o);
+      const float f = (m == M2) ? 1.0f : __expf(m - M2);
+      const float f_o = (m_o == M2) ? 1.0f : __expf(m_o - M2);
+      den = den * f + den_o * f_o;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) pacc[e] = pacc[e] * f + __shfl_xor(pacc[e], off, 64) * f_o;
+      m = M2;
+    }
+    if (grp == 0) {
+      const float inv = nv > 0 ? 1.0f / den : 0.0f;
+      f32x4 a, b;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { a[e] = pacc[e] * inv; b[e] = pacc[4 + e] * inv; }
+      *reinterpret_cast<f32x4*>(bufB + pi * FP + gl * 8) = a;
+      *reinterpret_cast<f32x4*>(bufB + pi * FP + gl * 8 + 4) = b;
+    }
+  }
+  __syncthreads();
+  if (wave < DB) {   // z = t0 + p W_v
+    const f32x16 o = tile_gemm_lds<D>(bufB, FP, Wvl, wave, lane, l32, h);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int pr = pbase + 8 * (r >> 2) + 4 * h + (r & 3);
+      if (pr < P) z[(size_t)pr * D + wave * 32 + l32] = ts[r] + o[r];
+    }
   }
 }
 
@@ -625,6 +855,35 @@ laser_status gsta_split_launch(const GstaArgs& a) {
   if (!gsta_split_supports(a)) return LASER_ERR_UNSUPPORTED;
   if (a.d == 64) launch_split<64>(a);
   else launch_split<128>(a);
+  return launch_status();
+}
+
+bool gsta_one_supports(const GstaArgs& a) {
+  if (a.dt != LASER_BF16 || a.M != 1) return false;
+  if (!(a.d == 64 || a.d == 128)) return false;
+  return rows_needed(a.S, a.d) <= 8;   // four H' blocks per wave are held in registers
+}
+
+template <int D>
+static void launch_one_kernel(const GstaArgs& a) {
+  const int P = a.U * a.C;
+  const unsigned tiles = (unsigned)((P + GT_ROWS - 1) / GT_ROWS);
+  const int rows = rows_needed(a.S, a.d);
+#define LASER_ONE(R)                                                                                               \
+  hipLaunchKernelGGL((gsta_one_kernel<D, R>), dim3(tiles), dim3(GT_THREADS), 0, a.stream,                         \
+                     (const unsigned short*)a.seg, (const unsigned short*)a.t0, (const unsigned short*)a.wq,       \
+                     (const unsigned short*)a.wk, (const unsigned short*)a.wv, a.lens, P, a.C, a.L, a.w, a.S,      \
+                     a.z_out)
+  if (rows <= 2) LASER_ONE(2);
+  else if (rows <= 4) LASER_ONE(4);
+  else LASER_ONE(8);
+#undef LASER_ONE
+}
+
+laser_status gsta_one_launch(const GstaArgs& a) {
+  if (!gsta_one_supports(a)) return LASER_ERR_UNSUPPORTED;
+  if (a.d == 64) launch_one_kernel<64>(a);
+  else launch_one_kernel<128>(a);
   return launch_status();
 }
 

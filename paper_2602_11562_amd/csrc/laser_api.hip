@@ -55,6 +55,7 @@ static laser_sta_variant pick_sta(const StaArgs& a) {
 }
 
 static laser_gsta_variant pick_gsta(const GstaArgs& a) {
+  if (gsta_one_supports(a)) return LASER_GSTA_ONE;
   if (gsta_split_supports(a)) return LASER_GSTA_SPLIT;
   return gsta_tiled_supports(a) ? LASER_GSTA_TILED : LASER_GSTA_GENERIC;
 }
@@ -77,6 +78,7 @@ static laser_status run_gsta(const GstaArgs& a, laser_gsta_variant variant) {
     case LASER_GSTA_GENERIC: return gsta_generic_launch(a);
     case LASER_GSTA_TILED: return gsta_tiled_launch(a);
     case LASER_GSTA_SPLIT: return gsta_split_launch(a);
+    case LASER_GSTA_ONE: return gsta_one_launch(a);
     default: return LASER_ERR_UNSUPPORTED;
   }
 }
@@ -111,7 +113,7 @@ laser_status laser_gsta_forward_variant(const void* seg, const void* t0, const v
   GstaArgs a;
   laser_status s = validate_gsta(seg, t0, wq, wk, wv, lens, U, C, L, d, w, M, dt, z_out, stream, &a);
   if (s != LASER_OK) return s;
-  if (variant < LASER_GSTA_AUTO || variant > LASER_GSTA_SPLIT) return LASER_ERR_UNSUPPORTED;
+  if (variant < LASER_GSTA_AUTO || variant > LASER_GSTA_ONE) return LASER_ERR_UNSUPPORTED;
   return run_gsta(a, variant);
 }
 
@@ -154,6 +156,7 @@ const char* laser_gsta_kernel_name(int C, int S, int d, laser_dtype dt) {
   if (C <= 0 || S <= 0 || d <= 0 || (dt != LASER_F32 && dt != LASER_BF16)) return "invalid";
   switch (pick_gsta(a)) {
     case LASER_GSTA_SPLIT: return "gsta_split_bf16";
+    case LASER_GSTA_ONE: return "gsta_one_bf16";
     case LASER_GSTA_TILED: return "gsta_tiled_bf16";
     default: return "gsta_generic";
   }

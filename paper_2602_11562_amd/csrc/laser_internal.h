@@ -49,6 +49,8 @@ bool gsta_tiled_supports(const GstaArgs& a);
 laser_status gsta_tiled_launch(const GstaArgs& a);
 bool gsta_split_supports(const GstaArgs& a);
 laser_status gsta_split_launch(const GstaArgs& a);
+bool gsta_one_supports(const GstaArgs& a);
+laser_status gsta_one_launch(const GstaArgs& a);
 
 inline laser_status launch_status() { return hipGetLastError() == hipSuccess ? LASER_OK : LASER_ERR_LAUNCH; }
 
@@ -98,6 +100,23 @@ __device__ __forceinline__ void write_seg_cnt(int32_t* seg_cnt, int u, int n, in
     seg_cnt[(size_t)u * S + i] = hi > lo ? hi - lo : 0;
   }
 }
+
+// Sum over aligned groups of LANES consecutive lanes (2, 4, 8 or 16), the result in every lane of the group. The
+// adds read their second operand through the data-parallel-primitive lane permutations of a 16-lane row (swap in
+// pairs, swap pairs in quads, mirror the half row, mirror the row: after each step the lanes that were combined
+// hold equal values, so a mirror reaches the other half's sum). A generic shuffle is an LDS round trip per step.
+#define LASER_DPP_ADD(v, ctrl) \
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, 0xf, 0xf, false))
+template <int LANES>
+__device__ __forceinline__ float row_sum(float v) {
+  static_assert(LANES == 1 || LANES == 2 || LANES == 4 || LANES == 8 || LANES == 16, "one 16-lane row at most");
+  if (LANES >= 2) LASER_DPP_ADD(v, 0xB1);    // quad_perm [1,0,3,2]
+  if (LANES >= 4) LASER_DPP_ADD(v, 0x4E);    // quad_perm [2,3,0,1]
+  if (LANES >= 8) LASER_DPP_ADD(v, 0x141);   // row_half_mirror
+  if (LANES >= 16) LASER_DPP_ADD(v, 0x140);  // row_mirror
+  return v;
+}
+#undef LASER_DPP_ADD
 
 __device__ __forceinline__ float wave_sum(float x) {
 #pragma unroll

@@ -110,8 +110,7 @@ __global__ __launch_bounds__(256) void sta_stream_kernel(const unsigned short* _
             float s = 0.0f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) s = fmaf(kf[e], qf[c][e], s);
-#pragma unroll
-            for (int off = 1; off < LQ; off <<= 1) s += __shfl_xor(s, off, 64);
+            s = row_sum<LQ>(s);
             const bool ok = (j0 + kl * RQ + rq) < hi;
             const float g = ok ? __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(s * neg_scale_log2e)) : 0.0f;
             if (SAME) {

@@ -18,7 +18,7 @@ pytestmark = pytest.mark.gpu
 laser = pytest.importorskip("paper_2602_11562_amd")
 
 STA_VARIANTS = {"auto": 0, "generic": 1, "mfma": 2, "stream": 3}
-GSTA_VARIANTS = {"auto": 0, "generic": 1, "tiled": 2, "split": 3}
+GSTA_VARIANTS = {"auto": 0, "generic": 1, "tiled": 2, "split": 3, "one": 4}
 
 C = workloads.CONFIGS
 REDUCED = {
