@@ -2,13 +2,17 @@
 //
 // With one or a few candidates the STA equation of Sec. 3.4.2 does about one flop per byte of history read, so
 // the matrix cores have nothing to amortise and the only thing that matters is that K and V are read once, in
-// full 16-byte lanes, with enough loads in flight. One workgroup owns (user, segment); its four waves take
-// alternating chunks of the segment's items. A K row is spread over d_q/8 lanes (16 bytes each), a V row over
+// full 16-byte lanes, with enough loads in flight. One workgroup owns a user's run of consecutive segments (the
+// whole user when there are enough users to fill the machine: a segment is a few tens of KB, too little to pay
+// a workgroup launch, a length load and a query load for); it walks them one after the other, its four waves
+// taking alternating chunks of the current segment's items. A K row is spread over d_q/8 lanes (16 bytes each), a V row over
 // d/8 lanes: the score is an 8-term dot product per lane plus a shuffle tree over the row's lanes, the gate is
 // evaluated once per (item, candidate), and each lane accumulates gate * v for its 8 value columns. Segment sums
 // are then reduced across the row groups of a wave with shuffles and across the four waves through LDS in a
-// fixed order (deterministic). Items at or past the valid length are neither read nor counted; empty segments
-// are written as zeros.
+// fixed order (deterministic). Items at or past the valid length are never read (a partial chunk re-reads the
+// segment's last valid row under a zero gate); empty segments are written as zeros.
+#include <cstdlib>
+
 #include "laser_internal.h"
 
 namespace laser {
@@ -28,7 +32,8 @@ __global__ __launch_bounds__(256) void sta_stream_kernel(const unsigned short* _
                                                          const unsigned short* __restrict__ k,
                                                          const unsigned short* __restrict__ v,
                                                          const int32_t* __restrict__ lens, int C, int L, int w, int S,
-                                                         float neg_scale_log2e, unsigned short* __restrict__ seg_out,
+                                                         int spg, int groups, float neg_scale_log2e,
+                                                         unsigned short* __restrict__ seg_out,
                                                          int32_t* __restrict__ seg_cnt) {
   constexpr int LQ = DQ / 8, LV = D / 8;           // lanes per K row / V row
   constexpr int RQ = 64 / LQ, RV = 64 / LV;        // rows per wave-wide load
@@ -38,23 +43,10 @@ __global__ __launch_bounds__(256) void sta_stream_kernel(const unsigned short* _
   __shared__ float red[4][CMAX][D];
   __shared__ float gs[4][CMAX][IPC];
 
-  const int u = blockIdx.x / S, i = blockIdx.x % S;
+  const int u = blockIdx.x / groups, grp = blockIdx.x % groups;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int n = valid_len(lens, u, L);
-  if (i == 0) write_seg_cnt(seg_cnt, u, n, L, w, S, tid, 256);
-  const int lo = i * w;
-  int hi = lo + w;
-  if (hi > L) hi = L;
-  if (hi > n) hi = n;
-
-  if (hi <= lo) {   // empty segment: exact zeros
-    for (int e = tid; e < C * D; e += 256) {
-      const int c = e / D, col = e - c * D;
-      seg_out[(((size_t)u * C + c) * S + i) * D + col] = 0;
-    }
-    return;
-  }
-
+  if (grp == 0) write_seg_cnt(seg_cnt, u, n, L, w, S, tid, 256);
   const int rq = lane / LQ, cq = lane % LQ;
   const int rv = lane / LV, cv = lane % LV;
 
@@ -65,48 +57,67 @@ __global__ __launch_bounds__(256) void sta_stream_kernel(const unsigned short* _
     if (c < C) raw = *reinterpret_cast<const u32x4*>(q + ((size_t)u * C + c) * DQ + cq * 8);
     unpack8(raw, qf[c]);
   }
-  float acc[CMAX][8];
-#pragma unroll
-  for (int c = 0; c < CMAX; ++c)
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc[c][e] = 0.0f;
-
   const unsigned short* kU = k + (size_t)u * L * DQ;
   const unsigned short* vU = v + (size_t)u * L * D;
 
-  // UNR chunks per step: all their loads are issued before the first one is consumed
-  constexpr int UNR = 4;
-  for (int jb = lo + wave * IPC; jb < hi; jb += 4 * IPC * UNR) {
-    u32x4 kreg[UNR][NKL], vreg[UNR][NVL];
+  const int i_beg = grp * spg;
+  const int i_end = (grp + 1) * spg < S ? (grp + 1) * spg : S;
+  // valid items are a prefix of the history, so the non-empty segments of the run are a prefix of the run
+  int i_ne = (n + w - 1) / w;
+  if (i_ne > i_end) i_ne = i_end;
+  if (i_ne < i_beg) i_ne = i_beg;
+  auto seg_hi = [&](int i) {
+    int hi = i * w + w;
+    if (hi > L) hi = L;
+    if (hi > n) hi = n;
+    return hi;
+  };
+
+  // A step is UNR chunks per wave (4 waves x UNR x IPC items of one segment); all waves take the same steps. The
+  // loads of the next step (possibly the next segment's first) are issued before the current step is consumed.
+  // Rows at or past the end of the segment are read from its last valid row and get a zero gate: straight-line
+  // loads, which the compiler can leave in flight behind the arithmetic.
+  constexpr int UNR = 4, STRIDE = 4 * IPC * UNR;
+  struct Regs { u32x4 k[UNR][NKL], v[UNR][NVL]; };
+  auto load_step = [&](int base, int hi, Regs& r) {
 #pragma unroll
     for (int uu = 0; uu < UNR; ++uu) {
-      const int j0 = jb + uu * 4 * IPC;
+      const int j0 = base + wave * IPC + uu * 4 * IPC;
 #pragma unroll
       for (int kl = 0; kl < NKL; ++kl) {
-        const int row = j0 + kl * RQ + rq;
-        kreg[uu][kl] = u32x4{0u, 0u, 0u, 0u};
-        if (row < hi) kreg[uu][kl] = *reinterpret_cast<const u32x4*>(kU + (size_t)row * DQ + cq * 8);
+        int row = j0 + kl * RQ + rq;
+        row = row < hi ? row : hi - 1;
+        r.k[uu][kl] = *reinterpret_cast<const u32x4*>(kU + (size_t)row * DQ + cq * 8);
       }
 #pragma unroll
       for (int vl = 0; vl < NVL; ++vl) {
-        const int row = j0 + vl * RV + rv;
-        vreg[uu][vl] = u32x4{0u, 0u, 0u, 0u};
-        if (row < hi) vreg[uu][vl] = *reinterpret_cast<const u32x4*>(vU + (size_t)row * D + cv * 8);
+        int row = j0 + vl * RV + rv;
+        row = row < hi ? row : hi - 1;
+        r.v[uu][vl] = *reinterpret_cast<const u32x4*>(vU + (size_t)row * D + cv * 8);
       }
     }
+  };
+  float acc[CMAX][8];
+  auto clear_acc = [&]() {
+#pragma unroll
+    for (int c = 0; c < CMAX; ++c)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[c][e] = 0.0f;
+  };
+  auto compute_step = [&](int base, int hi, const Regs& r) {
 #pragma unroll
     for (int uu = 0; uu < UNR; ++uu) {
-      const int j0 = jb + uu * 4 * IPC;
+      const int j0 = base + wave * IPC + uu * 4 * IPC;
       float vf[NVL][8];
 #pragma unroll
-      for (int vl = 0; vl < NVL; ++vl) unpack8(vreg[uu][vl], vf[vl]);
+      for (int vl = 0; vl < NVL; ++vl) unpack8(r.v[uu][vl], vf[vl]);
 #pragma unroll
       for (int c = 0; c < CMAX; ++c) {
         if (c < C) {
 #pragma unroll
           for (int kl = 0; kl < NKL; ++kl) {
             float kf[8];
-            unpack8(kreg[uu][kl], kf);
+            unpack8(r.k[uu][kl], kf);
             float s = 0.0f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) s = fmaf(kf[e], qf[c][e], s);
@@ -123,7 +134,7 @@ __global__ __launch_bounds__(256) void sta_stream_kernel(const unsigned short* _
           if (!SAME) {   // LDS operations of one wave execute in order: the gates written above are visible here
 #pragma unroll
             for (int vl = 0; vl < NVL; ++vl) {
-              const float g = gs[wave][c][vl * RV + rv];
+              const float g = gs[wave][c][vl * RV + rv];   // 0 for rows past the end (written as such above)
 #pragma unroll
               for (int e = 0; e < 8; ++e) acc[c][e] = fmaf(g, vf[vl][e], acc[c][e]);
             }
@@ -131,27 +142,62 @@ __global__ __launch_bounds__(256) void sta_stream_kernel(const unsigned short* _
         }
       }
     }
-  }
-
-  // sum over the row groups of the wave, then over the four waves (fixed order)
+  };
+  // segment done: sum over the row groups of the wave, then over the four waves (fixed order), and store
+  auto finish_segment = [&](int i) {
 #pragma unroll
-  for (int c = 0; c < CMAX; ++c) {
-    if (c < C) {
+    for (int c = 0; c < CMAX; ++c) {
+      if (c < C) {
 #pragma unroll
-      for (int off = LV; off < 64; off <<= 1)
+        for (int off = LV; off < 64; off <<= 1)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[c][e] += __shfl_xor(acc[c][e], off, 64);
-      if (rv == 0) {
+          for (int e = 0; e < 8; ++e) acc[c][e] += __shfl_xor(acc[c][e], off, 64);
+        if (rv == 0) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) red[wave][c][cv * 8 + e] = acc[c][e];
+          for (int e = 0; e < 8; ++e) red[wave][c][cv * 8 + e] = acc[c][e];
+        }
       }
     }
+    __syncthreads();
+    for (int e = tid; e < C * D; e += 256) {
+      const int c = e / D, col = e - c * D;
+      const float s = ((red[0][c][col] + red[1][c][col]) + red[2][c][col]) + red[3][c][col];
+      seg_out[(((size_t)u * C + c) * S + i) * D + col] = f32_to_bf16_bits(s);
+    }
+    __syncthreads();   // the reduction buffer is reused by the next segment
+  };
+
+  if (i_beg < i_ne) {
+    int ci = i_beg, cbase = i_beg * w, chi = seg_hi(i_beg);
+    Regs cur, nxt;
+    load_step(cbase, chi, cur);
+    clear_acc();
+    bool more = true;
+    while (more) {
+      int ni = ci, nbase = cbase + STRIDE, nhi = chi;
+      if (nbase >= chi) {
+        ni = ci + 1;
+        nbase = ni * w;
+        nhi = ni < i_ne ? seg_hi(ni) : 0;
+      }
+      more = ni < i_ne;
+      if (more) load_step(nbase, nhi, nxt);
+      compute_step(cbase, chi, cur);
+      if (ni != ci) {
+        finish_segment(ci);
+        clear_acc();
+      }
+      cur = nxt;
+      ci = ni;
+      cbase = nbase;
+      chi = nhi;
+    }
   }
-  __syncthreads();
-  for (int e = tid; e < C * D; e += 256) {
-    const int c = e / D, col = e - c * D;
-    const float s = ((red[0][c][col] + red[1][c][col]) + red[2][c][col]) + red[3][c][col];
-    seg_out[(((size_t)u * C + c) * S + i) * D + col] = f32_to_bf16_bits(s);
+  // empty segments of the run: exact zeros
+  for (int e = tid; e < (i_end - i_ne) * C * D; e += 256) {
+    const int ii = i_ne + e / (C * D), r2 = e % (C * D);
+    const int c = r2 / D, col = r2 - c * D;
+    seg_out[(((size_t)u * C + c) * S + ii) * D + col] = 0;
   }
 }
 
@@ -161,16 +207,26 @@ bool sta_stream_supports(const StaArgs& a) {
   if (a.C > 8) return false;
   if (!(a.d_q == 32 || a.d_q == 64 || a.d_q == 128)) return false;
   if (!(a.d == 64 || a.d == 128)) return false;
-  return (long long)a.U * a.S <= 0x7fffffffLL;
+  return (long long)a.U * a.S <= 0x7fffffffLL;   // an upper bound of the grid size
 }
 
 template <int DQ, int D>
 static void launch_c(const StaArgs& a, float nsl) {
-  const unsigned blocks = (unsigned)((long long)a.U * a.S);
+  // runs of segments per user: the whole user per workgroup once that still gives every compute unit eight
+  // workgroups, shorter runs when there are few users
+  int groups = (2048 + a.U - 1) / a.U;
+  if (groups > a.S) groups = a.S;
+  int spg = (a.S + groups - 1) / groups;
+  if (const char* e = getenv("LASER_STREAM_SPG")) {   // tuning override
+    const int vv = atoi(e);
+    if (vv >= 1 && vv <= a.S) spg = vv;
+  }
+  groups = (a.S + spg - 1) / spg;
+  const unsigned blocks = (unsigned)((long long)a.U * groups);
 #define LASER_STREAM_LAUNCH(CM)                                                                                      \
   hipLaunchKernelGGL((sta_stream_kernel<DQ, D, CM>), dim3(blocks), dim3(256), 0, a.stream,                         \
                      (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens,   \
-                     a.C, a.L, a.w, a.S, nsl, (unsigned short*)a.seg_out, a.seg_cnt)
+                     a.C, a.L, a.w, a.S, spg, groups, nsl, (unsigned short*)a.seg_out, a.seg_cnt)
   if (a.C <= 1) LASER_STREAM_LAUNCH(1);
   else if (a.C <= 2) LASER_STREAM_LAUNCH(2);
   else if (a.C <= 4) LASER_STREAM_LAUNCH(4);
