@@ -213,7 +213,16 @@ def main() -> int:
         roof = {"bound": "mfma", "achieved": sta_f / (sta_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
+    # HBM bytes per launch as counted by rocprofv3 (FETCH_SIZE / WRITE_SIZE, calibrated): taken from the committed
+    # summary of the profiling run of this same command, when it covers this workload and kernel; else null
     roof["traffic"] = None
+    prof = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"bench_{spec.name}.txt")
+    if os.path.exists(prof):
+        for line in open(prof):
+            f = line.split()
+            if len(f) == 3 and f[0] == "traffic_bytes_per_launch" and f[1] == sta_kernel:
+                roof["traffic"] = float(f[2])
+                roof["traffic_source"] = os.path.relpath(prof, os.path.dirname(os.path.abspath(__file__)))
     roof.update({"kernel": sta_kernel, "kernel_ms": sta_ms, "algorithmic_bytes": sta_b, "algorithmic_flops": sta_f,
                  "tflops": sta_f / (sta_ms * 1e-3) / 1e12, "gbps": sta_b / (sta_ms * 1e-3) / 1e9})
 

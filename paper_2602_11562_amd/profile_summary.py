@@ -15,8 +15,9 @@ import sys
 
 
 def _short(name: str) -> str:
-    for key in ("sta_mfma_pipe_kernel", "sta_mfma_kernel", "sta_stream_kernel", "sta_generic_kernel",
-                "gsta_tiled_kernel", "gsta_generic_kernel", "seg_cnt_kernel"):
+    for key in ("sta_mfma_dma_kernel", "sta_mfma_pipe_kernel", "sta_mfma_kernel", "sta_stream_kernel",
+                "sta_generic_kernel", "gsta_one_kernel", "gsta_r_kernel", "gsta_pool_kernel", "gsta_out_kernel",
+                "gsta_tiled_kernel", "gsta_generic_kernel"):
         if key in name:
             return key
     return name[:70]
