@@ -23,6 +23,7 @@
 // H' leaves through a wave-private LDS patch, 64 value columns at a time, so that global stores are whole
 // 128-byte row pieces instead of 8-byte fragments of 32 different rows.
 #include <cstdlib>
+#include <type_traits>
 
 #include "laser_internal.h"
 
@@ -558,6 +559,31 @@ __device__ __forceinline__ bf16x8 lds_read_tr(lds_bytes p) {
   return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
+// Instruction J (0..71) of the 16 gates of a lane, in dependency order per half of 8: scale (8), exp2 (8), 1 + (8),
+// reciprocal (8), round pairs to bf16 (4). The scores are transformed in place.
+template <int J>
+__device__ __forceinline__ void gate_step(f32x16& sc, bf16x8& p0, bf16x8& p1, float nsl) {
+  constexpr int half = J / 36, r = J % 36, stage = r / 8, e = r % 8, i = half * 8 + e;
+  if constexpr (stage == 0) sc[i] *= nsl;
+  else if constexpr (stage == 1) sc[i] = __builtin_amdgcn_exp2f(sc[i]);
+  else if constexpr (stage == 2) sc[i] += 1.0f;
+  else if constexpr (stage == 3) sc[i] = __builtin_amdgcn_rcpf(sc[i]);
+  else {
+    constexpr int a0 = half * 8 + 2 * e;
+    if constexpr (half == 0) { p0[2 * e] = (__bf16)sc[a0]; p0[2 * e + 1] = (__bf16)sc[a0 + 1]; }
+    else { p1[2 * e] = (__bf16)sc[a0]; p1[2 * e + 1] = (__bf16)sc[a0 + 1]; }
+  }
+}
+template <int J0>
+__device__ __forceinline__ void gate_steps6(f32x16& sc, bf16x8& p0, bf16x8& p1, float nsl) {
+  gate_step<J0>(sc, p0, p1, nsl);
+  gate_step<J0 + 1>(sc, p0, p1, nsl);
+  gate_step<J0 + 2>(sc, p0, p1, nsl);
+  gate_step<J0 + 3>(sc, p0, p1, nsl);
+  gate_step<J0 + 4>(sc, p0, p1, nsl);
+  gate_step<J0 + 5>(sc, p0, p1, nsl);
+}
+
 // Barrier without the fence of __syncthreads(): the compiler neither waits for the wave's outstanding LDS reads
 // (they are awaited where their registers are used) nor moves memory operations across it.
 __device__ __forceinline__ void bare_barrier() { asm volatile("s_barrier" ::: "memory"); }
@@ -701,14 +727,18 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
   unsigned char* oU = reinterpret_cast<unsigned char*>(seg_out) + ((size_t)u * C + cbase) * S * (D * 2);
   const bool all_rows = cbase + CW <= C;
   auto flush = [&](int seg) {
-    u32x4 val[CW / RPI];   // all reads first: one LDS latency per segment instead of one per row group
+    // reads in batches of four rows groups: one LDS latency per batch instead of one per row group
 #pragma unroll
-    for (int it = 0; it < CW / RPI; ++it) val[it] = *reinterpret_cast<const u32x4*>(opr + it * RPI * OP);
+    for (int b0 = 0; b0 < CW / RPI; b0 += 4) {
+      u32x4 val[4];
 #pragma unroll
-    for (int it = 0; it < CW / RPI; ++it) {
-      unsigned char* dst = oU + ((size_t)it * RPI * S + seg) * (D * 2);
-      if (all_rows || cbase + it * RPI + lane / LPR < C)
-        asm volatile("global_store_dwordx4 %0, %1, %2 nt" ::"v"(ooff), "v"(val[it]), "s"(dst) : "memory");
+      for (int it = 0; it < 4; ++it) val[it] = *reinterpret_cast<const u32x4*>(opr + (b0 + it) * RPI * OP);
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        unsigned char* dst = oU + ((size_t)(b0 + it) * RPI * S + seg) * (D * 2);
+        if (all_rows || cbase + (b0 + it) * RPI + lane / LPR < C)
+          asm volatile("global_store_dwordx4 %0, %1, %2 nt" ::"v"(ooff), "v"(val[it]), "s"(dst) : "memory");
+      }
     }
   };
 
@@ -800,46 +830,55 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
     }
     issue_next();
 
+    // One path for every tile, written in issue order with six vector-ALU instructions behind every MFMA (what a
+    // MFMA leaves room for): the eight score MFMAs of the next tile carry the gates of the first 16 items and a
+    // third of the second 16, the four aggregation MFMAs of the first 16 items carry the rest. Nothing may be
+    // moved across the slot borders. After the last tile the score MFMAs run on whatever the K registers hold and
+    // their result is dropped; in a partial tile the gates of the rows past the end (copies of the last valid
+    // row) are cleared after rounding.
     f32x16 sc_nxt;
-    bf16x8 p[2];
+    bf16x8 p0, p1;
     const int nvt = cur.hi - cur.t0;
-    if (has_next && nvt >= DT_TI) {
-      // steady state, one basic block: the score chain of the next tile with this tile's gates between its links
-      sc_nxt = scores();
+    const bool first = cur.t0 == cur.seg * w;
+    auto clear_past_end = [&](bf16x8& pp, int half) {
+      u32x4 bits = __builtin_bit_cast(u32x4, pp);
 #pragma unroll
-      for (int s = 0; s < 2; ++s)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) p[s][e] = (__bf16)gate(sc_cur[s * 8 + e], neg_scale_log2e);
-#pragma unroll
-      for (int i = 0; i < KSTEPS; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-        __builtin_amdgcn_sched_group_barrier(0x002, 9, 0);   // nine vector-ALU instructions
+      for (int e2 = 0; e2 < 4; ++e2) {
+        const int i0 = half * 16 + 8 * (e2 >> 1) + 4 * h + 2 * (e2 & 1);
+        bits[e2] &= (i0 < nvt ? 0x0000ffffu : 0u) | (i0 + 1 < nvt ? 0xffff0000u : 0u);
       }
-    } else {
-      if (has_next) sc_nxt = scores();
-      // partial tile: rows >= nvt are copies of the last valid row, their gates are zero
-#pragma unroll
-      for (int s = 0; s < 2; ++s)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int item = s * 16 + 8 * (e >> 2) + 4 * h + (e & 3);
-          p[s][e] = (__bf16)(item < nvt ? gate(sc_cur[s * 8 + e], neg_scale_log2e) : 0.0f);
-        }
-    }
-    if (has_next2) read_k(nbuf2);
-    if (cur.t0 == cur.seg * w) {   // first tile of a segment: start from an inline zero (no clearing pass)
+      pp = __builtin_bit_cast(bf16x8, bits);
+    };
+    {
       const f32x16 zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-      for (int db = 0; db < DB; ++db) acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[0][db], p[0], zero, 0, 0, 0);
-#pragma unroll
-      for (int db = 0; db < DB; ++db) acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[1][db], p[1], acc[db], 0, 0, 0);
-    } else {
-#pragma unroll
-      for (int s = 0; s < 2; ++s)
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-          acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[s][db], p[s], acc[db], 0, 0, 0);
+#define LASER_QK_SLOT(I)                                                                                             \
+  sc_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[I], qreg[I], I == 0 ? zero : sc_nxt, 0, 0, 0);                 \
+  __builtin_amdgcn_sched_barrier(0);                                                                                 \
+  gate_steps6<6 * (I)>(sc_cur, p0, p1, neg_scale_log2e);                                                             \
+  __builtin_amdgcn_sched_barrier(0);
+      LASER_QK_SLOT(0) LASER_QK_SLOT(1) LASER_QK_SLOT(2) LASER_QK_SLOT(3)
+      LASER_QK_SLOT(4) LASER_QK_SLOT(5)
+      if (nvt < DT_TI) clear_past_end(p0, 0);
+      LASER_QK_SLOT(6) LASER_QK_SLOT(7)
+#undef LASER_QK_SLOT
+#define LASER_PV_SLOT(I, CIN)                                                                                        \
+  acc[I] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[0][I], p0, CIN, 0, 0, 0);                                      \
+  __builtin_amdgcn_sched_barrier(0);                                                                                 \
+  gate_steps6<6 * (8 + (I))>(sc_cur, p0, p1, neg_scale_log2e);                                                       \
+  __builtin_amdgcn_sched_barrier(0);
+      if (first) {   // first tile of a segment: the sums start from an inline zero (no clearing pass, and the
+                     // accumulator registers are free between two segments)
+        LASER_PV_SLOT(0, zero) LASER_PV_SLOT(1, zero) LASER_PV_SLOT(2, zero) LASER_PV_SLOT(3, zero)
+      } else {
+        LASER_PV_SLOT(0, acc[0]) LASER_PV_SLOT(1, acc[1]) LASER_PV_SLOT(2, acc[2]) LASER_PV_SLOT(3, acc[3])
+      }
+#undef LASER_PV_SLOT
+      if (nvt < DT_TI) clear_past_end(p1, 1);
     }
+    // operand reads of later tiles are requested as soon as their registers are free
+    if (has_next2) read_k(nbuf2);
+#pragma unroll
+    for (int db = 0; db < DB; ++db) acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[1][db], p1, acc[db], 0, 0, 0);
     if (has_next) read_v(nbuf);
 
     if (nxt.seg != cur.seg) {   // segment finished: park H' rows in the patch
