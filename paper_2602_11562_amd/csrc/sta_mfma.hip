@@ -639,12 +639,33 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
       dma16(qU, (unsigned)c * ROWB + ((fpos ^ (row & 15)) << 4), qlds + j * 1024);
     }
   }
-  const int n = __builtin_amdgcn_readfirstlane(valid_len(lens, u, L));
-
   const unsigned char* kU = reinterpret_cast<const unsigned char*>(k + (size_t)u * L * DQ);
   const unsigned char* vU = reinterpret_cast<const unsigned char*>(v + (size_t)u * L * D);
-
   const int seg_lo = srun * spw;
+
+  // ---- fetch side: this wave moves rows 4 g .. 4 g + 3 of every tile, g = wave * IPW + j
+  unsigned fk[IPW], fv[IPW];   // per-lane byte offsets inside a full tile (row and swizzled chunk)
+#pragma unroll
+  for (int j = 0; j < IPW; ++j) {
+    const int row = (wave * IPW + j) * 4 + frow;
+    fk[j] = row * ROWB + ((fpos ^ (row & 15)) << 4);
+    fv[j] = row * ROWB + ((fpos ^ (4 * (row & 3))) << 4);
+  }
+  // The first tile of the run is requested before the valid length is known (the length is one more round trip
+  // to memory, and nothing can be computed before this tile has landed): its 32 rows exist whenever they lie
+  // inside the history, whatever they hold. If the length then says the tile is not a full one, the request is
+  // simply made again the regular way, into the same buffer; it lands after this one (loads retire in order).
+  const bool spec = seg_lo < S && w >= DT_TI && seg_lo * w + DT_TI <= L;
+  if (spec) {
+#pragma unroll
+    for (int j = 0; j < IPW; ++j) {
+      const int g = wave * IPW + j;
+      dma16(kU + (size_t)seg_lo * w * ROWB, fk[j], lds_base + g * 1024);
+      dma16(vU + (size_t)seg_lo * w * ROWB, fv[j], lds_base + KB + g * 1024);
+    }
+  }
+  const int n = __builtin_amdgcn_readfirstlane(valid_len(lens, u, L));
+
   const int seg_hi = (seg_lo + spw) < S ? (seg_lo + spw) : S;
   int seg_ne = seg_lo;
   while (seg_ne < seg_hi && seg_ne * w < n) ++seg_ne;
@@ -655,14 +676,6 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
     return e;
   };
 
-  // ---- fetch side: this wave moves rows 4 g .. 4 g + 3 of every tile, g = wave * IPW + j
-  unsigned fk[IPW], fv[IPW];   // per-lane byte offsets inside a full tile (row and swizzled chunk)
-#pragma unroll
-  for (int j = 0; j < IPW; ++j) {
-    const int row = (wave * IPW + j) * 4 + frow;
-    fk[j] = row * ROWB + ((fpos ^ (row & 15)) << 4);
-    fv[j] = row * ROWB + ((fpos ^ (4 * (row & 3))) << 4);
-  }
   auto issue_tile = [&](int t0, int hi, int buf) {   // requires t0 < hi
     const unsigned char* kT = kU + (size_t)t0 * ROWB;
     const unsigned char* vT = vU + (size_t)t0 * ROWB;
@@ -763,11 +776,16 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
     wait_vm(OPT * (beyond > 0 ? beyond : 0));
   };
   if (any) {
+    if (spec && fet.hi - fet.t0 >= DT_TI) {   // the early request was the right one: count it
+      fet = advance(fet);
+      fetched = 1;
+      fbuf = 1;
+    }
 #pragma unroll 1
-    for (int a = 0; a < DT_AHEAD; ++a) issue_next();
+    for (int a = fetched; a < DT_AHEAD; ++a) issue_next();
   }
   if (srun == 0 && ct == 0) write_seg_cnt(seg_cnt, u, n, L, w, S, tid, NT);
-  wait_tile(0);   // and the queries, which are older (with no tile requested this waits for everything)
+  wait_tile(1);   // tiles 0 and 1, and the queries, which are older (with nothing requested: everything)
   __syncthreads();
 
   bf16x8 qreg[KSTEPS], ka[KSTEPS], va[2][DB];
@@ -811,8 +829,6 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
   };
   f32x16 sc_cur;
   if (any) {
-    wait_tile(1);
-    __syncthreads();
     sc_cur = scores();
     if (advance(cur).seg < seg_ne) read_k(1);
   }

@@ -144,6 +144,10 @@ EDGE_SPECS = {
     "dq_differs_from_d": _spec("bf16", 2, 64, 512, 128, 64, 128, 1, 2007),
     "small_dims": _spec("f32", 2, 3, 50, 8, 8, 7, 3, 2008),
     "three_layers_long_tail": _spec("bf16", 3, 33, 1300, 64, 64, 256, 3, 2009),
+    # more than 128 candidates with d_q = d = 128: the direct-to-LDS STA kernel, on ragged histories
+    "many_candidates_ragged": _spec("bf16", 5, 200, 1000, 128, 128, 100, 1, 2011),   # w not a multiple of the tile
+    "many_candidates_small_w": _spec("bf16", 2, 130, 300, 128, 128, 10, 1, 2012),    # segments shorter than a tile
+    "many_candidates_two_tiles": _spec("bf16", 3, 257, 512, 128, 128, 128, 1, 2013),  # two candidate tiles per user
 }
 
 EDGE_LENS = {
@@ -151,6 +155,9 @@ EDGE_LENS = {
     "three_layers_long_tail": [1299, 257, 0],
     "odd_candidate_count": [640, 129],
     "small_dims": [50, 13],
+    "many_candidates_ragged": [1000, 333, 0, 37, 32],
+    "many_candidates_small_w": [300, 95],
+    "many_candidates_two_tiles": [512, 1, 200],
 }
 
 
@@ -162,9 +169,13 @@ def test_edge_cases(name, sta_variant):
     wl = make_workload(spec)
     if name in EDGE_LENS:
         wl.lens = np.array(EDGE_LENS[name], dtype=np.int32)
-    dw = DeviceWorkload(wl)
     print(f"edge {name} sta variant {sta_variant} spec {spec} lens {wl.lens.tolist()}", flush=True)
     Hp_ref, cnt_ref, z_ref = oracle_batch(wl)
+    if spec.dtype == "bf16":   # the checker has its expected values: now poison what must never be read
+        for r, n in enumerate(wl.lens):
+            wl.k[r, n:] = np.uint16(0x7FC0)
+            wl.v[r, n:] = np.uint16(0x7FC0)
+    dw = DeviceWorkload(wl)
     seg, cnt = _run_sta(dw, STA_VARIANTS[sta_variant])
     z = _run_gsta(dw, seg, 0)
     torch.cuda.synchronize()
