@@ -134,6 +134,7 @@ laser_status laser_forward(const void* q, const void* k, const void* v, const vo
   if (s != LASER_OK) return s;
   s = validate_gsta(seg_out, t0, wq, wk, wv, lens, U, C, L, d, w, M, dt, z_out, stream, &ga);
   if (s != LASER_OK) return s;   // both validated before the first launch
+  sa.reread = true;   // GSTA streams H' next: leave it where the last-level cache can keep it
   s = run_sta(sa, LASER_STA_AUTO);
   if (s != LASER_OK) return s;
   return run_gsta(ga, LASER_GSTA_AUTO);

@@ -20,6 +20,7 @@ struct StaArgs {
   void* seg_out;
   int32_t* seg_cnt;   // may be nullptr
   hipStream_t stream;
+  bool reread;        // H' is read again right after this launch (the whole path): store it cacheable
 };
 
 struct GstaArgs {

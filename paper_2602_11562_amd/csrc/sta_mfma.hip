@@ -515,7 +515,8 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_pipe_kernel(const unsigned s
 //    outstanding at the next use of a register it cannot prove idle); completion is awaited explicitly with
 //    s_waitcnt vmcnt(n), n = the number of younger fetches allowed to stay outstanding. Operand reads from LDS
 //    are ordinary loads whose waits the compiler places itself;
-//  * H' rows leave with the non-temporal hint: they are not read again by this kernel.
+//  * H' rows leave with the non-temporal hint when the launch stands alone, and cacheable when the caller is the
+//    whole path, whose next launch streams them back (measured: about 3 us of the step).
 constexpr int DT_TI = 32, DT_NBUF = 5, DT_AHEAD = 4;
 
 // 16 bytes per lane from global (uniform base + per-lane byte offset) to LDS (uniform address + 16 * lane)
@@ -594,7 +595,7 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
                                                                const unsigned short* __restrict__ v,
                                                                const int32_t* __restrict__ lens, int C, int L, int w,
                                                                int S, int spw, int ctiles, int sruns,
-                                                               float neg_scale_log2e,
+                                                               int nt_store, float neg_scale_log2e,
                                                                unsigned short* __restrict__ seg_out,
                                                                int32_t* __restrict__ seg_cnt) {
   constexpr int DQ = 128, D = 128, KSTEPS = DQ / 16, DB = D / 32;
@@ -749,8 +750,11 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
 #pragma unroll
       for (int it = 0; it < 4; ++it) {
         unsigned char* dst = oU + ((size_t)(b0 + it) * RPI * S + seg) * (D * 2);
-        if (all_rows || cbase + (b0 + it) * RPI + lane / LPR < C)
-          asm volatile("global_store_dwordx4 %0, %1, %2 nt" ::"v"(ooff), "v"(val[it]), "s"(dst) : "memory");
+        if (all_rows || cbase + (b0 + it) * RPI + lane / LPR < C) {
+          // non-temporal when nobody reads H' soon; cacheable when the next launch streams it (the whole path)
+          if (nt_store) asm volatile("global_store_dwordx4 %0, %1, %2 nt" ::"v"(ooff), "v"(val[it]), "s"(dst) : "memory");
+          else asm volatile("global_store_dwordx4 %0, %1, %2" ::"v"(ooff), "v"(val[it]), "s"(dst) : "memory");
+        }
       }
     }
   };
@@ -959,7 +963,7 @@ static void launch_nw(const StaArgs& a, int nw, int spw, int ctiles, int sruns, 
     const unsigned blocks = (unsigned)((long long)a.U * ctiles * sruns);
     hipLaunchKernelGGL((sta_mfma_dma_kernel<8>), dim3(blocks), dim3(512), 0, a.stream, (const unsigned short*)a.q,
                        (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens, a.C, a.L, a.w, a.S, spw,
-                       ctiles, sruns, nsl, (unsigned short*)a.seg_out, a.seg_cnt);
+                       ctiles, sruns, a.reread ? 0 : 1, nsl, (unsigned short*)a.seg_out, a.seg_cnt);
   } else if (nw == 8) {
     const unsigned blocks = (unsigned)((long long)a.U * ctiles * sruns);
     hipLaunchKernelGGL((sta_mfma_pipe_kernel<DQ, D, 8>), dim3(blocks), dim3(512), 0, a.stream,
