@@ -166,7 +166,8 @@ __global__ __launch_bounds__(GT_THREADS) void gsta_tiled_kernel(const unsigned s
   __shared__ __attribute__((aligned(16))) float bufB[GT_ROWS * FP];
   __shared__ __attribute__((aligned(16))) unsigned char Wl[D * WP];
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: the valid lengths become scalar loads
   const int l32 = lane & 31, h = lane >> 5;
   const int pbase = blockIdx.x * PT;
   const float scale = 1.0f / sqrtf((float)D);
@@ -479,7 +480,8 @@ __global__ __launch_bounds__(GS_THREADS) void gsta_pool_kernel(const unsigned sh
                                                                const int32_t* __restrict__ lens, int P, int C, int L,
                                                                int w, int S, float* __restrict__ z) {
   constexpr int LPR = D / 8, RPW = 64 / LPR;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: the valid length is a scalar load
   const int pr = blockIdx.x * (GS_THREADS / 64) + wave;
   if (pr >= P) return;
   const int grp = lane / LPR, gl = lane % LPR;

@@ -834,7 +834,7 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
   f32x16 sc_cur;
   if (any) {
     sc_cur = scores();
-    if (advance(cur).seg < seg_ne) read_k(1);
+    read_k(1);
   }
   while (cur.seg < seg_ne) {
     const Cur nxt = advance(cur);
@@ -844,10 +844,6 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
     const int nbuf2 = nbuf + 1 == DT_NBUF ? 0 : nbuf + 1;
     wait_tile(done + 2);
     bare_barrier();
-    if (out_seg >= 0) {   // right after the wait: the stores have a whole step to complete before the next one
-      flush(out_seg);
-      out_seg = -1;
-    }
     issue_next();
 
     // One path for every tile, written in issue order with six vector-ALU instructions behind every MFMA (what a
@@ -881,6 +877,13 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
       if (nvt < DT_TI) clear_past_end(p0, 0);
       LASER_QK_SLOT(6) LASER_QK_SLOT(7)
 #undef LASER_QK_SLOT
+      // The finished segment's rows leave here rather than right after the barrier: the patch reads and their
+      // waits sit behind a branch, and ahead of the score MFMAs they made the compiler wait for every operand
+      // read in flight. The stores still have most of a step to complete before the next fetch wait.
+      if (out_seg >= 0) {
+        flush(out_seg);
+        out_seg = -1;
+      }
 #define LASER_PV_SLOT(I, CIN)                                                                                        \
   acc[I] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[0][I], p0, CIN, 0, 0, 0);                                      \
   __builtin_amdgcn_sched_barrier(0);                                                                                 \
@@ -895,11 +898,14 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
 #undef LASER_PV_SLOT
       if (nvt < DT_TI) clear_past_end(p1, 1);
     }
-    // operand reads of later tiles are requested as soon as their registers are free
-    if (has_next2) read_k(nbuf2);
+    // Operand reads of later tiles are requested as soon as their registers are free, unconditionally: with no
+    // branch around them the compiler counts the outstanding reads exactly and waits only for the ones an
+    // instruction needs (with a branch it falls back to waiting for all of them at the top of every step, which
+    // exposes the latency of the V reads issued just before). Without such a tile they read stale LDS, unused.
+    read_k(nbuf2);
 #pragma unroll
     for (int db = 0; db < DB; ++db) acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[1][db], p1, acc[db], 0, 0, 0);
-    if (has_next) read_v(nbuf);
+    read_v(nbuf);
 
     if (nxt.seg != cur.seg) {   // segment finished: park H' rows in the patch
 #pragma unroll
