@@ -31,6 +31,7 @@ namespace laser {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -589,13 +590,15 @@ __device__ __forceinline__ void gate_steps6(f32x16& sc, bf16x8& p0, bf16x8& p1, 
 // (they are awaited where their registers are used) nor moves memory operations across it.
 __device__ __forceinline__ void bare_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
-template <int NW>
+// NT: H' rows leave with the non-temporal hint (nobody reads them soon) or cacheable (the whole path: the next
+// launch streams them back)
+template <int NW, bool NTS>
 __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned short* __restrict__ q,
                                                                const unsigned short* __restrict__ k,
                                                                const unsigned short* __restrict__ v,
                                                                const int32_t* __restrict__ lens, int C, int L, int w,
                                                                int S, int spw, int ctiles, int sruns,
-                                                               int nt_store, float neg_scale_log2e,
+                                                               float neg_scale_log2e,
                                                                unsigned short* __restrict__ seg_out,
                                                                int32_t* __restrict__ seg_cnt) {
   constexpr int DQ = 128, D = 128, KSTEPS = DQ / 16, DB = D / 32;
@@ -738,24 +741,37 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
   constexpr int LPR = D / 8, RPI = 64 / LPR;
   const unsigned char* opr = opatch + (lane / LPR) * OP + (lane % LPR) * 16;
   const unsigned ooff = (unsigned)(lane / LPR) * (unsigned)S * (D * 2) + (lane % LPR) * 16;
+  const unsigned ooff2 = ooff + (unsigned)RPI * (unsigned)S * (D * 2);   // the unit's second row group
   unsigned char* oU = reinterpret_cast<unsigned char*>(seg_out) + ((size_t)u * C + cbase) * S * (D * 2);
   const bool all_rows = cbase + CW <= C;
-  auto flush = [&](int seg) {
-    // reads in batches of four rows groups: one LDS latency per batch instead of one per row group
-#pragma unroll
-    for (int b0 = 0; b0 < CW / RPI; b0 += 4) {
-      u32x4 val[4];
-#pragma unroll
-      for (int it = 0; it < 4; ++it) val[it] = *reinterpret_cast<const u32x4*>(opr + (b0 + it) * RPI * OP);
-#pragma unroll
-      for (int it = 0; it < 4; ++it) {
-        unsigned char* dst = oU + ((size_t)(b0 + it) * RPI * S + seg) * (D * 2);
-        if (all_rows || cbase + (b0 + it) * RPI + lane / LPR < C) {
-          // non-temporal when nobody reads H' soon; cacheable when the next launch streams it (the whole path)
-          if (nt_store) asm volatile("global_store_dwordx4 %0, %1, %2 nt" ::"v"(ooff), "v"(val[it]), "s"(dst) : "memory");
-          else asm volatile("global_store_dwordx4 %0, %1, %2" ::"v"(ooff), "v"(val[it]), "s"(dst) : "memory");
-        }
+  // A finished segment leaves in FU units of two row groups (eight rows, 2 KB per wave), a few per step: all
+  // waves of a compute unit storing whole patches in the same step saturate its store path for most of a step
+  // while it idles in the others. flush_units(seg, from, n) stores units from .. from+n-1.
+  constexpr int FU = CW / RPI / 2;
+  const size_t unit_stride = (size_t)2 * RPI * S * (D * 2);   // bytes between the first rows of two units in H'
+  auto flush_units = [&](int seg, int from, int n) {
+    // scalar work per unit is kept to two 64-bit additions: a wave issues one instruction every few cycles,
+    // whatever its kind, and the other wave of the SIMD is at the same point of the same step
+    unsigned char* dst = oU + (size_t)seg * (D * 2) + (size_t)from * unit_stride;
+    const unsigned char* src = opr + from * (2 * RPI * OP);
+    int row = cbase + from * (2 * RPI) + lane / LPR;
+#pragma unroll 1
+    for (int b = 0; b < n; ++b) {
+      const u32x4 v0 = *reinterpret_cast<const u32x4*>(src);
+      const u32x4 v1 = *reinterpret_cast<const u32x4*>(src + RPI * OP);
+      if (all_rows || row < C) {
+        // (the s_nop: a store of more than 8 bytes reads its data registers for two more cycles after issue; the
+        // compiler pads its own stores against a following register write, but cannot see into this one)
+        if (NTS) asm volatile("global_store_dwordx4 %0, %1, %2 nt\n\ts_nop 1" ::"v"(ooff), "v"(v0), "s"(dst) : "memory");
+        else asm volatile("global_store_dwordx4 %0, %1, %2\n\ts_nop 1" ::"v"(ooff), "v"(v0), "s"(dst) : "memory");
       }
+      if (all_rows || row + RPI < C) {
+        if (NTS) asm volatile("global_store_dwordx4 %0, %1, %2 nt\n\ts_nop 1" ::"v"(ooff2), "v"(v1), "s"(dst) : "memory");
+        else asm volatile("global_store_dwordx4 %0, %1, %2\n\ts_nop 1" ::"v"(ooff2), "v"(v1), "s"(dst) : "memory");
+      }
+      dst += unit_stride;
+      src += 2 * RPI * OP;
+      row += 2 * RPI;
     }
   };
 
@@ -811,9 +827,8 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) qreg[ks] = lds_read16(lds_at(kofs[ks] + qlds));
     read_k(0);
-    read_v(0);
   }
-  int out_seg = -1;
+  int out_seg = -1, out_units = 0;   // segment parked in the patch (-1: none) and how much of it has left
 
   // One step per tile, one barrier per step, software-pipelined inside the wave so that the matrix pipe always
   // has work while the vector ALU evaluates gates:
@@ -832,9 +847,20 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
     return sc;
   };
   f32x16 sc_cur;
+  u32x4 p0, p1;   // gates of items 0..15 / 16..31 of the current tile, rounded to bf16 pairs: B operands of the
+                  // aggregation
   if (any) {
     sc_cur = scores();
     read_k(1);
+    // gates of items 0..15 of the first tile, up to the rounding of the last pair (done by the first slot of
+    // the loop, as for every later tile)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sc_cur[i] = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(sc_cur[i] * neg_scale_log2e));
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+      const bf16x2 c = {(__bf16)sc_cur[2 * j], (__bf16)sc_cur[2 * j + 1]};
+      p0[j] = __builtin_bit_cast(unsigned, c);
+    }
   }
   while (cur.seg < seg_ne) {
     const Cur nxt = advance(cur);
@@ -842,70 +868,106 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
     const bool has_next2 = has_next && advance(nxt).seg < seg_ne;
     const int nbuf = cbuf + 1 == DT_NBUF ? 0 : cbuf + 1;
     const int nbuf2 = nbuf + 1 == DT_NBUF ? 0 : nbuf + 1;
-    wait_tile(done + 2);
+    // tile done+2 has landed: at this point fetched <= done + 4, so at most one younger tile stays outstanding
+    if (fetched - done >= 4) __builtin_amdgcn_s_waitcnt(vmcnt_imm(OPT));
+    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     bare_barrier();
-    issue_next();
+    if (wave < NW / 2) issue_next();
 
-    // One path for every tile, written in issue order with six vector-ALU instructions behind every MFMA (what a
-    // MFMA leaves room for): the eight score MFMAs of the next tile carry the gates of the first 16 items and a
-    // third of the second 16, the four aggregation MFMAs of the first 16 items carry the rest. Nothing may be
-    // moved across the slot borders. After the last tile the score MFMAs run on whatever the K registers hold and
-    // their result is dropped; in a partial tile the gates of the rows past the end (copies of the last valid
-    // row) are cleared after rounding.
+    // One path for every tile, written in issue order. A step issues 16 MFMAs per wave: the eight score MFMAs of
+    // the next tile (A0..A7), then the eight aggregation MFMAs of this tile (B0..B7). The 72 gate instructions of
+    // a tile (per lane: 16 x scale, exp2, +1, reciprocal; 8 x round a pair to bf16) are spread over 16 MFMAs so
+    // that each MFMA hides four or five of them and at most two of the slow exp2/reciprocal ones (measured: a
+    // MFMA hides 2 slow + 2..3 plain VALU instructions of the two waves of its SIMD completely, more than that
+    // extends the slot): the gates of items 0..15 of tile t+1 ride behind B1..B7 of step t (their scores exist
+    // since A7), those of items 16..31 of tile t behind A0..A7 of step t. Consumers sit at least one slot behind
+    // an exp2 or reciprocal. Nothing may be moved across the slot borders. After the last tile the score MFMAs run
+    // on whatever the K registers hold and their result is dropped; in a partial tile the gates of the rows past
+    // the end (copies of the last valid row) are cleared after rounding.
     f32x16 sc_nxt;
-    bf16x8 p0, p1;
     const int nvt = cur.hi - cur.t0;
     const bool first = cur.t0 == cur.seg * w;
-    auto clear_past_end = [&](bf16x8& pp, int half) {
-      u32x4 bits = __builtin_bit_cast(u32x4, pp);
+    auto clear_past_end = [&](u32x4& bits, int half) {
 #pragma unroll
       for (int e2 = 0; e2 < 4; ++e2) {
         const int i0 = half * 16 + 8 * (e2 >> 1) + 4 * h + 2 * (e2 & 1);
         bits[e2] &= (i0 < nvt ? 0x0000ffffu : 0u) | (i0 + 1 < nvt ? 0xffff0000u : 0u);
       }
-      pp = __builtin_bit_cast(bf16x8, bits);
     };
     {
       const f32x16 zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
-#define LASER_QK_SLOT(I)                                                                                             \
-  sc_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[I], qreg[I], I == 0 ? zero : sc_nxt, 0, 0, 0);                 \
+// every gate instruction is followed by an empty asm that takes its result: the compiler otherwise sinks the
+// arithmetic towards its use in a later block and undoes the placement
+#define LASER_PIN(X) asm volatile("" : "+v"(X));
+#define GM(S, I) { float t_ = S[I] * neg_scale_log2e; LASER_PIN(t_) S[I] = t_; }
+#define GE(S, I) { float t_ = __builtin_amdgcn_exp2f(S[I]); LASER_PIN(t_) S[I] = t_; }
+#define GA(S, I) { float t_ = S[I] + 1.0f; LASER_PIN(t_) S[I] = t_; }
+#define GR(S, I) { float t_ = __builtin_amdgcn_rcpf(S[I]); LASER_PIN(t_) S[I] = t_; }
+#define GC(P, J, S, I) { bf16x2 c_ = {(__bf16)S[I], (__bf16)S[(I) + 1]}; unsigned t_ = __builtin_bit_cast(unsigned, c_); LASER_PIN(t_) P[J] = t_; }
+#define LASER_SLOT(MFMA, OPS)                                                                                        \
+  MFMA;                                                                                                              \
   __builtin_amdgcn_sched_barrier(0);                                                                                 \
-  gate_steps6<6 * (I)>(sc_cur, p0, p1, neg_scale_log2e);                                                             \
+  OPS                                                                                                                \
   __builtin_amdgcn_sched_barrier(0);
-      LASER_QK_SLOT(0) LASER_QK_SLOT(1) LASER_QK_SLOT(2) LASER_QK_SLOT(3)
-      LASER_QK_SLOT(4) LASER_QK_SLOT(5)
+#define LASER_QK(I) sc_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[I], qreg[I], I == 0 ? zero : sc_nxt, 0, 0, 0)
+      LASER_SLOT(LASER_QK(0), GC(p0, 3, sc_cur, 6) GM(sc_cur, 8) GM(sc_cur, 9) GM(sc_cur, 10) GM(sc_cur, 11) GE(sc_cur, 8) GE(sc_cur, 9))
       if (nvt < DT_TI) clear_past_end(p0, 0);
-      LASER_QK_SLOT(6) LASER_QK_SLOT(7)
-#undef LASER_QK_SLOT
+      LASER_SLOT(LASER_QK(1), GA(sc_cur, 8) GA(sc_cur, 9) GM(sc_cur, 12) GM(sc_cur, 13) GE(sc_cur, 10) GE(sc_cur, 11))
+      // V of this tile, for the second half of this step. (Requested at the end of the previous step these reads
+      // were the youngest in flight at the top of the step, and the LDS wait counter, which counts in order and
+      // no further than 15, made every score MFMA wait for most of them.)
+      read_v(cbuf);
+      LASER_SLOT(LASER_QK(2), GA(sc_cur, 10) GA(sc_cur, 11) GR(sc_cur, 8) GR(sc_cur, 9))
+      LASER_SLOT(LASER_QK(3), GM(sc_cur, 14) GM(sc_cur, 15) GC(p1, 0, sc_cur, 8) GE(sc_cur, 12) GE(sc_cur, 13))
+      LASER_SLOT(LASER_QK(4), GA(sc_cur, 12) GA(sc_cur, 13) GR(sc_cur, 10) GR(sc_cur, 11))
+      LASER_SLOT(LASER_QK(5), GC(p1, 1, sc_cur, 10) GE(sc_cur, 14) GE(sc_cur, 15))
+      LASER_SLOT(LASER_QK(6), GA(sc_cur, 14) GA(sc_cur, 15) GR(sc_cur, 12) GR(sc_cur, 13))
+      LASER_SLOT(LASER_QK(7), GC(p1, 2, sc_cur, 12) GR(sc_cur, 14) GR(sc_cur, 15))
+#undef LASER_QK
       // The finished segment's rows leave here rather than right after the barrier: the patch reads and their
       // waits sit behind a branch, and ahead of the score MFMAs they made the compiler wait for every operand
       // read in flight. The stores still have most of a step to complete before the next fetch wait.
-      if (out_seg >= 0) {
-        flush(out_seg);
-        out_seg = -1;
+      if (out_seg >= 0) {   // an equal share in every step that is left before the patch is needed again
+        const int steps_left = (nvt + DT_TI - 1) / DT_TI;
+        const int left = FU - out_units;   // n = ceil(left / steps_left), left <= FU = 4, without a division
+        static_assert(FU == 4, "the share below is written out for four units");
+        const int n = steps_left >= left ? 1 : (steps_left == 1 ? left : 2);
+        flush_units(out_seg, out_units, n);
+        out_units += n;
+        if (out_units == FU) out_seg = -1;
       }
-#define LASER_PV_SLOT(I, CIN)                                                                                        \
-  acc[I] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[0][I], p0, CIN, 0, 0, 0);                                      \
-  __builtin_amdgcn_sched_barrier(0);                                                                                 \
-  gate_steps6<6 * (8 + (I))>(sc_cur, p0, p1, neg_scale_log2e);                                                       \
-  __builtin_amdgcn_sched_barrier(0);
-      if (first) {   // first tile of a segment: the sums start from an inline zero (no clearing pass, and the
-                     // accumulator registers are free between two segments)
-        LASER_PV_SLOT(0, zero) LASER_PV_SLOT(1, zero) LASER_PV_SLOT(2, zero) LASER_PV_SLOT(3, zero)
-      } else {
-        LASER_PV_SLOT(0, acc[0]) LASER_PV_SLOT(1, acc[1]) LASER_PV_SLOT(2, acc[2]) LASER_PV_SLOT(3, acc[3])
-      }
-#undef LASER_PV_SLOT
-      if (nvt < DT_TI) clear_past_end(p1, 1);
-    }
-    // Operand reads of later tiles are requested as soon as their registers are free, unconditionally: with no
-    // branch around them the compiler counts the outstanding reads exactly and waits only for the ones an
-    // instruction needs (with a branch it falls back to waiting for all of them at the top of every step, which
-    // exposes the latency of the V reads issued just before). Without such a tile they read stale LDS, unused.
-    read_k(nbuf2);
+      if (first) {   // first tile of a segment: the sums restart (in a branch of its own: two copies of the slots
+                     // below, one starting from an inline zero, made the compiler shuffle registers at the join)
 #pragma unroll
-    for (int db = 0; db < DB; ++db) acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[1][db], p1, acc[db], 0, 0, 0);
-    read_v(nbuf);
+        for (int db = 0; db < DB; ++db) acc[db] = zero;
+      }
+#define LASER_PV0(I) acc[I] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[0][I], __builtin_bit_cast(bf16x8, p0), acc[I], 0, 0, 0)
+      LASER_SLOT(LASER_PV0(0), GC(p1, 3, sc_cur, 14))
+      LASER_SLOT(LASER_PV0(1), GM(sc_nxt, 0) GM(sc_nxt, 1) GM(sc_nxt, 2) GM(sc_nxt, 3) GE(sc_nxt, 0) GE(sc_nxt, 1))
+      LASER_SLOT(LASER_PV0(2), GA(sc_nxt, 0) GA(sc_nxt, 1) GM(sc_nxt, 4) GM(sc_nxt, 5) GE(sc_nxt, 2) GE(sc_nxt, 3))
+      LASER_SLOT(LASER_PV0(3), GA(sc_nxt, 2) GA(sc_nxt, 3) GM(sc_nxt, 6) GM(sc_nxt, 7) GR(sc_nxt, 0) GR(sc_nxt, 1))
+#undef LASER_PV0
+      if (nvt < DT_TI) clear_past_end(p1, 1);
+      // Operand reads of later tiles are requested as soon as their registers are free, unconditionally: with no
+      // branch around them the compiler counts the outstanding reads exactly and waits only for the ones an
+      // instruction needs (with a branch it falls back to waiting for all of them at the top of every step, which
+      // exposes the latency of the V reads issued just before). Without such a tile they read stale LDS, unused.
+      read_k(nbuf2);
+#define LASER_PV1(I) acc[I] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[1][I], __builtin_bit_cast(bf16x8, p1), acc[I], 0, 0, 0)
+      // p0 is rewritten for the next tile from here on: its last reader was B3
+      LASER_SLOT(LASER_PV1(0), GC(p0, 0, sc_nxt, 0) GE(sc_nxt, 4) GE(sc_nxt, 5) GR(sc_nxt, 2) GR(sc_nxt, 3))
+      LASER_SLOT(LASER_PV1(1), GA(sc_nxt, 4) GA(sc_nxt, 5) GC(p0, 1, sc_nxt, 2) GE(sc_nxt, 6) GE(sc_nxt, 7))
+      LASER_SLOT(LASER_PV1(2), GA(sc_nxt, 6) GA(sc_nxt, 7) GR(sc_nxt, 4) GR(sc_nxt, 5))
+      LASER_SLOT(LASER_PV1(3), GC(p0, 2, sc_nxt, 4) GR(sc_nxt, 6) GR(sc_nxt, 7))
+#undef LASER_PV1
+#undef LASER_SLOT
+#undef LASER_PIN
+#undef GM
+#undef GE
+#undef GA
+#undef GR
+#undef GC
+    }
 
     if (nxt.seg != cur.seg) {   // segment finished: park H' rows in the patch
 #pragma unroll
@@ -918,13 +980,15 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
           *reinterpret_cast<u32x2*>(opatch + l32 * OP + (db * 32 + g * 8 + h * 4) * 2) = __builtin_bit_cast(u32x2, o);
         }
       out_seg = cur.seg;
+      out_units = 0;
     }
+    if (wave >= NW / 2) issue_next();
     ++done;
     cbuf = nbuf;
     cur = nxt;
     if (has_next) sc_cur = sc_nxt;
   }
-  if (out_seg >= 0) flush(out_seg);
+  if (out_seg >= 0) flush_units(out_seg, out_units, FU - out_units);
 
   if (seg_ne < seg_hi) {   // empty segments of the run: exact zeros
     const int ncand = (C - ct * (CW * NW)) < CW * NW ? (C - ct * (CW * NW)) : CW * NW;
@@ -967,9 +1031,14 @@ static void launch_nw(const StaArgs& a, int nw, int spw, int ctiles, int sruns, 
   // smaller workgroups overlap memory and MFMA work across the several workgroups that share a compute unit
   if (nw == 8 && DQ == 128 && D == 128 && getenv("LASER_STA_NODMA") == nullptr) {
     const unsigned blocks = (unsigned)((long long)a.U * ctiles * sruns);
-    hipLaunchKernelGGL((sta_mfma_dma_kernel<8>), dim3(blocks), dim3(512), 0, a.stream, (const unsigned short*)a.q,
-                       (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens, a.C, a.L, a.w, a.S, spw,
-                       ctiles, sruns, a.reread ? 0 : 1, nsl, (unsigned short*)a.seg_out, a.seg_cnt);
+    if (a.reread)
+      hipLaunchKernelGGL((sta_mfma_dma_kernel<8, false>), dim3(blocks), dim3(512), 0, a.stream,
+                         (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens,
+                         a.C, a.L, a.w, a.S, spw, ctiles, sruns, nsl, (unsigned short*)a.seg_out, a.seg_cnt);
+    else
+      hipLaunchKernelGGL((sta_mfma_dma_kernel<8, true>), dim3(blocks), dim3(512), 0, a.stream,
+                         (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens,
+                         a.C, a.L, a.w, a.S, spw, ctiles, sruns, nsl, (unsigned short*)a.seg_out, a.seg_cnt);
   } else if (nw == 8) {
     const unsigned blocks = (unsigned)((long long)a.U * ctiles * sruns);
     hipLaunchKernelGGL((sta_mfma_pipe_kernel<DQ, D, 8>), dim3(blocks), dim3(512), 0, a.stream,
