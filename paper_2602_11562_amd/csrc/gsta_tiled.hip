@@ -549,13 +549,13 @@ __global__ __launch_bounds__(GS_THREADS) void gsta_pool_kernel(const unsigned sh
 }
 
 // ------------------------------------------------------------------------------------------ one-kernel form (M = 1)
-// The three steps of the split form in one launch, for a tile of 32 pairs per workgroup (8 waves, 4 pairs each),
+// The three steps of the split form in one launch, for a tile of 32 pairs per workgroup (8 waves, 5 or 3 pairs each),
 // so that the layer costs one launch and about one round trip to memory plus the H' stream:
 //   * the lower four waves request the three weight matrices and the t0 tile (coalesced 16-byte pieces, a few
 //     registers per lane) and park them in LDS, each matrix in the layout its MFMA operand read wants: W_q and
 //     W_v (contraction index = row) padded for the transpose load, W_k (contraction index = column) padded for
 //     16-byte row reads; waves 0 .. d/32-1 then run q' = t0 W_q and r = q' W_k^T / sqrt(d) from LDS;
-//   * every wave reads the H' blocks of its four pairs into registers (all S rows, unconditionally: rows of empty
+//   * every wave reads the H' blocks of its pairs into registers (all S rows, unconditionally: rows of empty
 //     segments are replaced by zeros when they are used, so nothing waits for the valid lengths); when each wave
 //     asks for them is explained in the kernel;
 //   * each wave reduces its pairs from registers (scores, softmax, weighted sum);
@@ -581,7 +581,7 @@ __device__ __forceinline__ f32x16 tile_gemm_lds_rows(const float* X, int FP, con
   return acc;
 }
 
-template <int D, int ROWS>
+template <int D, int ROWS, int PPU>
 __global__ __launch_bounds__(GT_THREADS) void gsta_one_kernel(const unsigned short* __restrict__ seg,
                                                               const unsigned short* __restrict__ t0,
                                                               const unsigned short* __restrict__ wq,
@@ -591,7 +591,12 @@ __global__ __launch_bounds__(GT_THREADS) void gsta_one_kernel(const unsigned sho
                                                               int w, int S, float* __restrict__ z) {
   constexpr int FP = D + 4, DB = D / 32, LPR = D / 8, RPW = 64 / LPR;
   constexpr int WP = WPitch<D>::v, RP = RPitch<D>::v, CH = D / 8;
-  constexpr int PPW = GT_ROWS / GT_WAVES;   // pairs per wave
+  // pairs per wave: PPU for the upper waves, which hold their blocks from the start, PPL for the lower waves, which
+  // ask for theirs once the projection chain is done. 5 + 3 when every compute unit has a workgroup (the launch is
+  // then a stream of H' at memory speed, and the earlier a block is requested the better), 4 + 4 for small batches
+  // (latency-bound: the longest wave decides)
+  constexpr int PPL = GT_ROWS / (GT_WAVES / 2) - PPU;
+  static_assert((GT_WAVES / 2) * (PPU + PPL) == GT_ROWS, "the pairs of a tile are dealt to the two halves");
   __shared__ __attribute__((aligned(16))) float bufA[GT_ROWS * FP];
   __shared__ __attribute__((aligned(16))) float bufB[GT_ROWS * FP];
   __shared__ __attribute__((aligned(16))) unsigned char Wql[D * WP];
@@ -602,11 +607,14 @@ __global__ __launch_bounds__(GT_THREADS) void gsta_one_kernel(const unsigned sho
   const int pbase = blockIdx.x * GT_ROWS;
   const int grp = lane / LPR, gl = lane % LPR;
   // (a vector load of a length here would make the compiler wait for every load in flight, the H' stream included)
-  int nvs[PPW];
+  const bool front = wave < GT_WAVES / 2;
+  // first pair of this wave inside the tile and how many it has
+  const int pfirst = front ? (GT_WAVES / 2) * PPU + wave * PPL : (wave - GT_WAVES / 2) * PPU;
+  int nvs[PPU];
 #pragma unroll
-  for (int it = 0; it < PPW; ++it) {
-    const int pr = pbase + wave * PPW + it;
-    nvs[it] = pr < P ? (valid_len(lens, pr / C, L) + w - 1) / w : 0;
+  for (int it = 0; it < PPU; ++it) {
+    const int pr = pbase + pfirst + it;
+    nvs[it] = (pr < P && (it < PPL || !front)) ? (valid_len(lens, pr / C, L) + w - 1) / w : 0;
   }
 
   // One register set per pair. A wave issues in order, and a compute unit's memory pipeline accepts requests only
@@ -616,9 +624,9 @@ __global__ __launch_bounds__(GT_THREADS) void gsta_one_kernel(const unsigned sho
   // small operands and run the projection chain, synchronising among themselves through a counter in LDS (the
   // hardware barrier counts every wave of the workgroup); they ask for their own blocks once r is written, and
   // those stream in while the upper waves, which share their SIMDs, reduce.
-  u32x4 hring[PPW][ROWS];
+  u32x4 hring[PPU][ROWS];
   auto load_pair = [&](int it, u32x4 (&hreg)[ROWS]) {
-    const int pr = (pbase + wave * PPW + it) < P ? (pbase + wave * PPW + it) : (P - 1);   // past the batch: repeat
+    const int pr = (pbase + pfirst + it) < P ? (pbase + pfirst + it) : (P - 1);   // past the batch: repeat
     const unsigned short* H = seg + (size_t)pr * S * D;
 #pragma unroll
     for (int j = 0; j < ROWS; ++j) {
@@ -626,7 +634,6 @@ __global__ __launch_bounds__(GT_THREADS) void gsta_one_kernel(const unsigned sho
       hreg[j] = *reinterpret_cast<const u32x4*>(H + (size_t)(i < S ? i : S - 1) * D + gl * 8);
     }
   };
-  const bool front = wave < GT_WAVES / 2;
   __shared__ unsigned int arrived[2];
   if (tid < 2) arrived[tid] = 0u;
   __syncthreads();   // everyone is here within the first instructions; nothing has been requested yet
@@ -639,7 +646,7 @@ __global__ __launch_bounds__(GT_THREADS) void gsta_one_kernel(const unsigned sho
   };
   if (!front) {
 #pragma unroll
-    for (int it = 0; it < PPW; ++it) load_pair(it, hring[it]);
+    for (int it = 0; it < PPU; ++it) load_pair(it, hring[it]);
   } else {
     constexpr int FT = GT_THREADS / 2;
     constexpr int WIT = D * CH / FT;                   // 16-byte pieces per thread and matrix
@@ -697,13 +704,10 @@ __global__ __launch_bounds__(GT_THREADS) void gsta_one_kernel(const unsigned sho
   __syncthreads();   // r complete in bufA; q' in bufB consumed
   if (front) {
 #pragma unroll
-    for (int it = 0; it < PPW; ++it) load_pair(it, hring[it]);
+    for (int it = 0; it < PPL; ++it) load_pair(it, hring[it]);
   }
 
-#pragma unroll
-  for (int it = 0; it < PPW; ++it) {
-    u32x4 (&hcur)[ROWS] = hring[it];
-    const int pi = wave * PPW + it, nv = nvs[it];
+  auto reduce_pair = [&](const u32x4 (&hcur)[ROWS], int pi, int nv) __attribute__((always_inline)) {
     float rs[8];
     {
       const f32x4 a = *reinterpret_cast<const f32x4*>(bufA + pi * FP + gl * 8);
@@ -768,6 +772,12 @@ __global__ __launch_bounds__(GT_THREADS) void gsta_one_kernel(const unsigned sho
       *reinterpret_cast<f32x4*>(bufB + pi * FP + gl * 8) = a;
       *reinterpret_cast<f32x4*>(bufB + pi * FP + gl * 8 + 4) = b;
     }
+  };
+#pragma unroll
+  for (int it = 0; it < PPL; ++it) reduce_pair(hring[it], pfirst + it, nvs[it]);
+  if (!front) {
+#pragma unroll
+    for (int it = PPL; it < PPU; ++it) reduce_pair(hring[it], pfirst + it, nvs[it]);
   }
   __syncthreads();
   if (wave < DB) {   // z = t0 + p W_v
@@ -863,7 +873,7 @@ laser_status gsta_split_launch(const GstaArgs& a) {
 bool gsta_one_supports(const GstaArgs& a) {
   if (a.dt != LASER_BF16 || a.M != 1) return false;
   if (!(a.d == 64 || a.d == 128)) return false;
-  return rows_needed(a.S, a.d) <= 8;   // four H' blocks per wave are held in registers
+  return rows_needed(a.S, a.d) <= 8;   // five H' blocks per upper wave are held in registers
 }
 
 template <int D>
@@ -871,14 +881,15 @@ static void launch_one_kernel(const GstaArgs& a) {
   const int P = a.U * a.C;
   const unsigned tiles = (unsigned)((P + GT_ROWS - 1) / GT_ROWS);
   const int rows = rows_needed(a.S, a.d);
-#define LASER_ONE(R)                                                                                               \
-  hipLaunchKernelGGL((gsta_one_kernel<D, R>), dim3(tiles), dim3(GT_THREADS), 0, a.stream,                         \
+#define LASER_ONE(R, PU)                                                                                           \
+  hipLaunchKernelGGL((gsta_one_kernel<D, R, PU>), dim3(tiles), dim3(GT_THREADS), 0, a.stream,                     \
                      (const unsigned short*)a.seg, (const unsigned short*)a.t0, (const unsigned short*)a.wq,       \
                      (const unsigned short*)a.wk, (const unsigned short*)a.wv, a.lens, P, a.C, a.L, a.w, a.S,      \
                      a.z_out)
-  if (rows <= 2) LASER_ONE(2);
-  else if (rows <= 4) LASER_ONE(4);
-  else LASER_ONE(8);
+  const bool fills = tiles >= 256;   // a workgroup for every compute unit
+  if (rows <= 2) { if (fills) LASER_ONE(2, 5); else LASER_ONE(2, 4); }
+  else if (rows <= 4) { if (fills) LASER_ONE(4, 5); else LASER_ONE(4, 4); }
+  else { if (fills) LASER_ONE(8, 5); else LASER_ONE(8, 4); }
 #undef LASER_ONE
 }
 
