@@ -17,7 +17,9 @@ Readings where the paper is silent (listed in full in the design notes):
   * GSTA: segments with no valid item are left out of the softmax; when no
     segment is valid the layer output is 0 (so z = t);
   * GSTA scale is sqrt(d) with d the embedding dim; single head; H' is the same
-    in every layer; weights differ per layer; y = x @ W.
+    in every layer; weights differ per layer; y = x @ W;
+  * multi-resolution views (Sec. 3.4.4): max-pooling runs over the segments that hold a
+    valid item; "the r most recent segments" are rows 0..r-1 of H'.
 
 Pin status: every function below is pinned by tests/test_oracle_pins.py (brute
 force written independently, closed forms, invariants, and reduction to library
@@ -162,6 +164,44 @@ def gsta_forward(Hp, t0, wq, wk, wv, cnt) -> np.ndarray:
         for c in range(C):
             z[u, c] = gsta_pair(Hp[u, c], t0[u, c], wq, wk, wv, valid)
     return z
+
+
+def multires_pair(Hp: np.ndarray, seg_valid: np.ndarray, r: int):
+    """The two other views of the multi-resolution fusion for one (user, candidate) (Sec. 3.4.4).
+
+    Hp [S, d]; seg_valid [S] bool; r <= S. Returns (pool [d], recent [r, d]):
+      pool   = max_pool(H'): component-wise maximum over the segment vectors. Reading (the paper does not
+               mention padding): only segments with at least one valid item take part, as in GSTA; with no
+               such segment the pooled vector is 0;
+      recent = s_1 .. s_r, the r most recent segments: rows 0 .. r-1 of H' (the paper counts the history from
+               its most recent item, so segment 1 is row 0). Segments without a valid item are the zero rows
+               H' already holds.
+    """
+    S, d = Hp.shape
+    pool = np.zeros(d, dtype=np.float64)
+    seen = False
+    for i in range(S):
+        if not seg_valid[i]:
+            continue
+        for e in range(d):
+            if not seen or Hp[i, e] > pool[e]:
+                pool[e] = Hp[i, e]
+        seen = True
+    recent = np.array(Hp[:r], dtype=np.float64)
+    return pool, recent
+
+
+def multires_forward(Hp, cnt, r: int):
+    """pool [U, C, d] and recent [U, C, r, d] for a batch (Sec. 3.4.4). Hp [U,C,S,d], cnt [U,S]."""
+    Hp = np.asarray(Hp, dtype=np.float64)
+    U, C, S, d = Hp.shape
+    pool = np.zeros((U, C, d), dtype=np.float64)
+    recent = np.zeros((U, C, r, d), dtype=np.float64)
+    for u in range(U):
+        valid = np.asarray(cnt[u]) > 0
+        for c in range(C):
+            pool[u, c], recent[u, c] = multires_pair(Hp[u, c], valid, r)
+    return pool, recent
 
 
 def laser_forward(q, k, v, t0, wq, wk, wv, lens, w: int, gamma: float):

@@ -319,3 +319,60 @@ def test_p8_planted_mistakes_are_caught(monkeypatch):
         mp.setattr(lo, "math", types.SimpleNamespace(sqrt=lambda x: x))
         assert _p1_error(None) > 1e-4
     assert _p1_error(None) < 1e-11
+
+
+# ------------------------------------------------------------------ multi-resolution views (Sec. 3.4.4)
+def _multires_brute(Hp, valid, r):
+    """Scalar Python, written independently of the checker: built-in max over the valid rows, row slices."""
+    S, d = len(Hp), len(Hp[0])
+    rows = [i for i in range(S) if valid[i]]
+    pool = [max(Hp[i][e] for i in rows) if rows else 0.0 for e in range(d)]
+    recent = [[Hp[i][e] for e in range(d)] for i in range(r)]
+    return pool, recent
+
+
+@pytest.mark.parametrize("S,d,r,nvalid", [(7, 5, 3, 7), (7, 5, 7, 4), (4, 3, 1, 1), (5, 2, 2, 0)])
+def test_multires_brute_force(S, d, r, nvalid):
+    rng = np.random.default_rng(100 * S + nvalid)
+    Hp = rng.normal(size=(S, d))
+    valid = np.arange(S) < nvalid            # valid segments are a prefix, as tail padding leaves them
+    Hp[~valid] = 0.0                         # what STA stores for segments without a valid item
+    pool, recent = lo.multires_pair(Hp, valid, r)
+    bp, br = _multires_brute(Hp.tolist(), valid.tolist(), r)
+    assert np.array_equal(pool, np.array(bp)) and np.array_equal(recent, np.array(br).reshape(r, d))
+
+
+def test_multires_closed_forms_and_invariants():
+    rng = np.random.default_rng(4242)
+    S, d = 9, 6
+    Hp = rng.normal(size=(S, d))
+    valid = np.ones(S, dtype=bool)
+    pool, recent = lo.multires_pair(Hp, valid, S)
+    assert np.array_equal(recent, Hp)                                   # r = L': the whole compressed sequence
+    assert np.array_equal(pool, Hp.max(axis=0))                         # the library's reduction
+    assert np.array_equal(pool, torch.amax(torch.from_numpy(Hp), dim=0).numpy())
+    assert (pool >= Hp).all() and all(pool[e] in Hp[:, e] for e in range(d))
+    perm = rng.permutation(S)                                           # pooling ignores the order of the segments
+    assert np.array_equal(lo.multires_pair(Hp[perm], valid, 1)[0], pool)
+    one = np.zeros(S, dtype=bool); one[3] = True                        # a single valid segment pools to itself
+    assert np.array_equal(lo.multires_pair(Hp, one, 1)[0], Hp[3])
+    neg = -np.abs(Hp) - 1.0                                             # all-negative vectors: a masked zero row must
+    neg[5:] = 0.0                                                       # not win the maximum
+    pv = lo.multires_pair(neg, np.arange(S) < 5, 2)[0]
+    assert (pv < 0).all() and np.array_equal(pv, neg[:5].max(axis=0))
+    assert np.array_equal(lo.multires_pair(Hp, np.zeros(S, dtype=bool), 2)[0], np.zeros(d))   # nothing valid: 0
+
+
+def test_multires_batch_matches_pairs():
+    rng = np.random.default_rng(77)
+    U, C, S, d, r = 3, 2, 5, 4, 2
+    Hp = rng.normal(size=(U, C, S, d))
+    cnt = np.array([[3, 3, 3, 3, 1], [3, 2, 0, 0, 0], [0, 0, 0, 0, 0]], dtype=np.int32)
+    for u in range(U):
+        Hp[u][:, cnt[u] == 0] = 0.0
+    pool, recent = oracle.multires_forward(Hp, cnt, r)
+    for u in range(U):
+        for c in range(C):
+            p1, r1 = lo.multires_pair(Hp[u, c], cnt[u] > 0, r)
+            assert np.array_equal(pool[u, c], p1) and np.array_equal(recent[u, c], r1)
+    assert np.array_equal(pool[2], np.zeros((C, d)))
