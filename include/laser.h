@@ -125,6 +125,23 @@ laser_status laser_forward(const void* q, const void* k, const void* v, const vo
                            int U, int C, int L, int d_q, int d, int w, float gamma, int M, laser_dtype dt,
                            void* seg_out, int32_t* seg_cnt, float* z_out, void* stream);
 
+/*
+ * Multi-resolution feature fusion (paper Sec. 3.4.4): besides the global context z, the representation holds
+ * max_pool(H') and the r most recent segments s_1 .. s_r. Both are taken from a stored H':
+ *   pool_out   [U,C,d]   dt   component-wise maximum over the segment vectors of the pair that hold at least one
+ *                             valid item (segment i of user u is valid iff i*w < lens[u], as in GSTA); zeros when
+ *                             there is none. Exact: a maximum of stored values. May be NULL (not wanted).
+ *   recent_out [U,C,r,d] dt   rows 0 .. r-1 of H' (the paper counts the history from its most recent item, so
+ *                             s_1 is row 0), copied as stored (zeros for segments without a valid item).
+ *                             0 <= r <= S; NULL exactly when r == 0.
+ * seg [U,C,S,d] dt and lens [U] (NULL = all L) as for laser_gsta_forward; all pointers are device pointers,
+ * caller-owned, 16-byte aligned (lens 4-byte); outputs are fully overwritten; work is enqueued on `stream`.
+ * Errors: LASER_ERR_NULL (seg NULL, or both outputs NULL), LASER_ERR_SHAPE (sizes, r out of range, r and
+ * recent_out disagree), LASER_ERR_DTYPE, LASER_ERR_ALIGN, LASER_ERR_LAUNCH. Nothing is launched on an error.
+ */
+laser_status laser_multires_forward(const void* seg, const int32_t* lens, int U, int C, int L, int d, int w, int r,
+                                    laser_dtype dt, void* pool_out, void* recent_out, void* stream);
+
 /* Name of the STA / GSTA kernel AUTO would pick for a shape (static strings; host only, no GPU needed). */
 const char* laser_sta_kernel_name(int C, int d_q, int d, int w, laser_dtype dt);
 const char* laser_gsta_kernel_name(int C, int S, int d, laser_dtype dt);

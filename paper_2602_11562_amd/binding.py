@@ -20,7 +20,8 @@ GSTA_AUTO, GSTA_GENERIC, GSTA_TILED, GSTA_SPLIT, GSTA_ONE = 0, 1, 2, 3, 4
 
 EXPORTS = [
     "laser_sta_forward", "laser_sta_forward_variant", "laser_gsta_forward", "laser_gsta_forward_variant",
-    "laser_forward", "laser_sta_kernel_name", "laser_gsta_kernel_name", "laser_status_string", "laser_version",
+    "laser_forward", "laser_multires_forward", "laser_sta_kernel_name", "laser_gsta_kernel_name",
+    "laser_status_string", "laser_version",
 ]
 
 
@@ -52,6 +53,8 @@ def load_library() -> ctypes.CDLL:
     for name in ("laser_sta_forward", "laser_sta_forward_variant", "laser_gsta_forward",
                  "laser_gsta_forward_variant", "laser_forward", "laser_version"):
         getattr(lib, name).restype = i32
+    lib.laser_multires_forward.argtypes = [vp, ip, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp]
+    lib.laser_multires_forward.restype = i32
     lib.laser_sta_kernel_name.argtypes = [i32, i32, i32, i32, i32]
     lib.laser_sta_kernel_name.restype = ctypes.c_char_p
     lib.laser_gsta_kernel_name.argtypes = [i32, i32, i32, i32]
@@ -163,6 +166,27 @@ def laser_gsta_forward(seg, t0, wq, wk, wv, lens, L: int, w: int, z_out=None, st
         _stream(stream), int(variant))
     _check(code, "laser_gsta_forward")
     return z_out
+
+
+def laser_multires_forward(seg, lens, L: int, w: int, r: int, pool_out=None, recent_out=None, stream=None,
+                           want_pool: bool = True):
+    """seg [U,C,S,d], lens int32 [U] or None -> (pool [U,C,d] or None, recent [U,C,r,d] or None), dtype of seg."""
+    torch = _torch()
+    U, C, S, d = seg.shape
+    if S != -(-L // w):
+        raise ValueError("seg.shape[2] must be ceil(L / w)")
+    if pool_out is None and want_pool:
+        pool_out = torch.empty((U, C, d), dtype=seg.dtype, device=seg.device)
+    if recent_out is None and r > 0:
+        recent_out = torch.empty((U, C, r, d), dtype=seg.dtype, device=seg.device)
+    for name, x in (("pool_out", pool_out), ("recent_out", recent_out)):
+        if x is not None and x.dtype != seg.dtype:
+            raise TypeError(f"{name} must have the dtype of seg")
+    code = load_library().laser_multires_forward(
+        _ptr(seg, "seg"), _ptr(lens, "lens", torch.int32), U, C, int(L), d, int(w), int(r), _dt(seg),
+        _ptr(pool_out, "pool_out"), _ptr(recent_out, "recent_out"), _stream(stream))
+    _check(code, "laser_multires_forward")
+    return pool_out, recent_out
 
 
 def laser_forward(q, k, v, t0, wq, wk, wv, lens, w: int, gamma: float, seg_out=None, seg_cnt=None, z_out=None,

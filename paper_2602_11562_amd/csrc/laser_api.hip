@@ -48,6 +48,22 @@ static laser_status validate_gsta(const void* seg, const void* t0, const void* w
   return LASER_OK;
 }
 
+static laser_status validate_multires(const void* seg, const int32_t* lens, int U, int C, int L, int d, int w, int r,
+                                      laser_dtype dt, void* pool_out, void* recent_out, void* stream,
+                                      MultiresArgs* out) {
+  if (!seg || (!pool_out && !recent_out)) return LASER_ERR_NULL;
+  if (dt != LASER_F32 && dt != LASER_BF16) return LASER_ERR_DTYPE;
+  laser_status s = check_dims(U, C, L, d, d, w);
+  if (s != LASER_OK) return s;
+  const int S = (L + w - 1) / w;
+  if (r < 0 || r > S || (r > 0) != (recent_out != nullptr)) return LASER_ERR_SHAPE;
+  if ((long long)U * C * (r > 0 ? r : 1) * d > 0x7fffffffLL) return LASER_ERR_SHAPE;
+  if (!aligned16(seg) || !aligned16(pool_out) || !aligned16(recent_out)) return LASER_ERR_ALIGN;
+  if (lens && (reinterpret_cast<uintptr_t>(lens) & 3u)) return LASER_ERR_ALIGN;
+  *out = MultiresArgs{seg, lens, U, C, L, d, w, S, r, dt, pool_out, recent_out, static_cast<hipStream_t>(stream)};
+  return LASER_OK;
+}
+
 static laser_sta_variant pick_sta(const StaArgs& a) {
   if (sta_stream_supports(a)) return LASER_STA_STREAM;
   if (sta_mfma_supports(a)) return LASER_STA_MFMA;
@@ -138,6 +154,14 @@ laser_status laser_forward(const void* q, const void* k, const void* v, const vo
   s = run_sta(sa, LASER_STA_AUTO);
   if (s != LASER_OK) return s;
   return run_gsta(ga, LASER_GSTA_AUTO);
+}
+
+laser_status laser_multires_forward(const void* seg, const int32_t* lens, int U, int C, int L, int d, int w, int r,
+                                    laser_dtype dt, void* pool_out, void* recent_out, void* stream) {
+  MultiresArgs a;
+  laser_status s = validate_multires(seg, lens, U, C, L, d, w, r, dt, pool_out, recent_out, stream, &a);
+  if (s != LASER_OK) return s;
+  return multires_launch(a);
 }
 
 const char* laser_sta_kernel_name(int C, int d_q, int d, int w, laser_dtype dt) {

@@ -36,6 +36,17 @@ struct GstaArgs {
   hipStream_t stream;
 };
 
+struct MultiresArgs {
+  const void* seg;
+  const int32_t* lens;
+  int U, C, L, d, w, S, r;
+  laser_dtype dt;
+  void* pool_out;     // may be nullptr
+  void* recent_out;   // may be nullptr (r == 0)
+  hipStream_t stream;
+};
+laser_status multires_launch(const MultiresArgs& a);
+
 // Each launcher returns LASER_ERR_UNSUPPORTED (launching nothing) when the shape is outside its range.
 bool sta_generic_supports(const StaArgs& a);
 laser_status sta_generic_launch(const StaArgs& a);

@@ -105,3 +105,19 @@ def test_binding_refuses_host_tensors():
     with pytest.raises(ValueError):
         laser.laser_sta_forward(x, torch.zeros(1, 4, 8), torch.zeros(1, 4, 8), None, 2, 1.0,
                                 seg_out=torch.zeros(1, 2, 2, 8), want_cnt=False)
+
+
+def _multires(lib, seg=A, lens=None, U=2, C=3, L=64, d=16, w=8, r=2, dt=1, pool=A, recent=A):
+    return lib.laser_multires_forward(seg, lens, U, C, L, d, w, r, dt, pool, recent, None)
+
+
+def test_multires_argument_validation(lib):
+    NULL, SHAPE, DTYPE, ALIGN = 1, 2, 3, 6
+    assert _multires(lib, seg=None) == NULL
+    assert _multires(lib, pool=None, recent=None, r=0) == NULL           # nothing wanted
+    assert _multires(lib, dt=5) == DTYPE
+    for kw in ({"U": 0}, {"C": -1}, {"L": 0}, {"d": 12}, {"w": 0}, {"r": -1}, {"r": 9},   # S = 8
+               {"r": 0}, {"r": 2, "recent": None}):                                       # r and recent_out disagree
+        assert _multires(lib, **kw) == SHAPE, kw
+    assert _multires(lib, seg=A + 4) == ALIGN and _multires(lib, pool=A + 8) == ALIGN
+    assert _multires(lib, recent=A + 2) == ALIGN and _multires(lib, lens=A + 2) == ALIGN
