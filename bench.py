@@ -101,6 +101,9 @@ def main() -> int:
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copies", type=int, default=0, help="distinct input/output copies to rotate through (0 = auto)")
+    ap.add_argument("--views", type=int, default=0, metavar="R",
+                    help="also time the multi-resolution views (max-pooled H' and the R most recent segments): the "
+                         "stand-alone kernel and the whole path with them; reported under \"views\"")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device copy 5 times (reference reading for the FETCH_SIZE / "
                          "WRITE_SIZE counters when this command runs under rocprofv3 --pmc)")
@@ -182,6 +185,32 @@ def main() -> int:
     sta_ms = event_time(sta_only)
     gsta_ms = event_time(gsta_only)
 
+    views = None
+    if args.views > 0:
+        R = min(args.views, spec.S)
+        outs = [(torch.empty((spec.U, spec.C, spec.d), dtype=tdt, device="cuda"),
+                 torch.empty((spec.U, spec.C, R, spec.d), dtype=tdt, device="cuda")) for _ in range(copies)]
+
+        def views_only(i):
+            dw, seg, cnt, z = sets[i % copies]
+            pool, recent = outs[i % copies]
+            laser.laser_multires_forward(seg, dw.lens, spec.L, spec.w, R, pool_out=pool, recent_out=recent)
+
+        def step_views(i):
+            dw, seg, cnt, z = sets[i % copies]
+            pool, recent = outs[i % copies]
+            laser.laser_forward_multires(dw.q, dw.k, dw.v, dw.t0, dw.wq, dw.wk, dw.wv, dw.lens, spec.w, spec.gamma, R,
+                                         seg_out=seg, seg_cnt=cnt, z_out=z, pool_out=pool, recent_out=recent)
+
+        mr_ms = event_time(views_only)
+        path_ms = event_time(step_views)
+        # algorithmic bytes of the stand-alone kernel: the valid segments of H' once, both outputs once
+        nvalid = int(sum(-(-int(n) // spec.w) for n in wl.lens))
+        mr_b = (nvalid * spec.C * spec.d + spec.pairs * spec.d * (1 + 2 * R)) * esz
+        views = {"r": R, "kernel": "multires", "kernel_ms": mr_ms, "algorithmic_bytes": mr_b,
+                 "gbps": mr_b / (mr_ms * 1e-3) / 1e9, "frac_of_hbm_peak": mr_b / (mr_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                 "whole_path_ms_per_step": path_ms, "whole_path_pairs_per_s": spec.pairs / (path_ms * 1e-3)}
+
     if args.calibration_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
@@ -241,6 +270,7 @@ def main() -> int:
         "kernels": {"sta": {"name": sta_kernel, "ms": sta_ms}, "gsta": {
             "name": gsta_kernel, "ms": gsta_ms, "algorithmic_bytes": gsta_b, "algorithmic_flops": gsta_f,
             "gbps": gsta_b / (gsta_ms * 1e-3) / 1e9}},
+        "views": views,
         "parity": {"max_vector_rel_err": worst, "tolerance": TOL[spec.dtype], "ok": bool(parity_ok),
                    "sampled_pairs": 4},
     }

@@ -142,6 +142,18 @@ laser_status laser_forward(const void* q, const void* k, const void* v, const vo
 laser_status laser_multires_forward(const void* seg, const int32_t* lens, int U, int C, int L, int d, int w, int r,
                                     laser_dtype dt, void* pool_out, void* recent_out, void* stream);
 
+/*
+ * The whole path with all three views of Sec. 3.4.4: laser_forward followed by laser_multires_forward on the
+ * stored H', same arguments, same results, same errors; everything is validated before the first launch. Where
+ * the GSTA kernel holds a pair's H' block in registers (bf16, M = 1, S up to 8 * 64 / (d / 8)) the views are
+ * written by that kernel from the same pass over H'; otherwise a third launch reads H' again.
+ */
+laser_status laser_forward_multires(const void* q, const void* k, const void* v, const void* t0,
+                                    const void* wq, const void* wk, const void* wv, const int32_t* lens,
+                                    int U, int C, int L, int d_q, int d, int w, float gamma, int M, laser_dtype dt,
+                                    void* seg_out, int32_t* seg_cnt, float* z_out,
+                                    int r, void* pool_out, void* recent_out, void* stream);
+
 /* Name of the STA / GSTA kernel AUTO would pick for a shape (static strings; host only, no GPU needed). */
 const char* laser_sta_kernel_name(int C, int d_q, int d, int w, laser_dtype dt);
 const char* laser_gsta_kernel_name(int C, int S, int d, laser_dtype dt);

@@ -20,7 +20,7 @@ GSTA_AUTO, GSTA_GENERIC, GSTA_TILED, GSTA_SPLIT, GSTA_ONE = 0, 1, 2, 3, 4
 
 EXPORTS = [
     "laser_sta_forward", "laser_sta_forward_variant", "laser_gsta_forward", "laser_gsta_forward_variant",
-    "laser_forward", "laser_multires_forward", "laser_sta_kernel_name", "laser_gsta_kernel_name",
+    "laser_forward", "laser_multires_forward", "laser_forward_multires", "laser_sta_kernel_name", "laser_gsta_kernel_name",
     "laser_status_string", "laser_version",
 ]
 
@@ -55,6 +55,8 @@ def load_library() -> ctypes.CDLL:
         getattr(lib, name).restype = i32
     lib.laser_multires_forward.argtypes = [vp, ip, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp]
     lib.laser_multires_forward.restype = i32
+    lib.laser_forward_multires.argtypes = lib.laser_forward.argtypes[:-1] + [i32, vp, vp, vp]
+    lib.laser_forward_multires.restype = i32
     lib.laser_sta_kernel_name.argtypes = [i32, i32, i32, i32, i32]
     lib.laser_sta_kernel_name.restype = ctypes.c_char_p
     lib.laser_gsta_kernel_name.argtypes = [i32, i32, i32, i32]
@@ -166,6 +168,38 @@ def laser_gsta_forward(seg, t0, wq, wk, wv, lens, L: int, w: int, z_out=None, st
         _stream(stream), int(variant))
     _check(code, "laser_gsta_forward")
     return z_out
+
+
+def laser_forward_multires(q, k, v, t0, wq, wk, wv, lens, w: int, gamma: float, r: int, seg_out=None, seg_cnt=None,
+                           z_out=None, pool_out=None, recent_out=None, stream=None):
+    """The whole path with all three views. Returns (H', cnt, z fp32, pool [U,C,d], recent [U,C,r,d] or None)."""
+    torch = _torch()
+    U, C, d_q = q.shape
+    L, d = v.shape[1], v.shape[2]
+    M = wq.shape[0]
+    S = -(-L // w)
+    if any(x.dtype != q.dtype for x in (k, v, t0, wq, wk, wv)):
+        raise TypeError("all inputs must share a dtype")
+    if seg_out is None:
+        seg_out = torch.empty((U, C, S, d), dtype=q.dtype, device=q.device)
+    if seg_cnt is None:
+        seg_cnt = torch.empty((U, S), dtype=torch.int32, device=q.device)
+    if z_out is None:
+        z_out = torch.empty((U, C, d), dtype=torch.float32, device=q.device)
+    if pool_out is None:
+        pool_out = torch.empty((U, C, d), dtype=q.dtype, device=q.device)
+    if recent_out is None and r > 0:
+        recent_out = torch.empty((U, C, r, d), dtype=q.dtype, device=q.device)
+    for name, x in (("seg_out", seg_out), ("pool_out", pool_out), ("recent_out", recent_out)):
+        if x is not None and x.dtype != q.dtype:
+            raise TypeError(f"{name} must have the dtype of the inputs")
+    code = load_library().laser_forward_multires(
+        _ptr(q, "q"), _ptr(k, "k"), _ptr(v, "v"), _ptr(t0, "t0"), _ptr(wq, "wq"), _ptr(wk, "wk"), _ptr(wv, "wv"),
+        _ptr(lens, "lens", torch.int32), U, C, L, d_q, d, int(w), float(gamma), M, _dt(q), _ptr(seg_out, "seg_out"),
+        _ptr(seg_cnt, "seg_cnt", torch.int32), _ptr(z_out, "z_out", torch.float32), int(r),
+        _ptr(pool_out, "pool_out"), _ptr(recent_out, "recent_out"), _stream(stream))
+    _check(code, "laser_forward_multires")
+    return seg_out, seg_cnt, z_out, pool_out, recent_out
 
 
 def laser_multires_forward(seg, lens, L: int, w: int, r: int, pool_out=None, recent_out=None, stream=None,

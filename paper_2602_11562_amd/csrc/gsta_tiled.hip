@@ -581,16 +581,24 @@ __device__ __forceinline__ f32x16 tile_gemm_lds_rows(const float* X, int FP, con
   return acc;
 }
 
-template <int D, int ROWS, int PPU>
+// MR: also write max_pool(H') over the valid segments and the first r segments (Sec. 3.4.4) from the blocks held in
+// registers (pool [P, D], recent [P, r, D], bf16; either may be null). They are staged in the LDS that held W_q and
+// W_k (idle once r exists) and leave at the end, from the waves that have no part in the output product: a store
+// issued while the H' stream is in flight waits in the memory pipeline behind every request queued before it, and
+// the wave with it (measured: +5 us for a handful of stores per pair). r is limited by the staging space.
+template <int D, int ROWS, int PPU, bool MR>
 __global__ __launch_bounds__(GT_THREADS) void gsta_one_kernel(const unsigned short* __restrict__ seg,
                                                               const unsigned short* __restrict__ t0,
                                                               const unsigned short* __restrict__ wq,
                                                               const unsigned short* __restrict__ wk,
                                                               const unsigned short* __restrict__ wv,
                                                               const int32_t* __restrict__ lens, int P, int C, int L,
-                                                              int w, int S, float* __restrict__ z) {
+                                                              int w, int S, float* __restrict__ z,
+                                                              u32x4* __restrict__ pool, u32x4* __restrict__ recent,
+                                                              int r) {
   constexpr int FP = D + 4, DB = D / 32, LPR = D / 8, RPW = 64 / LPR;
   constexpr int WP = WPitch<D>::v, RP = RPitch<D>::v, CH = D / 8;
+  static_assert(RP == D * 2 + 16 && D * WP >= GT_ROWS * D * 2, "staging space assumed by gsta_one_max_recent / the pooled rows");
   // pairs per wave: PPU for the upper waves, which hold their blocks from the start, PPL for the lower waves, which
   // ask for theirs once the projection chain is done. 5 + 3 when every compute unit has a workgroup (the launch is
   // then a stream of H' at memory speed, and the earlier a block is requested the better), 4 + 4 for small batches
@@ -708,6 +716,48 @@ __global__ __launch_bounds__(GT_THREADS) void gsta_one_kernel(const unsigned sho
   }
 
   auto reduce_pair = [&](const u32x4 (&hcur)[ROWS], int pi, int nv) __attribute__((always_inline)) {
+    if (MR) {
+      u32x4* stage_pool = reinterpret_cast<u32x4*>(Wql);
+      u32x4* stage_recent = reinterpret_cast<u32x4*>(Wkl);
+      if (recent != nullptr) {
+#pragma unroll
+        for (int j = 0; j < ROWS; ++j) {
+          const int i = j * RPW + grp;
+          if (i < r) stage_recent[(pi * r + i) * LPR + gl] = hcur[j];   // as stored (zeros where no item is valid)
+        }
+      }
+      if (pool != nullptr) {
+        // maximum over the valid rows of this lane group, then over the lane groups; bf16 values compared as
+        // floats, bits passed through
+        float mx[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) mx[e] = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < ROWS; ++j) {
+          if ((j * RPW + grp) < nv) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              mx[2 * e] = fmaxf(mx[2 * e], __uint_as_float(hcur[j][e] << 16));
+              mx[2 * e + 1] = fmaxf(mx[2 * e + 1], __uint_as_float(hcur[j][e] & 0xffff0000u));
+            }
+          }
+        }
+#pragma unroll
+        for (int off = LPR; off < 64; off <<= 1)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], off, 64));
+        if (grp == 0) {
+          u32x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const unsigned int lo = nv > 0 ? (__float_as_uint(mx[2 * e]) >> 16) : 0u;
+            const unsigned int hi = nv > 0 ? (__float_as_uint(mx[2 * e + 1]) & 0xffff0000u) : 0u;
+            o[e] = lo | hi;
+          }
+          stage_pool[pi * LPR + gl] = o;
+        }
+      }
+    }
     float rs[8];
     {
       const f32x4 a = *reinterpret_cast<const f32x4*>(bufA + pi * FP + gl * 8);
@@ -780,6 +830,21 @@ __global__ __launch_bounds__(GT_THREADS) void gsta_one_kernel(const unsigned sho
     for (int it = PPL; it < PPU; ++it) reduce_pair(hring[it], pfirst + it, nvs[it]);
   }
   __syncthreads();
+  if (MR && wave >= DB) {   // the staged views leave while the other waves run the output product
+    constexpr int NT2 = (GT_WAVES - DB) * 64;
+    const int t2 = tid - DB * 64;
+    const int npair = (P - pbase) < GT_ROWS ? (P - pbase) : GT_ROWS;
+    if (recent != nullptr) {
+      const u32x4* st = reinterpret_cast<const u32x4*>(Wkl);
+      u32x4* dst = recent + (size_t)pbase * r * LPR;   // the tile's rows are contiguous in the output
+      for (int e = t2; e < npair * r * LPR; e += NT2) dst[e] = st[e];
+    }
+    if (pool != nullptr) {
+      const u32x4* st = reinterpret_cast<const u32x4*>(Wql);
+      u32x4* dst = pool + (size_t)pbase * LPR;
+      for (int e = t2; e < npair * LPR; e += NT2) dst[e] = st[e];
+    }
+  }
   if (wave < DB) {   // z = t0 + p W_v
     const f32x16 o = tile_gemm_lds<D>(bufB, FP, Wvl, wave, lane, l32, h);
 #pragma unroll
@@ -881,20 +946,31 @@ static void launch_one_kernel(const GstaArgs& a) {
   const int P = a.U * a.C;
   const unsigned tiles = (unsigned)((P + GT_ROWS - 1) / GT_ROWS);
   const int rows = rows_needed(a.S, a.d);
-#define LASER_ONE(R, PU)                                                                                           \
-  hipLaunchKernelGGL((gsta_one_kernel<D, R, PU>), dim3(tiles), dim3(GT_THREADS), 0, a.stream,                     \
+#define LASER_ONE_MR(R, PU, MRF)                                                                                   \
+  hipLaunchKernelGGL((gsta_one_kernel<D, R, PU, MRF>), dim3(tiles), dim3(GT_THREADS), 0, a.stream,                \
                      (const unsigned short*)a.seg, (const unsigned short*)a.t0, (const unsigned short*)a.wq,       \
                      (const unsigned short*)a.wk, (const unsigned short*)a.wv, a.lens, P, a.C, a.L, a.w, a.S,      \
-                     a.z_out)
+                     a.z_out, (u32x4*)a.pool_out, (u32x4*)a.recent_out, a.r)
+#define LASER_ONE(R, PU)                                                                                           \
+  do {                                                                                                             \
+    if (views) LASER_ONE_MR(R, PU, true);                                                                          \
+    else LASER_ONE_MR(R, PU, false);                                                                               \
+  } while (0)
+  const bool views = a.pool_out != nullptr || a.recent_out != nullptr;
   const bool fills = tiles >= 256;   // a workgroup for every compute unit
   if (rows <= 2) { if (fills) LASER_ONE(2, 5); else LASER_ONE(2, 4); }
   else if (rows <= 4) { if (fills) LASER_ONE(4, 5); else LASER_ONE(4, 4); }
   else { if (fills) LASER_ONE(8, 5); else LASER_ONE(8, 4); }
 #undef LASER_ONE
+#undef LASER_ONE_MR
 }
+
+// most recent segments the one-kernel form can stage per pair (the LDS of W_k holds them for a tile of pairs)
+int gsta_one_max_recent(int d) { return (d * (d * 2 + 16)) / (GT_ROWS * d * 2); }
 
 laser_status gsta_one_launch(const GstaArgs& a) {
   if (!gsta_one_supports(a)) return LASER_ERR_UNSUPPORTED;
+  if (a.recent_out != nullptr && a.r > gsta_one_max_recent(a.d)) return LASER_ERR_UNSUPPORTED;
   if (a.d == 64) launch_one_kernel<64>(a);
   else launch_one_kernel<128>(a);
   return launch_status();

@@ -164,6 +164,40 @@ laser_status laser_multires_forward(const void* seg, const int32_t* lens, int U,
   return multires_launch(a);
 }
 
+laser_status laser_forward_multires(const void* q, const void* k, const void* v, const void* t0, const void* wq,
+                                    const void* wk, const void* wv, const int32_t* lens, int U, int C, int L,
+                                    int d_q, int d, int w, float gamma, int M, laser_dtype dt, void* seg_out,
+                                    int32_t* seg_cnt, float* z_out, int r, void* pool_out, void* recent_out,
+                                    void* stream) {
+  StaArgs sa;
+  GstaArgs ga;
+  MultiresArgs ma;
+  laser_status s = validate_sta(q, k, v, lens, U, C, L, d_q, d, w, gamma, dt, seg_out, seg_cnt, stream, &sa);
+  if (s != LASER_OK) return s;
+  s = validate_gsta(seg_out, t0, wq, wk, wv, lens, U, C, L, d, w, M, dt, z_out, stream, &ga);
+  if (s != LASER_OK) return s;
+  s = validate_multires(seg_out, lens, U, C, L, d, w, r, dt, pool_out, recent_out, stream, &ma);
+  if (s != LASER_OK) return s;   // everything validated before the first launch
+  sa.reread = true;
+  s = run_sta(sa, LASER_STA_AUTO);
+  if (s != LASER_OK) return s;
+  if (pick_gsta(ga) == LASER_GSTA_ONE) {   // the views come out of the same pass over H'
+    ga.pool_out = pool_out;
+    if (r <= gsta_one_max_recent(d)) {
+      ga.recent_out = recent_out;
+      ga.r = r;
+      return run_gsta(ga, LASER_GSTA_ONE);
+    }
+    s = run_gsta(ga, LASER_GSTA_ONE);   // more recent segments than the kernel can stage: a copy launch for those
+    if (s != LASER_OK) return s;
+    ma.pool_out = nullptr;
+    return multires_launch(ma);
+  }
+  s = run_gsta(ga, LASER_GSTA_AUTO);
+  if (s != LASER_OK) return s;
+  return multires_launch(ma);
+}
+
 const char* laser_sta_kernel_name(int C, int d_q, int d, int w, laser_dtype dt) {
   StaArgs a{};
   a.U = 1; a.C = C; a.L = w > 0 ? w : 1; a.d_q = d_q; a.d = d; a.w = w; a.S = 1; a.gamma = 1.0f; a.dt = dt;

@@ -34,6 +34,10 @@ struct GstaArgs {
   laser_dtype dt;
   float* z_out;
   hipStream_t stream;
+  // optional: the views of laser_multires_forward from the same pass over H' (one-kernel form only)
+  void* pool_out = nullptr;
+  void* recent_out = nullptr;
+  int r = 0;
 };
 
 struct MultiresArgs {
@@ -63,6 +67,7 @@ bool gsta_split_supports(const GstaArgs& a);
 laser_status gsta_split_launch(const GstaArgs& a);
 bool gsta_one_supports(const GstaArgs& a);
 laser_status gsta_one_launch(const GstaArgs& a);
+int gsta_one_max_recent(int d);   // largest r whose recent_out the one-kernel form writes itself
 
 inline laser_status launch_status() { return hipGetLastError() == hipSuccess ? LASER_OK : LASER_ERR_LAUNCH; }
 

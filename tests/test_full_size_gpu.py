@@ -99,3 +99,27 @@ def test_sta_alone_at_full_size(full):
         worst = max(worst, vec_rel_err(seg_h[u, c], Hp_ref))
     print(f"  sampled pairs against the checker: {worst:.3e}", flush=True)
     assert worst <= tol
+
+
+@pytest.mark.timeout(900)
+def test_all_views_at_full_size(full):
+    """laser_forward_multires: z and H' as laser_forward gives them; pool and recent exact against the checker on the
+    sampled pairs and, everywhere, equal to the standalone kernel's (two different kernels where GSTA writes them)."""
+    import torch
+    wl, dw = full
+    s = wl.spec
+    r = min(4, s.S)
+    seg, cnt, z, pool, recent = laser.laser_forward_multires(dw.q, dw.k, dw.v, dw.t0, dw.wq, dw.wk, dw.wv, dw.lens,
+                                                             s.w, s.gamma, r)
+    seg0, cnt0, z0 = laser.laser_forward(dw.q, dw.k, dw.v, dw.t0, dw.wq, dw.wk, dw.wv, dw.lens, s.w, s.gamma)
+    pool1, recent1 = laser.laser_multires_forward(seg, dw.lens, s.L, s.w, r)
+    torch.cuda.synchronize()
+    print(f"case {s.name}: laser_forward_multires done", flush=True)
+    assert torch.equal(seg, seg0) and torch.equal(cnt, cnt0) and torch.equal(z, z0)
+    assert torch.equal(pool.float(), pool1.float()) and torch.equal(recent, recent1)   # (as numbers: -0 == +0)
+    seg_h = to_host_f64(seg)
+    cnt_h = cnt.cpu().numpy()
+    pool_h, recent_h = to_host_f64(pool), to_host_f64(recent)
+    for (u, c) in _sample_pairs(s, wl.lens):
+        p_ref, r_ref = oracle.multires_pair(seg_h[u, c], cnt_h[u] > 0, r)
+        assert np.array_equal(pool_h[u, c], p_ref) and np.array_equal(recent_h[u, c], r_ref)

@@ -85,3 +85,28 @@ def test_multires_after_sta_on_a_reduced_workload():
     assert np.array_equal(to_host_f64(pool), pool_ref) and np.array_equal(to_host_f64(recent), recent_ref)
     full = np.full_like(cnt.cpu().numpy(), 1)
     assert np.array_equal(to_host_f64(pool_n), oracle.multires_forward(Hs, full, 0)[0])
+
+
+@pytest.mark.parametrize("name,over,r", [
+    ("cfg3_high_fanout", dict(U=2, L=1024 + 128), 3),      # bf16, M = 1: the views come out of the GSTA kernel
+    ("cfg2_bf16", dict(U=6), 16),                          # same, d = 64, r = S, ragged lengths
+    ("cfg5_lifelong", dict(U=1, L=2 * 256 + 16), 2),       # M = 2: third launch
+    ("cfg1_tiny_f32", dict(), 5),                          # fp32: third launch
+    ("cfg4_low_fanout", dict(U=48), 1),                    # one candidate per user, short histories
+])
+def test_whole_path_with_all_views(name, over, r):
+    import torch
+    from workloads.configs import make_workload
+    from parity_util import DeviceWorkload
+    spec = workloads.CONFIGS[name].replace(**over)
+    wl = make_workload(spec)
+    dw = DeviceWorkload(wl)
+    print(f"case {spec}", flush=True)
+    seg, cnt, z, pool, recent = laser.laser_forward_multires(dw.q, dw.k, dw.v, dw.t0, dw.wq, dw.wk, dw.wv, dw.lens,
+                                                             spec.w, spec.gamma, r)
+    seg0, cnt0, z0 = laser.laser_forward(dw.q, dw.k, dw.v, dw.t0, dw.wq, dw.wk, dw.wv, dw.lens, spec.w, spec.gamma)
+    torch.cuda.synchronize()
+    assert torch.equal(seg, seg0) and torch.equal(cnt, cnt0) and torch.equal(z, z0)   # same kernels, same bits
+    pool_ref, recent_ref = oracle.multires_forward(to_host_f64(seg), cnt.cpu().numpy(), r)
+    assert np.array_equal(to_host_f64(pool), pool_ref)
+    assert np.array_equal(to_host_f64(recent), recent_ref)
