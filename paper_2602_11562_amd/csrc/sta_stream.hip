@@ -201,6 +201,168 @@ __global__ __launch_bounds__(256) void sta_stream_kernel(const unsigned short* _
   }
 }
 
+// Short segments (w below one step of the kernel above, e.g. the paper's w = 10 with L = 1000, Sec. 4.1.2
+// "Implementation Details"): a step of four waves would cover one segment and leave most of its lanes idle, and
+// every segment would pay two workgroup barriers. Here each wave owns whole segments (wave v takes segments
+// v, v + 4, ... of the run), reduces them inside the wave and stores them itself: no LDS reduction, no barrier.
+// Chunks of IPC items are loaded one ahead (the next chunk of the segment or the first of the wave's next one).
+template <int DQ, int D, int CMAX>
+__global__ __launch_bounds__(256) void sta_stream_short_kernel(const unsigned short* __restrict__ q,
+                                                               const unsigned short* __restrict__ k,
+                                                               const unsigned short* __restrict__ v,
+                                                               const int32_t* __restrict__ lens, int C, int L, int w,
+                                                               int S, int spg, int groups, float neg_scale_log2e,
+                                                               unsigned short* __restrict__ seg_out,
+                                                               int32_t* __restrict__ seg_cnt) {
+  constexpr int LQ = DQ / 8, LV = D / 8;
+  constexpr int RQ = 64 / LQ, RV = 64 / LV;
+  constexpr int IPC = RQ > RV ? RQ : RV;
+  constexpr int NKL = IPC / RQ, NVL = IPC / RV;
+  constexpr bool SAME = (LQ == LV);
+  __shared__ float gs[4][CMAX][IPC];
+
+  const int u = blockIdx.x / groups, grp = blockIdx.x % groups;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = __builtin_amdgcn_readfirstlane(valid_len(lens, u, L));
+  if (grp == 0) write_seg_cnt(seg_cnt, u, n, L, w, S, tid, 256);
+  const int rq = lane / LQ, cq = lane % LQ;
+  const int rv = lane / LV, cv = lane % LV;
+
+  float qf[CMAX][8];
+#pragma unroll
+  for (int c = 0; c < CMAX; ++c) {
+    u32x4 raw = {0u, 0u, 0u, 0u};
+    if (c < C) raw = *reinterpret_cast<const u32x4*>(q + ((size_t)u * C + c) * DQ + cq * 8);
+    unpack8(raw, qf[c]);
+  }
+  const unsigned short* kU = k + (size_t)u * L * DQ;
+  const unsigned short* vU = v + (size_t)u * L * D;
+
+  const int i_beg = grp * spg;
+  const int i_end = (grp + 1) * spg < S ? (grp + 1) * spg : S;
+  int i_ne = (n + w - 1) / w;   // non-empty segments of the run are a prefix of it
+  if (i_ne > i_end) i_ne = i_end;
+  if (i_ne < i_beg) i_ne = i_beg;
+  auto seg_hi = [&](int i) {
+    int hi = i * w + w;
+    if (hi > L) hi = L;
+    if (hi > n) hi = n;
+    return hi;
+  };
+
+  struct Regs { u32x4 k[NKL], v[NVL]; };
+  // rows at or past the end of the segment are read from its last valid row and get a zero gate
+  auto load_chunk = [&](int base, int hi, Regs& r) {
+#pragma unroll
+    for (int kl = 0; kl < NKL; ++kl) {
+      int row = base + kl * RQ + rq;
+      row = row < hi ? row : hi - 1;
+      r.k[kl] = *reinterpret_cast<const u32x4*>(kU + (size_t)row * DQ + cq * 8);
+    }
+#pragma unroll
+    for (int vl = 0; vl < NVL; ++vl) {
+      int row = base + vl * RV + rv;
+      row = row < hi ? row : hi - 1;
+      r.v[vl] = *reinterpret_cast<const u32x4*>(vU + (size_t)row * D + cv * 8);
+    }
+  };
+  float acc[CMAX][8];
+  auto clear_acc = [&]() {
+#pragma unroll
+    for (int c = 0; c < CMAX; ++c)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[c][e] = 0.0f;
+  };
+  auto compute_chunk = [&](int base, int hi, const Regs& r) {
+    float vf[NVL][8];
+#pragma unroll
+    for (int vl = 0; vl < NVL; ++vl) unpack8(r.v[vl], vf[vl]);
+#pragma unroll
+    for (int c = 0; c < CMAX; ++c) {
+      if (c < C) {
+#pragma unroll
+        for (int kl = 0; kl < NKL; ++kl) {
+          float kf[8];
+          unpack8(r.k[kl], kf);
+          float s = 0.0f;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) s = fmaf(kf[e], qf[c][e], s);
+          s = row_sum<LQ>(s);
+          const bool ok = (base + kl * RQ + rq) < hi;
+          const float g = ok ? __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(s * neg_scale_log2e)) : 0.0f;
+          if (SAME) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[c][e] = fmaf(g, vf[kl][e], acc[c][e]);
+          } else if (cq == 0) {
+            gs[wave][c][kl * RQ + rq] = g;
+          }
+        }
+        if (!SAME) {   // LDS operations of one wave execute in order: the gates written above are visible here
+#pragma unroll
+          for (int vl = 0; vl < NVL; ++vl) {
+            const float g = gs[wave][c][vl * RV + rv];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[c][e] = fmaf(g, vf[vl][e], acc[c][e]);
+          }
+        }
+      }
+    }
+  };
+  auto finish_segment = [&](int i) {   // sum over the row groups of the wave, one 16-byte store per value lane
+#pragma unroll
+    for (int c = 0; c < CMAX; ++c) {
+      if (c < C) {
+#pragma unroll
+        for (int off = LV; off < 64; off <<= 1)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[c][e] += __shfl_xor(acc[c][e], off, 64);
+        if (rv == 0) {
+          u32x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            o[e] = (unsigned)f32_to_bf16_bits(acc[c][2 * e]) | ((unsigned)f32_to_bf16_bits(acc[c][2 * e + 1]) << 16);
+          *reinterpret_cast<u32x4*>(seg_out + (((size_t)u * C + c) * S + i) * D + cv * 8) = o;
+        }
+      }
+    }
+  };
+
+  int ci = i_beg + wave;
+  if (ci < i_ne) {
+    int cbase = ci * w, chi = seg_hi(ci);
+    Regs cur, nxt;
+    load_chunk(cbase, chi, cur);
+    clear_acc();
+    bool more = true;
+    while (more) {
+      int ni = ci, nbase = cbase + IPC, nhi = chi;
+      if (nbase >= chi) {
+        ni = ci + 4;
+        nbase = ni * w;
+        nhi = ni < i_ne ? seg_hi(ni) : 0;
+      }
+      more = ni < i_ne;
+      if (more) load_chunk(nbase, nhi, nxt);
+      compute_chunk(cbase, chi, cur);
+      if (ni != ci) {
+        finish_segment(ci);
+        clear_acc();
+      }
+      cur = nxt;
+      ci = ni;
+      cbase = nbase;
+      chi = nhi;
+    }
+  }
+  // empty segments of the run: exact zeros
+  for (int e = tid; e < (i_end - i_ne) * C * D; e += 256) {
+    const int ii = i_ne + e / (C * D), r2 = e % (C * D);
+    const int c = r2 / D, col = r2 - c * D;
+    seg_out[(((size_t)u * C + c) * S + ii) * D + col] = 0;
+  }
+}
+
 // ------------------------------------------------------------------------------------------ host side
 bool sta_stream_supports(const StaArgs& a) {
   if (a.dt != LASER_BF16) return false;
@@ -223,10 +385,20 @@ static void launch_c(const StaArgs& a, float nsl) {
   }
   groups = (a.S + spg - 1) / spg;
   const unsigned blocks = (unsigned)((long long)a.U * groups);
+  // a step of the long form covers 4 waves x 4 chunks of IPC items; shorter segments go wave by wave
+  constexpr int IPC_ = (64 / (DQ / 8)) > (64 / (D / 8)) ? (64 / (DQ / 8)) : (64 / (D / 8));
+  const bool short_seg = a.w < 4 * 4 * IPC_;
 #define LASER_STREAM_LAUNCH(CM)                                                                                      \
-  hipLaunchKernelGGL((sta_stream_kernel<DQ, D, CM>), dim3(blocks), dim3(256), 0, a.stream,                         \
-                     (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens,   \
-                     a.C, a.L, a.w, a.S, spg, groups, nsl, (unsigned short*)a.seg_out, a.seg_cnt)
+  do {                                                                                                               \
+    if (short_seg)                                                                                                   \
+      hipLaunchKernelGGL((sta_stream_short_kernel<DQ, D, CM>), dim3(blocks), dim3(256), 0, a.stream,               \
+                         (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v,       \
+                         a.lens, a.C, a.L, a.w, a.S, spg, groups, nsl, (unsigned short*)a.seg_out, a.seg_cnt);     \
+    else                                                                                                             \
+      hipLaunchKernelGGL((sta_stream_kernel<DQ, D, CM>), dim3(blocks), dim3(256), 0, a.stream,                     \
+                         (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v,       \
+                         a.lens, a.C, a.L, a.w, a.S, spg, groups, nsl, (unsigned short*)a.seg_out, a.seg_cnt);     \
+  } while (0)
   if (a.C <= 1) LASER_STREAM_LAUNCH(1);
   else if (a.C <= 2) LASER_STREAM_LAUNCH(2);
   else if (a.C <= 4) LASER_STREAM_LAUNCH(4);

@@ -148,6 +148,12 @@ EDGE_SPECS = {
     "many_candidates_ragged": _spec("bf16", 5, 200, 1000, 128, 128, 100, 1, 2011),   # w not a multiple of the tile
     "many_candidates_small_w": _spec("bf16", 2, 130, 300, 128, 128, 10, 1, 2012),    # segments shorter than a tile
     "many_candidates_two_tiles": _spec("bf16", 3, 257, 512, 128, 128, 128, 1, 2013),  # two candidate tiles per user
+    # short segments with few candidates per user: the wave-per-segment streaming form (C = 1 is how the paper's
+    # own training batches look: one target per sample, Sec. 4.1.2)
+    "paper_default_one_target": _spec("bf16", 6, 1, 1000, 128, 32, 10, 2, 2014),
+    "short_segments_three_candidates": _spec("bf16", 3, 3, 500, 64, 64, 24, 1, 2015),
+    "short_segments_wide_keys": _spec("bf16", 2, 8, 203, 64, 128, 5, 1, 2016),
+    "short_segments_two_chunks": _spec("bf16", 2, 2, 640, 128, 32, 40, 1, 2017),
 }
 
 EDGE_LENS = {
@@ -158,6 +164,10 @@ EDGE_LENS = {
     "many_candidates_ragged": [1000, 333, 0, 37, 32],
     "many_candidates_small_w": [300, 95],
     "many_candidates_two_tiles": [512, 1, 200],
+    "paper_default_one_target": [1000, 995, 10, 9, 0, 123],
+    "short_segments_three_candidates": [500, 49, 24],
+    "short_segments_wide_keys": [203, 6],
+    "short_segments_two_chunks": [640, 41],
 }
 
 
