@@ -233,7 +233,7 @@ def main() -> int:
 
     dtl = laser.LASER_F32 if spec.dtype == "f32" else laser.LASER_BF16
     sta_kernel = laser.laser_sta_kernel_name(spec.C, spec.d_q, spec.d, spec.w, dtl)
-    gsta_kernel = laser.laser_gsta_kernel_name(spec.C, spec.S, spec.d, dtl)
+    gsta_kernel = laser.laser_gsta_kernel_name(spec.C, spec.S, spec.d, dtl, spec.M)
     t_hbm = sta_b / (HBM_PEAK_GBS * 1e9)
     t_mfma = sta_f / (MFMA_BF16_PEAK_TFLOPS * 1e12)
     if t_hbm >= t_mfma or spec.dtype == "f32":

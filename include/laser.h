@@ -156,7 +156,8 @@ laser_status laser_forward_multires(const void* q, const void* k, const void* v,
 
 /* Name of the STA / GSTA kernel AUTO would pick for a shape (static strings; host only, no GPU needed). */
 const char* laser_sta_kernel_name(int C, int d_q, int d, int w, laser_dtype dt);
-const char* laser_gsta_kernel_name(int C, int S, int d, laser_dtype dt);
+const char* laser_gsta_kernel_name(int C, int S, int d, laser_dtype dt);               /* one layer (M = 1) */
+const char* laser_gsta_kernel_name_layers(int C, int S, int d, int M, laser_dtype dt);
 
 /* Static, human-readable name of a status code. Never NULL. */
 const char* laser_status_string(laser_status s);

@@ -20,8 +20,9 @@ GSTA_AUTO, GSTA_GENERIC, GSTA_TILED, GSTA_SPLIT, GSTA_ONE = 0, 1, 2, 3, 4
 
 EXPORTS = [
     "laser_sta_forward", "laser_sta_forward_variant", "laser_gsta_forward", "laser_gsta_forward_variant",
-    "laser_forward", "laser_multires_forward", "laser_forward_multires", "laser_sta_kernel_name", "laser_gsta_kernel_name",
-    "laser_status_string", "laser_version",
+    "laser_forward", "laser_multires_forward", "laser_forward_multires", "laser_sta_kernel_name",
+    "laser_gsta_kernel_name",
+    "laser_gsta_kernel_name_layers", "laser_status_string", "laser_version",
 ]
 
 
@@ -61,6 +62,8 @@ def load_library() -> ctypes.CDLL:
     lib.laser_sta_kernel_name.restype = ctypes.c_char_p
     lib.laser_gsta_kernel_name.argtypes = [i32, i32, i32, i32]
     lib.laser_gsta_kernel_name.restype = ctypes.c_char_p
+    lib.laser_gsta_kernel_name_layers.argtypes = [i32, i32, i32, i32, i32]
+    lib.laser_gsta_kernel_name_layers.restype = ctypes.c_char_p
     lib.laser_status_string.argtypes = [i32]
     lib.laser_status_string.restype = ctypes.c_char_p
     _lib = lib
@@ -79,8 +82,8 @@ def laser_sta_kernel_name(C: int, d_q: int, d: int, w: int, dt: int) -> str:
     return load_library().laser_sta_kernel_name(C, d_q, d, w, dt).decode()
 
 
-def laser_gsta_kernel_name(C: int, S: int, d: int, dt: int) -> str:
-    return load_library().laser_gsta_kernel_name(C, S, d, dt).decode()
+def laser_gsta_kernel_name(C: int, S: int, d: int, dt: int, M: int = 1) -> str:
+    return load_library().laser_gsta_kernel_name_layers(C, S, d, M, dt).decode()
 
 
 # ----------------------------------------------------------------------------- tensor marshalling

@@ -210,9 +210,13 @@ const char* laser_sta_kernel_name(int C, int d_q, int d, int w, laser_dtype dt) 
 }
 
 const char* laser_gsta_kernel_name(int C, int S, int d, laser_dtype dt) {
+  return laser_gsta_kernel_name_layers(C, S, d, 1, dt);
+}
+
+const char* laser_gsta_kernel_name_layers(int C, int S, int d, int M, laser_dtype dt) {
   GstaArgs a{};
-  a.U = 1; a.C = C; a.L = S; a.w = 1; a.S = S; a.d = d; a.M = 1; a.dt = dt;
-  if (C <= 0 || S <= 0 || d <= 0 || (dt != LASER_F32 && dt != LASER_BF16)) return "invalid";
+  a.U = 1; a.C = C; a.L = S; a.w = 1; a.S = S; a.d = d; a.M = M; a.dt = dt;
+  if (C <= 0 || S <= 0 || d <= 0 || M <= 0 || (dt != LASER_F32 && dt != LASER_BF16)) return "invalid";
   switch (pick_gsta(a)) {
     case LASER_GSTA_SPLIT: return "gsta_split_bf16";
     case LASER_GSTA_ONE: return "gsta_one_bf16";

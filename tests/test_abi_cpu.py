@@ -97,6 +97,8 @@ def test_kernel_names(lib):
     assert laser.laser_sta_kernel_name(16, 64, 64, 64, laser.LASER_F32) == "sta_generic"
     assert laser.laser_sta_kernel_name(0, 64, 64, 64, laser.LASER_F32) == "invalid"
     assert laser.laser_gsta_kernel_name(16, 16, 64, laser.LASER_F32) == "gsta_generic"
+    assert laser.laser_gsta_kernel_name(128, 40, 128, laser.LASER_BF16, M=1) == "gsta_split_bf16"   # 10 row passes
+    assert laser.laser_gsta_kernel_name(128, 40, 128, laser.LASER_BF16, M=2) == "gsta_tiled_bf16"   # several layers
 
 
 def test_binding_refuses_host_tensors():
