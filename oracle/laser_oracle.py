@@ -18,6 +18,9 @@ Readings where the paper is silent (listed in full in the design notes):
     segment is valid the layer output is 0 (so z = t);
   * GSTA scale is sqrt(d) with d the embedding dim; single head; H' is the same
     in every layer; weights differ per layer; y = x @ W;
+  * FFN + LayerNorm on the segment vectors (Sec. 3.4.2): two linear layers with a relu between them
+    and biases, residual, LN over the d components with gain, bias and an epsilon argument; segments
+    without a valid item stay zero;
   * multi-resolution views (Sec. 3.4.4): max-pooling runs over the segments that hold a
     valid item; "the r most recent segments" are rows 0..r-1 of H'.
 
@@ -202,6 +205,51 @@ def multires_forward(Hp, cnt, r: int):
         for c in range(C):
             pool[u, c], recent[u, c] = multires_pair(Hp[u, c], valid, r)
     return pool, recent
+
+
+def segment_ffn_vector(s: np.ndarray, W1: np.ndarray, b1: np.ndarray, W2: np.ndarray, b2: np.ndarray,
+                       ln_g: np.ndarray, ln_b: np.ndarray, eps: float) -> np.ndarray:
+    """s <- LN(FFN(s) + s) for one segment vector (Sec. 3.4.2, the equation after the STA paragraph).
+
+    Readings (the paper names neither the FFN's shape nor the LN's constants): FFN(s) = relu(s W1 + b1) W2 + b2
+    with W1 [d, d_ff], W2 [d_ff, d] (the two-layer position-wise network of the Transformer); LN normalises
+    over the d components with the biased variance, LN(x) = (x - mean) / sqrt(var + eps) * ln_g + ln_b.
+    """
+    d = s.shape[0]
+    hidden = s @ W1 + b1                           # first layer
+    for j in range(hidden.shape[0]):               # relu, written out
+        if hidden[j] < 0.0:
+            hidden[j] = 0.0
+    x = hidden @ W2 + b2 + s                       # second layer and the residual
+    mean = 0.0
+    for e in range(d):
+        mean += x[e]
+    mean /= d
+    var = 0.0
+    for e in range(d):
+        var += (x[e] - mean) * (x[e] - mean)
+    var /= d
+    return (x - mean) / math.sqrt(var + eps) * ln_g + ln_b
+
+
+def segment_ffn_forward(Hp, cnt, W1, b1, W2, b2, ln_g, ln_b, eps: float) -> np.ndarray:
+    """The FFN + LN step on every segment vector of a batch. Hp [U,C,S,d], cnt [U,S] -> [U,C,S,d].
+
+    Reading: segments without a valid item stay the zero vectors they are (they are left out of everything
+    downstream; LN(FFN(0)) would be a constant vector that depends on the biases only).
+    """
+    Hp = np.asarray(Hp, dtype=np.float64)
+    W1, b1, W2, b2 = (np.asarray(x, dtype=np.float64) for x in (W1, b1, W2, b2))
+    ln_g, ln_b = np.asarray(ln_g, dtype=np.float64), np.asarray(ln_b, dtype=np.float64)
+    U, C, S, d = Hp.shape
+    out = np.zeros_like(Hp)
+    for u in range(U):
+        for i in range(S):
+            if cnt[u][i] <= 0:
+                continue
+            for c in range(C):
+                out[u, c, i] = segment_ffn_vector(Hp[u, c, i], W1, b1, W2, b2, ln_g, ln_b, eps)
+    return out
 
 
 def laser_forward(q, k, v, t0, wq, wk, wv, lens, w: int, gamma: float):

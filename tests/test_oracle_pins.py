@@ -376,3 +376,85 @@ def test_multires_batch_matches_pairs():
             p1, r1 = lo.multires_pair(Hp[u, c], cnt[u] > 0, r)
             assert np.array_equal(pool[u, c], p1) and np.array_equal(recent[u, c], r1)
     assert np.array_equal(pool[2], np.zeros((C, d)))
+
+
+# ------------------------------------------------------------------ segment FFN + LayerNorm (Sec. 3.4.2)
+def _ffn_brute(s, W1, b1, W2, b2, g, b, eps):
+    """Scalar Python with math only, written independently of the checker."""
+    d, dff = len(s), len(b1)
+    hid = [max(0.0, sum(s[e] * W1[e][j] for e in range(d)) + b1[j]) for j in range(dff)]
+    x = [sum(hid[j] * W2[j][e] for j in range(dff)) + b2[e] + s[e] for e in range(d)]
+    mu = sum(x) / d
+    var = sum((t - mu) ** 2 for t in x) / d
+    return [(x[e] - mu) / math.sqrt(var + eps) * g[e] + b[e] for e in range(d)]
+
+
+def _ffn_params(rng, d, dff):
+    return (rng.normal(size=(d, dff)) / math.sqrt(d), rng.normal(size=dff) * 0.3, rng.normal(size=(dff, d)) / math.sqrt(dff),
+            rng.normal(size=d) * 0.3, 1.0 + 0.2 * rng.normal(size=d), 0.1 * rng.normal(size=d))
+
+
+@pytest.mark.parametrize("d,dff,eps", [(3, 5, 1e-5), (8, 8, 1e-3), (6, 2, 1e-6)])
+def test_segment_ffn_brute_force(d, dff, eps):
+    rng = np.random.default_rng(31 * d + dff)
+    W1, b1, W2, b2, g, b = _ffn_params(rng, d, dff)
+    s = rng.normal(size=d)
+    got = lo.segment_ffn_vector(s.copy(), W1, b1, W2, b2, g, b, eps)
+    ref = _ffn_brute(s.tolist(), W1.tolist(), b1.tolist(), W2.tolist(), b2.tolist(), g.tolist(), b.tolist(), eps)
+    assert np.allclose(got, ref, rtol=1e-12, atol=1e-13)
+
+
+def test_segment_ffn_matches_library_layers():
+    """torch.nn.functional: linear, relu, layer_norm in fp64 (a reduction to library routines)."""
+    import torch.nn.functional as F
+    rng = np.random.default_rng(5150)
+    d, dff, eps = 16, 40, 1e-5
+    W1, b1, W2, b2, g, b = _ffn_params(rng, d, dff)
+    s = rng.normal(size=(7, d))
+    t = lambda x: torch.from_numpy(np.asarray(x, dtype=np.float64))
+    y = F.linear(F.relu(F.linear(t(s), t(W1).T, t(b1))), t(W2).T, t(b2)) + t(s)
+    ref = F.layer_norm(y, (d,), t(g), t(b), eps).numpy()
+    got = np.stack([lo.segment_ffn_vector(s[i].copy(), W1, b1, W2, b2, g, b, eps) for i in range(7)])
+    assert np.allclose(got, ref, rtol=1e-11, atol=1e-12)
+
+
+def test_segment_ffn_closed_forms_and_invariants():
+    rng = np.random.default_rng(99)
+    d, dff, eps = 12, 20, 1e-5
+    W1, b1, W2, b2, g, b = _ffn_params(rng, d, dff)
+    s = rng.normal(size=d)
+    one, zero = np.ones(d), np.zeros(d)
+    # W2 = 0, b2 = 0: FFN vanishes, the step is LN(s)
+    y = lo.segment_ffn_vector(s.copy(), W1, b1, np.zeros_like(W2), zero, one, zero, 0.0)
+    assert np.allclose(y, (s - s.mean()) / s.std(), rtol=1e-12) and abs(y.mean()) < 1e-12 and abs(y.var() - 1) < 1e-12
+    # LN forgets a shift and a positive scale of its input: b2 + const, and (with eps = 0) x -> a x
+    y0 = lo.segment_ffn_vector(s.copy(), W1, b1, W2, b2, g, b, 0.0)
+    assert np.allclose(lo.segment_ffn_vector(s.copy(), W1, b1, W2, b2 + 3.7, g, b, 0.0), y0, rtol=1e-10, atol=1e-12)
+    # relu: with b1 very negative every hidden unit is off, FFN(s) = b2
+    yoff = lo.segment_ffn_vector(s.copy(), W1, b1 - 1e6, W2, b2, one, zero, eps)
+    x = s + b2
+    assert np.allclose(yoff, (x - x.mean()) / np.sqrt(x.var() + eps), rtol=1e-12)
+    # with b1 very positive every unit is on: the network is affine, FFN(s) = (s W1 + b1) W2 + b2
+    big = 1e3
+    yon = lo.segment_ffn_vector(s.copy(), W1, b1 + big, W2, b2, one, zero, eps)
+    x = (s @ W1 + b1 + big) @ W2 + b2 + s
+    assert np.allclose(yon, (x - x.mean()) / np.sqrt(x.var() + eps), rtol=1e-10)
+    # gain and bias act after the normalisation, component by component
+    assert np.allclose(lo.segment_ffn_vector(s.copy(), W1, b1, W2, b2, 2 * g, b + 1, eps),
+                       2 * (lo.segment_ffn_vector(s.copy(), W1, b1, W2, b2, g, b, eps) - b) + b + 1, rtol=1e-12)
+
+
+def test_segment_ffn_batch_leaves_empty_segments_zero():
+    rng = np.random.default_rng(123)
+    U, C, S, d, dff = 2, 3, 4, 6, 9
+    W1, b1, W2, b2, g, b = _ffn_params(rng, d, dff)
+    Hp = rng.normal(size=(U, C, S, d))
+    cnt = np.array([[5, 5, 2, 0], [1, 0, 0, 0]], dtype=np.int32)
+    out = oracle.segment_ffn_forward(Hp, cnt, W1, b1, W2, b2, g, b, 1e-5)
+    for u in range(U):
+        for i in range(S):
+            for c in range(C):
+                if cnt[u, i] > 0:
+                    assert np.array_equal(out[u, c, i], lo.segment_ffn_vector(Hp[u, c, i].copy(), W1, b1, W2, b2, g, b, 1e-5))
+                else:
+                    assert np.array_equal(out[u, c, i], np.zeros(d))
