@@ -126,6 +126,35 @@ laser_status laser_forward(const void* q, const void* k, const void* v, const vo
                            void* seg_out, int32_t* seg_cnt, float* z_out, void* stream);
 
 /*
+ * Segment feed-forward step (paper Sec. 3.4.2, the equation after the STA paragraph): every segment vector of H'
+ * becomes s <- LN(FFN(s) + s). The paper names neither the network's shape nor the normalisation's constants; here
+ *   FFN(s) = relu(s W1 + b1) W2 + b2,  W1 [d, d_ff], W2 [d_ff, d]  (row vector times matrix, as everywhere),
+ *   LN(x)  = (x - mean(x)) / sqrt(var(x) + eps) * ln_g + ln_b       over the d components, biased variance.
+ * seg [U,C,S,d] dt (H' as stored), lens [U] or NULL as for laser_gsta_forward; w1, w2 in dt; b1 [d_ff], b2 [d],
+ * ln_g [d], ln_b [d] in fp32; d_ff a multiple of 8, at most 4096; eps >= 0. seg_out [U,C,S,d] dt is fully
+ * overwritten and may be seg itself (in place). Vectors of segments without a valid item (i*w >= lens[u]) are
+ * written as zeros. Arithmetic in fp32 (bf16 products on the matrix cores for bf16 storage, the hidden layer
+ * rounded to bf16 between the two products); the result is rounded to dt once.
+ * All pointers are device pointers, caller-owned; 16-byte alignment for seg, w1, w2, seg_out, 4-byte for the rest.
+ * Errors: LASER_ERR_NULL, LASER_ERR_SHAPE, LASER_ERR_DTYPE, LASER_ERR_ALIGN, LASER_ERR_UNSUPPORTED (a forced variant
+ * that does not take the shape), LASER_ERR_LAUNCH. Nothing is launched on an error.
+ */
+typedef enum {
+  LASER_FFN_AUTO = 0,
+  LASER_FFN_GENERIC = 1, /* fp32 FMA, any d and d_ff, either dtype                                   */
+  LASER_FFN_MFMA = 2     /* bf16 MFMA, d in {64, 128}, d_ff in {64, 128, 256} with the weights in LDS */
+} laser_ffn_variant;
+
+laser_status laser_segment_ffn_forward(const void* seg, const int32_t* lens, const void* w1, const float* b1,
+                                       const void* w2, const float* b2, const float* ln_g, const float* ln_b,
+                                       int U, int C, int L, int d, int d_ff, int w, float eps, laser_dtype dt,
+                                       void* seg_out, void* stream);
+laser_status laser_segment_ffn_forward_variant(const void* seg, const int32_t* lens, const void* w1, const float* b1,
+                                               const void* w2, const float* b2, const float* ln_g, const float* ln_b,
+                                               int U, int C, int L, int d, int d_ff, int w, float eps, laser_dtype dt,
+                                               void* seg_out, void* stream, laser_ffn_variant variant);
+
+/*
  * Multi-resolution feature fusion (paper Sec. 3.4.4): besides the global context z, the representation holds
  * max_pool(H') and the r most recent segments s_1 .. s_r. Both are taken from a stored H':
  *   pool_out   [U,C,d]   dt   component-wise maximum over the segment vectors of the pair that hold at least one

@@ -17,11 +17,12 @@ LIB_PATH = os.path.join(_HERE, "liblaser.so")
 LASER_F32, LASER_BF16 = 0, 1
 STA_AUTO, STA_GENERIC, STA_MFMA, STA_STREAM = 0, 1, 2, 3
 GSTA_AUTO, GSTA_GENERIC, GSTA_TILED, GSTA_SPLIT, GSTA_ONE = 0, 1, 2, 3, 4
+FFN_AUTO, FFN_GENERIC, FFN_MFMA = 0, 1, 2
 
 EXPORTS = [
     "laser_sta_forward", "laser_sta_forward_variant", "laser_gsta_forward", "laser_gsta_forward_variant",
     "laser_forward", "laser_multires_forward", "laser_forward_multires", "laser_sta_kernel_name",
-    "laser_gsta_kernel_name",
+    "laser_gsta_kernel_name", "laser_segment_ffn_forward", "laser_segment_ffn_forward_variant",
     "laser_gsta_kernel_name_layers", "laser_status_string", "laser_version",
 ]
 
@@ -58,6 +59,12 @@ def load_library() -> ctypes.CDLL:
     lib.laser_multires_forward.restype = i32
     lib.laser_forward_multires.argtypes = lib.laser_forward.argtypes[:-1] + [i32, vp, vp, vp]
     lib.laser_forward_multires.restype = i32
+    fp = ctypes.c_void_p
+    lib.laser_segment_ffn_forward.argtypes = [vp, ip, vp, fp, vp, fp, fp, fp, i32, i32, i32, i32, i32, i32, f32, i32,
+                                              vp, vp]
+    lib.laser_segment_ffn_forward.restype = i32
+    lib.laser_segment_ffn_forward_variant.argtypes = lib.laser_segment_ffn_forward.argtypes + [i32]
+    lib.laser_segment_ffn_forward_variant.restype = i32
     lib.laser_sta_kernel_name.argtypes = [i32, i32, i32, i32, i32]
     lib.laser_sta_kernel_name.restype = ctypes.c_char_p
     lib.laser_gsta_kernel_name.argtypes = [i32, i32, i32, i32]
@@ -171,6 +178,32 @@ def laser_gsta_forward(seg, t0, wq, wk, wv, lens, L: int, w: int, z_out=None, st
         _stream(stream), int(variant))
     _check(code, "laser_gsta_forward")
     return z_out
+
+
+def laser_segment_ffn_forward(seg, lens, w1, b1, w2, b2, ln_g, ln_b, L: int, w: int, eps: float = 1e-5, seg_out=None,
+                              stream=None, variant: int = FFN_AUTO):
+    """seg [U,C,S,d] -> LN(FFN(seg) + seg) [U,C,S,d] (same dtype); w1 [d,d_ff], w2 [d_ff,d] in seg's dtype, the rest fp32.
+    seg_out may be seg itself."""
+    torch = _torch()
+    U, C, S, d = seg.shape
+    d_ff = w1.shape[1]
+    if S != -(-L // w):
+        raise ValueError("seg.shape[2] must be ceil(L / w)")
+    if tuple(w1.shape) != (d, d_ff) or tuple(w2.shape) != (d_ff, d):
+        raise ValueError("w1 must be [d, d_ff] and w2 [d_ff, d]")
+    if tuple(b1.shape) != (d_ff,) or any(tuple(x.shape) != (d,) for x in (b2, ln_g, ln_b)):
+        raise ValueError("b1 must be [d_ff]; b2, ln_g, ln_b must be [d]")
+    if w1.dtype != seg.dtype or w2.dtype != seg.dtype:
+        raise TypeError("w1 and w2 must have the dtype of seg")
+    if seg_out is None:
+        seg_out = torch.empty_like(seg)
+    code = load_library().laser_segment_ffn_forward_variant(
+        _ptr(seg, "seg"), _ptr(lens, "lens", torch.int32), _ptr(w1, "w1"), _ptr(b1, "b1", torch.float32),
+        _ptr(w2, "w2"), _ptr(b2, "b2", torch.float32), _ptr(ln_g, "ln_g", torch.float32),
+        _ptr(ln_b, "ln_b", torch.float32), U, C, int(L), d, d_ff, int(w), float(eps), _dt(seg),
+        _ptr(seg_out, "seg_out", seg.dtype), _stream(stream), int(variant))
+    _check(code, "laser_segment_ffn_forward")
+    return seg_out
 
 
 def laser_forward_multires(q, k, v, t0, wq, wk, wv, lens, w: int, gamma: float, r: int, seg_out=None, seg_cnt=None,

@@ -1,4 +1,6 @@
 // Host side of the C ABI: argument validation (GPU-free), kernel selection, launches.
+#include <initializer_list>
+
 #include "laser_internal.h"
 
 namespace laser {
@@ -196,6 +198,34 @@ laser_status laser_forward_multires(const void* q, const void* k, const void* v,
   s = run_gsta(ga, LASER_GSTA_AUTO);
   if (s != LASER_OK) return s;
   return multires_launch(ma);
+}
+
+laser_status laser_segment_ffn_forward_variant(const void* seg, const int32_t* lens, const void* w1, const float* b1,
+                                               const void* w2, const float* b2, const float* ln_g, const float* ln_b,
+                                               int U, int C, int L, int d, int d_ff, int w, float eps, laser_dtype dt,
+                                               void* seg_out, void* stream, laser_ffn_variant variant) {
+  if (!seg || !w1 || !b1 || !w2 || !b2 || !ln_g || !ln_b || !seg_out) return LASER_ERR_NULL;
+  if (dt != LASER_F32 && dt != LASER_BF16) return LASER_ERR_DTYPE;
+  laser_status s = check_dims(U, C, L, d, d, w);
+  if (s != LASER_OK) return s;
+  if (d_ff <= 0 || d_ff > 4096 || (d_ff % 8) != 0) return LASER_ERR_SHAPE;
+  if (!(eps >= 0.0f) || !(eps < INFINITY)) return LASER_ERR_SHAPE;
+  if (!aligned16(seg) || !aligned16(w1) || !aligned16(w2) || !aligned16(seg_out)) return LASER_ERR_ALIGN;
+  for (const void* p : {(const void*)b1, (const void*)b2, (const void*)ln_g, (const void*)ln_b, (const void*)lens})
+    if (reinterpret_cast<uintptr_t>(p) & 3u) return LASER_ERR_ALIGN;
+  if (variant < LASER_FFN_AUTO || variant > LASER_FFN_MFMA) return LASER_ERR_UNSUPPORTED;
+  const FfnArgs a{seg, lens, w1, b1, w2, b2, ln_g, ln_b, U, C, L, d, d_ff, w, (L + w - 1) / w, eps, dt, seg_out,
+                  static_cast<hipStream_t>(stream)};
+  if (variant == LASER_FFN_AUTO) variant = segment_ffn_mfma_supports(a) ? LASER_FFN_MFMA : LASER_FFN_GENERIC;
+  return variant == LASER_FFN_MFMA ? segment_ffn_mfma_launch(a) : segment_ffn_generic_launch(a);
+}
+
+laser_status laser_segment_ffn_forward(const void* seg, const int32_t* lens, const void* w1, const float* b1,
+                                       const void* w2, const float* b2, const float* ln_g, const float* ln_b, int U,
+                                       int C, int L, int d, int d_ff, int w, float eps, laser_dtype dt, void* seg_out,
+                                       void* stream) {
+  return laser_segment_ffn_forward_variant(seg, lens, w1, b1, w2, b2, ln_g, ln_b, U, C, L, d, d_ff, w, eps, dt, seg_out,
+                                           stream, LASER_FFN_AUTO);
 }
 
 const char* laser_sta_kernel_name(int C, int d_q, int d, int w, laser_dtype dt) {

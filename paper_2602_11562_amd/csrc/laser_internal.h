@@ -51,6 +51,26 @@ struct MultiresArgs {
 };
 laser_status multires_launch(const MultiresArgs& a);
 
+struct FfnArgs {
+  const void* seg;
+  const int32_t* lens;
+  const void* w1;
+  const float* b1;
+  const void* w2;
+  const float* b2;
+  const float* ln_g;
+  const float* ln_b;
+  int U, C, L, d, d_ff, w, S;
+  float eps;
+  laser_dtype dt;
+  void* seg_out;
+  hipStream_t stream;
+};
+bool segment_ffn_generic_supports(const FfnArgs& a);
+laser_status segment_ffn_generic_launch(const FfnArgs& a);
+bool segment_ffn_mfma_supports(const FfnArgs& a);
+laser_status segment_ffn_mfma_launch(const FfnArgs& a);
+
 // Each launcher returns LASER_ERR_UNSUPPORTED (launching nothing) when the shape is outside its range.
 bool sta_generic_supports(const StaArgs& a);
 laser_status sta_generic_launch(const StaArgs& a);

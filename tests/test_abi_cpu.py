@@ -123,3 +123,23 @@ def test_multires_argument_validation(lib):
         assert _multires(lib, **kw) == SHAPE, kw
     assert _multires(lib, seg=A + 4) == ALIGN and _multires(lib, pool=A + 8) == ALIGN
     assert _multires(lib, recent=A + 2) == ALIGN and _multires(lib, lens=A + 2) == ALIGN
+
+
+def _ffn(lib, seg=A, lens=None, w1=A, b1=A, w2=A, b2=A, g=A, b=A, U=2, C=3, L=64, d=16, dff=32, w=8, eps=1e-5, dt=1,
+         out=A, variant=0):
+    return lib.laser_segment_ffn_forward_variant(seg, lens, w1, b1, w2, b2, g, b, U, C, L, d, dff, w, eps, dt, out,
+                                                 None, variant)
+
+
+def test_segment_ffn_argument_validation(lib):
+    NULL, SHAPE, DTYPE, UNSUP, ALIGN = 1, 2, 3, 4, 6
+    for kw in ({"seg": None}, {"w1": None}, {"b1": None}, {"w2": None}, {"b2": None}, {"g": None}, {"b": None},
+               {"out": None}):
+        assert _ffn(lib, **kw) == NULL, kw
+    assert _ffn(lib, dt=7) == DTYPE
+    for kw in ({"U": 0}, {"d": 12}, {"dff": 0}, {"dff": 12}, {"dff": 8192}, {"w": 0}, {"eps": -1.0},
+               {"eps": float("inf")}, {"eps": float("nan")}):
+        assert _ffn(lib, **kw) == SHAPE, kw
+    assert _ffn(lib, seg=A + 8) == ALIGN and _ffn(lib, w2=A + 4) == ALIGN and _ffn(lib, b1=A + 2) == ALIGN
+    assert _ffn(lib, variant=9) == UNSUP
+    assert _ffn(lib, variant=2, d=16) == UNSUP        # the matrix-core form does not take d = 16
