@@ -104,6 +104,9 @@ def main() -> int:
     ap.add_argument("--views", type=int, default=0, metavar="R",
                     help="also time the multi-resolution views (max-pooled H' and the R most recent segments): the "
                          "stand-alone kernel and the whole path with them; reported under \"views\"")
+    ap.add_argument("--ffn", type=int, default=0, metavar="D_FF",
+                    help="also time the segment FFN + LayerNorm step (hidden size D_FF) on the workload's H'; "
+                         "reported under \"ffn\"")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device copy 5 times (reference reading for the FETCH_SIZE / "
                          "WRITE_SIZE counters when this command runs under rocprofv3 --pmc)")
@@ -211,6 +214,33 @@ def main() -> int:
                  "gbps": mr_b / (mr_ms * 1e-3) / 1e9, "frac_of_hbm_peak": mr_b / (mr_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                  "whole_path_ms_per_step": path_ms, "whole_path_pairs_per_s": spec.pairs / (path_ms * 1e-3)}
 
+    ffn = None
+    if args.ffn > 0:
+        rng = np.random.default_rng(spec.seed + 5)
+        to_t = lambda x: torch.from_numpy(np.asarray(x, dtype=np.float32)).cuda()
+        w1 = to_t(rng.normal(size=(spec.d, args.ffn)) / math.sqrt(spec.d)).to(tdt)
+        w2 = to_t(rng.normal(size=(args.ffn, spec.d)) / math.sqrt(args.ffn)).to(tdt)
+        b1, b2 = to_t(rng.normal(size=args.ffn) * 0.3), to_t(rng.normal(size=spec.d) * 0.3)
+        ln_g, ln_b = to_t(1.0 + 0.2 * rng.normal(size=spec.d)), to_t(0.1 * rng.normal(size=spec.d))
+        outs2 = [torch.empty_like(sets[i][1]) for i in range(copies)]
+
+        def ffn_only(i):
+            dw, seg, cnt, z = sets[i % copies]
+            laser.laser_segment_ffn_forward(seg, dw.lens, w1, b1, w2, b2, ln_g, ln_b, spec.L, spec.w, 1e-5,
+                                            seg_out=outs2[i % copies])
+
+        ffn_ms = event_time(ffn_only)
+        nvalid = int(sum(-(-int(n) // spec.w) for n in wl.lens))
+        # algorithmic work: valid segment vectors read once, every vector written once, the weights once;
+        # two products of d x d_ff per valid vector
+        ffn_b = (nvalid * spec.C * spec.d + spec.pairs * spec.S * spec.d + 2 * spec.d * args.ffn) * esz
+        ffn_f = 4.0 * nvalid * spec.C * spec.d * args.ffn
+        t_h, t_m = ffn_b / (HBM_PEAK_GBS * 1e9), ffn_f / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+        ffn = {"d_ff": args.ffn, "kernel_ms": ffn_ms, "algorithmic_bytes": ffn_b, "algorithmic_flops": ffn_f,
+               "gbps": ffn_b / (ffn_ms * 1e-3) / 1e9, "tflops": ffn_f / (ffn_ms * 1e-3) / 1e12,
+               "bound": "hbm" if t_h >= t_m else "mfma",
+               "frac": (t_h if t_h >= t_m else t_m) / (ffn_ms * 1e-3)}
+
     if args.calibration_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
@@ -271,6 +301,7 @@ def main() -> int:
             "name": gsta_kernel, "ms": gsta_ms, "algorithmic_bytes": gsta_b, "algorithmic_flops": gsta_f,
             "gbps": gsta_b / (gsta_ms * 1e-3) / 1e9}},
         "views": views,
+        "ffn": ffn,
         "parity": {"max_vector_rel_err": worst, "tolerance": TOL[spec.dtype], "ok": bool(parity_ok),
                    "sampled_pairs": 4},
     }
