@@ -186,8 +186,11 @@ __global__ __launch_bounds__(FM_THREADS) void segment_ffn_mfma_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
   // ---- park the weights
-  for (int e = tid; e < D * DFF / 8; e += FM_THREADS) {          // W1 [D][DFF]: 16 bytes = 8 hidden units of one k
-    const int kk = e / (DFF / 8), n0 = (e % (DFF / 8)) * 8;
+  // W1 [D][DFF]: 16 bytes = 8 hidden units of one k. Consecutive threads take consecutive k, so that their 2-byte
+  // writes into the transposed rows fall next to each other (with consecutive unit blocks per thread instead, the
+  // writes of a wave are 8 rows apart and share two banks)
+  for (int e = tid; e < D * DFF / 8; e += FM_THREADS) {
+    const int kk = e % D, n0 = (e / D) * 8;
     const u32x4 raw = *reinterpret_cast<const u32x4*>(w1 + (size_t)kk * DFF + n0);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -258,16 +261,31 @@ __global__ __launch_bounds__(FM_THREADS) void segment_ffn_mfma_kernel(
         acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(idA[0], xreg[2 * db], zero, 0, 0, 0);
         acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(idA[1], xreg[2 * db + 1], acc[db], 0, 0, 0);
       }
+      // Operand reads run ahead of their use: the second layer's weights of a hidden tile are requested before its
+      // first-layer products start, the first layer's weights of the next tile as soon as those products are
+      // issued; the fences keep that placement (reads are only awaited where their registers are used).
+      bf16x8 w1r[KSTEPS], w2r[2][DB];
+      auto read_w1 = [&](int j) {
+        const unsigned char* a1 = w1a + j * 32 * W1P;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) w1r[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(a1 + ks * 32));
+      };
+      read_w1(0);
 #pragma unroll 1
       for (int j = 0; j < HT; ++j) {
-        const unsigned char* a1 = w1a + j * 32 * W1P;
-        f32x16 hid = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-            __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(a1)), xreg[0], zero, 0, 0, 0);
+        const unsigned char* a2 = W2L + j * 32 * ROWB;
 #pragma unroll
-        for (int ks = 1; ks < KSTEPS; ++ks)
-          hid = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(a1 + ks * 32)), xreg[ks], hid, 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);   // keeps the second layer's operand reads (32 registers) below this point
+        for (int db = 0; db < DB; ++db) {
+          w2r[0][db] = ffn_lds_tr(a2 + vofs[db]);
+          w2r[1][db] = ffn_lds_tr(a2 + vofs[db] + 4096);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        f32x16 hid = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1r[0], xreg[0], zero, 0, 0, 0);
+#pragma unroll
+        for (int ks = 1; ks < KSTEPS; ++ks) hid = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1r[ks], xreg[ks], hid, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        read_w1(j + 1 < HT ? j + 1 : j);
+        __builtin_amdgcn_sched_barrier(0);
         // + b1, relu, round: hidden unit of element r is 32 j + 8 (r >> 2) + 4 h + (r & 3)
         u32x4 p0, p1;
 #pragma unroll
@@ -280,18 +298,19 @@ __global__ __launch_bounds__(FM_THREADS) void segment_ffn_mfma_kernel(
           if (g < 2) { p0[2 * g] = __builtin_bit_cast(unsigned, c0); p0[2 * g + 1] = __builtin_bit_cast(unsigned, c1); }
           else { p1[2 * (g - 2)] = __builtin_bit_cast(unsigned, c0); p1[2 * (g - 2) + 1] = __builtin_bit_cast(unsigned, c1); }
         }
-        const unsigned char* a2 = W2L + j * 32 * ROWB;
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-          acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ffn_lds_tr(a2 + vofs[db]), __builtin_bit_cast(bf16x8, p0), acc[db], 0, 0, 0);
-          acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ffn_lds_tr(a2 + vofs[db] + 4096), __builtin_bit_cast(bf16x8, p1), acc[db], 0, 0, 0);
+          acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w2r[0][db], __builtin_bit_cast(bf16x8, p0), acc[db], 0, 0, 0);
+          acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w2r[1][db], __builtin_bit_cast(bf16x8, p1), acc[db], 0, 0, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
     }
-    // ---- + b2, LayerNorm over d (this lane holds 64 of the row's 128 values, lane ^ 32 the others), gain, bias
-    float sum = 0.0f;
+    // ---- + b2, LayerNorm over d (this lane holds 64 of the row's 128 values, lane ^ 32 the others), gain, bias.
+    // One pass for the sum and the sum of squares (values of order one, 128 terms, fp32: the cancellation in
+    // E[x^2] - mean^2 costs ~1e-6), two multiply-adds per value for the normalisation.
+    float sum = 0.0f, sq = 0.0f;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -299,22 +318,18 @@ __global__ __launch_bounds__(FM_THREADS) void segment_ffn_mfma_kernel(
         const f32x4 bb = *reinterpret_cast<const f32x4*>(b2s + db * 32 + 8 * g + 4 * h);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          acc[db][4 * g + e] += bb[e];
-          sum += acc[db][4 * g + e];
+          const float xv = acc[db][4 * g + e] + bb[e];
+          acc[db][4 * g + e] = xv;
+          sum += xv;
+          sq = fmaf(xv, xv, sq);
         }
       }
     sum += __shfl_xor(sum, 32, 64);
-    const float mean = sum * (1.0f / D);
-    float sq = 0.0f;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float tt = acc[db][r] - mean;
-        sq = fmaf(tt, tt, sq);
-      }
     sq += __shfl_xor(sq, 32, 64);
-    const float rstd = 1.0f / sqrtf(sq * (1.0f / D) + eps);
+    const float mean = sum * (1.0f / D);
+    const float var = fmaxf(sq * (1.0f / D) - mean * mean, 0.0f);
+    const float rstd = 1.0f / sqrtf(var + eps);
+    const float nmr = -mean * rstd;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -323,7 +338,7 @@ __global__ __launch_bounds__(FM_THREADS) void segment_ffn_mfma_kernel(
         const f32x4 bb = *reinterpret_cast<const f32x4*>(bs + db * 32 + 8 * g + 4 * h);
         bf16x4 o;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = (__bf16)((acc[db][4 * g + e] - mean) * rstd * gg[e] + bb[e]);
+        for (int e = 0; e < 4; ++e) o[e] = (__bf16)fmaf(fmaf(acc[db][4 * g + e], rstd, nmr), gg[e], bb[e]);
         *reinterpret_cast<u32x2*>(opatch + l32 * OP + (db * 32 + g * 8 + h * 4) * 2) = __builtin_bit_cast(u32x2, o);
       }
     // ---- rows leave as whole 256-byte rows (LDS operations of a wave execute in order: no barrier needed)
