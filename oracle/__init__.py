@@ -2,8 +2,8 @@
 imported by tests/, by the smoke check and by the benchmark's CPU-baseline leg."""
 from .laser_oracle import (num_segments, segment_counts, sigmoid, sta_segment, sta_pair, sta_pair_global,
                            gsta_pair, sta_forward, gsta_forward, laser_forward, multires_pair, multires_forward,
-                           segment_ffn_vector, segment_ffn_forward)
+                           segment_ffn_vector, segment_ffn_forward, project_rows, project_qkv)
 
 __all__ = ["num_segments", "segment_counts", "sigmoid", "sta_segment", "sta_pair", "sta_pair_global",
            "gsta_pair", "sta_forward", "gsta_forward", "laser_forward", "multires_pair", "multires_forward",
-           "segment_ffn_vector", "segment_ffn_forward"]
+           "segment_ffn_vector", "segment_ffn_forward", "project_rows", "project_qkv"]

@@ -21,6 +21,7 @@ Readings where the paper is silent (listed in full in the design notes):
   * FFN + LayerNorm on the segment vectors (Sec. 3.4.2): two linear layers with a relu between them
     and biases, residual, LN over the d components with gain, bias and an epsilon argument; segments
     without a valid item stay zero;
+  * projections (Sec. 3.5.1): y = x @ W with W [d_in, n], no bias;
   * multi-resolution views (Sec. 3.4.4): max-pooling runs over the segments that hold a
     valid item; "the r most recent segments" are rows 0..r-1 of H'.
 
@@ -250,6 +251,22 @@ def segment_ffn_forward(Hp, cnt, W1, b1, W2, b2, ln_g, ln_b, eps: float) -> np.n
             for c in range(C):
                 out[u, c, i] = segment_ffn_vector(Hp[u, c, i], W1, b1, W2, b2, ln_g, ln_b, eps)
     return out
+
+
+def project_rows(X: np.ndarray, W: np.ndarray) -> np.ndarray:
+    """Y = X W for row vectors X [..., d_in] and W [d_in, n] (Sec. 3.5.1, the first two equations: every item of the
+    history, and every target, goes through the same matrix)."""
+    X = np.asarray(X, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    if X.shape[-1] != W.shape[0]:
+        raise ValueError("inner dimensions differ")
+    return X @ W
+
+
+def project_qkv(t, H, Wq, Wk, Wv):
+    """Q = t W_q [U,C,d_q], K = H W_k [U,L,d_q], V = H W_v [U,L,d] (Sec. 3.5.1): the inputs of STA from the
+    target embeddings t [U,C,d_in] and the raw history H [U,L,d_in]. No bias (the paper writes none)."""
+    return project_rows(t, Wq), project_rows(H, Wk), project_rows(H, Wv)
 
 
 def laser_forward(q, k, v, t0, wq, wk, wv, lens, w: int, gamma: float):

@@ -458,3 +458,46 @@ def test_segment_ffn_batch_leaves_empty_segments_zero():
                     assert np.array_equal(out[u, c, i], lo.segment_ffn_vector(Hp[u, c, i].copy(), W1, b1, W2, b2, g, b, 1e-5))
                 else:
                     assert np.array_equal(out[u, c, i], np.zeros(d))
+
+
+# ------------------------------------------------------------------ projections (Sec. 3.5.1)
+def test_projection_brute_force_and_selectors():
+    rng = np.random.default_rng(77)
+    X, W = rng.normal(size=(5, 4)), rng.normal(size=(4, 7))
+    ref = [[sum(X[i][e] * W[e][j] for e in range(4)) for j in range(7)] for i in range(5)]
+    assert np.allclose(lo.project_rows(X, W), ref, rtol=1e-13, atol=1e-14)
+    assert np.array_equal(lo.project_rows(X, np.eye(4)), X)                      # identity matrix
+    assert np.array_equal(lo.project_rows(np.eye(4), W), W)                      # unit rows pick the rows of W
+    a, b = 1.7, -0.3                                                             # linear in the rows
+    X2 = rng.normal(size=(5, 4))
+    assert np.allclose(lo.project_rows(a * X + b * X2, W), a * lo.project_rows(X, W) + b * lo.project_rows(X2, W), rtol=1e-12)
+    with pytest.raises(ValueError):                                              # a transposed operand is refused
+        lo.project_rows(X, W.T)
+
+
+def test_projection_shapes_and_batch():
+    rng = np.random.default_rng(78)
+    U, C, L, din, dq, d = 2, 3, 6, 5, 4, 7
+    t, H = rng.normal(size=(U, C, din)), rng.normal(size=(U, L, din))
+    Wq, Wk, Wv = rng.normal(size=(din, dq)), rng.normal(size=(din, dq)), rng.normal(size=(din, d))
+    Q, K, V = oracle.project_qkv(t, H, Wq, Wk, Wv)
+    assert Q.shape == (U, C, dq) and K.shape == (U, L, dq) and V.shape == (U, L, d)
+    for u in range(U):
+        for j in range(L):
+            assert np.allclose(K[u, j], [sum(H[u, j, e] * Wk[e, n] for e in range(din)) for n in range(dq)], rtol=1e-12)
+            assert np.allclose(V[u, j], [sum(H[u, j, e] * Wv[e, n] for e in range(din)) for n in range(d)], rtol=1e-12)
+        for c in range(C):
+            assert np.allclose(Q[u, c], [sum(t[u, c, e] * Wq[e, n] for e in range(din)) for n in range(dq)], rtol=1e-12)
+
+
+def test_projection_then_sta_equals_the_folded_form():
+    """q . k_j = t (W_q W_k^T) h_j, and sum_j g_j (h_j W_v) = (sum_j g_j h_j) W_v: STA on the projected tensors equals
+    STA run on the raw history with the folded query, projected afterwards (Sec. 3.5.1 with Sec. 3.4.2)."""
+    rng = np.random.default_rng(79)
+    L, w, n, din, dq, d, gamma = 23, 5, 19, 6, 4, 8, 2.0
+    t, H = rng.normal(size=din), rng.normal(size=(L, din))
+    Wq, Wk, Wv = rng.normal(size=(din, dq)), rng.normal(size=(din, dq)), rng.normal(size=(din, d))
+    direct = lo.sta_pair(lo.project_rows(t, Wq), lo.project_rows(H, Wk), lo.project_rows(H, Wv), n, w, gamma)
+    folded_q = lo.project_rows(lo.project_rows(t, Wq), Wk.T)
+    folded = lo.project_rows(lo.sta_pair(folded_q, H, H, n, w, gamma), Wv)
+    assert np.allclose(direct, folded, rtol=1e-11, atol=1e-12)
