@@ -142,7 +142,7 @@ laser_status laser_forward(const void* q, const void* k, const void* v, const vo
 typedef enum {
   LASER_FFN_AUTO = 0,
   LASER_FFN_GENERIC = 1, /* fp32 FMA, any d and d_ff, either dtype                                   */
-  LASER_FFN_MFMA = 2     /* bf16 MFMA, d in {64, 128}, d_ff in {64, 128, 256} with the weights in LDS */
+  LASER_FFN_MFMA = 2     /* bf16 MFMA, d = 128, d_ff in {64, 128}, both weight matrices in LDS     */
 } laser_ffn_variant;
 
 laser_status laser_segment_ffn_forward(const void* seg, const int32_t* lens, const void* w1, const float* b1,
@@ -182,6 +182,37 @@ laser_status laser_forward_multires(const void* q, const void* k, const void* v,
                                     int U, int C, int L, int d_q, int d, int w, float gamma, int M, laser_dtype dt,
                                     void* seg_out, int32_t* seg_cnt, float* z_out,
                                     int r, void* pool_out, void* recent_out, void* stream);
+
+/*
+ * The linear maps ahead of STA (paper Sec. 3.5.1, first two equations): Q = t W_q for the targets, and K = H W_k,
+ * V = H W_v for every item of the raw history, both from one pass over H. Row vector times matrix, no bias.
+ *   t   [U,C,d_in] dt   target embeddings          w_q [d_in,d_q] dt     q_out [U,C,d_q] dt
+ *   h   [U,L,d_in] dt   raw history embeddings     w_k [d_in,d_q] dt     k_out [U,L,d_q] dt
+ *                                                  w_v [d_in,d]   dt     v_out [U,L,d]   dt
+ * The outputs are the q, k, v arguments of laser_sta_forward / laser_forward (items past a user's valid length are
+ * projected like any other; STA never reads them). Products in fp32 (bf16 operands on the matrix cores for bf16
+ * storage), accumulated over d_in in fp32, rounded to dt once. 1 <= d_in, d_q, d <= 4096.
+ * All pointers are device pointers, caller-owned, 16-byte aligned; outputs are fully overwritten and must not
+ * overlap the inputs; work is enqueued on `stream`.
+ * Errors: LASER_ERR_NULL, LASER_ERR_SHAPE, LASER_ERR_DTYPE, LASER_ERR_ALIGN, LASER_ERR_UNSUPPORTED (a forced variant
+ * that does not take the shape), LASER_ERR_LAUNCH. Nothing is launched on an error.
+ */
+typedef enum {
+  LASER_PROJECT_AUTO = 0,
+  LASER_PROJECT_GENERIC = 1, /* fp32 FMA, any sizes, either dtype                                               */
+  LASER_PROJECT_MFMA = 2     /* bf16 MFMA, d_in = 128, output widths multiples of 32, each <= 128, weights in LDS */
+} laser_project_variant;
+
+laser_status laser_project_q_forward(const void* t, const void* w_q, int U, int C, int d_in, int d_q, laser_dtype dt,
+                                     void* q_out, void* stream);
+laser_status laser_project_q_forward_variant(const void* t, const void* w_q, int U, int C, int d_in, int d_q,
+                                             laser_dtype dt, void* q_out, void* stream,
+                                             laser_project_variant variant);
+laser_status laser_project_kv_forward(const void* h, const void* w_k, const void* w_v, int U, int L, int d_in, int d_q,
+                                      int d, laser_dtype dt, void* k_out, void* v_out, void* stream);
+laser_status laser_project_kv_forward_variant(const void* h, const void* w_k, const void* w_v, int U, int L, int d_in,
+                                              int d_q, int d, laser_dtype dt, void* k_out, void* v_out, void* stream,
+                                              laser_project_variant variant);
 
 /* Name of the STA / GSTA kernel AUTO would pick for a shape (static strings; host only, no GPU needed). */
 const char* laser_sta_kernel_name(int C, int d_q, int d, int w, laser_dtype dt);

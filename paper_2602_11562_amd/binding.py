@@ -18,12 +18,14 @@ LASER_F32, LASER_BF16 = 0, 1
 STA_AUTO, STA_GENERIC, STA_MFMA, STA_STREAM = 0, 1, 2, 3
 GSTA_AUTO, GSTA_GENERIC, GSTA_TILED, GSTA_SPLIT, GSTA_ONE = 0, 1, 2, 3, 4
 FFN_AUTO, FFN_GENERIC, FFN_MFMA = 0, 1, 2
+PROJECT_AUTO, PROJECT_GENERIC, PROJECT_MFMA = 0, 1, 2
 
 EXPORTS = [
     "laser_sta_forward", "laser_sta_forward_variant", "laser_gsta_forward", "laser_gsta_forward_variant",
     "laser_forward", "laser_multires_forward", "laser_forward_multires", "laser_sta_kernel_name",
     "laser_gsta_kernel_name", "laser_segment_ffn_forward", "laser_segment_ffn_forward_variant",
-    "laser_gsta_kernel_name_layers", "laser_status_string", "laser_version",
+    "laser_gsta_kernel_name_layers", "laser_project_q_forward", "laser_project_q_forward_variant",
+    "laser_project_kv_forward", "laser_project_kv_forward_variant", "laser_status_string", "laser_version",
 ]
 
 
@@ -65,6 +67,13 @@ def load_library() -> ctypes.CDLL:
     lib.laser_segment_ffn_forward.restype = i32
     lib.laser_segment_ffn_forward_variant.argtypes = lib.laser_segment_ffn_forward.argtypes + [i32]
     lib.laser_segment_ffn_forward_variant.restype = i32
+    lib.laser_project_q_forward.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp]
+    lib.laser_project_q_forward_variant.argtypes = lib.laser_project_q_forward.argtypes + [i32]
+    lib.laser_project_kv_forward.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp]
+    lib.laser_project_kv_forward_variant.argtypes = lib.laser_project_kv_forward.argtypes + [i32]
+    for name in ("laser_project_q_forward", "laser_project_q_forward_variant", "laser_project_kv_forward",
+                 "laser_project_kv_forward_variant"):
+        getattr(lib, name).restype = i32
     lib.laser_sta_kernel_name.argtypes = [i32, i32, i32, i32, i32]
     lib.laser_sta_kernel_name.restype = ctypes.c_char_p
     lib.laser_gsta_kernel_name.argtypes = [i32, i32, i32, i32]
@@ -204,6 +213,50 @@ def laser_segment_ffn_forward(seg, lens, w1, b1, w2, b2, ln_g, ln_b, L: int, w: 
         _ptr(seg_out, "seg_out", seg.dtype), _stream(stream), int(variant))
     _check(code, "laser_segment_ffn_forward")
     return seg_out
+
+
+def laser_project_q_forward(t, w_q, q_out=None, stream=None, variant: int = PROJECT_AUTO):
+    """Q = t W_q: t [U,C,d_in], w_q [d_in,d_q] (same dtype) -> [U,C,d_q]."""
+    torch = _torch()
+    U, C, d_in = t.shape
+    if w_q.dim() != 2 or w_q.shape[0] != d_in:
+        raise ValueError("w_q must be [d_in, d_q]")
+    if w_q.dtype != t.dtype:
+        raise TypeError("w_q must have the dtype of t")
+    d_q = w_q.shape[1]
+    if q_out is None:
+        q_out = torch.empty((U, C, d_q), dtype=t.dtype, device=t.device)
+    elif tuple(q_out.shape) != (U, C, d_q):
+        raise ValueError("q_out must be [U, C, d_q]")
+    code = load_library().laser_project_q_forward_variant(
+        _ptr(t, "t"), _ptr(w_q, "w_q"), U, C, d_in, d_q, _dt(t), _ptr(q_out, "q_out", t.dtype), _stream(stream),
+        int(variant))
+    _check(code, "laser_project_q_forward")
+    return q_out
+
+
+def laser_project_kv_forward(h, w_k, w_v, k_out=None, v_out=None, stream=None, variant: int = PROJECT_AUTO):
+    """K = H W_k, V = H W_v from one pass over h [U,L,d_in]: w_k [d_in,d_q], w_v [d_in,d] -> ([U,L,d_q], [U,L,d])."""
+    torch = _torch()
+    U, L, d_in = h.shape
+    if w_k.dim() != 2 or w_v.dim() != 2 or w_k.shape[0] != d_in or w_v.shape[0] != d_in:
+        raise ValueError("w_k must be [d_in, d_q] and w_v [d_in, d]")
+    if w_k.dtype != h.dtype or w_v.dtype != h.dtype:
+        raise TypeError("w_k and w_v must have the dtype of h")
+    d_q, d = w_k.shape[1], w_v.shape[1]
+    if k_out is None:
+        k_out = torch.empty((U, L, d_q), dtype=h.dtype, device=h.device)
+    elif tuple(k_out.shape) != (U, L, d_q):
+        raise ValueError("k_out must be [U, L, d_q]")
+    if v_out is None:
+        v_out = torch.empty((U, L, d), dtype=h.dtype, device=h.device)
+    elif tuple(v_out.shape) != (U, L, d):
+        raise ValueError("v_out must be [U, L, d]")
+    code = load_library().laser_project_kv_forward_variant(
+        _ptr(h, "h"), _ptr(w_k, "w_k"), _ptr(w_v, "w_v"), U, L, d_in, d_q, d, _dt(h), _ptr(k_out, "k_out", h.dtype),
+        _ptr(v_out, "v_out", h.dtype), _stream(stream), int(variant))
+    _check(code, "laser_project_kv_forward")
+    return k_out, v_out
 
 
 def laser_forward_multires(q, k, v, t0, wq, wk, wv, lens, w: int, gamma: float, r: int, seg_out=None, seg_cnt=None,

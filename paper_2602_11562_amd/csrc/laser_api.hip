@@ -228,6 +228,47 @@ laser_status laser_segment_ffn_forward(const void* seg, const int32_t* lens, con
                                            stream, LASER_FFN_AUTO);
 }
 
+static laser_status run_project(ProjArgs& a, laser_project_variant variant) {
+  if (a.dt != LASER_F32 && a.dt != LASER_BF16) return LASER_ERR_DTYPE;
+  if (a.rows < 0 || a.rows > (1LL << 40) || a.d_in <= 0 || a.d_in > 4096) return LASER_ERR_SHAPE;
+  for (int o = 0; o < 2; ++o) {
+    if (a.n[o] < 0 || a.n[o] > 4096 || (o == 0 && a.n[o] == 0)) return LASER_ERR_SHAPE;
+    if (a.n[o] > 0 && (!a.w[o] || !a.y[o])) return LASER_ERR_NULL;
+    if (!aligned16(a.w[o]) || !aligned16(a.y[o])) return LASER_ERR_ALIGN;
+  }
+  if (!a.x) return LASER_ERR_NULL;
+  if (!aligned16(a.x)) return LASER_ERR_ALIGN;
+  if (variant < LASER_PROJECT_AUTO || variant > LASER_PROJECT_MFMA) return LASER_ERR_UNSUPPORTED;
+  if (variant == LASER_PROJECT_AUTO) variant = project_mfma_supports(a) ? LASER_PROJECT_MFMA : LASER_PROJECT_GENERIC;
+  return variant == LASER_PROJECT_MFMA ? project_mfma_launch(a) : project_generic_launch(a);
+}
+
+laser_status laser_project_q_forward_variant(const void* t, const void* w_q, int U, int C, int d_in, int d_q,
+                                             laser_dtype dt, void* q_out, void* stream,
+                                             laser_project_variant variant) {
+  if (U <= 0 || C <= 0) return LASER_ERR_SHAPE;
+  ProjArgs a{t, (long long)U * C, d_in, {w_q, nullptr}, {d_q, 0}, {q_out, nullptr}, dt, static_cast<hipStream_t>(stream)};
+  return run_project(a, variant);
+}
+
+laser_status laser_project_q_forward(const void* t, const void* w_q, int U, int C, int d_in, int d_q, laser_dtype dt,
+                                     void* q_out, void* stream) {
+  return laser_project_q_forward_variant(t, w_q, U, C, d_in, d_q, dt, q_out, stream, LASER_PROJECT_AUTO);
+}
+
+laser_status laser_project_kv_forward_variant(const void* h, const void* w_k, const void* w_v, int U, int L, int d_in,
+                                              int d_q, int d, laser_dtype dt, void* k_out, void* v_out, void* stream,
+                                              laser_project_variant variant) {
+  if (U <= 0 || L <= 0 || d <= 0) return LASER_ERR_SHAPE;
+  ProjArgs a{h, (long long)U * L, d_in, {w_k, w_v}, {d_q, d}, {k_out, v_out}, dt, static_cast<hipStream_t>(stream)};
+  return run_project(a, variant);
+}
+
+laser_status laser_project_kv_forward(const void* h, const void* w_k, const void* w_v, int U, int L, int d_in, int d_q,
+                                      int d, laser_dtype dt, void* k_out, void* v_out, void* stream) {
+  return laser_project_kv_forward_variant(h, w_k, w_v, U, L, d_in, d_q, d, dt, k_out, v_out, stream, LASER_PROJECT_AUTO);
+}
+
 const char* laser_sta_kernel_name(int C, int d_q, int d, int w, laser_dtype dt) {
   StaArgs a{};
   a.U = 1; a.C = C; a.L = w > 0 ? w : 1; a.d_q = d_q; a.d = d; a.w = w; a.S = 1; a.gamma = 1.0f; a.dt = dt;

@@ -71,6 +71,20 @@ laser_status segment_ffn_generic_launch(const FfnArgs& a);
 bool segment_ffn_mfma_supports(const FfnArgs& a);
 laser_status segment_ffn_mfma_launch(const FfnArgs& a);
 
+struct ProjArgs {          // Y_a = X W_a and, when n[1] > 0, Y_b = X W_b from the same pass over X
+  const void* x;           // [rows, d_in]
+  long long rows;
+  int d_in;
+  const void* w[2];        // [d_in, n[o]]
+  int n[2];
+  void* y[2];              // [rows, n[o]]
+  laser_dtype dt;
+  hipStream_t stream;
+};
+laser_status project_generic_launch(const ProjArgs& a);
+bool project_mfma_supports(const ProjArgs& a);
+laser_status project_mfma_launch(const ProjArgs& a);
+
 // Each launcher returns LASER_ERR_UNSUPPORTED (launching nothing) when the shape is outside its range.
 bool sta_generic_supports(const StaArgs& a);
 laser_status sta_generic_launch(const StaArgs& a);

@@ -143,3 +143,30 @@ def test_segment_ffn_argument_validation(lib):
     assert _ffn(lib, seg=A + 8) == ALIGN and _ffn(lib, w2=A + 4) == ALIGN and _ffn(lib, b1=A + 2) == ALIGN
     assert _ffn(lib, variant=9) == UNSUP
     assert _ffn(lib, variant=2, d=16) == UNSUP        # the matrix-core form does not take d = 16
+
+
+def _proj_kv(lib, h=A, wk=A, wv=A, U=2, L=64, din=16, dq=8, d=16, dt=1, k=A, v=A, variant=0):
+    return lib.laser_project_kv_forward_variant(h, wk, wv, U, L, din, dq, d, dt, k, v, None, variant)
+
+
+def _proj_q(lib, t=A, wq=A, U=2, C=3, din=16, dq=8, dt=1, q=A, variant=0):
+    return lib.laser_project_q_forward_variant(t, wq, U, C, din, dq, dt, q, None, variant)
+
+
+def test_projection_argument_validation(lib):
+    NULL, SHAPE, DTYPE, UNSUP, ALIGN = 1, 2, 3, 4, 6
+    for kw in ({"h": None}, {"wk": None}, {"wv": None}, {"k": None}, {"v": None}):
+        assert _proj_kv(lib, **kw) == NULL, kw
+    for kw in ({"t": None}, {"wq": None}, {"q": None}):
+        assert _proj_q(lib, **kw) == NULL, kw
+    assert _proj_kv(lib, dt=4) == DTYPE and _proj_q(lib, dt=-1) == DTYPE
+    for kw in ({"U": 0}, {"L": 0}, {"din": 0}, {"dq": 0}, {"d": 0}, {"din": 8192}, {"d": 8192}, {"dq": -8}):
+        assert _proj_kv(lib, **kw) == SHAPE, kw
+    for kw in ({"U": 0}, {"C": 0}, {"din": 0}, {"dq": 0}, {"dq": 5000}):
+        assert _proj_q(lib, **kw) == SHAPE, kw
+    assert _proj_kv(lib, h=A + 8) == ALIGN and _proj_kv(lib, wv=A + 4) == ALIGN and _proj_kv(lib, k=A + 2) == ALIGN
+    assert _proj_q(lib, wq=A + 8) == ALIGN and _proj_q(lib, q=A + 1) == ALIGN
+    assert _proj_kv(lib, variant=5) == UNSUP and _proj_q(lib, variant=-1) == UNSUP
+    assert _proj_kv(lib, variant=2) == UNSUP          # the matrix-core form does not take d_in = 16
+    assert _proj_kv(lib, variant=2, din=128, dq=48, d=128) == UNSUP   # widths must be multiples of 32
+    assert _proj_q(lib, variant=2, din=128, dq=128, dt=0) == UNSUP    # bf16 only
