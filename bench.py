@@ -107,6 +107,9 @@ def main() -> int:
     ap.add_argument("--ffn", type=int, default=0, metavar="D_FF",
                     help="also time the segment FFN + LayerNorm step (hidden size D_FF) on the workload's H'; "
                          "reported under \"ffn\"")
+    ap.add_argument("--project", type=int, default=0, metavar="D_IN",
+                    help="also time the projections ahead of STA (Q = t W_q, K = H W_k, V = H W_v from raw embeddings "
+                         "of width D_IN) and the whole path that starts from them; reported under \"project\"")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device copy 5 times (reference reading for the FETCH_SIZE / "
                          "WRITE_SIZE counters when this command runs under rocprofv3 --pmc)")
@@ -241,6 +244,45 @@ def main() -> int:
                "bound": "hbm" if t_h >= t_m else "mfma",
                "frac": (t_h if t_h >= t_m else t_m) / (ffn_ms * 1e-3)}
 
+    project = None
+    if args.project > 0:
+        din = args.project
+        rng = np.random.default_rng(spec.seed + 6)
+        to_t = lambda x: torch.from_numpy(np.asarray(x, dtype=np.float32)).cuda().to(tdt)
+        wq_p, wk_p = (to_t(rng.normal(size=(din, spec.d_q)) / math.sqrt(din)) for _ in range(2))
+        wv_p = to_t(rng.normal(size=(din, spec.d)) / math.sqrt(din))
+        raws = [(to_t(rng.normal(size=(spec.U, spec.C, din))), to_t(rng.normal(size=(spec.U, spec.L, din))))
+                for _ in range(min(copies, 2))]
+
+        def kv_only(i):
+            dw, seg, cnt, z = sets[i % copies]
+            laser.laser_project_kv_forward(raws[i % len(raws)][1], wk_p, wv_p, k_out=dw.k, v_out=dw.v)
+
+        def q_only(i):
+            dw, seg, cnt, z = sets[i % copies]
+            laser.laser_project_q_forward(raws[i % len(raws)][0], wq_p, q_out=dw.q)
+
+        def step_from_raw(i):
+            q_only(i)
+            kv_only(i)
+            step(i)
+
+        kv_ms, q_ms, raw_ms = event_time(kv_only), event_time(q_only), event_time(step_from_raw)
+        # algorithmic work of the K/V kernel: H read once, K and V written once, the weights once
+        rows = spec.U * spec.L
+        kv_b = (rows * (din + spec.d_q + spec.d) + din * (spec.d_q + spec.d)) * esz
+        kv_f = 2.0 * rows * din * (spec.d_q + spec.d)
+        t_h, t_m = kv_b / (HBM_PEAK_GBS * 1e9), kv_f / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+        project = {"d_in": din, "kv_kernel_ms": kv_ms, "q_kernel_ms": q_ms, "algorithmic_bytes": kv_b,
+                   "algorithmic_flops": kv_f, "gbps": kv_b / (kv_ms * 1e-3) / 1e9,
+                   "tflops": kv_f / (kv_ms * 1e-3) / 1e12, "bound": "hbm" if t_h >= t_m else "mfma",
+                   "frac": (t_h if t_h >= t_m else t_m) / (kv_ms * 1e-3),
+                   "whole_path_ms_per_step": raw_ms, "whole_path_pairs_per_s": spec.pairs / (raw_ms * 1e-3)}
+        for (dw, seg, cnt, z) in sets:   # the timed loops above overwrote q, k, v: restore the workload's own
+            fresh = DeviceWorkload(wl)
+            dw.q.copy_(fresh.q), dw.k.copy_(fresh.k), dw.v.copy_(fresh.v)
+        torch.cuda.synchronize()
+
     if args.calibration_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
@@ -302,6 +344,7 @@ def main() -> int:
             "gbps": gsta_b / (gsta_ms * 1e-3) / 1e9}},
         "views": views,
         "ffn": ffn,
+        "project": project,
         "parity": {"max_vector_rel_err": worst, "tolerance": TOL[spec.dtype], "ok": bool(parity_ok),
                    "sampled_pairs": 4},
     }

@@ -1,9 +1,9 @@
 """fp64 CPU checker of the STA + GSTA forward pass. Test infrastructure only:
 imported by tests/, by the smoke check and by the benchmark's CPU-baseline leg."""
-from .laser_oracle import (num_segments, segment_counts, sigmoid, sta_segment, sta_pair, sta_pair_global,
+from .laser_oracle import (num_segments, segment_counts, sigmoid, sta_segment, sta_pair, sta_pair_global, sta_pair_heads,
                            gsta_pair, sta_forward, gsta_forward, laser_forward, multires_pair, multires_forward,
                            segment_ffn_vector, segment_ffn_forward, project_rows, project_qkv)
 
-__all__ = ["num_segments", "segment_counts", "sigmoid", "sta_segment", "sta_pair", "sta_pair_global",
+__all__ = ["num_segments", "segment_counts", "sigmoid", "sta_segment", "sta_pair", "sta_pair_global", "sta_pair_heads",
            "gsta_pair", "sta_forward", "gsta_forward", "laser_forward", "multires_pair", "multires_forward",
            "segment_ffn_vector", "segment_ffn_forward", "project_rows", "project_qkv"]

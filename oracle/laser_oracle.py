@@ -21,6 +21,8 @@ Readings where the paper is silent (listed in full in the design notes):
   * FFN + LayerNorm on the segment vectors (Sec. 3.4.2): two linear layers with a relu between them
     and biases, residual, LN over the d components with gain, bias and an epsilon argument; segments
     without a valid item stay zero;
+  * several heads (Sec. 4.1.2): head h owns the h-th run of d_q / heads columns of Q and K and of d / heads
+    columns of V; same gamma; outputs side by side;
   * projections (Sec. 3.5.1): y = x @ W with W [d_in, n], no bias;
   * multi-resolution views (Sec. 3.4.4): max-pooling runs over the segments that hold a
     valid item; "the r most recent segments" are rows 0..r-1 of H'.
@@ -111,6 +113,26 @@ def sta_pair_global(Q: np.ndarray, K: np.ndarray, V: np.ndarray, length: int, w:
     return np.matmul(A_hat, V_hat).reshape(S, d)
 
 
+def sta_pair_heads(Q: np.ndarray, K: np.ndarray, V: np.ndarray, length: int, w: int, gamma: float,
+                   heads: int) -> np.ndarray:
+    """H' [S, d] of one (user, candidate) with several attention heads (Sec. 4.1.2 sets two heads with d_q = 16 per
+    head and a value width equal to the embedding width d).
+
+    Reading (the paper gives the head count and the widths only): as in multi-head attention, head h owns the
+    h-th run of d_q / heads columns of Q and K and the h-th run of d / heads columns of V; every head is the STA of
+    Sec. 3.4.2 on its own columns with the same gamma; the outputs are laid side by side, so H' keeps the width d.
+    """
+    dq, d = K.shape[1], V.shape[1]
+    if heads < 1 or dq % heads or d % heads:
+        raise ValueError("heads must divide d_q and d")
+    a, b = dq // heads, d // heads
+    Hp = np.zeros((num_segments(K.shape[0], w), d), dtype=np.float64)
+    for h in range(heads):
+        Hp[:, h * b:(h + 1) * b] = sta_pair(Q[h * a:(h + 1) * a], K[:, h * a:(h + 1) * a], V[:, h * b:(h + 1) * b],
+                                            length, w, gamma)
+    return Hp
+
+
 def gsta_pair(Hp: np.ndarray, t: np.ndarray, Wq: np.ndarray, Wk: np.ndarray, Wv: np.ndarray,
               seg_valid: np.ndarray) -> np.ndarray:
     """z = t_M for one (user, candidate) (Sec. 3.4.3, attention equation and residual update).
@@ -137,7 +159,7 @@ def gsta_pair(Hp: np.ndarray, t: np.ndarray, Wq: np.ndarray, Wk: np.ndarray, Wv:
     return t_l
 
 
-def sta_forward(q, k, v, lens, w: int, gamma: float, global_form: bool = False):
+def sta_forward(q, k, v, lens, w: int, gamma: float, global_form: bool = False, heads: int = 1):
     """H' [U, C, S, d] and cnt [U, S] for a batch. q [U,C,d_q], k [U,L,d_q], v [U,L,d], lens [U] or None."""
     q = np.asarray(q, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
@@ -150,7 +172,10 @@ def sta_forward(q, k, v, lens, w: int, gamma: float, global_form: bool = False):
     Hp = np.zeros((U, C, S, d), dtype=np.float64)
     for u in range(U):
         for c in range(C):
-            Hp[u, c] = one(q[u, c], k[u], v[u], int(lens[u]), w, gamma)
+            if heads == 1:
+                Hp[u, c] = one(q[u, c], k[u], v[u], int(lens[u]), w, gamma)
+            else:
+                Hp[u, c] = sta_pair_heads(q[u, c], k[u], v[u], int(lens[u]), w, gamma, heads)
     return Hp, segment_counts(lens, L, w)
 
 

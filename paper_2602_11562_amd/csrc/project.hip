@@ -6,6 +6,8 @@
 // rows so that the weights, which it reads from L2, are used eight times. project_mfma_kernel: bf16 storage,
 // d_in = 128, output widths multiples of 32 with at most 256 columns together, the product on the matrix cores
 // with both weight matrices resident in LDS.
+#include <cstdlib>
+
 #include "laser_internal.h"
 
 namespace laser {
@@ -88,6 +90,7 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int PM_WAVES = 8, PM_THREADS = 64 * PM_WAVES, PM_ROWS = 32, PM_D = 128, PM_NMAX = 256, PM_OMAX = 128;
 
+template <bool PF, bool NTS>   // PF: rows of the next tile requested one tile ahead; NTS: non-temporal output stores
 __global__ __launch_bounds__(PM_THREADS) void project_mfma_kernel(const unsigned short* __restrict__ x,
                                                                   const unsigned short* __restrict__ wa,
                                                                   const unsigned short* __restrict__ wb, long long rows,
@@ -101,6 +104,21 @@ __global__ __launch_bounds__(PM_THREADS) void project_mfma_kernel(const unsigned
 
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+  // The wave's first rows are requested before the weights are parked, and each later tile's rows while the
+  // current tile is multiplied: the row loads are the only traffic that waits on HBM.
+  const long long ntiles = (rows + PM_ROWS - 1) / PM_ROWS;
+  const long long tstride = (long long)gridDim.x * PM_WAVES;
+  long long t = (long long)blockIdx.x * PM_WAVES + wave;
+  bf16x8 xreg[KSTEPS], xnext[KSTEPS];
+  auto load_rows = [&](long long tile, bf16x8 (&dst)[KSTEPS]) {   // rows past the end repeat the last one; never stored
+    long long r = tile * PM_ROWS + l32;
+    r = r < rows ? r : rows - 1;
+    const unsigned short* xr = x + (size_t)r * D + h * 8;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) dst[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(xr + ks * 16));
+  };
+  load_rows(t < ntiles ? t : 0, xnext);
 
   // ---- park the weights: 16 bytes = 8 output columns of one k; consecutive threads take consecutive k, so that
   // their 2-byte writes into the transposed rows fall next to each other
@@ -123,16 +141,11 @@ __global__ __launch_bounds__(PM_THREADS) void project_mfma_kernel(const unsigned
   unsigned char* opatch = patch + wave * PM_ROWS * OP;
   const int nta = na / 32, ntiles_out = (na + nb) / 32;
 
-  const long long ntiles = (rows + PM_ROWS - 1) / PM_ROWS;
-  for (long long t = (long long)blockIdx.x * PM_WAVES + wave; t < ntiles; t += (long long)gridDim.x * PM_WAVES) {
+  for (; t < ntiles; t += tstride) {
     const long long r0 = t * PM_ROWS;
-    bf16x8 xreg[KSTEPS];   // the wave's rows as the B operand (rows past the end repeat the last one; never stored)
-    {
-      const long long r = (r0 + l32) < rows ? (r0 + l32) : (rows - 1);
-      const unsigned short* xr = x + (size_t)r * D + h * 8;
 #pragma unroll
-      for (int ks = 0; ks < KSTEPS; ++ks) xreg[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(xr + ks * 16));
-    }
+    for (int ks = 0; ks < KSTEPS; ++ks) xreg[ks] = xnext[ks];   // the wave's rows as the B operand
+    if (PF) load_rows(t + tstride < ntiles ? t + tstride : t, xnext);
     const f32x16 zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
     bf16x8 wr[KSTEPS];
     auto read_w = [&](int j) {
@@ -167,10 +180,15 @@ __global__ __launch_bounds__(PM_THREADS) void project_mfma_kernel(const unsigned
         for (int idx = lane; idx < PM_ROWS * lpr; idx += 64) {
           const int rr = idx / lpr, c = idx - rr * lpr;
           const u32x4 val = *reinterpret_cast<const u32x4*>(opatch + rr * OP + c * 16);
-          if (r0 + rr < rows) *reinterpret_cast<u32x4*>(y + (size_t)(r0 + rr) * n + c * 8) = val;
+          if (r0 + rr < rows) {
+            u32x4* dst = reinterpret_cast<u32x4*>(y + (size_t)(r0 + rr) * n + c * 8);
+            if (NTS) __builtin_nontemporal_store(val, dst);
+            else *dst = val;
+          }
         }
       }
     }
+    if (!PF && t + tstride < ntiles) load_rows(t + tstride, xnext);
   }
 }
 
@@ -187,9 +205,20 @@ laser_status project_mfma_launch(const ProjArgs& a) {
   const long long ntiles = (a.rows + PM_ROWS - 1) / PM_ROWS;
   long long blocks = (ntiles + PM_WAVES - 1) / PM_WAVES;
   if (blocks > 256) blocks = 256;   // one workgroup per compute unit (LDS), each walking several tiles per wave
-  hipLaunchKernelGGL(project_mfma_kernel, dim3((unsigned)blocks), dim3(PM_THREADS), 0, a.stream,
-                     (const unsigned short*)a.x, (const unsigned short*)a.w[0], (const unsigned short*)a.w[1], a.rows,
-                     a.n[0], a.n[1], (unsigned short*)a.y[0], (unsigned short*)a.y[1]);
+  // Non-temporal stores are worth 10-15 % up to about a gigabyte of traffic and cost a few per cent beyond it;
+  // requesting rows a tile ahead gains nothing measurable (two waves per SIMD already cover the latency).
+  const double bytes = (double)a.rows * (a.d_in + a.n[0] + a.n[1]) * 2.0;
+  int mode = bytes <= 2.0e9 ? 2 : 0;
+  if (const char* e = getenv("LASER_PROJECT_MODE")) mode = atoi(e) & 3;   // tuning override: 1 = PF, 2 = NTS
+#define LASER_PROJECT_LAUNCH(PF, NTS)                                                                              \
+  hipLaunchKernelGGL((project_mfma_kernel<PF, NTS>), dim3((unsigned)blocks), dim3(PM_THREADS), 0, a.stream,        \
+                     (const unsigned short*)a.x, (const unsigned short*)a.w[0], (const unsigned short*)a.w[1],     \
+                     a.rows, a.n[0], a.n[1], (unsigned short*)a.y[0], (unsigned short*)a.y[1])
+  if (mode == 0) LASER_PROJECT_LAUNCH(false, false);
+  else if (mode == 1) LASER_PROJECT_LAUNCH(true, false);
+  else if (mode == 2) LASER_PROJECT_LAUNCH(false, true);
+  else LASER_PROJECT_LAUNCH(true, true);
+#undef LASER_PROJECT_LAUNCH
   return launch_status();
 }
 

@@ -501,3 +501,59 @@ def test_projection_then_sta_equals_the_folded_form():
     folded_q = lo.project_rows(lo.project_rows(t, Wq), Wk.T)
     folded = lo.project_rows(lo.sta_pair(folded_q, H, H, n, w, gamma), Wv)
     assert np.allclose(direct, folded, rtol=1e-11, atol=1e-12)
+
+
+# ------------------------------------------------------------------ several heads (Sec. 4.1.2)
+def _heads_brute(q, K, V, n, w, gamma, heads):
+    """Scalar Python, written independently: every output component from its own head's scores."""
+    L, dq, d = len(K), len(q), len(V[0])
+    a, b = dq // heads, d // heads
+    S = -(-L // w)
+    out = [[0.0] * d for _ in range(S)]
+    for i in range(S):
+        for e in range(d):
+            h = e // b
+            acc = 0.0
+            for j in range(i * w, min((i + 1) * w, L, n)):
+                score = sum(q[h * a + x] * K[j][h * a + x] for x in range(a)) / gamma
+                acc += V[j][e] / (1.0 + math.exp(-score))
+            out[i][e] = acc
+    return out
+
+
+@pytest.mark.parametrize("heads,dq,d", [(1, 4, 6), (2, 4, 6), (3, 6, 3), (2, 2, 8)])
+def test_heads_brute_force(heads, dq, d):
+    rng = np.random.default_rng(100 * heads + dq)
+    L, w, n, gamma = 17, 5, 13, 1.7
+    q, K, V = rng.normal(size=dq), rng.normal(size=(L, dq)), rng.normal(size=(L, d))
+    got = lo.sta_pair_heads(q, K, V, n, w, gamma, heads)
+    assert np.allclose(got, _heads_brute(q.tolist(), K.tolist(), V.tolist(), n, w, gamma, heads), rtol=1e-12, atol=1e-13)
+
+
+def test_heads_special_cases_and_invariants():
+    rng = np.random.default_rng(2026)
+    L, w, n, gamma, dq, d = 23, 4, 21, 2.0, 8, 12
+    q, K, V = rng.normal(size=dq), rng.normal(size=(L, dq)), rng.normal(size=(L, d))
+    assert np.array_equal(lo.sta_pair_heads(q, K, V, n, w, gamma, 1), lo.sta_pair(q, K, V, n, w, gamma))
+    base = lo.sta_pair_heads(q, K, V, n, w, gamma, 2)
+    # a head sees only its own columns of Q and K, and writes only its own columns of H'
+    q2 = q.copy()
+    q2[:4] += rng.normal(size=4)
+    moved = lo.sta_pair_heads(q2, K, V, n, w, gamma, 2)
+    assert np.array_equal(moved[:, 6:], base[:, 6:]) and not np.allclose(moved[:, :6], base[:, :6])
+    K2 = K.copy()
+    K2[:, 4:] *= -1.0
+    moved = lo.sta_pair_heads(q, K2, V, n, w, gamma, 2)
+    assert np.array_equal(moved[:, :6], base[:, :6]) and not np.allclose(moved[:, 6:], base[:, 6:])
+    # two heads whose query and key columns repeat each other gate alike: the result is the one-head STA of those columns
+    qq, KK = np.concatenate([q[:4], q[:4]]), np.concatenate([K[:, :4], K[:, :4]], axis=1)
+    assert np.allclose(lo.sta_pair_heads(qq, KK, V, n, w, gamma, 2), lo.sta_pair(q[:4], K[:, :4], V, n, w, gamma), rtol=1e-13)
+    # zero query: every gate is one half in every head
+    half = lo.sta_pair_heads(np.zeros(dq), K, V, L, w, gamma, 4)
+    for i in range(6):
+        assert np.allclose(half[i], 0.5 * V[i * w:(i + 1) * w].sum(axis=0), rtol=1e-13)
+    with pytest.raises(ValueError):
+        lo.sta_pair_heads(q, K, V, n, w, gamma, 3)      # 3 does not divide d_q = 8
+    # batch form
+    Hb, _ = oracle.sta_forward(q[None, None], K[None], V[None], [n], w, gamma, heads=2)
+    assert np.array_equal(Hb[0, 0], base)
