@@ -92,6 +92,22 @@ laser_status laser_sta_forward_variant(const void* q, const void* k, const void*
                                        void* seg_out, int32_t* seg_cnt, void* stream, laser_sta_variant variant);
 
 /*
+ * STA with several attention heads (paper Sec. 4.1.2 runs the compression module with 2 heads, d_q = 16 per head, and
+ * a value width equal to the embedding width). The paper gives the head count and the widths only; here, as in
+ * multi-head attention, head h owns columns [h d_q/heads, (h+1) d_q/heads) of q and k and columns
+ * [h d/heads, (h+1) d/heads) of v and seg_out: every head is the STA above on its own columns, with the same gamma,
+ * and the heads' outputs lie side by side, so all shapes and layouts are those of laser_sta_forward. heads = 1 is
+ * laser_sta_forward_variant. heads must divide d_q and d (1 <= heads <= 64), else LASER_ERR_SHAPE. The streaming
+ * kernel takes 1 or 2 heads (d_q/heads and d/heads multiples of 8); the matrix-core kernel takes one head; other
+ * cases run on the generic kernel (AUTO picks; a forced variant that does not take the case returns
+ * LASER_ERR_UNSUPPORTED). Everything else as for laser_sta_forward.
+ */
+laser_status laser_sta_forward_heads(const void* q, const void* k, const void* v, const int32_t* lens,
+                                     int U, int C, int L, int d_q, int d, int w, float gamma, int heads,
+                                     laser_dtype dt, void* seg_out, int32_t* seg_cnt, void* stream,
+                                     laser_sta_variant variant);
+
+/*
  * Global Stacked Target Attention, forward (paper Sec. 3.4.3): for l = 1..M
  *   a_l = softmax((t_{l-1} W_q^l)(H' W_k^l)^T / sqrt(d)),  o_l = a_l (H' W_v^l),  t_l = t_{l-1} + o_l
  * with t_0 = t0 and z = t_M. The softmax runs over the segments of user u that hold at

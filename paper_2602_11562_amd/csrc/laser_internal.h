@@ -21,6 +21,7 @@ struct StaArgs {
   int32_t* seg_cnt;   // may be nullptr
   hipStream_t stream;
   bool reread;        // H' is read again right after this launch (the whole path): store it cacheable
+  int heads = 1;      // attention heads: head h owns the h-th run of d_q / heads and d / heads columns
 };
 
 struct GstaArgs {

@@ -20,14 +20,16 @@ template <typename T>
 __global__ __launch_bounds__(256) void sta_generic_kernel(const T* __restrict__ q, const T* __restrict__ k,
                                                           const T* __restrict__ v, const int32_t* __restrict__ lens,
                                                           int C, int L, int dq, int d, int w, int S, int TI,
-                                                          float inv_gamma, T* __restrict__ seg_out,
+                                                          int heads, float inv_gamma, T* __restrict__ seg_out,
                                                           int32_t* __restrict__ seg_cnt) {
   extern __shared__ float smem[];
   const int kpitch = dq + 1;                   // +1: lanes read different rows at the same column
   float* Ks = smem;                            // [TI][dq + 1]
   float* Vs = Ks + (size_t)TI * kpitch;        // [TI][d]
   float* qs = Vs + (size_t)TI * d;             // [4][dq]
-  float* gs = qs + GEN_WAVES * dq;             // [4][TI]
+  float* gs = qs + GEN_WAVES * dq;             // [4][heads][TI]
+  // several heads (Sec. 4.1.2): head h owns the h-th run of dq / heads columns of q and k and of d / heads columns of v
+  const int dqh = dq / heads, dh = d / heads;
 
   const int cblocks = (C + GEN_WAVES - 1) / GEN_WAVES;
   int bid = blockIdx.x;
@@ -67,19 +69,20 @@ __global__ __launch_bounds__(256) void sta_generic_kernel(const T* __restrict__ 
     for (int e = tid; e < nj * d; e += 256) Vs[e] = load_as_f32(vU, (size_t)j0 * d + e);
     __syncthreads();
     if (lane < nj) {
-      float e = 0.0f;
       const float* kr = Ks + lane * kpitch;
       const float* qr = qs + wave * dq;
-      for (int a = 0; a < dq; ++a) e = fmaf(qr[a], kr[a], e);
-      gs[wave * TI + lane] = 1.0f / (1.0f + expf(-e * inv_gamma));   // independent gate per item
+      for (int hh = 0; hh < heads; ++hh) {
+        float e = 0.0f;
+        for (int a = hh * dqh; a < (hh + 1) * dqh; ++a) e = fmaf(qr[a], kr[a], e);
+        gs[(wave * heads + hh) * TI + lane] = 1.0f / (1.0f + expf(-e * inv_gamma));   // independent gate per item
+      }
     }
     __syncthreads();
     for (int jj = 0; jj < nj; ++jj) {
-      const float g = gs[wave * TI + jj];
 #pragma unroll
       for (int b = 0; b < GEN_MAX_COLS; ++b) {
         const int col = lane + 64 * b;
-        if (col < d) acc[b] = fmaf(g, Vs[jj * d + col], acc[b]);
+        if (col < d) acc[b] = fmaf(gs[(wave * heads + col / dh) * TI + jj], Vs[jj * d + col], acc[b]);
       }
     }
   }
@@ -94,37 +97,39 @@ __global__ __launch_bounds__(256) void sta_generic_kernel(const T* __restrict__ 
   }
 }
 
-static size_t gen_lds_bytes(int TI, int dq, int d) {
-  return sizeof(float) * ((size_t)TI * (dq + 1) + (size_t)TI * d + GEN_WAVES * dq + GEN_WAVES * TI);
+static size_t gen_lds_bytes(int TI, int dq, int d, int heads) {
+  return sizeof(float) * ((size_t)TI * (dq + 1) + (size_t)TI * d + GEN_WAVES * dq + (size_t)GEN_WAVES * heads * TI);
 }
 
-static int gen_pick_ti(int dq, int d) {
+static int gen_pick_ti(int dq, int d, int heads) {
   for (int ti = 64; ti >= 1; ti >>= 1)
-    if (gen_lds_bytes(ti, dq, d) <= 60 * 1024) return ti;
+    if (gen_lds_bytes(ti, dq, d, heads) <= 60 * 1024) return ti;
   return 0;
 }
 
 bool sta_generic_supports(const StaArgs& a) {
   if (a.d > 64 * GEN_MAX_COLS || a.d_q > 1024) return false;
-  if (gen_pick_ti(a.d_q, a.d) == 0) return false;
+  if (a.heads < 1 || a.d_q % a.heads != 0 || a.d % a.heads != 0) return false;
+  if (gen_pick_ti(a.d_q, a.d, a.heads) == 0) return false;
   const long long blocks = (long long)a.U * ((a.C + GEN_WAVES - 1) / GEN_WAVES) * a.S;
   return blocks <= 0x7fffffffLL;
 }
 
 laser_status sta_generic_launch(const StaArgs& a) {
   if (!sta_generic_supports(a)) return LASER_ERR_UNSUPPORTED;
-  const int TI = gen_pick_ti(a.d_q, a.d);
-  const size_t lds = gen_lds_bytes(TI, a.d_q, a.d);
+  const int TI = gen_pick_ti(a.d_q, a.d, a.heads);
+  const size_t lds = gen_lds_bytes(TI, a.d_q, a.d, a.heads);
   const unsigned blocks = (unsigned)((long long)a.U * ((a.C + GEN_WAVES - 1) / GEN_WAVES) * a.S);
   const float inv_gamma = 1.0f / a.gamma;
   if (a.dt == LASER_F32) {
     hipLaunchKernelGGL(sta_generic_kernel<float>, dim3(blocks), dim3(256), lds, a.stream, (const float*)a.q,
-                       (const float*)a.k, (const float*)a.v, a.lens, a.C, a.L, a.d_q, a.d, a.w, a.S, TI, inv_gamma,
-                       (float*)a.seg_out, a.seg_cnt);
+                       (const float*)a.k, (const float*)a.v, a.lens, a.C, a.L, a.d_q, a.d, a.w, a.S, TI, a.heads,
+                       inv_gamma, (float*)a.seg_out, a.seg_cnt);
   } else {
     hipLaunchKernelGGL(sta_generic_kernel<unsigned short>, dim3(blocks), dim3(256), lds, a.stream,
                        (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens,
-                       a.C, a.L, a.d_q, a.d, a.w, a.S, TI, inv_gamma, (unsigned short*)a.seg_out, a.seg_cnt);
+                       a.C, a.L, a.d_q, a.d, a.w, a.S, TI, a.heads, inv_gamma, (unsigned short*)a.seg_out,
+                       a.seg_cnt);
   }
   return launch_status();
 }

@@ -27,7 +27,7 @@ __device__ __forceinline__ void unpack8(const u32x4& r, float (&x)[8]) {
   }
 }
 
-template <int DQ, int D, int CMAX>
+template <int DQ, int D, int CMAX, int HEADS>
 __global__ __launch_bounds__(256) void sta_stream_kernel(const unsigned short* __restrict__ q,
                                                          const unsigned short* __restrict__ k,
                                                          const unsigned short* __restrict__ v,
@@ -40,8 +40,12 @@ __global__ __launch_bounds__(256) void sta_stream_kernel(const unsigned short* _
   constexpr int IPC = RQ > RV ? RQ : RV;           // items per chunk
   constexpr int NKL = IPC / RQ, NVL = IPC / RV;    // loads per chunk
   constexpr bool SAME = (LQ == LV);
+  // Several heads (Sec. 4.1.2): head h owns the h-th run of LQH lanes of a K row and of LVH lanes of a V row; a
+  // score is summed over its head's lanes only, and a value lane takes the gate of its own head.
+  constexpr int LQH = LQ / HEADS, LVH = LV / HEADS;
+  static_assert(LQ % HEADS == 0 && LV % HEADS == 0, "a head's columns must fill whole 16-byte lanes");
   __shared__ float red[4][CMAX][D];
-  __shared__ float gs[4][CMAX][IPC];
+  __shared__ float gs[4][CMAX][HEADS][IPC];
 
   const int u = blockIdx.x / groups, grp = blockIdx.x % groups;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -121,20 +125,20 @@ __global__ __launch_bounds__(256) void sta_stream_kernel(const unsigned short* _
             float s = 0.0f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) s = fmaf(kf[e], qf[c][e], s);
-            s = row_sum<LQ>(s);
+            s = row_sum<LQH>(s);
             const bool ok = (j0 + kl * RQ + rq) < hi;
             const float g = ok ? __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(s * neg_scale_log2e)) : 0.0f;
             if (SAME) {
 #pragma unroll
               for (int e = 0; e < 8; ++e) acc[c][e] = fmaf(g, vf[kl][e], acc[c][e]);
-            } else if (cq == 0) {
-              gs[wave][c][kl * RQ + rq] = g;
+            } else if (cq % LQH == 0) {
+              gs[wave][c][cq / LQH][kl * RQ + rq] = g;
             }
           }
           if (!SAME) {   // LDS operations of one wave execute in order: the gates written above are visible here
 #pragma unroll
             for (int vl = 0; vl < NVL; ++vl) {
-              const float g = gs[wave][c][vl * RV + rv];   // 0 for rows past the end (written as such above)
+              const float g = gs[wave][c][cv / LVH][vl * RV + rv];   // 0 for rows past the end (written as such above)
 #pragma unroll
               for (int e = 0; e < 8; ++e) acc[c][e] = fmaf(g, vf[vl][e], acc[c][e]);
             }
@@ -206,7 +210,7 @@ __global__ __launch_bounds__(256) void sta_stream_kernel(const unsigned short* _
 // every segment would pay two workgroup barriers. Here each wave owns whole segments (wave v takes segments
 // v, v + 4, ... of the run), reduces them inside the wave and stores them itself: no LDS reduction, no barrier.
 // Chunks of IPC items are loaded one ahead (the next chunk of the segment or the first of the wave's next one).
-template <int DQ, int D, int CMAX>
+template <int DQ, int D, int CMAX, int HEADS>
 __global__ __launch_bounds__(256) void sta_stream_short_kernel(const unsigned short* __restrict__ q,
                                                                const unsigned short* __restrict__ k,
                                                                const unsigned short* __restrict__ v,
@@ -219,7 +223,9 @@ __global__ __launch_bounds__(256) void sta_stream_short_kernel(const unsigned sh
   constexpr int IPC = RQ > RV ? RQ : RV;
   constexpr int NKL = IPC / RQ, NVL = IPC / RV;
   constexpr bool SAME = (LQ == LV);
-  __shared__ float gs[4][CMAX][IPC];
+  constexpr int LQH = LQ / HEADS, LVH = LV / HEADS;   // lanes per head, as in the kernel above
+  static_assert(LQ % HEADS == 0 && LV % HEADS == 0, "a head's columns must fill whole 16-byte lanes");
+  __shared__ float gs[4][CMAX][HEADS][IPC];
 
   const int u = blockIdx.x / groups, grp = blockIdx.x % groups;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -288,20 +294,20 @@ __global__ __launch_bounds__(256) void sta_stream_short_kernel(const unsigned sh
           float s = 0.0f;
 #pragma unroll
           for (int e = 0; e < 8; ++e) s = fmaf(kf[e], qf[c][e], s);
-          s = row_sum<LQ>(s);
+          s = row_sum<LQH>(s);
           const bool ok = (base + kl * RQ + rq) < hi;
           const float g = ok ? __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(s * neg_scale_log2e)) : 0.0f;
           if (SAME) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[c][e] = fmaf(g, vf[kl][e], acc[c][e]);
-          } else if (cq == 0) {
-            gs[wave][c][kl * RQ + rq] = g;
+          } else if (cq % LQH == 0) {
+            gs[wave][c][cq / LQH][kl * RQ + rq] = g;
           }
         }
         if (!SAME) {   // LDS operations of one wave execute in order: the gates written above are visible here
 #pragma unroll
           for (int vl = 0; vl < NVL; ++vl) {
-            const float g = gs[wave][c][vl * RV + rv];
+            const float g = gs[wave][c][cv / LVH][vl * RV + rv];
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[c][e] = fmaf(g, vf[vl][e], acc[c][e]);
           }
@@ -367,12 +373,13 @@ __global__ __launch_bounds__(256) void sta_stream_short_kernel(const unsigned sh
 bool sta_stream_supports(const StaArgs& a) {
   if (a.dt != LASER_BF16) return false;
   if (a.C > 8) return false;
+  if (a.heads != 1 && a.heads != 2) return false;
   if (!(a.d_q == 32 || a.d_q == 64 || a.d_q == 128)) return false;
   if (!(a.d == 64 || a.d == 128)) return false;
   return (long long)a.U * a.S <= 0x7fffffffLL;   // an upper bound of the grid size
 }
 
-template <int DQ, int D>
+template <int DQ, int D, int HEADS>
 static void launch_c(const StaArgs& a, float nsl) {
   // runs of segments per user: the whole user per workgroup once that still gives every compute unit eight
   // workgroups, shorter runs when there are few users
@@ -391,11 +398,11 @@ static void launch_c(const StaArgs& a, float nsl) {
 #define LASER_STREAM_LAUNCH(CM)                                                                                      \
   do {                                                                                                               \
     if (short_seg)                                                                                                   \
-      hipLaunchKernelGGL((sta_stream_short_kernel<DQ, D, CM>), dim3(blocks), dim3(256), 0, a.stream,               \
+      hipLaunchKernelGGL((sta_stream_short_kernel<DQ, D, CM, HEADS>), dim3(blocks), dim3(256), 0, a.stream,               \
                          (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v,       \
                          a.lens, a.C, a.L, a.w, a.S, spg, groups, nsl, (unsigned short*)a.seg_out, a.seg_cnt);     \
     else                                                                                                             \
-      hipLaunchKernelGGL((sta_stream_kernel<DQ, D, CM>), dim3(blocks), dim3(256), 0, a.stream,                     \
+      hipLaunchKernelGGL((sta_stream_kernel<DQ, D, CM, HEADS>), dim3(blocks), dim3(256), 0, a.stream,                     \
                          (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v,       \
                          a.lens, a.C, a.L, a.w, a.S, spg, groups, nsl, (unsigned short*)a.seg_out, a.seg_cnt);     \
   } while (0)
@@ -410,15 +417,20 @@ laser_status sta_stream_launch(const StaArgs& a) {
   if (!sta_stream_supports(a)) return LASER_ERR_UNSUPPORTED;
   const float nsl = -1.4426950408889634f / a.gamma;
   const int key = a.d_q * 1000 + a.d;
+#define LASER_STREAM_SHAPE(DQ_, D_)                    \
+  if (a.heads == 2) launch_c<DQ_, D_, 2>(a, nsl);      \
+  else launch_c<DQ_, D_, 1>(a, nsl);                   \
+  break
   switch (key) {
-    case 32064: launch_c<32, 64>(a, nsl); break;
-    case 32128: launch_c<32, 128>(a, nsl); break;
-    case 64064: launch_c<64, 64>(a, nsl); break;
-    case 64128: launch_c<64, 128>(a, nsl); break;
-    case 128064: launch_c<128, 64>(a, nsl); break;
-    case 128128: launch_c<128, 128>(a, nsl); break;
+    case 32064: LASER_STREAM_SHAPE(32, 64);
+    case 32128: LASER_STREAM_SHAPE(32, 128);
+    case 64064: LASER_STREAM_SHAPE(64, 64);
+    case 64128: LASER_STREAM_SHAPE(64, 128);
+    case 128064: LASER_STREAM_SHAPE(128, 64);
+    case 128128: LASER_STREAM_SHAPE(128, 128);
     default: return LASER_ERR_UNSUPPORTED;
   }
+#undef LASER_STREAM_SHAPE
   return launch_status();
 }
 

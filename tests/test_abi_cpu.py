@@ -170,3 +170,16 @@ def test_projection_argument_validation(lib):
     assert _proj_kv(lib, variant=2) == UNSUP          # the matrix-core form does not take d_in = 16
     assert _proj_kv(lib, variant=2, din=128, dq=48, d=128) == UNSUP   # widths must be multiples of 32
     assert _proj_q(lib, variant=2, din=128, dq=128, dt=0) == UNSUP    # bf16 only
+
+
+def test_sta_heads_argument_validation(lib):
+    NULL, SHAPE, UNSUP = 1, 2, 4
+    f = lambda heads=2, dq=16, d=16, variant=0, q=A, C=3: lib.laser_sta_forward_heads(
+        q, A, A, None, 2, C, 64, dq, d, 8, 1.0, heads, 1, A, None, None, variant)
+    assert f(q=None) == NULL
+    for kw in ({"heads": 0}, {"heads": -2}, {"heads": 65}, {"heads": 3}, {"heads": 4, "dq": 16, "d": 24 + 2},
+               {"heads": 2, "dq": 24, "d": 8 * 3 + 8 + 1}):
+        assert f(**kw) == SHAPE, kw
+    assert f(variant=9) == UNSUP
+    assert f(heads=2, dq=128, d=128, C=64, variant=2) == UNSUP     # the matrix-core kernel takes one head
+    assert f(heads=4, dq=32, d=128, variant=3) == UNSUP            # the streaming kernel takes one or two
