@@ -294,6 +294,51 @@ def project_qkv(t, H, Wq, Wk, Wv):
     return project_rows(t, Wq), project_rows(H, Wk), project_rows(H, Wv)
 
 
+def fold_query_weights(Wq: np.ndarray, Wk: np.ndarray, heads: int) -> np.ndarray:
+    """A [d_in, heads * d_in] with A[:, h d_in + k] = sum_x W_q[:, h a + x] W_k[k, h a + x], a = d_q / heads: the
+    matrix that takes a target embedding straight to the vector its head-h score is a dot product of with a raw
+    history item, q_h . k_j,h = (t W_q)_h . (h_j W_k)_h = (t A_h) . h_j (Sec. 3.5.1: the matrices do not depend on
+    the position, so products may be re-associated)."""
+    Wq, Wk = np.asarray(Wq, dtype=np.float64), np.asarray(Wk, dtype=np.float64)
+    d_in, dq = Wq.shape
+    if Wk.shape != (d_in, dq) or heads < 1 or dq % heads:
+        raise ValueError("W_q and W_k must be [d_in, d_q] with heads dividing d_q")
+    a = dq // heads
+    A = np.zeros((d_in, heads * d_in), dtype=np.float64)
+    for h in range(heads):
+        A[:, h * d_in:(h + 1) * d_in] = Wq[:, h * a:(h + 1) * a] @ Wk[:, h * a:(h + 1) * a].T
+    return A
+
+
+def project_heads(G: np.ndarray, Wv: np.ndarray, heads: int) -> np.ndarray:
+    """out[p, i, h b:(h+1) b] = G[p, h, i, :] W_v[:, h b:(h+1) b], b = d / heads: the value projection applied after
+    the gated sums (sum_j g_j (h_j W_v) = (sum_j g_j h_j) W_v), head h with its own columns of W_v.
+    G [P, heads, S, d_in], W_v [d_in, d] -> [P, S, d]."""
+    G, Wv = np.asarray(G, dtype=np.float64), np.asarray(Wv, dtype=np.float64)
+    P, H, S, d_in = G.shape
+    d = Wv.shape[1]
+    if H != heads or Wv.shape[0] != d_in or d % heads:
+        raise ValueError("shapes disagree")
+    b = d // heads
+    out = np.zeros((P, S, d), dtype=np.float64)
+    for h in range(heads):
+        out[:, :, h * b:(h + 1) * b] = G[:, h] @ Wv[:, h * b:(h + 1) * b]
+    return out
+
+
+def sta_folded_forward(t, H, Wq, Wk, Wv, lens, w: int, gamma: float, heads: int = 1):
+    """H' [U,C,S,d] and cnt [U,S] from the raw embeddings t [U,C,d_in], H [U,L,d_in] without forming K and V: the
+    folded queries t A, STA over the raw history with one pseudo-candidate per (candidate, head) and the raw items as
+    keys and values, then the value projection per head. Equal, in exact arithmetic, to projections followed by STA."""
+    t, H = np.asarray(t, dtype=np.float64), np.asarray(H, dtype=np.float64)
+    U, C, d_in = t.shape
+    qf = project_rows(t, fold_query_weights(Wq, Wk, heads)).reshape(U, C * heads, d_in)
+    G, cnt = sta_forward(qf, H, H, lens, w, gamma)                    # [U, C*heads, S, d_in]
+    S = G.shape[2]
+    out = project_heads(G.reshape(U * C, heads, S, d_in), Wv, heads)
+    return out.reshape(U, C, S, -1), cnt
+
+
 def laser_forward(q, k, v, t0, wq, wk, wv, lens, w: int, gamma: float):
     """STA followed by GSTA. Returns (H' [U,C,S,d], cnt [U,S], z [U,C,d])."""
     Hp, cnt = sta_forward(q, k, v, lens, w, gamma)

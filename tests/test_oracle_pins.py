@@ -557,3 +557,42 @@ def test_heads_special_cases_and_invariants():
     # batch form
     Hb, _ = oracle.sta_forward(q[None, None], K[None], V[None], [n], w, gamma, heads=2)
     assert np.array_equal(Hb[0, 0], base)
+
+
+# ------------------------------------------------------------------ folded form (Sec. 3.5.1 re-association)
+def test_folded_weights_and_head_projection_brute_force():
+    rng = np.random.default_rng(404)
+    din, dq, d, heads, P, S = 5, 6, 4, 2, 3, 4
+    Wq, Wk, Wv = rng.normal(size=(din, dq)), rng.normal(size=(din, dq)), rng.normal(size=(din, d))
+    A = lo.fold_query_weights(Wq, Wk, heads)
+    a, b = dq // heads, d // heads
+    for h in range(heads):
+        for r in range(din):
+            for k in range(din):
+                assert abs(A[r, h * din + k] - sum(Wq[r, h * a + x] * Wk[k, h * a + x] for x in range(a))) < 1e-13
+    G = rng.normal(size=(P, heads, S, din))
+    out = lo.project_heads(G, Wv, heads)
+    for p in range(P):
+        for i in range(S):
+            for e in range(d):
+                assert abs(out[p, i, e] - sum(G[p, e // b, i, k] * Wv[k, e] for k in range(din))) < 1e-13
+    # the defining property of A: (t A_h) . x = (t W_q)_h . (x W_k)_h for any t, x
+    t, x = rng.normal(size=din), rng.normal(size=din)
+    for h in range(heads):
+        lhs = (t @ A[:, h * din:(h + 1) * din]) @ x
+        rhs = (t @ Wq)[h * a:(h + 1) * a] @ (x @ Wk)[h * a:(h + 1) * a]
+        assert abs(lhs - rhs) < 1e-12
+
+
+@pytest.mark.parametrize("heads", [1, 2, 3])
+def test_folded_form_equals_projections_then_sta(heads):
+    rng = np.random.default_rng(405 + heads)
+    U, C, L, w, din, dq, d, gamma = 2, 3, 19, 4, 5, 6, 12, 1.3
+    t, H = rng.normal(size=(U, C, din)), rng.normal(size=(U, L, din))
+    Wq, Wk, Wv = rng.normal(size=(din, dq)), rng.normal(size=(din, dq)), rng.normal(size=(din, d))
+    lens = [19, 6]
+    Q, K, V = oracle.project_qkv(t, H, Wq, Wk, Wv)
+    direct, cnt = oracle.sta_forward(Q, K, V, lens, w, gamma, heads=heads)
+    folded, cnt2 = oracle.sta_folded_forward(t, H, Wq, Wk, Wv, lens, w, gamma, heads)
+    assert np.array_equal(cnt, cnt2)
+    assert np.allclose(direct, folded, rtol=1e-11, atol=1e-12)
