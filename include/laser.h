@@ -230,6 +230,38 @@ laser_status laser_project_kv_forward_variant(const void* h, const void* w_k, co
                                               int d_q, int d, laser_dtype dt, void* k_out, void* v_out, void* stream,
                                               laser_project_variant variant);
 
+/*
+ * Folded form of projections + STA for few candidates per user (paper Sec. 3.5.1: the matrices do not depend on the
+ * position, so the products can be re-associated; here that is taken one step further than the paper does). K and V
+ * are never formed and the raw history is read once:
+ *   score of head h for item j   (t W_q)_h . (h_j W_k)_h  =  (t A_h) . h_j,     A_h = W_q,h W_k,h^T  [d_in, d_in]
+ *   segment vector of head h     sum_j g_j (h_j W_v,h)    =  (sum_j g_j h_j) W_v,h
+ * with W_x,h head h's run of columns (d_q / heads of W_q and W_k, d / heads of W_v), as in laser_sta_forward_heads.
+ *
+ * laser_fold_query_weights: a_out [d_in, heads * d_in] dt, A = [A_1 | ... | A_heads], from w_q, w_k [d_in, d_q] dt
+ *   (fp32 sums rounded once to dt). Done once per model.
+ * laser_project_heads_forward: y[p, i, h b + e] = sum_k x[p, h, i, k] w_v[k, h b + e], b = d / heads;
+ *   x [P, heads, S, d_in] dt, w_v [d_in, d] dt, y [P, S, d] dt. d_in, d multiples of 8, heads divides d.
+ * laser_sta_folded_forward: the whole chain from raw embeddings to H':
+ *   qf_work [U, C * heads, d_in] dt   <- t A                      (laser_project_q_forward with A)
+ *   g_work  [U, C * heads, S, d_in] dt <- STA(qf_work, h, h)      (laser_sta_forward: keys = values = raw items)
+ *   seg_out [U, C, S, d] dt           <- laser_project_heads_forward(g_work, w_v)
+ *   t [U,C,d_in], h [U,L,d_in], a_fold from laser_fold_query_weights, lens / seg_cnt / gamma as for
+ *   laser_sta_forward. The two work buffers are caller-owned scratch (contents on return: the intermediates above,
+ *   each rounded to dt); the library allocates nothing. Equal to projections followed by STA in exact arithmetic;
+ *   in bf16 the intermediates are rounded at other places, so the two forms differ within the tolerance.
+ * All pointers are device pointers, caller-owned, 16-byte aligned (lens, seg_cnt 4-byte); work is enqueued on
+ * `stream`. Errors as for laser_sta_forward and laser_project_kv_forward; nothing is launched on an error.
+ */
+laser_status laser_fold_query_weights(const void* w_q, const void* w_k, int d_in, int d_q, int heads, laser_dtype dt,
+                                      void* a_out, void* stream);
+laser_status laser_project_heads_forward(const void* x, const void* w_v, int P, int S, int d_in, int d, int heads,
+                                         laser_dtype dt, void* y, void* stream, laser_project_variant variant);
+laser_status laser_sta_folded_forward(const void* t, const void* h, const void* a_fold, const void* w_v,
+                                      const int32_t* lens, int U, int C, int L, int d_in, int d, int w, float gamma,
+                                      int heads, laser_dtype dt, void* qf_work, void* g_work, void* seg_out,
+                                      int32_t* seg_cnt, void* stream);
+
 /* Name of the STA / GSTA kernel AUTO would pick for a shape (static strings; host only, no GPU needed). */
 const char* laser_sta_kernel_name(int C, int d_q, int d, int w, laser_dtype dt);
 const char* laser_gsta_kernel_name(int C, int S, int d, laser_dtype dt);               /* one layer (M = 1) */

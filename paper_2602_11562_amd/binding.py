@@ -25,7 +25,8 @@ EXPORTS = [
     "laser_forward", "laser_multires_forward", "laser_forward_multires", "laser_sta_kernel_name",
     "laser_gsta_kernel_name", "laser_segment_ffn_forward", "laser_segment_ffn_forward_variant",
     "laser_gsta_kernel_name_layers", "laser_project_q_forward", "laser_project_q_forward_variant",
-    "laser_project_kv_forward", "laser_project_kv_forward_variant", "laser_status_string", "laser_version",
+    "laser_project_kv_forward", "laser_project_kv_forward_variant", "laser_fold_query_weights",
+    "laser_project_heads_forward", "laser_sta_folded_forward", "laser_status_string", "laser_version",
 ]
 
 
@@ -75,6 +76,12 @@ def load_library() -> ctypes.CDLL:
     lib.laser_project_kv_forward_variant.argtypes = lib.laser_project_kv_forward.argtypes + [i32]
     for name in ("laser_project_q_forward", "laser_project_q_forward_variant", "laser_project_kv_forward",
                  "laser_project_kv_forward_variant"):
+        getattr(lib, name).restype = i32
+    lib.laser_fold_query_weights.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp]
+    lib.laser_project_heads_forward.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, i32]
+    lib.laser_sta_folded_forward.argtypes = [vp, vp, vp, vp, ip, i32, i32, i32, i32, i32, i32, f32, i32, i32,
+                                             vp, vp, vp, ip, vp]
+    for name in ("laser_fold_query_weights", "laser_project_heads_forward", "laser_sta_folded_forward"):
         getattr(lib, name).restype = i32
     lib.laser_sta_kernel_name.argtypes = [i32, i32, i32, i32, i32]
     lib.laser_sta_kernel_name.restype = ctypes.c_char_p
@@ -267,6 +274,71 @@ def laser_project_kv_forward(h, w_k, w_v, k_out=None, v_out=None, stream=None, v
         _ptr(v_out, "v_out", h.dtype), _stream(stream), int(variant))
     _check(code, "laser_project_kv_forward")
     return k_out, v_out
+
+
+def laser_fold_query_weights(w_q, w_k, heads: int = 1, a_out=None, stream=None):
+    """A = [W_q,h W_k,h^T for every head] : w_q, w_k [d_in, d_q] -> [d_in, heads * d_in] (same dtype)."""
+    torch = _torch()
+    d_in, d_q = w_q.shape
+    if tuple(w_k.shape) != (d_in, d_q) or w_k.dtype != w_q.dtype:
+        raise ValueError("w_q and w_k must both be [d_in, d_q] in one dtype")
+    if a_out is None:
+        a_out = torch.empty((d_in, heads * d_in), dtype=w_q.dtype, device=w_q.device)
+    code = load_library().laser_fold_query_weights(_ptr(w_q, "w_q"), _ptr(w_k, "w_k"), d_in, d_q, int(heads), _dt(w_q),
+                                                   _ptr(a_out, "a_out", w_q.dtype), _stream(stream))
+    _check(code, "laser_fold_query_weights")
+    return a_out
+
+
+def laser_project_heads_forward(x, w_v, y=None, stream=None, variant: int = PROJECT_AUTO):
+    """x [P, heads, S, d_in], w_v [d_in, d] -> y [P, S, d]: head h's columns of w_v applied to x[:, h]."""
+    torch = _torch()
+    P, heads, S, d_in = x.shape
+    if w_v.dim() != 2 or w_v.shape[0] != d_in or w_v.dtype != x.dtype:
+        raise ValueError("w_v must be [d_in, d] in the dtype of x")
+    d = w_v.shape[1]
+    if y is None:
+        y = torch.empty((P, S, d), dtype=x.dtype, device=x.device)
+    elif tuple(y.shape) != (P, S, d):
+        raise ValueError("y must be [P, S, d]")
+    code = load_library().laser_project_heads_forward(_ptr(x, "x"), _ptr(w_v, "w_v"), P, S, d_in, d, heads, _dt(x),
+                                                      _ptr(y, "y", x.dtype), _stream(stream), int(variant))
+    _check(code, "laser_project_heads_forward")
+    return y
+
+
+def laser_sta_folded_forward(t, h, a_fold, w_v, lens, w: int, gamma: float, heads: int = 1, qf_work=None, g_work=None,
+                             seg_out=None, seg_cnt=None, stream=None, want_cnt: bool = True):
+    """Raw embeddings t [U,C,d_in], h [U,L,d_in] -> (H' [U,C,S,d], cnt [U,S] or None) without forming K and V.
+    a_fold comes from laser_fold_query_weights. Pass your own work buffers (qf_work [U,C*heads,d_in],
+    g_work [U,C*heads,S,d_in]) to reuse them across calls; otherwise they are allocated here, by torch."""
+    torch = _torch()
+    U, C, d_in = t.shape
+    L = h.shape[1]
+    d = w_v.shape[1]
+    S = -(-L // w)
+    if tuple(h.shape) != (U, L, d_in) or tuple(a_fold.shape) != (d_in, heads * d_in) or w_v.shape[0] != d_in:
+        raise ValueError("t, h, a_fold, w_v shapes disagree")
+    if any(x.dtype != t.dtype for x in (h, a_fold, w_v)):
+        raise TypeError("t, h, a_fold and w_v must share a dtype")
+    if qf_work is None:
+        qf_work = torch.empty((U, C * heads, d_in), dtype=t.dtype, device=t.device)
+    if g_work is None:
+        g_work = torch.empty((U, C * heads, S, d_in), dtype=t.dtype, device=t.device)
+    if seg_out is None:
+        seg_out = torch.empty((U, C, S, d), dtype=t.dtype, device=t.device)
+    if seg_cnt is None and want_cnt:
+        seg_cnt = torch.empty((U, S), dtype=torch.int32, device=t.device)
+    if tuple(qf_work.shape) != (U, C * heads, d_in) or tuple(g_work.shape) != (U, C * heads, S, d_in) or \
+            tuple(seg_out.shape) != (U, C, S, d):
+        raise ValueError("work / output buffer shapes disagree")
+    code = load_library().laser_sta_folded_forward(
+        _ptr(t, "t"), _ptr(h, "h"), _ptr(a_fold, "a_fold"), _ptr(w_v, "w_v"), _ptr(lens, "lens", torch.int32), U, C, L,
+        d_in, d, int(w), float(gamma), int(heads), _dt(t), _ptr(qf_work, "qf_work", t.dtype),
+        _ptr(g_work, "g_work", t.dtype), _ptr(seg_out, "seg_out", t.dtype), _ptr(seg_cnt, "seg_cnt", torch.int32),
+        _stream(stream))
+    _check(code, "laser_sta_folded_forward")
+    return seg_out, seg_cnt
 
 
 def laser_forward_multires(q, k, v, t0, wq, wk, wv, lens, w: int, gamma: float, r: int, seg_out=None, seg_cnt=None,

@@ -281,6 +281,71 @@ laser_status laser_project_kv_forward(const void* h, const void* w_k, const void
   return laser_project_kv_forward_variant(h, w_k, w_v, U, L, d_in, d_q, d, dt, k_out, v_out, stream, LASER_PROJECT_AUTO);
 }
 
+laser_status laser_fold_query_weights(const void* w_q, const void* w_k, int d_in, int d_q, int heads, laser_dtype dt,
+                                      void* a_out, void* stream) {
+  if (!w_q || !w_k || !a_out) return LASER_ERR_NULL;
+  if (dt != LASER_F32 && dt != LASER_BF16) return LASER_ERR_DTYPE;
+  if (d_in <= 0 || d_in > 4096 || d_q <= 0 || d_q > 4096 || heads < 1 || heads > 64 || d_q % heads != 0)
+    return LASER_ERR_SHAPE;
+  if (!aligned16(w_q) || !aligned16(w_k) || !aligned16(a_out)) return LASER_ERR_ALIGN;
+  return fold_weights_launch(w_q, w_k, d_in, d_q, heads, dt, a_out, static_cast<hipStream_t>(stream));
+}
+
+static laser_status validate_project_heads(const void* x, const void* w_v, int P, int S, int d_in, int d, int heads,
+                                           laser_dtype dt, void* y, void* stream, ProjHeadsArgs* out) {
+  if (!x || !w_v || !y) return LASER_ERR_NULL;
+  if (dt != LASER_F32 && dt != LASER_BF16) return LASER_ERR_DTYPE;
+  if (P <= 0 || S <= 0 || d_in <= 0 || d_in > 4096 || d <= 0 || d > 4096 || heads < 1 || heads > 64 || d % heads != 0)
+    return LASER_ERR_SHAPE;
+  if ((d_in % 8) != 0 || (d % 8) != 0) return LASER_ERR_SHAPE;
+  if ((long long)P * heads * S * d_in > 0x7fffffffLL || (long long)P * S * d > 0x7fffffffLL) return LASER_ERR_SHAPE;
+  if (!aligned16(x) || !aligned16(w_v) || !aligned16(y)) return LASER_ERR_ALIGN;
+  *out = ProjHeadsArgs{x, w_v, (long long)P, S, d_in, d, heads, dt, y, static_cast<hipStream_t>(stream)};
+  return LASER_OK;
+}
+
+static laser_status run_project_heads(const ProjHeadsArgs& a, laser_project_variant variant) {
+  if (variant == LASER_PROJECT_AUTO)
+    variant = project_heads_mfma_supports(a) ? LASER_PROJECT_MFMA : LASER_PROJECT_GENERIC;
+  return variant == LASER_PROJECT_MFMA ? project_heads_mfma_launch(a) : project_heads_generic_launch(a);
+}
+
+laser_status laser_project_heads_forward(const void* x, const void* w_v, int P, int S, int d_in, int d, int heads,
+                                         laser_dtype dt, void* y, void* stream, laser_project_variant variant) {
+  ProjHeadsArgs a;
+  laser_status s = validate_project_heads(x, w_v, P, S, d_in, d, heads, dt, y, stream, &a);
+  if (s != LASER_OK) return s;
+  if (variant < LASER_PROJECT_AUTO || variant > LASER_PROJECT_MFMA) return LASER_ERR_UNSUPPORTED;
+  return run_project_heads(a, variant);
+}
+
+laser_status laser_sta_folded_forward(const void* t, const void* h, const void* a_fold, const void* w_v,
+                                      const int32_t* lens, int U, int C, int L, int d_in, int d, int w, float gamma,
+                                      int heads, laser_dtype dt, void* qf_work, void* g_work, void* seg_out,
+                                      int32_t* seg_cnt, void* stream) {
+  if (!t || !a_fold || !qf_work) return LASER_ERR_NULL;
+  if (heads < 1 || heads > 64 || C <= 0 || (long long)C * heads > 0x7fffffffLL) return LASER_ERR_SHAPE;
+  if (!aligned16(t) || !aligned16(a_fold)) return LASER_ERR_ALIGN;
+  StaArgs sa;
+  ProjHeadsArgs pa;
+  // STA over the raw history: one pseudo-candidate per (candidate, head), the raw items as keys and values
+  laser_status s = validate_sta(qf_work, h, h, lens, U, C * heads, L, d_in, d_in, w, gamma, dt, g_work, seg_cnt, stream,
+                                &sa);
+  if (s != LASER_OK) return s;
+  if ((long long)U * C > 0x7fffffffLL) return LASER_ERR_SHAPE;
+  s = validate_project_heads(g_work, w_v, U * C, sa.S, d_in, d, heads, dt, seg_out, stream, &pa);
+  if (s != LASER_OK) return s;   // everything validated before the first launch
+  ProjArgs qa{t, (long long)U * C, d_in, {a_fold, nullptr}, {heads * d_in, 0}, {qf_work, nullptr}, dt,
+              static_cast<hipStream_t>(stream)};
+  if (qa.n[0] > 4096) return LASER_ERR_SHAPE;
+  s = run_project(qa, LASER_PROJECT_AUTO);
+  if (s != LASER_OK) return s;
+  sa.reread = true;
+  s = run_sta(sa, LASER_STA_AUTO);
+  if (s != LASER_OK) return s;
+  return run_project_heads(pa, LASER_PROJECT_AUTO);
+}
+
 const char* laser_sta_kernel_name(int C, int d_q, int d, int w, laser_dtype dt) {
   StaArgs a{};
   a.U = 1; a.C = C; a.L = w > 0 ? w : 1; a.d_q = d_q; a.d = d; a.w = w; a.S = 1; a.gamma = 1.0f; a.dt = dt;

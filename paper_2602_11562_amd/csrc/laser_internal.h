@@ -86,6 +86,21 @@ laser_status project_generic_launch(const ProjArgs& a);
 bool project_mfma_supports(const ProjArgs& a);
 laser_status project_mfma_launch(const ProjArgs& a);
 
+struct ProjHeadsArgs {     // y[p, i, h b + e] = sum_k x[p, h, i, k] wv[k, h b + e], b = d / heads
+  const void* x;           // [P, heads, S, d_in]
+  const void* wv;          // [d_in, d]
+  long long P;
+  int S, d_in, d, heads;
+  laser_dtype dt;
+  void* y;                 // [P, S, d]
+  hipStream_t stream;
+};
+laser_status project_heads_generic_launch(const ProjHeadsArgs& a);
+bool project_heads_mfma_supports(const ProjHeadsArgs& a);
+laser_status project_heads_mfma_launch(const ProjHeadsArgs& a);
+laser_status fold_weights_launch(const void* wq, const void* wk, int d_in, int d_q, int heads, laser_dtype dt,
+                                 void* a_out, hipStream_t stream);
+
 // Each launcher returns LASER_ERR_UNSUPPORTED (launching nothing) when the shape is outside its range.
 bool sta_generic_supports(const StaArgs& a);
 laser_status sta_generic_launch(const StaArgs& a);

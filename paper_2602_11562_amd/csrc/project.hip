@@ -192,6 +192,190 @@ __global__ __launch_bounds__(PM_THREADS) void project_mfma_kernel(const unsigned
   }
 }
 
+// ------------------------------------------------------------------------------------------ folded form
+// With few candidates per user it is cheaper not to form K and V at all (Sec. 3.5.1: the matrices do not depend on
+// the position, so the products can be re-associated): the score of head h is (t A_h) . h_j with
+// A_h = W_q,h W_k,h^T, the gated sums run over the raw items, and W_v is applied to the S segment sums instead of
+// the L items. fold_weights_kernel forms A = [A_1 | ... | A_heads] once per model; the STA kernels then run with one
+// pseudo-candidate per (candidate, head) and the raw history as keys and values; project_heads_* apply head h's
+// columns of W_v to that head's sums and lay the results side by side:
+//   y[p, i, h b + e] = sum_k x[p, h, i, k] W_v[k, h b + e],   b = d / heads,   x [P, heads, S, d_in], y [P, S, d].
+template <typename T>
+__global__ __launch_bounds__(256) void fold_weights_kernel(const T* __restrict__ wq, const T* __restrict__ wk, int d_in,
+                                                           int d_q, int heads, T* __restrict__ a_out) {
+  const long long total = (long long)d_in * heads * d_in;
+  const int a = d_q / heads;
+  for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long long)gridDim.x * 256) {
+    const int r = (int)(e / ((long long)heads * d_in));
+    const int c = (int)(e % ((long long)heads * d_in));
+    const int h = c / d_in, kk = c % d_in;
+    float acc = 0.0f;
+    for (int x = 0; x < a; ++x)
+      acc = fmaf(load_as_f32(wq, (size_t)r * d_q + h * a + x), load_as_f32(wk, (size_t)kk * d_q + h * a + x), acc);
+    store_from_f32(a_out, (size_t)e, acc);
+  }
+}
+
+laser_status fold_weights_launch(const void* wq, const void* wk, int d_in, int d_q, int heads, laser_dtype dt,
+                                 void* a_out, hipStream_t stream) {
+  const long long total = (long long)d_in * heads * d_in;
+  const unsigned blocks = (unsigned)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
+  if (dt == LASER_BF16)
+    hipLaunchKernelGGL(fold_weights_kernel<unsigned short>, dim3(blocks), dim3(256), 0, stream,
+                       (const unsigned short*)wq, (const unsigned short*)wk, d_in, d_q, heads, (unsigned short*)a_out);
+  else
+    hipLaunchKernelGGL(fold_weights_kernel<float>, dim3(blocks), dim3(256), 0, stream, (const float*)wq,
+                       (const float*)wk, d_in, d_q, heads, (float*)a_out);
+  return launch_status();
+}
+
+template <typename T>
+__global__ __launch_bounds__(PG_THREADS) void project_heads_generic_kernel(const T* __restrict__ x,
+                                                                           const T* __restrict__ wv, long long rows,
+                                                                           int S, int d_in, int d, int heads,
+                                                                           T* __restrict__ y) {
+  extern __shared__ float xs[];            // [PG_ROWS][heads][d_in]
+  const int tid = threadIdx.x;
+  const long long row0 = (long long)blockIdx.x * PG_ROWS;
+  const int per_row = heads * d_in;
+  for (int e = tid; e < PG_ROWS * per_row; e += PG_THREADS) {
+    const int rr = e / per_row, rem = e - rr * per_row;
+    const int h = rem / d_in, c = rem - h * d_in;
+    const long long r = row0 + rr;
+    float val = 0.0f;
+    if (r < rows) {
+      const long long p = r / S;
+      const int i = (int)(r - p * S);
+      val = load_as_f32(x, (size_t)(((p * heads + h) * S + i) * d_in + c));
+    }
+    xs[e] = val;
+  }
+  __syncthreads();
+  const int b = d / heads;
+  for (int j = tid; j < d; j += PG_THREADS) {
+    const int h = j / b;
+    float acc[PG_ROWS];
+#pragma unroll
+    for (int rr = 0; rr < PG_ROWS; ++rr) acc[rr] = 0.0f;
+    for (int e = 0; e < d_in; ++e) {
+      const float w = load_as_f32(wv, (size_t)e * d + j);
+#pragma unroll
+      for (int rr = 0; rr < PG_ROWS; ++rr) acc[rr] = fmaf(xs[(rr * heads + h) * d_in + e], w, acc[rr]);
+    }
+#pragma unroll
+    for (int rr = 0; rr < PG_ROWS; ++rr)
+      if (row0 + rr < rows) store_from_f32(y, (size_t)(row0 + rr) * d + j, acc[rr]);
+  }
+}
+
+laser_status project_heads_generic_launch(const ProjHeadsArgs& a) {
+  const size_t lds = (size_t)PG_ROWS * a.heads * a.d_in * sizeof(float);
+  if (lds > 150 * 1024) return LASER_ERR_UNSUPPORTED;
+  const long long rows = a.P * a.S;
+  const long long blocks = (rows + PG_ROWS - 1) / PG_ROWS;
+  if (blocks > 0x7fffffffLL) return LASER_ERR_SHAPE;
+  if (blocks == 0) return LASER_OK;
+  if (a.dt == LASER_BF16) {
+    auto kern = project_heads_generic_kernel<unsigned short>;
+    if (lds > 48 * 1024 &&
+        hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return LASER_ERR_LAUNCH;
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(PG_THREADS), lds, a.stream, (const unsigned short*)a.x,
+                       (const unsigned short*)a.wv, rows, a.S, a.d_in, a.d, a.heads, (unsigned short*)a.y);
+  } else {
+    auto kern = project_heads_generic_kernel<float>;
+    if (lds > 48 * 1024 &&
+        hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return LASER_ERR_LAUNCH;
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(PG_THREADS), lds, a.stream, (const float*)a.x,
+                       (const float*)a.wv, rows, a.S, a.d_in, a.d, a.heads, (float*)a.y);
+  }
+  return launch_status();
+}
+
+// Matrix-core form of the same: project_mfma_kernel with one output, whose 32 rows are re-read per head from that
+// head's block of x (row r = p S + i of head h lies at ((p heads + h) S + i) d_in) before the head's column tiles.
+__global__ __launch_bounds__(PM_THREADS) void project_heads_mfma_kernel(const unsigned short* __restrict__ x,
+                                                                        const unsigned short* __restrict__ wv,
+                                                                        long long rows, int S, int d, int heads,
+                                                                        unsigned short* __restrict__ y) {
+  constexpr int D = PM_D, KSTEPS = D / 16;
+  constexpr int WP = D * 2 + 16, OP = PM_OMAX * 2 + 16;
+  __shared__ __attribute__((aligned(16))) unsigned char WT[PM_OMAX * WP];
+  __shared__ __attribute__((aligned(16))) unsigned char patch[PM_WAVES * PM_ROWS * OP];
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  for (int e = tid; e < D * d / 8; e += PM_THREADS) {   // W_v transposed, as in project_mfma_kernel
+    const int kk = e % D, n0 = (e / D) * 8;
+    const u32x4 raw = *reinterpret_cast<const u32x4*>(wv + (size_t)kk * d + n0);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const unsigned short val = (unsigned short)((raw[j >> 1] >> ((j & 1) * 16)) & 0xffffu);
+      *reinterpret_cast<unsigned short*>(WT + (n0 + j) * WP + kk * 2) = val;
+    }
+  }
+  __syncthreads();
+  const unsigned char* wlane = WT + l32 * WP + h * 16;
+  unsigned char* opatch = patch + wave * PM_ROWS * OP;
+  const int tiles_per_head = d / heads / 32;
+  const int lpr = d / 8;
+  const long long ntiles = (rows + PM_ROWS - 1) / PM_ROWS;
+  for (long long t = (long long)blockIdx.x * PM_WAVES + wave; t < ntiles; t += (long long)gridDim.x * PM_WAVES) {
+    const long long r0 = t * PM_ROWS;
+    long long r = r0 + l32;
+    r = r < rows ? r : rows - 1;           // rows past the end repeat the last one; never stored
+    const long long p = r / S;
+    const int i = (int)(r - p * S);
+    const f32x16 zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll 1
+    for (int hd = 0; hd < heads; ++hd) {
+      bf16x8 xreg[KSTEPS];
+      const unsigned short* xr = x + (size_t)(((p * heads + hd) * S + i) * D) + h * 8;
+#pragma unroll
+      for (int ks = 0; ks < KSTEPS; ++ks) xreg[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(xr + ks * 16));
+#pragma unroll 1
+      for (int jt = 0; jt < tiles_per_head; ++jt) {
+        const int j = hd * tiles_per_head + jt;
+        const unsigned char* a1 = wlane + j * 32 * WP;
+        bf16x8 wr[KSTEPS];
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) wr[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(a1 + ks * 32));
+        f32x16 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[0], xreg[0], zero, 0, 0, 0);
+#pragma unroll
+        for (int ks = 1; ks < KSTEPS; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[ks], xreg[ks], acc, 0, 0, 0);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const bf16x4 o = {(__bf16)acc[4 * g], (__bf16)acc[4 * g + 1], (__bf16)acc[4 * g + 2], (__bf16)acc[4 * g + 3]};
+          *reinterpret_cast<u32x2*>(opatch + l32 * OP + (j * 32 + g * 8 + h * 4) * 2) = __builtin_bit_cast(u32x2, o);
+        }
+      }
+    }
+    for (int idx = lane; idx < PM_ROWS * lpr; idx += 64) {   // LDS operations of a wave execute in order: no barrier
+      const int rr = idx / lpr, c = idx - rr * lpr;
+      const u32x4 val = *reinterpret_cast<const u32x4*>(opatch + rr * OP + c * 16);
+      if (r0 + rr < rows) *reinterpret_cast<u32x4*>(y + (size_t)(r0 + rr) * d + c * 8) = val;
+    }
+  }
+}
+
+bool project_heads_mfma_supports(const ProjHeadsArgs& a) {
+  if (a.dt != LASER_BF16 || a.d_in != PM_D || a.d > PM_OMAX || a.heads < 1) return false;
+  return a.d % a.heads == 0 && (a.d / a.heads) % 32 == 0;
+}
+
+laser_status project_heads_mfma_launch(const ProjHeadsArgs& a) {
+  if (!project_heads_mfma_supports(a)) return LASER_ERR_UNSUPPORTED;
+  const long long rows = a.P * a.S;
+  if (rows == 0) return LASER_OK;
+  const long long ntiles = (rows + PM_ROWS - 1) / PM_ROWS;
+  long long blocks = (ntiles + PM_WAVES - 1) / PM_WAVES;
+  if (blocks > 256) blocks = 256;
+  hipLaunchKernelGGL(project_heads_mfma_kernel, dim3((unsigned)blocks), dim3(PM_THREADS), 0, a.stream,
+                     (const unsigned short*)a.x, (const unsigned short*)a.wv, rows, a.S, a.d, a.heads,
+                     (unsigned short*)a.y);
+  return launch_status();
+}
+
 bool project_mfma_supports(const ProjArgs& a) {
   if (a.dt != LASER_BF16 || a.d_in != PM_D) return false;
   for (int o = 0; o < 2; ++o)

@@ -183,3 +183,23 @@ def test_sta_heads_argument_validation(lib):
     assert f(variant=9) == UNSUP
     assert f(heads=2, dq=128, d=128, C=64, variant=2) == UNSUP     # the matrix-core kernel takes one head
     assert f(heads=4, dq=32, d=128, variant=3) == UNSUP            # the streaming kernel takes one or two
+
+
+def test_folded_form_argument_validation(lib):
+    NULL, SHAPE, DTYPE, UNSUP, ALIGN = 1, 2, 3, 4, 6
+    fold = lambda wq=A, wk=A, din=16, dq=8, heads=2, dt=1, out=A: lib.laser_fold_query_weights(wq, wk, din, dq, heads, dt, out, None)
+    assert fold(wq=None) == NULL and fold(out=None) == NULL and fold(dt=9) == DTYPE
+    assert fold(heads=3) == SHAPE and fold(heads=0) == SHAPE and fold(din=0) == SHAPE and fold(wk=A + 8) == ALIGN
+    ph = lambda x=A, wv=A, P=4, S=5, din=16, d=16, heads=2, dt=1, y=A, variant=0: lib.laser_project_heads_forward(
+        x, wv, P, S, din, d, heads, dt, y, None, variant)
+    assert ph(x=None) == NULL and ph(y=None) == NULL and ph(dt=-1) == DTYPE
+    for kw in ({"P": 0}, {"S": 0}, {"din": 12}, {"d": 20}, {"heads": 3}, {"heads": 0}, {"P": 1 << 20, "S": 1 << 12}):
+        assert ph(**kw) == SHAPE, kw
+    assert ph(wv=A + 4) == ALIGN and ph(variant=7) == UNSUP and ph(variant=2) == UNSUP   # d_in = 16: no matrix-core form
+    fo = lambda t=A, h=A, a=A, wv=A, U=2, C=1, L=64, din=16, d=16, w=8, gamma=1.0, heads=2, dt=1, qf=A, g=A, out=A: \
+        lib.laser_sta_folded_forward(t, h, a, wv, None, U, C, L, din, d, w, gamma, heads, dt, qf, g, out, None, None)
+    for kw in ({"t": None}, {"h": None}, {"a": None}, {"wv": None}, {"qf": None}, {"g": None}, {"out": None}):
+        assert fo(**kw) == NULL, kw
+    for kw in ({"heads": 0}, {"heads": 3}, {"U": 0}, {"C": 0}, {"w": 0}, {"gamma": 0.0}, {"din": 12}):
+        assert fo(**kw) == SHAPE, kw
+    assert fo(dt=5) == DTYPE and fo(a=A + 8) == ALIGN and fo(g=A + 2) == ALIGN
