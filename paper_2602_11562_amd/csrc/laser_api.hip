@@ -259,7 +259,8 @@ laser_status laser_project_q_forward_variant(const void* t, const void* w_q, int
                                              laser_dtype dt, void* q_out, void* stream,
                                              laser_project_variant variant) {
   if (U <= 0 || C <= 0) return LASER_ERR_SHAPE;
-  ProjArgs a{t, (long long)U * C, d_in, {w_q, nullptr}, {d_q, 0}, {q_out, nullptr}, dt, static_cast<hipStream_t>(stream)};
+  ProjArgs a{t, (long long)U * C, d_in, {w_q, nullptr}, {d_q, 0}, {q_out, nullptr}, dt, static_cast<hipStream_t>(stream),
+             {d_q, 0}, {d_q, 0}};
   return run_project(a, variant);
 }
 
@@ -272,7 +273,8 @@ laser_status laser_project_kv_forward_variant(const void* h, const void* w_k, co
                                               int d_q, int d, laser_dtype dt, void* k_out, void* v_out, void* stream,
                                               laser_project_variant variant) {
   if (U <= 0 || L <= 0 || d <= 0) return LASER_ERR_SHAPE;
-  ProjArgs a{h, (long long)U * L, d_in, {w_k, w_v}, {d_q, d}, {k_out, v_out}, dt, static_cast<hipStream_t>(stream)};
+  ProjArgs a{h, (long long)U * L, d_in, {w_k, w_v}, {d_q, d}, {k_out, v_out}, dt, static_cast<hipStream_t>(stream),
+             {d_q, d}, {d_q, d}};
   return run_project(a, variant);
 }
 
@@ -335,9 +337,17 @@ laser_status laser_sta_folded_forward(const void* t, const void* h, const void* 
   if ((long long)U * C > 0x7fffffffLL) return LASER_ERR_SHAPE;
   s = validate_project_heads(g_work, w_v, U * C, sa.S, d_in, d, heads, dt, seg_out, stream, &pa);
   if (s != LASER_OK) return s;   // everything validated before the first launch
-  ProjArgs qa{t, (long long)U * C, d_in, {a_fold, nullptr}, {heads * d_in, 0}, {qf_work, nullptr}, dt,
-              static_cast<hipStream_t>(stream)};
-  if (qa.n[0] > 4096) return LASER_ERR_SHAPE;
+  const int nq = heads * d_in;
+  if (nq > 4096) return LASER_ERR_SHAPE;
+  ProjArgs qa{t, (long long)U * C, d_in, {a_fold, nullptr}, {nq, 0}, {qf_work, nullptr}, dt,
+              static_cast<hipStream_t>(stream), {nq, 0}, {nq, 0}};
+  if (heads == 2 && dt == LASER_BF16) {   // two heads: the halves of A and of the output as the kernel's two outputs
+    const size_t half = (size_t)d_in * 2;   // bytes
+    qa.w[1] = static_cast<const char*>(a_fold) + half;
+    qa.y[1] = static_cast<char*>(qf_work) + half;
+    qa.n[0] = qa.n[1] = d_in;
+    qa.wpitch[1] = qa.ypitch[1] = nq;
+  }
   s = run_project(qa, LASER_PROJECT_AUTO);
   if (s != LASER_OK) return s;
   sa.reread = true;

@@ -81,6 +81,8 @@ struct ProjArgs {          // Y_a = X W_a and, when n[1] > 0, Y_b = X W_b from t
   void* y[2];              // [rows, n[o]]
   laser_dtype dt;
   hipStream_t stream;
+  int wpitch[2];           // elements between rows of w[o] and of y[o]: n[o] unless the matrices are column blocks of
+  int ypitch[2];           // wider ones (the folded queries: two halves of one [d_in, 2 d_in] matrix and of its output)
 };
 laser_status project_generic_launch(const ProjArgs& a);
 bool project_mfma_supports(const ProjArgs& a);

@@ -17,8 +17,8 @@ constexpr int PG_ROWS = 8, PG_THREADS = 256;
 template <typename T>
 __global__ __launch_bounds__(PG_THREADS) void project_generic_kernel(const T* __restrict__ x, const T* __restrict__ wa,
                                                                      const T* __restrict__ wb, long long rows, int d_in,
-                                                                     int na, int nb, T* __restrict__ ya,
-                                                                     T* __restrict__ yb) {
+                                                                     int na, int nb, int wpa, int wpb, int ypa, int ypb,
+                                                                     T* __restrict__ ya, T* __restrict__ yb) {
   extern __shared__ float xs[];            // [PG_ROWS][d_in]
   const int tid = threadIdx.x;
   const long long row0 = (long long)blockIdx.x * PG_ROWS;
@@ -31,19 +31,19 @@ __global__ __launch_bounds__(PG_THREADS) void project_generic_kernel(const T* __
   for (int j = tid; j < na + nb; j += PG_THREADS) {   // output column j of the eight rows
     const bool second = j >= na;
     const T* w = second ? wb : wa;
-    const int n = second ? nb : na, col = second ? j - na : j;
+    const int col = second ? j - na : j, wp = second ? wpb : wpa, yp = second ? ypb : ypa;
     float acc[PG_ROWS];
 #pragma unroll
     for (int rr = 0; rr < PG_ROWS; ++rr) acc[rr] = 0.0f;
     for (int e = 0; e < d_in; ++e) {
-      const float wv = load_as_f32(w, (size_t)e * n + col);
+      const float wv = load_as_f32(w, (size_t)e * wp + col);
 #pragma unroll
       for (int rr = 0; rr < PG_ROWS; ++rr) acc[rr] = fmaf(xs[rr * d_in + e], wv, acc[rr]);
     }
     T* y = second ? yb : ya;
 #pragma unroll
     for (int rr = 0; rr < PG_ROWS; ++rr)
-      if (row0 + rr < rows) store_from_f32(y, (size_t)(row0 + rr) * n + col, acc[rr]);
+      if (row0 + rr < rows) store_from_f32(y, (size_t)(row0 + rr) * yp + col, acc[rr]);
   }
 }
 
@@ -60,15 +60,16 @@ laser_status project_generic_launch(const ProjArgs& a) {
       return LASER_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(PG_THREADS), lds, a.stream, (const unsigned short*)a.x,
                        (const unsigned short*)a.w[0], (const unsigned short*)a.w[1], a.rows, a.d_in, a.n[0], a.n[1],
-                       (unsigned short*)a.y[0], (unsigned short*)a.y[1]);
+                       a.wpitch[0], a.wpitch[1], a.ypitch[0], a.ypitch[1], (unsigned short*)a.y[0],
+                       (unsigned short*)a.y[1]);
   } else {
     auto kern = project_generic_kernel<float>;
     if (lds > 48 * 1024 &&
         hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
       return LASER_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(PG_THREADS), lds, a.stream, (const float*)a.x,
-                       (const float*)a.w[0], (const float*)a.w[1], a.rows, a.d_in, a.n[0], a.n[1], (float*)a.y[0],
-                       (float*)a.y[1]);
+                       (const float*)a.w[0], (const float*)a.w[1], a.rows, a.d_in, a.n[0], a.n[1], a.wpitch[0],
+                       a.wpitch[1], a.ypitch[0], a.ypitch[1], (float*)a.y[0], (float*)a.y[1]);
   }
   return launch_status();
 }
@@ -94,7 +95,8 @@ template <bool PF, bool NTS>   // PF: rows of the next tile requested one tile a
 __global__ __launch_bounds__(PM_THREADS) void project_mfma_kernel(const unsigned short* __restrict__ x,
                                                                   const unsigned short* __restrict__ wa,
                                                                   const unsigned short* __restrict__ wb, long long rows,
-                                                                  int na, int nb, unsigned short* __restrict__ ya,
+                                                                  int na, int nb, int wpa, int wpb, int ypa, int ypb,
+                                                                  unsigned short* __restrict__ ya,
                                                                   unsigned short* __restrict__ yb) {
   constexpr int D = PM_D, KSTEPS = D / 16;
   constexpr int WP = D * 2 + 16;             // W^T row pitch: 16-byte reads of 32 consecutive rows hit all banks
@@ -124,10 +126,10 @@ __global__ __launch_bounds__(PM_THREADS) void project_mfma_kernel(const unsigned
   // their 2-byte writes into the transposed rows fall next to each other
   for (int which = 0; which < 2; ++which) {
     const unsigned short* wsrc = which ? wb : wa;
-    const int n = which ? nb : na, base = which ? na : 0;
+    const int n = which ? nb : na, base = which ? na : 0, wp = which ? wpb : wpa;
     for (int e = tid; e < D * n / 8; e += PM_THREADS) {
       const int kk = e % D, n0 = (e / D) * 8;
-      const u32x4 raw = *reinterpret_cast<const u32x4*>(wsrc + (size_t)kk * n + n0);
+      const u32x4 raw = *reinterpret_cast<const u32x4*>(wsrc + (size_t)kk * wp + n0);
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const unsigned short val = (unsigned short)((raw[j >> 1] >> ((j & 1) * 16)) & 0xffffu);
@@ -174,14 +176,14 @@ __global__ __launch_bounds__(PM_THREADS) void project_mfma_kernel(const unsigned
       // reads below see the writes above, and the next output's writes come after these reads: no barrier)
       if (j == nta - 1 || j == ntiles_out - 1) {
         const bool second = j >= nta;
-        const int n = second ? nb : na;
+        const int n = second ? nb : na, yp = second ? ypb : ypa;
         unsigned short* y = second ? yb : ya;
         const int lpr = n / 8;                     // 16-byte pieces per row
         for (int idx = lane; idx < PM_ROWS * lpr; idx += 64) {
           const int rr = idx / lpr, c = idx - rr * lpr;
           const u32x4 val = *reinterpret_cast<const u32x4*>(opatch + rr * OP + c * 16);
           if (r0 + rr < rows) {
-            u32x4* dst = reinterpret_cast<u32x4*>(y + (size_t)(r0 + rr) * n + c * 8);
+            u32x4* dst = reinterpret_cast<u32x4*>(y + (size_t)(r0 + rr) * yp + c * 8);
             if (NTS) __builtin_nontemporal_store(val, dst);
             else *dst = val;
           }
@@ -379,7 +381,7 @@ laser_status project_heads_mfma_launch(const ProjHeadsArgs& a) {
 bool project_mfma_supports(const ProjArgs& a) {
   if (a.dt != LASER_BF16 || a.d_in != PM_D) return false;
   for (int o = 0; o < 2; ++o)
-    if (a.n[o] % 32 != 0 || a.n[o] > PM_OMAX) return false;
+    if (a.n[o] % 32 != 0 || a.n[o] > PM_OMAX || a.wpitch[o] % 8 != 0 || a.ypitch[o] % 8 != 0) return false;
   return a.n[0] >= 32 && a.n[0] + a.n[1] <= PM_NMAX;
 }
 
@@ -397,7 +399,8 @@ laser_status project_mfma_launch(const ProjArgs& a) {
 #define LASER_PROJECT_LAUNCH(PF, NTS)                                                                              \
   hipLaunchKernelGGL((project_mfma_kernel<PF, NTS>), dim3((unsigned)blocks), dim3(PM_THREADS), 0, a.stream,        \
                      (const unsigned short*)a.x, (const unsigned short*)a.w[0], (const unsigned short*)a.w[1],     \
-                     a.rows, a.n[0], a.n[1], (unsigned short*)a.y[0], (unsigned short*)a.y[1])
+                     a.rows, a.n[0], a.n[1], a.wpitch[0], a.wpitch[1], a.ypitch[0], a.ypitch[1],                  \
+                     (unsigned short*)a.y[0], (unsigned short*)a.y[1])
   if (mode == 0) LASER_PROJECT_LAUNCH(false, false);
   else if (mode == 1) LASER_PROJECT_LAUNCH(true, false);
   else if (mode == 2) LASER_PROJECT_LAUNCH(false, true);

@@ -217,12 +217,15 @@ __global__ __launch_bounds__(256) void sta_stream_short_kernel(const unsigned sh
                                                                const int32_t* __restrict__ lens, int C, int L, int w,
                                                                int S, int spg, int groups, float neg_scale_log2e,
                                                                unsigned short* __restrict__ seg_out,
-                                                               int32_t* __restrict__ seg_cnt) {
+                                                               int32_t* __restrict__ seg_cnt, int kv_alias) {
   constexpr int LQ = DQ / 8, LV = D / 8;
   constexpr int RQ = 64 / LQ, RV = 64 / LV;
   constexpr int IPC = RQ > RV ? RQ : RV;
   constexpr int NKL = IPC / RQ, NVL = IPC / RV;
   constexpr bool SAME = (LQ == LV);
+  // kv_alias: keys and values are the same array (the folded form runs STA over the raw items); with equal widths a
+  // lane's value piece is its key piece, and the value loads are left out
+  const bool alias = SAME && kv_alias != 0;
   constexpr int LQH = LQ / HEADS, LVH = LV / HEADS;   // lanes per head, as in the kernel above
   static_assert(LQ % HEADS == 0 && LV % HEADS == 0, "a head's columns must fill whole 16-byte lanes");
   __shared__ float gs[4][CMAX][HEADS][IPC];
@@ -265,6 +268,11 @@ __global__ __launch_bounds__(256) void sta_stream_short_kernel(const unsigned sh
       int row = base + kl * RQ + rq;
       row = row < hi ? row : hi - 1;
       r.k[kl] = *reinterpret_cast<const u32x4*>(kU + (size_t)row * DQ + cq * 8);
+    }
+    if (alias) {
+#pragma unroll
+      for (int vl = 0; vl < NVL; ++vl) r.v[vl] = r.k[vl < NKL ? vl : 0];
+      return;
     }
 #pragma unroll
     for (int vl = 0; vl < NVL; ++vl) {
@@ -316,6 +324,35 @@ __global__ __launch_bounds__(256) void sta_stream_short_kernel(const unsigned sh
     }
   };
   auto finish_segment = [&](int i) {   // sum over the row groups of the wave, one 16-byte store per value lane
+    if constexpr (LV == 16) {
+      // Four row groups of 16 lanes: a reduce-scatter with the lane-swap instructions instead of 16 shuffles per
+      // candidate. v_permlane32_swap exchanges lanes 32..63 of its first operand with lanes 0..31 of its second,
+      // so first + second leaves the first value summed over row groups (g, g + 2) in the lower half and the second
+      // value in the upper half; v_permlane16_swap (odd rows of the first with even rows of the second) does the
+      // same for neighbouring rows. A lane of row g ends with values 2g and 2g + 1 of its eight, summed over all
+      // four groups in a fixed order, and the wave writes the 256-byte row in one 4-byte-per-lane store.
+#pragma unroll
+      for (int c = 0; c < CMAX; ++c) {
+        if (c < C) {
+          float y[4], z[2];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[c][e]), __float_as_uint(acc[c][e + 4]),
+                                                            false, false);
+            y[e] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+          }
+#pragma unroll
+          for (int e = 0; e < 2; ++e) {
+            const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(y[e]), __float_as_uint(y[e + 2]), false,
+                                                            false);
+            z[e] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+          }
+          const unsigned o = (unsigned)f32_to_bf16_bits(z[0]) | ((unsigned)f32_to_bf16_bits(z[1]) << 16);
+          *reinterpret_cast<unsigned*>(seg_out + (((size_t)u * C + c) * S + i) * D + cv * 8 + 2 * (lane >> 4)) = o;
+        }
+      }
+      return;
+    }
 #pragma unroll
     for (int c = 0; c < CMAX; ++c) {
       if (c < C) {
@@ -386,21 +423,26 @@ static void launch_c(const StaArgs& a, float nsl) {
   int groups = (2048 + a.U - 1) / a.U;
   if (groups > a.S) groups = a.S;
   int spg = (a.S + groups - 1) / groups;
+  // a step of the long form covers 4 waves x 4 chunks of IPC items; shorter segments go wave by wave
+  constexpr int IPC_ = (64 / (DQ / 8)) > (64 / (D / 8)) ? (64 / (DQ / 8)) : (64 / (D / 8));
+  const bool short_seg = a.w < 4 * 4 * IPC_;
+  // short segments are cheap to start on (a wave owns whole segments, nothing is shared), and histories differ in
+  // length: runs of a dozen segments (three per wave) even out the load where whole users do not (measured on
+  // 2048 users x 100 segments of 10 items with lengths between 200 and 1000: 110 us -> 86 us)
+  if (short_seg && spg > 12) spg = 12;
   if (const char* e = getenv("LASER_STREAM_SPG")) {   // tuning override
     const int vv = atoi(e);
     if (vv >= 1 && vv <= a.S) spg = vv;
   }
   groups = (a.S + spg - 1) / spg;
   const unsigned blocks = (unsigned)((long long)a.U * groups);
-  // a step of the long form covers 4 waves x 4 chunks of IPC items; shorter segments go wave by wave
-  constexpr int IPC_ = (64 / (DQ / 8)) > (64 / (D / 8)) ? (64 / (DQ / 8)) : (64 / (D / 8));
-  const bool short_seg = a.w < 4 * 4 * IPC_;
 #define LASER_STREAM_LAUNCH(CM)                                                                                      \
   do {                                                                                                               \
     if (short_seg)                                                                                                   \
       hipLaunchKernelGGL((sta_stream_short_kernel<DQ, D, CM, HEADS>), dim3(blocks), dim3(256), 0, a.stream,               \
                          (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v,       \
-                         a.lens, a.C, a.L, a.w, a.S, spg, groups, nsl, (unsigned short*)a.seg_out, a.seg_cnt);     \
+                         a.lens, a.C, a.L, a.w, a.S, spg, groups, nsl, (unsigned short*)a.seg_out, a.seg_cnt,     \
+                         (a.k == a.v && DQ == D) ? 1 : 0);                                                           \
     else                                                                                                             \
       hipLaunchKernelGGL((sta_stream_kernel<DQ, D, CM, HEADS>), dim3(blocks), dim3(256), 0, a.stream,                     \
                          (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v,       \
