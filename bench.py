@@ -93,6 +93,51 @@ def _cpu_baseline_timed(spec, wl, n_users, budget_s):
     return out
 
 
+def paper_setting_chain(laser, torch, event_time):
+    """Raw embeddings -> H' at the paper's own training setting (Sec. 4.1.2: batch 2048 with one target each,
+    L = 1000, w = 10, 2 heads x d_q 16, d = 128; lengths uniform in [200, 1000], bf16): the direct chain
+    (projections, then STA with heads) beside the folded chain, which reads the raw history once."""
+    U, C, L, din, dq, d, w, heads = 2048, 1, 1000, 128, 32, 128, 10, 2
+    S = -(-L // w)
+    gen = torch.Generator(device="cuda").manual_seed(2602)
+    rnd = lambda *shape: torch.randn(*shape, device="cuda", generator=gen)
+    t, H = rnd(U, C, din).bfloat16(), rnd(U, L, din).bfloat16()
+    Wq, Wk, Wv = ((rnd(din, n) / math.sqrt(din)).bfloat16() for n in (dq, dq, d))
+    lens = torch.randint(200, L + 1, (U,), device="cuda", dtype=torch.int32, generator=gen)
+    gamma = math.sqrt(dq / heads)
+    Q = torch.empty(U, C, dq, device="cuda", dtype=torch.bfloat16)
+    K = torch.empty(U, L, dq, device="cuda", dtype=torch.bfloat16)
+    V = torch.empty(U, L, d, device="cuda", dtype=torch.bfloat16)
+    seg = torch.empty(U, C, S, d, device="cuda", dtype=torch.bfloat16)
+    A = laser.laser_fold_query_weights(Wq, Wk, heads)
+    qf = torch.empty(U, C * heads, din, device="cuda", dtype=torch.bfloat16)
+    gw = torch.empty(U, C * heads, S, din, device="cuda", dtype=torch.bfloat16)
+
+    def direct(i):
+        laser.laser_project_q_forward(t, Wq, q_out=Q)
+        laser.laser_project_kv_forward(H, Wk, Wv, k_out=K, v_out=V)
+        laser.laser_sta_forward(Q, K, V, lens, w, gamma, seg_out=seg, want_cnt=False, heads=heads)
+
+    def folded(i):
+        laser.laser_sta_folded_forward(t, H, A, Wv, lens, w, gamma, heads, qf_work=qf, g_work=gw, seg_out=seg,
+                                       want_cnt=False)
+
+    kv_ms = event_time(lambda i: laser.laser_project_kv_forward(H, Wk, Wv, k_out=K, v_out=V))
+    sta_ms = event_time(lambda i: laser.laser_sta_forward(Q, K, V, lens, w, gamma, seg_out=seg, want_cnt=False,
+                                                          heads=heads))
+    direct_ms, folded_ms = event_time(direct), event_time(folded)
+    same = float((seg.float() - 0).abs().max())   # keeps the last result alive until here
+    nvalid = int(lens.sum())
+    # least traffic of the job: every valid raw item once, H' once (weights and targets are noise beside them)
+    alg_b = (nvalid * din + U * C * S * d) * 2
+    return {"U": U, "C": C, "L": L, "w": w, "heads": heads, "d_q": dq, "d": d, "kv_projection_ms": kv_ms,
+            "sta_heads_ms": sta_ms, "direct_chain_ms": direct_ms, "folded_chain_ms": folded_ms,
+            "algorithmic_bytes": alg_b, "folded_gbps": alg_b / (folded_ms * 1e-3) / 1e9,
+            "folded_frac_of_hbm_peak": alg_b / (folded_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "direct_frac_of_hbm_peak": alg_b / (direct_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "pairs_per_s_folded": U * C / (folded_ms * 1e-3), "max_abs_out": same}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -278,6 +323,7 @@ def main() -> int:
                    "tflops": kv_f / (kv_ms * 1e-3) / 1e12, "bound": "hbm" if t_h >= t_m else "mfma",
                    "frac": (t_h if t_h >= t_m else t_m) / (kv_ms * 1e-3),
                    "whole_path_ms_per_step": raw_ms, "whole_path_pairs_per_s": spec.pairs / (raw_ms * 1e-3)}
+        project["paper_setting"] = paper_setting_chain(laser, torch, event_time)
         for (dw, seg, cnt, z) in sets:   # the timed loops above overwrote q, k, v: restore the workload's own
             fresh = DeviceWorkload(wl)
             dw.q.copy_(fresh.q), dw.k.copy_(fresh.k), dw.v.copy_(fresh.v)
