@@ -23,6 +23,7 @@ Readings where the paper is silent (listed in full in the design notes):
     without a valid item stay zero;
   * several heads (Sec. 4.1.2): head h owns the h-th run of d_q / heads columns of Q and K and of d / heads
     columns of V; same gamma; outputs side by side;
+  * softmax variant (Sec. 4.4.1): normalised over the valid items of a segment, per head;
   * projections (Sec. 3.5.1): y = x @ W with W [d_in, n], no bias;
   * multi-resolution views (Sec. 3.4.4): max-pooling runs over the segments that hold a
     valid item; "the r most recent segments" are rows 0..r-1 of H'.
@@ -133,6 +134,34 @@ def sta_pair_heads(Q: np.ndarray, K: np.ndarray, V: np.ndarray, length: int, w: 
     return Hp
 
 
+def sta_pair_softmax(Q: np.ndarray, K: np.ndarray, V: np.ndarray, length: int, w: int, gamma: float,
+                     heads: int = 1) -> np.ndarray:
+    """H' [S, d] of one (user, candidate) in the ablation variant of Sec. 4.4.1, where the sigmoid aggregation of
+    Sec. 3.4.2 is replaced by the conventional softmax: s_i = softmax(Q K_i^T / gamma) V_i.
+
+    Reading: the softmax runs over the valid items of segment i (the window STA aggregates over), per head on the
+    head's own columns as in sta_pair_heads; a segment without a valid item gives zeros.
+    """
+    L, dq = K.shape
+    d = V.shape[1]
+    if heads < 1 or dq % heads or d % heads:
+        raise ValueError("heads must divide d_q and d")
+    a, b = dq // heads, d // heads
+    S = num_segments(L, w)
+    n = min(max(int(length), 0), L)
+    Hp = np.zeros((S, d), dtype=np.float64)
+    for i in range(S):
+        lo = i * w
+        hi = min(min((i + 1) * w, L), n)
+        if hi <= lo:
+            continue
+        for h in range(heads):
+            score = (K[lo:hi, h * a:(h + 1) * a] @ Q[h * a:(h + 1) * a]) / gamma
+            e = np.exp(score - score.max())
+            Hp[i, h * b:(h + 1) * b] = (e / e.sum()) @ V[lo:hi, h * b:(h + 1) * b]
+    return Hp
+
+
 def gsta_pair(Hp: np.ndarray, t: np.ndarray, Wq: np.ndarray, Wk: np.ndarray, Wv: np.ndarray,
               seg_valid: np.ndarray) -> np.ndarray:
     """z = t_M for one (user, candidate) (Sec. 3.4.3, attention equation and residual update).
@@ -159,7 +188,8 @@ def gsta_pair(Hp: np.ndarray, t: np.ndarray, Wq: np.ndarray, Wk: np.ndarray, Wv:
     return t_l
 
 
-def sta_forward(q, k, v, lens, w: int, gamma: float, global_form: bool = False, heads: int = 1):
+def sta_forward(q, k, v, lens, w: int, gamma: float, global_form: bool = False, heads: int = 1,
+                softmax: bool = False):
     """H' [U, C, S, d] and cnt [U, S] for a batch. q [U,C,d_q], k [U,L,d_q], v [U,L,d], lens [U] or None."""
     q = np.asarray(q, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
@@ -172,7 +202,9 @@ def sta_forward(q, k, v, lens, w: int, gamma: float, global_form: bool = False, 
     Hp = np.zeros((U, C, S, d), dtype=np.float64)
     for u in range(U):
         for c in range(C):
-            if heads == 1:
+            if softmax:
+                Hp[u, c] = sta_pair_softmax(q[u, c], k[u], v[u], int(lens[u]), w, gamma, heads)
+            elif heads == 1:
                 Hp[u, c] = one(q[u, c], k[u], v[u], int(lens[u]), w, gamma)
             else:
                 Hp[u, c] = sta_pair_heads(q[u, c], k[u], v[u], int(lens[u]), w, gamma, heads)

@@ -596,3 +596,62 @@ def test_folded_form_equals_projections_then_sta(heads):
     folded, cnt2 = oracle.sta_folded_forward(t, H, Wq, Wk, Wv, lens, w, gamma, heads)
     assert np.array_equal(cnt, cnt2)
     assert np.allclose(direct, folded, rtol=1e-11, atol=1e-12)
+
+
+# ------------------------------------------------------------------ softmax aggregation (ablation of Sec. 4.4.1)
+def _softmax_brute(q, K, V, n, w, gamma, heads):
+    L, dq, d = len(K), len(q), len(V[0])
+    a, b = dq // heads, d // heads
+    S = -(-L // w)
+    out = [[0.0] * d for _ in range(S)]
+    for i in range(S):
+        items = range(i * w, min((i + 1) * w, L, n))
+        for e in range(d):
+            h = e // b
+            es = [math.exp(sum(q[h * a + x] * K[j][h * a + x] for x in range(a)) / gamma) for j in items]
+            if es:
+                out[i][e] = sum(p * V[j][e] for p, j in zip(es, items)) / sum(es)
+    return out
+
+
+@pytest.mark.parametrize("heads", [1, 2])
+def test_softmax_variant_brute_force_and_library(heads):
+    rng = np.random.default_rng(700 + heads)
+    L, w, n, gamma, dq, d = 19, 5, 17, 0.9, 4, 6
+    q, K, V = rng.normal(size=dq), rng.normal(size=(L, dq)), rng.normal(size=(L, d))
+    got = lo.sta_pair_softmax(q, K, V, n, w, gamma, heads)
+    assert np.allclose(got, _softmax_brute(q.tolist(), K.tolist(), V.tolist(), n, w, gamma, heads), rtol=1e-12, atol=1e-13)
+    if heads == 1:   # reduction to the library routine, segment by segment
+        for i in range(4):
+            lo_, hi_ = i * w, min((i + 1) * w, n)
+            ref = scipy.special.softmax(K[lo_:hi_] @ q / gamma) @ V[lo_:hi_] if hi_ > lo_ else np.zeros(d)
+            assert np.allclose(got[i], ref, rtol=1e-12, atol=1e-13)
+
+
+def test_softmax_variant_invariants():
+    rng = np.random.default_rng(701)
+    L, w, gamma, dq, d = 24, 6, 1.1, 5, 7
+    q, K, V = rng.normal(size=dq), rng.normal(size=(L, dq)), rng.normal(size=(L, d))
+    base = lo.sta_pair_softmax(q, K, V, L, w, gamma)
+    # a convex combination of the segment's value rows: inside their range, and rows of ones give ones
+    for i in range(4):
+        seg = V[i * w:(i + 1) * w]
+        assert (base[i] >= seg.min(axis=0) - 1e-12).all() and (base[i] <= seg.max(axis=0) + 1e-12).all()
+    assert np.allclose(lo.sta_pair_softmax(q, K, np.ones((L, d)), L, w, gamma), 1.0, rtol=1e-13)
+    # zero query: the mean of the valid items (17 valid: the last segment is empty, the third holds 5 items)
+    m = lo.sta_pair_softmax(np.zeros(dq), K, V, 17, w, gamma)
+    assert np.allclose(m[0], V[:6].mean(axis=0)) and np.allclose(m[2], V[12:17].mean(axis=0)) and not m[3].any()
+    # a score shift common to a segment cancels: one more key column that is constant, times any query entry
+    K2, q2 = np.concatenate([K, np.full((L, 1), 3.0)], axis=1), np.concatenate([q, [5.0]])
+    assert np.allclose(lo.sta_pair_softmax(q2, K2, V, L, w, gamma), base, rtol=1e-11)
+    # one item per segment: that item's value, whatever the score; very large scores do not overflow
+    assert np.allclose(lo.sta_pair_softmax(q, K, V, L, 1, gamma), V, rtol=1e-13)
+    big = lo.sta_pair_softmax(1e4 * q, K, V, L, w, gamma)
+    assert np.isfinite(big).all()
+    for i in range(4):   # the winner takes all
+        j = i * w + int(np.argmax(K[i * w:(i + 1) * w] @ q))
+        assert np.allclose(big[i], V[j], rtol=1e-9)
+    # differs from the sigmoid form, which is not normalised
+    assert not np.allclose(base, lo.sta_pair(q, K, V, L, w, gamma))
+    Hb, _ = oracle.sta_forward(q[None, None], K[None], V[None], [L], w, gamma, softmax=True)
+    assert np.array_equal(Hb[0, 0], base)
