@@ -108,6 +108,20 @@ laser_status laser_sta_forward_heads(const void* q, const void* k, const void* v
                                      laser_sta_variant variant);
 
 /*
+ * The ablation variant of paper Sec. 4.4.1, in which the sigmoid aggregation of STA is replaced by the conventional
+ * softmax:  seg_out[u,c,i,:] = sum_j softmax_j(dot(q[u,c,:], k[u,j,:]) / gamma) * v[u,j,:], the softmax taken over the
+ * valid items j of segment i (per head on the head's own columns, as in laser_sta_forward_heads); segments without a
+ * valid item give zeros. Arguments, layouts, limits and errors as for laser_sta_forward_heads. Kernels: the streaming
+ * kernel for short segments (C <= 8, bf16, w below one step of its long form) and the generic kernel; the matrix-core
+ * kernel and the long-segment streaming kernel carry sigmoid gates only (a forced variant that does not take the case
+ * returns LASER_ERR_UNSUPPORTED).
+ */
+laser_status laser_sta_forward_softmax(const void* q, const void* k, const void* v, const int32_t* lens,
+                                       int U, int C, int L, int d_q, int d, int w, float gamma, int heads,
+                                       laser_dtype dt, void* seg_out, int32_t* seg_cnt, void* stream,
+                                       laser_sta_variant variant);
+
+/*
  * Global Stacked Target Attention, forward (paper Sec. 3.4.3): for l = 1..M
  *   a_l = softmax((t_{l-1} W_q^l)(H' W_k^l)^T / sqrt(d)),  o_l = a_l (H' W_v^l),  t_l = t_{l-1} + o_l
  * with t_0 = t0 and z = t_M. The softmax runs over the segments of user u that hold at

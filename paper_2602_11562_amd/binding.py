@@ -21,7 +21,7 @@ FFN_AUTO, FFN_GENERIC, FFN_MFMA = 0, 1, 2
 PROJECT_AUTO, PROJECT_GENERIC, PROJECT_MFMA = 0, 1, 2
 
 EXPORTS = [
-    "laser_sta_forward", "laser_sta_forward_variant", "laser_sta_forward_heads", "laser_gsta_forward", "laser_gsta_forward_variant",
+    "laser_sta_forward", "laser_sta_forward_variant", "laser_sta_forward_heads", "laser_sta_forward_softmax", "laser_gsta_forward", "laser_gsta_forward_variant",
     "laser_forward", "laser_multires_forward", "laser_forward_multires", "laser_sta_kernel_name",
     "laser_gsta_kernel_name", "laser_segment_ffn_forward", "laser_segment_ffn_forward_variant",
     "laser_gsta_kernel_name_layers", "laser_project_q_forward", "laser_project_q_forward_variant",
@@ -53,6 +53,8 @@ def load_library() -> ctypes.CDLL:
     lib.laser_sta_forward_variant.argtypes = lib.laser_sta_forward.argtypes + [i32]
     lib.laser_sta_forward_heads.argtypes = [vp, vp, vp, ip, i32, i32, i32, i32, i32, i32, f32, i32, i32, vp, ip, vp, i32]
     lib.laser_sta_forward_heads.restype = i32
+    lib.laser_sta_forward_softmax.argtypes = lib.laser_sta_forward_heads.argtypes
+    lib.laser_sta_forward_softmax.restype = i32
     lib.laser_gsta_forward.argtypes = [vp, vp, vp, vp, vp, ip, i32, i32, i32, i32, i32, i32, i32, vp, vp]
     lib.laser_gsta_forward_variant.argtypes = lib.laser_gsta_forward.argtypes + [i32]
     lib.laser_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, ip, i32, i32, i32, i32, i32, i32, f32, i32, i32,
@@ -150,9 +152,10 @@ def _check(code: int, where: str) -> None:
 
 
 def laser_sta_forward(q, k, v, lens, w: int, gamma: float, seg_out=None, seg_cnt=None, stream=None,
-                      variant: int = STA_AUTO, want_cnt: bool = True, heads: int = 1):
+                      variant: int = STA_AUTO, want_cnt: bool = True, heads: int = 1, softmax: bool = False):
     """q [U,C,d_q], k [U,L,d_q], v [U,L,d], lens int32 [U] or None -> (H' [U,C,S,d], cnt [U,S] or None).
-    heads > 1 calls laser_sta_forward_heads (head h owns the h-th run of columns of q, k, v and H')."""
+    heads > 1 calls laser_sta_forward_heads (head h owns the h-th run of columns of q, k, v and H'); softmax=True
+    calls laser_sta_forward_softmax (softmax over a segment's valid items instead of sigmoid gates)."""
     torch = _torch()
     U, C, d_q = q.shape
     L, d = v.shape[1], v.shape[2]
@@ -169,12 +172,13 @@ def laser_sta_forward(q, k, v, lens, w: int, gamma: float, seg_out=None, seg_cnt
         seg_cnt = torch.empty((U, S), dtype=torch.int32, device=q.device)
     if lens is not None and tuple(lens.shape) != (U,):
         raise ValueError("lens must be [U]")
-    if int(heads) != 1:
-        code = load_library().laser_sta_forward_heads(
+    if softmax or int(heads) != 1:
+        fn = load_library().laser_sta_forward_softmax if softmax else load_library().laser_sta_forward_heads
+        code = fn(
             _ptr(q, "q"), _ptr(k, "k"), _ptr(v, "v"), _ptr(lens, "lens", torch.int32), U, C, L, d_q, d, int(w),
             float(gamma), int(heads), _dt(q), _ptr(seg_out, "seg_out"), _ptr(seg_cnt, "seg_cnt", torch.int32),
             _stream(stream), int(variant))
-        _check(code, "laser_sta_forward_heads")
+        _check(code, "laser_sta_forward_softmax" if softmax else "laser_sta_forward_heads")
         return seg_out, seg_cnt
     code = load_library().laser_sta_forward_variant(
         _ptr(q, "q"), _ptr(k, "k"), _ptr(v, "v"), _ptr(lens, "lens", torch.int32), U, C, L, d_q, d, int(w),

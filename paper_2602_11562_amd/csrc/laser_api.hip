@@ -129,6 +129,19 @@ laser_status laser_sta_forward_heads(const void* q, const void* k, const void* v
   return run_sta(a, variant);
 }
 
+laser_status laser_sta_forward_softmax(const void* q, const void* k, const void* v, const int32_t* lens, int U, int C,
+                                       int L, int d_q, int d, int w, float gamma, int heads, laser_dtype dt,
+                                       void* seg_out, int32_t* seg_cnt, void* stream, laser_sta_variant variant) {
+  StaArgs a;
+  laser_status s = validate_sta(q, k, v, lens, U, C, L, d_q, d, w, gamma, dt, seg_out, seg_cnt, stream, &a);
+  if (s != LASER_OK) return s;
+  if (heads < 1 || heads > 64 || d_q % heads != 0 || d % heads != 0) return LASER_ERR_SHAPE;
+  if (variant < LASER_STA_AUTO || variant > LASER_STA_STREAM) return LASER_ERR_UNSUPPORTED;
+  a.heads = heads;
+  a.softmax = true;
+  return run_sta(a, variant);
+}
+
 laser_status laser_sta_forward(const void* q, const void* k, const void* v, const int32_t* lens, int U, int C,
                                int L, int d_q, int d, int w, float gamma, laser_dtype dt, void* seg_out,
                                int32_t* seg_cnt, void* stream) {

@@ -22,6 +22,7 @@ struct StaArgs {
   hipStream_t stream;
   bool reread;        // H' is read again right after this launch (the whole path): store it cacheable
   int heads = 1;      // attention heads: head h owns the h-th run of d_q / heads and d / heads columns
+  bool softmax = false;   // softmax over a segment's valid items instead of sigmoid gates (ablation of Sec. 4.4.1)
 };
 
 struct GstaArgs {

@@ -20,7 +20,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void sta_generic_kernel(const T* __restrict__ q, const T* __restrict__ k,
                                                           const T* __restrict__ v, const int32_t* __restrict__ lens,
                                                           int C, int L, int dq, int d, int w, int S, int TI,
-                                                          int heads, float inv_gamma, T* __restrict__ seg_out,
+                                                          int heads, int softmax, float inv_gamma,
+                                                          T* __restrict__ seg_out,
                                                           int32_t* __restrict__ seg_cnt) {
   extern __shared__ float smem[];
   const int kpitch = dq + 1;                   // +1: lanes read different rows at the same column
@@ -52,9 +53,15 @@ __global__ __launch_bounds__(256) void sta_generic_kernel(const T* __restrict__ 
   for (int a = lane; a < dq; a += 64)
     qs[wave * dq + a] = active ? load_as_f32(q, ((size_t)u * C + c) * dq + a) : 0.0f;
 
-  float acc[GEN_MAX_COLS];
+  // softmax (ablation of Sec. 4.4.1): gs then holds the scaled scores, and every column keeps a running maximum
+  // and denominator of its head's scores, rescaling its sum when the maximum moves (items in ascending order)
+  float acc[GEN_MAX_COLS], sm_m[GEN_MAX_COLS], sm_l[GEN_MAX_COLS];
 #pragma unroll
-  for (int b = 0; b < GEN_MAX_COLS; ++b) acc[b] = 0.0f;
+  for (int b = 0; b < GEN_MAX_COLS; ++b) {
+    acc[b] = 0.0f;
+    sm_m[b] = -INFINITY;
+    sm_l[b] = 0.0f;
+  }
 
   const T* kU = k + (size_t)u * L * dq;
   const T* vU = v + (size_t)u * L * d;
@@ -74,7 +81,8 @@ __global__ __launch_bounds__(256) void sta_generic_kernel(const T* __restrict__ 
       for (int hh = 0; hh < heads; ++hh) {
         float e = 0.0f;
         for (int a = hh * dqh; a < (hh + 1) * dqh; ++a) e = fmaf(qr[a], kr[a], e);
-        gs[(wave * heads + hh) * TI + lane] = 1.0f / (1.0f + expf(-e * inv_gamma));   // independent gate per item
+        gs[(wave * heads + hh) * TI + lane] =
+            softmax ? e * inv_gamma : 1.0f / (1.0f + expf(-e * inv_gamma));   // independent gate per item
       }
     }
     __syncthreads();
@@ -82,7 +90,19 @@ __global__ __launch_bounds__(256) void sta_generic_kernel(const T* __restrict__ 
 #pragma unroll
       for (int b = 0; b < GEN_MAX_COLS; ++b) {
         const int col = lane + 64 * b;
-        if (col < d) acc[b] = fmaf(gs[(wave * heads + col / dh) * TI + jj], Vs[jj * d + col], acc[b]);
+        if (col < d) {
+          const float g = gs[(wave * heads + col / dh) * TI + jj];
+          if (softmax) {
+            const float m_new = fmaxf(sm_m[b], g);
+            const float sc = expf(sm_m[b] - m_new);   // 0 the first time (the maximum starts at minus infinity)
+            const float pr = expf(g - m_new);
+            acc[b] = fmaf(pr, Vs[jj * d + col], acc[b] * sc);
+            sm_l[b] = fmaf(sm_l[b], sc, pr);
+            sm_m[b] = m_new;
+          } else {
+            acc[b] = fmaf(g, Vs[jj * d + col], acc[b]);
+          }
+        }
       }
     }
   }
@@ -92,7 +112,7 @@ __global__ __launch_bounds__(256) void sta_generic_kernel(const T* __restrict__ 
 #pragma unroll
     for (int b = 0; b < GEN_MAX_COLS; ++b) {
       const int col = lane + 64 * b;
-      if (col < d) store_from_f32(seg_out, base + col, acc[b]);
+      if (col < d) store_from_f32(seg_out, base + col, (softmax && sm_l[b] > 0.0f) ? acc[b] / sm_l[b] : acc[b]);
     }
   }
 }
@@ -124,12 +144,12 @@ laser_status sta_generic_launch(const StaArgs& a) {
   if (a.dt == LASER_F32) {
     hipLaunchKernelGGL(sta_generic_kernel<float>, dim3(blocks), dim3(256), lds, a.stream, (const float*)a.q,
                        (const float*)a.k, (const float*)a.v, a.lens, a.C, a.L, a.d_q, a.d, a.w, a.S, TI, a.heads,
-                       inv_gamma, (float*)a.seg_out, a.seg_cnt);
+                       a.softmax ? 1 : 0, inv_gamma, (float*)a.seg_out, a.seg_cnt);
   } else {
     hipLaunchKernelGGL(sta_generic_kernel<unsigned short>, dim3(blocks), dim3(256), lds, a.stream,
                        (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens,
-                       a.C, a.L, a.d_q, a.d, a.w, a.S, TI, a.heads, inv_gamma, (unsigned short*)a.seg_out,
-                       a.seg_cnt);
+                       a.C, a.L, a.d_q, a.d, a.w, a.S, TI, a.heads, a.softmax ? 1 : 0, inv_gamma,
+                       (unsigned short*)a.seg_out, a.seg_cnt);
   }
   return launch_status();
 }

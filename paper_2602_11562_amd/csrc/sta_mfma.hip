@@ -1010,7 +1010,7 @@ bool sta_mfma_supports(const StaArgs& a) {
   if (a.dt != LASER_BF16) return false;
   if (!(a.d_q == 32 || a.d_q == 64 || a.d_q == 128)) return false;
   if (!(a.d == 64 || a.d == 128)) return false;
-  if (a.heads != 1) return false;   // one gate per (item, candidate): several heads go to the other kernels
+  if (a.heads != 1 || a.softmax) return false;   // one sigmoid gate per (item, candidate); the rest elsewhere
   if (a.C < 9) return false;   // fewer candidates than that: the streaming kernel's range
   const int nw = pick_nw(a.C);
   const long long ctiles = (a.C + CW * nw - 1) / (CW * nw);

@@ -210,7 +210,11 @@ __global__ __launch_bounds__(256) void sta_stream_kernel(const unsigned short* _
 // every segment would pay two workgroup barriers. Here each wave owns whole segments (wave v takes segments
 // v, v + 4, ... of the run), reduces them inside the wave and stores them itself: no LDS reduction, no barrier.
 // Chunks of IPC items are loaded one ahead (the next chunk of the segment or the first of the wave's next one).
-template <int DQ, int D, int CMAX, int HEADS>
+// SOFTMAX: the ablation variant of Sec. 4.4.1 (softmax over the valid items of a segment instead of independent
+// sigmoid gates). Every value lane keeps a running maximum m and denominator l of its row group's scores (base 2)
+// beside its sums, rescaling them when the maximum moves; at the end of a segment the row groups agree on the
+// largest maximum, rescale once more, and the reduced sums are divided by the reduced denominator.
+template <int DQ, int D, int CMAX, int HEADS, bool SOFTMAX>
 __global__ __launch_bounds__(256) void sta_stream_short_kernel(const unsigned short* __restrict__ q,
                                                                const unsigned short* __restrict__ k,
                                                                const unsigned short* __restrict__ v,
@@ -282,11 +286,26 @@ __global__ __launch_bounds__(256) void sta_stream_short_kernel(const unsigned sh
     }
   };
   float acc[CMAX][8];
+  constexpr float NEG = -1.0e30f;      // "no score yet": finite, so that differences of maxima stay finite
+  float sm_m[CMAX], sm_l[CMAX];        // softmax state (unused otherwise)
   auto clear_acc = [&]() {
 #pragma unroll
-    for (int c = 0; c < CMAX; ++c)
+    for (int c = 0; c < CMAX; ++c) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[c][e] = 0.0f;
+      sm_m[c] = NEG;
+      sm_l[c] = 0.0f;
+    }
+  };
+  // one row's share of the softmax: t = score * log2(e) / gamma of a valid row, or nothing for a row past the end
+  auto softmax_row = [&](int c, float t, bool ok, const float (&vrow)[8]) {
+    const float m_new = ok ? fmaxf(sm_m[c], t) : sm_m[c];
+    const float sc = __builtin_amdgcn_exp2f(sm_m[c] - m_new);
+    const float pr = ok ? __builtin_amdgcn_exp2f(t - m_new) : 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[c][e] = fmaf(pr, vrow[e], acc[c][e] * sc);
+    sm_l[c] = fmaf(sm_l[c], sc, pr);
+    sm_m[c] = m_new;
   };
   auto compute_chunk = [&](int base, int hi, const Regs& r) {
     float vf[NVL][8];
@@ -304,6 +323,12 @@ __global__ __launch_bounds__(256) void sta_stream_short_kernel(const unsigned sh
           for (int e = 0; e < 8; ++e) s = fmaf(kf[e], qf[c][e], s);
           s = row_sum<LQH>(s);
           const bool ok = (base + kl * RQ + rq) < hi;
+          if (SOFTMAX) {
+            const float t = -s * neg_scale_log2e;
+            if (SAME) softmax_row(c, t, ok, vf[kl]);
+            else if (cq % LQH == 0) gs[wave][c][cq / LQH][kl * RQ + rq] = t;
+            continue;
+          }
           const float g = ok ? __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(s * neg_scale_log2e)) : 0.0f;
           if (SAME) {
 #pragma unroll
@@ -316,6 +341,10 @@ __global__ __launch_bounds__(256) void sta_stream_short_kernel(const unsigned sh
 #pragma unroll
           for (int vl = 0; vl < NVL; ++vl) {
             const float g = gs[wave][c][cv / LVH][vl * RV + rv];
+            if (SOFTMAX) {
+              softmax_row(c, g, (base + vl * RV + rv) < hi, vf[vl]);
+              continue;
+            }
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[c][e] = fmaf(g, vf[vl][e], acc[c][e]);
           }
@@ -324,6 +353,25 @@ __global__ __launch_bounds__(256) void sta_stream_short_kernel(const unsigned sh
     }
   };
   auto finish_segment = [&](int i) {   // sum over the row groups of the wave, one 16-byte store per value lane
+    float inv_l[CMAX];
+    if constexpr (SOFTMAX) {
+#pragma unroll
+      for (int c = 0; c < CMAX; ++c) {
+        inv_l[c] = 0.0f;
+        if (c < C) {
+          float mx = sm_m[c];
+#pragma unroll
+          for (int off = LV; off < 64; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+          const float sc = __builtin_amdgcn_exp2f(sm_m[c] - mx);   // 0 for a row group that saw no valid row
+          float lsum = sm_l[c] * sc;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[c][e] *= sc;
+#pragma unroll
+          for (int off = LV; off < 64; off <<= 1) lsum += __shfl_xor(lsum, off, 64);
+          inv_l[c] = 1.0f / lsum;   // a segment that is finished holds at least one valid item
+        }
+      }
+    }
     if constexpr (LV == 16) {
       // Four row groups of 16 lanes: a reduce-scatter with the lane-swap instructions instead of 16 shuffles per
       // candidate. v_permlane32_swap exchanges lanes 32..63 of its first operand with lanes 0..31 of its second,
@@ -347,6 +395,10 @@ __global__ __launch_bounds__(256) void sta_stream_short_kernel(const unsigned sh
                                                             false);
             z[e] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
           }
+          if (SOFTMAX) {
+            z[0] *= inv_l[c];
+            z[1] *= inv_l[c];
+          }
           const unsigned o = (unsigned)f32_to_bf16_bits(z[0]) | ((unsigned)f32_to_bf16_bits(z[1]) << 16);
           *reinterpret_cast<unsigned*>(seg_out + (((size_t)u * C + c) * S + i) * D + cv * 8 + 2 * (lane >> 4)) = o;
         }
@@ -362,9 +414,11 @@ __global__ __launch_bounds__(256) void sta_stream_short_kernel(const unsigned sh
           for (int e = 0; e < 8; ++e) acc[c][e] += __shfl_xor(acc[c][e], off, 64);
         if (rv == 0) {
           u32x4 o;
+          const float mul = SOFTMAX ? inv_l[c] : 1.0f;
 #pragma unroll
           for (int e = 0; e < 4; ++e)
-            o[e] = (unsigned)f32_to_bf16_bits(acc[c][2 * e]) | ((unsigned)f32_to_bf16_bits(acc[c][2 * e + 1]) << 16);
+            o[e] = (unsigned)f32_to_bf16_bits(acc[c][2 * e] * mul) |
+                   ((unsigned)f32_to_bf16_bits(acc[c][2 * e + 1] * mul) << 16);
           *reinterpret_cast<u32x4*>(seg_out + (((size_t)u * C + c) * S + i) * D + cv * 8) = o;
         }
       }
@@ -411,6 +465,11 @@ bool sta_stream_supports(const StaArgs& a) {
   if (a.dt != LASER_BF16) return false;
   if (a.C > 8) return false;
   if (a.heads != 1 && a.heads != 2) return false;
+  if (a.softmax) {   // only the short-segment form carries the softmax state
+    const int lq = a.d_q / 8, lv = a.d / 8;
+    const int ipc = (64 / lq) > (64 / lv) ? (64 / lq) : (64 / lv);
+    if (a.w >= 4 * 4 * ipc) return false;
+  }
   if (!(a.d_q == 32 || a.d_q == 64 || a.d_q == 128)) return false;
   if (!(a.d == 64 || a.d == 128)) return false;
   return (long long)a.U * a.S <= 0x7fffffffLL;   // an upper bound of the grid size
@@ -438,8 +497,13 @@ static void launch_c(const StaArgs& a, float nsl) {
   const unsigned blocks = (unsigned)((long long)a.U * groups);
 #define LASER_STREAM_LAUNCH(CM)                                                                                      \
   do {                                                                                                               \
-    if (short_seg)                                                                                                   \
-      hipLaunchKernelGGL((sta_stream_short_kernel<DQ, D, CM, HEADS>), dim3(blocks), dim3(256), 0, a.stream,               \
+    if (short_seg && a.softmax)                                                                                      \
+      hipLaunchKernelGGL((sta_stream_short_kernel<DQ, D, CM, HEADS, true>), dim3(blocks), dim3(256), 0, a.stream,  \
+                         (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v,       \
+                         a.lens, a.C, a.L, a.w, a.S, spg, groups, nsl, (unsigned short*)a.seg_out, a.seg_cnt,     \
+                         (a.k == a.v && DQ == D) ? 1 : 0);                                                           \
+    else if (short_seg)                                                                                              \
+      hipLaunchKernelGGL((sta_stream_short_kernel<DQ, D, CM, HEADS, false>), dim3(blocks), dim3(256), 0, a.stream, \
                          (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v,       \
                          a.lens, a.C, a.L, a.w, a.S, spg, groups, nsl, (unsigned short*)a.seg_out, a.seg_cnt,     \
                          (a.k == a.v && DQ == D) ? 1 : 0);                                                           \

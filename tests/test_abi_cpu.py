@@ -203,3 +203,13 @@ def test_folded_form_argument_validation(lib):
     for kw in ({"heads": 0}, {"heads": 3}, {"U": 0}, {"C": 0}, {"w": 0}, {"gamma": 0.0}, {"din": 12}):
         assert fo(**kw) == SHAPE, kw
     assert fo(dt=5) == DTYPE and fo(a=A + 8) == ALIGN and fo(g=A + 2) == ALIGN
+
+
+def test_sta_softmax_argument_validation(lib):
+    NULL, SHAPE, UNSUP = 1, 2, 4
+    f = lambda heads=1, dq=16, d=16, variant=0, q=A, C=3, w=8: lib.laser_sta_forward_softmax(
+        q, A, A, None, 2, C, 64, dq, d, w, 1.0, heads, 1, A, None, None, variant)
+    assert f(q=None) == NULL and f(heads=0) == SHAPE and f(heads=3) == SHAPE and f(w=0) == SHAPE
+    assert f(variant=9) == UNSUP
+    assert f(dq=128, d=128, C=64, variant=2) == UNSUP      # the matrix-core kernel carries sigmoid gates only
+    assert f(dq=64, d=64, C=2, w=200, variant=3) == UNSUP  # long segments: the streaming kernel's long form does not either
