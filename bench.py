@@ -125,13 +125,15 @@ def paper_setting_chain(laser, torch, event_time):
     kv_ms = event_time(lambda i: laser.laser_project_kv_forward(H, Wk, Wv, k_out=K, v_out=V))
     sta_ms = event_time(lambda i: laser.laser_sta_forward(Q, K, V, lens, w, gamma, seg_out=seg, want_cnt=False,
                                                           heads=heads))
+    softmax_ms = event_time(lambda i: laser.laser_sta_forward(Q, K, V, lens, w, gamma, seg_out=seg, want_cnt=False,
+                                                              heads=heads, softmax=True))
     direct_ms, folded_ms = event_time(direct), event_time(folded)
     same = float((seg.float() - 0).abs().max())   # keeps the last result alive until here
     nvalid = int(lens.sum())
     # least traffic of the job: every valid raw item once, H' once (weights and targets are noise beside them)
     alg_b = (nvalid * din + U * C * S * d) * 2
     return {"U": U, "C": C, "L": L, "w": w, "heads": heads, "d_q": dq, "d": d, "kv_projection_ms": kv_ms,
-            "sta_heads_ms": sta_ms, "direct_chain_ms": direct_ms, "folded_chain_ms": folded_ms,
+            "sta_heads_ms": sta_ms, "sta_softmax_variant_ms": softmax_ms, "direct_chain_ms": direct_ms, "folded_chain_ms": folded_ms,
             "algorithmic_bytes": alg_b, "folded_gbps": alg_b / (folded_ms * 1e-3) / 1e9,
             "folded_frac_of_hbm_peak": alg_b / (folded_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
             "direct_frac_of_hbm_peak": alg_b / (direct_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
