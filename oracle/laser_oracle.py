@@ -376,3 +376,26 @@ def laser_forward(q, k, v, t0, wq, wk, wv, lens, w: int, gamma: float):
     Hp, cnt = sta_forward(q, k, v, lens, w, gamma)
     z = gsta_forward(Hp, t0, wq, wk, wv, cnt)
     return Hp, cnt, z
+
+
+def laser_forward_ragged(q, k, v, t0, wq, wk, wv, lens, cand_off, w: int, gamma: float):
+    """STA followed by GSTA when every user brings its own number of candidates (serving batches): the pair tensors
+    are packed, q [P,d_q] and t0 [P,d], and user u owns rows cand_off[u] .. cand_off[u+1]-1 (cand_off [U+1], starts
+    at 0, non-decreasing, ends at P). Each pair is computed exactly as in the dense batch (Sec. 3.4.2, 3.4.3): the
+    packing changes where a pair is stored, not what it is. Returns (H' [P,S,d], cnt [U,S], z [P,d])."""
+    q, k, v, t0 = (np.asarray(x, dtype=np.float64) for x in (q, k, v, t0))
+    wq, wk, wv = (np.asarray(x, dtype=np.float64) for x in (wq, wk, wv))
+    cand_off = np.asarray(cand_off, dtype=np.int64)
+    U, L, d = v.shape
+    P = q.shape[0]
+    if cand_off.shape != (U + 1,) or cand_off[0] != 0 or cand_off[U] != P or (np.diff(cand_off) < 0).any():
+        raise ValueError("cand_off must start at 0, end at P and not decrease")
+    lens = np.full(U, L, dtype=np.int64) if lens is None else np.asarray(lens, dtype=np.int64)
+    cnt = segment_counts(lens, L, w)
+    Hp = np.zeros((P, num_segments(L, w), d), dtype=np.float64)
+    z = np.zeros((P, d), dtype=np.float64)
+    for u in range(U):
+        for p in range(int(cand_off[u]), int(cand_off[u + 1])):
+            Hp[p] = sta_pair(q[p], k[u], v[u], int(lens[u]), w, gamma)
+            z[p] = gsta_pair(Hp[p], t0[p], wq, wk, wv, cnt[u] > 0)
+    return Hp, cnt, z

@@ -655,3 +655,32 @@ def test_softmax_variant_invariants():
     assert not np.allclose(base, lo.sta_pair(q, K, V, L, w, gamma))
     Hb, _ = oracle.sta_forward(q[None, None], K[None], V[None], [L], w, gamma, softmax=True)
     assert np.array_equal(Hb[0, 0], base)
+
+
+# ------------------------------------------------------------------ ragged candidate counts (packed pairs)
+def test_ragged_batch_is_the_dense_batch_repacked():
+    rng = np.random.default_rng(811)
+    U, C, L, w, dq, d, M, gamma = 3, 4, 21, 5, 4, 6, 2, 1.4
+    q, t0 = rng.normal(size=(U, C, dq)), rng.normal(size=(U, C, d))
+    k, v = rng.normal(size=(U, L, dq)), rng.normal(size=(U, L, d))
+    wq, wk, wv = (rng.normal(size=(M, d, d)) / math.sqrt(d) for _ in range(3))
+    lens = [21, 8, 0]
+    Hd, cntd, zd = oracle.laser_forward(q, k, v, t0, wq, wk, wv, lens, w, gamma)
+    # equal counts: the packed batch is the dense one reshaped
+    Hr, cntr, zr = oracle.laser_forward_ragged(q.reshape(U * C, dq), k, v, t0.reshape(U * C, d), wq, wk, wv, lens,
+                                               np.arange(U + 1) * C, w, gamma)
+    assert np.array_equal(Hr, Hd.reshape(U * C, -1, d)) and np.array_equal(zr, zd.reshape(U * C, d))
+    assert np.array_equal(cntr, cntd)
+    # unequal counts, a user without candidates: every row equals the dense result of its (user, candidate)
+    take = [[0, 2, 3], [], [1]]
+    rows = [(u, c) for u in range(U) for c in take[u]]
+    off = np.cumsum([0] + [len(t) for t in take])
+    qp = np.stack([q[u, c] for u, c in rows])
+    tp = np.stack([t0[u, c] for u, c in rows])
+    Hr, cntr, zr = oracle.laser_forward_ragged(qp, k, v, tp, wq, wk, wv, lens, off, w, gamma)
+    for i, (u, c) in enumerate(rows):
+        assert np.array_equal(Hr[i], Hd[u, c]) and np.array_equal(zr[i], zd[u, c])
+    assert np.array_equal(cntr, cntd)
+    for bad in ([1, 3, 3, 4], [0, 3, 2, 4], [0, 3, 3, 5]):
+        with pytest.raises(ValueError):
+            oracle.laser_forward_ragged(qp, k, v, tp, wq, wk, wv, lens, bad, w, gamma)
