@@ -157,6 +157,9 @@ def main() -> int:
     ap.add_argument("--project", type=int, default=0, metavar="D_IN",
                     help="also time the projections ahead of STA (Q = t W_q, K = H W_k, V = H W_v from raw embeddings "
                          "of width D_IN) and the whole path that starts from them; reported under \"project\"")
+    ap.add_argument("--ragged", action="store_true",
+                    help="also time the packed-pairs entry point with a seeded ragged candidate count per user "
+                         "(uniform between a quarter of C and C); reported under \"ragged\"")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device copy 5 times (reference reading for the FETCH_SIZE / "
                          "WRITE_SIZE counters when this command runs under rocprofv3 --pmc)")
@@ -331,6 +334,38 @@ def main() -> int:
             dw.q.copy_(fresh.q), dw.k.copy_(fresh.k), dw.v.copy_(fresh.v)
         torch.cuda.synchronize()
 
+    ragged = None
+    if args.ragged:
+        rng = np.random.default_rng(spec.seed + 7)
+        counts = rng.integers(max(1, spec.C // 4), spec.C + 1, size=spec.U)
+        off_h = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+        Pr = int(off_h[-1])
+        off_d = torch.from_numpy(off_h).cuda()
+        dw0 = sets[0][0]
+        # the packed batch takes each user's first counts[u] candidates of the dense workload
+        rows = torch.from_numpy(np.concatenate([u * spec.C + np.arange(counts[u]) for u in range(spec.U)])).cuda()
+        qp = dw0.q.reshape(spec.U * spec.C, spec.d_q)[rows].contiguous()
+        tp = dw0.t0.reshape(spec.U * spec.C, spec.d)[rows].contiguous()
+        segp = torch.empty((Pr, spec.S, spec.d), dtype=tdt, device="cuda")
+        cntp = torch.empty((spec.U, spec.S), dtype=torch.int32, device="cuda")
+        zp = torch.empty((Pr, spec.d), dtype=torch.float32, device="cuda")
+
+        def step_ragged(i):
+            dw = sets[i % copies][0]
+            laser.laser_forward_ragged(qp, dw.k, dw.v, tp, dw.wq, dw.wk, dw.wv, dw.lens, off_d, spec.C, spec.w,
+                                       spec.gamma, seg_out=segp, seg_cnt=cntp, z_out=zp)
+
+        rag_ms = event_time(step_ragged)
+        # the same pairs against the dense result (bit for bit: the packing changes where a pair is stored only)
+        step(0)
+        step_ragged(0)
+        torch.cuda.synchronize()
+        same = bool(torch.equal(sets[0][1].reshape(spec.U * spec.C, spec.S, spec.d)[rows], segp) and
+                    torch.equal(sets[0][3].reshape(spec.U * spec.C, spec.d)[rows], zp))
+        ragged = {"pairs": Pr, "counts_min": int(counts.min()), "counts_max": int(counts.max()),
+                  "ms_per_step": rag_ms, "pairs_per_s": Pr / (rag_ms * 1e-3),
+                  "dense_padded_ms_per_step": ms_per_step, "equals_dense_rows": same}
+
     if args.calibration_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
@@ -393,6 +428,7 @@ def main() -> int:
         "views": views,
         "ffn": ffn,
         "project": project,
+        "ragged": ragged,
         "parity": {"max_vector_rel_err": worst, "tolerance": TOL[spec.dtype], "ok": bool(parity_ok),
                    "sampled_pairs": 4},
     }

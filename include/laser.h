@@ -156,6 +156,31 @@ laser_status laser_forward(const void* q, const void* k, const void* v, const vo
                            void* seg_out, int32_t* seg_cnt, float* z_out, void* stream);
 
 /*
+ * Ragged candidate counts per user (serving batches: every request brings its own number of candidates). The pair
+ * tensors are packed: q [P,d_q], t0 [P,d], seg_out [P,S,d], z_out [P,d] hold the P pairs of the batch one after the
+ * other, user by user, and cand_off [U+1] int32 (device) gives each user's rows, cand_off[u] .. cand_off[u+1]-1, with
+ * cand_off[0] = 0, non-decreasing, cand_off[U] = P, and at most C_max rows per user (C_max sizes the launch; users
+ * without candidates are allowed). Everything else (k, v, lens, seg_cnt [U,S], weights, arithmetic, kernels, limits
+ * with C_max in the place of C) is as in laser_sta_forward / laser_gsta_forward / laser_forward, and with equal
+ * counts the results are those of the dense entry points bit for bit. The host cannot see the offsets: on the device
+ * they are clamped so that no access leaves the P rows (a user's first row into [0, P], its count into
+ * [0, min(C_max, P - first)]); offsets that break the rules above give unspecified values in the rows concerned,
+ * never a fault. Rows that belong to no user are not written.
+ * Errors: as for the dense entry points, and LASER_ERR_NULL (cand_off), LASER_ERR_ALIGN (cand_off not 4-byte aligned),
+ * LASER_ERR_SHAPE (P < 1, P > U * C_max, P * S * d >= 2^31). Nothing is launched on an error.
+ */
+laser_status laser_sta_forward_ragged(const void* q, const void* k, const void* v, const int32_t* lens,
+                                      const int32_t* cand_off, int U, int C_max, int P, int L, int d_q, int d, int w,
+                                      float gamma, laser_dtype dt, void* seg_out, int32_t* seg_cnt, void* stream);
+laser_status laser_gsta_forward_ragged(const void* seg, const void* t0, const void* wq, const void* wk, const void* wv,
+                                       const int32_t* lens, const int32_t* cand_off, int U, int C_max, int P, int L,
+                                       int d, int w, int M, laser_dtype dt, float* z_out, void* stream);
+laser_status laser_forward_ragged(const void* q, const void* k, const void* v, const void* t0, const void* wq,
+                                  const void* wk, const void* wv, const int32_t* lens, const int32_t* cand_off, int U,
+                                  int C_max, int P, int L, int d_q, int d, int w, float gamma, int M, laser_dtype dt,
+                                  void* seg_out, int32_t* seg_cnt, float* z_out, void* stream);
+
+/*
  * Segment feed-forward step (paper Sec. 3.4.2, the equation after the STA paragraph): every segment vector of H'
  * becomes s <- LN(FFN(s) + s). The paper names neither the network's shape nor the normalisation's constants; here
  *   FFN(s) = relu(s W1 + b1) W2 + b2,  W1 [d, d_ff], W2 [d_ff, d]  (row vector times matrix, as everywhere),

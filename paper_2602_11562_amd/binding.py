@@ -21,7 +21,8 @@ FFN_AUTO, FFN_GENERIC, FFN_MFMA = 0, 1, 2
 PROJECT_AUTO, PROJECT_GENERIC, PROJECT_MFMA = 0, 1, 2
 
 EXPORTS = [
-    "laser_sta_forward", "laser_sta_forward_variant", "laser_sta_forward_heads", "laser_sta_forward_softmax", "laser_gsta_forward", "laser_gsta_forward_variant",
+    "laser_sta_forward", "laser_sta_forward_variant", "laser_sta_forward_heads", "laser_sta_forward_softmax", "laser_sta_forward_ragged",
+    "laser_gsta_forward_ragged", "laser_forward_ragged", "laser_gsta_forward", "laser_gsta_forward_variant",
     "laser_forward", "laser_multires_forward", "laser_forward_multires", "laser_sta_kernel_name",
     "laser_gsta_kernel_name", "laser_segment_ffn_forward", "laser_segment_ffn_forward_variant",
     "laser_gsta_kernel_name_layers", "laser_project_q_forward", "laser_project_q_forward_variant",
@@ -84,6 +85,12 @@ def load_library() -> ctypes.CDLL:
     lib.laser_sta_folded_forward.argtypes = [vp, vp, vp, vp, ip, i32, i32, i32, i32, i32, i32, f32, i32, i32,
                                              vp, vp, vp, ip, vp]
     for name in ("laser_fold_query_weights", "laser_project_heads_forward", "laser_sta_folded_forward"):
+        getattr(lib, name).restype = i32
+    lib.laser_sta_forward_ragged.argtypes = [vp, vp, vp, ip, ip, i32, i32, i32, i32, i32, i32, i32, f32, i32, vp, ip, vp]
+    lib.laser_gsta_forward_ragged.argtypes = [vp, vp, vp, vp, vp, ip, ip, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp]
+    lib.laser_forward_ragged.argtypes = [vp, vp, vp, vp, vp, vp, vp, ip, ip, i32, i32, i32, i32, i32, i32, i32, f32,
+                                         i32, i32, vp, ip, vp, vp]
+    for name in ("laser_sta_forward_ragged", "laser_gsta_forward_ragged", "laser_forward_ragged"):
         getattr(lib, name).restype = i32
     lib.laser_sta_kernel_name.argtypes = [i32, i32, i32, i32, i32]
     lib.laser_sta_kernel_name.restype = ctypes.c_char_p
@@ -278,6 +285,44 @@ def laser_project_kv_forward(h, w_k, w_v, k_out=None, v_out=None, stream=None, v
         _ptr(v_out, "v_out", h.dtype), _stream(stream), int(variant))
     _check(code, "laser_project_kv_forward")
     return k_out, v_out
+
+
+def laser_forward_ragged(q, k, v, t0, wq, wk, wv, lens, cand_off, c_max: int, w: int, gamma: float, seg_out=None,
+                         seg_cnt=None, z_out=None, stream=None, want_cnt: bool = True, stage: str = "both"):
+    """Packed pairs: q [P,d_q], t0 [P,d] with cand_off int32 [U+1] (device) -> (H' [P,S,d], cnt [U,S], z [P,d] fp32).
+    stage = "sta" runs STA only (t0 and the weights may be None, z is None), "gsta" runs GSTA only on seg_out."""
+    torch = _torch()
+    U, L = k.shape[0], k.shape[1]
+    P = q.shape[0] if q is not None else seg_out.shape[0]
+    d = v.shape[2]
+    S = -(-L // w)
+    if tuple(cand_off.shape) != (U + 1,):
+        raise ValueError("cand_off must be [U + 1]")
+    dev, tdt = k.device, k.dtype
+    if seg_out is None:
+        seg_out = torch.empty((P, S, d), dtype=tdt, device=dev)
+    if seg_cnt is None and want_cnt and stage != "gsta":
+        seg_cnt = torch.empty((U, S), dtype=torch.int32, device=dev)
+    if z_out is None and stage != "sta":
+        z_out = torch.empty((P, d), dtype=torch.float32, device=dev)
+    lib = load_library()
+    common = (_ptr(lens, "lens", torch.int32), _ptr(cand_off, "cand_off", torch.int32), U, int(c_max), P, L)
+    if stage == "sta":
+        code = lib.laser_sta_forward_ragged(_ptr(q, "q"), _ptr(k, "k"), _ptr(v, "v"), *common, q.shape[1], d, int(w),
+                                            float(gamma), _dt(k), _ptr(seg_out, "seg_out", tdt),
+                                            _ptr(seg_cnt, "seg_cnt", torch.int32), _stream(stream))
+    elif stage == "gsta":
+        code = lib.laser_gsta_forward_ragged(_ptr(seg_out, "seg_out"), _ptr(t0, "t0"), _ptr(wq, "wq"), _ptr(wk, "wk"),
+                                             _ptr(wv, "wv"), *common, d, int(w), wq.shape[0], _dt(k),
+                                             _ptr(z_out, "z_out", torch.float32), _stream(stream))
+    else:
+        code = lib.laser_forward_ragged(_ptr(q, "q"), _ptr(k, "k"), _ptr(v, "v"), _ptr(t0, "t0"), _ptr(wq, "wq"),
+                                        _ptr(wk, "wk"), _ptr(wv, "wv"), *common, q.shape[1], d, int(w), float(gamma),
+                                        wq.shape[0], _dt(k), _ptr(seg_out, "seg_out", tdt),
+                                        _ptr(seg_cnt, "seg_cnt", torch.int32), _ptr(z_out, "z_out", torch.float32),
+                                        _stream(stream))
+    _check(code, "laser_forward_ragged")
+    return seg_out, seg_cnt, z_out
 
 
 def laser_fold_query_weights(w_q, w_k, heads: int = 1, a_out=None, stream=None):

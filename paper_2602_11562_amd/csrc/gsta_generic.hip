@@ -14,8 +14,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void gsta_generic_kernel(const T* __restrict__ seg, const T* __restrict__ t0,
                                                            const T* __restrict__ wq, const T* __restrict__ wk,
                                                            const T* __restrict__ wv, const int32_t* __restrict__ lens,
-                                                           int C, int L, int d, int w, int S, int M,
-                                                           float* __restrict__ z) {
+                                                           const int32_t* __restrict__ cand_off, int U, int C, int L,
+                                                           int d, int w, int S, int M, float* __restrict__ z) {
   extern __shared__ float smem[];
   float* ts = smem;        // [d] running target vector t_l
   float* qp = ts + d;      // [d] t W_q
@@ -25,7 +25,7 @@ __global__ __launch_bounds__(256) void gsta_generic_kernel(const T* __restrict__
   __shared__ float red[2];
 
   const int pair = blockIdx.x;
-  const int u = pair / C;
+  const int u = pair_user(cand_off, U, C, pair);
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int n = valid_len(lens, u, L);
   const int nv = (n + w - 1) / w;          // valid segments are a prefix
@@ -98,15 +98,16 @@ bool gsta_generic_supports(const GstaArgs& a) {
 laser_status gsta_generic_launch(const GstaArgs& a) {
   if (!gsta_generic_supports(a)) return LASER_ERR_UNSUPPORTED;
   const size_t lds = sizeof(float) * (4 * (size_t)a.d + a.S);
-  const unsigned blocks = (unsigned)(a.U * a.C);
+  const unsigned blocks = (unsigned)gsta_pairs(a);
+  if (blocks == 0) return LASER_OK;
   if (a.dt == LASER_F32) {
     hipLaunchKernelGGL(gsta_generic_kernel<float>, dim3(blocks), dim3(256), lds, a.stream, (const float*)a.seg,
-                       (const float*)a.t0, (const float*)a.wq, (const float*)a.wk, (const float*)a.wv, a.lens, a.C,
+                       (const float*)a.t0, (const float*)a.wq, (const float*)a.wk, (const float*)a.wv, a.lens, a.cand_off, a.U, a.C,
                        a.L, a.d, a.w, a.S, a.M, a.z_out);
   } else {
     hipLaunchKernelGGL(gsta_generic_kernel<unsigned short>, dim3(blocks), dim3(256), lds, a.stream,
                        (const unsigned short*)a.seg, (const unsigned short*)a.t0, (const unsigned short*)a.wq,
-                       (const unsigned short*)a.wk, (const unsigned short*)a.wv, a.lens, a.C, a.L, a.d, a.w, a.S,
+                       (const unsigned short*)a.wk, (const unsigned short*)a.wv, a.lens, a.cand_off, a.U, a.C, a.L, a.d, a.w, a.S,
                        a.M, a.z_out);
   }
   return launch_status();

@@ -154,7 +154,7 @@ __global__ __launch_bounds__(GT_THREADS) void gsta_tiled_kernel(const unsigned s
                                                          const unsigned short* __restrict__ wq,
                                                          const unsigned short* __restrict__ wk,
                                                          const unsigned short* __restrict__ wv,
-                                                         const int32_t* __restrict__ lens, int P, int C, int L, int w,
+                                                         const int32_t* __restrict__ lens, const int32_t* __restrict__ cand_off, int U, int P, int C, int L, int w,
                                                          int S, int M, float* __restrict__ z) {
   constexpr int FP = D + 4;          // fp32 row pitch: 16 B mod 256 B, conflict-free 16-byte row reads
   constexpr int DB = D / 32;         // 32-column blocks; waves >= DB idle in the MFMA steps
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(GT_THREADS) void gsta_tiled_kernel(const unsigned s
   for (int it = 0; it < PPW; ++it) {
     const int pr = pbase + wave + it * GT_WAVES;
     nvs[it] = 0;
-    if (pr < P) nvs[it] = (valid_len(lens, pr / C, L) + w - 1) / w;
+    if (pr < P) nvs[it] = (valid_len(lens, pair_user(cand_off, U, C, pr), L) + w - 1) / w;
   }
   // H' block of one pair: rows j*RPW + grp, 16 bytes per lane; rows of invalid segments are not read.
   // DEPTH blocks are kept in flight per wave (a ring of register sets).
@@ -304,7 +304,7 @@ __global__ __launch_bounds__(GT_THREADS) void gsta_tiled_kernel(const unsigned s
       for (int it = 0; it < PPW; ++it) {
         const int pr = pbase + wave + it * GT_WAVES;
         int nv = 0;
-        if (pr < P) nv = (valid_len(lens, pr / C, L) + w - 1) / w;
+        if (pr < P) nv = (valid_len(lens, pair_user(cand_off, U, C, pr), L) + w - 1) / w;
         if (it > 0) load_pair(wave + it * GT_WAVES, nv, hring[0]);
         reduce_pair(wave + it * GT_WAVES, nv, hring[0], -1, 0);
       }
@@ -477,7 +477,7 @@ __global__ __launch_bounds__(GS_THREADS) void gsta_out_kernel(const unsigned sho
 // one wave per pair; ROWS register rows of 16 bytes cover the pair's S x D block
 template <int D, int ROWS>
 __global__ __launch_bounds__(GS_THREADS) void gsta_pool_kernel(const unsigned short* __restrict__ seg,
-                                                               const int32_t* __restrict__ lens, int P, int C, int L,
+                                                               const int32_t* __restrict__ lens, const int32_t* __restrict__ cand_off, int U, int P, int C, int L,
                                                                int w, int S, float* __restrict__ z) {
   constexpr int LPR = D / 8, RPW = 64 / LPR;
   const int lane = threadIdx.x & 63;
@@ -485,7 +485,7 @@ __global__ __launch_bounds__(GS_THREADS) void gsta_pool_kernel(const unsigned sh
   const int pr = blockIdx.x * (GS_THREADS / 64) + wave;
   if (pr >= P) return;
   const int grp = lane / LPR, gl = lane % LPR;
-  const int nv = (valid_len(lens, pr / C, L) + w - 1) / w;
+  const int nv = (valid_len(lens, pair_user(cand_off, U, C, pr), L) + w - 1) / w;
   const unsigned short* H = seg + (size_t)pr * S * D;
   u32x4 hreg[ROWS];
 #pragma unroll
@@ -592,7 +592,7 @@ __global__ __launch_bounds__(GT_THREADS) void gsta_one_kernel(const unsigned sho
                                                               const unsigned short* __restrict__ wq,
                                                               const unsigned short* __restrict__ wk,
                                                               const unsigned short* __restrict__ wv,
-                                                              const int32_t* __restrict__ lens, int P, int C, int L,
+                                                              const int32_t* __restrict__ lens, const int32_t* __restrict__ cand_off, int U, int P, int C, int L,
                                                               int w, int S, float* __restrict__ z,
                                                               u32x4* __restrict__ pool, u32x4* __restrict__ recent,
                                                               int r) {
@@ -622,7 +622,7 @@ __global__ __launch_bounds__(GT_THREADS) void gsta_one_kernel(const unsigned sho
 #pragma unroll
   for (int it = 0; it < PPU; ++it) {
     const int pr = pbase + pfirst + it;
-    nvs[it] = (pr < P && (it < PPL || !front)) ? (valid_len(lens, pr / C, L) + w - 1) / w : 0;
+    nvs[it] = (pr < P && (it < PPL || !front)) ? (valid_len(lens, pair_user(cand_off, U, C, pr), L) + w - 1) / w : 0;
   }
 
   // One register set per pair. A wave issues in order, and a compute unit's memory pipeline accepts requests only
@@ -865,10 +865,10 @@ bool gsta_tiled_supports(const GstaArgs& a) {
 
 template <int D, int ROWS, int PT>
 static void launch_pt(const GstaArgs& a) {
-  const int P = a.U * a.C;
+  const int P = gsta_pairs(a);
   hipLaunchKernelGGL((gsta_tiled_kernel<D, ROWS, PT>), dim3((P + PT - 1) / PT), dim3(GT_THREADS), 0, a.stream,
                      (const unsigned short*)a.seg, (const unsigned short*)a.t0, (const unsigned short*)a.wq,
-                     (const unsigned short*)a.wk, (const unsigned short*)a.wv, a.lens, P, a.C, a.L, a.w, a.S, a.M,
+                     (const unsigned short*)a.wk, (const unsigned short*)a.wv, a.lens, a.cand_off, a.U, P, a.C, a.L, a.w, a.S, a.M,
                      a.z_out);
 }
 
@@ -884,7 +884,7 @@ static int pick_pt(int P) {
 
 template <int D, int ROWS>
 static void launch_rows(const GstaArgs& a) {
-  const int pt = pick_pt(a.U * a.C);
+  const int pt = pick_pt(gsta_pairs(a));
   if (pt == 32) launch_pt<D, ROWS, 32>(a);
   else if (pt == 16) launch_pt<D, ROWS, 16>(a);
   else launch_pt<D, ROWS, 8>(a);
@@ -901,7 +901,7 @@ static void launch_d(const GstaArgs& a) {
 
 template <int D>
 static void launch_split(const GstaArgs& a) {
-  const int P = a.U * a.C;
+  const int P = gsta_pairs(a);
   const unsigned tiles = (unsigned)((P + GT_ROWS - 1) / GT_ROWS);
   const unsigned short* t0 = (const unsigned short*)a.t0;
   hipLaunchKernelGGL((gsta_r_kernel<D>), dim3(tiles), dim3(GS_THREADS), 0, a.stream, t0,
@@ -910,7 +910,7 @@ static void launch_split(const GstaArgs& a) {
   const unsigned pblocks = (unsigned)((P + GS_THREADS / 64 - 1) / (GS_THREADS / 64));
 #define LASER_POOL(R)                                                                                             \
   hipLaunchKernelGGL((gsta_pool_kernel<D, R>), dim3(pblocks), dim3(GS_THREADS), 0, a.stream,                     \
-                     (const unsigned short*)a.seg, a.lens, P, a.C, a.L, a.w, a.S, a.z_out)
+                     (const unsigned short*)a.seg, a.lens, a.cand_off, a.U, P, a.C, a.L, a.w, a.S, a.z_out)
   if (rows <= 2) LASER_POOL(2);
   else if (rows <= 4) LASER_POOL(4);
   else if (rows <= 8) LASER_POOL(8);
@@ -943,13 +943,13 @@ bool gsta_one_supports(const GstaArgs& a) {
 
 template <int D>
 static void launch_one_kernel(const GstaArgs& a) {
-  const int P = a.U * a.C;
+  const int P = gsta_pairs(a);
   const unsigned tiles = (unsigned)((P + GT_ROWS - 1) / GT_ROWS);
   const int rows = rows_needed(a.S, a.d);
 #define LASER_ONE_MR(R, PU, MRF)                                                                                   \
   hipLaunchKernelGGL((gsta_one_kernel<D, R, PU, MRF>), dim3(tiles), dim3(GT_THREADS), 0, a.stream,                \
                      (const unsigned short*)a.seg, (const unsigned short*)a.t0, (const unsigned short*)a.wq,       \
-                     (const unsigned short*)a.wk, (const unsigned short*)a.wv, a.lens, P, a.C, a.L, a.w, a.S,      \
+                     (const unsigned short*)a.wk, (const unsigned short*)a.wv, a.lens, a.cand_off, a.U, P, a.C, a.L, a.w, a.S,      \
                      a.z_out, (u32x4*)a.pool_out, (u32x4*)a.recent_out, a.r)
 #define LASER_ONE(R, PU)                                                                                           \
   do {                                                                                                             \

@@ -142,6 +142,62 @@ laser_status laser_sta_forward_softmax(const void* q, const void* k, const void*
   return run_sta(a, variant);
 }
 
+// Ragged candidate counts: the pair tensors hold P rows, user u's candidates are rows cand_off[u] .. cand_off[u+1]-1
+static laser_status validate_ragged(const int32_t* cand_off, int U, int C_max, int P, int L, int d_q, int d, int w) {
+  if (!cand_off) return LASER_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(cand_off) & 3u) return LASER_ERR_ALIGN;
+  if (P <= 0 || (long long)P > (long long)U * C_max) return LASER_ERR_SHAPE;
+  const long long S = ((long long)L + w - 1) / w;
+  if ((long long)P * S * d > 0x7fffffffLL || (long long)P * d_q > 0x7fffffffLL) return LASER_ERR_SHAPE;
+  return LASER_OK;
+}
+
+laser_status laser_sta_forward_ragged(const void* q, const void* k, const void* v, const int32_t* lens,
+                                      const int32_t* cand_off, int U, int C_max, int P, int L, int d_q, int d, int w,
+                                      float gamma, laser_dtype dt, void* seg_out, int32_t* seg_cnt, void* stream) {
+  StaArgs a;
+  laser_status s = validate_sta(q, k, v, lens, U, C_max, L, d_q, d, w, gamma, dt, seg_out, seg_cnt, stream, &a);
+  if (s != LASER_OK) return s;
+  s = validate_ragged(cand_off, U, C_max, P, L, d_q, d, w);
+  if (s != LASER_OK) return s;
+  a.cand_off = cand_off;
+  a.P = P;
+  return run_sta(a, LASER_STA_AUTO);
+}
+
+laser_status laser_gsta_forward_ragged(const void* seg, const void* t0, const void* wq, const void* wk, const void* wv,
+                                       const int32_t* lens, const int32_t* cand_off, int U, int C_max, int P, int L,
+                                       int d, int w, int M, laser_dtype dt, float* z_out, void* stream) {
+  GstaArgs a;
+  laser_status s = validate_gsta(seg, t0, wq, wk, wv, lens, U, C_max, L, d, w, M, dt, z_out, stream, &a);
+  if (s != LASER_OK) return s;
+  s = validate_ragged(cand_off, U, C_max, P, L, d, d, w);
+  if (s != LASER_OK) return s;
+  a.cand_off = cand_off;
+  a.P = P;
+  return run_gsta(a, LASER_GSTA_AUTO);
+}
+
+laser_status laser_forward_ragged(const void* q, const void* k, const void* v, const void* t0, const void* wq,
+                                  const void* wk, const void* wv, const int32_t* lens, const int32_t* cand_off, int U,
+                                  int C_max, int P, int L, int d_q, int d, int w, float gamma, int M, laser_dtype dt,
+                                  void* seg_out, int32_t* seg_cnt, float* z_out, void* stream) {
+  StaArgs sa;
+  GstaArgs ga;
+  laser_status s = validate_sta(q, k, v, lens, U, C_max, L, d_q, d, w, gamma, dt, seg_out, seg_cnt, stream, &sa);
+  if (s != LASER_OK) return s;
+  s = validate_gsta(seg_out, t0, wq, wk, wv, lens, U, C_max, L, d, w, M, dt, z_out, stream, &ga);
+  if (s != LASER_OK) return s;
+  s = validate_ragged(cand_off, U, C_max, P, L, d_q, d, w);
+  if (s != LASER_OK) return s;   // everything validated before the first launch
+  sa.cand_off = ga.cand_off = cand_off;
+  sa.P = ga.P = P;
+  sa.reread = true;
+  s = run_sta(sa, LASER_STA_AUTO);
+  if (s != LASER_OK) return s;
+  return run_gsta(ga, LASER_GSTA_AUTO);
+}
+
 laser_status laser_sta_forward(const void* q, const void* k, const void* v, const int32_t* lens, int U, int C,
                                int L, int d_q, int d, int w, float gamma, laser_dtype dt, void* seg_out,
                                int32_t* seg_cnt, void* stream) {

@@ -21,6 +21,10 @@ struct StaArgs {
   int32_t* seg_cnt;   // may be nullptr
   hipStream_t stream;
   bool reread;        // H' is read again right after this launch (the whole path): store it cacheable
+  // ragged candidate counts: user u owns pairs cand_off[u] .. cand_off[u+1]-1 of q and seg_out (at most C of
+  // them), P pairs in all; nullptr = every user has exactly C (pair index u * C + c)
+  const int32_t* cand_off = nullptr;
+  int P = 0;
   int heads = 1;      // attention heads: head h owns the h-th run of d_q / heads and d / heads columns
   bool softmax = false;   // softmax over a segment's valid items instead of sigmoid gates (ablation of Sec. 4.4.1)
 };
@@ -40,6 +44,9 @@ struct GstaArgs {
   void* pool_out = nullptr;
   void* recent_out = nullptr;
   int r = 0;
+  // ragged candidate counts, as in StaArgs (seg, t0 and z_out hold P pairs)
+  const int32_t* cand_off = nullptr;
+  int P = 0;
 };
 
 struct MultiresArgs {
@@ -52,6 +59,7 @@ struct MultiresArgs {
   hipStream_t stream;
 };
 laser_status multires_launch(const MultiresArgs& a);
+inline int gsta_pairs(const GstaArgs& a) { return a.cand_off ? a.P : a.U * a.C; }   // pairs in seg, t0 and z_out
 
 struct FfnArgs {
   const void* seg;
@@ -156,6 +164,32 @@ __device__ __forceinline__ int valid_len(const int32_t* lens, int u, int L) {
   if (lens == nullptr) return L;
   int n = lens[u];
   return n < 0 ? 0 : (n > L ? L : n);
+}
+
+// Pairs of user u: first pair index and how many. Dense layout (cand_off == nullptr): u * C and C. Ragged layout:
+// cand_off[u] and cand_off[u+1] - cand_off[u], clamped to [0, P] and [0, min(C, P - first)], so that whatever the
+// offsets hold, no index leaves the P pairs the buffers have.
+struct CandRange { int first, count; };
+__device__ __forceinline__ CandRange cand_range(const int32_t* cand_off, int u, int C, int P) {
+  if (cand_off == nullptr) return CandRange{u * C, C};
+  int b = cand_off[u], n = cand_off[u + 1] - b;
+  b = b < 0 ? 0 : (b > P ? P : b);
+  const int room = (P - b) < C ? (P - b) : C;
+  n = n < 0 ? 0 : (n > room ? room : n);
+  return CandRange{b, n};
+}
+
+// User of pair pr: pr / C in the dense layout, else the last u with cand_off[u] <= pr (users without candidates
+// share their offset with the next user and are passed over).
+__device__ __forceinline__ int pair_user(const int32_t* cand_off, int U, int C, int pr) {
+  if (cand_off == nullptr) return pr / C;
+  int lo = 0, hi = U;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (cand_off[mid] <= pr) lo = mid;
+    else hi = mid;
+  }
+  return lo;
 }
 
 // seg_cnt[u, i] = number of valid items of user u inside segment i (integer, exact). Called by one workgroup per

@@ -19,7 +19,8 @@ constexpr int GEN_MAX_COLS = 16;  // d <= 64 * 16
 template <typename T>
 __global__ __launch_bounds__(256) void sta_generic_kernel(const T* __restrict__ q, const T* __restrict__ k,
                                                           const T* __restrict__ v, const int32_t* __restrict__ lens,
-                                                          int C, int L, int dq, int d, int w, int S, int TI,
+                                                          const int32_t* __restrict__ cand_off, int P, int C_all,
+                                                          int L, int dq, int d, int w, int S, int TI,
                                                           int heads, int softmax, float inv_gamma,
                                                           T* __restrict__ seg_out,
                                                           int32_t* __restrict__ seg_cnt) {
@@ -32,7 +33,7 @@ __global__ __launch_bounds__(256) void sta_generic_kernel(const T* __restrict__ 
   // several heads (Sec. 4.1.2): head h owns the h-th run of dq / heads columns of q and k and of d / heads columns of v
   const int dqh = dq / heads, dh = d / heads;
 
-  const int cblocks = (C + GEN_WAVES - 1) / GEN_WAVES;
+  const int cblocks = (C_all + GEN_WAVES - 1) / GEN_WAVES;
   int bid = blockIdx.x;
   const int i = bid % S;
   bid /= S;
@@ -40,18 +41,22 @@ __global__ __launch_bounds__(256) void sta_generic_kernel(const T* __restrict__ 
   const int u = bid / cblocks;
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const CandRange cr = cand_range(cand_off, u, C_all, P);
+  const int C = cr.count;            // this user's candidates
+  const size_t pb = (size_t)cr.first;   // and the index of their first pair
   const int c = cb * GEN_WAVES + wave;
   const bool active = c < C;
 
   const int n = valid_len(lens, u, L);
   if (i == 0 && cb == 0) write_seg_cnt(seg_cnt, u, n, L, w, S, tid, 256);
+  if (cb * GEN_WAVES >= C) return;   // a candidate block past this user's count (the whole workgroup leaves)
   const int lo = i * w;
   int hi = lo + w;
   if (hi > L) hi = L;
   if (hi > n) hi = n;
 
   for (int a = lane; a < dq; a += 64)
-    qs[wave * dq + a] = active ? load_as_f32(q, ((size_t)u * C + c) * dq + a) : 0.0f;
+    qs[wave * dq + a] = active ? load_as_f32(q, (pb + c) * dq + a) : 0.0f;
 
   // softmax (ablation of Sec. 4.4.1): gs then holds the scaled scores, and every column keeps a running maximum
   // and denominator of its head's scores, rescaling its sum when the maximum moves (items in ascending order)
@@ -108,7 +113,7 @@ __global__ __launch_bounds__(256) void sta_generic_kernel(const T* __restrict__ 
   }
 
   if (active) {
-    const size_t base = (((size_t)u * C + c) * S + i) * d;
+    const size_t base = ((pb + c) * S + i) * d;
 #pragma unroll
     for (int b = 0; b < GEN_MAX_COLS; ++b) {
       const int col = lane + 64 * b;
@@ -143,12 +148,12 @@ laser_status sta_generic_launch(const StaArgs& a) {
   const float inv_gamma = 1.0f / a.gamma;
   if (a.dt == LASER_F32) {
     hipLaunchKernelGGL(sta_generic_kernel<float>, dim3(blocks), dim3(256), lds, a.stream, (const float*)a.q,
-                       (const float*)a.k, (const float*)a.v, a.lens, a.C, a.L, a.d_q, a.d, a.w, a.S, TI, a.heads,
+                       (const float*)a.k, (const float*)a.v, a.lens, a.cand_off, a.P, a.C, a.L, a.d_q, a.d, a.w, a.S, TI, a.heads,
                        a.softmax ? 1 : 0, inv_gamma, (float*)a.seg_out, a.seg_cnt);
   } else {
     hipLaunchKernelGGL(sta_generic_kernel<unsigned short>, dim3(blocks), dim3(256), lds, a.stream,
                        (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens,
-                       a.C, a.L, a.d_q, a.d, a.w, a.S, TI, a.heads, a.softmax ? 1 : 0, inv_gamma,
+                       a.cand_off, a.P, a.C, a.L, a.d_q, a.d, a.w, a.S, TI, a.heads, a.softmax ? 1 : 0, inv_gamma,
                        (unsigned short*)a.seg_out, a.seg_cnt);
   }
   return launch_status();

@@ -107,7 +107,9 @@ template <int DQ, int D, int NW, int NBUF>
 __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short* __restrict__ q,
                                                            const unsigned short* __restrict__ k,
                                                            const unsigned short* __restrict__ v,
-                                                           const int32_t* __restrict__ lens, int C, int L, int w,
+                                                           const int32_t* __restrict__ lens,
+                                                           const int32_t* __restrict__ cand_off, int P, int C_all,
+                                                           int L, int w,
                                                            int S, int spw, int ctiles, int sruns,
                                                            float neg_scale_log2e, unsigned short* __restrict__ seg_out,
                                                            int32_t* __restrict__ seg_cnt) {
@@ -123,6 +125,13 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short*
   bid /= sruns;
   const int ct = bid % ctiles;
   const int u = bid / ctiles;
+  const CandRange crange = cand_range(cand_off, u, C_all, P);
+  const int C = crange.count;               // this user's candidates
+  const size_t pb = (size_t)crange.first;   // and the index of their first pair
+  if (ct * (CW * NW) >= C) {   // a candidate tile past this user's count: nothing to do (the first still writes the counts)
+    if (srun == 0 && ct == 0) write_seg_cnt(seg_cnt, u, valid_len(lens, u, L), L, w, S, threadIdx.x, 64 * NW);
+    return;
+  }
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int l32 = lane & 31, h = lane >> 5;
@@ -138,7 +147,7 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short*
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) {
       u32x4 raw = {0u, 0u, 0u, 0u};
-      if (c < C) raw = *reinterpret_cast<const u32x4*>(q + ((size_t)u * C + c) * DQ + ks * 16 + h * 8);
+      if (c < C) raw = *reinterpret_cast<const u32x4*>(q + (pb + c) * DQ + ks * 16 + h * 8);
       qreg[ks] = __builtin_bit_cast(bf16x8, raw);
     }
   }
@@ -185,7 +194,7 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short*
       const u32x4 val = *reinterpret_cast<const u32x4*>(opatch + row * OP + (lane % LPR) * 16);
       const int cr = cbase + row;
       if (cr < C)
-        *reinterpret_cast<u32x4*>(seg_out + (((size_t)u * C + cr) * S + seg) * D + (lane % LPR) * 8) = val;
+        *reinterpret_cast<u32x4*>(seg_out + ((pb + cr) * S + seg) * D + (lane % LPR) * 8) = val;
     }
   };
   int out_seg = -1;
@@ -299,7 +308,7 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short*
     for (int e = tid; e < rows * per_row; e += NT) {
       const int row = e / per_row, ch = e - row * per_row;
       const int cc = row / (seg_hi - seg_ne), ii = seg_ne + row % (seg_hi - seg_ne);
-      *reinterpret_cast<u32x4*>(seg_out + (((size_t)u * C + ct * (CW * NW) + cc) * S + ii) * D + ch * 8) =
+      *reinterpret_cast<u32x4*>(seg_out + ((pb + ct * (CW * NW) + cc) * S + ii) * D + ch * 8) =
           u32x4{0u, 0u, 0u, 0u};
     }
   }
@@ -319,7 +328,9 @@ template <int DQ, int D, int NW>
 __global__ __launch_bounds__(64 * NW) void sta_mfma_pipe_kernel(const unsigned short* __restrict__ q,
                                                                 const unsigned short* __restrict__ k,
                                                                 const unsigned short* __restrict__ v,
-                                                                const int32_t* __restrict__ lens, int C, int L,
+                                                                const int32_t* __restrict__ lens,
+                                                                const int32_t* __restrict__ cand_off, int P, int C_all,
+                                                                int L,
                                                                 int w, int S, int spw, int ctiles, int sruns,
                                                                 float neg_scale_log2e,
                                                                 unsigned short* __restrict__ seg_out,
@@ -336,6 +347,13 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_pipe_kernel(const unsigned s
   bid /= sruns;
   const int ct = bid % ctiles;
   const int u = bid / ctiles;
+  const CandRange crange = cand_range(cand_off, u, C_all, P);
+  const int C = crange.count;               // this user's candidates
+  const size_t pb = (size_t)crange.first;   // and the index of their first pair
+  if (ct * (CW * NW) >= C) {   // a candidate tile past this user's count: nothing to do (the first still writes the counts)
+    if (srun == 0 && ct == 0) write_seg_cnt(seg_cnt, u, valid_len(lens, u, L), L, w, S, threadIdx.x, 64 * NW);
+    return;
+  }
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int l32 = lane & 31, h = lane >> 5;
@@ -350,7 +368,7 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_pipe_kernel(const unsigned s
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) {
       u32x4 raw = {0u, 0u, 0u, 0u};
-      if (c < C) raw = *reinterpret_cast<const u32x4*>(q + ((size_t)u * C + c) * DQ + ks * 16 + h * 8);
+      if (c < C) raw = *reinterpret_cast<const u32x4*>(q + (pb + c) * DQ + ks * 16 + h * 8);
       qreg[ks] = __builtin_bit_cast(bf16x8, raw);
     }
   }
@@ -417,7 +435,7 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_pipe_kernel(const unsigned s
       const u32x4 val = *reinterpret_cast<const u32x4*>(opatch + row * OP + (lane % LPR) * 16);
       const int cr = cbase + row;
       if (cr < C)
-        *reinterpret_cast<u32x4*>(seg_out + (((size_t)u * C + cr) * S + seg) * D + (lane % LPR) * 8) = val;
+        *reinterpret_cast<u32x4*>(seg_out + ((pb + cr) * S + seg) * D + (lane % LPR) * 8) = val;
     }
   };
 
@@ -490,7 +508,7 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_pipe_kernel(const unsigned s
     for (int e = tid; e < rows * per_row; e += NT) {
       const int row = e / per_row, ch = e - row * per_row;
       const int cc = row / (seg_hi - seg_ne), ii = seg_ne + row % (seg_hi - seg_ne);
-      *reinterpret_cast<u32x4*>(seg_out + (((size_t)u * C + ct * (CW * NW) + cc) * S + ii) * D + ch * 8) =
+      *reinterpret_cast<u32x4*>(seg_out + ((pb + ct * (CW * NW) + cc) * S + ii) * D + ch * 8) =
           u32x4{0u, 0u, 0u, 0u};
     }
   }
@@ -596,7 +614,9 @@ template <int NW, bool NTS>
 __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned short* __restrict__ q,
                                                                const unsigned short* __restrict__ k,
                                                                const unsigned short* __restrict__ v,
-                                                               const int32_t* __restrict__ lens, int C, int L, int w,
+                                                               const int32_t* __restrict__ lens,
+                                                           const int32_t* __restrict__ cand_off, int P, int C_all,
+                                                           int L, int w,
                                                                int S, int spw, int ctiles, int sruns,
                                                                float neg_scale_log2e,
                                                                unsigned short* __restrict__ seg_out,
@@ -620,6 +640,13 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
   bid /= sruns;
   const int ct = bid % ctiles;
   const int u = bid / ctiles;
+  const CandRange crange = cand_range(cand_off, u, C_all, P);
+  const int C = crange.count;               // this user's candidates
+  const size_t pb = (size_t)crange.first;   // and the index of their first pair
+  if (ct * (CW * NW) >= C) {   // a candidate tile past this user's count: nothing to do (the first still writes the counts)
+    if (srun == 0 && ct == 0) write_seg_cnt(seg_cnt, u, valid_len(lens, u, L), L, w, S, threadIdx.x, 64 * NW);
+    return;
+  }
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: fetch addresses and cursors stay scalar
@@ -635,7 +662,7 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
   const int frow = lane >> 4, fpos = lane & 15;
   const unsigned qlds = lds_base + DT_NBUF * TB + wave * OBYTES;
   {
-    const unsigned char* qU = reinterpret_cast<const unsigned char*>(q + (size_t)u * C * DQ);
+    const unsigned char* qU = reinterpret_cast<const unsigned char*>(q + pb * DQ);
 #pragma unroll
     for (int j = 0; j < CW / 4; ++j) {
       const int row = j * 4 + frow;
@@ -742,7 +769,7 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
   const unsigned char* opr = opatch + (lane / LPR) * OP + (lane % LPR) * 16;
   const unsigned ooff = (unsigned)(lane / LPR) * (unsigned)S * (D * 2) + (lane % LPR) * 16;
   const unsigned ooff2 = ooff + (unsigned)RPI * (unsigned)S * (D * 2);   // the unit's second row group
-  unsigned char* oU = reinterpret_cast<unsigned char*>(seg_out) + ((size_t)u * C + cbase) * S * (D * 2);
+  unsigned char* oU = reinterpret_cast<unsigned char*>(seg_out) + (pb + cbase) * S * (D * 2);
   const bool all_rows = cbase + CW <= C;
   // A finished segment leaves in FU units of two row groups (eight rows, 2 KB per wave), a few per step: all
   // waves of a compute unit storing whole patches in the same step saturate its store path for most of a step
@@ -997,7 +1024,7 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
     for (int e = tid; e < rows * per_row; e += NT) {
       const int row = e / per_row, ch = e - row * per_row;
       const int cc = row / (seg_hi - seg_ne), ii = seg_ne + row % (seg_hi - seg_ne);
-      *reinterpret_cast<u32x4*>(seg_out + (((size_t)u * C + ct * (CW * NW) + cc) * S + ii) * D + ch * 8) =
+      *reinterpret_cast<u32x4*>(seg_out + ((pb + ct * (CW * NW) + cc) * S + ii) * D + ch * 8) =
           u32x4{0u, 0u, 0u, 0u};
     }
   }
@@ -1021,7 +1048,7 @@ template <int DQ, int D, int NW, int NBUF>
 static void launch_one(const StaArgs& a, int spw, int ctiles, int sruns, float nsl) {
   const unsigned blocks = (unsigned)((long long)a.U * ctiles * sruns);
   hipLaunchKernelGGL((sta_mfma_kernel<DQ, D, NW, NBUF>), dim3(blocks), dim3(64 * NW), 0, a.stream,
-                     (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens, a.C,
+                     (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens, a.cand_off, a.P, a.C,
                      a.L, a.w, a.S, spw, ctiles, sruns, nsl, (unsigned short*)a.seg_out, a.seg_cnt);
 }
 
@@ -1035,16 +1062,16 @@ static void launch_nw(const StaArgs& a, int nw, int spw, int ctiles, int sruns, 
     if (a.reread)
       hipLaunchKernelGGL((sta_mfma_dma_kernel<8, false>), dim3(blocks), dim3(512), 0, a.stream,
                          (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens,
-                         a.C, a.L, a.w, a.S, spw, ctiles, sruns, nsl, (unsigned short*)a.seg_out, a.seg_cnt);
+                         a.cand_off, a.P, a.C, a.L, a.w, a.S, spw, ctiles, sruns, nsl, (unsigned short*)a.seg_out, a.seg_cnt);
     else
       hipLaunchKernelGGL((sta_mfma_dma_kernel<8, true>), dim3(blocks), dim3(512), 0, a.stream,
                          (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens,
-                         a.C, a.L, a.w, a.S, spw, ctiles, sruns, nsl, (unsigned short*)a.seg_out, a.seg_cnt);
+                         a.cand_off, a.P, a.C, a.L, a.w, a.S, spw, ctiles, sruns, nsl, (unsigned short*)a.seg_out, a.seg_cnt);
   } else if (nw == 8) {
     const unsigned blocks = (unsigned)((long long)a.U * ctiles * sruns);
     hipLaunchKernelGGL((sta_mfma_pipe_kernel<DQ, D, 8>), dim3(blocks), dim3(512), 0, a.stream,
                        (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens,
-                       a.C, a.L, a.w, a.S, spw, ctiles, sruns, nsl, (unsigned short*)a.seg_out, a.seg_cnt);
+                       a.cand_off, a.P, a.C, a.L, a.w, a.S, spw, ctiles, sruns, nsl, (unsigned short*)a.seg_out, a.seg_cnt);
   }
   else if (nw == 4) launch_one<DQ, D, 4, 1>(a, spw, ctiles, sruns, nsl);
   else if (nw == 2) launch_one<DQ, D, 2, 1>(a, spw, ctiles, sruns, nsl);

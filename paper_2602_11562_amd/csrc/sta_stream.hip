@@ -31,8 +31,9 @@ template <int DQ, int D, int CMAX, int HEADS>
 __global__ __launch_bounds__(256) void sta_stream_kernel(const unsigned short* __restrict__ q,
                                                          const unsigned short* __restrict__ k,
                                                          const unsigned short* __restrict__ v,
-                                                         const int32_t* __restrict__ lens, int C, int L, int w, int S,
-                                                         int spg, int groups, float neg_scale_log2e,
+                                                         const int32_t* __restrict__ lens,
+                                                         const int32_t* __restrict__ cand_off, int P, int C_all, int L,
+                                                         int w, int S, int spg, int groups, float neg_scale_log2e,
                                                          unsigned short* __restrict__ seg_out,
                                                          int32_t* __restrict__ seg_cnt) {
   constexpr int LQ = DQ / 8, LV = D / 8;           // lanes per K row / V row
@@ -51,6 +52,10 @@ __global__ __launch_bounds__(256) void sta_stream_kernel(const unsigned short* _
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int n = valid_len(lens, u, L);
   if (grp == 0) write_seg_cnt(seg_cnt, u, n, L, w, S, tid, 256);
+  const CandRange cr = cand_range(cand_off, u, C_all, P);
+  const int C = cr.count;               // this user's candidates
+  const size_t pb = (size_t)cr.first;   // and the index of their first pair
+  if (C == 0) return;                   // (the whole workgroup leaves, before any barrier)
   const int rq = lane / LQ, cq = lane % LQ;
   const int rv = lane / LV, cv = lane % LV;
 
@@ -58,7 +63,7 @@ __global__ __launch_bounds__(256) void sta_stream_kernel(const unsigned short* _
 #pragma unroll
   for (int c = 0; c < CMAX; ++c) {
     u32x4 raw = {0u, 0u, 0u, 0u};
-    if (c < C) raw = *reinterpret_cast<const u32x4*>(q + ((size_t)u * C + c) * DQ + cq * 8);
+    if (c < C) raw = *reinterpret_cast<const u32x4*>(q + (pb + c) * DQ + cq * 8);
     unpack8(raw, qf[c]);
   }
   const unsigned short* kU = k + (size_t)u * L * DQ;
@@ -166,7 +171,7 @@ __global__ __launch_bounds__(256) void sta_stream_kernel(const unsigned short* _
     for (int e = tid; e < C * D; e += 256) {
       const int c = e / D, col = e - c * D;
       const float s = ((red[0][c][col] + red[1][c][col]) + red[2][c][col]) + red[3][c][col];
-      seg_out[(((size_t)u * C + c) * S + i) * D + col] = f32_to_bf16_bits(s);
+      seg_out[((pb + c) * S + i) * D + col] = f32_to_bf16_bits(s);
     }
     __syncthreads();   // the reduction buffer is reused by the next segment
   };
@@ -201,7 +206,7 @@ __global__ __launch_bounds__(256) void sta_stream_kernel(const unsigned short* _
   for (int e = tid; e < (i_end - i_ne) * C * D; e += 256) {
     const int ii = i_ne + e / (C * D), r2 = e % (C * D);
     const int c = r2 / D, col = r2 - c * D;
-    seg_out[(((size_t)u * C + c) * S + ii) * D + col] = 0;
+    seg_out[((pb + c) * S + ii) * D + col] = 0;
   }
 }
 
@@ -218,8 +223,10 @@ template <int DQ, int D, int CMAX, int HEADS, bool SOFTMAX>
 __global__ __launch_bounds__(256) void sta_stream_short_kernel(const unsigned short* __restrict__ q,
                                                                const unsigned short* __restrict__ k,
                                                                const unsigned short* __restrict__ v,
-                                                               const int32_t* __restrict__ lens, int C, int L, int w,
-                                                               int S, int spg, int groups, float neg_scale_log2e,
+                                                               const int32_t* __restrict__ lens,
+                                                               const int32_t* __restrict__ cand_off, int P, int C_all,
+                                                               int L, int w, int S, int spg, int groups,
+                                                               float neg_scale_log2e,
                                                                unsigned short* __restrict__ seg_out,
                                                                int32_t* __restrict__ seg_cnt, int kv_alias) {
   constexpr int LQ = DQ / 8, LV = D / 8;
@@ -239,6 +246,10 @@ __global__ __launch_bounds__(256) void sta_stream_short_kernel(const unsigned sh
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = __builtin_amdgcn_readfirstlane(valid_len(lens, u, L));
   if (grp == 0) write_seg_cnt(seg_cnt, u, n, L, w, S, tid, 256);
+  const CandRange cr = cand_range(cand_off, u, C_all, P);
+  const int C = __builtin_amdgcn_readfirstlane(cr.count);   // this user's candidates
+  const size_t pb = (size_t)cr.first;                        // and the index of their first pair
+  if (C == 0) return;
   const int rq = lane / LQ, cq = lane % LQ;
   const int rv = lane / LV, cv = lane % LV;
 
@@ -246,7 +257,7 @@ __global__ __launch_bounds__(256) void sta_stream_short_kernel(const unsigned sh
 #pragma unroll
   for (int c = 0; c < CMAX; ++c) {
     u32x4 raw = {0u, 0u, 0u, 0u};
-    if (c < C) raw = *reinterpret_cast<const u32x4*>(q + ((size_t)u * C + c) * DQ + cq * 8);
+    if (c < C) raw = *reinterpret_cast<const u32x4*>(q + (pb + c) * DQ + cq * 8);
     unpack8(raw, qf[c]);
   }
   const unsigned short* kU = k + (size_t)u * L * DQ;
@@ -400,7 +411,7 @@ __global__ __launch_bounds__(256) void sta_stream_short_kernel(const unsigned sh
             z[1] *= inv_l[c];
           }
           const unsigned o = (unsigned)f32_to_bf16_bits(z[0]) | ((unsigned)f32_to_bf16_bits(z[1]) << 16);
-          *reinterpret_cast<unsigned*>(seg_out + (((size_t)u * C + c) * S + i) * D + cv * 8 + 2 * (lane >> 4)) = o;
+          *reinterpret_cast<unsigned*>(seg_out + ((pb + c) * S + i) * D + cv * 8 + 2 * (lane >> 4)) = o;
         }
       }
       return;
@@ -419,7 +430,7 @@ __global__ __launch_bounds__(256) void sta_stream_short_kernel(const unsigned sh
           for (int e = 0; e < 4; ++e)
             o[e] = (unsigned)f32_to_bf16_bits(acc[c][2 * e] * mul) |
                    ((unsigned)f32_to_bf16_bits(acc[c][2 * e + 1] * mul) << 16);
-          *reinterpret_cast<u32x4*>(seg_out + (((size_t)u * C + c) * S + i) * D + cv * 8) = o;
+          *reinterpret_cast<u32x4*>(seg_out + ((pb + c) * S + i) * D + cv * 8) = o;
         }
       }
     }
@@ -456,7 +467,7 @@ __global__ __launch_bounds__(256) void sta_stream_short_kernel(const unsigned sh
   for (int e = tid; e < (i_end - i_ne) * C * D; e += 256) {
     const int ii = i_ne + e / (C * D), r2 = e % (C * D);
     const int c = r2 / D, col = r2 - c * D;
-    seg_out[(((size_t)u * C + c) * S + ii) * D + col] = 0;
+    seg_out[((pb + c) * S + ii) * D + col] = 0;
   }
 }
 
@@ -500,17 +511,17 @@ static void launch_c(const StaArgs& a, float nsl) {
     if (short_seg && a.softmax)                                                                                      \
       hipLaunchKernelGGL((sta_stream_short_kernel<DQ, D, CM, HEADS, true>), dim3(blocks), dim3(256), 0, a.stream,  \
                          (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v,       \
-                         a.lens, a.C, a.L, a.w, a.S, spg, groups, nsl, (unsigned short*)a.seg_out, a.seg_cnt,     \
+                         a.lens, a.cand_off, a.P, a.C, a.L, a.w, a.S, spg, groups, nsl, (unsigned short*)a.seg_out, a.seg_cnt,     \
                          (a.k == a.v && DQ == D) ? 1 : 0);                                                           \
     else if (short_seg)                                                                                              \
       hipLaunchKernelGGL((sta_stream_short_kernel<DQ, D, CM, HEADS, false>), dim3(blocks), dim3(256), 0, a.stream, \
                          (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v,       \
-                         a.lens, a.C, a.L, a.w, a.S, spg, groups, nsl, (unsigned short*)a.seg_out, a.seg_cnt,     \
+                         a.lens, a.cand_off, a.P, a.C, a.L, a.w, a.S, spg, groups, nsl, (unsigned short*)a.seg_out, a.seg_cnt,     \
                          (a.k == a.v && DQ == D) ? 1 : 0);                                                           \
     else                                                                                                             \
       hipLaunchKernelGGL((sta_stream_kernel<DQ, D, CM, HEADS>), dim3(blocks), dim3(256), 0, a.stream,                     \
                          (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v,       \
-                         a.lens, a.C, a.L, a.w, a.S, spg, groups, nsl, (unsigned short*)a.seg_out, a.seg_cnt);     \
+                         a.lens, a.cand_off, a.P, a.C, a.L, a.w, a.S, spg, groups, nsl, (unsigned short*)a.seg_out, a.seg_cnt);     \
   } while (0)
   if (a.C <= 1) LASER_STREAM_LAUNCH(1);
   else if (a.C <= 2) LASER_STREAM_LAUNCH(2);

@@ -213,3 +213,20 @@ def test_sta_softmax_argument_validation(lib):
     assert f(variant=9) == UNSUP
     assert f(dq=128, d=128, C=64, variant=2) == UNSUP      # the matrix-core kernel carries sigmoid gates only
     assert f(dq=64, d=64, C=2, w=200, variant=3) == UNSUP  # long segments: the streaming kernel's long form does not either
+
+
+def test_ragged_argument_validation(lib):
+    NULL, SHAPE, DTYPE, ALIGN = 1, 2, 3, 6
+    sta = lambda q=A, off=A, U=3, C=8, P=10, L=64, dq=16, d=16, w=8, gamma=1.0, dt=1, out=A: \
+        lib.laser_sta_forward_ragged(q, A, A, None, off, U, C, P, L, dq, d, w, gamma, dt, out, None, None)
+    assert sta(q=None) == NULL and sta(off=None) == NULL and sta(out=None) == NULL and sta(dt=9) == DTYPE
+    for kw in ({"P": 0}, {"P": -3}, {"P": 25}, {"U": 0}, {"C": 0}, {"w": 0}, {"gamma": 0.0}, {"d": 12}):   # 25 > U * C_max
+        assert sta(**kw) == SHAPE, kw
+    assert sta(off=A + 2) == ALIGN and sta(q=A + 8) == ALIGN
+    gsta = lambda seg=A, off=A, U=3, C=8, P=10, M=1, z=A: \
+        lib.laser_gsta_forward_ragged(seg, A, A, A, A, None, off, U, C, P, 64, 16, 8, M, 1, z, None)
+    assert gsta(seg=None) == NULL and gsta(off=None) == NULL and gsta(z=None) == NULL
+    assert gsta(P=0) == SHAPE and gsta(P=99) == SHAPE and gsta(M=0) == SHAPE and gsta(off=A + 1) == ALIGN
+    whole = lambda off=A, P=10, t0=A, z=A: lib.laser_forward_ragged(A, A, A, t0, A, A, A, None, off, 3, 8, P, 64, 16, 16,
+                                                                     8, 1.0, 1, 1, A, None, z, None)
+    assert whole(off=None) == NULL and whole(t0=None) == NULL and whole(z=None) == NULL and whole(P=25) == SHAPE
