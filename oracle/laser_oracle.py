@@ -399,3 +399,33 @@ def laser_forward_ragged(q, k, v, t0, wq, wk, wv, lens, cand_off, w: int, gamma:
             Hp[p] = sta_pair(q[p], k[u], v[u], int(lens[u]), w, gamma)
             z[p] = gsta_pair(Hp[p], t0[p], wq, wk, wv, cnt[u] > 0)
     return Hp, cnt, z
+
+
+def sta_backward(q, k, v, lens, w: int, gamma: float, dHp):
+    """Gradients of a scalar loss through STA (Sec. 3.4.2), given dHp = d loss / d H' [U,C,S,d]: returns
+    (dq [U,C,d_q], dk [U,L,d_q], dv [U,L,d]). Written out from the forward definition
+        H'[c,i,:] = sum_{j in segment i, j < len} g_cj v_j,   g_cj = sigmoid(s_cj),   s_cj = q_c . k_j / gamma,
+    by the chain rule, item by item:
+        d loss / d v_j  = sum_c g_cj dHp[c, i(j), :]
+        d loss / d s_cj = (dHp[c, i(j), :] . v_j) g_cj (1 - g_cj)
+        d loss / d q_c  = sum_j (d loss / d s_cj) k_j / gamma,    d loss / d k_j = sum_c (d loss / d s_cj) q_c / gamma.
+    Items at or past the valid length take no part in the forward pass, so their gradients are zero (the paper
+    trains the module, Sec. 3.5.1 / 4.1.2, but prints no backward formulas: these are the derivatives of its
+    forward equations)."""
+    q, k, v, dHp = (np.asarray(x, dtype=np.float64) for x in (q, k, v, dHp))
+    U, C, dq_dim = q.shape
+    L, d = v.shape[1], v.shape[2]
+    lens = np.full(U, L, dtype=np.int64) if lens is None else np.asarray(lens, dtype=np.int64)
+    dq, dk, dv = np.zeros_like(q), np.zeros_like(k), np.zeros_like(v)
+    for u in range(U):
+        n = min(max(int(lens[u]), 0), L)
+        for j in range(n):
+            i = j // w
+            for c in range(C):
+                g = float(sigmoid(np.array(q[u, c] @ k[u, j] / gamma)))
+                up = dHp[u, c, i]
+                dv[u, j] += g * up
+                ds = (up @ v[u, j]) * g * (1.0 - g)
+                dq[u, c] += ds * k[u, j] / gamma
+                dk[u, j] += ds * q[u, c] / gamma
+    return dq, dk, dv

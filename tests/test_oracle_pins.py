@@ -684,3 +684,62 @@ def test_ragged_batch_is_the_dense_batch_repacked():
     for bad in ([1, 3, 3, 4], [0, 3, 2, 4], [0, 3, 3, 5]):
         with pytest.raises(ValueError):
             oracle.laser_forward_ragged(qp, k, v, tp, wq, wk, wv, lens, bad, w, gamma)
+
+
+# ------------------------------------------------------------------ STA backward
+def _torch_sta(q, k, v, lens, w, gamma):
+    """The forward pass in torch fp64 ops, written independently (mask + index_add), for autograd to differentiate."""
+    U, C, _ = q.shape
+    L, d = v.shape[1], v.shape[2]
+    S = -(-L // w)
+    seg_of = torch.arange(L) // w
+    out = []
+    for u in range(U):
+        g = torch.sigmoid(q[u] @ k[u].T / gamma) * (torch.arange(L) < int(lens[u])).to(q.dtype)   # [C, L]
+        contrib = g[:, :, None] * v[u][None, :, :]                                                  # [C, L, d]
+        out.append(torch.zeros(C, S, d, dtype=q.dtype).index_add(1, seg_of, contrib))
+    return torch.stack(out)
+
+
+def test_sta_backward_matches_autograd_and_finite_differences():
+    rng = np.random.default_rng(4321)
+    U, C, L, w, dq, d, gamma = 2, 3, 11, 4, 5, 6, 1.3
+    lens = [11, 6]
+    q, k, v = rng.normal(size=(U, C, dq)), rng.normal(size=(U, L, dq)), rng.normal(size=(U, L, d))
+    up = rng.normal(size=(U, C, 3, d))
+    got = oracle.sta_backward(q, k, v, lens, w, gamma, up)
+    tq, tk, tv = (torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (q, k, v))
+    # the torch forward agrees with the checker's forward, and its autograd gradients with the checker's backward
+    fwd = _torch_sta(tq, tk, tv, lens, w, gamma)
+    assert np.allclose(fwd.detach().numpy(), oracle.sta_forward(q, k, v, lens, w, gamma)[0], rtol=1e-12, atol=1e-13)
+    (fwd * torch.tensor(up)).sum().backward()
+    for mine, ref in zip(got, (tq.grad, tk.grad, tv.grad)):
+        assert np.allclose(mine, ref.numpy(), rtol=1e-10, atol=1e-12)
+    # items past the valid length get no gradient
+    assert not got[1][1, 6:].any() and not got[2][1, 6:].any()
+    # central differences of loss = sum(H' * up) in a few random directions
+    loss = lambda q_, k_, v_: float((oracle.sta_forward(q_, k_, v_, lens, w, gamma)[0] * up).sum())
+    for _ in range(3):
+        dq_, dk_, dv_ = rng.normal(size=q.shape), rng.normal(size=k.shape), rng.normal(size=v.shape)
+        h = 1e-6
+        num = (loss(q + h * dq_, k + h * dk_, v + h * dv_) - loss(q - h * dq_, k - h * dk_, v - h * dv_)) / (2 * h)
+        ana = (got[0] * dq_).sum() + (got[1] * dk_).sum() + (got[2] * dv_).sum()
+        assert abs(num - ana) <= 1e-6 * max(1.0, abs(ana))
+
+
+def test_sta_backward_closed_forms():
+    rng = np.random.default_rng(4322)
+    U, C, L, w, dq, d, gamma = 1, 2, 8, 4, 3, 4, 2.0
+    k, v, up = rng.normal(size=(U, L, dq)), rng.normal(size=(U, L, d)), rng.normal(size=(U, C, 2, d))
+    # zero query: every gate is 1/2 and g (1 - g) = 1/4
+    dq_, dk_, dv_ = oracle.sta_backward(np.zeros((U, C, dq)), k, v, None, w, gamma, up)
+    assert not dk_.any()                                                   # dk_j = sum_c ds q_c = 0
+    for j in range(L):
+        assert np.allclose(dv_[0, j], 0.5 * up[0, :, j // w].sum(axis=0))
+    ref = sum(0.25 * (up[0, 0, j // w] @ v[0, j]) * k[0, j] / gamma for j in range(L))
+    assert np.allclose(dq_[0, 0], ref)
+    # linear in the upstream gradient
+    q = rng.normal(size=(U, C, dq))
+    a = oracle.sta_backward(q, k, v, None, w, gamma, up)
+    b = oracle.sta_backward(q, k, v, None, w, gamma, -2.0 * up)
+    assert all(np.allclose(y, -2.0 * x) for x, y in zip(a, b))
