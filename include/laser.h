@@ -29,6 +29,7 @@
 #ifndef LASER_H_
 #define LASER_H_
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -300,6 +301,29 @@ laser_status laser_sta_folded_forward(const void* t, const void* h, const void* 
                                       const int32_t* lens, int U, int C, int L, int d_in, int d, int w, float gamma,
                                       int heads, laser_dtype dt, void* qf_work, void* g_work, void* seg_out,
                                       int32_t* seg_cnt, void* stream);
+
+/*
+ * Backward pass of STA (the derivatives of the forward equations of paper Sec. 3.4.2; the paper trains the module,
+ * Sec. 4.1.2, and prints no backward formulas). Given dseg = d loss / d H' [U,C,S,d] (dt), with
+ *   g_cj = sigmoid(q_c . k_j / gamma)   and   ds_cj = (dseg[c, i(j), :] . v_j) g_cj (1 - g_cj),   i(j) = j / w:
+ *   dv_out[u,j,:] = sum_c g_cj dseg[u,c,i(j),:]           [U,L,d]   fp32
+ *   dk_out[u,j,:] = sum_c ds_cj q[u,c,:] / gamma          [U,L,d_q] fp32
+ *   dq_out[u,c,:] = sum_j ds_cj k[u,j,:] / gamma          [U,C,d_q] fp32
+ * over the valid items j < lens[u]; items at or past the valid length get zeros (all outputs are fully overwritten).
+ * q, k, v, lens, sizes and gamma as for laser_sta_forward (one head, sigmoid gates). Arithmetic in fp32 from the stored
+ * inputs; sums in a fixed order (results are reproducible run to run).
+ * Built for training batches, which hold one or a few targets per sample: C <= 8 and d_q, d <= 256; other shapes
+ * return LASER_ERR_UNSUPPORTED. work is caller-owned scratch of at least laser_sta_backward_work_bytes(U, C, L, d_q, w)
+ * bytes (partial dq sums; contents unspecified on return); the library allocates nothing.
+ * All pointers are device pointers, 16-byte aligned (lens 4-byte); work is enqueued on `stream`.
+ * Errors: LASER_ERR_NULL, LASER_ERR_SHAPE (sizes, gamma, work_bytes too small), LASER_ERR_DTYPE, LASER_ERR_ALIGN,
+ * LASER_ERR_UNSUPPORTED, LASER_ERR_LAUNCH. Nothing is launched on an error.
+ */
+size_t laser_sta_backward_work_bytes(int U, int C, int L, int d_q, int w);   /* host only; 0 for invalid sizes */
+laser_status laser_sta_backward(const void* q, const void* k, const void* v, const int32_t* lens, const void* dseg,
+                                int U, int C, int L, int d_q, int d, int w, float gamma, laser_dtype dt,
+                                float* dq_out, float* dk_out, float* dv_out, void* work, size_t work_bytes,
+                                void* stream);
 
 /* Name of the STA / GSTA kernel AUTO would pick for a shape (static strings; host only, no GPU needed). */
 const char* laser_sta_kernel_name(int C, int d_q, int d, int w, laser_dtype dt);

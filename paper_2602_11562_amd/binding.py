@@ -27,7 +27,8 @@ EXPORTS = [
     "laser_gsta_kernel_name", "laser_segment_ffn_forward", "laser_segment_ffn_forward_variant",
     "laser_gsta_kernel_name_layers", "laser_project_q_forward", "laser_project_q_forward_variant",
     "laser_project_kv_forward", "laser_project_kv_forward_variant", "laser_fold_query_weights",
-    "laser_project_heads_forward", "laser_sta_folded_forward", "laser_status_string", "laser_version",
+    "laser_project_heads_forward", "laser_sta_folded_forward", "laser_sta_backward", "laser_sta_backward_work_bytes",
+    "laser_status_string", "laser_version",
 ]
 
 
@@ -92,6 +93,11 @@ def load_library() -> ctypes.CDLL:
                                          i32, i32, vp, ip, vp, vp]
     for name in ("laser_sta_forward_ragged", "laser_gsta_forward_ragged", "laser_forward_ragged"):
         getattr(lib, name).restype = i32
+    lib.laser_sta_backward_work_bytes.argtypes = [i32, i32, i32, i32, i32]
+    lib.laser_sta_backward_work_bytes.restype = ctypes.c_size_t
+    lib.laser_sta_backward.argtypes = [vp, vp, vp, ip, vp, i32, i32, i32, i32, i32, i32, f32, i32, vp, vp, vp, vp,
+                                       ctypes.c_size_t, vp]
+    lib.laser_sta_backward.restype = i32
     lib.laser_sta_kernel_name.argtypes = [i32, i32, i32, i32, i32]
     lib.laser_sta_kernel_name.restype = ctypes.c_char_p
     lib.laser_gsta_kernel_name.argtypes = [i32, i32, i32, i32]
@@ -323,6 +329,34 @@ def laser_forward_ragged(q, k, v, t0, wq, wk, wv, lens, cand_off, c_max: int, w:
                                         _stream(stream))
     _check(code, "laser_forward_ragged")
     return seg_out, seg_cnt, z_out
+
+
+def laser_sta_backward(q, k, v, lens, dseg, w: int, gamma: float, dq_out=None, dk_out=None, dv_out=None, work=None,
+                       stream=None):
+    """Gradients of STA: dseg = dL/dH' [U,C,S,d] (dtype of q) -> (dq [U,C,d_q], dk [U,L,d_q], dv [U,L,d]) in fp32."""
+    torch = _torch()
+    U, C, d_q = q.shape
+    L, d = v.shape[1], v.shape[2]
+    S = -(-L // w)
+    if tuple(k.shape) != (U, L, d_q) or tuple(v.shape) != (U, L, d) or tuple(dseg.shape) != (U, C, S, d):
+        raise ValueError("q, k, v, dseg shapes disagree")
+    if any(x.dtype != q.dtype for x in (k, v, dseg)):
+        raise TypeError("q, k, v and dseg must share a dtype")
+    f32 = dict(dtype=torch.float32, device=q.device)
+    dq_out = torch.empty((U, C, d_q), **f32) if dq_out is None else dq_out
+    dk_out = torch.empty((U, L, d_q), **f32) if dk_out is None else dk_out
+    dv_out = torch.empty((U, L, d), **f32) if dv_out is None else dv_out
+    lib = load_library()
+    need = lib.laser_sta_backward_work_bytes(U, C, L, d_q, int(w))
+    if work is None:
+        work = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    code = lib.laser_sta_backward(_ptr(q, "q"), _ptr(k, "k"), _ptr(v, "v"), _ptr(lens, "lens", torch.int32),
+                                  _ptr(dseg, "dseg"), U, C, L, d_q, d, int(w), float(gamma), _dt(q),
+                                  _ptr(dq_out, "dq_out", torch.float32), _ptr(dk_out, "dk_out", torch.float32),
+                                  _ptr(dv_out, "dv_out", torch.float32), _ptr(work, "work"),
+                                  work.numel() * work.element_size(), _stream(stream))
+    _check(code, "laser_sta_backward")
+    return dq_out, dk_out, dv_out
 
 
 def laser_fold_query_weights(w_q, w_k, heads: int = 1, a_out=None, stream=None):

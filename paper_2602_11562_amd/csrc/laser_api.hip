@@ -425,6 +425,26 @@ laser_status laser_sta_folded_forward(const void* t, const void* h, const void* 
   return run_project_heads(pa, LASER_PROJECT_AUTO);
 }
 
+size_t laser_sta_backward_work_bytes(int U, int C, int L, int d_q, int w) {
+  if (U <= 0 || C <= 0 || L <= 0 || d_q <= 0 || w <= 0) return 0;
+  return sta_backward_work_bytes(U, C, L, d_q, w);
+}
+
+laser_status laser_sta_backward(const void* q, const void* k, const void* v, const int32_t* lens, const void* dseg, int U,
+                                int C, int L, int d_q, int d, int w, float gamma, laser_dtype dt, float* dq_out,
+                                float* dk_out, float* dv_out, void* work, size_t work_bytes, void* stream) {
+  if (!dseg || !dq_out || !dk_out || !dv_out || !work) return LASER_ERR_NULL;
+  StaArgs fa;   // the forward pass's checks of the shared arguments (dseg stands in for seg_out: same shape and type)
+  laser_status s = validate_sta(q, k, v, lens, U, C, L, d_q, d, w, gamma, dt, const_cast<void*>(dseg), nullptr, stream,
+                                &fa);
+  if (s != LASER_OK) return s;
+  if (!aligned16(dq_out) || !aligned16(dk_out) || !aligned16(dv_out) || !aligned16(work)) return LASER_ERR_ALIGN;
+  if (work_bytes < sta_backward_work_bytes(U, C, L, d_q, w)) return LASER_ERR_SHAPE;
+  const StaBwdArgs a{q, k, v, dseg, lens, U, C, L, d_q, d, w, fa.S, gamma, dt, dq_out, dk_out, dv_out,
+                     static_cast<float*>(work), static_cast<hipStream_t>(stream)};
+  return sta_backward_launch(a);
+}
+
 const char* laser_sta_kernel_name(int C, int d_q, int d, int w, laser_dtype dt) {
   StaArgs a{};
   a.U = 1; a.C = C; a.L = w > 0 ? w : 1; a.d_q = d_q; a.d = d; a.w = w; a.S = 1; a.gamma = 1.0f; a.dt = dt;

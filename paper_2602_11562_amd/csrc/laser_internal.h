@@ -112,6 +112,25 @@ laser_status project_heads_mfma_launch(const ProjHeadsArgs& a);
 laser_status fold_weights_launch(const void* wq, const void* wk, int d_in, int d_q, int heads, laser_dtype dt,
                                  void* a_out, hipStream_t stream);
 
+struct StaBwdArgs {        // gradients of STA: dq [U,C,d_q], dk [U,L,d_q], dv [U,L,d] (fp32) from dhp = dH' [U,C,S,d]
+  const void* q;
+  const void* k;
+  const void* v;
+  const void* dhp;
+  const int32_t* lens;
+  int U, C, L, d_q, d, w, S;
+  float gamma;
+  laser_dtype dt;
+  float* dq;
+  float* dk;
+  float* dv;
+  float* work;             // [U, groups, C, d_q] partial dq sums, sta_backward_work_bytes() bytes
+  hipStream_t stream;
+};
+bool sta_backward_supports(const StaBwdArgs& a);
+size_t sta_backward_work_bytes(int U, int C, int L, int d_q, int w);
+laser_status sta_backward_launch(const StaBwdArgs& a);
+
 // Each launcher returns LASER_ERR_UNSUPPORTED (launching nothing) when the shape is outside its range.
 bool sta_generic_supports(const StaArgs& a);
 laser_status sta_generic_launch(const StaArgs& a);

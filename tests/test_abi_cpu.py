@@ -230,3 +230,20 @@ def test_ragged_argument_validation(lib):
     whole = lambda off=A, P=10, t0=A, z=A: lib.laser_forward_ragged(A, A, A, t0, A, A, A, None, off, 3, 8, P, 64, 16, 16,
                                                                      8, 1.0, 1, 1, A, None, z, None)
     assert whole(off=None) == NULL and whole(t0=None) == NULL and whole(z=None) == NULL and whole(P=25) == SHAPE
+
+
+def test_sta_backward_argument_validation(lib):
+    NULL, SHAPE, DTYPE, UNSUP, ALIGN = 1, 2, 3, 4, 6
+    lib.laser_sta_backward_work_bytes.restype = ctypes.c_size_t
+    need = lib.laser_sta_backward_work_bytes(3, 2, 64, 16, 8)
+    assert need >= 3 * 2 * 16 * 4 and lib.laser_sta_backward_work_bytes(0, 2, 64, 16, 8) == 0
+    f = lambda q=A, dseg=A, U=3, C=2, L=64, dq=16, d=16, w=8, gamma=1.0, dt=1, dqo=A, dko=A, dvo=A, work=A, wb=1 << 20: \
+        lib.laser_sta_backward(q, A, A, None, dseg, U, C, L, dq, d, w, ctypes.c_float(gamma), dt, dqo, dko, dvo, work,
+                               ctypes.c_size_t(wb), None)
+    for kw in ({"q": None}, {"dseg": None}, {"dqo": None}, {"dko": None}, {"dvo": None}, {"work": None}):
+        assert f(**kw) == NULL, kw
+    assert f(dt=6) == DTYPE
+    for kw in ({"U": 0}, {"C": 0}, {"w": 0}, {"gamma": 0.0}, {"d": 12}, {"wb": 8}):
+        assert f(**kw) == SHAPE, kw
+    assert f(dko=A + 4) == ALIGN and f(work=A + 8) == ALIGN
+    assert f(C=9) == UNSUP and f(dq=512, d=512) == UNSUP

@@ -1,0 +1,100 @@
+"""GPU parity of the STA backward pass against the fp64 checker (itself pinned to autograd and central differences),
+element by element. The checker reads the stored inputs; the kernel computes in fp32 from the same values and writes
+fp32 gradients, so the tolerance is the fp32 one (1e-5) for both storage types. Metric: dq and dv per output vector, as
+everywhere. dk per user: with one candidate dk_j is the query times the scalar ds_j = (dH' . v_j) g (1 - g), a dot
+product of d signed terms that cancels to anything between 0 and its terms' size, so an fp32 sum has an absolute, not
+a relative, error bound (about d 2^-24 times the terms); a row whose dot product happens to cancel would fail a
+per-row relative test at any precision short of exact. Rows that must be zero must still be exactly zero."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+
+from parity_util import to_device, to_host_f64, vec_rel_err
+
+pytestmark = pytest.mark.gpu
+
+laser = pytest.importorskip("paper_2602_11562_amd")
+
+BWD_TOL = 1e-5
+
+CASES = {
+    # dtype, C, L, d_q, d, w, lens
+    "paper_setting": ("bf16", 1, 1000, 32, 128, 10, [1000, 995, 404, 7, 0, 1000]),
+    "eight_candidates": ("bf16", 8, 300, 64, 64, 64, [300, 65, 64]),
+    "wide_rows": ("bf16", 2, 520, 256, 256, 128, [520, 129]),
+    "one_user_many_runs": ("bf16", 1, 4096, 64, 64, 64, [3000]),
+    "odd_widths_f32": ("f32", 3, 130, 24, 48, 16, [130, 50]),
+    "f32_paper_setting": ("f32", 1, 200, 32, 128, 10, [200, 33, 0]),
+}
+
+
+def _store(x, dtype):
+    x = np.asarray(x, dtype=np.float32)
+    if dtype == "bf16":
+        bits = workloads.f32_to_bf16_bits(x)
+        return bits, workloads.bf16_bits_to_f32(bits).astype(np.float64)
+    return x, x.astype(np.float64)
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_sta_backward_matches_checker(name):
+    import torch
+    dtype, C, L, dq, d, w, lens = CASES[name]
+    U, S = len(lens), -(-L // w)
+    rng = np.random.default_rng(2100 + sum(map(ord, name)))
+    (qs, qv), (ks, kv), (vs, vv), (gs, gv) = (_store(rng.normal(size=s), dtype)
+                                              for s in ((U, C, dq), (U, L, dq), (U, L, d), (U, C, S, d)))
+    lens = np.array(lens, dtype=np.int32)
+    gamma = math.sqrt(dq)
+    print(f"case {name}", flush=True)
+    ref = oracle.sta_backward(qv, kv, vv, lens, w, gamma, gv)
+    got = laser.laser_sta_backward(to_device(qs), to_device(ks), to_device(vs), to_device(lens), to_device(gs), w, gamma)
+    torch.cuda.synchronize()
+    for nm, a, b in zip(("dq", "dk", "dv"), got, ref):
+        a = to_host_f64(a)
+        if nm == "dk":
+            assert not a[b == 0].any()      # padding rows: exactly zero
+            a, b = a.reshape(U, -1), b.reshape(U, -1)
+        err = vec_rel_err(a, b)
+        print(f"  {nm}: max relative error {err:.3e}", flush=True)
+        assert err <= BWD_TOL, nm
+    # reproducible: a second call gives the same bits
+    again = laser.laser_sta_backward(to_device(qs), to_device(ks), to_device(vs), to_device(lens), to_device(gs), w, gamma)
+    torch.cuda.synchronize()
+    assert all(torch.equal(x, y) for x, y in zip(got, again))
+
+
+def test_sta_backward_is_the_gradient_of_the_library_forward():
+    """d/d eps of sum(H'(q + eps dq, ...) * dseg) through the library's own fp32 forward pass agrees with the inner
+    product of the library's gradients with the direction (central difference; fp32 forward, so to about 1e-3)."""
+    import torch
+    rng = np.random.default_rng(9)
+    U, C, L, dq, d, w = 3, 2, 96, 16, 32, 8
+    f = lambda *s: torch.from_numpy(rng.normal(size=s).astype(np.float32)).cuda()
+    q, k, v, up = f(U, C, dq), f(U, L, dq), f(U, L, d), f(U, C, L // w, d)
+    lens = to_device(np.array([96, 50, 9], dtype=np.int32))
+    gamma = 2.0
+    gq, gk, gv = laser.laser_sta_backward(q, k, v, lens, up, w, gamma)
+    dq_, dk_, dv_ = f(U, C, dq), f(U, L, dq), f(U, L, d)
+    h = 1e-2
+    loss = lambda s: float((laser.laser_sta_forward(q + s * dq_, k + s * dk_, v + s * dv_, lens, w, gamma,
+                                                    want_cnt=False)[0].double() * up.double()).sum())
+    num = (loss(h) - loss(-h)) / (2 * h)
+    ana = float((gq.double() * dq_).sum() + (gk.double() * dk_).sum() + (gv.double() * dv_).sum())
+    assert abs(num - ana) <= 2e-3 * max(1.0, abs(ana))
+
+
+def test_sta_backward_refuses_what_it_does_not_take():
+    import torch
+    z = lambda *s: torch.zeros(*s, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(laser.LaserError) as e:
+        laser.laser_sta_backward(z(1, 9, 32), z(1, 64, 32), z(1, 64, 32), None, z(1, 9, 8, 32), 8, 1.0)
+    assert e.value.code == 4      # more than eight candidates per user
+    with pytest.raises(laser.LaserError) as e:
+        laser.laser_sta_backward(z(1, 1, 32), z(1, 64, 32), z(1, 64, 32), None, z(1, 1, 8, 32), 8, 1.0,
+                                 work=torch.zeros(16, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == 2      # scratch too small
