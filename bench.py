@@ -127,6 +127,14 @@ def paper_setting_chain(laser, torch, event_time):
                                                           heads=heads))
     softmax_ms = event_time(lambda i: laser.laser_sta_forward(Q, K, V, lens, w, gamma, seg_out=seg, want_cnt=False,
                                                               heads=heads, softmax=True))
+    dseg = (rnd(U, C, S, d)).bfloat16()
+    gq = torch.empty(U, C, dq, device="cuda")
+    gk = torch.empty(U, L, dq, device="cuda")
+    gv = torch.empty(U, L, d, device="cuda")
+    work = torch.empty(max(16, laser.load_library().laser_sta_backward_work_bytes(U, C, L, dq, w)), dtype=torch.uint8,
+                       device="cuda")
+    bwd_ms = event_time(lambda i: laser.laser_sta_backward(Q, K, V, lens, dseg, w, gamma, dq_out=gq, dk_out=gk,
+                                                           dv_out=gv, work=work))
     direct_ms, folded_ms = event_time(direct), event_time(folded)
     same = float((seg.float() - 0).abs().max())   # keeps the last result alive until here
     nvalid = int(lens.sum())
@@ -137,7 +145,12 @@ def paper_setting_chain(laser, torch, event_time):
             "algorithmic_bytes": alg_b, "folded_gbps": alg_b / (folded_ms * 1e-3) / 1e9,
             "folded_frac_of_hbm_peak": alg_b / (folded_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
             "direct_frac_of_hbm_peak": alg_b / (direct_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-            "pairs_per_s_folded": U * C / (folded_ms * 1e-3), "max_abs_out": same}
+            "pairs_per_s_folded": U * C / (folded_ms * 1e-3), "max_abs_out": same,
+            # backward of STA: valid K and V rows and dH' read once (bf16), dk and dv written once (fp32, every row)
+            "sta_backward_ms": bwd_ms,
+            "sta_backward_algorithmic_bytes": nvalid * (dq + d) * 2 + U * C * S * d * 2 + U * L * (dq + d) * 4,
+            "sta_backward_frac_of_hbm_peak": (nvalid * (dq + d) * 2 + U * C * S * d * 2 + U * L * (dq + d) * 4)
+            / (bwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
 
 def main() -> int:

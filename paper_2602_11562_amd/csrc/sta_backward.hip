@@ -5,12 +5,14 @@
 //   ds_cj = (dH'[c,i(j),:] . v_j) g_cj (1 - g_cj)           dq_c = sum_j ds_cj k_j / gamma
 // Like the forward pass with few candidates this is HBM streaming work (K and V read once, dk and dv written once),
 // so the layout is the streaming kernel's: a workgroup owns a user's run of consecutive segments and its four waves
-// take alternating items. A wave holds one item at a time, lane l the elements l, l + 64, ... of its key and value
+// take alternating segments. A wave holds one item at a time, lane l the elements l, l + 64, ... of its key and value
 // rows; the two dot products per (item, candidate) are wave-wide sums, after which every lane knows the gate and ds
 // and updates its own elements of dv_j, dk_j (stored once per item, fp32) and of dq_c (kept in registers over the
-// run). The upstream gradients of the current segment and the queries sit in LDS as fp32. dq is summed over a
-// workgroup's waves in LDS and over a user's workgroups by a second small kernel, both in a fixed order
-// (deterministic). Items at or past the valid length get zero gradients.
+// run). The queries and the upstream gradient of the current segment sit in registers in the same lane layout. dq is
+// summed over a workgroup's waves in LDS and over a user's workgroups by a second small kernel, both in a fixed
+// order (deterministic). Items at or past the valid length get zero gradients.
+#include <cstdlib>
+
 #include "laser_internal.h"
 
 namespace laser {
@@ -18,24 +20,28 @@ namespace laser {
 constexpr int SB_CMAX = 8;    // candidates per user
 constexpr int SB_TMAX = 4;    // 64-element slices per row: d_q, d <= 256
 
-template <typename T>
+// Sum over the 64 lanes, the same value in every lane: inside each row of 16 lanes with the lane-permute adds, then the
+// four row sums are read into scalar registers and added (six generic shuffles would be six LDS round trips in the
+// middle of every item's dependency chain).
+__device__ __forceinline__ float wave_sum_rows(float x) {
+  x = row_sum<16>(x);
+  const int b = __float_as_int(x);
+  return ((__int_as_float(__builtin_amdgcn_readlane(b, 0)) + __int_as_float(__builtin_amdgcn_readlane(b, 16))) +
+          __int_as_float(__builtin_amdgcn_readlane(b, 32))) + __int_as_float(__builtin_amdgcn_readlane(b, 48));
+}
+
+template <typename T, int TQ, int TV, int CMAX>   // TQ, TV: 64-element slices of a key / value row; CMAX >= C
 __global__ __launch_bounds__(256) void sta_bwd_kernel(const T* __restrict__ q, const T* __restrict__ k,
                                                       const T* __restrict__ v, const T* __restrict__ dhp,
                                                       const int32_t* __restrict__ lens, int C, int L, int dq, int d, int w,
-                                                      int S, int spg, int groups, float inv_gamma,
+                                                      int S, int spg, int groups, float neg_scale_log2e, float inv_gamma,
                                                       float* __restrict__ dk, float* __restrict__ dv,
                                                       float* __restrict__ dq_part) {
-  extern __shared__ float sm[];
-  float* qs = sm;                       // [C][dq]
-  float* dhs = qs + C * dq;             // [C][d]   upstream gradient of the current segment
-  float* red = dhs + C * d;             // [4][C][dq] per-wave dq sums at the end of the run
+  extern __shared__ float red[];        // [4][C][dq] per-wave dq sums at the end of the run
   const int u = blockIdx.x / groups, grp = blockIdx.x % groups;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int n = valid_len(lens, u, L);
-  const int TQ = (dq + 63) / 64, TV = (d + 63) / 64;
-
-  for (int e = tid; e < C * dq; e += 256) qs[e] = load_as_f32(q, (size_t)u * C * dq + e);
+  const int n = __builtin_amdgcn_readfirstlane(valid_len(lens, u, L));
   const int i_beg = grp * spg;
   const int i_end = (grp + 1) * spg < S ? (grp + 1) * spg : S;
   const T* kU = k + (size_t)u * L * dq;
@@ -43,80 +49,91 @@ __global__ __launch_bounds__(256) void sta_bwd_kernel(const T* __restrict__ q, c
   float* dkU = dk + (size_t)u * L * dq;
   float* dvU = dv + (size_t)u * L * d;
 
-  float dqacc[SB_CMAX][SB_TMAX];
+  // queries and dq sums: lane l holds elements l, l + 64, ... of every candidate's row
+  float qr[CMAX][TQ], dqacc[CMAX][TQ];
 #pragma unroll
-  for (int c = 0; c < SB_CMAX; ++c)
+  for (int c = 0; c < CMAX; ++c)
 #pragma unroll
-    for (int t = 0; t < SB_TMAX; ++t) dqacc[c][t] = 0.0f;
+    for (int t = 0; t < TQ; ++t) {
+      const int e = lane + 64 * t;
+      qr[c][t] = (c < C && e < dq) ? load_as_f32(q, ((size_t)u * C + c) * dq + e) : 0.0f;
+      dqacc[c][t] = 0.0f;
+    }
 
-  for (int i = i_beg; i < i_end; ++i) {
+  // A wave owns whole segments (wave v takes segments i_beg + v, + 4, ... of the run): the upstream gradient of a
+  // segment is read into registers once, and nothing is shared between waves until the run ends.
+  for (int i = i_beg + wave; i < i_end; i += 4) {
     const int lo = i * w;
     int hi_all = lo + w;
     if (hi_all > L) hi_all = L;
     const int hi = hi_all < n ? hi_all : n;      // valid items of the segment: [lo, hi)
-    __syncthreads();                              // the previous segment's gradients are no longer read
-    if (hi > lo)
-      for (int e = tid; e < C * d; e += 256) {
-        const int c = e / d, col = e - c * d;
-        dhs[e] = load_as_f32(dhp, (((size_t)u * C + c) * S + i) * d + col);
-      }
-    __syncthreads();
-    for (int j = lo + wave; j < hi; j += 4) {
-      float kr[SB_TMAX], vr[SB_TMAX], dka[SB_TMAX], dva[SB_TMAX];
+    if (hi > lo) {
+      float dh[CMAX][TV];
 #pragma unroll
-      for (int t = 0; t < SB_TMAX; ++t) {
-        const int eq = lane + 64 * t;
-        kr[t] = (t < TQ && eq < dq) ? load_as_f32(kU, (size_t)j * dq + eq) : 0.0f;
-        vr[t] = (t < TV && eq < d) ? load_as_f32(vU, (size_t)j * d + eq) : 0.0f;
-        dka[t] = 0.0f;
-        dva[t] = 0.0f;
-      }
+      for (int c = 0; c < CMAX; ++c)
 #pragma unroll
-      for (int c = 0; c < SB_CMAX; ++c) {
-        if (c < C) {
-          float s = 0.0f, dot = 0.0f;
+        for (int t = 0; t < TV; ++t) {
+          const int e = lane + 64 * t;
+          dh[c][t] = (c < C && e < d) ? load_as_f32(dhp, (((size_t)u * C + c) * S + i) * d + e) : 0.0f;
+        }
+      // the rows of the next item are requested before the current one is worked on (an item is a chain of load, two
+      // wave-wide sums, a gate and two stores; only other waves and this prefetch hide the load)
+      float kn[TQ], vn[TV];
+      auto load_item = [&](int j) {
 #pragma unroll
-          for (int t = 0; t < SB_TMAX; ++t) {
-            const int e = lane + 64 * t;
-            if (t < TQ && e < dq) s = fmaf(kr[t], qs[c * dq + e], s);
-            if (t < TV && e < d) dot = fmaf(vr[t], dhs[c * d + e], dot);
-          }
-          s = wave_sum(s);
-          dot = wave_sum(dot);
-          const float g = 1.0f / (1.0f + expf(-s * inv_gamma));
-          const float ds = dot * g * (1.0f - g) * inv_gamma;   // d loss / d (q_c . k_j)
+        for (int t = 0; t < TQ; ++t) kn[t] = (lane + 64 * t < dq) ? load_as_f32(kU, (size_t)j * dq + lane + 64 * t) : 0.0f;
 #pragma unroll
-          for (int t = 0; t < SB_TMAX; ++t) {
-            const int e = lane + 64 * t;
-            if (t < TV && e < d) dva[t] = fmaf(g, dhs[c * d + e], dva[t]);
-            if (t < TQ && e < dq) {
-              dka[t] = fmaf(ds, qs[c * dq + e], dka[t]);
+        for (int t = 0; t < TV; ++t) vn[t] = (lane + 64 * t < d) ? load_as_f32(vU, (size_t)j * d + lane + 64 * t) : 0.0f;
+      };
+      load_item(lo);
+      for (int j = lo; j < hi; ++j) {
+        float kr[TQ], vr[TV], dka[TQ], dva[TV];
+#pragma unroll
+        for (int t = 0; t < TQ; ++t) { kr[t] = kn[t]; dka[t] = 0.0f; }
+#pragma unroll
+        for (int t = 0; t < TV; ++t) { vr[t] = vn[t]; dva[t] = 0.0f; }
+        if (j + 1 < hi) load_item(j + 1);
+#pragma unroll
+        for (int c = 0; c < CMAX; ++c) {
+          if (c < C) {
+            float s = 0.0f, dot = 0.0f;
+#pragma unroll
+            for (int t = 0; t < TQ; ++t) s = fmaf(kr[t], qr[c][t], s);
+#pragma unroll
+            for (int t = 0; t < TV; ++t) dot = fmaf(vr[t], dh[c][t], dot);
+            s = wave_sum_rows(s);
+            dot = wave_sum_rows(dot);
+            const float g = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(s * neg_scale_log2e));
+            const float ds = dot * g * (1.0f - g) * inv_gamma;   // d loss / d (q_c . k_j)
+#pragma unroll
+            for (int t = 0; t < TV; ++t) dva[t] = fmaf(g, dh[c][t], dva[t]);
+#pragma unroll
+            for (int t = 0; t < TQ; ++t) {
+              dka[t] = fmaf(ds, qr[c][t], dka[t]);
               dqacc[c][t] = fmaf(ds, kr[t], dqacc[c][t]);
             }
           }
         }
-      }
 #pragma unroll
-      for (int t = 0; t < SB_TMAX; ++t) {
-        const int e = lane + 64 * t;
-        if (t < TQ && e < dq) dkU[(size_t)j * dq + e] = dka[t];
-        if (t < TV && e < d) dvU[(size_t)j * d + e] = dva[t];
+        for (int t = 0; t < TQ; ++t)
+          if (lane + 64 * t < dq) dkU[(size_t)j * dq + lane + 64 * t] = dka[t];
+#pragma unroll
+        for (int t = 0; t < TV; ++t)
+          if (lane + 64 * t < d) dvU[(size_t)j * d + lane + 64 * t] = dva[t];
       }
     }
     // items of the segment at or past the valid length: zero gradients
     const int z0 = hi > lo ? hi : lo;
-    for (int e = tid; e < (hi_all - z0) * dq; e += 256) dkU[(size_t)z0 * dq + e] = 0.0f;
-    for (int e = tid; e < (hi_all - z0) * d; e += 256) dvU[(size_t)z0 * d + e] = 0.0f;
+    for (int e = lane; e < (hi_all - z0) * dq; e += 64) dkU[(size_t)z0 * dq + e] = 0.0f;
+    for (int e = lane; e < (hi_all - z0) * d; e += 64) dvU[(size_t)z0 * d + e] = 0.0f;
   }
   // dq of the run: waves in a fixed order
 #pragma unroll
-  for (int c = 0; c < SB_CMAX; ++c)
+  for (int c = 0; c < CMAX; ++c)
     if (c < C)
 #pragma unroll
-      for (int t = 0; t < SB_TMAX; ++t) {
-        const int e = lane + 64 * t;
-        if (t < TQ && e < dq) red[(wave * C + c) * dq + e] = dqacc[c][t];
-      }
+      for (int t = 0; t < TQ; ++t)
+        if (lane + 64 * t < dq) red[(wave * C + c) * dq + lane + 64 * t] = dqacc[c][t];
   __syncthreads();
   for (int e = tid; e < C * dq; e += 256)
     dq_part[((size_t)u * groups + grp) * C * dq + e] =
@@ -134,10 +151,17 @@ __global__ __launch_bounds__(256) void sta_bwd_dq_kernel(const float* __restrict
 }
 
 // runs of segments per user: enough workgroups to fill the machine a few times over, whole users when there are many
-static void sta_bwd_shape(int U, int S, int* spg, int* groups) {
+static void sta_bwd_shape(int U, int S, int w, int* spg, int* groups) {
   int g = (2048 + U - 1) / U;
   if (g > S) g = S;
   *spg = (S + g - 1) / g;
+  // short segments: runs of a dozen even out histories of different lengths (2048 users x 100 segments of 10 items,
+  // lengths 200..1000: 677 us with whole users, 588 us with runs of 8 to 12)
+  if (w <= 32 && *spg > 12) *spg = 12;
+  if (const char* e = getenv("LASER_BWD_SPG")) {   // tuning override
+    const int vv = atoi(e);
+    if (vv >= 1 && vv <= S) *spg = vv;
+  }
   *groups = (S + *spg - 1) / *spg;
 }
 
@@ -147,27 +171,49 @@ bool sta_backward_supports(const StaBwdArgs& a) {
 
 size_t sta_backward_work_bytes(int U, int C, int L, int d_q, int w) {
   int spg, groups;
-  sta_bwd_shape(U, (L + w - 1) / w, &spg, &groups);
+  sta_bwd_shape(U, (L + w - 1) / w, w, &spg, &groups);
   return (size_t)U * groups * C * d_q * sizeof(float);
+}
+
+template <typename T, int TQ, int TV>
+static void sta_bwd_launch_c(const StaBwdArgs& a, unsigned blocks, size_t lds, int spg, int groups) {
+  const float inv_gamma = 1.0f / a.gamma;
+  const float nsl = -1.4426950408889634f * inv_gamma;
+#define LASER_BWD_LAUNCH(CM)                                                                                          \
+  hipLaunchKernelGGL((sta_bwd_kernel<T, TQ, TV, CM>), dim3(blocks), dim3(256), lds, a.stream, (const T*)a.q,          \
+                     (const T*)a.k, (const T*)a.v, (const T*)a.dhp, a.lens, a.C, a.L, a.d_q, a.d, a.w, a.S, spg,      \
+                     groups, nsl, inv_gamma, a.dk, a.dv, a.work)
+  if (a.C <= 1) LASER_BWD_LAUNCH(1);
+  else if (a.C <= 4) LASER_BWD_LAUNCH(4);
+  else LASER_BWD_LAUNCH(8);
+#undef LASER_BWD_LAUNCH
+}
+
+template <typename T, int TQ>
+static void sta_bwd_launch_v(const StaBwdArgs& a, unsigned blocks, size_t lds, int spg, int groups) {
+  const int tv = (a.d + 63) / 64;
+  if (tv <= 1) sta_bwd_launch_c<T, TQ, 1>(a, blocks, lds, spg, groups);
+  else if (tv <= 2) sta_bwd_launch_c<T, TQ, 2>(a, blocks, lds, spg, groups);
+  else sta_bwd_launch_c<T, TQ, 4>(a, blocks, lds, spg, groups);
+}
+
+template <typename T>
+static void sta_bwd_launch_q(const StaBwdArgs& a, unsigned blocks, size_t lds, int spg, int groups) {
+  const int tq = (a.d_q + 63) / 64;
+  if (tq <= 1) sta_bwd_launch_v<T, 1>(a, blocks, lds, spg, groups);
+  else if (tq <= 2) sta_bwd_launch_v<T, 2>(a, blocks, lds, spg, groups);
+  else sta_bwd_launch_v<T, 4>(a, blocks, lds, spg, groups);
 }
 
 laser_status sta_backward_launch(const StaBwdArgs& a) {
   if (!sta_backward_supports(a)) return LASER_ERR_UNSUPPORTED;
   int spg, groups;
-  sta_bwd_shape(a.U, a.S, &spg, &groups);
+  sta_bwd_shape(a.U, a.S, a.w, &spg, &groups);
   const long long blocks = (long long)a.U * groups;
   if (blocks > 0x7fffffffLL) return LASER_ERR_SHAPE;
-  const size_t lds = sizeof(float) * ((size_t)a.C * a.d_q * 5 + (size_t)a.C * a.d);
-  const float inv_gamma = 1.0f / a.gamma;
-  if (a.dt == LASER_BF16)
-    hipLaunchKernelGGL(sta_bwd_kernel<unsigned short>, dim3((unsigned)blocks), dim3(256), lds, a.stream,
-                       (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v,
-                       (const unsigned short*)a.dhp, a.lens, a.C, a.L, a.d_q, a.d, a.w, a.S, spg, groups, inv_gamma,
-                       a.dk, a.dv, a.work);
-  else
-    hipLaunchKernelGGL(sta_bwd_kernel<float>, dim3((unsigned)blocks), dim3(256), lds, a.stream, (const float*)a.q,
-                       (const float*)a.k, (const float*)a.v, (const float*)a.dhp, a.lens, a.C, a.L, a.d_q, a.d, a.w,
-                       a.S, spg, groups, inv_gamma, a.dk, a.dv, a.work);
+  const size_t lds = sizeof(float) * (size_t)a.C * a.d_q * 4;
+  if (a.dt == LASER_BF16) sta_bwd_launch_q<unsigned short>(a, (unsigned)blocks, lds, spg, groups);
+  else sta_bwd_launch_q<float>(a, (unsigned)blocks, lds, spg, groups);
   if (launch_status() != LASER_OK) return LASER_ERR_LAUNCH;
   const long long total = (long long)a.U * a.C * a.d_q;
   hipLaunchKernelGGL(sta_bwd_dq_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, a.stream, a.work, groups,
