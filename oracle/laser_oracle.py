@@ -429,3 +429,67 @@ def sta_backward(q, k, v, lens, w: int, gamma: float, dHp):
                 dq[u, c] += ds * k[u, j] / gamma
                 dk[u, j] += ds * q[u, c] / gamma
     return dq, dk, dv
+
+
+def gsta_pair_backward(Hp, t, Wq, Wk, Wv, seg_valid, dz):
+    """Gradients of a scalar loss through GSTA for one pair (Sec. 3.4.3), given dz = d loss / d z [d]: returns
+    (dHp [S,d], dt [d], dWq, dWk, dWv [M,d,d]). The forward pass is replayed as gsta_pair defines it (projections
+    K' = H' W_k, V' = H' W_v as written in the paper, softmax over the valid segments, residual update), keeping
+    every layer's intermediates, and the chain rule is applied layer by layer from the last to the first:
+        t_l = t_{l-1} + o,  o = a V',  a = softmax(e),  e = K' q' / sqrt(d),  q' = t_{l-1} W_q.
+    Segments without a valid item take no part, so their rows of dHp are zero."""
+    Hp, t, dz = (np.asarray(x, dtype=np.float64) for x in (Hp, t, dz))
+    Wq, Wk, Wv = (np.asarray(x, dtype=np.float64) for x in (Wq, Wk, Wv))
+    S, d = Hp.shape
+    M = Wq.shape[0]
+    idx = np.flatnonzero(np.asarray(seg_valid))
+    dHp = np.zeros((S, d), dtype=np.float64)
+    dWq, dWk, dWv = np.zeros_like(Wq), np.zeros_like(Wk), np.zeros_like(Wv)
+    if idx.size == 0:
+        return dHp, dz.copy(), dWq, dWk, dWv          # z = t
+    Hv = Hp[idx]
+    saved = []
+    t_l = t.copy()
+    for l in range(M):                                # forward, as in gsta_pair
+        qp = t_l @ Wq[l]
+        Kp = Hv @ Wk[l]
+        Vp = Hv @ Wv[l]
+        e = (Kp @ qp) / math.sqrt(d)
+        pe = np.exp(e - e.max())
+        a = pe / pe.sum()
+        saved.append((t_l, qp, Kp, Vp, a))
+        t_l = t_l + a @ Vp
+    g = dz.copy()                                     # d loss / d t_l, walking down
+    dHv = np.zeros_like(Hv)
+    for l in range(M - 1, -1, -1):
+        t_in, qp, Kp, Vp, a = saved[l]
+        da = Vp @ g                                   # o = a V'
+        dVp = np.outer(a, g)
+        de = a * (da - a @ da)                        # softmax
+        dKp = np.outer(de, qp) / math.sqrt(d)         # e = K' q' / sqrt(d)
+        dqp = (de @ Kp) / math.sqrt(d)
+        dWv[l] = Hv.T @ dVp                           # V' = H' W_v
+        dWk[l] = Hv.T @ dKp                           # K' = H' W_k
+        dHv += dVp @ Wv[l].T + dKp @ Wk[l].T
+        dWq[l] = np.outer(t_in, dqp)                  # q' = t W_q
+        g = g + dqp @ Wq[l].T                         # residual path plus the path through q'
+    dHp[idx] = dHv
+    return dHp, g, dWq, dWk, dWv
+
+
+def gsta_backward(Hp, t0, wq, wk, wv, cnt, dz):
+    """Batch form: Hp [U,C,S,d], t0 [U,C,d], dz [U,C,d] -> (dHp [U,C,S,d], dt0 [U,C,d], dWq, dWk, dWv [M,d,d]); the
+    weight gradients are summed over all pairs."""
+    Hp, t0, dz = (np.asarray(x, dtype=np.float64) for x in (Hp, t0, dz))
+    U, C, S, d = Hp.shape
+    dHp, dt0 = np.zeros_like(Hp), np.zeros_like(t0)
+    dWq, dWk, dWv = (np.zeros(np.asarray(x).shape, dtype=np.float64) for x in (wq, wk, wv))
+    for u in range(U):
+        valid = np.asarray(cnt[u]) > 0
+        for c in range(C):
+            a, b, gq, gk, gv = gsta_pair_backward(Hp[u, c], t0[u, c], wq, wk, wv, valid, dz[u, c])
+            dHp[u, c], dt0[u, c] = a, b
+            dWq += gq
+            dWk += gk
+            dWv += gv
+    return dHp, dt0, dWq, dWk, dWv

@@ -743,3 +743,56 @@ def test_sta_backward_closed_forms():
     a = oracle.sta_backward(q, k, v, None, w, gamma, up)
     b = oracle.sta_backward(q, k, v, None, w, gamma, -2.0 * up)
     assert all(np.allclose(y, -2.0 * x) for x, y in zip(a, b))
+
+
+# ------------------------------------------------------------------ GSTA backward
+def _torch_gsta(Hp, t, Wq, Wk, Wv, valid):
+    """One pair's forward pass in torch fp64 ops with a key mask (written independently of the checker)."""
+    d = Hp.shape[1]
+    mask = torch.tensor(valid)
+    for l in range(Wq.shape[0]):
+        if not mask.any():
+            break
+        e = (Hp @ Wk[l]) @ (t @ Wq[l]) / math.sqrt(d)
+        a = torch.softmax(e.masked_fill(~mask, float("-inf")), dim=0)
+        t = t + a @ (Hp @ Wv[l])
+    return t
+
+
+@pytest.mark.parametrize("M,valid", [(1, [1, 1, 1, 1, 1]), (3, [1, 1, 1, 0, 0]), (2, [0, 0, 0, 0, 0]), (2, [1, 0, 0, 0, 0])])
+def test_gsta_backward_matches_autograd(M, valid):
+    rng = np.random.default_rng(5000 + M + sum(valid))
+    S, d = 5, 6
+    valid = np.array(valid, dtype=bool)
+    Hp, t, dz = rng.normal(size=(S, d)), rng.normal(size=d), rng.normal(size=d)
+    Wq, Wk, Wv = (rng.normal(size=(M, d, d)) / math.sqrt(d) for _ in range(3))
+    got = lo.gsta_pair_backward(Hp, t, Wq, Wk, Wv, valid, dz)
+    th = [torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (Hp, t, Wq, Wk, Wv)]
+    z = _torch_gsta(*th, valid)
+    assert np.allclose(z.detach().numpy(), lo.gsta_pair(Hp, t, Wq, Wk, Wv, valid), rtol=1e-12)
+    (z * torch.tensor(dz)).sum().backward()
+    for mine, ref in zip(got, th):
+        ref = np.zeros_like(mine) if ref.grad is None else ref.grad.numpy()
+        assert np.allclose(mine, ref, rtol=1e-10, atol=1e-12)
+    assert not got[0][~valid].any()            # segments without a valid item get no gradient
+
+
+def test_gsta_backward_batch_and_finite_differences():
+    rng = np.random.default_rng(5100)
+    U, C, S, d, M = 2, 2, 4, 5, 2
+    Hp, t0, dz = rng.normal(size=(U, C, S, d)), rng.normal(size=(U, C, d)), rng.normal(size=(U, C, d))
+    Wq, Wk, Wv = (rng.normal(size=(M, d, d)) / math.sqrt(d) for _ in range(3))
+    cnt = np.array([[3, 3, 1, 0], [2, 0, 0, 0]])
+    dHp, dt0, dWq, dWk, dWv = oracle.gsta_backward(Hp, t0, Wq, Wk, Wv, cnt, dz)
+    loss = lambda Hp_, t_, q_, k_, v_: float((oracle.gsta_forward(Hp_, t_, q_, k_, v_, cnt) * dz).sum())
+    h = 1e-6
+    for _ in range(3):
+        dirs = [rng.normal(size=x.shape) for x in (Hp, t0, Wq, Wk, Wv)]
+        plus = loss(*[x + h * dx for x, dx in zip((Hp, t0, Wq, Wk, Wv), dirs)])
+        minus = loss(*[x - h * dx for x, dx in zip((Hp, t0, Wq, Wk, Wv), dirs)])
+        ana = sum((g * dx).sum() for g, dx in zip((dHp, dt0, dWq, dWk, dWv), dirs))
+        assert abs((plus - minus) / (2 * h) - ana) <= 1e-6 * max(1.0, abs(ana))
+    # weight gradients are sums over the pairs
+    one = lo.gsta_pair_backward(Hp[0, 1], t0[0, 1], Wq, Wk, Wv, cnt[0] > 0, dz[0, 1])
+    rest = oracle.gsta_backward(Hp, t0, Wq, Wk, Wv, cnt, np.where(np.arange(U * C).reshape(U, C, 1) == 1, 0.0, dz))
+    assert np.allclose(dWk, one[3] + rest[3], rtol=1e-11, atol=1e-13)
