@@ -325,6 +325,29 @@ laser_status laser_sta_backward(const void* q, const void* k, const void* v, con
                                 float* dq_out, float* dk_out, float* dv_out, void* work, size_t work_bytes,
                                 void* stream);
 
+/*
+ * Backward pass of GSTA (the derivatives of the forward equations of paper Sec. 3.4.3: per layer q' = t W_q,
+ * e = (H' W_k) q' / sqrt(d), a = softmax over the valid segments, t <- t + a (H' W_v); the paper prints no backward
+ * formulas). Given dz = d loss / d z [U,C,d] (fp32):
+ *   dseg_out [U,C,S,d] dt    d loss / d H' through GSTA (rows of segments without a valid item are zeros); this is the
+ *                            dseg argument of laser_sta_backward (add the other consumers of H' first, if any)
+ *   dt0_out  [U,C,d]   fp32  d loss / d t0
+ *   dwq_out, dwk_out, dwv_out [M,d,d] fp32, summed over all pairs in a fixed order
+ * seg, t0, wq, wk, wv, lens and the sizes as for laser_gsta_forward. Arithmetic in fp32 from the stored inputs; dseg_out
+ * is rounded once to dt. Generic kernels (one workgroup per pair, H' and its gradient in LDS): d <= 256, M <= 8 and
+ * (2 S d + (M + 7) d + 2 S) * 4 bytes <= 150 KB; other shapes return LASER_ERR_UNSUPPORTED. work is caller-owned scratch
+ * of at least laser_gsta_backward_work_bytes(U, C, d, M) bytes (six d-vectors per pair and layer, whose outer products
+ * are the weight gradients); the library allocates nothing.
+ * All pointers are device pointers, 16-byte aligned (lens 4-byte); outputs are fully overwritten; work is enqueued on
+ * `stream`. Errors: LASER_ERR_NULL, LASER_ERR_SHAPE (sizes, work_bytes too small), LASER_ERR_DTYPE, LASER_ERR_ALIGN,
+ * LASER_ERR_UNSUPPORTED, LASER_ERR_LAUNCH. Nothing is launched on an error.
+ */
+size_t laser_gsta_backward_work_bytes(int U, int C, int d, int M);   /* host only; 0 for invalid sizes */
+laser_status laser_gsta_backward(const void* seg, const void* t0, const void* wq, const void* wk, const void* wv,
+                                 const int32_t* lens, const float* dz, int U, int C, int L, int d, int w, int M,
+                                 laser_dtype dt, void* dseg_out, float* dt0_out, float* dwq_out, float* dwk_out,
+                                 float* dwv_out, void* work, size_t work_bytes, void* stream);
+
 /* Name of the STA / GSTA kernel AUTO would pick for a shape (static strings; host only, no GPU needed). */
 const char* laser_sta_kernel_name(int C, int d_q, int d, int w, laser_dtype dt);
 const char* laser_gsta_kernel_name(int C, int S, int d, laser_dtype dt);               /* one layer (M = 1) */

@@ -27,7 +27,8 @@ EXPORTS = [
     "laser_gsta_kernel_name", "laser_segment_ffn_forward", "laser_segment_ffn_forward_variant",
     "laser_gsta_kernel_name_layers", "laser_project_q_forward", "laser_project_q_forward_variant",
     "laser_project_kv_forward", "laser_project_kv_forward_variant", "laser_fold_query_weights",
-    "laser_project_heads_forward", "laser_sta_folded_forward", "laser_sta_backward", "laser_sta_backward_work_bytes",
+    "laser_project_heads_forward", "laser_sta_folded_forward", "laser_sta_backward", "laser_sta_backward_work_bytes", "laser_gsta_backward",
+    "laser_gsta_backward_work_bytes",
     "laser_status_string", "laser_version",
 ]
 
@@ -98,6 +99,11 @@ def load_library() -> ctypes.CDLL:
     lib.laser_sta_backward.argtypes = [vp, vp, vp, ip, vp, i32, i32, i32, i32, i32, i32, f32, i32, vp, vp, vp, vp,
                                        ctypes.c_size_t, vp]
     lib.laser_sta_backward.restype = i32
+    lib.laser_gsta_backward_work_bytes.argtypes = [i32, i32, i32, i32]
+    lib.laser_gsta_backward_work_bytes.restype = ctypes.c_size_t
+    lib.laser_gsta_backward.argtypes = [vp, vp, vp, vp, vp, ip, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp,
+                                        vp, ctypes.c_size_t, vp]
+    lib.laser_gsta_backward.restype = i32
     lib.laser_sta_kernel_name.argtypes = [i32, i32, i32, i32, i32]
     lib.laser_sta_kernel_name.restype = ctypes.c_char_p
     lib.laser_gsta_kernel_name.argtypes = [i32, i32, i32, i32]
@@ -357,6 +363,30 @@ def laser_sta_backward(q, k, v, lens, dseg, w: int, gamma: float, dq_out=None, d
                                   work.numel() * work.element_size(), _stream(stream))
     _check(code, "laser_sta_backward")
     return dq_out, dk_out, dv_out
+
+
+def laser_gsta_backward(seg, t0, wq, wk, wv, lens, dz, L: int, w: int, work=None, stream=None):
+    """Gradients of GSTA from dz [U,C,d] fp32: (dseg [U,C,S,d] in seg's dtype, dt0 [U,C,d], dwq, dwk, dwv [M,d,d] fp32)."""
+    torch = _torch()
+    U, C, S, d = seg.shape
+    M = wq.shape[0]
+    if S != -(-L // w) or tuple(dz.shape) != (U, C, d) or tuple(t0.shape) != (U, C, d):
+        raise ValueError("seg, t0, dz shapes disagree")
+    f32 = dict(dtype=torch.float32, device=seg.device)
+    dseg = torch.empty_like(seg)
+    dt0 = torch.empty((U, C, d), **f32)
+    dwq, dwk, dwv = (torch.empty((M, d, d), **f32) for _ in range(3))
+    lib = load_library()
+    need = lib.laser_gsta_backward_work_bytes(U, C, d, M)
+    if work is None:
+        work = torch.empty(max(need, 16), dtype=torch.uint8, device=seg.device)
+    code = lib.laser_gsta_backward(_ptr(seg, "seg"), _ptr(t0, "t0"), _ptr(wq, "wq"), _ptr(wk, "wk"), _ptr(wv, "wv"),
+                                   _ptr(lens, "lens", torch.int32), _ptr(dz, "dz", torch.float32), U, C, int(L), d,
+                                   int(w), M, _dt(seg), _ptr(dseg, "dseg"), _ptr(dt0, "dt0"), _ptr(dwq, "dwq"),
+                                   _ptr(dwk, "dwk"), _ptr(dwv, "dwv"), _ptr(work, "work"),
+                                   work.numel() * work.element_size(), _stream(stream))
+    _check(code, "laser_gsta_backward")
+    return dseg, dt0, dwq, dwk, dwv
 
 
 def laser_fold_query_weights(w_q, w_k, heads: int = 1, a_out=None, stream=None):

@@ -1,0 +1,236 @@
+// Backward pass of GSTA (derivatives of the forward equations of paper Sec. 3.4.3), generic form: fp32 arithmetic,
+// either storage type, one workgroup per (user, candidate) pair with the pair's valid rows of H' and their
+// gradients in LDS. Per layer, in the re-associated form the forward kernels use (exact re-association):
+//   q' = t W_q,  r = W_k q',  e_i = H'_i . r / sqrt(d),  a = softmax(e),  p = sum_i a_i H'_i,  o = p W_v,  t += o.
+// The layers' inputs t_l are kept from a first forward sweep; the backward sweep replays a layer's q', r, a, p and
+// applies the chain rule. All three weight gradients of a pair and layer are outer products of d-vectors,
+//   dW_v = p (x) do,   dW_k = dr (x) q',   dW_q = t_l (x) dq',
+// so the pair kernel only writes those six vectors to the caller's scratch, and a second kernel sums the outer
+// products over all pairs in a fixed order (deterministic).
+#include "laser_internal.h"
+
+namespace laser {
+
+constexpr int GB_THREADS = 256, GB_MAXM = 8, GB_MAXD = 256;
+
+template <typename T>
+__global__ __launch_bounds__(GB_THREADS) void gsta_bwd_kernel(const T* __restrict__ seg, const T* __restrict__ t0,
+                                                              const T* __restrict__ wq, const T* __restrict__ wk,
+                                                              const T* __restrict__ wv, const int32_t* __restrict__ lens,
+                                                              const float* __restrict__ dz, int C, int L, int d, int w,
+                                                              int S, int M, T* __restrict__ dseg,
+                                                              float* __restrict__ dt0, float* __restrict__ pv) {
+  extern __shared__ float sm[];
+  const int pair = blockIdx.x, u = pair / C;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nv = (valid_len(lens, u, L) + w - 1) / w;     // valid segments are a prefix
+  float* Hs = sm;                    // [nv][d]
+  float* dHs = Hs + (size_t)nv * d;  // [nv][d]
+  float* ts = dHs + (size_t)nv * d;  // [M][d]  t_0 .. t_{M-1}
+  float* qp = ts + M * d;            // the seven vectors below: [d] each
+  float* rv = qp + d;
+  float* pvv = rv + d;
+  float* g = pvv + d;
+  float* dp = g + d;
+  float* drv = dp + d;
+  float* dqp = drv + d;
+  float* av = dqp + d;               // [S] softmax weights
+  float* da = av + S;                // [S]
+  __shared__ float red[4];
+  const float scale = 1.0f / sqrtf((float)d);
+  const T* H = seg + (size_t)pair * S * d;
+  T* dH = dseg + (size_t)pair * S * d;
+  float* pvp = pv + (size_t)pair * M * 6 * d;
+
+  for (int e = tid; e < nv * d; e += GB_THREADS) {
+    Hs[e] = load_as_f32(H, (size_t)e);
+    dHs[e] = 0.0f;
+  }
+  for (int e = tid; e < d; e += GB_THREADS) {
+    ts[e] = load_as_f32(t0, (size_t)pair * d + e);
+    g[e] = dz[(size_t)pair * d + e];
+  }
+  __syncthreads();
+  if (nv == 0) {   // z = t0: the gradient passes straight through, nothing else gets any
+    for (int e = tid; e < d; e += GB_THREADS) dt0[(size_t)pair * d + e] = g[e];
+    for (int e = tid; e < S * d; e += GB_THREADS) store_from_f32(dH, (size_t)e, 0.0f);
+    for (int e = tid; e < M * 6 * d; e += GB_THREADS) pvp[e] = 0.0f;
+    return;
+  }
+
+  // out[y] = sum_x in[x] W[x][y]: one thread per column, coalesced over y
+  auto col_matvec = [&](float* out, const float* in, const T* W) {
+    for (int y = tid; y < d; y += GB_THREADS) {
+      float acc = 0.0f;
+      for (int x = 0; x < d; ++x) acc = fmaf(in[x], load_as_f32(W, (size_t)x * d + y), acc);
+      out[y] = acc;
+    }
+  };
+  // out[x] (+)= sum_y W[x][y] in[y]: one wave per row, lanes along the row
+  auto row_matvec = [&](float* out, const float* in, const T* W, bool add) {
+    for (int x = wave; x < d; x += GB_THREADS / 64) {
+      float acc = 0.0f;
+      for (int y = lane; y < d; y += 64) acc = fmaf(load_as_f32(W, (size_t)x * d + y), in[y], acc);
+      acc = wave_sum(acc);
+      if (lane == 0) out[x] = add ? out[x] + acc : acc;
+    }
+  };
+  // q', r, a, p of layer l from its input t_l (the forward pass up to the value projection)
+  auto replay = [&](int l) {
+    col_matvec(qp, ts + l * d, wq + (size_t)l * d * d);
+    __syncthreads();
+    row_matvec(rv, qp, wk + (size_t)l * d * d, false);
+    __syncthreads();
+    for (int i = wave; i < nv; i += GB_THREADS / 64) {
+      float acc = 0.0f;
+      for (int x = lane; x < d; x += 64) acc = fmaf(Hs[i * d + x], rv[x], acc);
+      acc = wave_sum(acc);
+      if (lane == 0) av[i] = acc * scale;
+    }
+    __syncthreads();
+    if (wave == 0) {   // softmax over the valid segments
+      float m = -INFINITY;
+      for (int i = lane; i < nv; i += 64) m = fmaxf(m, av[i]);
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+      float ssum = 0.0f;
+      for (int i = lane; i < nv; i += 64) {
+        const float ex = expf(av[i] - m);
+        av[i] = ex;
+        ssum += ex;
+      }
+      ssum = wave_sum(ssum);
+      if (lane == 0) red[0] = 1.0f / ssum;
+    }
+    __syncthreads();
+    for (int i = tid; i < nv; i += GB_THREADS) av[i] *= red[0];
+    __syncthreads();
+    for (int x = tid; x < d; x += GB_THREADS) {
+      float acc = 0.0f;
+      for (int i = 0; i < nv; ++i) acc = fmaf(av[i], Hs[i * d + x], acc);
+      pvv[x] = acc;
+    }
+    __syncthreads();
+  };
+
+  // forward sweep: the inputs of layers 1 .. M-1
+  for (int l = 0; l + 1 < M; ++l) {
+    replay(l);
+    col_matvec(dp, pvv, wv + (size_t)l * d * d);   // o = p W_v (dp is free here)
+    __syncthreads();
+    for (int e = tid; e < d; e += GB_THREADS) ts[(l + 1) * d + e] = ts[l * d + e] + dp[e];
+    __syncthreads();
+  }
+  // backward sweep
+  for (int l = M - 1; l >= 0; --l) {
+    replay(l);
+    float* out6 = pvp + (size_t)l * 6 * d;
+    row_matvec(dp, g, wv + (size_t)l * d * d, false);             // dp = do W_v^T, do = g
+    for (int e = tid; e < d; e += GB_THREADS) {
+      out6[e] = pvv[e];                                           // dW_v = p (x) do
+      out6[d + e] = g[e];
+    }
+    __syncthreads();
+    for (int i = wave; i < nv; i += GB_THREADS / 64) {            // da_i = dp . H'_i
+      float acc = 0.0f;
+      for (int x = lane; x < d; x += 64) acc = fmaf(Hs[i * d + x], dp[x], acc);
+      acc = wave_sum(acc);
+      if (lane == 0) da[i] = acc;
+    }
+    __syncthreads();
+    if (wave == 0) {                                              // sum_k a_k da_k
+      float acc = 0.0f;
+      for (int i = lane; i < nv; i += 64) acc = fmaf(av[i], da[i], acc);
+      acc = wave_sum(acc);
+      if (lane == 0) red[1] = acc;
+    }
+    __syncthreads();
+    for (int e = tid; e < nv * d; e += GB_THREADS) {              // dH'_i += a_i dp + de_i r / sqrt(d)
+      const int i = e / d, x = e - i * d;
+      const float de = av[i] * (da[i] - red[1]);
+      dHs[e] += av[i] * dp[x] + de * rv[x] * scale;
+    }
+    for (int x = tid; x < d; x += GB_THREADS) {                   // dr = sum_i de_i H'_i / sqrt(d)
+      float acc = 0.0f;
+      for (int i = 0; i < nv; ++i) acc = fmaf(av[i] * (da[i] - red[1]), Hs[i * d + x], acc);
+      drv[x] = acc * scale;
+    }
+    __syncthreads();
+    col_matvec(dqp, drv, wk + (size_t)l * d * d);                 // dq' = dr W_k
+    __syncthreads();
+    for (int e = tid; e < d; e += GB_THREADS) {
+      out6[2 * d + e] = drv[e];                                   // dW_k = dr (x) q'
+      out6[3 * d + e] = qp[e];
+      out6[4 * d + e] = ts[l * d + e];                            // dW_q = t_l (x) dq'
+      out6[5 * d + e] = dqp[e];
+    }
+    row_matvec(g, dqp, wq + (size_t)l * d * d, true);             // g += dq' W_q^T (the residual path keeps g)
+    __syncthreads();
+  }
+  for (int e = tid; e < d; e += GB_THREADS) dt0[(size_t)pair * d + e] = g[e];
+  for (int e = tid; e < S * d; e += GB_THREADS) store_from_f32(dH, (size_t)e, e < nv * d ? dHs[e] : 0.0f);
+}
+
+// dW[l][x][y] = sum over pairs of A[pair][l][x] * B[pair][l][y], pairs in ascending order; one thread per (x, y)
+__global__ __launch_bounds__(256) void gsta_bwd_w_kernel(const float* __restrict__ pv, int P, int M, int d,
+                                                         float* __restrict__ dwq, float* __restrict__ dwk,
+                                                         float* __restrict__ dwv) {
+  const int tiles = (d + 15) / 16;
+  int bid = blockIdx.x;
+  const int ty = bid % tiles;
+  bid /= tiles;
+  const int tx = bid % tiles;
+  bid /= tiles;
+  const int which = bid % 3, l = bid / 3;     // 0: dW_v (p, do), 1: dW_k (dr, q'), 2: dW_q (t_l, dq')
+  const int x = tx * 16 + threadIdx.x / 16, y = ty * 16 + threadIdx.x % 16;
+  if (x >= d || y >= d) return;
+  const float* a = pv + ((size_t)l * 6 + 2 * which) * d + x;
+  const float* b = pv + ((size_t)l * 6 + 2 * which + 1) * d + y;
+  const size_t stride = (size_t)M * 6 * d;
+  float acc = 0.0f;
+  for (int p = 0; p < P; ++p) acc = fmaf(a[p * stride], b[p * stride], acc);
+  float* out = which == 0 ? dwv : (which == 1 ? dwk : dwq);
+  out[((size_t)l * d + x) * d + y] = acc;
+}
+
+static size_t gsta_bwd_lds(const GstaBwdArgs& a) {
+  return sizeof(float) * (2 * (size_t)a.S * a.d + (size_t)(a.M + 7) * a.d + 2 * (size_t)a.S);
+}
+
+bool gsta_backward_supports(const GstaBwdArgs& a) {
+  return a.d <= GB_MAXD && a.M <= GB_MAXM && gsta_bwd_lds(a) <= 150 * 1024;
+}
+
+size_t gsta_backward_work_bytes(int U, int C, int d, int M) { return (size_t)U * C * M * 6 * d * sizeof(float); }
+
+laser_status gsta_backward_launch(const GstaBwdArgs& a) {
+  if (!gsta_backward_supports(a)) return LASER_ERR_UNSUPPORTED;
+  const int P = a.U * a.C;
+  const size_t lds = gsta_bwd_lds(a);
+  if (a.dt == LASER_BF16) {
+    auto kern = gsta_bwd_kernel<unsigned short>;
+    if (lds > 48 * 1024 &&
+        hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return LASER_ERR_LAUNCH;
+    hipLaunchKernelGGL(kern, dim3((unsigned)P), dim3(GB_THREADS), lds, a.stream, (const unsigned short*)a.seg,
+                       (const unsigned short*)a.t0, (const unsigned short*)a.wq, (const unsigned short*)a.wk,
+                       (const unsigned short*)a.wv, a.lens, a.dz, a.C, a.L, a.d, a.w, a.S, a.M,
+                       (unsigned short*)a.dseg, a.dt0, a.work);
+  } else {
+    auto kern = gsta_bwd_kernel<float>;
+    if (lds > 48 * 1024 &&
+        hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return LASER_ERR_LAUNCH;
+    hipLaunchKernelGGL(kern, dim3((unsigned)P), dim3(GB_THREADS), lds, a.stream, (const float*)a.seg,
+                       (const float*)a.t0, (const float*)a.wq, (const float*)a.wk, (const float*)a.wv, a.lens, a.dz, a.C,
+                       a.L, a.d, a.w, a.S, a.M, (float*)a.dseg, a.dt0, a.work);
+  }
+  if (launch_status() != LASER_OK) return LASER_ERR_LAUNCH;
+  const int tiles = (a.d + 15) / 16;
+  hipLaunchKernelGGL(gsta_bwd_w_kernel, dim3((unsigned)(a.M * 3 * tiles * tiles)), dim3(256), 0, a.stream, a.work, P,
+                     a.M, a.d, a.dwq, a.dwk, a.dwv);
+  return launch_status();
+}
+
+}  // namespace laser

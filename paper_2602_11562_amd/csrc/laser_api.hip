@@ -445,6 +445,28 @@ laser_status laser_sta_backward(const void* q, const void* k, const void* v, con
   return sta_backward_launch(a);
 }
 
+size_t laser_gsta_backward_work_bytes(int U, int C, int d, int M) {
+  if (U <= 0 || C <= 0 || d <= 0 || M <= 0) return 0;
+  return gsta_backward_work_bytes(U, C, d, M);
+}
+
+laser_status laser_gsta_backward(const void* seg, const void* t0, const void* wq, const void* wk, const void* wv,
+                                 const int32_t* lens, const float* dz, int U, int C, int L, int d, int w, int M,
+                                 laser_dtype dt, void* dseg_out, float* dt0_out, float* dwq_out, float* dwk_out,
+                                 float* dwv_out, void* work, size_t work_bytes, void* stream) {
+  if (!dz || !dseg_out || !dt0_out || !dwq_out || !dwk_out || !dwv_out || !work) return LASER_ERR_NULL;
+  GstaArgs fa;   // the forward pass's checks of the shared arguments (dt0_out stands in for z_out: same shape and type)
+  laser_status s = validate_gsta(seg, t0, wq, wk, wv, lens, U, C, L, d, w, M, dt, dt0_out, stream, &fa);
+  if (s != LASER_OK) return s;
+  for (const void* p : {(const void*)dz, (const void*)dseg_out, (const void*)dwq_out, (const void*)dwk_out,
+                        (const void*)dwv_out, (const void*)work})
+    if (!aligned16(p)) return LASER_ERR_ALIGN;
+  if (work_bytes < gsta_backward_work_bytes(U, C, d, M)) return LASER_ERR_SHAPE;
+  const GstaBwdArgs a{seg, t0, wq, wk, wv, lens, dz, U, C, L, d, w, fa.S, M, dt, dseg_out, dt0_out, dwq_out, dwk_out,
+                      dwv_out, static_cast<float*>(work), static_cast<hipStream_t>(stream)};
+  return gsta_backward_launch(a);
+}
+
 const char* laser_sta_kernel_name(int C, int d_q, int d, int w, laser_dtype dt) {
   StaArgs a{};
   a.U = 1; a.C = C; a.L = w > 0 ? w : 1; a.d_q = d_q; a.d = d; a.w = w; a.S = 1; a.gamma = 1.0f; a.dt = dt;

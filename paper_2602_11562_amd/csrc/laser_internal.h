@@ -131,6 +131,28 @@ bool sta_backward_supports(const StaBwdArgs& a);
 size_t sta_backward_work_bytes(int U, int C, int L, int d_q, int w);
 laser_status sta_backward_launch(const StaBwdArgs& a);
 
+struct GstaBwdArgs {       // gradients of GSTA from dz = d loss / d z [U,C,d] (fp32)
+  const void* seg;         // H' [U,C,S,d]
+  const void* t0;
+  const void* wq;
+  const void* wk;
+  const void* wv;
+  const int32_t* lens;
+  const float* dz;
+  int U, C, L, d, w, S, M;
+  laser_dtype dt;
+  void* dseg;              // [U,C,S,d] dt
+  float* dt0;              // [U,C,d]
+  float* dwq;              // [M,d,d] each, summed over all pairs
+  float* dwk;
+  float* dwv;
+  float* work;             // [U*C, M, 6, d] per-pair vectors, gsta_backward_work_bytes() bytes
+  hipStream_t stream;
+};
+bool gsta_backward_supports(const GstaBwdArgs& a);
+size_t gsta_backward_work_bytes(int U, int C, int d, int M);
+laser_status gsta_backward_launch(const GstaBwdArgs& a);
+
 // Each launcher returns LASER_ERR_UNSUPPORTED (launching nothing) when the shape is outside its range.
 bool sta_generic_supports(const StaArgs& a);
 laser_status sta_generic_launch(const StaArgs& a);
