@@ -173,6 +173,9 @@ def main() -> int:
     ap.add_argument("--ragged", action="store_true",
                     help="also time the packed-pairs entry point with a seeded ragged candidate count per user "
                          "(uniform between a quarter of C and C); reported under \"ragged\"")
+    ap.add_argument("--backward", action="store_true",
+                    help="also time the backward pass of GSTA on the workload's H' (and of STA when the workload has "
+                         "at most 8 candidates per user); reported under \"backward\"")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device copy 5 times (reference reading for the FETCH_SIZE / "
                          "WRITE_SIZE counters when this command runs under rocprofv3 --pmc)")
@@ -379,6 +382,50 @@ def main() -> int:
                   "ms_per_step": rag_ms, "pairs_per_s": Pr / (rag_ms * 1e-3),
                   "dense_padded_ms_per_step": ms_per_step, "equals_dense_rows": same}
 
+    backward = None
+    if args.backward:
+        gen = torch.Generator(device="cuda").manual_seed(spec.seed + 8)
+        dz = torch.randn(spec.U, spec.C, spec.d, device="cuda", generator=gen)
+        lib = laser.load_library()
+        gwork = torch.empty(max(16, lib.laser_gsta_backward_work_bytes(spec.U, spec.C, spec.d, spec.M)), dtype=torch.uint8,
+                            device="cuda")
+        step(0)
+        torch.cuda.synchronize()
+
+        def gsta_bwd(i):
+            dw, seg, cnt, z = sets[i % copies]
+            return laser.laser_gsta_backward(seg, dw.t0, dw.wq, dw.wk, dw.wv, dw.lens, dz, spec.L, spec.w, work=gwork)
+
+        backward = {}
+        try:
+            g_ms = event_time(gsta_bwd)
+            nvalid = int(sum(-(-int(n) // spec.w) for n in wl.lens))
+            # H' (valid rows) read once and dH' (every row) written once in the storage type; t0, dz, dt0 and the six
+            # vectors per pair and layer once; the weights once
+            g_b = ((nvalid * spec.C * spec.d + spec.pairs * spec.S * spec.d + spec.pairs * spec.d) * esz
+                   + spec.pairs * spec.d * 4 * (2 + 12 * spec.M) + 3 * spec.M * spec.d * spec.d * (esz + 4))
+            backward["gsta"] = {"ms": g_ms, "algorithmic_bytes": g_b, "gbps": g_b / (g_ms * 1e-3) / 1e9,
+                                "frac_of_hbm_peak": g_b / (g_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        except laser.LaserError as e:
+            backward["gsta"] = {"error": str(e)}
+        if spec.C <= 8:
+            dseg = torch.randn(spec.U, spec.C, spec.S, spec.d, device="cuda", generator=gen).to(tdt)
+            swork = torch.empty(max(16, lib.laser_sta_backward_work_bytes(spec.U, spec.C, spec.L, spec.d_q, spec.w)),
+                                dtype=torch.uint8, device="cuda")
+            outs_b = (torch.empty(spec.U, spec.C, spec.d_q, device="cuda"), torch.empty(spec.U, spec.L, spec.d_q, device="cuda"),
+                      torch.empty(spec.U, spec.L, spec.d, device="cuda"))
+
+            def sta_bwd(i):
+                dw = sets[i % copies][0]
+                laser.laser_sta_backward(dw.q, dw.k, dw.v, dw.lens, dseg, spec.w, spec.gamma, dq_out=outs_b[0],
+                                         dk_out=outs_b[1], dv_out=outs_b[2], work=swork)
+
+            s_ms = event_time(sta_bwd)
+            nitems = int(sum(int(n) for n in wl.lens))
+            s_b = (nitems * (spec.d_q + spec.d) + spec.pairs * spec.S * spec.d) * esz + spec.U * spec.L * (spec.d_q + spec.d) * 4
+            backward["sta"] = {"ms": s_ms, "algorithmic_bytes": s_b, "gbps": s_b / (s_ms * 1e-3) / 1e9,
+                               "frac_of_hbm_peak": s_b / (s_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
     if args.calibration_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
@@ -442,6 +489,7 @@ def main() -> int:
         "ffn": ffn,
         "project": project,
         "ragged": ragged,
+        "backward": backward,
         "parity": {"max_vector_rel_err": worst, "tolerance": TOL[spec.dtype], "ok": bool(parity_ok),
                    "sampled_pairs": 4},
     }

@@ -13,6 +13,26 @@ namespace laser {
 
 constexpr int GB_THREADS = 256, GB_MAXM = 8, GB_MAXD = 256;
 
+// eight consecutive elements (16-byte aligned for bf16, 32-byte for fp32) as fp32
+__device__ __forceinline__ void load8_as_f32(const unsigned short* p, float (&out)[8]) {
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 raw = *reinterpret_cast<const u32x4*>(p);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    out[2 * e] = __uint_as_float(raw[e] << 16);
+    out[2 * e + 1] = __uint_as_float(raw[e] & 0xffff0000u);
+  }
+}
+__device__ __forceinline__ void load8_as_f32(const float* p, float (&out)[8]) {
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  const f32x4 a = *reinterpret_cast<const f32x4*>(p), b = *reinterpret_cast<const f32x4*>(p + 4);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    out[e] = a[e];
+    out[4 + e] = b[e];
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(GB_THREADS) void gsta_bwd_kernel(const T* __restrict__ seg, const T* __restrict__ t0,
                                                               const T* __restrict__ wq, const T* __restrict__ wk,
@@ -67,13 +87,19 @@ __global__ __launch_bounds__(GB_THREADS) void gsta_bwd_kernel(const T* __restric
       out[y] = acc;
     }
   };
-  // out[x] (+)= sum_y W[x][y] in[y]: one wave per row, lanes along the row
+  // out[x] (+)= sum_y W[x][y] in[y]: one thread per row, the row read in 16-byte pieces (a wave's 64 rows stay in
+  // the first-level cache from one piece to the next; a wave per row would be a chain of load, wave-wide sum and
+  // store per row, with nothing to overlap it)
   auto row_matvec = [&](float* out, const float* in, const T* W, bool add) {
-    for (int x = wave; x < d; x += GB_THREADS / 64) {
+    for (int x = tid; x < d; x += GB_THREADS) {
       float acc = 0.0f;
-      for (int y = lane; y < d; y += 64) acc = fmaf(load_as_f32(W, (size_t)x * d + y), in[y], acc);
-      acc = wave_sum(acc);
-      if (lane == 0) out[x] = add ? out[x] + acc : acc;
+      for (int y = 0; y < d; y += 8) {
+        float wrow[8];
+        load8_as_f32(W + (size_t)x * d + y, wrow);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc = fmaf(wrow[e], in[y + e], acc);
+      }
+      out[x] = add ? out[x] + acc : acc;
     }
   };
   // q', r, a, p of layer l from its input t_l (the forward pass up to the value projection)
@@ -85,7 +111,7 @@ __global__ __launch_bounds__(GB_THREADS) void gsta_bwd_kernel(const T* __restric
     for (int i = wave; i < nv; i += GB_THREADS / 64) {
       float acc = 0.0f;
       for (int x = lane; x < d; x += 64) acc = fmaf(Hs[i * d + x], rv[x], acc);
-      acc = wave_sum(acc);
+      acc = wave_sum_rows(acc);
       if (lane == 0) av[i] = acc * scale;
     }
     __syncthreads();
@@ -100,7 +126,7 @@ __global__ __launch_bounds__(GB_THREADS) void gsta_bwd_kernel(const T* __restric
         av[i] = ex;
         ssum += ex;
       }
-      ssum = wave_sum(ssum);
+      ssum = wave_sum_rows(ssum);
       if (lane == 0) red[0] = 1.0f / ssum;
     }
     __syncthreads();
@@ -135,14 +161,14 @@ __global__ __launch_bounds__(GB_THREADS) void gsta_bwd_kernel(const T* __restric
     for (int i = wave; i < nv; i += GB_THREADS / 64) {            // da_i = dp . H'_i
       float acc = 0.0f;
       for (int x = lane; x < d; x += 64) acc = fmaf(Hs[i * d + x], dp[x], acc);
-      acc = wave_sum(acc);
+      acc = wave_sum_rows(acc);
       if (lane == 0) da[i] = acc;
     }
     __syncthreads();
     if (wave == 0) {                                              // sum_k a_k da_k
       float acc = 0.0f;
       for (int i = lane; i < nv; i += 64) acc = fmaf(av[i], da[i], acc);
-      acc = wave_sum(acc);
+      acc = wave_sum_rows(acc);
       if (lane == 0) red[1] = acc;
     }
     __syncthreads();

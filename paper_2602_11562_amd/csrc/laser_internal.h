@@ -263,6 +263,16 @@ __device__ __forceinline__ float row_sum(float v) {
 }
 #undef LASER_DPP_ADD
 
+// Sum over the 64 lanes, the same value in every lane: inside each row of 16 lanes with the lane-permute adds, then the
+// four row sums are read into scalar registers and added (six generic shuffles would be six LDS round trips in the
+// middle of every item's dependency chain).
+__device__ __forceinline__ float wave_sum_rows(float x) {
+  x = row_sum<16>(x);
+  const int b = __float_as_int(x);
+  return ((__int_as_float(__builtin_amdgcn_readlane(b, 0)) + __int_as_float(__builtin_amdgcn_readlane(b, 16))) +
+          __int_as_float(__builtin_amdgcn_readlane(b, 32))) + __int_as_float(__builtin_amdgcn_readlane(b, 48));
+}
+
 __device__ __forceinline__ float wave_sum(float x) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);

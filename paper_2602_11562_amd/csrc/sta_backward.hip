@@ -20,16 +20,6 @@ namespace laser {
 constexpr int SB_CMAX = 8;    // candidates per user
 constexpr int SB_TMAX = 4;    // 64-element slices per row: d_q, d <= 256
 
-// Sum over the 64 lanes, the same value in every lane: inside each row of 16 lanes with the lane-permute adds, then the
-// four row sums are read into scalar registers and added (six generic shuffles would be six LDS round trips in the
-// middle of every item's dependency chain).
-__device__ __forceinline__ float wave_sum_rows(float x) {
-  x = row_sum<16>(x);
-  const int b = __float_as_int(x);
-  return ((__int_as_float(__builtin_amdgcn_readlane(b, 0)) + __int_as_float(__builtin_amdgcn_readlane(b, 16))) +
-          __int_as_float(__builtin_amdgcn_readlane(b, 32))) + __int_as_float(__builtin_amdgcn_readlane(b, 48));
-}
-
 template <typename T, int TQ, int TV, int CMAX>   // TQ, TV: 64-element slices of a key / value row; CMAX >= C
 __global__ __launch_bounds__(256) void sta_bwd_kernel(const T* __restrict__ q, const T* __restrict__ k,
                                                       const T* __restrict__ v, const T* __restrict__ dhp,
