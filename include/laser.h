@@ -337,7 +337,7 @@ laser_status laser_sta_backward(const void* q, const void* k, const void* v, con
  * is rounded once to dt. Generic kernels (one workgroup per pair, H' and its gradient in LDS): d <= 256, M <= 8 and
  * (2 S d + (M + 7) d + 2 S) * 4 bytes <= 150 KB; other shapes return LASER_ERR_UNSUPPORTED. work is caller-owned scratch
  * of at least laser_gsta_backward_work_bytes(U, C, d, M) bytes (six d-vectors per pair and layer, whose outer products
- * are the weight gradients); the library allocates nothing.
+ * are the weight gradients, and partial sums of those); the library allocates nothing.
  * All pointers are device pointers, 16-byte aligned (lens 4-byte); outputs are fully overwritten; work is enqueued on
  * `stream`. Errors: LASER_ERR_NULL, LASER_ERR_SHAPE (sizes, work_bytes too small), LASER_ERR_DTYPE, LASER_ERR_ALIGN,
  * LASER_ERR_UNSUPPORTED, LASER_ERR_LAUNCH. Nothing is launched on an error.

@@ -5,7 +5,7 @@
 // The layers' inputs t_l are kept from a first forward sweep; the backward sweep replays a layer's q', r, a, p and
 // applies the chain rule. All three weight gradients of a pair and layer are outer products of d-vectors,
 //   dW_v = p (x) do,   dW_k = dr (x) q',   dW_q = t_l (x) dq',
-// so the pair kernel only writes those six vectors to the caller's scratch, and a second kernel sums the outer
+// so the pair kernel only writes those six vectors to the caller's scratch, and two small kernels sum the outer
 // products over all pairs in a fixed order (deterministic).
 #include "laser_internal.h"
 
@@ -198,26 +198,51 @@ __global__ __launch_bounds__(GB_THREADS) void gsta_bwd_kernel(const T* __restric
   for (int e = tid; e < S * d; e += GB_THREADS) store_from_f32(dH, (size_t)e, e < nv * d ? dHs[e] : 0.0f);
 }
 
-// dW[l][x][y] = sum over pairs of A[pair][l][x] * B[pair][l][y], pairs in ascending order; one thread per (x, y)
-__global__ __launch_bounds__(256) void gsta_bwd_w_kernel(const float* __restrict__ pv, int P, int M, int d,
-                                                         float* __restrict__ dwq, float* __restrict__ dwk,
-                                                         float* __restrict__ dwv) {
+// dW[l][x][y] = sum over pairs of A[pair][l][x] * B[pair][l][y]. Two steps, both in a fixed order: the pairs are cut
+// into chunks, a workgroup sums one chunk for a 16 x 16 tile of one matrix (one thread per entry, pairs ascending),
+// and a second kernel adds the chunks' partial matrices in ascending order.
+__global__ __launch_bounds__(256) void gsta_bwd_w_partial_kernel(const float* __restrict__ pv, int P, int M, int d,
+                                                                 int chunks, float* __restrict__ part) {
   const int tiles = (d + 15) / 16;
   int bid = blockIdx.x;
   const int ty = bid % tiles;
   bid /= tiles;
   const int tx = bid % tiles;
   bid /= tiles;
-  const int which = bid % 3, l = bid / 3;     // 0: dW_v (p, do), 1: dW_k (dr, q'), 2: dW_q (t_l, dq')
+  const int which = bid % 3;     // 0: dW_v (p, do), 1: dW_k (dr, q'), 2: dW_q (t_l, dq')
+  bid /= 3;
+  const int l = bid % M, chunk = bid / M;
   const int x = tx * 16 + threadIdx.x / 16, y = ty * 16 + threadIdx.x % 16;
   if (x >= d || y >= d) return;
+  const int per = (P + chunks - 1) / chunks;
+  const int p0 = chunk * per, p1 = (p0 + per) < P ? (p0 + per) : P;
   const float* a = pv + ((size_t)l * 6 + 2 * which) * d + x;
   const float* b = pv + ((size_t)l * 6 + 2 * which + 1) * d + y;
   const size_t stride = (size_t)M * 6 * d;
   float acc = 0.0f;
-  for (int p = 0; p < P; ++p) acc = fmaf(a[p * stride], b[p * stride], acc);
+  for (int p = p0; p < p1; ++p) acc = fmaf(a[p * stride], b[p * stride], acc);
+  part[((((size_t)chunk * M + l) * 3 + which) * d + x) * d + y] = acc;
+}
+
+__global__ __launch_bounds__(256) void gsta_bwd_w_reduce_kernel(const float* __restrict__ part, int M, int d, int chunks,
+                                                                float* __restrict__ dwq, float* __restrict__ dwk,
+                                                                float* __restrict__ dwv) {
+  const long long per_l = (long long)3 * d * d, total = (long long)M * per_l;
+  const long long e = (long long)blockIdx.x * 256 + threadIdx.x;     // (l, which, x, y)
+  if (e >= total) return;
+  float acc = 0.0f;
+  for (int c = 0; c < chunks; ++c) acc += part[(size_t)c * total + e];
+  const int l = (int)(e / per_l);
+  const long long r = e - (long long)l * per_l;
+  const int which = (int)(r / ((long long)d * d));
+  const long long xy = r - (long long)which * d * d;
   float* out = which == 0 ? dwv : (which == 1 ? dwk : dwq);
-  out[((size_t)l * d + x) * d + y] = acc;
+  out[(size_t)l * d * d + xy] = acc;
+}
+
+static int gsta_bwd_chunks(int P) {
+  int c = (P + 63) / 64;
+  return c < 1 ? 1 : (c > 32 ? 32 : c);
 }
 
 static size_t gsta_bwd_lds(const GstaBwdArgs& a) {
@@ -228,7 +253,11 @@ bool gsta_backward_supports(const GstaBwdArgs& a) {
   return a.d <= GB_MAXD && a.M <= GB_MAXM && gsta_bwd_lds(a) <= 150 * 1024;
 }
 
-size_t gsta_backward_work_bytes(int U, int C, int d, int M) { return (size_t)U * C * M * 6 * d * sizeof(float); }
+// per-pair vectors [P][M][6][d], then the chunks' partial weight gradients [chunks][M][3][d][d]
+size_t gsta_backward_work_bytes(int U, int C, int d, int M) {
+  const size_t P = (size_t)U * C;
+  return (P * M * 6 * d + (size_t)gsta_bwd_chunks((int)P) * M * 3 * d * d) * sizeof(float);
+}
 
 laser_status gsta_backward_launch(const GstaBwdArgs& a) {
   if (!gsta_backward_supports(a)) return LASER_ERR_UNSUPPORTED;
@@ -253,9 +282,14 @@ laser_status gsta_backward_launch(const GstaBwdArgs& a) {
                        a.L, a.d, a.w, a.S, a.M, (float*)a.dseg, a.dt0, a.work);
   }
   if (launch_status() != LASER_OK) return LASER_ERR_LAUNCH;
-  const int tiles = (a.d + 15) / 16;
-  hipLaunchKernelGGL(gsta_bwd_w_kernel, dim3((unsigned)(a.M * 3 * tiles * tiles)), dim3(256), 0, a.stream, a.work, P,
-                     a.M, a.d, a.dwq, a.dwk, a.dwv);
+  const int tiles = (a.d + 15) / 16, chunks = gsta_bwd_chunks(P);
+  float* part = a.work + (size_t)P * a.M * 6 * a.d;
+  hipLaunchKernelGGL(gsta_bwd_w_partial_kernel, dim3((unsigned)(chunks * a.M * 3 * tiles * tiles)), dim3(256), 0,
+                     a.stream, a.work, P, a.M, a.d, chunks, part);
+  if (launch_status() != LASER_OK) return LASER_ERR_LAUNCH;
+  const long long total = (long long)a.M * 3 * a.d * a.d;
+  hipLaunchKernelGGL(gsta_bwd_w_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, a.stream, part, a.M,
+                     a.d, chunks, a.dwq, a.dwk, a.dwv);
   return launch_status();
 }
 
