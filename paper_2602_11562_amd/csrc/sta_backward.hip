@@ -113,9 +113,14 @@ __global__ __launch_bounds__(256) void sta_bwd_kernel(const T* __restrict__ q, c
       }
     }
     // items of the segment at or past the valid length: zero gradients
+    // (16 bytes per lane: rows are multiples of eight elements and the outputs 16-byte aligned)
     const int z0 = hi > lo ? hi : lo;
-    for (int e = lane; e < (hi_all - z0) * dq; e += 64) dkU[(size_t)z0 * dq + e] = 0.0f;
-    for (int e = lane; e < (hi_all - z0) * d; e += 64) dvU[(size_t)z0 * d + e] = 0.0f;
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    const f32x4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+    f32x4* zk = reinterpret_cast<f32x4*>(dkU + (size_t)z0 * dq);
+    f32x4* zv = reinterpret_cast<f32x4*>(dvU + (size_t)z0 * d);
+    for (int e = lane; e < (hi_all - z0) * dq / 4; e += 64) __builtin_nontemporal_store(zero4, zk + e);
+    for (int e = lane; e < (hi_all - z0) * d / 4; e += 64) __builtin_nontemporal_store(zero4, zv + e);
   }
   // dq of the run: waves in a fixed order
 #pragma unroll
@@ -128,6 +133,196 @@ __global__ __launch_bounds__(256) void sta_bwd_kernel(const T* __restrict__ q, c
   for (int e = tid; e < C * dq; e += 256)
     dq_part[((size_t)u * groups + grp) * C * dq + e] =
         ((red[e] + red[C * dq + e]) + red[2 * C * dq + e]) + red[3 * C * dq + e];
+}
+
+// The same computation in the lane layout of the forward streaming kernels, for bf16 storage and the usual widths:
+// a key row is spread over d_q / 8 lanes and a value row over d / 8 lanes (16 bytes each), so one wave-wide load
+// brings several items, and every instruction below works on 4 to 16 items at once instead of one. The two dot
+// products of an (item, candidate) live on different lanes when the widths differ (the score on the key lanes, the
+// product dH' . v on the value lanes), and each side needs the other's result (the value lanes the gate, the key
+// lanes ds): they change sides through a wave-private LDS patch (LDS operations of a wave execute in order).
+typedef unsigned int u32x4b __attribute__((ext_vector_type(4)));
+typedef float f32x4b __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void unpack8b(const u32x4b& r, float (&x)[8]) {
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    x[2 * e] = __uint_as_float(r[e] << 16);
+    x[2 * e + 1] = __uint_as_float(r[e] & 0xffff0000u);
+  }
+}
+
+template <int DQ, int D, int CMAX>
+__global__ __launch_bounds__(256) void sta_bwd_wide_kernel(const unsigned short* __restrict__ q,
+                                                           const unsigned short* __restrict__ k,
+                                                           const unsigned short* __restrict__ v,
+                                                           const unsigned short* __restrict__ dhp,
+                                                           const int32_t* __restrict__ lens, int C, int L, int w, int S,
+                                                           int spg, int groups, float neg_scale_log2e, float inv_gamma,
+                                                           float* __restrict__ dk, float* __restrict__ dv,
+                                                           float* __restrict__ dq_part) {
+  constexpr int LQ = DQ / 8, LV = D / 8;           // lanes per key row / value row
+  constexpr int RQ = 64 / LQ, RV = 64 / LV;        // rows per wave-wide load
+  constexpr int IPC = RQ > RV ? RQ : RV;           // items per chunk
+  constexpr int NKL = IPC / RQ, NVL = IPC / RV;    // loads per chunk
+  constexpr bool SAME = (LQ == LV);
+  __shared__ float xg[4][CMAX][IPC];               // gate per item, key lanes -> value lanes
+  __shared__ float xd[4][CMAX][IPC];               // dH' . v per item, value lanes -> key lanes
+  __shared__ float red[4][CMAX][DQ];
+
+  const int u = blockIdx.x / groups, grp = blockIdx.x % groups;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = __builtin_amdgcn_readfirstlane(valid_len(lens, u, L));
+  const int rq = lane / LQ, cq = lane % LQ;
+  const int rv = lane / LV, cv = lane % LV;
+  const int i_beg = grp * spg;
+  const int i_end = (grp + 1) * spg < S ? (grp + 1) * spg : S;
+  const unsigned short* kU = k + (size_t)u * L * DQ;
+  const unsigned short* vU = v + (size_t)u * L * D;
+  float* dkU = dk + (size_t)u * L * DQ;
+  float* dvU = dv + (size_t)u * L * D;
+
+  float qf[CMAX][8], dqacc[CMAX][8];
+#pragma unroll
+  for (int c = 0; c < CMAX; ++c) {
+    u32x4b raw = {0u, 0u, 0u, 0u};
+    if (c < C) raw = *reinterpret_cast<const u32x4b*>(q + ((size_t)u * C + c) * DQ + cq * 8);
+    unpack8b(raw, qf[c]);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dqacc[c][e] = 0.0f;
+  }
+
+  for (int i = i_beg + wave; i < i_end; i += 4) {   // a wave owns whole segments
+    const int lo = i * w;
+    int hi_all = lo + w;
+    if (hi_all > L) hi_all = L;
+    const int hi = hi_all < n ? hi_all : n;          // valid items of the segment: [lo, hi)
+    if (hi > lo) {
+      float dh[CMAX][8];                             // this lane's piece of the segment's upstream gradient rows
+#pragma unroll
+      for (int c = 0; c < CMAX; ++c) {
+        u32x4b raw = {0u, 0u, 0u, 0u};
+        if (c < C) raw = *reinterpret_cast<const u32x4b*>(dhp + (((size_t)u * C + c) * S + i) * D + cv * 8);
+        unpack8b(raw, dh[c]);
+      }
+      u32x4b kn[NKL], vn[NVL];
+      // rows at or past the end of the segment are read from its last valid row and take no part (zero gate)
+      auto load_chunk = [&](int base) {
+#pragma unroll
+        for (int kl = 0; kl < NKL; ++kl) {
+          int row = base + kl * RQ + rq;
+          row = row < hi ? row : hi - 1;
+          kn[kl] = *reinterpret_cast<const u32x4b*>(kU + (size_t)row * DQ + cq * 8);
+        }
+#pragma unroll
+        for (int vl = 0; vl < NVL; ++vl) {
+          int row = base + vl * RV + rv;
+          row = row < hi ? row : hi - 1;
+          vn[vl] = *reinterpret_cast<const u32x4b*>(vU + (size_t)row * D + cv * 8);
+        }
+      };
+      load_chunk(lo);
+      for (int base = lo; base < hi; base += IPC) {
+        float kf[NKL][8], vf[NVL][8], dka[NKL][8], dva[NVL][8];
+#pragma unroll
+        for (int kl = 0; kl < NKL; ++kl) {
+          unpack8b(kn[kl], kf[kl]);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) dka[kl][e] = 0.0f;
+        }
+#pragma unroll
+        for (int vl = 0; vl < NVL; ++vl) {
+          unpack8b(vn[vl], vf[vl]);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) dva[vl][e] = 0.0f;
+        }
+        if (base + IPC < hi) load_chunk(base + IPC);   // the next chunk is on its way during the arithmetic
+#pragma unroll
+        for (int c = 0; c < CMAX; ++c) {
+          if (c < C) {
+            float dots[NVL];
+#pragma unroll
+            for (int vl = 0; vl < NVL; ++vl) {         // value lanes: dH' . v of the lane's row
+              float t = 0.0f;
+#pragma unroll
+              for (int e = 0; e < 8; ++e) t = fmaf(vf[vl][e], dh[c][e], t);
+              dots[vl] = row_sum<LV>(t);
+              if (!SAME && cv == 0) xd[wave][c][vl * RV + rv] = dots[vl];
+            }
+            float gates[NKL];
+#pragma unroll
+            for (int kl = 0; kl < NKL; ++kl) {         // key lanes: score, gate, ds; dk and dq
+              float sc = 0.0f;
+#pragma unroll
+              for (int e = 0; e < 8; ++e) sc = fmaf(kf[kl][e], qf[c][e], sc);
+              sc = row_sum<LQ>(sc);
+              const bool ok = (base + kl * RQ + rq) < hi;
+              const float g = ok ? __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(sc * neg_scale_log2e)) : 0.0f;
+              gates[kl] = g;
+              const float dot = SAME ? dots[kl < NVL ? kl : 0] : xd[wave][c][kl * RQ + rq];
+              const float ds = dot * g * (1.0f - g) * inv_gamma;
+#pragma unroll
+              for (int e = 0; e < 8; ++e) {
+                dka[kl][e] = fmaf(ds, qf[c][e], dka[kl][e]);
+                dqacc[c][e] = fmaf(ds, kf[kl][e], dqacc[c][e]);
+              }
+              if (!SAME && cq == 0) xg[wave][c][kl * RQ + rq] = g;
+            }
+#pragma unroll
+            for (int vl = 0; vl < NVL; ++vl) {         // value lanes: dv
+              const float g = SAME ? gates[vl < NKL ? vl : 0] : xg[wave][c][vl * RV + rv];
+#pragma unroll
+              for (int e = 0; e < 8; ++e) dva[vl][e] = fmaf(g, dh[c][e], dva[vl][e]);
+            }
+          }
+        }
+#pragma unroll
+        for (int kl = 0; kl < NKL; ++kl) {
+          const int row = base + kl * RQ + rq;
+          if (row < hi) {
+            f32x4b* dst = reinterpret_cast<f32x4b*>(dkU + (size_t)row * DQ + cq * 8);
+            dst[0] = f32x4b{dka[kl][0], dka[kl][1], dka[kl][2], dka[kl][3]};
+            dst[1] = f32x4b{dka[kl][4], dka[kl][5], dka[kl][6], dka[kl][7]};
+          }
+        }
+#pragma unroll
+        for (int vl = 0; vl < NVL; ++vl) {
+          const int row = base + vl * RV + rv;
+          if (row < hi) {
+            f32x4b* dst = reinterpret_cast<f32x4b*>(dvU + (size_t)row * D + cv * 8);
+            dst[0] = f32x4b{dva[vl][0], dva[vl][1], dva[vl][2], dva[vl][3]};
+            dst[1] = f32x4b{dva[vl][4], dva[vl][5], dva[vl][6], dva[vl][7]};
+          }
+        }
+      }
+    }
+    // items of the segment at or past the valid length: zero gradients
+    const int z0 = hi > lo ? hi : lo;
+    const f32x4b zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+    f32x4b* zk = reinterpret_cast<f32x4b*>(dkU + (size_t)z0 * DQ);
+    f32x4b* zv = reinterpret_cast<f32x4b*>(dvU + (size_t)z0 * D);
+    for (int e = lane; e < (hi_all - z0) * DQ / 4; e += 64) __builtin_nontemporal_store(zero4, zk + e);
+    for (int e = lane; e < (hi_all - z0) * D / 4; e += 64) __builtin_nontemporal_store(zero4, zv + e);
+  }
+  // dq of the run: the row groups of a wave, then the waves, in a fixed order
+#pragma unroll
+  for (int c = 0; c < CMAX; ++c)
+    if (c < C) {
+#pragma unroll
+      for (int off = LQ; off < 64; off <<= 1)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dqacc[c][e] += __shfl_xor(dqacc[c][e], off, 64);
+      if (rq == 0)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) red[wave][c][cq * 8 + e] = dqacc[c][e];
+    }
+  __syncthreads();
+  for (int e = tid; e < C * DQ; e += 256) {
+    const int c = e / DQ, col = e - c * DQ;
+    dq_part[((size_t)u * groups + grp) * C * DQ + e] =
+        ((red[0][c][col] + red[1][c][col]) + red[2][c][col]) + red[3][c][col];
+  }
 }
 
 __global__ __launch_bounds__(256) void sta_bwd_dq_kernel(const float* __restrict__ dq_part, int groups, int row,
@@ -195,6 +390,26 @@ static void sta_bwd_launch_q(const StaBwdArgs& a, unsigned blocks, size_t lds, i
   else sta_bwd_launch_v<T, 4>(a, blocks, lds, spg, groups);
 }
 
+static bool sta_bwd_wide_supports(const StaBwdArgs& a) {
+  return a.dt == LASER_BF16 && a.C <= 4 && (a.d_q == 32 || a.d_q == 64 || a.d_q == 128) && (a.d == 64 || a.d == 128) &&
+         getenv("LASER_BWD_NARROW") == nullptr;   // tuning override: the one-item-per-wave kernel for every shape
+}
+
+template <int DQ, int D>
+static void sta_bwd_wide_launch(const StaBwdArgs& a, unsigned blocks, int spg, int groups) {
+  const float inv_gamma = 1.0f / a.gamma;
+  const float nsl = -1.4426950408889634f * inv_gamma;
+#define LASER_BWD_WIDE(CM)                                                                                           \
+  hipLaunchKernelGGL((sta_bwd_wide_kernel<DQ, D, CM>), dim3(blocks), dim3(256), 0, a.stream,                        \
+                     (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v,            \
+                     (const unsigned short*)a.dhp, a.lens, a.C, a.L, a.w, a.S, spg, groups, nsl, inv_gamma, a.dk,   \
+                     a.dv, a.work)
+  if (a.C <= 1) LASER_BWD_WIDE(1);
+  else if (a.C <= 2) LASER_BWD_WIDE(2);
+  else LASER_BWD_WIDE(4);
+#undef LASER_BWD_WIDE
+}
+
 laser_status sta_backward_launch(const StaBwdArgs& a) {
   if (!sta_backward_supports(a)) return LASER_ERR_UNSUPPORTED;
   int spg, groups;
@@ -202,7 +417,17 @@ laser_status sta_backward_launch(const StaBwdArgs& a) {
   const long long blocks = (long long)a.U * groups;
   if (blocks > 0x7fffffffLL) return LASER_ERR_SHAPE;
   const size_t lds = sizeof(float) * (size_t)a.C * a.d_q * 4;
-  if (a.dt == LASER_BF16) sta_bwd_launch_q<unsigned short>(a, (unsigned)blocks, lds, spg, groups);
+  if (sta_bwd_wide_supports(a)) {
+    const unsigned nb = (unsigned)blocks;
+    switch (a.d_q * 1000 + a.d) {
+      case 32064: sta_bwd_wide_launch<32, 64>(a, nb, spg, groups); break;
+      case 32128: sta_bwd_wide_launch<32, 128>(a, nb, spg, groups); break;
+      case 64064: sta_bwd_wide_launch<64, 64>(a, nb, spg, groups); break;
+      case 64128: sta_bwd_wide_launch<64, 128>(a, nb, spg, groups); break;
+      case 128064: sta_bwd_wide_launch<128, 64>(a, nb, spg, groups); break;
+      default: sta_bwd_wide_launch<128, 128>(a, nb, spg, groups); break;
+    }
+  } else if (a.dt == LASER_BF16) sta_bwd_launch_q<unsigned short>(a, (unsigned)blocks, lds, spg, groups);
   else sta_bwd_launch_q<float>(a, (unsigned)blocks, lds, spg, groups);
   if (launch_status() != LASER_OK) return LASER_ERR_LAUNCH;
   const long long total = (long long)a.U * a.C * a.d_q;

@@ -27,6 +27,9 @@ CASES = {
     "eight_candidates": ("bf16", 8, 300, 64, 64, 64, [300, 65, 64]),
     "wide_rows": ("bf16", 2, 520, 256, 256, 128, [520, 129]),
     "one_user_many_runs": ("bf16", 1, 4096, 64, 64, 64, [3000]),
+    "three_candidates_wide_keys": ("bf16", 3, 333, 128, 64, 20, [333, 21, 20, 1]),
+    "two_candidates_same_widths": ("bf16", 2, 700, 128, 128, 64, [700, 65, 64]),
+    "four_candidates_narrow_keys": ("bf16", 4, 1500, 64, 128, 300, [1500, 301]),
     "odd_widths_f32": ("f32", 3, 130, 24, 48, 16, [130, 50]),
     "f32_paper_setting": ("f32", 1, 200, 32, 128, 10, [200, 33, 0]),
 }
