@@ -135,6 +135,15 @@ def paper_setting_chain(laser, torch, event_time):
                        device="cuda")
     bwd_ms = event_time(lambda i: laser.laser_sta_backward(Q, K, V, lens, dseg, w, gamma, dq_out=gq, dk_out=gk,
                                                            dv_out=gv, work=work))
+    t0p = rnd(U, C, d).bfloat16()
+    gw3 = [(rnd(1, d, d) / math.sqrt(d)).bfloat16() for _ in range(3)]
+    zp = torch.empty(U, C, d, device="cuda")
+    dzp = rnd(U, C, d)
+    gwork = torch.empty(max(16, laser.load_library().laser_gsta_backward_work_bytes(U, C, d, 1)), dtype=torch.uint8,
+                        device="cuda")
+    laser.laser_sta_forward(Q, K, V, lens, w, gamma, seg_out=seg, want_cnt=False, heads=heads)
+    gsta_ms = event_time(lambda i: laser.laser_gsta_forward(seg, t0p, *gw3, lens, L, w, z_out=zp))
+    gsta_bwd_ms = event_time(lambda i: laser.laser_gsta_backward(seg, t0p, *gw3, lens, dzp, L, w, work=gwork))
     direct_ms, folded_ms = event_time(direct), event_time(folded)
     same = float((seg.float() - 0).abs().max())   # keeps the last result alive until here
     nvalid = int(lens.sum())
@@ -147,6 +156,7 @@ def paper_setting_chain(laser, torch, event_time):
             "direct_frac_of_hbm_peak": alg_b / (direct_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
             "pairs_per_s_folded": U * C / (folded_ms * 1e-3), "max_abs_out": same,
             # backward of STA: valid K and V rows and dH' read once (bf16), dk and dv written once (fp32, every row)
+            "gsta_forward_ms": gsta_ms, "gsta_backward_ms": gsta_bwd_ms,
             "sta_backward_ms": bwd_ms,
             "sta_backward_algorithmic_bytes": nvalid * (dq + d) * 2 + U * C * S * d * 2 + U * L * (dq + d) * 4,
             "sta_backward_frac_of_hbm_peak": (nvalid * (dq + d) * 2 + U * C * S * d * 2 + U * L * (dq + d) * 4)

@@ -45,9 +45,12 @@ __global__ __launch_bounds__(GB_THREADS) void gsta_bwd_kernel(const T* __restric
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nv = (valid_len(lens, u, L) + w - 1) / w;     // valid segments are a prefix
+  // With one layer the gradient of H' is written straight from the layer's vectors at the end, and its block is
+  // not kept: less LDS, more workgroups per compute unit.
+  const bool keep = M > 1;
   float* Hs = sm;                    // [nv][d]
-  float* dHs = Hs + (size_t)nv * d;  // [nv][d]
-  float* ts = dHs + (size_t)nv * d;  // [M][d]  t_0 .. t_{M-1}
+  float* dHs = Hs + (size_t)nv * d;  // [nv][d] (several layers only)
+  float* ts = dHs + (keep ? (size_t)nv * d : 0);  // [M][d]  t_0 .. t_{M-1}
   float* qp = ts + M * d;            // the seven vectors below: [d] each
   float* rv = qp + d;
   float* pvv = rv + d;
@@ -58,14 +61,20 @@ __global__ __launch_bounds__(GB_THREADS) void gsta_bwd_kernel(const T* __restric
   float* av = dqp + d;               // [S] softmax weights
   float* da = av + S;                // [S]
   __shared__ float red[4];
+  __shared__ float halves[GB_THREADS / 2];
   const float scale = 1.0f / sqrtf((float)d);
   const T* H = seg + (size_t)pair * S * d;
   T* dH = dseg + (size_t)pair * S * d;
   float* pvp = pv + (size_t)pair * M * 6 * d;
 
-  for (int e = tid; e < nv * d; e += GB_THREADS) {
-    Hs[e] = load_as_f32(H, (size_t)e);
-    dHs[e] = 0.0f;
+  for (int e = tid * 8; e < nv * d; e += GB_THREADS * 8) {   // d is a multiple of eight: 16 or 32 bytes per load
+    float h8[8];
+    load8_as_f32(H + e, h8);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      Hs[e + j] = h8[j];
+      if (keep) dHs[e + j] = 0.0f;
+    }
   }
   for (int e = tid; e < d; e += GB_THREADS) {
     ts[e] = load_as_f32(t0, (size_t)pair * d + e);
@@ -80,7 +89,19 @@ __global__ __launch_bounds__(GB_THREADS) void gsta_bwd_kernel(const T* __restric
   }
 
   // out[y] = sum_x in[x] W[x][y]: one thread per column, coalesced over y
+  // (with d <= 128 the two halves of the workgroup take the two halves of x and meet in LDS)
   auto col_matvec = [&](float* out, const float* in, const T* W) {
+    if (d <= GB_THREADS / 2) {
+      const int half = tid / (GB_THREADS / 2), y = tid % (GB_THREADS / 2);
+      const int x0 = half * (d / 2), x1 = half ? d : d / 2;
+      float acc = 0.0f;
+      if (y < d)
+        for (int x = x0; x < x1; ++x) acc = fmaf(in[x], load_as_f32(W, (size_t)x * d + y), acc);
+      if (half == 1 && y < d) halves[y] = acc;
+      __syncthreads();
+      if (half == 0 && y < d) out[y] = acc + halves[y];
+      return;
+    }
     for (int y = tid; y < d; y += GB_THREADS) {
       float acc = 0.0f;
       for (int x = 0; x < d; ++x) acc = fmaf(in[x], load_as_f32(W, (size_t)x * d + y), acc);
@@ -175,7 +196,9 @@ __global__ __launch_bounds__(GB_THREADS) void gsta_bwd_kernel(const T* __restric
     for (int e = tid; e < nv * d; e += GB_THREADS) {              // dH'_i += a_i dp + de_i r / sqrt(d)
       const int i = e / d, x = e - i * d;
       const float de = av[i] * (da[i] - red[1]);
-      dHs[e] += av[i] * dp[x] + de * rv[x] * scale;
+      const float val = av[i] * dp[x] + de * rv[x] * scale;
+      if (keep) dHs[e] += val;
+      else store_from_f32(dH, (size_t)e, val);
     }
     for (int x = tid; x < d; x += GB_THREADS) {                   // dr = sum_i de_i H'_i / sqrt(d)
       float acc = 0.0f;
@@ -195,15 +218,21 @@ __global__ __launch_bounds__(GB_THREADS) void gsta_bwd_kernel(const T* __restric
     __syncthreads();
   }
   for (int e = tid; e < d; e += GB_THREADS) dt0[(size_t)pair * d + e] = g[e];
-  for (int e = tid; e < S * d; e += GB_THREADS) store_from_f32(dH, (size_t)e, e < nv * d ? dHs[e] : 0.0f);
+  if (keep)
+    for (int e = tid; e < nv * d; e += GB_THREADS) store_from_f32(dH, (size_t)e, dHs[e]);
+  for (int e = nv * d + tid; e < S * d; e += GB_THREADS) store_from_f32(dH, (size_t)e, 0.0f);
 }
 
 // dW[l][x][y] = sum over pairs of A[pair][l][x] * B[pair][l][y]. Two steps, both in a fixed order: the pairs are cut
-// into chunks, a workgroup sums one chunk for a 16 x 16 tile of one matrix (one thread per entry, pairs ascending),
-// and a second kernel adds the chunks' partial matrices in ascending order.
+// into chunks, a workgroup sums one chunk for a 32 x 32 tile of one matrix (pairs ascending), and a second kernel adds
+// the chunks' partial matrices in ascending order.
 __global__ __launch_bounds__(256) void gsta_bwd_w_partial_kernel(const float* __restrict__ pv, int P, int M, int d,
                                                                  int chunks, float* __restrict__ part) {
-  const int tiles = (d + 15) / 16;
+  // a 32 x 32 tile of one matrix per workgroup, 2 x 2 entries per thread; the two vectors of 64 pairs at a time are
+  // staged in LDS (32 consecutive floats of each), so every global load is a 32-byte piece and is used 32 times
+  constexpr int TP = 64, TW = 32;
+  __shared__ float As[TP][TW + 1], Bs[TP][TW + 1];
+  const int tiles = (d + TW - 1) / TW;
   int bid = blockIdx.x;
   const int ty = bid % tiles;
   bid /= tiles;
@@ -212,16 +241,40 @@ __global__ __launch_bounds__(256) void gsta_bwd_w_partial_kernel(const float* __
   const int which = bid % 3;     // 0: dW_v (p, do), 1: dW_k (dr, q'), 2: dW_q (t_l, dq')
   bid /= 3;
   const int l = bid % M, chunk = bid / M;
-  const int x = tx * 16 + threadIdx.x / 16, y = ty * 16 + threadIdx.x % 16;
-  if (x >= d || y >= d) return;
+  const int tid = threadIdx.x, r = tid / 16, c = tid % 16;
   const int per = (P + chunks - 1) / chunks;
   const int p0 = chunk * per, p1 = (p0 + per) < P ? (p0 + per) : P;
-  const float* a = pv + ((size_t)l * 6 + 2 * which) * d + x;
-  const float* b = pv + ((size_t)l * 6 + 2 * which + 1) * d + y;
+  const float* a = pv + ((size_t)l * 6 + 2 * which) * d + tx * TW;
+  const float* b = pv + ((size_t)l * 6 + 2 * which + 1) * d + ty * TW;
   const size_t stride = (size_t)M * 6 * d;
-  float acc = 0.0f;
-  for (int p = p0; p < p1; ++p) acc = fmaf(a[p * stride], b[p * stride], acc);
-  part[((((size_t)chunk * M + l) * 3 + which) * d + x) * d + y] = acc;
+  const int spr = tid / 4, sc = (tid % 4) * 8;   // staging: pair row and first of this thread's eight columns
+  float acc[2][2] = {{0.0f, 0.0f}, {0.0f, 0.0f}};
+  for (int pb = p0; pb < p1; pb += TP) {
+    const int pr = pb + spr;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const bool oka = pr < p1 && tx * TW + sc + e < d, okb = pr < p1 && ty * TW + sc + e < d;
+      As[spr][sc + e] = oka ? a[(size_t)pr * stride + sc + e] : 0.0f;
+      Bs[spr][sc + e] = okb ? b[(size_t)pr * stride + sc + e] : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll 8
+    for (int pp = 0; pp < TP; ++pp) {   // pairs in ascending order (rows past the chunk hold zeros)
+      const float a0 = As[pp][2 * r], a1 = As[pp][2 * r + 1], b0 = Bs[pp][2 * c], b1 = Bs[pp][2 * c + 1];
+      acc[0][0] = fmaf(a0, b0, acc[0][0]);
+      acc[0][1] = fmaf(a0, b1, acc[0][1]);
+      acc[1][0] = fmaf(a1, b0, acc[1][0]);
+      acc[1][1] = fmaf(a1, b1, acc[1][1]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int jx = 0; jx < 2; ++jx) {
+      const int x = tx * TW + 2 * r + i, y = ty * TW + 2 * c + jx;
+      if (x < d && y < d) part[((((size_t)chunk * M + l) * 3 + which) * d + x) * d + y] = acc[i][jx];
+    }
 }
 
 __global__ __launch_bounds__(256) void gsta_bwd_w_reduce_kernel(const float* __restrict__ part, int M, int d, int chunks,
@@ -246,7 +299,8 @@ static int gsta_bwd_chunks(int P) {
 }
 
 static size_t gsta_bwd_lds(const GstaBwdArgs& a) {
-  return sizeof(float) * (2 * (size_t)a.S * a.d + (size_t)(a.M + 7) * a.d + 2 * (size_t)a.S);
+  const size_t blocks = a.M > 1 ? 2 : 1;   // H', and its gradient when several layers add to it
+  return sizeof(float) * (blocks * (size_t)a.S * a.d + (size_t)(a.M + 7) * a.d + 2 * (size_t)a.S);
 }
 
 bool gsta_backward_supports(const GstaBwdArgs& a) {
@@ -282,7 +336,7 @@ laser_status gsta_backward_launch(const GstaBwdArgs& a) {
                        a.L, a.d, a.w, a.S, a.M, (float*)a.dseg, a.dt0, a.work);
   }
   if (launch_status() != LASER_OK) return LASER_ERR_LAUNCH;
-  const int tiles = (a.d + 15) / 16, chunks = gsta_bwd_chunks(P);
+  const int tiles = (a.d + 31) / 32, chunks = gsta_bwd_chunks(P);
   float* part = a.work + (size_t)P * a.M * 6 * a.d;
   hipLaunchKernelGGL(gsta_bwd_w_partial_kernel, dim3((unsigned)(chunks * a.M * 3 * tiles * tiles)), dim3(256), 0,
                      a.stream, a.work, P, a.M, a.d, chunks, part);
