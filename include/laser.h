@@ -335,7 +335,7 @@ laser_status laser_sta_backward(const void* q, const void* k, const void* v, con
  *   dwq_out, dwk_out, dwv_out [M,d,d] fp32, summed over all pairs in a fixed order
  * seg, t0, wq, wk, wv, lens and the sizes as for laser_gsta_forward. Arithmetic in fp32 from the stored inputs; dseg_out
  * is rounded once to dt. Generic kernels (one workgroup per pair, H' and, with several layers, its gradient in LDS): d <= 256,
- * M <= 8 and ((M > 1 ? 2 : 1) S d + (M + 7) d + 2 S) * 4 bytes <= 150 KB; other shapes return LASER_ERR_UNSUPPORTED. work is caller-owned scratch
+ * M <= 8 and S d sizeof(dt) + ((M > 1 ? S d : 0) + (M + 7) d + 2 S + 4) * 4 bytes <= 150 KB; other shapes return LASER_ERR_UNSUPPORTED. work is caller-owned scratch
  * of at least laser_gsta_backward_work_bytes(U, C, d, M) bytes (six d-vectors per pair and layer, whose outer products
  * are the weight gradients, and partial sums of those); the library allocates nothing.
  * All pointers are device pointers, 16-byte aligned (lens 4-byte); outputs are fully overwritten; work is enqueued on

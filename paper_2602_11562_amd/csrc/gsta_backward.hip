@@ -48,8 +48,9 @@ __global__ __launch_bounds__(GB_THREADS) void gsta_bwd_kernel(const T* __restric
   // With one layer the gradient of H' is written straight from the layer's vectors at the end, and its block is
   // not kept: less LDS, more workgroups per compute unit.
   const bool keep = M > 1;
-  float* Hs = sm;                    // [nv][d]
-  float* dHs = Hs + (size_t)nv * d;  // [nv][d] (several layers only)
+  // H' stays in LDS in its storage type (half the space for bf16: more workgroups per compute unit, and the pair
+  // kernel is a chain of short phases that only other workgroups can overlap)
+  float* dHs = sm;                                // [nv][d] (several layers only)
   float* ts = dHs + (keep ? (size_t)nv * d : 0);  // [M][d]  t_0 .. t_{M-1}
   float* qp = ts + M * d;            // the seven vectors below: [d] each
   float* rv = qp + d;
@@ -60,6 +61,7 @@ __global__ __launch_bounds__(GB_THREADS) void gsta_bwd_kernel(const T* __restric
   float* dqp = drv + d;
   float* av = dqp + d;               // [S] softmax weights
   float* da = av + S;                // [S]
+  T* Hs = reinterpret_cast<T*>(da + S + ((2 * S) & 3));   // [nv][d]; the two [S] arrays are padded to 16 bytes
   __shared__ float red[4];
   __shared__ float halves[GB_THREADS / 2];
   const float scale = 1.0f / sqrtf((float)d);
@@ -67,12 +69,10 @@ __global__ __launch_bounds__(GB_THREADS) void gsta_bwd_kernel(const T* __restric
   T* dH = dseg + (size_t)pair * S * d;
   float* pvp = pv + (size_t)pair * M * 6 * d;
 
-  for (int e = tid * 8; e < nv * d; e += GB_THREADS * 8) {   // d is a multiple of eight: 16 or 32 bytes per load
-    float h8[8];
-    load8_as_f32(H + e, h8);
+  for (int e = tid * 8; e < nv * d; e += GB_THREADS * 8) {   // d is a multiple of eight
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      Hs[e + j] = h8[j];
+      Hs[e + j] = H[e + j];
       if (keep) dHs[e + j] = 0.0f;
     }
   }
@@ -131,7 +131,7 @@ __global__ __launch_bounds__(GB_THREADS) void gsta_bwd_kernel(const T* __restric
     __syncthreads();
     for (int i = wave; i < nv; i += GB_THREADS / 64) {
       float acc = 0.0f;
-      for (int x = lane; x < d; x += 64) acc = fmaf(Hs[i * d + x], rv[x], acc);
+      for (int x = lane; x < d; x += 64) acc = fmaf(load_as_f32(Hs, (size_t)(i * d + x)), rv[x], acc);
       acc = wave_sum_rows(acc);
       if (lane == 0) av[i] = acc * scale;
     }
@@ -155,7 +155,7 @@ __global__ __launch_bounds__(GB_THREADS) void gsta_bwd_kernel(const T* __restric
     __syncthreads();
     for (int x = tid; x < d; x += GB_THREADS) {
       float acc = 0.0f;
-      for (int i = 0; i < nv; ++i) acc = fmaf(av[i], Hs[i * d + x], acc);
+      for (int i = 0; i < nv; ++i) acc = fmaf(av[i], load_as_f32(Hs, (size_t)(i * d + x)), acc);
       pvv[x] = acc;
     }
     __syncthreads();
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(GB_THREADS) void gsta_bwd_kernel(const T* __restric
     __syncthreads();
     for (int i = wave; i < nv; i += GB_THREADS / 64) {            // da_i = dp . H'_i
       float acc = 0.0f;
-      for (int x = lane; x < d; x += 64) acc = fmaf(Hs[i * d + x], dp[x], acc);
+      for (int x = lane; x < d; x += 64) acc = fmaf(load_as_f32(Hs, (size_t)(i * d + x)), dp[x], acc);
       acc = wave_sum_rows(acc);
       if (lane == 0) da[i] = acc;
     }
@@ -202,7 +202,7 @@ __global__ __launch_bounds__(GB_THREADS) void gsta_bwd_kernel(const T* __restric
     }
     for (int x = tid; x < d; x += GB_THREADS) {                   // dr = sum_i de_i H'_i / sqrt(d)
       float acc = 0.0f;
-      for (int i = 0; i < nv; ++i) acc = fmaf(av[i] * (da[i] - red[1]), Hs[i * d + x], acc);
+      for (int i = 0; i < nv; ++i) acc = fmaf(av[i] * (da[i] - red[1]), load_as_f32(Hs, (size_t)(i * d + x)), acc);
       drv[x] = acc * scale;
     }
     __syncthreads();
@@ -299,8 +299,10 @@ static int gsta_bwd_chunks(int P) {
 }
 
 static size_t gsta_bwd_lds(const GstaBwdArgs& a) {
-  const size_t blocks = a.M > 1 ? 2 : 1;   // H', and its gradient when several layers add to it
-  return sizeof(float) * (blocks * (size_t)a.S * a.d + (size_t)(a.M + 7) * a.d + 2 * (size_t)a.S);
+  const size_t esz = a.dt == LASER_BF16 ? 2 : 4;
+  // H' in its storage type, its gradient in fp32 when several layers add to it, the vectors, alignment slack
+  return (size_t)a.S * a.d * esz + sizeof(float) * ((a.M > 1 ? (size_t)a.S * a.d : 0) + (size_t)(a.M + 7) * a.d +
+                                                    2 * (size_t)a.S + 4);
 }
 
 bool gsta_backward_supports(const GstaBwdArgs& a) {
