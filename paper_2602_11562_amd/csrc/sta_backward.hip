@@ -4,13 +4,17 @@
 //   dv_j = sum_c g_cj dH'[c,i(j),:]                         dk_j = sum_c ds_cj q_c / gamma
 //   ds_cj = (dH'[c,i(j),:] . v_j) g_cj (1 - g_cj)           dq_c = sum_j ds_cj k_j / gamma
 // Like the forward pass with few candidates this is HBM streaming work (K and V read once, dk and dv written once),
-// so the layout is the streaming kernel's: a workgroup owns a user's run of consecutive segments and its four waves
-// take alternating segments. A wave holds one item at a time, lane l the elements l, l + 64, ... of its key and value
-// rows; the two dot products per (item, candidate) are wave-wide sums, after which every lane knows the gate and ds
-// and updates its own elements of dv_j, dk_j (stored once per item, fp32) and of dq_c (kept in registers over the
-// run). The queries and the upstream gradient of the current segment sit in registers in the same lane layout. dq is
-// summed over a workgroup's waves in LDS and over a user's workgroups by a second small kernel, both in a fixed
-// order (deterministic). Items at or past the valid length get zero gradients.
+// so the work is dealt as in the streaming kernels: a workgroup owns a user's run of consecutive segments and its
+// four waves take alternating segments. Two kernels share that frame.
+// sta_bwd_kernel (any widths up to 256, either storage type, up to eight candidates): a wave holds one item at a
+// time, lane l the elements l, l + 64, ... of its key and value rows; the two dot products per (item, candidate) are
+// wave-wide sums, after which every lane knows the gate and ds and updates its own elements of dv_j, dk_j (stored once
+// per item, fp32) and of dq_c (kept in registers over the run). The queries and the upstream gradient of the current
+// segment sit in registers in the same lane layout.
+// sta_bwd_wide_kernel (bf16, the usual widths, up to four candidates; further down): the forward kernels' lane layout,
+// several items per wave-wide load.
+// In both, dq is summed over a workgroup's waves in LDS and over a user's workgroups by a second small kernel, in a
+// fixed order (deterministic), and items at or past the valid length get zero gradients.
 #include <cstdlib>
 
 #include "laser_internal.h"
