@@ -181,6 +181,18 @@ laser_status laser_forward_ragged(const void* q, const void* k, const void* v, c
                                   int C_max, int P, int L, int d_q, int d, int w, float gamma, int M, laser_dtype dt,
                                   void* seg_out, int32_t* seg_cnt, float* z_out, void* stream);
 
+/* The views of Sec. 3.4.4 and the segment FFN + LayerNorm step of Sec. 3.4.2 on packed pairs: seg [P,S,d], pool_out
+ * [P,d], recent_out [P,r,d], seg_out [P,S,d]; cand_off, C_max and P as above, everything else as for
+ * laser_multires_forward and laser_segment_ffn_forward (kernel chosen as by LASER_FFN_AUTO). */
+laser_status laser_multires_forward_ragged(const void* seg, const int32_t* lens, const int32_t* cand_off, int U,
+                                           int C_max, int P, int L, int d, int w, int r, laser_dtype dt, void* pool_out,
+                                           void* recent_out, void* stream);
+laser_status laser_segment_ffn_forward_ragged(const void* seg, const int32_t* lens, const int32_t* cand_off,
+                                              const void* w1, const float* b1, const void* w2, const float* b2,
+                                              const float* ln_g, const float* ln_b, int U, int C_max, int P, int L,
+                                              int d, int d_ff, int w, float eps, laser_dtype dt, void* seg_out,
+                                              void* stream);
+
 /*
  * Segment feed-forward step (paper Sec. 3.4.2, the equation after the STA paragraph): every segment vector of H'
  * becomes s <- LN(FFN(s) + s). The paper names neither the network's shape nor the normalisation's constants; here

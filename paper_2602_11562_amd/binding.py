@@ -22,7 +22,8 @@ PROJECT_AUTO, PROJECT_GENERIC, PROJECT_MFMA = 0, 1, 2
 
 EXPORTS = [
     "laser_sta_forward", "laser_sta_forward_variant", "laser_sta_forward_heads", "laser_sta_forward_softmax", "laser_sta_forward_ragged",
-    "laser_gsta_forward_ragged", "laser_forward_ragged", "laser_gsta_forward", "laser_gsta_forward_variant",
+    "laser_gsta_forward_ragged", "laser_forward_ragged", "laser_multires_forward_ragged",
+    "laser_segment_ffn_forward_ragged", "laser_gsta_forward", "laser_gsta_forward_variant",
     "laser_forward", "laser_multires_forward", "laser_forward_multires", "laser_sta_kernel_name",
     "laser_gsta_kernel_name", "laser_segment_ffn_forward", "laser_segment_ffn_forward_variant",
     "laser_gsta_kernel_name_layers", "laser_project_q_forward", "laser_project_q_forward_variant",
@@ -92,7 +93,11 @@ def load_library() -> ctypes.CDLL:
     lib.laser_gsta_forward_ragged.argtypes = [vp, vp, vp, vp, vp, ip, ip, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp]
     lib.laser_forward_ragged.argtypes = [vp, vp, vp, vp, vp, vp, vp, ip, ip, i32, i32, i32, i32, i32, i32, i32, f32,
                                          i32, i32, vp, ip, vp, vp]
-    for name in ("laser_sta_forward_ragged", "laser_gsta_forward_ragged", "laser_forward_ragged"):
+    lib.laser_multires_forward_ragged.argtypes = [vp, ip, ip, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp]
+    lib.laser_segment_ffn_forward_ragged.argtypes = [vp, ip, ip, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32,
+                                                     i32, f32, i32, vp, vp]
+    for name in ("laser_sta_forward_ragged", "laser_gsta_forward_ragged", "laser_forward_ragged",
+                 "laser_multires_forward_ragged", "laser_segment_ffn_forward_ragged"):
         getattr(lib, name).restype = i32
     lib.laser_sta_backward_work_bytes.argtypes = [i32, i32, i32, i32, i32]
     lib.laser_sta_backward_work_bytes.restype = ctypes.c_size_t
@@ -387,6 +392,37 @@ def laser_gsta_backward(seg, t0, wq, wk, wv, lens, dz, L: int, w: int, work=None
                                    work.numel() * work.element_size(), _stream(stream))
     _check(code, "laser_gsta_backward")
     return dseg, dt0, dwq, dwk, dwv
+
+
+def laser_multires_forward_ragged(seg, lens, cand_off, c_max: int, L: int, w: int, r: int, stream=None):
+    """Packed pairs: seg [P,S,d] with cand_off [U+1] -> (pool [P,d], recent [P,r,d] or None)."""
+    torch = _torch()
+    P, S, d = seg.shape
+    U = cand_off.shape[0] - 1
+    pool = torch.empty((P, d), dtype=seg.dtype, device=seg.device)
+    recent = torch.empty((P, r, d), dtype=seg.dtype, device=seg.device) if r > 0 else None
+    code = load_library().laser_multires_forward_ragged(
+        _ptr(seg, "seg"), _ptr(lens, "lens", torch.int32), _ptr(cand_off, "cand_off", torch.int32), U, int(c_max), P,
+        int(L), d, int(w), int(r), _dt(seg), _ptr(pool, "pool"), _ptr(recent, "recent"), _stream(stream))
+    _check(code, "laser_multires_forward_ragged")
+    return pool, recent
+
+
+def laser_segment_ffn_forward_ragged(seg, lens, cand_off, c_max: int, w1, b1, w2, b2, ln_g, ln_b, L: int, w: int,
+                                     eps: float = 1e-5, seg_out=None, stream=None):
+    """Packed pairs: seg [P,S,d] with cand_off [U+1] -> LN(FFN(seg) + seg) [P,S,d]; seg_out may be seg."""
+    torch = _torch()
+    P, S, d = seg.shape
+    U = cand_off.shape[0] - 1
+    if seg_out is None:
+        seg_out = torch.empty_like(seg)
+    code = load_library().laser_segment_ffn_forward_ragged(
+        _ptr(seg, "seg"), _ptr(lens, "lens", torch.int32), _ptr(cand_off, "cand_off", torch.int32), _ptr(w1, "w1"),
+        _ptr(b1, "b1", torch.float32), _ptr(w2, "w2"), _ptr(b2, "b2", torch.float32), _ptr(ln_g, "ln_g", torch.float32),
+        _ptr(ln_b, "ln_b", torch.float32), U, int(c_max), P, int(L), d, w1.shape[1], int(w), float(eps), _dt(seg),
+        _ptr(seg_out, "seg_out", seg.dtype), _stream(stream))
+    _check(code, "laser_segment_ffn_forward_ragged")
+    return seg_out
 
 
 def laser_fold_query_weights(w_q, w_k, heads: int = 1, a_out=None, stream=None):

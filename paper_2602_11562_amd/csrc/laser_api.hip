@@ -66,6 +66,23 @@ static laser_status validate_multires(const void* seg, const int32_t* lens, int 
   return LASER_OK;
 }
 
+static laser_status validate_ffn(const void* seg, const int32_t* lens, const void* w1, const float* b1, const void* w2,
+                                 const float* b2, const float* ln_g, const float* ln_b, int U, int C, int L, int d,
+                                 int d_ff, int w, float eps, laser_dtype dt, void* seg_out, void* stream, FfnArgs* out) {
+  if (!seg || !w1 || !b1 || !w2 || !b2 || !ln_g || !ln_b || !seg_out) return LASER_ERR_NULL;
+  if (dt != LASER_F32 && dt != LASER_BF16) return LASER_ERR_DTYPE;
+  laser_status s = check_dims(U, C, L, d, d, w);
+  if (s != LASER_OK) return s;
+  if (d_ff <= 0 || d_ff > 4096 || (d_ff % 8) != 0) return LASER_ERR_SHAPE;
+  if (!(eps >= 0.0f) || !(eps < INFINITY)) return LASER_ERR_SHAPE;
+  if (!aligned16(seg) || !aligned16(w1) || !aligned16(w2) || !aligned16(seg_out)) return LASER_ERR_ALIGN;
+  for (const void* p : {(const void*)b1, (const void*)b2, (const void*)ln_g, (const void*)ln_b, (const void*)lens})
+    if (reinterpret_cast<uintptr_t>(p) & 3u) return LASER_ERR_ALIGN;
+  *out = FfnArgs{seg, lens, w1, b1, w2, b2, ln_g, ln_b, U, C, L, d, d_ff, w, (L + w - 1) / w, eps, dt, seg_out,
+                 static_cast<hipStream_t>(stream)};
+  return LASER_OK;
+}
+
 static laser_sta_variant pick_sta(const StaArgs& a) {
   if (sta_stream_supports(a)) return LASER_STA_STREAM;
   if (sta_mfma_supports(a)) return LASER_STA_MFMA;
@@ -247,6 +264,35 @@ laser_status laser_multires_forward(const void* seg, const int32_t* lens, int U,
   return multires_launch(a);
 }
 
+laser_status laser_multires_forward_ragged(const void* seg, const int32_t* lens, const int32_t* cand_off, int U,
+                                           int C_max, int P, int L, int d, int w, int r, laser_dtype dt, void* pool_out,
+                                           void* recent_out, void* stream) {
+  MultiresArgs a;
+  laser_status s = validate_multires(seg, lens, U, C_max, L, d, w, r, dt, pool_out, recent_out, stream, &a);
+  if (s != LASER_OK) return s;
+  s = validate_ragged(cand_off, U, C_max, P, L, d, d, w);
+  if (s != LASER_OK) return s;
+  a.cand_off = cand_off;
+  a.P = P;
+  return multires_launch(a);
+}
+
+laser_status laser_segment_ffn_forward_ragged(const void* seg, const int32_t* lens, const int32_t* cand_off,
+                                              const void* w1, const float* b1, const void* w2, const float* b2,
+                                              const float* ln_g, const float* ln_b, int U, int C_max, int P, int L,
+                                              int d, int d_ff, int w, float eps, laser_dtype dt, void* seg_out,
+                                              void* stream) {
+  FfnArgs a;
+  laser_status s = validate_ffn(seg, lens, w1, b1, w2, b2, ln_g, ln_b, U, C_max, L, d, d_ff, w, eps, dt, seg_out, stream,
+                                &a);
+  if (s != LASER_OK) return s;
+  s = validate_ragged(cand_off, U, C_max, P, L, d, d, w);
+  if (s != LASER_OK) return s;
+  a.cand_off = cand_off;
+  a.P = P;
+  return segment_ffn_mfma_supports(a) ? segment_ffn_mfma_launch(a) : segment_ffn_generic_launch(a);
+}
+
 laser_status laser_forward_multires(const void* q, const void* k, const void* v, const void* t0, const void* wq,
                                     const void* wk, const void* wv, const int32_t* lens, int U, int C, int L,
                                     int d_q, int d, int w, float gamma, int M, laser_dtype dt, void* seg_out,
@@ -285,18 +331,11 @@ laser_status laser_segment_ffn_forward_variant(const void* seg, const int32_t* l
                                                const void* w2, const float* b2, const float* ln_g, const float* ln_b,
                                                int U, int C, int L, int d, int d_ff, int w, float eps, laser_dtype dt,
                                                void* seg_out, void* stream, laser_ffn_variant variant) {
-  if (!seg || !w1 || !b1 || !w2 || !b2 || !ln_g || !ln_b || !seg_out) return LASER_ERR_NULL;
-  if (dt != LASER_F32 && dt != LASER_BF16) return LASER_ERR_DTYPE;
-  laser_status s = check_dims(U, C, L, d, d, w);
+  FfnArgs a;
+  const laser_status s = validate_ffn(seg, lens, w1, b1, w2, b2, ln_g, ln_b, U, C, L, d, d_ff, w, eps, dt, seg_out,
+                                      stream, &a);
   if (s != LASER_OK) return s;
-  if (d_ff <= 0 || d_ff > 4096 || (d_ff % 8) != 0) return LASER_ERR_SHAPE;
-  if (!(eps >= 0.0f) || !(eps < INFINITY)) return LASER_ERR_SHAPE;
-  if (!aligned16(seg) || !aligned16(w1) || !aligned16(w2) || !aligned16(seg_out)) return LASER_ERR_ALIGN;
-  for (const void* p : {(const void*)b1, (const void*)b2, (const void*)ln_g, (const void*)ln_b, (const void*)lens})
-    if (reinterpret_cast<uintptr_t>(p) & 3u) return LASER_ERR_ALIGN;
   if (variant < LASER_FFN_AUTO || variant > LASER_FFN_MFMA) return LASER_ERR_UNSUPPORTED;
-  const FfnArgs a{seg, lens, w1, b1, w2, b2, ln_g, ln_b, U, C, L, d, d_ff, w, (L + w - 1) / w, eps, dt, seg_out,
-                  static_cast<hipStream_t>(stream)};
   if (variant == LASER_FFN_AUTO) variant = segment_ffn_mfma_supports(a) ? LASER_FFN_MFMA : LASER_FFN_GENERIC;
   return variant == LASER_FFN_MFMA ? segment_ffn_mfma_launch(a) : segment_ffn_generic_launch(a);
 }

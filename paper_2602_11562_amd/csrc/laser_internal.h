@@ -57,6 +57,8 @@ struct MultiresArgs {
   void* pool_out;     // may be nullptr
   void* recent_out;   // may be nullptr (r == 0)
   hipStream_t stream;
+  const int32_t* cand_off = nullptr;   // ragged candidate counts, as in StaArgs (seg and the outputs hold P pairs)
+  int P = 0;
 };
 laser_status multires_launch(const MultiresArgs& a);
 inline int gsta_pairs(const GstaArgs& a) { return a.cand_off ? a.P : a.U * a.C; }   // pairs in seg, t0 and z_out
@@ -75,6 +77,8 @@ struct FfnArgs {
   laser_dtype dt;
   void* seg_out;
   hipStream_t stream;
+  const int32_t* cand_off = nullptr;   // ragged candidate counts, as in StaArgs (seg and seg_out hold P pairs)
+  int P = 0;
 };
 bool segment_ffn_generic_supports(const FfnArgs& a);
 laser_status segment_ffn_generic_launch(const FfnArgs& a);

@@ -35,13 +35,14 @@ __device__ __forceinline__ u32x4 max_piece(const u32x4& a, const u32x4& b) {
 // pieces = 16-byte pieces per row; one thread per (pair, piece)
 template <bool BF16>
 __global__ __launch_bounds__(256) void multires_kernel(const u32x4* __restrict__ seg, const int32_t* __restrict__ lens,
+                                                       const int32_t* __restrict__ cand_off, int U,
                                                        long long total, int pieces, int C, int L, int w, int S, int r,
                                                        u32x4* __restrict__ pool, u32x4* __restrict__ recent) {
   const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= total) return;
   const long long pair = t / pieces;
   const int piece = (int)(t - pair * pieces);
-  const int u = (int)(pair / C);
+  const int u = pair_user(cand_off, U, C, (int)pair);
   const int nv = (valid_len(lens, u, L) + w - 1) / w;   // segments with a valid item: a prefix
   const u32x4* H = seg + (size_t)pair * S * pieces + piece;
   if (recent != nullptr) {
@@ -67,15 +68,15 @@ __global__ __launch_bounds__(256) void multires_kernel(const u32x4* __restrict__
 laser_status multires_launch(const MultiresArgs& a) {
   const int esize = a.dt == LASER_BF16 ? 2 : 4;
   const int pieces = a.d * esize / 16;
-  const long long total = (long long)a.U * a.C * pieces;
+  const long long total = (long long)(a.cand_off ? a.P : a.U * a.C) * pieces;
   const long long blocks = (total + 255) / 256;
   if (blocks > 0x7fffffffLL) return LASER_ERR_SHAPE;
   if (a.dt == LASER_BF16)
     hipLaunchKernelGGL((multires_kernel<true>), dim3((unsigned)blocks), dim3(256), 0, a.stream, (const u32x4*)a.seg,
-                       a.lens, total, pieces, a.C, a.L, a.w, a.S, a.r, (u32x4*)a.pool_out, (u32x4*)a.recent_out);
+                       a.lens, a.cand_off, a.U, total, pieces, a.C, a.L, a.w, a.S, a.r, (u32x4*)a.pool_out, (u32x4*)a.recent_out);
   else
     hipLaunchKernelGGL((multires_kernel<false>), dim3((unsigned)blocks), dim3(256), 0, a.stream, (const u32x4*)a.seg,
-                       a.lens, total, pieces, a.C, a.L, a.w, a.S, a.r, (u32x4*)a.pool_out, (u32x4*)a.recent_out);
+                       a.lens, a.cand_off, a.U, total, pieces, a.C, a.L, a.w, a.S, a.r, (u32x4*)a.pool_out, (u32x4*)a.recent_out);
   return launch_status();
 }
 

@@ -15,7 +15,8 @@ template <typename T>
 __global__ __launch_bounds__(FG_THREADS) void segment_ffn_generic_kernel(
     const T* seg, const int32_t* __restrict__ lens, const T* __restrict__ w1, const float* __restrict__ b1,
     const T* __restrict__ w2, const float* __restrict__ b2, const float* __restrict__ ln_g,
-    const float* __restrict__ ln_b, long long rows, int C, int L, int d, int d_ff, int w, int S, float eps,
+    const float* __restrict__ ln_b, const int32_t* __restrict__ cand_off, int U, long long rows, int C, int L, int d,
+    int d_ff, int w, int S, float eps,
     T* out) {   // out may be seg: a workgroup has read its rows before it writes them
   extern __shared__ float sm[];            // x [FG_ROWS][d], hidden [FG_ROWS][d_ff], y [FG_ROWS][d], stats [FG_ROWS][2]
   float* x = sm;
@@ -30,7 +31,7 @@ __global__ __launch_bounds__(FG_THREADS) void segment_ffn_generic_kernel(
     int ok = 0;
     if (r < rows) {
       const int i = (int)(r % S);
-      const int u = (int)(r / ((long long)C * S));
+      const int u = pair_user(cand_off, U, C, (int)(r / S));
       ok = (long long)i * w < valid_len(lens, u, L);
     }
     valid[tid] = ok;
@@ -107,7 +108,7 @@ bool segment_ffn_generic_supports(const FfnArgs& a) {
 
 laser_status segment_ffn_generic_launch(const FfnArgs& a) {
   if (!segment_ffn_generic_supports(a)) return LASER_ERR_UNSUPPORTED;
-  const long long rows = (long long)a.U * a.C * a.S;
+  const long long rows = (long long)(a.cand_off ? a.P : a.U * a.C) * a.S;
   const long long blocks = (rows + FG_ROWS - 1) / FG_ROWS;
   if (blocks > 0x7fffffffLL) return LASER_ERR_SHAPE;
   const size_t lds = (size_t)FG_ROWS * (2 * a.d + a.d_ff + 2) * sizeof(float);
@@ -118,14 +119,14 @@ laser_status segment_ffn_generic_launch(const FfnArgs& a) {
       return LASER_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(FG_THREADS), lds, a.stream, (const unsigned short*)a.seg,
                        a.lens, (const unsigned short*)a.w1, a.b1, (const unsigned short*)a.w2, a.b2, a.ln_g, a.ln_b,
-                       rows, a.C, a.L, a.d, a.d_ff, a.w, a.S, a.eps, (unsigned short*)a.seg_out);
+                       a.cand_off, a.U, rows, a.C, a.L, a.d, a.d_ff, a.w, a.S, a.eps, (unsigned short*)a.seg_out);
   } else {
     auto kern = segment_ffn_generic_kernel<float>;
     if (lds > 48 * 1024 &&
         hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
       return LASER_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(FG_THREADS), lds, a.stream, (const float*)a.seg, a.lens,
-                       (const float*)a.w1, a.b1, (const float*)a.w2, a.b2, a.ln_g, a.ln_b, rows, a.C, a.L, a.d,
+                       (const float*)a.w1, a.b1, (const float*)a.w2, a.b2, a.ln_g, a.ln_b, a.cand_off, a.U, rows, a.C, a.L, a.d,
                        a.d_ff, a.w, a.S, a.eps, (float*)a.seg_out);
   }
   return launch_status();
@@ -170,7 +171,8 @@ template <int DFF>
 __global__ __launch_bounds__(FM_THREADS) void segment_ffn_mfma_kernel(
     const unsigned short* seg, const int32_t* __restrict__ lens, const unsigned short* __restrict__ w1,
     const float* __restrict__ b1, const unsigned short* __restrict__ w2, const float* __restrict__ b2,
-    const float* __restrict__ ln_g, const float* __restrict__ ln_b, long long rows, int C, int L, int w, int S, float eps,
+    const float* __restrict__ ln_g, const float* __restrict__ ln_b, const int32_t* __restrict__ cand_off, int U,
+    long long rows, int C, int L, int w, int S, float eps,
     unsigned short* out) {
   constexpr int D = 128, KSTEPS = D / 16, DB = D / 32, HT = DFF / 32;
   constexpr int W1P = D * 2 + 16;            // W1^T row pitch: 16-byte reads of 32 consecutive rows hit all banks
@@ -248,7 +250,7 @@ __global__ __launch_bounds__(FM_THREADS) void segment_ffn_mfma_kernel(
       int ok = 0;
       if (r < rows) {
         const int i = (int)(r % S);
-        const int u = (int)(r / ((long long)C * S));
+        const int u = pair_user(cand_off, U, C, (int)(r / S));
         ok = (long long)i * w < valid_len(lens, u, L);
       }
       rowok[wave][lane] = ok;
@@ -358,14 +360,14 @@ bool segment_ffn_mfma_supports(const FfnArgs& a) {
 
 laser_status segment_ffn_mfma_launch(const FfnArgs& a) {
   if (!segment_ffn_mfma_supports(a)) return LASER_ERR_UNSUPPORTED;
-  const long long rows = (long long)a.U * a.C * a.S;
+  const long long rows = (long long)(a.cand_off ? a.P : a.U * a.C) * a.S;
   const long long ntiles = (rows + FM_ROWS - 1) / FM_ROWS;
   long long blocks = (ntiles + FM_WAVES - 1) / FM_WAVES;
   if (blocks > 256) blocks = 256;   // one workgroup per compute unit (LDS), each walking several tiles per wave
 #define LASER_FFN_LAUNCH(FF)                                                                                          \
   hipLaunchKernelGGL((segment_ffn_mfma_kernel<FF>), dim3((unsigned)blocks), dim3(FM_THREADS), 0, a.stream,            \
                      (const unsigned short*)a.seg, a.lens, (const unsigned short*)a.w1, a.b1,                        \
-                     (const unsigned short*)a.w2, a.b2, a.ln_g, a.ln_b, rows, a.C, a.L, a.w, a.S, a.eps,              \
+                     (const unsigned short*)a.w2, a.b2, a.ln_g, a.ln_b, a.cand_off, a.U, rows, a.C, a.L, a.w, a.S, a.eps, \
                      (unsigned short*)a.seg_out)
   if (a.d_ff == 64) LASER_FFN_LAUNCH(64);
   else LASER_FFN_LAUNCH(128);

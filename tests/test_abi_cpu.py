@@ -267,3 +267,15 @@ def test_gsta_backward_argument_validation(lib):
     big = 1 << 30
     assert f(d=512, wb=big) == UNSUP and f(M=9, wb=big) == UNSUP
     assert f(L=1 << 15, w=8, d=256, wb=big) == UNSUP    # H' block too large for LDS
+
+
+def test_ragged_views_and_ffn_argument_validation(lib):
+    NULL, SHAPE, ALIGN = 1, 2, 6
+    mr = lambda seg=A, off=A, P=10, r=2, pool=A, rec=A: lib.laser_multires_forward_ragged(
+        seg, None, off, 3, 8, P, 64, 16, 8, r, 1, pool, rec, None)
+    assert mr(seg=None) == NULL and mr(off=None) == NULL and mr(P=0) == SHAPE and mr(P=25) == SHAPE
+    assert mr(r=9) == SHAPE and mr(off=A + 2) == ALIGN
+    ffn = lambda seg=A, off=A, P=10, dff=32, out=A: lib.laser_segment_ffn_forward_ragged(
+        seg, None, off, A, A, A, A, A, A, 3, 8, P, 64, 16, dff, 8, ctypes.c_float(1e-5), 1, out, None)
+    assert ffn(seg=None) == NULL and ffn(off=None) == NULL and ffn(out=None) == NULL
+    assert ffn(P=0) == SHAPE and ffn(P=25) == SHAPE and ffn(dff=12) == SHAPE and ffn(off=A + 1) == ALIGN

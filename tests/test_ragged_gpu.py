@@ -127,3 +127,43 @@ def test_offsets_that_break_the_rules_stay_inside_the_buffers():
         torch.cuda.synchronize()
         for b in (segbuf, zbuf):
             assert (b[:guard] == 3.0).all() and (b[-guard:] == 3.0).all(), bad
+
+
+@pytest.mark.parametrize("name", ["matrix_core_two_waves", "streaming_short_segments", "generic_f32"])
+def test_ragged_views_and_ffn_match_checker(name):
+    """The views (Sec. 3.4.4) and the FFN + LayerNorm step (Sec. 3.4.2) on packed pairs: every pair against the
+    checker's per-pair functions with its own user's valid segments. Views are selections of stored values: equality."""
+    import torch
+    dtype, t, lens, off, cmax, w, gamma = _case(name)
+    dev = {k: to_device(v[0]) for k, v in t.items()}
+    L = t["k"][0].shape[1]
+    d = t["v"][0].shape[2]
+    seg, cnt, _ = laser.laser_forward_ragged(dev["q"], dev["k"], dev["v"], None, None, None, None, to_device(lens),
+                                             to_device(off), cmax, w, gamma, stage="sta")
+    S = seg.shape[1]
+    r = min(3, S)
+    pool, recent = laser.laser_multires_forward_ragged(seg, to_device(lens), to_device(off), cmax, L, w, r)
+    rng = np.random.default_rng(5)
+    dff = 32
+    W1s, W1v = _store(rng.normal(size=(d, dff)) / math.sqrt(d), dtype)
+    W2s, W2v = _store(rng.normal(size=(dff, d)) / math.sqrt(dff), dtype)
+    f32 = lambda x: np.asarray(x, dtype=np.float32)
+    b1, b2 = f32(rng.normal(size=dff) * 0.3), f32(rng.normal(size=d) * 0.3)
+    g, b = f32(1.0 + 0.2 * rng.normal(size=d)), f32(0.1 * rng.normal(size=d))
+    out = laser.laser_segment_ffn_forward_ragged(seg, to_device(lens), to_device(off), cmax, to_device(W1s), to_device(b1),
+                                                 to_device(W2s), to_device(b2), to_device(g), to_device(b), L, w, 1e-5)
+    torch.cuda.synchronize()
+    segh, cnth = to_host_f64(seg), cnt.cpu().numpy()
+    poolh, rech, outh = to_host_f64(pool), to_host_f64(recent), to_host_f64(out)
+    worst = 0.0
+    for u in range(len(lens)):
+        valid = cnth[u] > 0
+        for p in range(off[u], off[u + 1]):
+            pr, rr = oracle.multires_pair(segh[p], valid, r)
+            assert np.array_equal(poolh[p], pr) and np.array_equal(rech[p], rr)
+            for i in range(S):
+                ref = (oracle.segment_ffn_vector(segh[p, i].copy(), W1v, b1, W2v, b2, g, b, 1e-5) if valid[i]
+                       else np.zeros(d))
+                worst = max(worst, vec_rel_err(outh[p, i], ref))
+    print(f"  {name}: FFN + LN worst {worst:.3e}", flush=True)
+    assert worst <= TOL[dtype]
