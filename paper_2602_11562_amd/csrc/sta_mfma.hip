@@ -1031,7 +1031,13 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
 }
 
 // ------------------------------------------------------------------------------------------ host side
-static int pick_nw(int C) { return C > 128 ? 8 : (C > 64 ? 4 : (C > 32 ? 2 : 1)); }
+static int pick_nw(int C) {
+  if (const char* e = getenv("LASER_STA_NW")) {   // tuning override: waves (32 candidates each) per workgroup
+    const int vv = atoi(e);
+    if (vv == 1 || vv == 2 || vv == 4 || vv == 8) return vv;
+  }
+  return C > 128 ? 8 : (C > 64 ? 4 : (C > 32 ? 2 : 1));
+}
 
 bool sta_mfma_supports(const StaArgs& a) {
   if (a.dt != LASER_BF16) return false;
@@ -1084,7 +1090,9 @@ laser_status sta_mfma_launch(const StaArgs& a) {
   const int ctiles = (a.C + CW * nw - 1) / (CW * nw);
   // consecutive segments per workgroup (they share the query registers and the prefetch pipeline): as many as
   // still leave one eight-wave workgroup, or two smaller ones, per compute unit
-  const long long want = nw == 8 ? 256 : 512;
+  // (smaller workgroups: more of them fit a compute unit, so more are wanted; 64 users x 64 candidates x 16
+  // segments, two waves: 15.1 us with 512 workgroups of two segments, 11.2 us with 1024 of one)
+  const long long want = 2048 / nw;
   int spw = 1;
   while (spw < 8 && (long long)a.U * ctiles * ((a.S + 2 * spw - 1) / (2 * spw)) >= want) spw *= 2;
   if (const char* e = getenv("LASER_STA_SPW")) {   // tuning override
