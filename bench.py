@@ -171,6 +171,10 @@ def main() -> int:
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copies", type=int, default=0, help="distinct input/output copies to rotate through (0 = auto)")
+    ap.add_argument("--streams", type=int, default=3,
+                    help="HIP streams (default priority) over which consecutive steps, which are independent batches, "
+                         "are dealt in turn; 1 = every step waits for the one before. The figure with one stream is "
+                         "always reported beside the headline")
     ap.add_argument("--views", type=int, default=0, metavar="R",
                     help="also time the multi-resolution views (max-pooled H' and the R most recent segments): the "
                          "stand-alone kernel and the whole path with them; reported under \"views\"")
@@ -218,7 +222,9 @@ def main() -> int:
     gsta_f = cm.gsta_flops(wl.lens, spec.C, spec.d, spec.w, spec.M)
     footprint = (wl.q.nbytes + wl.k.nbytes + wl.v.nbytes + wl.t0.nbytes + spec.U * spec.C * spec.S * spec.d * esz
                  + spec.U * spec.C * spec.d * 4)
+    nstreams = max(1, min(4, args.streams))
     copies = args.copies or int(min(8, max(1, math.ceil(600e6 / footprint))))
+    copies = -(-copies // nstreams) * nstreams   # a multiple of the streams: a buffer set is only ever used on one stream
 
     sets = []
     for _ in range(copies):
@@ -228,10 +234,10 @@ def main() -> int:
         z = torch.empty((spec.U, spec.C, spec.d), dtype=torch.float32, device="cuda")
         sets.append((dw, seg, cnt, z))
 
-    def step(i):
+    def step(i, stream=None):
         dw, seg, cnt, z = sets[i % copies]
         laser.laser_forward(dw.q, dw.k, dw.v, dw.t0, dw.wq, dw.wk, dw.wv, dw.lens, spec.w, spec.gamma,
-                            seg_out=seg, seg_cnt=cnt, z_out=z)
+                            seg_out=seg, seg_cnt=cnt, z_out=z, stream=stream)
 
     def sta_only(i):
         dw, seg, cnt, z = sets[i % copies]
@@ -241,14 +247,22 @@ def main() -> int:
         dw, seg, cnt, z = sets[i % copies]
         laser.laser_gsta_forward(seg, dw.t0, dw.wq, dw.wk, dw.wv, dw.lens, spec.L, spec.w, z_out=z)
 
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    def timed_steps(streams):
+        """W warm-up steps, then K timed steps between two device synchronisations; step i goes to stream i mod n."""
+        n = len(streams)
+        for i in range(args.warmup):
+            step(i, streams[i % n])
+        torch.cuda.synchronize()
+        t_start = time.perf_counter()
+        for i in range(args.steps):
+            step(i, streams[i % n])
+        torch.cuda.synchronize()
+        return time.perf_counter() - t_start
+
+    # One stream: the latency of a step. Several: consecutive steps are independent batches (a serving process has
+    # many in flight), and the tail of one step's kernels overlaps the start of the next step's.
+    wall_one = timed_steps([torch.cuda.current_stream()])
+    wall = timed_steps([torch.cuda.Stream() for _ in range(nstreams)]) if nstreams > 1 else wall_one
     ms_per_step = wall * 1e3 / args.steps
 
     def event_time(fn):
@@ -489,7 +503,10 @@ def main() -> int:
         "dtype": spec.dtype, "data": "synthetic",
         "config": {"workload": spec.name, "U": spec.U, "C": spec.C, "L": spec.L, "d": spec.d, "d_q": spec.d_q,
                    "w": spec.w, "S": spec.S, "M": spec.M, "pairs": spec.pairs, "input_copies": copies,
+                   "streams": nstreams,
                    "footprint_mb": footprint / 1e6, "seg_out_written": True},
+        "single_stream": {"ms_per_step": wall_one * 1e3 / args.steps,
+                          "value": spec.pairs / (wall_one / args.steps)},
         "roofline": roof,
         "cpu_baseline": cpu,
         "kernels": {"sta": {"name": sta_kernel, "ms": sta_ms}, "gsta": {
