@@ -28,14 +28,24 @@ template <typename T, int TQ, int TV, int CMAX>   // TQ, TV: 64-element slices o
 __global__ __launch_bounds__(256) void sta_bwd_kernel(const T* __restrict__ q, const T* __restrict__ k,
                                                       const T* __restrict__ v, const T* __restrict__ dhp,
                                                       const int32_t* __restrict__ lens, int C, int L, int dq, int d, int w,
-                                                      int S, int spg, int groups, float neg_scale_log2e, float inv_gamma,
+                                                      int S, int spg, int groups, int users, int classes,
+                                                      float neg_scale_log2e, float inv_gamma,
                                                       float* __restrict__ dk, float* __restrict__ dv,
                                                       float* __restrict__ dq_part) {
   extern __shared__ float red[];        // [4][C][dq] per-wave dq sums at the end of the run
-  const int u = blockIdx.x / groups, grp = blockIdx.x % groups;
+  // longest histories first (length classes, as in the forward streaming kernel): the grid holds every (user, run)
+  // once per class and a workgroup leaves at once unless its user's length falls in its class
+  const int per_class = users * groups;
+  const int cls = blockIdx.x / per_class, rest = blockIdx.x - cls * per_class;
+  const int u = rest / groups, grp = rest % groups;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = __builtin_amdgcn_readfirstlane(valid_len(lens, u, L));
+  if (classes > 1) {
+    int mine = 0;
+    while (mine < classes - 1 && n <= (L >> (mine + 1))) ++mine;
+    if (mine != cls) return;   // (the whole workgroup, before any barrier)
+  }
   const int i_beg = grp * spg;
   const int i_end = (grp + 1) * spg < S ? (grp + 1) * spg : S;
   const T* kU = k + (size_t)u * L * dq;
@@ -162,7 +172,8 @@ __global__ __launch_bounds__(256) void sta_bwd_wide_kernel(const unsigned short*
                                                            const unsigned short* __restrict__ v,
                                                            const unsigned short* __restrict__ dhp,
                                                            const int32_t* __restrict__ lens, int C, int L, int w, int S,
-                                                           int spg, int groups, float neg_scale_log2e, float inv_gamma,
+                                                           int spg, int groups, int users, int classes,
+                                                           float neg_scale_log2e, float inv_gamma,
                                                            float* __restrict__ dk, float* __restrict__ dv,
                                                            float* __restrict__ dq_part) {
   constexpr int LQ = DQ / 8, LV = D / 8;           // lanes per key row / value row
@@ -174,10 +185,19 @@ __global__ __launch_bounds__(256) void sta_bwd_wide_kernel(const unsigned short*
   __shared__ float xd[4][CMAX][IPC];               // dH' . v per item, value lanes -> key lanes
   __shared__ float red[4][CMAX][DQ];
 
-  const int u = blockIdx.x / groups, grp = blockIdx.x % groups;
+  // longest histories first (length classes, as in the forward streaming kernel): the grid holds every (user, run)
+  // once per class and a workgroup leaves at once unless its user's length falls in its class
+  const int per_class = users * groups;
+  const int cls = blockIdx.x / per_class, rest = blockIdx.x - cls * per_class;
+  const int u = rest / groups, grp = rest % groups;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = __builtin_amdgcn_readfirstlane(valid_len(lens, u, L));
+  if (classes > 1) {
+    int mine = 0;
+    while (mine < classes - 1 && n <= (L >> (mine + 1))) ++mine;
+    if (mine != cls) return;   // (the whole workgroup, before any barrier)
+  }
   const int rq = lane / LQ, cq = lane % LQ;
   const int rv = lane / LV, cv = lane % LV;
   const int i_beg = grp * spg;
@@ -354,6 +374,16 @@ static void sta_bwd_shape(int U, int S, int w, int* spg, int* groups) {
   *groups = (S + *spg - 1) / *spg;
 }
 
+// length classes: worth their empty workgroups once the launch is several rounds of workgroups and lengths differ
+static int sta_bwd_classes(const StaBwdArgs& a, unsigned blocks) {
+  int classes = (a.lens != nullptr && blocks >= 4096 && (unsigned long long)blocks * 4 <= 0x7fffffffULL) ? 4 : 1;
+  if (const char* e = getenv("LASER_STREAM_CLASSES")) {   // tuning override, shared with the forward kernel
+    const int vv = atoi(e);
+    if (vv >= 1 && vv <= 8 && (unsigned long long)blocks * vv <= 0x7fffffffULL) classes = vv;
+  }
+  return classes;
+}
+
 bool sta_backward_supports(const StaBwdArgs& a) {
   return a.C <= SB_CMAX && a.d_q <= 64 * SB_TMAX && a.d <= 64 * SB_TMAX;
 }
@@ -368,10 +398,11 @@ template <typename T, int TQ, int TV>
 static void sta_bwd_launch_c(const StaBwdArgs& a, unsigned blocks, size_t lds, int spg, int groups) {
   const float inv_gamma = 1.0f / a.gamma;
   const float nsl = -1.4426950408889634f * inv_gamma;
+  const int classes = sta_bwd_classes(a, blocks);
 #define LASER_BWD_LAUNCH(CM)                                                                                          \
-  hipLaunchKernelGGL((sta_bwd_kernel<T, TQ, TV, CM>), dim3(blocks), dim3(256), lds, a.stream, (const T*)a.q,          \
-                     (const T*)a.k, (const T*)a.v, (const T*)a.dhp, a.lens, a.C, a.L, a.d_q, a.d, a.w, a.S, spg,      \
-                     groups, nsl, inv_gamma, a.dk, a.dv, a.work)
+  hipLaunchKernelGGL((sta_bwd_kernel<T, TQ, TV, CM>), dim3(blocks * classes), dim3(256), lds, a.stream,               \
+                     (const T*)a.q, (const T*)a.k, (const T*)a.v, (const T*)a.dhp, a.lens, a.C, a.L, a.d_q, a.d, a.w, \
+                     a.S, spg, groups, a.U, classes, nsl, inv_gamma, a.dk, a.dv, a.work)
   if (a.C <= 1) LASER_BWD_LAUNCH(1);
   else if (a.C <= 4) LASER_BWD_LAUNCH(4);
   else LASER_BWD_LAUNCH(8);
@@ -403,11 +434,12 @@ template <int DQ, int D>
 static void sta_bwd_wide_launch(const StaBwdArgs& a, unsigned blocks, int spg, int groups) {
   const float inv_gamma = 1.0f / a.gamma;
   const float nsl = -1.4426950408889634f * inv_gamma;
+  const int classes = sta_bwd_classes(a, blocks);
 #define LASER_BWD_WIDE(CM)                                                                                           \
-  hipLaunchKernelGGL((sta_bwd_wide_kernel<DQ, D, CM>), dim3(blocks), dim3(256), 0, a.stream,                        \
+  hipLaunchKernelGGL((sta_bwd_wide_kernel<DQ, D, CM>), dim3(blocks * classes), dim3(256), 0, a.stream,              \
                      (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v,            \
-                     (const unsigned short*)a.dhp, a.lens, a.C, a.L, a.w, a.S, spg, groups, nsl, inv_gamma, a.dk,   \
-                     a.dv, a.work)
+                     (const unsigned short*)a.dhp, a.lens, a.C, a.L, a.w, a.S, spg, groups, a.U, classes, nsl,      \
+                     inv_gamma, a.dk, a.dv, a.work)
   if (a.C <= 1) LASER_BWD_WIDE(1);
   else if (a.C <= 2) LASER_BWD_WIDE(2);
   else LASER_BWD_WIDE(4);
