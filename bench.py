@@ -144,6 +144,9 @@ def paper_setting_chain(laser, torch, event_time):
     laser.laser_sta_forward(Q, K, V, lens, w, gamma, seg_out=seg, want_cnt=False, heads=heads)
     gsta_ms = event_time(lambda i: laser.laser_gsta_forward(seg, t0p, *gw3, lens, L, w, z_out=zp))
     gsta_bwd_ms = event_time(lambda i: laser.laser_gsta_backward(seg, t0p, *gw3, lens, dzp, L, w, work=gwork))
+    gk16, gv16 = torch.empty(U, L, dq, device="cuda", dtype=torch.bfloat16), torch.empty(U, L, d, device="cuda", dtype=torch.bfloat16)
+    bwd16_ms = event_time(lambda i: laser.laser_sta_backward(Q, K, V, lens, dseg, w, gamma, dq_out=gq, dk_out=gk16,
+                                                             dv_out=gv16, work=work, grads_bf16=True))
     direct_ms, folded_ms = event_time(direct), event_time(folded)
     same = float((seg.float() - 0).abs().max())   # keeps the last result alive until here
     nvalid = int(lens.sum())
@@ -157,6 +160,9 @@ def paper_setting_chain(laser, torch, event_time):
             "pairs_per_s_folded": U * C / (folded_ms * 1e-3), "max_abs_out": same,
             # backward of STA: valid K and V rows and dH' read once (bf16), dk and dv written once (fp32, every row)
             "gsta_forward_ms": gsta_ms, "gsta_backward_ms": gsta_bwd_ms,
+            "sta_backward_bf16_gradients_ms": bwd16_ms,
+            "sta_backward_bf16_gradients_frac_of_hbm_peak": (nvalid * (dq + d) * 2 + U * C * S * d * 2 + U * L * (dq + d) * 2)
+            / (bwd16_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
             "sta_backward_ms": bwd_ms,
             "sta_backward_algorithmic_bytes": nvalid * (dq + d) * 2 + U * C * S * d * 2 + U * L * (dq + d) * 4,
             "sta_backward_frac_of_hbm_peak": (nvalid * (dq + d) * 2 + U * C * S * d * 2 + U * L * (dq + d) * 4)

@@ -338,6 +338,15 @@ laser_status laser_sta_backward(const void* q, const void* k, const void* v, con
                                 void* stream);
 
 /*
+ * The same with bf16 inputs and the two large gradients in bf16 as well: dk_out [U,L,d_q] and dv_out [U,L,d] in the
+ * storage type of k and v (fp32 sums rounded once), dq_out [U,C,d_q] fp32. Half the bytes of the pass's largest
+ * outputs. C <= 4, d_q in {32, 64, 128}, d in {64, 128}; otherwise LASER_ERR_UNSUPPORTED. Everything else as above.
+ */
+laser_status laser_sta_backward_bf16(const void* q, const void* k, const void* v, const int32_t* lens, const void* dseg,
+                                     int U, int C, int L, int d_q, int d, int w, float gamma, float* dq_out,
+                                     void* dk_out, void* dv_out, void* work, size_t work_bytes, void* stream);
+
+/*
  * Backward pass of GSTA (the derivatives of the forward equations of paper Sec. 3.4.3: per layer q' = t W_q,
  * e = (H' W_k) q' / sqrt(d), a = softmax over the valid segments, t <- t + a (H' W_v); the paper prints no backward
  * formulas). Given dz = d loss / d z [U,C,d] (fp32):

@@ -28,7 +28,7 @@ EXPORTS = [
     "laser_gsta_kernel_name", "laser_segment_ffn_forward", "laser_segment_ffn_forward_variant",
     "laser_gsta_kernel_name_layers", "laser_project_q_forward", "laser_project_q_forward_variant",
     "laser_project_kv_forward", "laser_project_kv_forward_variant", "laser_fold_query_weights",
-    "laser_project_heads_forward", "laser_sta_folded_forward", "laser_sta_backward", "laser_sta_backward_work_bytes", "laser_gsta_backward",
+    "laser_project_heads_forward", "laser_sta_folded_forward", "laser_sta_backward", "laser_sta_backward_bf16", "laser_sta_backward_work_bytes", "laser_gsta_backward",
     "laser_gsta_backward_work_bytes",
     "laser_status_string", "laser_version",
 ]
@@ -104,6 +104,9 @@ def load_library() -> ctypes.CDLL:
     lib.laser_sta_backward.argtypes = [vp, vp, vp, ip, vp, i32, i32, i32, i32, i32, i32, f32, i32, vp, vp, vp, vp,
                                        ctypes.c_size_t, vp]
     lib.laser_sta_backward.restype = i32
+    lib.laser_sta_backward_bf16.argtypes = [vp, vp, vp, ip, vp, i32, i32, i32, i32, i32, i32, f32, vp, vp, vp, vp,
+                                            ctypes.c_size_t, vp]
+    lib.laser_sta_backward_bf16.restype = i32
     lib.laser_gsta_backward_work_bytes.argtypes = [i32, i32, i32, i32]
     lib.laser_gsta_backward_work_bytes.restype = ctypes.c_size_t
     lib.laser_gsta_backward.argtypes = [vp, vp, vp, vp, vp, ip, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp,
@@ -343,8 +346,9 @@ def laser_forward_ragged(q, k, v, t0, wq, wk, wv, lens, cand_off, c_max: int, w:
 
 
 def laser_sta_backward(q, k, v, lens, dseg, w: int, gamma: float, dq_out=None, dk_out=None, dv_out=None, work=None,
-                       stream=None):
-    """Gradients of STA: dseg = dL/dH' [U,C,S,d] (dtype of q) -> (dq [U,C,d_q], dk [U,L,d_q], dv [U,L,d]) in fp32."""
+                       stream=None, grads_bf16: bool = False):
+    """Gradients of STA: dseg = dL/dH' [U,C,S,d] (dtype of q) -> (dq [U,C,d_q], dk [U,L,d_q], dv [U,L,d]) in fp32;
+    with grads_bf16 (bf16 inputs) dk and dv come back in bf16 (laser_sta_backward_bf16)."""
     torch = _torch()
     U, C, d_q = q.shape
     L, d = v.shape[1], v.shape[2]
@@ -355,12 +359,24 @@ def laser_sta_backward(q, k, v, lens, dseg, w: int, gamma: float, dq_out=None, d
         raise TypeError("q, k, v and dseg must share a dtype")
     f32 = dict(dtype=torch.float32, device=q.device)
     dq_out = torch.empty((U, C, d_q), **f32) if dq_out is None else dq_out
-    dk_out = torch.empty((U, L, d_q), **f32) if dk_out is None else dk_out
-    dv_out = torch.empty((U, L, d), **f32) if dv_out is None else dv_out
+    gkw = dict(dtype=torch.bfloat16, device=q.device) if grads_bf16 else f32
+    dk_out = torch.empty((U, L, d_q), **gkw) if dk_out is None else dk_out
+    dv_out = torch.empty((U, L, d), **gkw) if dv_out is None else dv_out
     lib = load_library()
     need = lib.laser_sta_backward_work_bytes(U, C, L, d_q, int(w))
     if work is None:
         work = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    if grads_bf16:
+        if q.dtype != torch.bfloat16:
+            raise TypeError("grads_bf16 needs bf16 inputs")
+        code = lib.laser_sta_backward_bf16(_ptr(q, "q"), _ptr(k, "k"), _ptr(v, "v"), _ptr(lens, "lens", torch.int32),
+                                           _ptr(dseg, "dseg"), U, C, L, d_q, d, int(w), float(gamma),
+                                           _ptr(dq_out, "dq_out", torch.float32),
+                                           _ptr(dk_out, "dk_out", torch.bfloat16),
+                                           _ptr(dv_out, "dv_out", torch.bfloat16), _ptr(work, "work"),
+                                           work.numel() * work.element_size(), _stream(stream))
+        _check(code, "laser_sta_backward_bf16")
+        return dq_out, dk_out, dv_out
     code = lib.laser_sta_backward(_ptr(q, "q"), _ptr(k, "k"), _ptr(v, "v"), _ptr(lens, "lens", torch.int32),
                                   _ptr(dseg, "dseg"), U, C, L, d_q, d, int(w), float(gamma), _dt(q),
                                   _ptr(dq_out, "dq_out", torch.float32), _ptr(dk_out, "dk_out", torch.float32),

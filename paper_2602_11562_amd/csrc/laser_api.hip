@@ -469,9 +469,10 @@ size_t laser_sta_backward_work_bytes(int U, int C, int L, int d_q, int w) {
   return sta_backward_work_bytes(U, C, L, d_q, w);
 }
 
-laser_status laser_sta_backward(const void* q, const void* k, const void* v, const int32_t* lens, const void* dseg, int U,
-                                int C, int L, int d_q, int d, int w, float gamma, laser_dtype dt, float* dq_out,
-                                float* dk_out, float* dv_out, void* work, size_t work_bytes, void* stream) {
+static laser_status sta_backward_any(const void* q, const void* k, const void* v, const int32_t* lens, const void* dseg,
+                                     int U, int C, int L, int d_q, int d, int w, float gamma, laser_dtype dt,
+                                     float* dq_out, void* dk_out, void* dv_out, bool grads_bf16, void* work,
+                                     size_t work_bytes, void* stream) {
   if (!dseg || !dq_out || !dk_out || !dv_out || !work) return LASER_ERR_NULL;
   StaArgs fa;   // the forward pass's checks of the shared arguments (dseg stands in for seg_out: same shape and type)
   laser_status s = validate_sta(q, k, v, lens, U, C, L, d_q, d, w, gamma, dt, const_cast<void*>(dseg), nullptr, stream,
@@ -479,9 +480,24 @@ laser_status laser_sta_backward(const void* q, const void* k, const void* v, con
   if (s != LASER_OK) return s;
   if (!aligned16(dq_out) || !aligned16(dk_out) || !aligned16(dv_out) || !aligned16(work)) return LASER_ERR_ALIGN;
   if (work_bytes < sta_backward_work_bytes(U, C, L, d_q, w)) return LASER_ERR_SHAPE;
-  const StaBwdArgs a{q, k, v, dseg, lens, U, C, L, d_q, d, w, fa.S, gamma, dt, dq_out, dk_out, dv_out,
-                     static_cast<float*>(work), static_cast<hipStream_t>(stream)};
+  StaBwdArgs a{q, k, v, dseg, lens, U, C, L, d_q, d, w, fa.S, gamma, dt, dq_out, dk_out, dv_out,
+               static_cast<float*>(work), static_cast<hipStream_t>(stream)};
+  a.grads_bf16 = grads_bf16;
   return sta_backward_launch(a);
+}
+
+laser_status laser_sta_backward(const void* q, const void* k, const void* v, const int32_t* lens, const void* dseg, int U,
+                                int C, int L, int d_q, int d, int w, float gamma, laser_dtype dt, float* dq_out,
+                                float* dk_out, float* dv_out, void* work, size_t work_bytes, void* stream) {
+  return sta_backward_any(q, k, v, lens, dseg, U, C, L, d_q, d, w, gamma, dt, dq_out, dk_out, dv_out, false, work,
+                          work_bytes, stream);
+}
+
+laser_status laser_sta_backward_bf16(const void* q, const void* k, const void* v, const int32_t* lens, const void* dseg,
+                                     int U, int C, int L, int d_q, int d, int w, float gamma, float* dq_out,
+                                     void* dk_out, void* dv_out, void* work, size_t work_bytes, void* stream) {
+  return sta_backward_any(q, k, v, lens, dseg, U, C, L, d_q, d, w, gamma, LASER_BF16, dq_out, dk_out, dv_out, true, work,
+                          work_bytes, stream);
 }
 
 size_t laser_gsta_backward_work_bytes(int U, int C, int d, int M) {

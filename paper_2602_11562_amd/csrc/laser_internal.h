@@ -126,10 +126,11 @@ struct StaBwdArgs {        // gradients of STA: dq [U,C,d_q], dk [U,L,d_q], dv [
   float gamma;
   laser_dtype dt;
   float* dq;
-  float* dk;
-  float* dv;
+  void* dk;                // fp32, or bf16 when grads_bf16
+  void* dv;
   float* work;             // [U, groups, C, d_q] partial dq sums, sta_backward_work_bytes() bytes
   hipStream_t stream;
+  bool grads_bf16 = false; // dk and dv in bf16 (the storage type of k and v)
 };
 bool sta_backward_supports(const StaBwdArgs& a);
 size_t sta_backward_work_bytes(int U, int C, int L, int d_q, int w);

@@ -16,6 +16,7 @@
 // In both, dq is summed over a workgroup's waves in LDS and over a user's workgroups by a second small kernel, in a
 // fixed order (deterministic), and items at or past the valid length get zero gradients.
 #include <cstdlib>
+#include <type_traits>
 
 #include "laser_internal.h"
 
@@ -166,7 +167,9 @@ __device__ __forceinline__ void unpack8b(const u32x4b& r, float (&x)[8]) {
   }
 }
 
-template <int DQ, int D, int CMAX>
+// GB16: dk and dv are written in bf16 (the storage type of k and v: half the bytes of the two largest outputs) instead
+// of fp32; the sums are fp32 either way and rounded once.
+template <int DQ, int D, int CMAX, bool GB16>
 __global__ __launch_bounds__(256) void sta_bwd_wide_kernel(const unsigned short* __restrict__ q,
                                                            const unsigned short* __restrict__ k,
                                                            const unsigned short* __restrict__ v,
@@ -174,8 +177,9 @@ __global__ __launch_bounds__(256) void sta_bwd_wide_kernel(const unsigned short*
                                                            const int32_t* __restrict__ lens, int C, int L, int w, int S,
                                                            int spg, int groups, int users, int classes,
                                                            float neg_scale_log2e, float inv_gamma,
-                                                           float* __restrict__ dk, float* __restrict__ dv,
+                                                           void* __restrict__ dk, void* __restrict__ dv,
                                                            float* __restrict__ dq_part) {
+  typedef typename std::conditional<GB16, unsigned short, float>::type G;   // element type of dk and dv
   constexpr int LQ = DQ / 8, LV = D / 8;           // lanes per key row / value row
   constexpr int RQ = 64 / LQ, RV = 64 / LV;        // rows per wave-wide load
   constexpr int IPC = RQ > RV ? RQ : RV;           // items per chunk
@@ -204,8 +208,21 @@ __global__ __launch_bounds__(256) void sta_bwd_wide_kernel(const unsigned short*
   const int i_end = (grp + 1) * spg < S ? (grp + 1) * spg : S;
   const unsigned short* kU = k + (size_t)u * L * DQ;
   const unsigned short* vU = v + (size_t)u * L * D;
-  float* dkU = dk + (size_t)u * L * DQ;
-  float* dvU = dv + (size_t)u * L * D;
+  G* dkU = static_cast<G*>(dk) + (size_t)u * L * DQ;
+  G* dvU = static_cast<G*>(dv) + (size_t)u * L * D;
+  auto store8 = [](G* dst, const float (&x)[8]) {   // eight consecutive gradient values: 16 or 32 bytes
+    if constexpr (GB16) {
+      u32x4b o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        o[e] = (unsigned)f32_to_bf16_bits(x[2 * e]) | ((unsigned)f32_to_bf16_bits(x[2 * e + 1]) << 16);
+      *reinterpret_cast<u32x4b*>(dst) = o;
+    } else {
+      f32x4b* d4 = reinterpret_cast<f32x4b*>(dst);
+      d4[0] = f32x4b{x[0], x[1], x[2], x[3]};
+      d4[1] = f32x4b{x[4], x[5], x[6], x[7]};
+    }
+  };
 
   float qf[CMAX][8], dqacc[CMAX][8];
 #pragma unroll
@@ -304,30 +321,23 @@ __global__ __launch_bounds__(256) void sta_bwd_wide_kernel(const unsigned short*
 #pragma unroll
         for (int kl = 0; kl < NKL; ++kl) {
           const int row = base + kl * RQ + rq;
-          if (row < hi) {
-            f32x4b* dst = reinterpret_cast<f32x4b*>(dkU + (size_t)row * DQ + cq * 8);
-            dst[0] = f32x4b{dka[kl][0], dka[kl][1], dka[kl][2], dka[kl][3]};
-            dst[1] = f32x4b{dka[kl][4], dka[kl][5], dka[kl][6], dka[kl][7]};
-          }
+          if (row < hi) store8(dkU + (size_t)row * DQ + cq * 8, dka[kl]);
         }
 #pragma unroll
         for (int vl = 0; vl < NVL; ++vl) {
           const int row = base + vl * RV + rv;
-          if (row < hi) {
-            f32x4b* dst = reinterpret_cast<f32x4b*>(dvU + (size_t)row * D + cv * 8);
-            dst[0] = f32x4b{dva[vl][0], dva[vl][1], dva[vl][2], dva[vl][3]};
-            dst[1] = f32x4b{dva[vl][4], dva[vl][5], dva[vl][6], dva[vl][7]};
-          }
+          if (row < hi) store8(dvU + (size_t)row * D + cv * 8, dva[vl]);
         }
       }
     }
     // items of the segment at or past the valid length: zero gradients
     const int z0 = hi > lo ? hi : lo;
     const f32x4b zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+    constexpr int PER16 = 16 / (int)sizeof(G);   // gradient elements per 16-byte store
     f32x4b* zk = reinterpret_cast<f32x4b*>(dkU + (size_t)z0 * DQ);
     f32x4b* zv = reinterpret_cast<f32x4b*>(dvU + (size_t)z0 * D);
-    for (int e = lane; e < (hi_all - z0) * DQ / 4; e += 64) __builtin_nontemporal_store(zero4, zk + e);
-    for (int e = lane; e < (hi_all - z0) * D / 4; e += 64) __builtin_nontemporal_store(zero4, zv + e);
+    for (int e = lane; e < (hi_all - z0) * DQ / PER16; e += 64) __builtin_nontemporal_store(zero4, zk + e);
+    for (int e = lane; e < (hi_all - z0) * D / PER16; e += 64) __builtin_nontemporal_store(zero4, zv + e);
   }
   // dq of the run: the row groups of a wave, then the waves, in a fixed order
 #pragma unroll
@@ -374,6 +384,8 @@ static void sta_bwd_shape(int U, int S, int w, int* spg, int* groups) {
   *groups = (S + *spg - 1) / *spg;
 }
 
+static bool sta_bwd_wide_supports(const StaBwdArgs& a);
+
 // length classes: worth their empty workgroups once the launch is several rounds of workgroups and lengths differ
 static int sta_bwd_classes(const StaBwdArgs& a, unsigned blocks) {
   int classes = (a.lens != nullptr && blocks >= 4096 && (unsigned long long)blocks * 4 <= 0x7fffffffULL) ? 4 : 1;
@@ -385,6 +397,7 @@ static int sta_bwd_classes(const StaBwdArgs& a, unsigned blocks) {
 }
 
 bool sta_backward_supports(const StaBwdArgs& a) {
+  if (a.grads_bf16) return sta_bwd_wide_supports(a);   // bf16 gradients: the wide kernel only
   return a.C <= SB_CMAX && a.d_q <= 64 * SB_TMAX && a.d <= 64 * SB_TMAX;
 }
 
@@ -402,7 +415,7 @@ static void sta_bwd_launch_c(const StaBwdArgs& a, unsigned blocks, size_t lds, i
 #define LASER_BWD_LAUNCH(CM)                                                                                          \
   hipLaunchKernelGGL((sta_bwd_kernel<T, TQ, TV, CM>), dim3(blocks * classes), dim3(256), lds, a.stream,               \
                      (const T*)a.q, (const T*)a.k, (const T*)a.v, (const T*)a.dhp, a.lens, a.C, a.L, a.d_q, a.d, a.w, \
-                     a.S, spg, groups, a.U, classes, nsl, inv_gamma, a.dk, a.dv, a.work)
+                     a.S, spg, groups, a.U, classes, nsl, inv_gamma, static_cast<float*>(a.dk), static_cast<float*>(a.dv), a.work)
   if (a.C <= 1) LASER_BWD_LAUNCH(1);
   else if (a.C <= 4) LASER_BWD_LAUNCH(4);
   else LASER_BWD_LAUNCH(8);
@@ -436,10 +449,18 @@ static void sta_bwd_wide_launch(const StaBwdArgs& a, unsigned blocks, int spg, i
   const float nsl = -1.4426950408889634f * inv_gamma;
   const int classes = sta_bwd_classes(a, blocks);
 #define LASER_BWD_WIDE(CM)                                                                                           \
-  hipLaunchKernelGGL((sta_bwd_wide_kernel<DQ, D, CM>), dim3(blocks * classes), dim3(256), 0, a.stream,              \
-                     (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v,            \
-                     (const unsigned short*)a.dhp, a.lens, a.C, a.L, a.w, a.S, spg, groups, a.U, classes, nsl,      \
-                     inv_gamma, a.dk, a.dv, a.work)
+  do {                                                                                                               \
+    if (a.grads_bf16)                                                                                                \
+      hipLaunchKernelGGL((sta_bwd_wide_kernel<DQ, D, CM, true>), dim3(blocks * classes), dim3(256), 0, a.stream,    \
+                         (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v,        \
+                         (const unsigned short*)a.dhp, a.lens, a.C, a.L, a.w, a.S, spg, groups, a.U, classes, nsl,  \
+                         inv_gamma, a.dk, a.dv, a.work);                                                             \
+    else                                                                                                             \
+      hipLaunchKernelGGL((sta_bwd_wide_kernel<DQ, D, CM, false>), dim3(blocks * classes), dim3(256), 0, a.stream,   \
+                         (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v,        \
+                         (const unsigned short*)a.dhp, a.lens, a.C, a.L, a.w, a.S, spg, groups, a.U, classes, nsl,  \
+                         inv_gamma, a.dk, a.dv, a.work);                                                             \
+  } while (0)
   if (a.C <= 1) LASER_BWD_WIDE(1);
   else if (a.C <= 2) LASER_BWD_WIDE(2);
   else LASER_BWD_WIDE(4);

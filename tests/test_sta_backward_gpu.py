@@ -101,3 +101,37 @@ def test_sta_backward_refuses_what_it_does_not_take():
         laser.laser_sta_backward(z(1, 1, 32), z(1, 64, 32), z(1, 64, 32), None, z(1, 1, 8, 32), 8, 1.0,
                                  work=torch.zeros(16, dtype=torch.uint8, device="cuda"))
     assert e.value.code == 2      # scratch too small
+
+
+@pytest.mark.parametrize("name", ["paper_setting", "one_user_many_runs", "three_candidates_wide_keys",
+                                  "two_candidates_same_widths", "four_candidates_narrow_keys"])
+def test_sta_backward_with_bf16_gradients(name):
+    """dk and dv in the storage type: the fp32 sums of the fp32-output call, rounded once to bf16 (bit for bit), so the
+    error against the checker is the fp32 error plus one rounding (2^-9 relative: tolerance 2e-2 as for every bf16
+    output); dq stays fp32 and identical."""
+    import torch
+    dtype, C, L, dq, d, w, lens = CASES[name]
+    U, S = len(lens), -(-L // w)
+    rng = np.random.default_rng(2100 + sum(map(ord, name)))
+    (qs, qv), (ks, kv), (vs, vv), (gs, gv) = (_store(rng.normal(size=s), dtype)
+                                              for s in ((U, C, dq), (U, L, dq), (U, L, d), (U, C, S, d)))
+    lens = np.array(lens, dtype=np.int32)
+    gamma = math.sqrt(dq)
+    args = (to_device(qs), to_device(ks), to_device(vs), to_device(lens), to_device(gs), w, gamma)
+    full = laser.laser_sta_backward(*args)
+    low = laser.laser_sta_backward(*args, grads_bf16=True)
+    torch.cuda.synchronize()
+    assert low[1].dtype == torch.bfloat16 and low[2].dtype == torch.bfloat16
+    assert torch.equal(full[0], low[0])
+    assert torch.equal(full[1].bfloat16(), low[1]) and torch.equal(full[2].bfloat16(), low[2])
+    ref = oracle.sta_backward(qv, kv, vv, lens, w, gamma, gv)
+    assert vec_rel_err(to_host_f64(low[2]), ref[2]) <= 2e-2
+    assert vec_rel_err(to_host_f64(low[1]).reshape(U, -1), ref[1].reshape(U, -1)) <= 2e-2
+
+
+def test_bf16_gradients_need_the_wide_kernel():
+    import torch
+    z = lambda *s: torch.zeros(*s, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(laser.LaserError) as e:     # eight candidates: only the fp32-output kernel takes them
+        laser.laser_sta_backward(z(1, 8, 32), z(1, 64, 32), z(1, 64, 32), None, z(1, 8, 8, 32), 8, 1.0, grads_bf16=True)
+    assert e.value.code == 4
