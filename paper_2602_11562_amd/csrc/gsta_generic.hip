@@ -41,6 +41,7 @@ __global__ __launch_bounds__(256) void gsta_generic_kernel(const T* __restrict__
     __syncthreads();
     for (int b = tid; b < d; b += 256) {
       float s = 0.0f;
+#pragma unroll 8
       for (int a = 0; a < d; ++a) s = fmaf(ts[a], load_as_f32(Wq, (size_t)a * d + b), s);
       qp[b] = s;
     }
@@ -77,12 +78,14 @@ __global__ __launch_bounds__(256) void gsta_generic_kernel(const T* __restrict__
     __syncthreads();
     for (int b = tid; b < d; b += 256) {
       float s = 0.0f;
+#pragma unroll 8
       for (int i = 0; i < nv; ++i) s = fmaf(es[i], load_as_f32(H, (size_t)i * d + b), s);
       pp[b] = s;
     }
     __syncthreads();
     for (int b = tid; b < d; b += 256) {
       float s = 0.0f;
+#pragma unroll 8
       for (int a = 0; a < d; ++a) s = fmaf(pp[a], load_as_f32(Wv, (size_t)a * d + b), s);
       ts[b] += s;                           // residual update of the target
     }

@@ -70,14 +70,17 @@ __global__ __launch_bounds__(256) void sta_generic_kernel(const T* __restrict__ 
 
   const T* kU = k + (size_t)u * L * dq;
   const T* vU = v + (size_t)u * L * d;
+  const int nb = (d + 63) >> 6;   // blocks of 64 columns in use
 
   for (int j0 = lo; j0 < hi; j0 += TI) {
     const int nj = (hi - j0) < TI ? (hi - j0) : TI;
     __syncthreads();
-    for (int e = tid; e < nj * dq; e += 256) {
+#pragma unroll 8
+    for (int e = tid; e < nj * dq; e += 256) {   // unrolled so that the loads of several rounds are in flight together
       const int r = e / dq, a = e - r * dq;
       Ks[r * kpitch + a] = load_as_f32(kU, (size_t)(j0 + r) * dq + a);
     }
+#pragma unroll 8
     for (int e = tid; e < nj * d; e += 256) Vs[e] = load_as_f32(vU, (size_t)j0 * d + e);
     __syncthreads();
     if (lane < nj) {
@@ -85,15 +88,18 @@ __global__ __launch_bounds__(256) void sta_generic_kernel(const T* __restrict__ 
       const float* qr = qs + wave * dq;
       for (int hh = 0; hh < heads; ++hh) {
         float e = 0.0f;
+#pragma unroll 8
         for (int a = hh * dqh; a < (hh + 1) * dqh; ++a) e = fmaf(qr[a], kr[a], e);
         gs[(wave * heads + hh) * TI + lane] =
             softmax ? e * inv_gamma : 1.0f / (1.0f + expf(-e * inv_gamma));   // independent gate per item
       }
     }
     __syncthreads();
+#pragma unroll 4
     for (int jj = 0; jj < nj; ++jj) {
 #pragma unroll
       for (int b = 0; b < GEN_MAX_COLS; ++b) {
+        if (b >= nb) break;   // the same for the whole wave: blocks past d cost nothing
         const int col = lane + 64 * b;
         if (col < d) {
           const float g = gs[(wave * heads + col / dh) * TI + jj];
