@@ -194,8 +194,8 @@ def main() -> int:
                     help="also time the packed-pairs entry point with a seeded ragged candidate count per user "
                          "(uniform between a quarter of C and C); reported under \"ragged\"")
     ap.add_argument("--backward", action="store_true",
-                    help="also time the backward pass of GSTA on the workload's H' (and of STA when the workload has "
-                         "at most 8 candidates per user); reported under \"backward\"")
+                    help="also time the backward pass of GSTA on the workload's H' and of STA (built for at most 8 "
+                         "candidates per user; more are taken 8 at a time); reported under \"backward\"")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device copy 5 times (reference reading for the FETCH_SIZE / "
                          "WRITE_SIZE counters when this command runs under rocprofv3 --pmc)")
@@ -438,7 +438,7 @@ def main() -> int:
                                 "frac_of_hbm_peak": g_b / (g_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
         except laser.LaserError as e:
             backward["gsta"] = {"error": str(e)}
-        if spec.C <= 8:
+        if spec.d_q <= 256 and spec.d <= 256:
             dseg = torch.randn(spec.U, spec.C, spec.S, spec.d, device="cuda", generator=gen).to(tdt)
             swork = torch.empty(max(16, lib.laser_sta_backward_work_bytes(spec.U, spec.C, spec.L, spec.d_q, spec.w)),
                                 dtype=torch.uint8, device="cuda")

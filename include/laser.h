@@ -324,8 +324,9 @@ laser_status laser_sta_folded_forward(const void* t, const void* h, const void* 
  * over the valid items j < lens[u]; items at or past the valid length get zeros (all outputs are fully overwritten).
  * q, k, v, lens, sizes and gamma as for laser_sta_forward (one head, sigmoid gates). Arithmetic in fp32 from the stored
  * inputs; sums in a fixed order (results are reproducible run to run).
- * Built for training batches, which hold one or a few targets per sample: C <= 8 and d_q, d <= 256; other shapes
- * return LASER_ERR_UNSUPPORTED. work is caller-owned scratch of at least laser_sta_backward_work_bytes(U, C, L, d_q, w)
+ * Built for training batches, which hold one or a few targets per sample: d_q, d <= 256 (wider rows return
+ * LASER_ERR_UNSUPPORTED), and up to eight candidates per user in one pass over k and v; more are taken eight at a
+ * time, one pass each, the later passes adding to dk_out and dv_out (correct for any C, fast for few). work is caller-owned scratch of at least laser_sta_backward_work_bytes(U, C, L, d_q, w)
  * bytes (partial dq sums; contents unspecified on return); the library allocates nothing.
  * All pointers are device pointers, 16-byte aligned (lens 4-byte); work is enqueued on `stream`.
  * Errors: LASER_ERR_NULL, LASER_ERR_SHAPE (sizes, gamma, work_bytes too small), LASER_ERR_DTYPE, LASER_ERR_ALIGN,

@@ -28,7 +28,8 @@ constexpr int SB_TMAX = 4;    // 64-element slices per row: d_q, d <= 256
 template <typename T, int TQ, int TV, int CMAX>   // TQ, TV: 64-element slices of a key / value row; CMAX >= C
 __global__ __launch_bounds__(256) void sta_bwd_kernel(const T* __restrict__ q, const T* __restrict__ k,
                                                       const T* __restrict__ v, const T* __restrict__ dhp,
-                                                      const int32_t* __restrict__ lens, int C, int L, int dq, int d, int w,
+                                                      const int32_t* __restrict__ lens, int C_all, int c0, int C,
+                                                      int accumulate, int L, int dq, int d, int w,
                                                       int S, int spg, int groups, int users, int classes,
                                                       float neg_scale_log2e, float inv_gamma,
                                                       float* __restrict__ dk, float* __restrict__ dv,
@@ -61,7 +62,7 @@ __global__ __launch_bounds__(256) void sta_bwd_kernel(const T* __restrict__ q, c
 #pragma unroll
     for (int t = 0; t < TQ; ++t) {
       const int e = lane + 64 * t;
-      qr[c][t] = (c < C && e < dq) ? load_as_f32(q, ((size_t)u * C + c) * dq + e) : 0.0f;
+      qr[c][t] = (c < C && e < dq) ? load_as_f32(q, ((size_t)u * C_all + c0 + c) * dq + e) : 0.0f;
       dqacc[c][t] = 0.0f;
     }
 
@@ -79,7 +80,7 @@ __global__ __launch_bounds__(256) void sta_bwd_kernel(const T* __restrict__ q, c
 #pragma unroll
         for (int t = 0; t < TV; ++t) {
           const int e = lane + 64 * t;
-          dh[c][t] = (c < C && e < d) ? load_as_f32(dhp, (((size_t)u * C + c) * S + i) * d + e) : 0.0f;
+          dh[c][t] = (c < C && e < d) ? load_as_f32(dhp, (((size_t)u * C_all + c0 + c) * S + i) * d + e) : 0.0f;
         }
       // the rows of the next item are requested before the current one is worked on (an item is a chain of load, two
       // wave-wide sums, a gate and two stores; only other waves and this prefetch hide the load)
@@ -119,12 +120,19 @@ __global__ __launch_bounds__(256) void sta_bwd_kernel(const T* __restrict__ q, c
             }
           }
         }
+        // (a later block of candidates adds to what the blocks before it left: the same wave owned the item then)
 #pragma unroll
         for (int t = 0; t < TQ; ++t)
-          if (lane + 64 * t < dq) dkU[(size_t)j * dq + lane + 64 * t] = dka[t];
+          if (lane + 64 * t < dq) {
+            float* o = dkU + (size_t)j * dq + lane + 64 * t;
+            *o = accumulate ? *o + dka[t] : dka[t];
+          }
 #pragma unroll
         for (int t = 0; t < TV; ++t)
-          if (lane + 64 * t < d) dvU[(size_t)j * d + lane + 64 * t] = dva[t];
+          if (lane + 64 * t < d) {
+            float* o = dvU + (size_t)j * d + lane + 64 * t;
+            *o = accumulate ? *o + dva[t] : dva[t];
+          }
       }
     }
     // items of the segment at or past the valid length: zero gradients
@@ -134,8 +142,10 @@ __global__ __launch_bounds__(256) void sta_bwd_kernel(const T* __restrict__ q, c
     const f32x4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
     f32x4* zk = reinterpret_cast<f32x4*>(dkU + (size_t)z0 * dq);
     f32x4* zv = reinterpret_cast<f32x4*>(dvU + (size_t)z0 * d);
-    for (int e = lane; e < (hi_all - z0) * dq / 4; e += 64) __builtin_nontemporal_store(zero4, zk + e);
-    for (int e = lane; e < (hi_all - z0) * d / 4; e += 64) __builtin_nontemporal_store(zero4, zv + e);
+    if (!accumulate) {
+      for (int e = lane; e < (hi_all - z0) * dq / 4; e += 64) __builtin_nontemporal_store(zero4, zk + e);
+      for (int e = lane; e < (hi_all - z0) * d / 4; e += 64) __builtin_nontemporal_store(zero4, zv + e);
+    }
   }
   // dq of the run: waves in a fixed order
 #pragma unroll
@@ -146,7 +156,7 @@ __global__ __launch_bounds__(256) void sta_bwd_kernel(const T* __restrict__ q, c
         if (lane + 64 * t < dq) red[(wave * C + c) * dq + lane + 64 * t] = dqacc[c][t];
   __syncthreads();
   for (int e = tid; e < C * dq; e += 256)
-    dq_part[((size_t)u * groups + grp) * C * dq + e] =
+    dq_part[(((size_t)u * groups + grp) * C_all + c0) * dq + e] =
         ((red[e] + red[C * dq + e]) + red[2 * C * dq + e]) + red[3 * C * dq + e];
 }
 
@@ -398,7 +408,7 @@ static int sta_bwd_classes(const StaBwdArgs& a, unsigned blocks) {
 
 bool sta_backward_supports(const StaBwdArgs& a) {
   if (a.grads_bf16) return sta_bwd_wide_supports(a);   // bf16 gradients: the wide kernel only
-  return a.C <= SB_CMAX && a.d_q <= 64 * SB_TMAX && a.d <= 64 * SB_TMAX;
+  return a.d_q <= 64 * SB_TMAX && a.d <= 64 * SB_TMAX;   // any number of candidates, SB_CMAX at a time
 }
 
 size_t sta_backward_work_bytes(int U, int C, int L, int d_q, int w) {
@@ -412,13 +422,19 @@ static void sta_bwd_launch_c(const StaBwdArgs& a, unsigned blocks, size_t lds, i
   const float inv_gamma = 1.0f / a.gamma;
   const float nsl = -1.4426950408889634f * inv_gamma;
   const int classes = sta_bwd_classes(a, blocks);
+  // more than SB_CMAX candidates per user: one launch per block of SB_CMAX, in order on the stream; the first
+  // writes dk and dv (and the zeros of the padding rows), the others add to them
 #define LASER_BWD_LAUNCH(CM)                                                                                          \
   hipLaunchKernelGGL((sta_bwd_kernel<T, TQ, TV, CM>), dim3(blocks * classes), dim3(256), lds, a.stream,               \
-                     (const T*)a.q, (const T*)a.k, (const T*)a.v, (const T*)a.dhp, a.lens, a.C, a.L, a.d_q, a.d, a.w, \
-                     a.S, spg, groups, a.U, classes, nsl, inv_gamma, static_cast<float*>(a.dk), static_cast<float*>(a.dv), a.work)
-  if (a.C <= 1) LASER_BWD_LAUNCH(1);
-  else if (a.C <= 4) LASER_BWD_LAUNCH(4);
-  else LASER_BWD_LAUNCH(8);
+                     (const T*)a.q, (const T*)a.k, (const T*)a.v, (const T*)a.dhp, a.lens, a.C, c0, cn, c0 > 0 ? 1 : 0, \
+                     a.L, a.d_q, a.d, a.w, a.S, spg, groups, a.U, classes, nsl, inv_gamma,                             \
+                     static_cast<float*>(a.dk), static_cast<float*>(a.dv), a.work)
+  for (int c0 = 0; c0 < a.C; c0 += SB_CMAX) {
+    const int cn = a.C - c0 < SB_CMAX ? a.C - c0 : SB_CMAX;
+    if (cn <= 1) LASER_BWD_LAUNCH(1);
+    else if (cn <= 4) LASER_BWD_LAUNCH(4);
+    else LASER_BWD_LAUNCH(8);
+  }
 #undef LASER_BWD_LAUNCH
 }
 
@@ -473,7 +489,7 @@ laser_status sta_backward_launch(const StaBwdArgs& a) {
   sta_bwd_shape(a.U, a.S, a.w, &spg, &groups);
   const long long blocks = (long long)a.U * groups;
   if (blocks > 0x7fffffffLL) return LASER_ERR_SHAPE;
-  const size_t lds = sizeof(float) * (size_t)a.C * a.d_q * 4;
+  const size_t lds = sizeof(float) * (size_t)(a.C < SB_CMAX ? a.C : SB_CMAX) * a.d_q * 4;
   if (sta_bwd_wide_supports(a)) {
     const unsigned nb = (unsigned)blocks;
     switch (a.d_q * 1000 + a.d) {

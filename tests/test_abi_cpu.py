@@ -246,7 +246,7 @@ def test_sta_backward_argument_validation(lib):
     for kw in ({"U": 0}, {"C": 0}, {"w": 0}, {"gamma": 0.0}, {"d": 12}, {"wb": 8}):
         assert f(**kw) == SHAPE, kw
     assert f(dko=A + 4) == ALIGN and f(work=A + 8) == ALIGN
-    assert f(C=9) == UNSUP and f(dq=512, d=512) == UNSUP
+    assert f(dq=512, d=512) == UNSUP
 
 
 def test_gsta_backward_argument_validation(lib):

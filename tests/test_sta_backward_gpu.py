@@ -31,6 +31,10 @@ CASES = {
     "two_candidates_same_widths": ("bf16", 2, 700, 128, 128, 64, [700, 65, 64]),
     "four_candidates_narrow_keys": ("bf16", 4, 1500, 64, 128, 300, [1500, 301]),
     "odd_widths_f32": ("f32", 3, 130, 24, 48, 16, [130, 50]),
+    # more than eight candidates per user: blocks of eight, one launch each, the later ones adding to dk and dv
+    "nine_candidates": ("bf16", 9, 300, 64, 64, 64, [300, 65, 0]),
+    "twenty_candidates_f32": ("f32", 20, 130, 24, 48, 16, [130, 50]),
+    "seventeen_candidates_wide": ("bf16", 17, 200, 128, 128, 32, [200, 33]),
     "f32_paper_setting": ("f32", 1, 200, 32, 128, 10, [200, 33, 0]),
 }
 
@@ -95,8 +99,8 @@ def test_sta_backward_refuses_what_it_does_not_take():
     import torch
     z = lambda *s: torch.zeros(*s, dtype=torch.bfloat16, device="cuda")
     with pytest.raises(laser.LaserError) as e:
-        laser.laser_sta_backward(z(1, 9, 32), z(1, 64, 32), z(1, 64, 32), None, z(1, 9, 8, 32), 8, 1.0)
-    assert e.value.code == 4      # more than eight candidates per user
+        laser.laser_sta_backward(z(1, 2, 512), z(1, 64, 512), z(1, 64, 32), None, z(1, 2, 8, 32), 8, 1.0)
+    assert e.value.code == 4      # rows of more than 256 elements
     with pytest.raises(laser.LaserError) as e:
         laser.laser_sta_backward(z(1, 1, 32), z(1, 64, 32), z(1, 64, 32), None, z(1, 1, 8, 32), 8, 1.0,
                                  work=torch.zeros(16, dtype=torch.uint8, device="cuda"))
