@@ -99,7 +99,7 @@ laser_status laser_sta_forward_variant(const void* q, const void* k, const void*
  * [h d/heads, (h+1) d/heads) of v and seg_out: every head is the STA above on its own columns, with the same gamma,
  * and the heads' outputs lie side by side, so all shapes and layouts are those of laser_sta_forward. heads = 1 is
  * laser_sta_forward_variant. heads must divide d_q and d (1 <= heads <= 64), else LASER_ERR_SHAPE. The streaming
- * kernel takes 1 or 2 heads (d_q/heads and d/heads multiples of 8); the matrix-core kernel takes one head; other
+ * kernel takes 1 or 2 heads (d_q/heads and d/heads multiples of 8); the matrix-core kernel takes 1 or 2 heads; other
  * cases run on the generic kernel (AUTO picks; a forced variant that does not take the case returns
  * LASER_ERR_UNSUPPORTED). Everything else as for laser_sta_forward.
  */

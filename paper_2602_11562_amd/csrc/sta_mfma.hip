@@ -103,7 +103,10 @@ struct Stage {
   }
 };
 
-template <int DQ, int D, int NW, int NBUF>
+// HEADS > 1 (Sec. 4.1.2): head h owns the h-th run of d_q / HEADS columns of q and k, a whole number of 16-wide
+// k-steps, and of d / HEADS columns of v and H', a whole number of 32-column blocks; one score block and one gate
+// per head, and every column block is aggregated with its own head's gates.
+template <int DQ, int D, int NW, int NBUF, int HEADS = 1>
 __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short* __restrict__ q,
                                                            const unsigned short* __restrict__ k,
                                                            const unsigned short* __restrict__ v,
@@ -116,6 +119,8 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short*
   constexpr int KP = KPitch<DQ>::v, VP = VPitch<D>::v;
   constexpr int NT = 64 * NW;
   constexpr int KSTEPS = DQ / 16, DB = D / 32;
+  constexpr int KH = KSTEPS / HEADS, DBH = DB / HEADS;   // k-steps and column blocks per head
+  static_assert(KSTEPS % HEADS == 0 && DB % HEADS == 0, "heads must own whole k-steps and whole column blocks");
   constexpr int OP = OPitch<D>::v;
   constexpr int KBYTES = TI * KP, VBYTES = TI * VP, OBYTES = CW * OP;
   __shared__ __attribute__((aligned(16))) unsigned char smem[NBUF * (KBYTES + VBYTES) + NW * OBYTES];
@@ -226,17 +231,21 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short*
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks)
           ka[ks] = *reinterpret_cast<const bf16x8*>(Ks + (ib * 32 + l32) * KP + (ks * 16 + h * 8) * 2);
-        f32x16 sc;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sc[r] = 0.0f;
-#pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[ks], sc, 0, 0, 0);
         // ---- gates, rounded to bf16: they become the B operand of the second product as they sit
-        bf16x8 p[2];
+        bf16x8 p[HEADS][2];
 #pragma unroll
-        for (int s = 0; s < 2; ++s)
+        for (int hd = 0; hd < HEADS; ++hd) {
+          f32x16 sc;
 #pragma unroll
-          for (int e = 0; e < 8; ++e) p[s][e] = (__bf16)gate(sc[s * 8 + e], neg_scale_log2e);
+          for (int r = 0; r < 16; ++r) sc[r] = 0.0f;
+#pragma unroll
+          for (int ks = hd * KH; ks < (hd + 1) * KH; ++ks)
+            sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[ks], sc, 0, 0, 0);
+#pragma unroll
+          for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) p[hd][s][e] = (__bf16)gate(sc[s * 8 + e], neg_scale_log2e);
+        }
         // ---- acc^T += V^T . P^T
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
@@ -252,7 +261,7 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short*
             const s16x4 hi4 =
                 __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(src + 8 * VP));
             const s16x8 both = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
-            acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), p[s], acc[db], 0, 0, 0);
+            acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), p[db / DBH][s], acc[db], 0, 0, 0);
           }
         }
       }
@@ -1043,17 +1052,18 @@ bool sta_mfma_supports(const StaArgs& a) {
   if (a.dt != LASER_BF16) return false;
   if (!(a.d_q == 32 || a.d_q == 64 || a.d_q == 128)) return false;
   if (!(a.d == 64 || a.d == 128)) return false;
-  if (a.heads != 1 || a.softmax) return false;   // one sigmoid gate per (item, candidate); the rest elsewhere
+  if (a.softmax) return false;                    // sigmoid gates only
+  if (a.heads != 1 && a.heads != 2) return false;   // two heads: the register-staged form, whole k-steps per head (d_q >= 32)
   if (a.C < 9) return false;   // fewer candidates than that: the streaming kernel's range
   const int nw = pick_nw(a.C);
   const long long ctiles = (a.C + CW * nw - 1) / (CW * nw);
   return (long long)a.U * ctiles * a.S <= 0x7fffffffLL;
 }
 
-template <int DQ, int D, int NW, int NBUF>
+template <int DQ, int D, int NW, int NBUF, int HEADS = 1>
 static void launch_one(const StaArgs& a, int spw, int ctiles, int sruns, float nsl) {
   const unsigned blocks = (unsigned)((long long)a.U * ctiles * sruns);
-  hipLaunchKernelGGL((sta_mfma_kernel<DQ, D, NW, NBUF>), dim3(blocks), dim3(64 * NW), 0, a.stream,
+  hipLaunchKernelGGL((sta_mfma_kernel<DQ, D, NW, NBUF, HEADS>), dim3(blocks), dim3(64 * NW), 0, a.stream,
                      (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens, a.cand_off, a.P, a.C,
                      a.L, a.w, a.S, spw, ctiles, sruns, nsl, (unsigned short*)a.seg_out, a.seg_cnt);
 }
@@ -1063,7 +1073,12 @@ static void launch_nw(const StaArgs& a, int nw, int spw, int ctiles, int sruns, 
   // eight waves fill a compute unit on their own and prefetch through LDS buffers of their own (direct-to-LDS
   // fetches for d_q = d = 128; LASER_STA_NODMA=1 selects the register-staged form there too, for comparison);
   // smaller workgroups overlap memory and MFMA work across the several workgroups that share a compute unit
-  if (nw == 8 && DQ == 128 && D == 128 && getenv("LASER_STA_NODMA") == nullptr) {
+  if (a.heads == 2) {   // the register-staged form for every workgroup size (two tile buffers with eight waves)
+    if (nw == 8) launch_one<DQ, D, 8, 2, 2>(a, spw, ctiles, sruns, nsl);
+    else if (nw == 4) launch_one<DQ, D, 4, 1, 2>(a, spw, ctiles, sruns, nsl);
+    else if (nw == 2) launch_one<DQ, D, 2, 1, 2>(a, spw, ctiles, sruns, nsl);
+    else launch_one<DQ, D, 1, 1, 2>(a, spw, ctiles, sruns, nsl);
+  } else if (nw == 8 && DQ == 128 && D == 128 && getenv("LASER_STA_NODMA") == nullptr) {
     const unsigned blocks = (unsigned)((long long)a.U * ctiles * sruns);
     if (a.reread)
       hipLaunchKernelGGL((sta_mfma_dma_kernel<8, false>), dim3(blocks), dim3(512), 0, a.stream,

@@ -24,7 +24,11 @@ CASES = {
     "long_segments_narrow_keys": ("bf16", 2, 8, 1500, 32, 64, 300, 2, [1500, 301]),
     "short_segments_wide": ("bf16", 3, 2, 700, 128, 128, 64, 2, [700, 65, 64]),
     "short_segments_three_candidates": ("bf16", 4, 3, 333, 64, 128, 20, 2, [333, 21, 20, 1]),
-    "many_candidates_two_heads": ("bf16", 2, 40, 512, 32, 128, 64, 2, [512, 100]),      # generic kernel
+    "many_candidates_two_heads": ("bf16", 2, 40, 512, 32, 128, 64, 2, [512, 100]),      # matrix cores, 2 waves
+    # the matrix-core kernel with two heads: every workgroup size, short segments of the paper's setting included
+    "mfma_paper_setting_ranking": ("bf16", 2, 200, 1000, 32, 128, 10, 2, [1000, 404]),   # 8 waves, 2 tile buffers
+    "mfma_one_wave_wide": ("bf16", 3, 20, 300, 128, 128, 64, 2, [300, 65, 0]),
+    "mfma_four_waves_narrow_values": ("bf16", 2, 100, 700, 64, 64, 128, 2, [700, 129]),
     "four_heads": ("bf16", 2, 5, 200, 32, 64, 16, 4, [200, 17]),                         # generic kernel
     "f32_three_heads": ("f32", 2, 3, 130, 24, 48, 16, 3, [130, 50]),
 }
@@ -47,7 +51,7 @@ def _case(name):
     return dtype, (qs, ks, vs), (qv, kv, vv), np.array(lens, dtype=np.int32), w, heads, math.sqrt(dq / heads)
 
 
-@pytest.mark.parametrize("variant", ["auto", "generic", "stream"])
+@pytest.mark.parametrize("variant", ["auto", "generic", "stream", "mfma"])
 @pytest.mark.parametrize("name", list(CASES))
 def test_heads_match_checker(name, variant):
     import torch
