@@ -113,9 +113,9 @@ laser_status laser_sta_forward_heads(const void* q, const void* k, const void* v
  * softmax:  seg_out[u,c,i,:] = sum_j softmax_j(dot(q[u,c,:], k[u,j,:]) / gamma) * v[u,j,:], the softmax taken over the
  * valid items j of segment i (per head on the head's own columns, as in laser_sta_forward_heads); segments without a
  * valid item give zeros. Arguments, layouts, limits and errors as for laser_sta_forward_heads. Kernels: the streaming
- * kernel for short segments (C <= 8, bf16, w below one step of its long form) and the generic kernel; the matrix-core
- * kernel and the long-segment streaming kernel carry sigmoid gates only (a forced variant that does not take the case
- * returns LASER_ERR_UNSUPPORTED).
+ * kernel for short segments (C <= 8, bf16, w below one step of its long form), the matrix-core kernel (C >= 9, bf16,
+ * 1 or 2 heads, its usual widths) and the generic kernel; the long-segment streaming kernel carries sigmoid gates only
+ * (a forced variant that does not take the case returns LASER_ERR_UNSUPPORTED).
  */
 laser_status laser_sta_forward_softmax(const void* q, const void* k, const void* v, const int32_t* lens,
                                        int U, int C, int L, int d_q, int d, int w, float gamma, int heads,

@@ -106,7 +106,11 @@ struct Stage {
 // HEADS > 1 (Sec. 4.1.2): head h owns the h-th run of d_q / HEADS columns of q and k, a whole number of 16-wide
 // k-steps, and of d / HEADS columns of v and H', a whole number of 32-column blocks; one score block and one gate
 // per head, and every column block is aggregated with its own head's gates.
-template <int DQ, int D, int NW, int NBUF, int HEADS = 1>
+// SOFTMAX (the ablation of Sec. 4.4.1): the gates of a segment are a softmax over its valid items, per candidate and
+// head, taken online: a running maximum and denominator per lane (the two lanes of a candidate agree on the maximum
+// after every block and add their denominators at the end of the segment), the sums rescaled when the maximum
+// moves. Zero-filled padding rows would count in the denominator, so their scores are masked in a partial block.
+template <int DQ, int D, int NW, int NBUF, int HEADS = 1, bool SOFTMAX = false>
 __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short* __restrict__ q,
                                                            const unsigned short* __restrict__ k,
                                                            const unsigned short* __restrict__ v,
@@ -189,6 +193,19 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short*
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[db][r] = 0.0f;
 
+  constexpr float SM_NEG = -1e30f;
+  float sm_m[HEADS], sm_l[HEADS];
+#pragma unroll
+  for (int hd = 0; hd < HEADS; ++hd) {
+    sm_m[hd] = SM_NEG;
+    sm_l[hd] = 0.0f;
+  }
+  auto both_halves = [](float x, bool take_max) {   // x combined with the value of lane ^ 32 (v_permlane32_swap)
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    const float a0 = __uint_as_float(r[0]), a1 = __uint_as_float(r[1]);
+    return take_max ? fmaxf(a0, a1) : a0 + a1;
+  };
+
   // patch -> global: 16 lanes x 16 B = one row; LDS operations of a wave execute in order, so the rows written
   // by this wave above are visible to its own reads here without a barrier
   constexpr int LPR = D / 8, RPI = 64 / LPR;   // lanes per row, rows per instruction
@@ -241,10 +258,40 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short*
 #pragma unroll
           for (int ks = hd * KH; ks < (hd + 1) * KH; ++ks)
             sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[ks], sc, 0, 0, 0);
+          if constexpr (SOFTMAX) {
+            const float sl = -neg_scale_log2e;            // log2(e) / gamma
+            const int left = chi - ct0 - ib * 32;         // valid items from the start of this block (>= 1)
+            float x[16], bm = SM_NEG;
 #pragma unroll
-          for (int s = 0; s < 2; ++s)
+            for (int r = 0; r < 16; ++r) {
+              x[r] = sc[r] * sl;
+              if (left < 32 && 8 * (r >> 2) + 4 * h + (r & 3) >= left) x[r] = SM_NEG;
+              bm = fmaxf(bm, x[r]);
+            }
+            bm = both_halves(bm, true);
+            const float m_new = fmaxf(sm_m[hd], bm);
+            const float corr = __builtin_amdgcn_exp2f(sm_m[hd] - m_new);   // 0 at the first block of a segment
+            float ps = 0.0f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) p[hd][s][e] = (__bf16)gate(sc[s * 8 + e], neg_scale_log2e);
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+              for (int e = 0; e < 8; ++e) {
+                const float pe = __builtin_amdgcn_exp2f(x[s * 8 + e] - m_new);
+                ps += pe;
+                p[hd][s][e] = (__bf16)pe;
+              }
+            sm_l[hd] = fmaf(sm_l[hd], corr, ps);
+            sm_m[hd] = m_new;
+#pragma unroll
+            for (int db = hd * DBH; db < (hd + 1) * DBH; ++db)
+#pragma unroll
+              for (int r = 0; r < 16; ++r) acc[db][r] *= corr;
+          } else {
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+              for (int e = 0; e < 8; ++e) p[hd][s][e] = (__bf16)gate(sc[s * 8 + e], neg_scale_log2e);
+          }
         }
         // ---- acc^T += V^T . P^T
 #pragma unroll
@@ -275,6 +322,18 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_kernel(const unsigned short*
       // ---- segment finished: H'[u, c, ci, :] is parked in the wave-private patch as bf16 rows; it is written
       // to global memory at the top of the next step, behind that step's prefetch loads, so that waiting for
       // the prefetch never has to wait for these stores first
+      if constexpr (SOFTMAX) {   // divide by the denominator (the segment holds a valid item: it is positive)
+#pragma unroll
+        for (int hd = 0; hd < HEADS; ++hd) {
+          const float inv = 1.0f / both_halves(sm_l[hd], false);
+#pragma unroll
+          for (int db = hd * DBH; db < (hd + 1) * DBH; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[db][r] *= inv;
+          sm_m[hd] = SM_NEG;
+          sm_l[hd] = 0.0f;
+        }
+      }
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -1052,7 +1111,6 @@ bool sta_mfma_supports(const StaArgs& a) {
   if (a.dt != LASER_BF16) return false;
   if (!(a.d_q == 32 || a.d_q == 64 || a.d_q == 128)) return false;
   if (!(a.d == 64 || a.d == 128)) return false;
-  if (a.softmax) return false;                    // sigmoid gates only
   if (a.heads != 1 && a.heads != 2) return false;   // two heads: the register-staged form, whole k-steps per head (d_q >= 32)
   if (a.C < 9) return false;   // fewer candidates than that: the streaming kernel's range
   const int nw = pick_nw(a.C);
@@ -1060,10 +1118,10 @@ bool sta_mfma_supports(const StaArgs& a) {
   return (long long)a.U * ctiles * a.S <= 0x7fffffffLL;
 }
 
-template <int DQ, int D, int NW, int NBUF, int HEADS = 1>
+template <int DQ, int D, int NW, int NBUF, int HEADS = 1, bool SOFTMAX = false>
 static void launch_one(const StaArgs& a, int spw, int ctiles, int sruns, float nsl) {
   const unsigned blocks = (unsigned)((long long)a.U * ctiles * sruns);
-  hipLaunchKernelGGL((sta_mfma_kernel<DQ, D, NW, NBUF, HEADS>), dim3(blocks), dim3(64 * NW), 0, a.stream,
+  hipLaunchKernelGGL((sta_mfma_kernel<DQ, D, NW, NBUF, HEADS, SOFTMAX>), dim3(blocks), dim3(64 * NW), 0, a.stream,
                      (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens, a.cand_off, a.P, a.C,
                      a.L, a.w, a.S, spw, ctiles, sruns, nsl, (unsigned short*)a.seg_out, a.seg_cnt);
 }
@@ -1073,11 +1131,20 @@ static void launch_nw(const StaArgs& a, int nw, int spw, int ctiles, int sruns, 
   // eight waves fill a compute unit on their own and prefetch through LDS buffers of their own (direct-to-LDS
   // fetches for d_q = d = 128; LASER_STA_NODMA=1 selects the register-staged form there too, for comparison);
   // smaller workgroups overlap memory and MFMA work across the several workgroups that share a compute unit
-  if (a.heads == 2) {   // the register-staged form for every workgroup size (two tile buffers with eight waves)
-    if (nw == 8) launch_one<DQ, D, 8, 2, 2>(a, spw, ctiles, sruns, nsl);
-    else if (nw == 4) launch_one<DQ, D, 4, 1, 2>(a, spw, ctiles, sruns, nsl);
-    else if (nw == 2) launch_one<DQ, D, 2, 1, 2>(a, spw, ctiles, sruns, nsl);
-    else launch_one<DQ, D, 1, 1, 2>(a, spw, ctiles, sruns, nsl);
+  // two heads, the softmax variant: the register-staged form for every workgroup size (two tile buffers with
+  // eight waves)
+#define LASER_STA_STAGED(H, SM)                                                      \
+  do {                                                                               \
+    if (nw == 8) launch_one<DQ, D, 8, 2, H, SM>(a, spw, ctiles, sruns, nsl);         \
+    else if (nw == 4) launch_one<DQ, D, 4, 1, H, SM>(a, spw, ctiles, sruns, nsl);    \
+    else if (nw == 2) launch_one<DQ, D, 2, 1, H, SM>(a, spw, ctiles, sruns, nsl);    \
+    else launch_one<DQ, D, 1, 1, H, SM>(a, spw, ctiles, sruns, nsl);                 \
+  } while (0)
+  if (a.softmax) {
+    if (a.heads == 2) LASER_STA_STAGED(2, true);
+    else LASER_STA_STAGED(1, true);
+  } else if (a.heads == 2) {
+    LASER_STA_STAGED(2, false);
   } else if (nw == 8 && DQ == 128 && D == 128 && getenv("LASER_STA_NODMA") == nullptr) {
     const unsigned blocks = (unsigned)((long long)a.U * ctiles * sruns);
     if (a.reread)

@@ -211,7 +211,7 @@ def test_sta_softmax_argument_validation(lib):
         q, A, A, None, 2, C, 64, dq, d, w, 1.0, heads, 1, A, None, None, variant)
     assert f(q=None) == NULL and f(heads=0) == SHAPE and f(heads=3) == SHAPE and f(w=0) == SHAPE
     assert f(variant=9) == UNSUP
-    assert f(dq=128, d=128, C=64, variant=2) == UNSUP      # the matrix-core kernel carries sigmoid gates only
+    assert f(dq=128, d=128, C=4, variant=2) == UNSUP       # the matrix-core kernel starts at nine candidates
     assert f(dq=64, d=64, C=2, w=200, variant=3) == UNSUP  # long segments: the streaming kernel's long form does not either
 
 

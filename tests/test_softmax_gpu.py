@@ -23,7 +23,11 @@ CASES = {
     "eight_candidates": ("bf16", 2, 8, 400, 64, 64, 30, 2, 1.0, [400, 31]),
     "sharp_scores": ("bf16", 2, 3, 333, 64, 128, 25, 1, 0.05, [333, 100]),        # near one-hot: the maximum moves often
     "long_segments": ("bf16", 2, 2, 1024, 64, 64, 256, 1, 1.0, [1024, 300]),       # generic kernel (long-segment shape)
-    "many_candidates": ("bf16", 2, 40, 256, 32, 128, 64, 1, 1.0, [256, 100]),      # generic kernel
+    "many_candidates": ("bf16", 2, 40, 256, 32, 128, 64, 1, 1.0, [256, 100]),      # matrix cores, 2 waves
+    # the matrix-core kernel: online softmax per candidate and head, partial blocks masked, every workgroup size
+    "mfma_paper_setting_ranking": ("bf16", 2, 200, 1000, 32, 128, 10, 2, 1.0, [1000, 404]),
+    "mfma_sharp_long_segments": ("bf16", 2, 20, 700, 64, 64, 300, 1, 0.05, [700, 301]),   # the maximum moves between blocks
+    "mfma_four_waves_wide": ("bf16", 3, 100, 333, 128, 128, 50, 2, 0.3, [333, 51, 0]),
     "f32_three_heads": ("f32", 2, 3, 130, 24, 48, 16, 3, 1.0, [130, 50]),
     "f32_sharp": ("f32", 1, 4, 96, 16, 16, 12, 1, 0.02, [90]),
 }
@@ -56,7 +60,6 @@ def test_softmax_variant_matches_checker(name, variant):
             pytest.skip("variant does not take this case")
         raise
     torch.cuda.synchronize()
-    assert variant != "mfma", "the matrix-core kernel carries sigmoid gates only"
     assert np.array_equal(cnt.cpu().numpy(), cnt_ref)
     err = vec_rel_err(to_host_f64(seg), ref)
     print(f"  max vector-relative error {err:.3e}", flush=True)
