@@ -169,6 +169,52 @@ def paper_setting_chain(laser, torch, event_time):
             / (bwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
 
+def paper_setting_ranking(laser, torch, event_time):
+    """Ranking at the paper's dimensions (Sec. 4.1.2: L = 1000, w = 10, 2 heads x d_q 16, d = 128) with many
+    candidates per user (64 users x 256 candidates, lengths uniform in [200, 1000], bf16): raw embeddings -> K, V, Q
+    -> H' (two heads, on the matrix cores) -> z, each step timed alone and the chain as a whole; the softmax variant
+    and the generic kernel beside them."""
+    U, C, L, din, dq, d, w, heads = 64, 256, 1000, 128, 32, 128, 10, 2
+    S = -(-L // w)
+    gen = torch.Generator(device="cuda").manual_seed(2603)
+    rnd = lambda *shape: torch.randn(*shape, device="cuda", generator=gen)
+    t, H = rnd(U, C, din).bfloat16(), rnd(U, L, din).bfloat16()
+    Wq, Wk, Wv = ((rnd(din, n) / math.sqrt(din)).bfloat16() for n in (dq, dq, d))
+    g3 = [(rnd(1, d, d) / math.sqrt(d)).bfloat16() for _ in range(3)]
+    lens = torch.randint(200, L + 1, (U,), device="cuda", dtype=torch.int32, generator=gen)
+    gamma = math.sqrt(dq / heads)
+    bf = dict(device="cuda", dtype=torch.bfloat16)
+    Q, K, V = torch.empty(U, C, dq, **bf), torch.empty(U, L, dq, **bf), torch.empty(U, L, d, **bf)
+    seg, z = torch.empty(U, C, S, d, **bf), torch.empty(U, C, d, device="cuda")
+
+    def sta(variant=0, softmax=False):
+        return lambda i: laser.laser_sta_forward(Q, K, V, lens, w, gamma, seg_out=seg, want_cnt=False, heads=heads,
+                                                 softmax=softmax, variant=variant)
+
+    def chain(i):
+        laser.laser_project_q_forward(t, Wq, q_out=Q)
+        laser.laser_project_kv_forward(H, Wk, Wv, k_out=K, v_out=V)
+        sta()(i)
+        laser.laser_gsta_forward(seg, t, *g3, lens, L, w, z_out=z)
+
+    chain(0)
+    out = {"U": U, "C": C, "L": L, "w": w, "heads": heads, "d_q": dq, "d": d,
+           "kv_projection_ms": event_time(lambda i: laser.laser_project_kv_forward(H, Wk, Wv, k_out=K, v_out=V)),
+           "q_projection_ms": event_time(lambda i: laser.laser_project_q_forward(t, Wq, q_out=Q)),
+           "sta_heads_ms": event_time(sta()), "sta_heads_softmax_ms": event_time(sta(softmax=True)),
+           "sta_heads_generic_kernel_ms": event_time(sta(variant=1)),
+           "gsta_ms": event_time(lambda i: laser.laser_gsta_forward(seg, t, *g3, lens, L, w, z_out=z)),
+           "chain_ms": event_time(chain)}
+    nvalid = int(lens.sum())
+    # STA alone: valid K and V rows, the queries, H' written once
+    sta_b = nvalid * (dq + d) * 2 + U * C * dq * 2 + U * C * S * d * 2
+    out["sta_algorithmic_bytes"] = sta_b
+    out["sta_heads_frac_of_hbm_peak"] = sta_b / (out["sta_heads_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS
+    out["pairs_per_s_chain"] = U * C / (out["chain_ms"] * 1e-3)
+    out["max_abs_z"] = float(z.abs().max())
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -375,6 +421,7 @@ def main() -> int:
                    "frac": (t_h if t_h >= t_m else t_m) / (kv_ms * 1e-3),
                    "whole_path_ms_per_step": raw_ms, "whole_path_pairs_per_s": spec.pairs / (raw_ms * 1e-3)}
         project["paper_setting"] = paper_setting_chain(laser, torch, event_time)
+        project["paper_setting_ranking"] = paper_setting_ranking(laser, torch, event_time)
         for (dw, seg, cnt, z) in sets:   # the timed loops above overwrote q, k, v: restore the workload's own
             fresh = DeviceWorkload(wl)
             dw.q.copy_(fresh.q), dw.k.copy_(fresh.k), dw.v.copy_(fresh.v)
