@@ -93,6 +93,41 @@ def test_heads_folded_form_and_softmax_at_the_paper_setting():
 
 
 @pytest.mark.timeout(900)
+def test_two_heads_and_softmax_on_the_matrix_cores_at_the_ranking_size():
+    """Ranking at the paper's dimensions (64 users x 256 candidates, L = 1000, w = 10, 2 heads x 16, d = 128: the shape
+    bench.py --project times): the matrix-core kernel with eight waves and two tile buffers against the generic kernel
+    on every element, and against the checker on sampled pairs; sigmoid gates and the softmax variant."""
+    import torch
+    U, C, L, dq, d, w, heads = 64, 256, 1000, 32, 128, 10, 2
+    gen = torch.Generator(device="cuda").manual_seed(2603)
+    Q, K, V = _rand(gen, U, C, dq), _rand(gen, U, L, dq), _rand(gen, U, L, d)
+    lens = torch.randint(200, L + 1, (U,), device="cuda", dtype=torch.int32, generator=gen)
+    lens[:4] = torch.tensor([L, 0, 1, 11], dtype=torch.int32)
+    gamma = math.sqrt(dq / heads)
+    lens_h = lens.cpu().numpy()
+    Qh, Kh, Vh = to_host_f64(Q), to_host_f64(K), to_host_f64(V)
+    rng = np.random.default_rng(8)
+    pairs = [(0, 0), (1, 5), (2, C - 1), (3, 17), (U - 1, C - 1)] + [(int(rng.integers(U)), int(rng.integers(C))) for _ in range(11)]
+    for softmax in (False, True):
+        print(f"softmax {softmax}", flush=True)
+        seg, cnt = laser.laser_sta_forward(Q, K, V, lens, w, gamma, heads=heads, softmax=softmax)
+        seg_m, _ = laser.laser_sta_forward(Q, K, V, lens, w, gamma, heads=heads, softmax=softmax,
+                                           variant=laser.STA_MFMA, want_cnt=False)
+        seg_g, _ = laser.laser_sta_forward(Q, K, V, lens, w, gamma, heads=heads, softmax=softmax,
+                                           variant=laser.STA_GENERIC, want_cnt=False)
+        assert torch.equal(seg, seg_m)                 # the matrix-core kernel is the one chosen for this shape
+        torch.cuda.synchronize()
+        assert np.array_equal(cnt.cpu().numpy(), oracle.segment_counts(lens_h, L, w))
+        segh = to_host_f64(seg)
+        assert vec_rel_err(segh, to_host_f64(seg_g)) <= 2 * TOL["bf16"]
+        assert not segh[1].any()                       # no valid item: exact zeros
+        one = oracle.sta_pair_softmax if softmax else oracle.sta_pair_heads
+        for u, c in pairs:
+            ref = one(Qh[u, c], Kh[u], Vh[u], int(lens_h[u]), w, gamma, heads)
+            assert vec_rel_err(segh[u, c], ref) <= TOL["bf16"], (u, c)
+
+
+@pytest.mark.timeout(900)
 def test_sta_backward_at_the_paper_setting():
     import torch
     p = _paper(seed=77)
