@@ -197,6 +197,28 @@ def paper_setting_ranking(laser, torch, event_time):
         sta()(i)
         laser.laser_gsta_forward(seg, t, *g3, lens, L, w, z_out=z)
 
+    # the complete head of Sec. 3.4: STA, the per-segment FFN + LayerNorm (in place, d_ff = d), GSTA, and the other two
+    # views (max-pool over the segments and the r = 8 most recent segment vectors)
+    d_ff, r = d, 8
+    w1, w2 = (rnd(d, d_ff) / math.sqrt(d)).bfloat16(), (rnd(d_ff, d) / math.sqrt(d_ff)).bfloat16()
+    b1, b2 = rnd(d_ff) * 0.3, rnd(d) * 0.3
+    ln_g, ln_b = 1.0 + 0.2 * rnd(d), 0.1 * rnd(d)
+    pool, recent = torch.empty(U, C, d, **bf), torch.empty(U, C, r, d, **bf)
+
+    def ffn(i):
+        laser.laser_segment_ffn_forward(seg, lens, w1, b1, w2, b2, ln_g, ln_b, L, w, 1e-5, seg_out=seg)
+
+    def views(i):
+        laser.laser_multires_forward(seg, lens, L, w, r, pool_out=pool, recent_out=recent)
+
+    def full_head(i):
+        laser.laser_project_q_forward(t, Wq, q_out=Q)
+        laser.laser_project_kv_forward(H, Wk, Wv, k_out=K, v_out=V)
+        sta()(i)
+        ffn(i)
+        laser.laser_gsta_forward(seg, t, *g3, lens, L, w, z_out=z)
+        views(i)
+
     chain(0)
     out = {"U": U, "C": C, "L": L, "w": w, "heads": heads, "d_q": dq, "d": d,
            "kv_projection_ms": event_time(lambda i: laser.laser_project_kv_forward(H, Wk, Wv, k_out=K, v_out=V)),
@@ -205,6 +227,11 @@ def paper_setting_ranking(laser, torch, event_time):
            "sta_heads_generic_kernel_ms": event_time(sta(variant=1)),
            "gsta_ms": event_time(lambda i: laser.laser_gsta_forward(seg, t, *g3, lens, L, w, z_out=z)),
            "chain_ms": event_time(chain)}
+    sta()(0)
+    out["ffn_layernorm_ms"] = event_time(ffn)     # (in place: later launches normalise normalised rows, same work)
+    out["views_ms"] = event_time(views)
+    out["full_head_ms"] = event_time(full_head)
+    out["pairs_per_s_full_head"] = U * C / (out["full_head_ms"] * 1e-3)
     nvalid = int(lens.sum())
     # STA alone: valid K and V rows, the queries, H' written once
     sta_b = nvalid * (dq + d) * 2 + U * C * dq * 2 + U * C * S * d * 2
