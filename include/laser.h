@@ -242,14 +242,25 @@ laser_status laser_multires_forward(const void* seg, const int32_t* lens, int U,
 /*
  * The whole path with all three views of Sec. 3.4.4: laser_forward followed by laser_multires_forward on the
  * stored H', same arguments, same results, same errors; everything is validated before the first launch. Where
- * the GSTA kernel holds a pair's H' block in registers (bf16, M = 1, S up to 8 * 64 / (d / 8)) the views are
- * written by that kernel from the same pass over H'; otherwise a third launch reads H' again.
+ * the GSTA kernel holds a pair's H' block in registers (bf16, M = 1, d in {64, 128}, S up to 32 * 64 / (d / 8)) the
+ * views are written by that kernel from the same pass over H'; otherwise a third launch reads H' again.
  */
 laser_status laser_forward_multires(const void* q, const void* k, const void* v, const void* t0,
                                     const void* wq, const void* wk, const void* wv, const int32_t* lens,
                                     int U, int C, int L, int d_q, int d, int w, float gamma, int M, laser_dtype dt,
                                     void* seg_out, int32_t* seg_cnt, float* z_out,
                                     int r, void* pool_out, void* recent_out, void* stream);
+
+/*
+ * GSTA and the two other views of Sec. 3.4.4 from a stored H' (for callers that put a step of their own between STA
+ * and GSTA, such as laser_segment_ffn_forward): laser_gsta_forward followed by laser_multires_forward on the same seg,
+ * same arguments, same results (z_out, pool_out and recent_out bit for bit), same errors, everything validated before
+ * the first launch; H' is read once where the GSTA kernel holds a pair's block in registers (see above), twice
+ * otherwise.
+ */
+laser_status laser_gsta_forward_multires(const void* seg, const void* t0, const void* wq, const void* wk, const void* wv,
+                                         const int32_t* lens, int U, int C, int L, int d, int w, int M, laser_dtype dt,
+                                         float* z_out, int r, void* pool_out, void* recent_out, void* stream);
 
 /*
  * The linear maps ahead of STA (paper Sec. 3.5.1, first two equations): Q = t W_q for the targets, and K = H W_k,

@@ -24,7 +24,8 @@ EXPORTS = [
     "laser_sta_forward", "laser_sta_forward_variant", "laser_sta_forward_heads", "laser_sta_forward_softmax", "laser_sta_forward_ragged",
     "laser_gsta_forward_ragged", "laser_forward_ragged", "laser_multires_forward_ragged",
     "laser_segment_ffn_forward_ragged", "laser_gsta_forward", "laser_gsta_forward_variant",
-    "laser_forward", "laser_multires_forward", "laser_forward_multires", "laser_sta_kernel_name",
+    "laser_forward", "laser_multires_forward", "laser_forward_multires", "laser_gsta_forward_multires",
+    "laser_sta_kernel_name",
     "laser_gsta_kernel_name", "laser_segment_ffn_forward", "laser_segment_ffn_forward_variant",
     "laser_gsta_kernel_name_layers", "laser_project_q_forward", "laser_project_q_forward_variant",
     "laser_project_kv_forward", "laser_project_kv_forward_variant", "laser_fold_query_weights",
@@ -70,6 +71,8 @@ def load_library() -> ctypes.CDLL:
     lib.laser_multires_forward.restype = i32
     lib.laser_forward_multires.argtypes = lib.laser_forward.argtypes[:-1] + [i32, vp, vp, vp]
     lib.laser_forward_multires.restype = i32
+    lib.laser_gsta_forward_multires.argtypes = lib.laser_gsta_forward.argtypes[:-1] + [i32, vp, vp, vp]
+    lib.laser_gsta_forward_multires.restype = i32
     fp = ctypes.c_void_p
     lib.laser_segment_ffn_forward.argtypes = [vp, ip, vp, fp, vp, fp, fp, fp, i32, i32, i32, i32, i32, i32, f32, i32,
                                               vp, vp]
@@ -536,6 +539,34 @@ def laser_forward_multires(q, k, v, t0, wq, wk, wv, lens, w: int, gamma: float, 
         _ptr(pool_out, "pool_out"), _ptr(recent_out, "recent_out"), _stream(stream))
     _check(code, "laser_forward_multires")
     return seg_out, seg_cnt, z_out, pool_out, recent_out
+
+
+def laser_gsta_forward_multires(seg, t0, wq, wk, wv, lens, L: int, w: int, r: int, z_out=None, pool_out=None,
+                                recent_out=None, stream=None):
+    """GSTA and the two other views from a stored H' [U,C,S,d]. Returns (z fp32 [U,C,d], pool [U,C,d], recent
+    [U,C,r,d] or None)."""
+    torch = _torch()
+    U, C, S, d = seg.shape
+    M = wq.shape[0]
+    if S != -(-L // w):
+        raise ValueError("seg.shape[2] must be ceil(L / w)")
+    if any(x.dtype != seg.dtype for x in (t0, wq, wk, wv)):
+        raise TypeError("all inputs must share a dtype")
+    if z_out is None:
+        z_out = torch.empty((U, C, d), dtype=torch.float32, device=seg.device)
+    if pool_out is None:
+        pool_out = torch.empty((U, C, d), dtype=seg.dtype, device=seg.device)
+    if recent_out is None and r > 0:
+        recent_out = torch.empty((U, C, r, d), dtype=seg.dtype, device=seg.device)
+    for name, x in (("pool_out", pool_out), ("recent_out", recent_out)):
+        if x is not None and x.dtype != seg.dtype:
+            raise TypeError(f"{name} must have the dtype of seg")
+    code = load_library().laser_gsta_forward_multires(
+        _ptr(seg, "seg"), _ptr(t0, "t0"), _ptr(wq, "wq"), _ptr(wk, "wk"), _ptr(wv, "wv"),
+        _ptr(lens, "lens", torch.int32), U, C, int(L), d, int(w), M, _dt(seg), _ptr(z_out, "z_out", torch.float32),
+        int(r), _ptr(pool_out, "pool_out"), _ptr(recent_out, "recent_out"), _stream(stream))
+    _check(code, "laser_gsta_forward_multires")
+    return z_out, pool_out, recent_out
 
 
 def laser_multires_forward(seg, lens, L: int, w: int, r: int, pool_out=None, recent_out=None, stream=None,

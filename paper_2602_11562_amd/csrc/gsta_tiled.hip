@@ -474,11 +474,15 @@ __global__ __launch_bounds__(GS_THREADS) void gsta_out_kernel(const unsigned sho
   }
 }
 
-// one wave per pair; ROWS register rows of 16 bytes cover the pair's S x D block
-template <int D, int ROWS>
+// one wave per pair; ROWS register rows of 16 bytes cover the pair's S x D block.
+// MR: the two other views of Sec. 3.4.4 from the same registers: the component-wise maximum over the valid segments
+// (exact in fp32: stored values are compared and passed through) and a copy of the first r rows as stored. Both leave
+// after the pair is reduced, behind the wave's last load.
+template <int D, int ROWS, bool MR>
 __global__ __launch_bounds__(GS_THREADS) void gsta_pool_kernel(const unsigned short* __restrict__ seg,
                                                                const int32_t* __restrict__ lens, const int32_t* __restrict__ cand_off, int U, int P, int C, int L,
-                                                               int w, int S, float* __restrict__ z) {
+                                                               int w, int S, float* __restrict__ z,
+                                                               u32x4* __restrict__ pool, u32x4* __restrict__ recent, int r) {
   constexpr int LPR = D / 8, RPW = 64 / LPR;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: the valid length is a scalar load
@@ -486,12 +490,16 @@ __global__ __launch_bounds__(GS_THREADS) void gsta_pool_kernel(const unsigned sh
   if (pr >= P) return;
   const int grp = lane / LPR, gl = lane % LPR;
   const int nv = (valid_len(lens, pair_user(cand_off, U, C, pr), L) + w - 1) / w;
+  const int nr = (MR && recent != nullptr) ? (r < S ? r : S) : 0;   // rows copied as stored, valid or not
   const unsigned short* H = seg + (size_t)pr * S * D;
   u32x4 hreg[ROWS];
 #pragma unroll
   for (int j = 0; j < ROWS; ++j) {
     const int i = j * RPW + grp;
-    hreg[j] = u32x4{0u, 0u, 0u, 0u};
+    // rows without a valid item are not read: zeros, or with MR the most negative finite value, which leaves the
+    // maximum alone and, multiplied by its weight of zero, the sums too (the loop below stays free of branches, so
+    // every row is worked on as soon as it arrives)
+    hreg[j] = MR ? u32x4{0xff7fff7fu, 0xff7fff7fu, 0xff7fff7fu, 0xff7fff7fu} : u32x4{0u, 0u, 0u, 0u};
     if (i < nv) hreg[j] = *reinterpret_cast<const u32x4*>(H + (size_t)i * D + gl * 8);
   }
   float rs[8];
@@ -502,9 +510,12 @@ __global__ __launch_bounds__(GS_THREADS) void gsta_pool_kernel(const unsigned sh
     for (int e = 0; e < 4; ++e) { rs[e] = a[e]; rs[4 + e] = b[e]; }
   }
   float m = -INFINITY, den = 0.0f;
-  float pacc[8];
+  float pacc[8], pmax[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) pacc[e] = 0.0f;
+  for (int e = 0; e < 8; ++e) {
+    pacc[e] = 0.0f;
+    pmax[e] = -INFINITY;
+  }
 #pragma unroll
   for (int j = 0; j < ROWS; ++j) {
     float x[8];
@@ -525,6 +536,10 @@ __global__ __launch_bounds__(GS_THREADS) void gsta_pool_kernel(const unsigned sh
 #pragma unroll
     for (int e = 0; e < 8; ++e) pacc[e] = fmaf(pacc[e], sc, a * x[e]);
     m = m_new;
+    if (MR) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) pmax[e] = fmaxf(pmax[e], x[e]);
+    }
   }
 #pragma unroll
   for (int off = LPR; off < 64; off <<= 1) {
@@ -538,6 +553,12 @@ __global__ __launch_bounds__(GS_THREADS) void gsta_pool_kernel(const unsigned sh
     for (int e = 0; e < 8; ++e) pacc[e] = pacc[e] * f + __shfl_xor(pacc[e], off, 64) * f_o;
     m = M2;
   }
+  if (MR && pool != nullptr) {
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) pmax[e] = fmaxf(pmax[e], __shfl_xor(pmax[e], off, 64));
+  }
   if (grp == 0) {   // the row's r has been read by these same lanes above: overwrite it with p
     const float inv = nv > 0 ? 1.0f / den : 0.0f;
     f32x4 a, b;
@@ -545,6 +566,19 @@ __global__ __launch_bounds__(GS_THREADS) void gsta_pool_kernel(const unsigned sh
     for (int e = 0; e < 4; ++e) { a[e] = pacc[e] * inv; b[e] = pacc[4 + e] * inv; }
     *reinterpret_cast<f32x4*>(z + (size_t)pr * D + gl * 8) = a;
     *reinterpret_cast<f32x4*>(z + (size_t)pr * D + gl * 8 + 4) = b;
+    if (MR && pool != nullptr) {   // no valid segment: zeros
+      u32x4 o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        o[e] = nv > 0 ? ((__float_as_uint(pmax[2 * e]) >> 16) | (__float_as_uint(pmax[2 * e + 1]) & 0xffff0000u)) : 0u;
+      pool[(size_t)pr * LPR + gl] = o;
+    }
+  }
+  // the first rows as stored, valid or not: read again (this wave fetched the valid ones a moment ago: cache hits)
+  // rather than kept, which would hold every row's registers to the end and cost a wave of occupancy
+  if (MR && nr > 0) {
+    for (int i = grp; i < nr; i += RPW)
+      recent[((size_t)pr * r + i) * LPR + gl] = *reinterpret_cast<const u32x4*>(H + (size_t)i * D + gl * 8);
   }
 }
 
@@ -908,9 +942,18 @@ static void launch_split(const GstaArgs& a) {
                      (const unsigned short*)a.wq, (const unsigned short*)a.wk, P, a.z_out);
   const int rows = rows_needed(a.S, a.d);
   const unsigned pblocks = (unsigned)((P + GS_THREADS / 64 - 1) / (GS_THREADS / 64));
+  const bool views = a.pool_out != nullptr || a.recent_out != nullptr;
 #define LASER_POOL(R)                                                                                             \
-  hipLaunchKernelGGL((gsta_pool_kernel<D, R>), dim3(pblocks), dim3(GS_THREADS), 0, a.stream,                     \
-                     (const unsigned short*)a.seg, a.lens, a.cand_off, a.U, P, a.C, a.L, a.w, a.S, a.z_out)
+  do {                                                                                                            \
+    if (views)                                                                                                    \
+      hipLaunchKernelGGL((gsta_pool_kernel<D, R, true>), dim3(pblocks), dim3(GS_THREADS), 0, a.stream,            \
+                         (const unsigned short*)a.seg, a.lens, a.cand_off, a.U, P, a.C, a.L, a.w, a.S, a.z_out,    \
+                         (u32x4*)a.pool_out, (u32x4*)a.recent_out, a.r);                                          \
+    else                                                                                                          \
+      hipLaunchKernelGGL((gsta_pool_kernel<D, R, false>), dim3(pblocks), dim3(GS_THREADS), 0, a.stream,           \
+                         (const unsigned short*)a.seg, a.lens, a.cand_off, a.U, P, a.C, a.L, a.w, a.S, a.z_out,    \
+                         (u32x4*)nullptr, (u32x4*)nullptr, 0);                                                    \
+  } while (0)
   if (rows <= 2) LASER_POOL(2);
   else if (rows <= 4) LASER_POOL(4);
   else if (rows <= 8) LASER_POOL(8);

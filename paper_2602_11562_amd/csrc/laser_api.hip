@@ -118,6 +118,34 @@ static laser_status run_gsta(const GstaArgs& a, laser_gsta_variant variant) {
   }
 }
 
+// GSTA and the two other views of Sec. 3.4.4 from one pass over H' where the GSTA kernel writes them itself (the
+// one-kernel form, up to the number of recent rows it can stage, and the split form's streaming kernel); a second
+// launch over H' otherwise
+static laser_status run_gsta_views(GstaArgs& ga, MultiresArgs& ma) {
+  const laser_gsta_variant variant = pick_gsta(ga);
+  if (variant == LASER_GSTA_ONE) {
+    ga.pool_out = ma.pool_out;
+    if (ma.r <= gsta_one_max_recent(ga.d)) {
+      ga.recent_out = ma.recent_out;
+      ga.r = ma.r;
+      return run_gsta(ga, LASER_GSTA_ONE);
+    }
+    const laser_status s = run_gsta(ga, LASER_GSTA_ONE);   // more recent segments than the kernel can stage: a copy launch for those
+    if (s != LASER_OK) return s;
+    ma.pool_out = nullptr;
+    return multires_launch(ma);
+  }
+  if (variant == LASER_GSTA_SPLIT) {
+    ga.pool_out = ma.pool_out;
+    ga.recent_out = ma.recent_out;
+    ga.r = ma.r;
+    return run_gsta(ga, LASER_GSTA_SPLIT);
+  }
+  const laser_status s = run_gsta(ga, variant);
+  if (s != LASER_OK) return s;
+  return multires_launch(ma);
+}
+
 }  // namespace laser
 
 using namespace laser;
@@ -310,21 +338,19 @@ laser_status laser_forward_multires(const void* q, const void* k, const void* v,
   sa.reread = true;
   s = run_sta(sa, LASER_STA_AUTO);
   if (s != LASER_OK) return s;
-  if (pick_gsta(ga) == LASER_GSTA_ONE) {   // the views come out of the same pass over H'
-    ga.pool_out = pool_out;
-    if (r <= gsta_one_max_recent(d)) {
-      ga.recent_out = recent_out;
-      ga.r = r;
-      return run_gsta(ga, LASER_GSTA_ONE);
-    }
-    s = run_gsta(ga, LASER_GSTA_ONE);   // more recent segments than the kernel can stage: a copy launch for those
-    if (s != LASER_OK) return s;
-    ma.pool_out = nullptr;
-    return multires_launch(ma);
-  }
-  s = run_gsta(ga, LASER_GSTA_AUTO);
+  return run_gsta_views(ga, ma);
+}
+
+laser_status laser_gsta_forward_multires(const void* seg, const void* t0, const void* wq, const void* wk, const void* wv,
+                                         const int32_t* lens, int U, int C, int L, int d, int w, int M, laser_dtype dt,
+                                         float* z_out, int r, void* pool_out, void* recent_out, void* stream) {
+  GstaArgs ga;
+  MultiresArgs ma;
+  laser_status s = validate_gsta(seg, t0, wq, wk, wv, lens, U, C, L, d, w, M, dt, z_out, stream, &ga);
   if (s != LASER_OK) return s;
-  return multires_launch(ma);
+  s = validate_multires(seg, lens, U, C, L, d, w, r, dt, pool_out, recent_out, stream, &ma);
+  if (s != LASER_OK) return s;
+  return run_gsta_views(ga, ma);
 }
 
 laser_status laser_segment_ffn_forward_variant(const void* seg, const int32_t* lens, const void* w1, const float* b1,

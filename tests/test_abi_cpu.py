@@ -125,6 +125,18 @@ def test_multires_argument_validation(lib):
     assert _multires(lib, recent=A + 2) == ALIGN and _multires(lib, lens=A + 2) == ALIGN
 
 
+def test_gsta_with_views_argument_validation(lib):
+    NULL, SHAPE, DTYPE, ALIGN = 1, 2, 3, 6
+    f = lambda seg=A, t0=A, wv=A, lens=None, U=2, C=3, L=64, d=16, w=8, M=1, dt=1, z=A, r=2, pool=A, recent=A: \
+        lib.laser_gsta_forward_multires(seg, t0, A, A, wv, lens, U, C, L, d, w, M, dt, z, r, pool, recent, None)
+    for kw in ({"seg": None}, {"t0": None}, {"wv": None}, {"z": None}, {"pool": None, "recent": None, "r": 0}):
+        assert f(**kw) == NULL, kw
+    assert f(dt=5) == DTYPE
+    for kw in ({"M": 0}, {"d": 4}, {"w": 0}, {"U": 0}, {"r": -1}, {"r": 9}, {"r": 0}, {"r": 2, "recent": None}):
+        assert f(**kw) == SHAPE, kw
+    assert f(pool=A + 8) == ALIGN and f(recent=A + 2) == ALIGN and f(lens=A + 2) == ALIGN and f(wv=A + 4) == ALIGN
+
+
 def _ffn(lib, seg=A, lens=None, w1=A, b1=A, w2=A, b2=A, g=A, b=A, U=2, C=3, L=64, d=16, dff=32, w=8, eps=1e-5, dt=1,
          out=A, variant=0):
     return lib.laser_segment_ffn_forward_variant(seg, lens, w1, b1, w2, b2, g, b, U, C, L, d, dff, w, eps, dt, out,

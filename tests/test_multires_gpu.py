@@ -110,3 +110,38 @@ def test_whole_path_with_all_views(name, over, r):
     pool_ref, recent_ref = oracle.multires_forward(to_host_f64(seg), cnt.cpu().numpy(), r)
     assert np.array_equal(to_host_f64(pool), pool_ref)
     assert np.array_equal(to_host_f64(recent), recent_ref)
+
+
+@pytest.mark.parametrize("name,over,r", [
+    ("cfg3_high_fanout", dict(U=2, L=1024 + 128), 3),      # one-kernel form: the views come out of the GSTA kernel
+    ("cfg3_high_fanout", dict(U=2, C=40, L=1000, w=10), 8),   # 100 segments: split form, views from its streaming kernel
+    ("cfg2_bf16", dict(U=5, C=9, L=2048, w=16), 128),      # split form, d = 64, r = S, ragged lengths (some rows invalid)
+    ("cfg3_high_fanout", dict(U=3, C=5, L=1000, w=10), 100),  # split form, r = S, few pairs
+    ("cfg5_lifelong", dict(U=1, L=2 * 256 + 16), 2),       # M = 2: the views take a launch of their own
+    ("cfg1_tiny_f32", dict(), 5),                          # fp32: the same
+])
+def test_gsta_with_views_from_a_stored_h(name, over, r):
+    """laser_gsta_forward_multires = laser_gsta_forward + laser_multires_forward on the same H', bit for bit, and the
+    views equal to the checker's (they are exact). H' is made by STA and, so that rows without a valid item hold
+    something other than zeros where lengths are ragged, left as STA wrote it (zeros there) in one run and filled
+    with a marker in those rows in a second: `recent` copies rows as stored, `pool` and GSTA must not see them."""
+    import torch
+    from workloads.configs import make_workload
+    from parity_util import DeviceWorkload
+    spec = workloads.CONFIGS[name].replace(**over)
+    wl = make_workload(spec)
+    dw = DeviceWorkload(wl)
+    print(f"case {spec} r {r}", flush=True)
+    seg, cnt = laser.laser_sta_forward(dw.q, dw.k, dw.v, dw.lens, spec.w, spec.gamma)
+    for marker in (False, True):
+        if marker:
+            seg = seg.clone()
+            seg[(cnt == 0)[:, None, :].expand(-1, spec.C, -1)] = 3.0
+        z, pool, recent = laser.laser_gsta_forward_multires(seg, dw.t0, dw.wq, dw.wk, dw.wv, dw.lens, spec.L, spec.w, r)
+        z0 = laser.laser_gsta_forward(seg, dw.t0, dw.wq, dw.wk, dw.wv, dw.lens, spec.L, spec.w)
+        pool0, recent0 = laser.laser_multires_forward(seg, dw.lens, spec.L, spec.w, r)
+        torch.cuda.synchronize()
+        assert torch.equal(z, z0) and torch.equal(pool, pool0) and torch.equal(recent, recent0)
+        pool_ref, _ = oracle.multires_forward(to_host_f64(seg), cnt.cpu().numpy(), r)
+        assert np.array_equal(to_host_f64(pool), pool_ref)
+        assert torch.equal(recent, seg[:, :, :r])
