@@ -99,7 +99,7 @@ laser_status laser_sta_forward_variant(const void* q, const void* k, const void*
  * [h d/heads, (h+1) d/heads) of v and seg_out: every head is the STA above on its own columns, with the same gamma,
  * and the heads' outputs lie side by side, so all shapes and layouts are those of laser_sta_forward. heads = 1 is
  * laser_sta_forward_variant. heads must divide d_q and d (1 <= heads <= 64), else LASER_ERR_SHAPE. The streaming
- * kernel takes 1 or 2 heads (d_q/heads and d/heads multiples of 8); the matrix-core kernel takes 1 or 2 heads; other
+ * kernel takes 1 or 2 heads (d_q/heads and d/heads multiples of 8); the matrix-core kernel takes 1, 2 or 4 heads (d_q / heads a multiple of 16, d / heads of 32); other
  * cases run on the generic kernel (AUTO picks; a forced variant that does not take the case returns
  * LASER_ERR_UNSUPPORTED). Everything else as for laser_sta_forward.
  */
@@ -114,7 +114,7 @@ laser_status laser_sta_forward_heads(const void* q, const void* k, const void* v
  * valid items j of segment i (per head on the head's own columns, as in laser_sta_forward_heads); segments without a
  * valid item give zeros. Arguments, layouts, limits and errors as for laser_sta_forward_heads. Kernels: the streaming
  * kernel for short segments (C <= 8, bf16, w below one step of its long form), the matrix-core kernel (C >= 9, bf16,
- * 1 or 2 heads, its usual widths) and the generic kernel; the long-segment streaming kernel carries sigmoid gates only
+ * 1, 2 or 4 heads, its usual widths) and the generic kernel; the long-segment streaming kernel carries sigmoid gates only
  * (a forced variant that does not take the case returns LASER_ERR_UNSUPPORTED).
  */
 laser_status laser_sta_forward_softmax(const void* q, const void* k, const void* v, const int32_t* lens,

@@ -1111,7 +1111,9 @@ bool sta_mfma_supports(const StaArgs& a) {
   if (a.dt != LASER_BF16) return false;
   if (!(a.d_q == 32 || a.d_q == 64 || a.d_q == 128)) return false;
   if (!(a.d == 64 || a.d == 128)) return false;
-  if (a.heads != 1 && a.heads != 2) return false;   // two heads: the register-staged form, whole k-steps per head (d_q >= 32)
+  // several heads: the register-staged form; a head owns whole 16-wide k-steps and whole 32-column blocks
+  if (a.heads != 1 && a.heads != 2 && a.heads != 4) return false;
+  if (a.heads == 4 && (a.d_q < 64 || a.d != 128)) return false;
   if (a.C < 9) return false;   // fewer candidates than that: the streaming kernel's range
   const int nw = pick_nw(a.C);
   const long long ctiles = (a.C + CW * nw - 1) / (CW * nw);
@@ -1140,7 +1142,12 @@ static void launch_nw(const StaArgs& a, int nw, int spw, int ctiles, int sruns, 
     else if (nw == 2) launch_one<DQ, D, 2, 1, H, SM>(a, spw, ctiles, sruns, nsl);    \
     else launch_one<DQ, D, 1, 1, H, SM>(a, spw, ctiles, sruns, nsl);                 \
   } while (0)
-  if (a.softmax) {
+  if (a.heads == 4) {
+    if constexpr ((DQ / 16) % 4 == 0 && (D / 32) % 4 == 0) {
+      if (a.softmax) LASER_STA_STAGED(4, true);
+      else LASER_STA_STAGED(4, false);
+    }
+  } else if (a.softmax) {
     if (a.heads == 2) LASER_STA_STAGED(2, true);
     else LASER_STA_STAGED(1, true);
   } else if (a.heads == 2) {

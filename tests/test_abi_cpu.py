@@ -193,7 +193,8 @@ def test_sta_heads_argument_validation(lib):
                {"heads": 2, "dq": 24, "d": 8 * 3 + 8 + 1}):
         assert f(**kw) == SHAPE, kw
     assert f(variant=9) == UNSUP
-    assert f(heads=4, dq=128, d=128, C=64, variant=2) == UNSUP     # the matrix-core kernel takes one or two heads
+    assert f(heads=8, dq=128, d=128, C=64, variant=2) == UNSUP     # the matrix-core kernel takes 1, 2 or 4 heads
+    assert f(heads=4, dq=32, d=128, C=64, variant=2) == UNSUP      # (a head needs a whole 16-wide k-step)
     assert f(heads=4, dq=32, d=128, variant=3) == UNSUP            # the streaming kernel takes one or two
 
 

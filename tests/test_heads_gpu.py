@@ -29,6 +29,8 @@ CASES = {
     "mfma_paper_setting_ranking": ("bf16", 2, 200, 1000, 32, 128, 10, 2, [1000, 404]),   # 8 waves, 2 tile buffers
     "mfma_one_wave_wide": ("bf16", 3, 20, 300, 128, 128, 64, 2, [300, 65, 0]),
     "mfma_four_waves_narrow_values": ("bf16", 2, 100, 700, 64, 64, 128, 2, [700, 129]),
+    "mfma_four_heads": ("bf16", 2, 70, 400, 64, 128, 40, 4, [400, 41]),
+    "mfma_four_heads_wide_keys": ("bf16", 1, 150, 300, 128, 128, 64, 4, [290]),
     "four_heads": ("bf16", 2, 5, 200, 32, 64, 16, 4, [200, 17]),                         # generic kernel
     "f32_three_heads": ("f32", 2, 3, 130, 24, 48, 16, 3, [130, 50]),
 }

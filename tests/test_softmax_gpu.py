@@ -28,6 +28,7 @@ CASES = {
     "mfma_paper_setting_ranking": ("bf16", 2, 200, 1000, 32, 128, 10, 2, 1.0, [1000, 404]),
     "mfma_sharp_long_segments": ("bf16", 2, 20, 700, 64, 64, 300, 1, 0.05, [700, 301]),   # the maximum moves between blocks
     "mfma_four_waves_wide": ("bf16", 3, 100, 333, 128, 128, 50, 2, 0.3, [333, 51, 0]),
+    "mfma_four_heads": ("bf16", 2, 40, 300, 64, 128, 30, 4, 0.5, [300, 31]),
     "f32_three_heads": ("f32", 2, 3, 130, 24, 48, 16, 3, 1.0, [130, 50]),
     "f32_sharp": ("f32", 1, 4, 96, 16, 16, 12, 1, 0.02, [90]),
 }
