@@ -257,10 +257,19 @@ __global__ __launch_bounds__(FM_THREADS) void segment_ffn_mfma_kernel(
     }
     f32x16 acc[DB];
     {
-      const f32x16 zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+      // the biases enter as the initial value of the accumulators (the same LDS reads as adding them afterwards,
+      // without the additions): b2 here, b1 below
 #pragma unroll
-      for (int db = 0; db < DB; ++db) {   // residual: Y^T = I . X^T
-        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(idA[0], xreg[2 * db], zero, 0, 0, 0);
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const f32x4 bb = *reinterpret_cast<const f32x4*>(b2s + db * 32 + 8 * g + 4 * h);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[db][4 * g + e] = bb[e];
+        }
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {   // residual: Y^T = b2 + I . X^T
+        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(idA[0], xreg[2 * db], acc[db], 0, 0, 0);
         acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(idA[1], xreg[2 * db + 1], acc[db], 0, 0, 0);
       }
       // Operand reads run ahead of their use: the second layer's weights of a hidden tile are requested before its
@@ -276,26 +285,31 @@ __global__ __launch_bounds__(FM_THREADS) void segment_ffn_mfma_kernel(
 #pragma unroll 1
       for (int j = 0; j < HT; ++j) {
         const unsigned char* a2 = W2L + j * 32 * ROWB;
+        f32x16 hid;   // starts at b1: hidden unit of element r is 32 j + 8 (r >> 2) + 4 h + (r & 3)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const f32x4 bb = *reinterpret_cast<const f32x4*>(b1s + j * 32 + 8 * g + 4 * h);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) hid[4 * g + e] = bb[e];
+        }
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
           w2r[0][db] = ffn_lds_tr(a2 + vofs[db]);
           w2r[1][db] = ffn_lds_tr(a2 + vofs[db] + 4096);
         }
         __builtin_amdgcn_sched_barrier(0);
-        f32x16 hid = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1r[0], xreg[0], zero, 0, 0, 0);
 #pragma unroll
-        for (int ks = 1; ks < KSTEPS; ++ks) hid = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1r[ks], xreg[ks], hid, 0, 0, 0);
+        for (int ks = 0; ks < KSTEPS; ++ks) hid = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1r[ks], xreg[ks], hid, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         read_w1(j + 1 < HT ? j + 1 : j);
         __builtin_amdgcn_sched_barrier(0);
-        // + b1, relu, round: hidden unit of element r is 32 j + 8 (r >> 2) + 4 h + (r & 3)
+        // relu, round
         u32x4 p0, p1;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const f32x4 bb = *reinterpret_cast<const f32x4*>(b1s + j * 32 + 8 * g + 4 * h);
           float v4[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v4[e] = fmaxf(hid[4 * g + e] + bb[e], 0.0f);
+          for (int e = 0; e < 4; ++e) v4[e] = fmaxf(hid[4 * g + e], 0.0f);
           const bf16x2 c0 = {(__bf16)v4[0], (__bf16)v4[1]}, c1 = {(__bf16)v4[2], (__bf16)v4[3]};
           if (g < 2) { p0[2 * g] = __builtin_bit_cast(unsigned, c0); p0[2 * g + 1] = __builtin_bit_cast(unsigned, c1); }
           else { p1[2 * (g - 2)] = __builtin_bit_cast(unsigned, c0); p1[2 * (g - 2) + 1] = __builtin_bit_cast(unsigned, c1); }
@@ -309,22 +323,17 @@ __global__ __launch_bounds__(FM_THREADS) void segment_ffn_mfma_kernel(
         __builtin_amdgcn_sched_barrier(0);
       }
     }
-    // ---- + b2, LayerNorm over d (this lane holds 64 of the row's 128 values, lane ^ 32 the others), gain, bias.
+    // ---- LayerNorm over d (this lane holds 64 of the row's 128 values, lane ^ 32 the others), gain, bias.
     // One pass for the sum and the sum of squares (values of order one, 128 terms, fp32: the cancellation in
     // E[x^2] - mean^2 costs ~1e-6), two multiply-adds per value for the normalisation.
     float sum = 0.0f, sq = 0.0f;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const f32x4 bb = *reinterpret_cast<const f32x4*>(b2s + db * 32 + 8 * g + 4 * h);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float xv = acc[db][4 * g + e] + bb[e];
-          acc[db][4 * g + e] = xv;
-          sum += xv;
-          sq = fmaf(xv, xv, sq);
-        }
+      for (int r = 0; r < 16; ++r) {
+        const float xv = acc[db][r];
+        sum += xv;
+        sq = fmaf(xv, xv, sq);
       }
     sum += __shfl_xor(sum, 32, 64);
     sq += __shfl_xor(sq, 32, 64);
