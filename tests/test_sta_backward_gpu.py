@@ -35,6 +35,8 @@ CASES = {
     "nine_candidates": ("bf16", 9, 300, 64, 64, 64, [300, 65, 0]),
     "twenty_candidates_f32": ("f32", 20, 130, 24, 48, 16, [130, 50]),
     "seventeen_candidates_wide": ("bf16", 17, 200, 128, 128, 32, [200, 33]),
+    "forty_candidates": ("bf16", 40, 150, 64, 128, 16, [150, 17]),            # five blocks
+    "ten_candidates_very_wide": ("bf16", 10, 100, 256, 256, 32, [100]),       # rows of 256 elements, 8 + 2
     "f32_paper_setting": ("f32", 1, 200, 32, 128, 10, [200, 33, 0]),
 }
 
