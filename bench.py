@@ -7,9 +7,12 @@ A step is one pass of the whole hot path (STA, segment counts, GSTA: `laser_forw
 seeded synthetic input already resident in HBM. Prints ONE JSON line (see the design doc for the fields).
 Order of work: (1) the fp64 CPU checker is timed on a bounded sample of the same workload, before the GPU
 is touched; (2) inputs are generated on the host and uploaded (several distinct copies so the working set
-exceeds the 256 MB last-level cache); (3) warm-up, then K timed steps; (4) the dominant kernel (STA) and GSTA
-are timed on their own with HIP events over K back-to-back launches each; (5) sampled outputs are compared
-with the checker.
+exceeds the 256 MB last-level cache); (3) warm-up, then K timed steps on ONE stream, each step waiting for the
+one before: `value`, `ms_per_step` and `roofline` (the whole step against max(HBM time, MFMA time) of its
+algorithmic bytes and flops) all describe that loop; the same steps dealt over several streams are reported
+beside it as `multi_stream`; (4) the two kernels of a step are timed on their own with HIP events over K
+back-to-back launches each, in the very forms `laser_forward` launches (STA with cacheable H' stores and segment
+counts); (5) sampled outputs are compared with the checker.
 """
 from __future__ import annotations
 
@@ -79,15 +82,18 @@ def _cpu_baseline_timed(spec, wl, n_users, budget_s):
     # the same code over all host cores (one process per core, before any GPU initialisation)
     try:
         import multiprocessing as mp
-        cores = len(os.sched_getaffinity(0))
-        cores = min(cores, 16)
+        host_cores = len(os.sched_getaffinity(0))
+        cores = min(host_cores, 16)   # worker processes: the GPU machines give a job 16 cores whatever they report
+        out["host_cores"] = host_cores
+        out["os_cpu_count"] = os.cpu_count()
         if cores > 1:
             chunks = [pairs[i::cores] for i in range(cores)]
             with mp.get_context("fork").Pool(cores) as pool:
                 t = time.perf_counter()
                 done = sum(pool.map(_oracle_pairs, [(wl, ch) for ch in chunks]))
                 allc = time.perf_counter() - t
-            out["all_cores"] = {"value": done / allc, "cores": cores, "seconds": round(allc, 2)}
+            out["all_cores"] = {"value": done / allc, "cores": cores, "host_cores": host_cores,
+                                "seconds": round(allc, 2)}
     except Exception as e:  # pragma: no cover
         out["all_cores"] = {"error": str(e)}
     return out
@@ -254,9 +260,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copies", type=int, default=0, help="distinct input/output copies to rotate through (0 = auto)")
     ap.add_argument("--streams", type=int, default=3,
-                    help="HIP streams (default priority) over which consecutive steps, which are independent batches, "
-                         "are dealt in turn; 1 = every step waits for the one before. The figure with one stream is "
-                         "always reported beside the headline")
+                    help="HIP streams (default priority) for the secondary \"multi_stream\" figure: consecutive steps, "
+                         "which are independent batches, dealt over that many streams in turn (0 or 1 = skip it). "
+                         "The headline is always the one-stream loop")
     ap.add_argument("--views", type=int, default=0, metavar="R",
                     help="also time the multi-resolution views (max-pooled H' and the R most recent segments): the "
                          "stand-alone kernel and the whole path with them; reported under \"views\"")
@@ -289,7 +295,7 @@ def main() -> int:
 
     import torch
     import paper_2602_11562_amd as laser
-    from parity_util import TOL, DeviceWorkload, oracle_pair, to_host_f64, vec_rel_err
+    from parity_util import ELEM_TOL, TOL, DeviceWorkload, elem_rel_err, oracle_pair, to_host_f64, vec_rel_err
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
@@ -305,6 +311,7 @@ def main() -> int:
     footprint = (wl.q.nbytes + wl.k.nbytes + wl.v.nbytes + wl.t0.nbytes + spec.U * spec.C * spec.S * spec.d * esz
                  + spec.U * spec.C * spec.d * 4)
     nstreams = max(1, min(4, args.streams))
+    dtl_sta = 4 if (spec.dtype == "bf16" and spec.C >= 9) else 0   # LASER_STA_MFMA_CACHED where laser_forward uses it
     copies = args.copies or int(min(8, max(1, math.ceil(600e6 / footprint))))
     copies = -(-copies // nstreams) * nstreams   # a multiple of the streams: a buffer set is only ever used on one stream
 
@@ -321,7 +328,12 @@ def main() -> int:
         laser.laser_forward(dw.q, dw.k, dw.v, dw.t0, dw.wq, dw.wk, dw.wv, dw.lens, spec.w, spec.gamma,
                             seg_out=seg, seg_cnt=cnt, z_out=z, stream=stream)
 
-    def sta_only(i):
+    def sta_only(i):   # the launch laser_forward makes: segment counts written, H' stored for a reader that follows
+        dw, seg, cnt, z = sets[i % copies]
+        laser.laser_sta_forward(dw.q, dw.k, dw.v, dw.lens, spec.w, spec.gamma, seg_out=seg, seg_cnt=cnt,
+                                variant=dtl_sta)
+
+    def sta_alone(i):  # what laser_sta_forward launches when nothing reads H' next (non-temporal stores, no counts)
         dw, seg, cnt, z = sets[i % copies]
         laser.laser_sta_forward(dw.q, dw.k, dw.v, dw.lens, spec.w, spec.gamma, seg_out=seg, want_cnt=False)
 
@@ -344,8 +356,8 @@ def main() -> int:
     # One stream: the latency of a step. Several: consecutive steps are independent batches (a serving process has
     # many in flight), and the tail of one step's kernels overlaps the start of the next step's.
     wall_one = timed_steps([torch.cuda.current_stream()])
-    wall = timed_steps([torch.cuda.Stream() for _ in range(nstreams)]) if nstreams > 1 else wall_one
-    ms_per_step = wall * 1e3 / args.steps
+    wall_multi = timed_steps([torch.cuda.Stream() for _ in range(nstreams)]) if nstreams > 1 else None
+    ms_per_step = wall_one * 1e3 / args.steps
 
     def event_time(fn):
         """Average duration (ms) of K back-to-back launches, HIP events on the launch stream."""
@@ -362,6 +374,8 @@ def main() -> int:
 
     sta_ms = event_time(sta_only)
     gsta_ms = event_time(gsta_only)
+    sta_alone_ms = event_time(sta_alone)
+    step_event_ms = event_time(step)   # the same one-stream loop between HIP events instead of host clocks
 
     views = None
     if args.views > 0:
@@ -487,7 +501,7 @@ def main() -> int:
                     torch.equal(sets[0][3].reshape(spec.U * spec.C, spec.d)[rows], zp))
         ragged = {"pairs": Pr, "counts_min": int(counts.min()), "counts_max": int(counts.max()),
                   "ms_per_step": rag_ms, "pairs_per_s": Pr / (rag_ms * 1e-3),
-                  "dense_padded_ms_per_step": ms_per_step, "equals_dense_rows": same}
+                  "dense_padded_ms_per_step": step_event_ms, "equals_dense_rows": same}
 
     backward = None
     if args.backward:
@@ -546,36 +560,52 @@ def main() -> int:
     torch.cuda.synchronize()
     dw, seg, cnt, z = sets[0]
     rng = np.random.default_rng(0)
-    worst = 0.0
+    worst = worst_el = 0.0
     for _ in range(4):
         r, c = int(rng.integers(spec.U)), int(rng.integers(spec.C))
         Hp_ref, z_ref = oracle_pair(wl, r, c)
         worst = max(worst, vec_rel_err(to_host_f64(seg[r, c]), Hp_ref), vec_rel_err(to_host_f64(z[r, c]), z_ref))
-    parity_ok = worst <= TOL[spec.dtype]
+        worst_el = max(worst_el, elem_rel_err(to_host_f64(seg[r, c]), Hp_ref), elem_rel_err(to_host_f64(z[r, c]), z_ref))
+    parity_ok = worst <= TOL[spec.dtype] and worst_el <= ELEM_TOL[spec.dtype]
 
     dtl = laser.LASER_F32 if spec.dtype == "f32" else laser.LASER_BF16
     sta_kernel = laser.laser_sta_kernel_name(spec.C, spec.d_q, spec.d, spec.w, dtl)
     gsta_kernel = laser.laser_gsta_kernel_name(spec.C, spec.S, spec.d, dtl, spec.M)
-    t_hbm = sta_b / (HBM_PEAK_GBS * 1e9)
-    t_mfma = sta_f / (MFMA_BF16_PEAK_TFLOPS * 1e12)
-    if t_hbm >= t_mfma or spec.dtype == "f32":
-        roof = {"bound": "hbm", "achieved": sta_b / (sta_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
-    else:
-        roof = {"bound": "mfma", "achieved": sta_f / (sta_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
-                "unit": "TFLOP/s"}
-    roof["frac"] = roof["achieved"] / roof["peak"]
-    # HBM bytes per launch as counted by rocprofv3 (FETCH_SIZE / WRITE_SIZE, calibrated): taken from the committed
-    # summary of the profiling run of this same command, when it covers this workload and kernel; else null
+
+    def roofline_of(bytes_, flops, ms):
+        """Time at the published peaks against the measured time: the larger of HBM time and bf16 MFMA time is the
+        bound (fp32 storage runs on the vector ALUs and is priced against HBM only)."""
+        t_h = bytes_ / (HBM_PEAK_GBS * 1e9)
+        t_m = 0.0 if spec.dtype == "f32" else flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+        if t_h >= t_m:
+            r = {"bound": "hbm", "achieved": bytes_ / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+        else:
+            r = {"bound": "mfma", "achieved": flops / (ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
+                 "unit": "TFLOP/s"}
+        r["frac"] = r["achieved"] / r["peak"]
+        r.update({"ms": ms, "algorithmic_bytes": bytes_, "algorithmic_flops": flops,
+                  "t_hbm_us": t_h * 1e6, "t_mfma_us": t_m * 1e6,
+                  "gbps": bytes_ / (ms * 1e-3) / 1e9, "tflops": flops / (ms * 1e-3) / 1e12})
+        return r
+
+    # The step as timed (one stream): algorithmic bytes and flops of the whole path, H' written once and not read back
+    path_b = cm.path_bytes(wl.lens, spec.U, spec.C, spec.L, spec.d_q, spec.d, spec.w, spec.M, spec.dtype)
+    path_f = cm.path_flops(wl.lens, spec.C, spec.d_q, spec.d, spec.w, spec.M)
+    roof = roofline_of(path_b, path_f, ms_per_step)
+    roof["scope"] = "whole step (laser_forward: STA + segment counts + GSTA), one stream, host-timed"
+    # HBM bytes per launch as counted by rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE) cannot be read from inside this
+    # process; the figures of the profiling runs of this same command are kept under profiles/
     roof["traffic"] = None
-    prof = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"bench_{spec.name}.txt")
-    if os.path.exists(prof):
-        for line in open(prof):
-            f = line.split()
-            if len(f) == 3 and f[0] == "traffic_bytes_per_launch" and f[1] == sta_kernel:
-                roof["traffic"] = float(f[2])
-                roof["traffic_source"] = os.path.relpath(prof, os.path.dirname(os.path.abspath(__file__)))
-    roof.update({"kernel": sta_kernel, "kernel_ms": sta_ms, "algorithmic_bytes": sta_b, "algorithmic_flops": sta_f,
-                 "tflops": sta_f / (sta_ms * 1e-3) / 1e12, "gbps": sta_b / (sta_ms * 1e-3) / 1e9})
+    roof["traffic_note"] = f"not measured in this run; see profiles/bench_{spec.name}.txt"
+    roof["step_event_ms"] = step_event_ms
+    # the step's two launches, each timed alone in the form laser_forward launches it
+    k_sta = roofline_of(sta_b, sta_f, sta_ms)
+    k_sta.update({"name": sta_kernel, "form": "as launched by laser_forward: seg_cnt written, H' stored cacheable"})
+    k_gsta = roofline_of(gsta_b, gsta_f, gsta_ms)
+    k_gsta.update({"name": gsta_kernel})
+    roof["dominant_kernel"] = k_sta if sta_ms >= gsta_ms else k_gsta
+    k_alone = roofline_of(sta_b, sta_f, sta_alone_ms)
+    k_alone.update({"name": sta_kernel, "form": "as launched by laser_sta_forward: no seg_cnt, non-temporal H' stores"})
 
     rec = {
         "metric": "STA+GSTA (user,candidate) pairs/sec",
@@ -586,22 +616,22 @@ def main() -> int:
         "dtype": spec.dtype, "data": "synthetic",
         "config": {"workload": spec.name, "U": spec.U, "C": spec.C, "L": spec.L, "d": spec.d, "d_q": spec.d_q,
                    "w": spec.w, "S": spec.S, "M": spec.M, "pairs": spec.pairs, "input_copies": copies,
-                   "streams": nstreams,
+                   "streams": 1,
                    "footprint_mb": footprint / 1e6, "seg_out_written": True},
-        "single_stream": {"ms_per_step": wall_one * 1e3 / args.steps,
-                          "value": spec.pairs / (wall_one / args.steps)},
+        "multi_stream": None if wall_multi is None else {
+            "streams": nstreams, "ms_per_step": wall_multi * 1e3 / args.steps,
+            "value": spec.pairs / (wall_multi / args.steps),
+            "note": "consecutive steps are independent batches dealt over the streams in turn; throughput, not latency"},
         "roofline": roof,
         "cpu_baseline": cpu,
-        "kernels": {"sta": {"name": sta_kernel, "ms": sta_ms}, "gsta": {
-            "name": gsta_kernel, "ms": gsta_ms, "algorithmic_bytes": gsta_b, "algorithmic_flops": gsta_f,
-            "gbps": gsta_b / (gsta_ms * 1e-3) / 1e9}},
+        "kernels": {"sta": k_sta, "gsta": k_gsta, "sta_standalone": k_alone},
         "views": views,
         "ffn": ffn,
         "project": project,
         "ragged": ragged,
         "backward": backward,
-        "parity": {"max_vector_rel_err": worst, "tolerance": TOL[spec.dtype], "ok": bool(parity_ok),
-                   "sampled_pairs": 4},
+        "parity": {"max_vector_rel_err": worst, "max_elementwise_err_floor": worst_el, "tolerance": TOL[spec.dtype],
+                   "ok": bool(parity_ok), "sampled_pairs": 4},
     }
     print(json.dumps(rec))
     return 0 if parity_ok else 1

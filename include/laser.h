@@ -43,10 +43,14 @@ typedef enum {
   LASER_ERR_DTYPE = 3,       /* dt is not a laser_dtype                          */
   LASER_ERR_UNSUPPORTED = 4, /* valid request that no kernel here implements     */
   LASER_ERR_LAUNCH = 5,      /* the HIP runtime refused a launch                 */
-  LASER_ERR_ALIGN = 6        /* a pointer is not 16-byte aligned                 */
+  LASER_ERR_ALIGN = 6,       /* a pointer is not 16-byte aligned                 */
+  LASER_STATUS_ANY_INT = 0x7fffffff
 } laser_status;
 
-typedef enum { LASER_F32 = 0, LASER_BF16 = 1 } laser_dtype;
+/* (The *_ANY_INT members below name no value of their own: they make every non-negative int a representable value of
+ * the enumeration, so that a caller's out-of-range number reaches the library's own check, which answers with
+ * LASER_ERR_DTYPE or LASER_ERR_UNSUPPORTED, instead of being undefined behaviour at the call.) */
+typedef enum { LASER_F32 = 0, LASER_BF16 = 1, LASER_DTYPE_ANY_INT = 0x7fffffff } laser_dtype;
 
 /* Which STA kernel runs. AUTO picks by (dt, C, d_q, d, w); the others force one
  * and return LASER_ERR_UNSUPPORTED when the shape is outside that kernel's range. */
@@ -54,7 +58,10 @@ typedef enum {
   LASER_STA_AUTO = 0,
   LASER_STA_GENERIC = 1, /* fp32 FMA, any shape, either dtype                        */
   LASER_STA_MFMA = 2,    /* bf16 MFMA, many candidates per user                      */
-  LASER_STA_STREAM = 3   /* bf16, few candidates per user, HBM streaming             */
+  LASER_STA_STREAM = 3,  /* bf16, few candidates per user, HBM streaming             */
+  LASER_STA_MFMA_CACHED = 4, /* LASER_STA_MFMA with H' stored cacheable instead of with the non-temporal hint: for a
+                              * caller whose next launch reads H' back (this is the form laser_forward launches) */
+  LASER_STA_VARIANT_ANY_INT = 0x7fffffff
 } laser_sta_variant;
 
 /* Which GSTA kernel runs. */
@@ -63,7 +70,8 @@ typedef enum {
   LASER_GSTA_GENERIC = 1, /* fp32 FMA, one workgroup per pair, any shape              */
   LASER_GSTA_TILED = 2,   /* bf16 storage, a tile of pairs per workgroup, MFMA, any M */
   LASER_GSTA_SPLIT = 3,   /* bf16 storage, M = 1: projection / streaming / output kernels; z_out is the scratch */
-  LASER_GSTA_ONE = 4      /* bf16 storage, M = 1: the same three steps in one launch, 32 pairs per workgroup */
+  LASER_GSTA_ONE = 4,     /* bf16 storage, M = 1: the same three steps in one launch, 32 pairs per workgroup */
+  LASER_GSTA_VARIANT_ANY_INT = 0x7fffffff
 } laser_gsta_variant;
 
 /*
@@ -210,7 +218,8 @@ laser_status laser_segment_ffn_forward_ragged(const void* seg, const int32_t* le
 typedef enum {
   LASER_FFN_AUTO = 0,
   LASER_FFN_GENERIC = 1, /* fp32 FMA, any d and d_ff, either dtype                                   */
-  LASER_FFN_MFMA = 2     /* bf16 MFMA, d = 128, d_ff in {64, 128}, both weight matrices in LDS     */
+  LASER_FFN_MFMA = 2,    /* bf16 MFMA, d = 128, d_ff in {64, 128}, both weight matrices in LDS     */
+  LASER_FFN_VARIANT_ANY_INT = 0x7fffffff
 } laser_ffn_variant;
 
 laser_status laser_segment_ffn_forward(const void* seg, const int32_t* lens, const void* w1, const float* b1,
@@ -279,7 +288,8 @@ laser_status laser_gsta_forward_multires(const void* seg, const void* t0, const 
 typedef enum {
   LASER_PROJECT_AUTO = 0,
   LASER_PROJECT_GENERIC = 1, /* fp32 FMA, any sizes, either dtype                                               */
-  LASER_PROJECT_MFMA = 2     /* bf16 MFMA, d_in = 128, output widths multiples of 32, each <= 128, weights in LDS */
+  LASER_PROJECT_MFMA = 2,    /* bf16 MFMA, d_in = 128, output widths multiples of 32, each <= 128, weights in LDS */
+  LASER_PROJECT_VARIANT_ANY_INT = 0x7fffffff
 } laser_project_variant;
 
 laser_status laser_project_q_forward(const void* t, const void* w_q, int U, int C, int d_in, int d_q, laser_dtype dt,

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblaser.so")
 
 LASER_F32, LASER_BF16 = 0, 1
-STA_AUTO, STA_GENERIC, STA_MFMA, STA_STREAM = 0, 1, 2, 3
+STA_AUTO, STA_GENERIC, STA_MFMA, STA_STREAM, STA_MFMA_CACHED = 0, 1, 2, 3, 4
 GSTA_AUTO, GSTA_GENERIC, GSTA_TILED, GSTA_SPLIT, GSTA_ONE = 0, 1, 2, 3, 4
 FFN_AUTO, FFN_GENERIC, FFN_MFMA = 0, 1, 2
 PROJECT_AUTO, PROJECT_GENERIC, PROJECT_MFMA = 0, 1, 2

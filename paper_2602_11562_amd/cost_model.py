@@ -87,3 +87,20 @@ def gsta_bytes(lens, U, C, L, d, w, M, dtype):
     e = _ESIZE[dtype]
     sv = float(np.sum(np.ceil(np.asarray(lens, dtype=np.float64) / w)))
     return sv * C * d * e + U * C * d * e + 3 * M * d * d * e + U * 4 + U * C * d * 4
+
+
+def path_bytes(lens, U, C, L, d_q, d, w, M, dtype, seg_out_written=True):
+    """HBM bytes one pass of the whole path (STA then GSTA) must move: valid K and V rows, Q, t0, the GSTA weights and
+    lens read once; H' written once when it is returned; z written (fp32). H' is not counted as read: the method
+    does not need it back from memory (GSTA could consume it where it is produced), so a second pass over it is
+    overhead of an implementation, not work of the algorithm."""
+    e = _ESIZE[dtype]
+    S = -(-L // w)
+    n = float(np.sum(np.asarray(lens, dtype=np.float64)))
+    b = n * (d_q + d) * e + U * C * (d_q + d) * e + 3 * M * d * d * e + U * 4 + U * C * d * 4
+    return b + (U * C * S * d * e if seg_out_written else 0)
+
+
+def path_flops(lens, C, d_q, d, w, M):
+    """STA over valid items plus GSTA in the re-associated order."""
+    return sta_flops(lens, C, d_q, d) + gsta_flops(lens, C, d, w, M)

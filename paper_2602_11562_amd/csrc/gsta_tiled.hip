@@ -680,11 +680,20 @@ __global__ __launch_bounds__(GT_THREADS) void gsta_one_kernel(const unsigned sho
   if (tid < 2) arrived[tid] = 0u;
   __syncthreads();   // everyone is here within the first instructions; nothing has been requested yet
   // arrival counter for the lower waves: LDS operations of a wave execute in order, so what it wrote before its
-  // increment is visible to whoever reads the new count; all four waves are resident, so the wait ends
+  // increment is visible to whoever reads the new count. The wait ends because the four lower waves of a workgroup
+  // are resident together (a workgroup is launched whole), none of them leaves the kernel or waits for an upper wave
+  // before its second arrival, and each arrives at each counter exactly once: the count reaches four as soon as the
+  // slowest of them gets there, a few microseconds at most. The poll is bounded all the same, so that no edit of
+  // the code around it can turn a lost arrival into a hang of the machine: after LOWER_SYNC_SPINS polls (about a
+  // tenth of a second, four orders of magnitude beyond any legitimate wait) the wave goes on without the others,
+  // the kernel ends normally, and the results of that workgroup are undefined.
+  constexpr int LOWER_SYNC_SPINS = 1 << 20;
   auto lower_sync = [&](int idx) {
     if (lane == 0) __hip_atomic_fetch_add(&arrived[idx], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
-    while (__hip_atomic_load(&arrived[idx], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < GT_WAVES / 2)
+    for (int spin = 0; spin < LOWER_SYNC_SPINS; ++spin) {
+      if (__hip_atomic_load(&arrived[idx], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) >= GT_WAVES / 2) break;
       __builtin_amdgcn_s_sleep(1);
+    }
   };
   if (!front) {
 #pragma unroll
@@ -909,10 +918,8 @@ static void launch_pt(const GstaArgs& a) {
 // pairs per workgroup: fewer when the batch is small, so that every compute unit still gets a few workgroups
 static int pick_pt(int P) {
   int pt = P >= 8192 ? 32 : 8;   // measured: the per-workgroup set-up cost favours full tiles once every compute unit has one
-  if (const char* e = getenv("LASER_GSTA_PT")) {   // tuning override
-    const int vv = atoi(e);
-    if (vv == 8 || vv == 16 || vv == 32) pt = vv;
-  }
+  const int vv = tuning_int("LASER_GSTA_PT", 0);   // tuning builds only
+  if (vv == 8 || vv == 16 || vv == 32) pt = vv;
   return pt;
 }
 

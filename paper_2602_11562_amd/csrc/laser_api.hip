@@ -7,16 +7,30 @@ namespace laser {
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// a * b * c * d <= lim for non-negative factors, without overflow: the product is cut off as soon as it passes lim
+static bool product_fits(long long lim, long long a, long long b = 1, long long c = 1, long long d = 1) {
+  long long p = 1;
+  for (long long f : {a, b, c, d}) {
+    if (f < 0) return false;
+    if (f != 0 && p > lim / f) return false;
+    p *= f;
+  }
+  return p <= lim;
+}
+
 static laser_status check_dims(int U, int C, int L, int d_q, int d, int w) {
   if (U <= 0 || C <= 0 || L <= 0 || d_q <= 0 || d <= 0 || w <= 0) return LASER_ERR_SHAPE;
   if (d_q > 1024 || d > 1024 || (d_q % 8) != 0 || (d % 8) != 0) return LASER_ERR_SHAPE;
   const long long S = ((long long)L + w - 1) / w;
   const long long lim = 0x7fffffffLL;
-  if ((long long)U * C * d_q > lim || (long long)U * L * d_q > lim || (long long)U * L * d > lim ||
-      (long long)U * C * S * d > lim || (long long)U * S > lim)
+  if (!product_fits(lim, U, C, d_q) || !product_fits(lim, U, L, d_q) || !product_fits(lim, U, L, d) ||
+      !product_fits(lim, U, C, S, d) || !product_fits(lim, U, S))
     return LASER_ERR_SHAPE;
   return LASER_OK;
 }
+
+// S = ceil(L / w) for sizes that passed check_dims (L + w may pass the range of int)
+static int segments(int L, int w) { return (int)(((long long)L + w - 1) / w); }
 
 static laser_status validate_sta(const void* q, const void* k, const void* v, const int32_t* lens, int U, int C,
                                  int L, int d_q, int d, int w, float gamma, laser_dtype dt, void* seg_out,
@@ -29,7 +43,7 @@ static laser_status validate_sta(const void* q, const void* k, const void* v, co
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(seg_out)) return LASER_ERR_ALIGN;
   if ((lens && (reinterpret_cast<uintptr_t>(lens) & 3u)) || (seg_cnt && (reinterpret_cast<uintptr_t>(seg_cnt) & 3u)))
     return LASER_ERR_ALIGN;
-  *out = StaArgs{q, k, v, lens, U, C, L, d_q, d, w, (L + w - 1) / w, gamma, dt, seg_out, seg_cnt,
+  *out = StaArgs{q, k, v, lens, U, C, L, d_q, d, w, segments(L, w), gamma, dt, seg_out, seg_cnt,
                  static_cast<hipStream_t>(stream)};
   return LASER_OK;
 }
@@ -41,7 +55,7 @@ static laser_status validate_gsta(const void* seg, const void* t0, const void* w
   if (dt != LASER_F32 && dt != LASER_BF16) return LASER_ERR_DTYPE;
   laser_status s = check_dims(U, C, L, d, d, w);
   if (s != LASER_OK) return s;
-  const int S = (L + w - 1) / w;
+  const int S = segments(L, w);
   if (M <= 0 || M > 64 || S > 4096) return LASER_ERR_SHAPE;
   if (!aligned16(seg) || !aligned16(t0) || !aligned16(wq) || !aligned16(wk) || !aligned16(wv) || !aligned16(z_out))
     return LASER_ERR_ALIGN;
@@ -57,9 +71,9 @@ static laser_status validate_multires(const void* seg, const int32_t* lens, int 
   if (dt != LASER_F32 && dt != LASER_BF16) return LASER_ERR_DTYPE;
   laser_status s = check_dims(U, C, L, d, d, w);
   if (s != LASER_OK) return s;
-  const int S = (L + w - 1) / w;
+  const int S = segments(L, w);
   if (r < 0 || r > S || (r > 0) != (recent_out != nullptr)) return LASER_ERR_SHAPE;
-  if ((long long)U * C * (r > 0 ? r : 1) * d > 0x7fffffffLL) return LASER_ERR_SHAPE;
+  if (!product_fits(0x7fffffffLL, U, C, r > 0 ? r : 1, d)) return LASER_ERR_SHAPE;
   if (!aligned16(seg) || !aligned16(pool_out) || !aligned16(recent_out)) return LASER_ERR_ALIGN;
   if (lens && (reinterpret_cast<uintptr_t>(lens) & 3u)) return LASER_ERR_ALIGN;
   *out = MultiresArgs{seg, lens, U, C, L, d, w, S, r, dt, pool_out, recent_out, static_cast<hipStream_t>(stream)};
@@ -78,7 +92,7 @@ static laser_status validate_ffn(const void* seg, const int32_t* lens, const voi
   if (!aligned16(seg) || !aligned16(w1) || !aligned16(w2) || !aligned16(seg_out)) return LASER_ERR_ALIGN;
   for (const void* p : {(const void*)b1, (const void*)b2, (const void*)ln_g, (const void*)ln_b, (const void*)lens})
     if (reinterpret_cast<uintptr_t>(p) & 3u) return LASER_ERR_ALIGN;
-  *out = FfnArgs{seg, lens, w1, b1, w2, b2, ln_g, ln_b, U, C, L, d, d_ff, w, (L + w - 1) / w, eps, dt, seg_out,
+  *out = FfnArgs{seg, lens, w1, b1, w2, b2, ln_g, ln_b, U, C, L, d, d_ff, w, segments(L, w), eps, dt, seg_out,
                  static_cast<hipStream_t>(stream)};
   return LASER_OK;
 }
@@ -101,6 +115,12 @@ static laser_status run_sta(const StaArgs& a, laser_sta_variant variant) {
   switch (variant) {
     case LASER_STA_GENERIC: s = sta_generic_launch(a); break;
     case LASER_STA_MFMA: s = sta_mfma_launch(a); break;
+    case LASER_STA_MFMA_CACHED: {
+      StaArgs b = a;
+      b.reread = true;
+      s = sta_mfma_launch(b);
+      break;
+    }
     case LASER_STA_STREAM: s = sta_stream_launch(a); break;
     default: return LASER_ERR_UNSUPPORTED;
   }
@@ -158,7 +178,7 @@ laser_status laser_sta_forward_variant(const void* q, const void* k, const void*
   StaArgs a;
   laser_status s = validate_sta(q, k, v, lens, U, C, L, d_q, d, w, gamma, dt, seg_out, seg_cnt, stream, &a);
   if (s != LASER_OK) return s;
-  if (variant < LASER_STA_AUTO || variant > LASER_STA_STREAM) return LASER_ERR_UNSUPPORTED;
+  if (variant < LASER_STA_AUTO || variant > LASER_STA_MFMA_CACHED) return LASER_ERR_UNSUPPORTED;
   return run_sta(a, variant);
 }
 
@@ -169,7 +189,7 @@ laser_status laser_sta_forward_heads(const void* q, const void* k, const void* v
   laser_status s = validate_sta(q, k, v, lens, U, C, L, d_q, d, w, gamma, dt, seg_out, seg_cnt, stream, &a);
   if (s != LASER_OK) return s;
   if (heads < 1 || heads > 64 || d_q % heads != 0 || d % heads != 0) return LASER_ERR_SHAPE;
-  if (variant < LASER_STA_AUTO || variant > LASER_STA_STREAM) return LASER_ERR_UNSUPPORTED;
+  if (variant < LASER_STA_AUTO || variant > LASER_STA_MFMA_CACHED) return LASER_ERR_UNSUPPORTED;
   a.heads = heads;
   return run_sta(a, variant);
 }
@@ -181,7 +201,7 @@ laser_status laser_sta_forward_softmax(const void* q, const void* k, const void*
   laser_status s = validate_sta(q, k, v, lens, U, C, L, d_q, d, w, gamma, dt, seg_out, seg_cnt, stream, &a);
   if (s != LASER_OK) return s;
   if (heads < 1 || heads > 64 || d_q % heads != 0 || d % heads != 0) return LASER_ERR_SHAPE;
-  if (variant < LASER_STA_AUTO || variant > LASER_STA_STREAM) return LASER_ERR_UNSUPPORTED;
+  if (variant < LASER_STA_AUTO || variant > LASER_STA_MFMA_CACHED) return LASER_ERR_UNSUPPORTED;
   a.heads = heads;
   a.softmax = true;
   return run_sta(a, variant);
@@ -193,7 +213,7 @@ static laser_status validate_ragged(const int32_t* cand_off, int U, int C_max, i
   if (reinterpret_cast<uintptr_t>(cand_off) & 3u) return LASER_ERR_ALIGN;
   if (P <= 0 || (long long)P > (long long)U * C_max) return LASER_ERR_SHAPE;
   const long long S = ((long long)L + w - 1) / w;
-  if ((long long)P * S * d > 0x7fffffffLL || (long long)P * d_q > 0x7fffffffLL) return LASER_ERR_SHAPE;
+  if (!product_fits(0x7fffffffLL, P, S, d) || !product_fits(0x7fffffffLL, P, d_q)) return LASER_ERR_SHAPE;
   return LASER_OK;
 }
 
@@ -434,7 +454,7 @@ static laser_status validate_project_heads(const void* x, const void* w_v, int P
   if (P <= 0 || S <= 0 || d_in <= 0 || d_in > 4096 || d <= 0 || d > 4096 || heads < 1 || heads > 64 || d % heads != 0)
     return LASER_ERR_SHAPE;
   if ((d_in % 8) != 0 || (d % 8) != 0) return LASER_ERR_SHAPE;
-  if ((long long)P * heads * S * d_in > 0x7fffffffLL || (long long)P * S * d > 0x7fffffffLL) return LASER_ERR_SHAPE;
+  if (!product_fits(0x7fffffffLL, P, heads, S, d_in) || !product_fits(0x7fffffffLL, P, S, d)) return LASER_ERR_SHAPE;
   if (!aligned16(x) || !aligned16(w_v) || !aligned16(y)) return LASER_ERR_ALIGN;
   *out = ProjHeadsArgs{x, w_v, (long long)P, S, d_in, d, heads, dt, y, static_cast<hipStream_t>(stream)};
   return LASER_OK;
@@ -491,24 +511,39 @@ laser_status laser_sta_folded_forward(const void* t, const void* h, const void* 
 }
 
 size_t laser_sta_backward_work_bytes(int U, int C, int L, int d_q, int w) {
-  if (U <= 0 || C <= 0 || L <= 0 || d_q <= 0 || w <= 0) return 0;
+  if (check_dims(U, C, L, d_q, 8, w) != LASER_OK) return 0;   // (8: any valid value width; it does not enter the size)
   return sta_backward_work_bytes(U, C, L, d_q, w);
+}
+
+// Everything about a backward call of STA except its scratch: checks, then the launcher's arguments (work unset)
+static laser_status sta_backward_validate(const void* q, const void* k, const void* v, const int32_t* lens,
+                                          const void* dseg, int U, int C, int L, int d_q, int d, int w, float gamma,
+                                          laser_dtype dt, float* dq_out, void* dk_out, void* dv_out, bool grads_bf16,
+                                          void* stream, StaBwdArgs* out) {
+  if (!dseg || !dq_out || !dk_out || !dv_out) return LASER_ERR_NULL;
+  StaArgs fa;   // the forward pass's checks of the shared arguments (dseg stands in for seg_out: same shape and type)
+  laser_status s = validate_sta(q, k, v, lens, U, C, L, d_q, d, w, gamma, dt, const_cast<void*>(dseg), nullptr, stream,
+                                &fa);
+  if (s != LASER_OK) return s;
+  if (!aligned16(dq_out) || !aligned16(dk_out) || !aligned16(dv_out)) return LASER_ERR_ALIGN;
+  *out = StaBwdArgs{q, k, v, dseg, lens, U, C, L, d_q, d, w, fa.S, gamma, dt, dq_out, dk_out, dv_out, nullptr,
+                    static_cast<hipStream_t>(stream)};
+  out->grads_bf16 = grads_bf16;
+  return LASER_OK;
 }
 
 static laser_status sta_backward_any(const void* q, const void* k, const void* v, const int32_t* lens, const void* dseg,
                                      int U, int C, int L, int d_q, int d, int w, float gamma, laser_dtype dt,
                                      float* dq_out, void* dk_out, void* dv_out, bool grads_bf16, void* work,
                                      size_t work_bytes, void* stream) {
-  if (!dseg || !dq_out || !dk_out || !dv_out || !work) return LASER_ERR_NULL;
-  StaArgs fa;   // the forward pass's checks of the shared arguments (dseg stands in for seg_out: same shape and type)
-  laser_status s = validate_sta(q, k, v, lens, U, C, L, d_q, d, w, gamma, dt, const_cast<void*>(dseg), nullptr, stream,
-                                &fa);
+  if (!work) return LASER_ERR_NULL;
+  StaBwdArgs a;
+  const laser_status s = sta_backward_validate(q, k, v, lens, dseg, U, C, L, d_q, d, w, gamma, dt, dq_out, dk_out,
+                                               dv_out, grads_bf16, stream, &a);
   if (s != LASER_OK) return s;
-  if (!aligned16(dq_out) || !aligned16(dk_out) || !aligned16(dv_out) || !aligned16(work)) return LASER_ERR_ALIGN;
+  if (!aligned16(work)) return LASER_ERR_ALIGN;
   if (work_bytes < sta_backward_work_bytes(U, C, L, d_q, w)) return LASER_ERR_SHAPE;
-  StaBwdArgs a{q, k, v, dseg, lens, U, C, L, d_q, d, w, fa.S, gamma, dt, dq_out, dk_out, dv_out,
-               static_cast<float*>(work), static_cast<hipStream_t>(stream)};
-  a.grads_bf16 = grads_bf16;
+  a.work = static_cast<float*>(work);
   return sta_backward_launch(a);
 }
 
@@ -527,7 +562,7 @@ laser_status laser_sta_backward_bf16(const void* q, const void* k, const void* v
 }
 
 size_t laser_gsta_backward_work_bytes(int U, int C, int d, int M) {
-  if (U <= 0 || C <= 0 || d <= 0 || M <= 0) return 0;
+  if (U <= 0 || C <= 0 || d <= 0 || M <= 0 || d > 1024 || M > 64 || !product_fits(0x7fffffffLL, U, C, d)) return 0;
   return gsta_backward_work_bytes(U, C, d, M);
 }
 
@@ -584,6 +619,7 @@ const char* laser_status_string(laser_status s) {
     case LASER_ERR_UNSUPPORTED: return "shape not supported by the requested kernel";
     case LASER_ERR_LAUNCH: return "HIP launch failed";
     case LASER_ERR_ALIGN: return "pointer not sufficiently aligned";
+    default: break;
   }
   return "unknown status";
 }

@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "laser.h"
 
@@ -175,6 +176,17 @@ laser_status gsta_split_launch(const GstaArgs& a);
 bool gsta_one_supports(const GstaArgs& a);
 laser_status gsta_one_launch(const GstaArgs& a);
 int gsta_one_max_recent(int d);   // largest r whose recent_out the one-kernel form writes itself
+
+// Tuning overrides (workgroup shapes, kernel forms) exist only in builds made with -DLASER_TUNING, which are for
+// parameter sweeps: the library as shipped never reads the environment, so it has one behaviour. Returns the
+// variable's integer value, or `unset` when the variable is absent or the build is the shipped one.
+inline int tuning_int(const char* name, int unset) {
+#ifdef LASER_TUNING
+  if (const char* e = getenv(name)) return atoi(e);
+#endif
+  (void)name;
+  return unset;
+}
 
 inline laser_status launch_status() { return hipGetLastError() == hipSuccess ? LASER_OK : LASER_ERR_LAUNCH; }
 

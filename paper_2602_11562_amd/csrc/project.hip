@@ -395,7 +395,7 @@ laser_status project_mfma_launch(const ProjArgs& a) {
   // requesting rows a tile ahead gains nothing measurable (two waves per SIMD already cover the latency).
   const double bytes = (double)a.rows * (a.d_in + a.n[0] + a.n[1]) * 2.0;
   int mode = bytes <= 2.0e9 ? 2 : 0;
-  if (const char* e = getenv("LASER_PROJECT_MODE")) mode = atoi(e) & 3;   // tuning override: 1 = PF, 2 = NTS
+  mode = tuning_int("LASER_PROJECT_MODE", mode) & 3;   // tuning builds only: 1 = PF, 2 = NTS
 #define LASER_PROJECT_LAUNCH(PF, NTS)                                                                              \
   hipLaunchKernelGGL((project_mfma_kernel<PF, NTS>), dim3((unsigned)blocks), dim3(PM_THREADS), 0, a.stream,        \
                      (const unsigned short*)a.x, (const unsigned short*)a.w[0], (const unsigned short*)a.w[1],     \

@@ -387,10 +387,8 @@ static void sta_bwd_shape(int U, int S, int w, int* spg, int* groups) {
   // short segments: runs of a dozen even out histories of different lengths (2048 users x 100 segments of 10 items,
   // lengths 200..1000: 677 us with whole users, 588 us with runs of 8 to 12)
   if (w <= 32 && *spg > 12) *spg = 12;
-  if (const char* e = getenv("LASER_BWD_SPG")) {   // tuning override
-    const int vv = atoi(e);
-    if (vv >= 1 && vv <= S) *spg = vv;
-  }
+  const int spg_forced = tuning_int("LASER_BWD_SPG", 0);   // tuning builds only
+  if (spg_forced >= 1 && spg_forced <= S) *spg = spg_forced;
   *groups = (S + *spg - 1) / *spg;
 }
 
@@ -399,10 +397,8 @@ static bool sta_bwd_wide_supports(const StaBwdArgs& a);
 // length classes: worth their empty workgroups once the launch is several rounds of workgroups and lengths differ
 static int sta_bwd_classes(const StaBwdArgs& a, unsigned blocks) {
   int classes = (a.lens != nullptr && blocks >= 4096 && (unsigned long long)blocks * 4 <= 0x7fffffffULL) ? 4 : 1;
-  if (const char* e = getenv("LASER_STREAM_CLASSES")) {   // tuning override, shared with the forward kernel
-    const int vv = atoi(e);
-    if (vv >= 1 && vv <= 8 && (unsigned long long)blocks * vv <= 0x7fffffffULL) classes = vv;
-  }
+  const int cls_forced = tuning_int("LASER_STREAM_CLASSES", 0);   // tuning builds only, shared with the forward kernel
+  if (cls_forced >= 1 && cls_forced <= 8 && (unsigned long long)blocks * cls_forced <= 0x7fffffffULL) classes = cls_forced;
   return classes;
 }
 
@@ -456,7 +452,7 @@ static void sta_bwd_launch_q(const StaBwdArgs& a, unsigned blocks, size_t lds, i
 
 static bool sta_bwd_wide_supports(const StaBwdArgs& a) {
   return a.dt == LASER_BF16 && a.C <= 4 && (a.d_q == 32 || a.d_q == 64 || a.d_q == 128) && (a.d == 64 || a.d == 128) &&
-         getenv("LASER_BWD_NARROW") == nullptr;   // tuning override: the one-item-per-wave kernel for every shape
+         tuning_int("LASER_BWD_NARROW", 0) == 0;   // tuning builds: the one-item-per-wave kernel for every shape
 }
 
 template <int DQ, int D>

@@ -1100,10 +1100,8 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
 
 // ------------------------------------------------------------------------------------------ host side
 static int pick_nw(int C) {
-  if (const char* e = getenv("LASER_STA_NW")) {   // tuning override: waves (32 candidates each) per workgroup
-    const int vv = atoi(e);
-    if (vv == 1 || vv == 2 || vv == 4 || vv == 8) return vv;
-  }
+  const int vv = tuning_int("LASER_STA_NW", 0);   // tuning builds: waves (32 candidates each) per workgroup
+  if (vv == 1 || vv == 2 || vv == 4 || vv == 8) return vv;
   return C > 128 ? 8 : (C > 64 ? 4 : (C > 32 ? 2 : 1));
 }
 
@@ -1131,7 +1129,7 @@ static void launch_one(const StaArgs& a, int spw, int ctiles, int sruns, float n
 template <int DQ, int D>
 static void launch_nw(const StaArgs& a, int nw, int spw, int ctiles, int sruns, float nsl) {
   // eight waves fill a compute unit on their own and prefetch through LDS buffers of their own (direct-to-LDS
-  // fetches for d_q = d = 128; LASER_STA_NODMA=1 selects the register-staged form there too, for comparison);
+  // fetches for d_q = d = 128; a tuning build can select the register-staged form there too, for comparison);
   // smaller workgroups overlap memory and MFMA work across the several workgroups that share a compute unit
   // two heads, the softmax variant: the register-staged form for every workgroup size (two tile buffers with
   // eight waves)
@@ -1152,7 +1150,7 @@ static void launch_nw(const StaArgs& a, int nw, int spw, int ctiles, int sruns, 
     else LASER_STA_STAGED(1, true);
   } else if (a.heads == 2) {
     LASER_STA_STAGED(2, false);
-  } else if (nw == 8 && DQ == 128 && D == 128 && getenv("LASER_STA_NODMA") == nullptr) {
+  } else if (nw == 8 && DQ == 128 && D == 128 && tuning_int("LASER_STA_NODMA", 0) == 0) {
     const unsigned blocks = (unsigned)((long long)a.U * ctiles * sruns);
     if (a.reread)
       hipLaunchKernelGGL((sta_mfma_dma_kernel<8, false>), dim3(blocks), dim3(512), 0, a.stream,
@@ -1184,10 +1182,8 @@ laser_status sta_mfma_launch(const StaArgs& a) {
   const long long want = 2048 / nw;
   int spw = 1;
   while (spw < 8 && (long long)a.U * ctiles * ((a.S + 2 * spw - 1) / (2 * spw)) >= want) spw *= 2;
-  if (const char* e = getenv("LASER_STA_SPW")) {   // tuning override
-    const int vv = atoi(e);
-    if (vv >= 1 && vv <= 64) spw = vv;
-  }
+  const int spw_forced = tuning_int("LASER_STA_SPW", 0);   // tuning builds only
+  if (spw_forced >= 1 && spw_forced <= 64) spw = spw_forced;
   const int sruns = (a.S + spw - 1) / spw;
   const float nsl = -1.4426950408889634f / a.gamma;
   const int key = a.d_q * 1000 + a.d;

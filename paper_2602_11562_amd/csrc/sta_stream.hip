@@ -513,20 +513,16 @@ static void launch_c(const StaArgs& a, float nsl) {
   // length: runs of a dozen segments (three per wave) even out the load where whole users do not (measured on
   // 2048 users x 100 segments of 10 items with lengths between 200 and 1000: 110 us -> 86 us)
   if (short_seg && spg > 12) spg = 12;
-  if (const char* e = getenv("LASER_STREAM_SPG")) {   // tuning override
-    const int vv = atoi(e);
-    if (vv >= 1 && vv <= a.S) spg = vv;
-  }
+  const int spg_forced = tuning_int("LASER_STREAM_SPG", 0);   // tuning builds only
+  if (spg_forced >= 1 && spg_forced <= a.S) spg = spg_forced;
   groups = (a.S + spg - 1) / spg;
   const unsigned blocks = (unsigned)((long long)a.U * groups);
   // length classes (long form only): worth their empty workgroups once the launch is several rounds of workgroups
   // and the lengths differ at all (4096 users with log-uniform lengths 64..4096: 206 us with one class, 193 with
   // two, 182 with four, 186 with eight)
   int classes = (a.lens != nullptr && blocks >= 4096 && (unsigned long long)blocks * 4 <= 0x7fffffffULL) ? 4 : 1;
-  if (const char* e = getenv("LASER_STREAM_CLASSES")) {   // tuning override
-    const int vv = atoi(e);
-    if (vv >= 1 && vv <= 8 && (unsigned long long)blocks * vv <= 0x7fffffffULL) classes = vv;
-  }
+  const int cls_forced = tuning_int("LASER_STREAM_CLASSES", 0);   // tuning builds only
+  if (cls_forced >= 1 && cls_forced <= 8 && (unsigned long long)blocks * cls_forced <= 0x7fffffffULL) classes = cls_forced;
 #define LASER_STREAM_LAUNCH(CM)                                                                                      \
   do {                                                                                                               \
     if (short_seg && a.softmax)                                                                                      \

@@ -1,0 +1,92 @@
+// Host-side check of the C ABI under AddressSanitizer and UndefinedBehaviorSanitizer (no GPU needed): every entry
+// point is called with arguments that validation must refuse before anything is launched, among them sizes at the
+// edge of int, so that the size arithmetic of the host code (products, roundings up, work-space sizes) runs under
+// the sanitizers. The data pointers are never dereferenced on these paths. Built by
+// paper_2602_11562_amd.build.build_host_check() with the host code of laser_api.hip instrumented; run by
+// tests/test_abi_cpu.py. Exit status 0 = every call returned the expected status (a sanitizer report aborts).
+#include <climits>
+#include <cstdint>
+#include <cstdio>
+
+#include "laser.h"
+
+static int failures = 0;
+#define EXPECT(call, want)                                                                   \
+  do {                                                                                       \
+    const int got_ = (int)(call);                                                            \
+    if (got_ != (int)(want)) {                                                               \
+      ++failures;                                                                            \
+      std::printf("line %d: status %d, expected %d: %s\n", __LINE__, got_, (int)(want), #call); \
+    }                                                                                        \
+  } while (0)
+
+int main() {
+  void* const A = reinterpret_cast<void*>(0x10000);   // aligned, non-NULL, never dereferenced
+  void* const A8 = reinterpret_cast<void*>(0x10008);
+  int32_t* const I = reinterpret_cast<int32_t*>(0x10000);
+  float* const F = reinterpret_cast<float*>(0x10000);
+  const laser_dtype bf = LASER_BF16;
+  const int BIG = INT_MAX;
+
+  // STA: NULL, dtype, sizes at the edge of int, alignment
+  EXPECT(laser_sta_forward(nullptr, A, A, nullptr, 2, 3, 64, 16, 16, 8, 1.0f, bf, A, nullptr, nullptr), LASER_ERR_NULL);
+  EXPECT(laser_sta_forward(A, A, A, nullptr, 2, 3, 64, 16, 16, 8, 1.0f, (laser_dtype)7, A, nullptr, nullptr), LASER_ERR_DTYPE);
+  EXPECT(laser_sta_forward(A, A, A, nullptr, BIG, BIG, BIG, 1024, 1024, 1, 1.0f, bf, A, nullptr, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_sta_forward(A, A, A, nullptr, 1, 1, BIG, 8, 8, BIG, 1.0f, bf, A, nullptr, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_sta_forward(A, A, A, nullptr, 1, 1, 2, 8, 8, BIG, 1.0f, bf, A8, nullptr, nullptr), LASER_ERR_ALIGN);
+  EXPECT(laser_sta_forward(A, A, A, nullptr, 1, BIG, 2, 8, 8, BIG, 1.0f, bf, A, nullptr, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_sta_forward(A, A, A, nullptr, INT_MIN, 3, 64, 16, 16, 8, 1.0f, bf, A, nullptr, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_sta_forward_variant(A, A, A, nullptr, 2, 3, 64, 16, 16, 8, 1.0f, bf, A, nullptr, nullptr, (laser_sta_variant)9), LASER_ERR_UNSUPPORTED);
+  EXPECT(laser_sta_forward_heads(A, A, A, nullptr, 2, 3, 64, 16, 16, 8, 1.0f, BIG, bf, A, nullptr, nullptr, LASER_STA_AUTO), LASER_ERR_SHAPE);
+  EXPECT(laser_sta_forward_softmax(A, A, A, nullptr, 2, 3, 64, 16, 16, 8, 1.0f, 0, bf, A, nullptr, nullptr, LASER_STA_AUTO), LASER_ERR_SHAPE);
+  EXPECT(laser_sta_forward_ragged(A, A, A, nullptr, I, 3, 8, BIG, 64, 16, 16, 8, 1.0f, bf, A, nullptr, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_sta_forward_ragged(A, A, A, nullptr, nullptr, 3, 8, 10, 64, 16, 16, 8, 1.0f, bf, A, nullptr, nullptr), LASER_ERR_NULL);
+
+  // GSTA and the whole path
+  EXPECT(laser_gsta_forward(A, A, A, A, nullptr, nullptr, 2, 3, 64, 16, 8, 1, bf, F, nullptr), LASER_ERR_NULL);
+  EXPECT(laser_gsta_forward(A, A, A, A, A, nullptr, 2, 3, BIG, 16, 1, 1, bf, F, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_gsta_forward(A, A, A, A, A, nullptr, 2, 3, 64, 16, 8, BIG, bf, F, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_gsta_forward_variant(A, A, A, A, A, nullptr, 2, 3, 64, 16, 8, 1, bf, F, nullptr, (laser_gsta_variant)77), LASER_ERR_UNSUPPORTED);
+  EXPECT(laser_gsta_forward_ragged(A, A, A, A, A, nullptr, I, 3, 8, BIG, 64, 16, 8, 1, bf, F, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_forward(A, A, A, nullptr, A, A, A, nullptr, 2, 3, 64, 16, 16, 8, 1.0f, 1, bf, A, nullptr, F, nullptr), LASER_ERR_NULL);
+  EXPECT(laser_forward(A, A, A, A, A, A, A, nullptr, 2, 3, 64, 16, 16, BIG, 1.0f, 0, bf, A, nullptr, F, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_forward_ragged(A, A, A, A, A, A, A, nullptr, I, 3, 8, 25, 64, 16, 16, 8, 1.0f, 1, bf, A, nullptr, F, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_forward_multires(A, A, A, A, A, A, A, nullptr, 2, 3, 64, 16, 16, 8, 1.0f, 1, bf, A, nullptr, F, BIG, A, A, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_gsta_forward_multires(A, A, A, A, A, nullptr, 2, 3, 64, 16, 8, 1, bf, F, -1, A, A, nullptr), LASER_ERR_SHAPE);
+
+  // views, FFN, projections, folded form
+  EXPECT(laser_multires_forward(A, nullptr, 2, 3, 64, 16, 8, 9, bf, A, A, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_multires_forward(A, nullptr, BIG, BIG, 64, 16, 8, 2, bf, A, A, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_multires_forward_ragged(A, nullptr, I, 3, 8, 0, 64, 16, 8, 2, bf, A, A, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_segment_ffn_forward(A, nullptr, A, F, A, F, F, F, 2, 3, 64, 16, BIG, 8, 1e-5f, bf, A, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_segment_ffn_forward_variant(A, nullptr, A, F, A, F, F, F, 2, 3, 64, 16, 32, 8, 1e-5f, bf, A, nullptr, (laser_ffn_variant)9), LASER_ERR_UNSUPPORTED);
+  EXPECT(laser_segment_ffn_forward_ragged(A, nullptr, I, A, F, A, F, F, F, 3, 8, 25, 64, 16, 32, 8, 1e-5f, bf, A, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_project_q_forward(A, A, BIG, BIG, 16, 8, bf, A, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_project_q_forward(A, A, 2, 3, BIG, 8, bf, A, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_project_kv_forward(A, A, A, 2, 64, 16, BIG, 16, bf, A, A, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_project_kv_forward_variant(A, A, A, 2, 64, 16, 8, 16, bf, A, A, nullptr, LASER_PROJECT_MFMA), LASER_ERR_UNSUPPORTED);
+  EXPECT(laser_fold_query_weights(A, A, 16, 8, 3, bf, A, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_project_heads_forward(A, A, BIG, BIG, 16, 16, 2, bf, A, nullptr, LASER_PROJECT_AUTO), LASER_ERR_SHAPE);
+  EXPECT(laser_sta_folded_forward(A, A, A, A, nullptr, 2, BIG, 64, 16, 16, 8, 1.0f, 64, bf, A, A, A, nullptr, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_sta_folded_forward(A, A, A, A, nullptr, 2, 1, 64, 4096, 16, 8, 1.0f, 2, bf, A, A, A, nullptr, nullptr), LASER_ERR_SHAPE);
+
+  // backward passes: the work-space sizes are computed from the caller's sizes before anything else
+  EXPECT(laser_sta_backward_work_bytes(0, 2, 64, 16, 8) != 0, 0);
+  EXPECT(laser_sta_backward_work_bytes(BIG, BIG, BIG, BIG, 1) == 0, 1);   // refused: 0
+  EXPECT(laser_sta_backward(A, A, A, nullptr, A, 3, 2, 64, 16, 16, 8, 1.0f, bf, F, F, F, A, 8, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_sta_backward(A, A, A, nullptr, A, 3, 2, 64, 512, 512, 8, 1.0f, bf, F, F, F, A, (size_t)1 << 30, nullptr), LASER_ERR_UNSUPPORTED);
+  EXPECT(laser_sta_backward_bf16(A, A, A, nullptr, A, 1, 8, 64, 32, 64, 8, 1.0f, F, A, A, A, (size_t)1 << 30, nullptr), LASER_ERR_UNSUPPORTED);
+  EXPECT(laser_gsta_backward_work_bytes(3, 0, 16, 2) != 0, 0);
+  EXPECT(laser_gsta_backward_work_bytes(BIG, BIG, BIG, BIG) == 0, 1);
+  EXPECT(laser_gsta_backward(A, A, A, A, A, nullptr, F, 3, 2, 64, 16, 8, 2, bf, A, F, F, F, F, A, 64, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_gsta_backward(A, A, A, A, A, nullptr, F, 3, 2, 1 << 15, 256, 8, 2, bf, A, F, F, F, F, A, (size_t)1 << 32, nullptr), LASER_ERR_UNSUPPORTED);
+
+  // names and strings
+  EXPECT(laser_sta_kernel_name(BIG, BIG, BIG, BIG, bf) == nullptr, 0);
+  EXPECT(laser_gsta_kernel_name_layers(BIG, BIG, BIG, BIG, bf) == nullptr, 0);
+  EXPECT(laser_status_string((laser_status)99) == nullptr, 0);
+  EXPECT(laser_version() >= 100, 1);
+
+  std::printf("abi_host_check: %d failure(s)\n", failures);
+  return failures == 0 ? 0 : 1;
+}

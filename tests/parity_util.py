@@ -4,6 +4,13 @@ Error metric (used for every floating-point output): for each output vector x (o
 z[u,c,:]) the error is max|x_gpu - x_ref| / max|x_ref|; the reported figure is the maximum over vectors.
 Vectors whose reference is exactly zero (empty segments) must be exactly zero on the GPU.
 Tolerances: 1e-5 for fp32 storage; 2e-2 for bf16 storage with fp32 accumulation.
+
+Second figure, element by element (`elem_rel_err`): |x_gpu - x_ref| / max(|x_ref|, floor) with floor = the root mean
+square of the reference vector the element belongs to, so that the small components of a vector are bounded one by one
+and not only through its largest one, while components that cancel to nearly nothing do not divide by nearly nothing.
+Its bound is the vector tolerance times 2.5, the ratio of the largest component to the root mean square in a vector
+of 64 to 128 roughly Gaussian components: the two figures then ask the same of the largest component and the second
+asks it of every other one too.
 """
 from __future__ import annotations
 
@@ -13,6 +20,7 @@ import oracle
 from workloads.configs import Workload, stored_values
 
 TOL = {"f32": 1e-5, "bf16": 2e-2}
+ELEM_TOL = {"f32": 2.5e-5, "bf16": 5e-2}
 
 
 def to_device(arr: np.ndarray):
@@ -67,6 +75,20 @@ def vec_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
     assert (num[zero] == 0).all(), "a vector that must be exactly zero is not"
     den = np.where(zero, 1.0, den)
     return float((num / den).max()) if num.size else 0.0
+
+
+def elem_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """Maximum over elements of |got - ref| / max(|ref|, rms of the element's reference vector (last axis))."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    if ref.size == 0:
+        return 0.0
+    floor = np.sqrt(np.mean(ref * ref, axis=-1, keepdims=True))
+    den = np.maximum(np.abs(ref), floor)
+    zero = den == 0                      # whole vector exactly zero: must match exactly (checked by vec_rel_err too)
+    assert (got[np.broadcast_to(zero, got.shape)] == 0).all(), "an element that must be exactly zero is not"
+    return float((np.abs(got - ref) / np.where(zero, 1.0, den)).max())
 
 
 def round_like(x: np.ndarray, dtype: str) -> np.ndarray:

@@ -292,3 +292,15 @@ def test_ragged_views_and_ffn_argument_validation(lib):
         seg, None, off, A, A, A, A, A, A, 3, 8, P, 64, 16, dff, 8, ctypes.c_float(1e-5), 1, out, None)
     assert ffn(seg=None) == NULL and ffn(off=None) == NULL and ffn(out=None) == NULL
     assert ffn(P=0) == SHAPE and ffn(P=25) == SHAPE and ffn(dff=12) == SHAPE and ffn(off=A + 1) == ALIGN
+
+
+def test_host_code_under_address_and_undefined_behaviour_sanitizers(lib, tmp_path):
+    """The host side of the boundary (validation, kernel selection, size arithmetic) instrumented with ASan and UBSan,
+    driven by tests/abi_host_check.cpp with sizes at the edge of int: a sanitizer report aborts the run."""
+    import subprocess
+    from paper_2602_11562_amd.build import build_host_check
+    exe = build_host_check(str(tmp_path / "abi_host_check"))
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    r = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=120)
+    assert r.returncode == 0, r.stdout[-3000:] + r.stderr[-3000:]
+    assert "0 failure(s)" in r.stdout

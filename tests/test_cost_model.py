@@ -52,3 +52,14 @@ def test_kernel_accounting_matches_hand_numbers_for_the_headline_workload():
     assert abs(cm.sta_flops(lens, 256, 128, 128) - 17.18e9) / 17.18e9 < 1e-3
     b = cm.sta_bytes(lens, 32, 256, 4096, 128, 128, 128, "bf16")
     assert abs(b - (67.1e6 + 2.1e6 + 67.1e6)) / 136.3e6 < 2e-3
+
+
+def test_whole_path_accounting_for_the_headline_workload():
+    # K, V 67.1 MB + Q, t0 4.2 MB + weights 0.1 MB + H' 67.1 MB + z 4.2 MB = 142.7 MB; 75.6 MB without H'
+    lens = np.full(32, 4096)
+    full = cm.path_bytes(lens, 32, 256, 4096, 128, 128, 128, 1, "bf16")
+    zonly = cm.path_bytes(lens, 32, 256, 4096, 128, 128, 128, 1, "bf16", seg_out_written=False)
+    assert abs(full - 142.7e6) / 142.7e6 < 2e-3 and abs(zonly - 75.6e6) / 75.6e6 < 2e-3
+    assert abs(full - zonly - 32 * 256 * 32 * 128 * 2) < 1
+    f = cm.path_flops(lens, 256, 128, 128, 128, 1)
+    assert abs(f - (17.18e9 + 0.67e9)) / 17.85e9 < 0.02
