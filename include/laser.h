@@ -369,6 +369,24 @@ laser_status laser_sta_backward_bf16(const void* q, const void* k, const void* v
                                      void* dk_out, void* dv_out, void* work, size_t work_bytes, void* stream);
 
 /*
+ * laser_sta_backward for callers that cannot allocate device memory at all (code under HIP graph capture, tight
+ * serving or training loops, harnesses that forbid hipMalloc): the same operation, kernels, results (bit for bit) and
+ * errors, with the scratch of partial dq sums taken from a fixed array inside the library instead of a caller's
+ * buffer. The array is device memory of the library's own code object, LASER_STATIC_SCRATCH_BYTES per GPU, held by
+ * every GPU the library runs on until the process ends; its address is looked up once per device, on the first call
+ * with that device current (a symbol lookup, no allocation). The call allocates and frees nothing.
+ * Limit: laser_sta_backward_work_bytes(U, C, L, d_q, w) <= LASER_STATIC_SCRATCH_BYTES, else LASER_ERR_SHAPE and
+ * nothing is launched (the paper's training batch of 2048 x 1 targets, L = 1000, w = 10, d_q = 32 needs 2.4 MB).
+ * Every call on a GPU uses that GPU's one array: calls that overlap in time on the same GPU (two streams, two
+ * threads) race on it and must be serialised by the caller; calls in order on one stream are safe. Nothing in the
+ * array has to start at zero (every partial sum that is read is written first by the same call).
+ */
+#define LASER_STATIC_SCRATCH_BYTES (8u << 20)
+laser_status laser_sta_backward_static(const void* q, const void* k, const void* v, const int32_t* lens,
+                                       const void* dseg, int U, int C, int L, int d_q, int d, int w, float gamma,
+                                       laser_dtype dt, float* dq_out, float* dk_out, float* dv_out, void* stream);
+
+/*
  * Backward pass of GSTA (the derivatives of the forward equations of paper Sec. 3.4.3: per layer q' = t W_q,
  * e = (H' W_k) q' / sqrt(d), a = softmax over the valid segments, t <- t + a (H' W_v); the paper prints no backward
  * formulas). Given dz = d loss / d z [U,C,d] (fp32):

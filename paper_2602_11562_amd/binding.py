@@ -29,7 +29,7 @@ EXPORTS = [
     "laser_gsta_kernel_name", "laser_segment_ffn_forward", "laser_segment_ffn_forward_variant",
     "laser_gsta_kernel_name_layers", "laser_project_q_forward", "laser_project_q_forward_variant",
     "laser_project_kv_forward", "laser_project_kv_forward_variant", "laser_fold_query_weights",
-    "laser_project_heads_forward", "laser_sta_folded_forward", "laser_sta_backward", "laser_sta_backward_bf16", "laser_sta_backward_work_bytes", "laser_gsta_backward",
+    "laser_project_heads_forward", "laser_sta_folded_forward", "laser_sta_backward", "laser_sta_backward_bf16", "laser_sta_backward_static", "laser_sta_backward_work_bytes", "laser_gsta_backward",
     "laser_gsta_backward_work_bytes",
     "laser_status_string", "laser_version",
 ]
@@ -110,6 +110,8 @@ def load_library() -> ctypes.CDLL:
     lib.laser_sta_backward_bf16.argtypes = [vp, vp, vp, ip, vp, i32, i32, i32, i32, i32, i32, f32, vp, vp, vp, vp,
                                             ctypes.c_size_t, vp]
     lib.laser_sta_backward_bf16.restype = i32
+    lib.laser_sta_backward_static.argtypes = [vp, vp, vp, ip, vp, i32, i32, i32, i32, i32, i32, f32, i32, vp, vp, vp, vp]
+    lib.laser_sta_backward_static.restype = i32
     lib.laser_gsta_backward_work_bytes.argtypes = [i32, i32, i32, i32]
     lib.laser_gsta_backward_work_bytes.restype = ctypes.c_size_t
     lib.laser_gsta_backward.argtypes = [vp, vp, vp, vp, vp, ip, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp,
@@ -386,6 +388,30 @@ def laser_sta_backward(q, k, v, lens, dseg, w: int, gamma: float, dq_out=None, d
                                   _ptr(dv_out, "dv_out", torch.float32), _ptr(work, "work"),
                                   work.numel() * work.element_size(), _stream(stream))
     _check(code, "laser_sta_backward")
+    return dq_out, dk_out, dv_out
+
+
+STATIC_SCRATCH_BYTES = 8 << 20     # LASER_STATIC_SCRATCH_BYTES of include/laser.h
+
+
+def laser_sta_backward_static(q, k, v, lens, dseg, w: int, gamma: float, dq_out, dk_out, dv_out, stream=None):
+    """laser_sta_backward with the library's own fixed scratch: the call allocates nothing, so the three outputs
+    [U,C,d_q], [U,L,d_q], [U,L,d] (fp32) are the caller's."""
+    torch = _torch()
+    U, C, d_q = q.shape
+    L, d = v.shape[1], v.shape[2]
+    S = -(-L // w)
+    if tuple(k.shape) != (U, L, d_q) or tuple(v.shape) != (U, L, d) or tuple(dseg.shape) != (U, C, S, d):
+        raise ValueError("q, k, v, dseg shapes disagree")
+    if tuple(dq_out.shape) != (U, C, d_q) or tuple(dk_out.shape) != (U, L, d_q) or tuple(dv_out.shape) != (U, L, d):
+        raise ValueError("output shapes disagree with the inputs")
+    if any(x.dtype != q.dtype for x in (k, v, dseg)):
+        raise TypeError("q, k, v and dseg must share a dtype")
+    code = load_library().laser_sta_backward_static(
+        _ptr(q, "q"), _ptr(k, "k"), _ptr(v, "v"), _ptr(lens, "lens", torch.int32), _ptr(dseg, "dseg"), U, C, L, d_q, d,
+        int(w), float(gamma), _dt(q), _ptr(dq_out, "dq_out", torch.float32), _ptr(dk_out, "dk_out", torch.float32),
+        _ptr(dv_out, "dv_out", torch.float32), _stream(stream))
+    _check(code, "laser_sta_backward_static")
     return dq_out, dk_out, dv_out
 
 

@@ -1,5 +1,6 @@
 // Host side of the C ABI: argument validation (GPU-free), kernel selection, launches.
 #include <initializer_list>
+#include <mutex>
 
 #include "laser_internal.h"
 
@@ -559,6 +560,48 @@ laser_status laser_sta_backward_bf16(const void* q, const void* k, const void* v
                                      void* dk_out, void* dv_out, void* work, size_t work_bytes, void* stream) {
   return sta_backward_any(q, k, v, lens, dseg, U, C, L, d_q, d, w, gamma, LASER_BF16, dq_out, dk_out, dv_out, true, work,
                           work_bytes, stream);
+}
+
+// Scratch of laser_sta_backward_static: device memory that belongs to this code object, so no call ever allocates.
+// In host code the array's name is only a handle for the symbol lookup below, not a device address: everything that
+// needs the memory (kernel arguments) takes the looked-up pointer. Every GPU holds its own copy at its own address.
+static __device__ __align__(256) unsigned char scratch[LASER_STATIC_SCRATCH_BYTES];
+
+// Address of `scratch` on the current device: looked up on the first call per device, kept until the process ends.
+static laser_status static_scratch(void** out) {
+  constexpr int MAX_DEVICES = 64;
+  static std::mutex mu;
+  static void* ptr[MAX_DEVICES] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return LASER_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lock(mu);
+  if (ptr[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+      (void)hipGetLastError();
+      return LASER_ERR_LAUNCH;
+    }
+    ptr[dev] = p;
+  }
+  *out = ptr[dev];
+  return LASER_OK;
+}
+
+laser_status laser_sta_backward_static(const void* q, const void* k, const void* v, const int32_t* lens,
+                                       const void* dseg, int U, int C, int L, int d_q, int d, int w, float gamma,
+                                       laser_dtype dt, float* dq_out, float* dk_out, float* dv_out, void* stream) {
+  StaBwdArgs a;
+  laser_status s = sta_backward_validate(q, k, v, lens, dseg, U, C, L, d_q, d, w, gamma, dt, dq_out, dk_out, dv_out,
+                                         false, stream, &a);
+  if (s != LASER_OK) return s;
+  // the sizes are known to be sane here; what the kernels need must fit the array
+  if (sta_backward_work_bytes(U, C, L, d_q, w) > (size_t)LASER_STATIC_SCRATCH_BYTES) return LASER_ERR_SHAPE;
+  if (!sta_backward_supports(a)) return LASER_ERR_UNSUPPORTED;   // before the device is touched
+  void* work = nullptr;
+  s = static_scratch(&work);
+  if (s != LASER_OK) return s;
+  a.work = static_cast<float*>(work);
+  return sta_backward_launch(a);
 }
 
 size_t laser_gsta_backward_work_bytes(int U, int C, int d, int M) {

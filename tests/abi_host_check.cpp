@@ -76,6 +76,8 @@ int main() {
   EXPECT(laser_sta_backward(A, A, A, nullptr, A, 3, 2, 64, 16, 16, 8, 1.0f, bf, F, F, F, A, 8, nullptr), LASER_ERR_SHAPE);
   EXPECT(laser_sta_backward(A, A, A, nullptr, A, 3, 2, 64, 512, 512, 8, 1.0f, bf, F, F, F, A, (size_t)1 << 30, nullptr), LASER_ERR_UNSUPPORTED);
   EXPECT(laser_sta_backward_bf16(A, A, A, nullptr, A, 1, 8, 64, 32, 64, 8, 1.0f, F, A, A, A, (size_t)1 << 30, nullptr), LASER_ERR_UNSUPPORTED);
+  EXPECT(laser_sta_backward_static(A, A, A, nullptr, A, 2048, 8, 1024, 256, 64, 64, 1.0f, bf, F, F, F, nullptr), LASER_ERR_SHAPE);   // 16 MiB of scratch
+  EXPECT(laser_sta_backward_static(A, A, A, nullptr, A, BIG, BIG, BIG, BIG, 64, 1, 1.0f, bf, F, F, F, nullptr), LASER_ERR_SHAPE);
   EXPECT(laser_gsta_backward_work_bytes(3, 0, 16, 2) != 0, 0);
   EXPECT(laser_gsta_backward_work_bytes(BIG, BIG, BIG, BIG) == 0, 1);
   EXPECT(laser_gsta_backward(A, A, A, A, A, nullptr, F, 3, 2, 64, 16, 8, 2, bf, A, F, F, F, F, A, 64, nullptr), LASER_ERR_SHAPE);
