@@ -377,6 +377,21 @@ def main() -> int:
     sta_alone_ms = event_time(sta_alone)
     step_event_ms = event_time(step)   # the same one-stream loop between HIP events instead of host clocks
 
+    # The same path with H' never stored (one GSTA layer): laser_forward_fused with its work buffer
+    zonly = None
+    if spec.M == 1:
+        lib = laser.load_library()
+        need = lib.laser_forward_fused_work_bytes(spec.U, spec.C, spec.L, spec.d_q, spec.d, spec.w,
+                                                  laser.LASER_F32 if spec.dtype == "f32" else laser.LASER_BF16)
+        fwork = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+
+        def step_fused(i):
+            dw, seg, cnt, z = sets[i % copies]
+            laser.laser_forward_fused(dw.q, dw.k, dw.v, dw.t0, dw.wq, dw.wk, dw.wv, dw.lens, spec.w, spec.gamma,
+                                      seg_cnt=cnt, z_out=z, work=fwork)
+
+        zonly = {"ms_per_step": event_time(step_fused), "work_bytes": int(need)}
+
     views = None
     if args.views > 0:
         R = min(args.views, spec.S)
@@ -604,6 +619,22 @@ def main() -> int:
     k_gsta = roofline_of(gsta_b, gsta_f, gsta_ms)
     k_gsta.update({"name": gsta_kernel})
     roof["dominant_kernel"] = k_sta if sta_ms >= gsta_ms else k_gsta
+    if zonly is not None:
+        zb = cm.path_bytes(wl.lens, spec.U, spec.C, spec.L, spec.d_q, spec.d, spec.w, spec.M, spec.dtype,
+                           seg_out_written=False)
+        zonly.update(roofline_of(zb, path_f, zonly["ms_per_step"]))
+        zonly["value"] = spec.pairs / (zonly["ms_per_step"] * 1e-3)
+        zonly["entry_point"] = "laser_forward_fused (H' never stored; one stream, HIP events)"
+        step_fused(0)
+        torch.cuda.synchronize()
+        zz = to_host_f64(sets[0][3])
+        rngz = np.random.default_rng(1)
+        zerr = 0.0
+        for _ in range(4):
+            r, c = int(rngz.integers(spec.U)), int(rngz.integers(spec.C))
+            zerr = max(zerr, vec_rel_err(zz[r, c], oracle_pair(wl, r, c)[1]))
+        zonly["parity_max_vector_rel_err"] = zerr
+        parity_ok = parity_ok and zerr <= TOL[spec.dtype]
     k_alone = roofline_of(sta_b, sta_f, sta_alone_ms)
     k_alone.update({"name": sta_kernel, "form": "as launched by laser_sta_forward: no seg_cnt, non-temporal H' stores"})
 
@@ -625,6 +656,7 @@ def main() -> int:
         "roofline": roof,
         "cpu_baseline": cpu,
         "kernels": {"sta": k_sta, "gsta": k_gsta, "sta_standalone": k_alone},
+        "z_only": zonly,
         "views": views,
         "ffn": ffn,
         "project": project,

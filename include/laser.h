@@ -14,7 +14,8 @@
  *   - Every data pointer is a DEVICE pointer (HBM), caller-owned, row-major,
  *     contiguous, 16-byte aligned. Nothing is copied to or from the host.
  *   - The library allocates nothing, keeps no state and never synchronises: work
- *     is enqueued on `stream` (a hipStream_t; NULL = the default stream).
+ *     is enqueued on `stream` (a hipStream_t; NULL = the default stream). (One exception
+ *     to "no state": laser_sta_backward_static owns a fixed scratch array per GPU.)
  *   - Outputs are overwritten in full, including exact zeros for empty segments.
  *   - Return value only; no exception or abort crosses the ABI. Arguments are
  *     validated on the host before anything is launched, so an error return means
@@ -155,14 +156,41 @@ laser_status laser_gsta_forward_variant(const void* seg, const void* t0, const v
 /*
  * The whole path: STA, then GSTA on the segment vectors it produced (paper Sec. 3.2,
  * "compress-then-refine"; the per-segment FFN + LayerNorm of Sec. 3.4.2 is not applied,
- * which is the paper's "-FFN+LayerNorm" ablation variant). Arguments as above; seg_out
- * [U,C,S,d] is required (it is the buffer GSTA reads), seg_cnt may be NULL.
- * GSTA consumes H' as stored in seg_out, i.e. after rounding to dt.
+ * which is the paper's "-FFN+LayerNorm" ablation variant). Arguments as above; seg_cnt may be NULL.
+ * seg_out [U,C,S,d] is the buffer GSTA reads: GSTA consumes H' as stored there, i.e. after rounding to dt.
+ * seg_out may be NULL when H' is not wanted (M = 1 only; M > 1 returns LASER_ERR_UNSUPPORTED, because every further
+ * layer reads every segment vector again): the call is then laser_forward_fused below without a work buffer, i.e.
+ * one launch in which every workgroup walks a whole history and nothing but z_out (and seg_cnt) is written.
  */
 laser_status laser_forward(const void* q, const void* k, const void* v, const void* t0,
                            const void* wq, const void* wk, const void* wv, const int32_t* lens,
                            int U, int C, int L, int d_q, int d, int w, float gamma, int M, laser_dtype dt,
                            void* seg_out, int32_t* seg_cnt, float* z_out, void* stream);
+
+/*
+ * The whole path with one GSTA layer and H' never stored (paper Sec. 3.4.2 and 3.4.3): the attention of Sec. 3.4.3,
+ *   a = softmax((t0 W_q)(H' W_k)^T / sqrt(d)),  z = t0 + a (H' W_v),
+ * is applied to each segment vector while it is still in registers, as an online softmax over the segments (running
+ * maximum, denominator and weighted sum per pair), with the products re-associated (H' (W_k (t0 W_q)^T) and (a H') W_v:
+ * exact). Same arguments, layouts, masks and limits as laser_forward with M = 1 (wq, wk, wv [d,d]); the segment vectors
+ * enter the layer as fp32 sums, not rounded to dt, so z_out agrees with laser_forward's within the tolerance, not bit
+ * for bit. seg_cnt [U,S] may be NULL.
+ * work: with few users a history must be cut into runs of segments that different workgroups walk, and each run
+ * leaves a partial result (maximum, denominator, weighted sum) per pair that a second, small launch merges in run
+ * order (fixed order: results are reproducible). work is caller-owned device scratch for those partial results, 16-byte
+ * aligned, at least laser_forward_fused_work_bytes(...) bytes (contents unspecified on return; 0 bytes are needed when
+ * there are enough users to fill the machine, or when no kernel here cuts histories for the shape). work may be NULL:
+ * every workgroup then walks a whole history, which is always correct and needs no scratch, but leaves compute units
+ * idle when U * ceil(C / 128) is small. Kernels: bf16 with d_q in {32, 64, 128} and d in {64, 128} on the matrix cores;
+ * everything else (fp32 storage, other widths) on a generic fp32 kernel, one run per user.
+ * Errors: as laser_forward, and LASER_ERR_ALIGN (work), LASER_ERR_SHAPE (work_bytes too small). Nothing is launched
+ * on an error.
+ */
+size_t laser_forward_fused_work_bytes(int U, int C, int L, int d_q, int d, int w, laser_dtype dt);   /* host only */
+laser_status laser_forward_fused(const void* q, const void* k, const void* v, const void* t0,
+                                 const void* wq, const void* wk, const void* wv, const int32_t* lens,
+                                 int U, int C, int L, int d_q, int d, int w, float gamma, laser_dtype dt,
+                                 int32_t* seg_cnt, float* z_out, void* work, size_t work_bytes, void* stream);
 
 /*
  * Ragged candidate counts per user (serving batches: every request brings its own number of candidates). The pair

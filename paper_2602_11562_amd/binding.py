@@ -24,7 +24,7 @@ EXPORTS = [
     "laser_sta_forward", "laser_sta_forward_variant", "laser_sta_forward_heads", "laser_sta_forward_softmax", "laser_sta_forward_ragged",
     "laser_gsta_forward_ragged", "laser_forward_ragged", "laser_multires_forward_ragged",
     "laser_segment_ffn_forward_ragged", "laser_gsta_forward", "laser_gsta_forward_variant",
-    "laser_forward", "laser_multires_forward", "laser_forward_multires", "laser_gsta_forward_multires",
+    "laser_forward", "laser_forward_fused", "laser_forward_fused_work_bytes", "laser_multires_forward", "laser_forward_multires", "laser_gsta_forward_multires",
     "laser_sta_kernel_name",
     "laser_gsta_kernel_name", "laser_segment_ffn_forward", "laser_segment_ffn_forward_variant",
     "laser_gsta_kernel_name_layers", "laser_project_q_forward", "laser_project_q_forward_variant",
@@ -64,6 +64,11 @@ def load_library() -> ctypes.CDLL:
     lib.laser_gsta_forward_variant.argtypes = lib.laser_gsta_forward.argtypes + [i32]
     lib.laser_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, ip, i32, i32, i32, i32, i32, i32, f32, i32, i32,
                                   vp, ip, vp, vp]
+    lib.laser_forward_fused.argtypes = [vp, vp, vp, vp, vp, vp, vp, ip, i32, i32, i32, i32, i32, i32, f32, i32,
+                                        ip, vp, vp, ctypes.c_size_t, vp]
+    lib.laser_forward_fused.restype = i32
+    lib.laser_forward_fused_work_bytes.argtypes = [i32, i32, i32, i32, i32, i32, i32]
+    lib.laser_forward_fused_work_bytes.restype = ctypes.c_size_t
     for name in ("laser_sta_forward", "laser_sta_forward_variant", "laser_gsta_forward",
                  "laser_gsta_forward_variant", "laser_forward", "laser_version"):
         getattr(lib, name).restype = i32
@@ -616,21 +621,53 @@ def laser_multires_forward(seg, lens, L: int, w: int, r: int, pool_out=None, rec
     return pool_out, recent_out
 
 
+def laser_forward_fused(q, k, v, t0, wq, wk, wv, lens, w: int, gamma: float, seg_cnt=None, z_out=None, work=None,
+                        stream=None, want_cnt: bool = True, use_work: bool = True):
+    """The whole path with one GSTA layer and H' never stored. Returns (cnt [U,S] or None, z [U,C,d] fp32).
+    work: device scratch for the partial results of the runs of a history (allocated here when None and use_work);
+    use_work=False passes NULL, i.e. one run per user."""
+    torch = _torch()
+    U, C, d_q = q.shape
+    L, d = v.shape[1], v.shape[2]
+    S = -(-L // w)
+    if tuple(wq.shape[-2:]) != (d, d) or wq.numel() != d * d:
+        raise ValueError("one layer: wq, wk, wv must hold d x d elements")
+    if seg_cnt is None and want_cnt:
+        seg_cnt = torch.empty((U, S), dtype=torch.int32, device=q.device)
+    if z_out is None:
+        z_out = torch.empty((U, C, d), dtype=torch.float32, device=q.device)
+    if any(x.dtype != q.dtype for x in (k, v, t0, wq, wk, wv)):
+        raise TypeError("all inputs must share a dtype")
+    lib = load_library()
+    if work is None and use_work:
+        need = lib.laser_forward_fused_work_bytes(U, C, L, d_q, d, int(w), _dt(q))
+        if need:
+            work = torch.empty(need, dtype=torch.uint8, device=q.device)
+    code = lib.laser_forward_fused(
+        _ptr(q, "q"), _ptr(k, "k"), _ptr(v, "v"), _ptr(t0, "t0"), _ptr(wq, "wq"), _ptr(wk, "wk"), _ptr(wv, "wv"),
+        _ptr(lens, "lens", torch.int32), U, C, L, d_q, d, int(w), float(gamma), _dt(q),
+        _ptr(seg_cnt, "seg_cnt", torch.int32), _ptr(z_out, "z_out", torch.float32), _ptr(work, "work"),
+        0 if work is None else work.numel() * work.element_size(), _stream(stream))
+    _check(code, "laser_forward_fused")
+    return seg_cnt, z_out
+
+
 def laser_forward(q, k, v, t0, wq, wk, wv, lens, w: int, gamma: float, seg_out=None, seg_cnt=None, z_out=None,
-                  stream=None, want_cnt: bool = True):
-    """The whole path. Returns (H' [U,C,S,d], cnt [U,S] or None, z [U,C,d] fp32)."""
+                  stream=None, want_cnt: bool = True, want_seg: bool = True):
+    """The whole path. Returns (H' [U,C,S,d], cnt [U,S] or None, z [U,C,d] fp32); with want_seg=False seg_out is passed
+    as NULL (H' is never stored: the fused kernels, one layer only) and None comes back in its place."""
     torch = _torch()
     U, C, d_q = q.shape
     L, d = v.shape[1], v.shape[2]
     M = wq.shape[0]
     S = -(-L // w)
-    if seg_out is None:
+    if seg_out is None and want_seg:
         seg_out = torch.empty((U, C, S, d), dtype=q.dtype, device=q.device)
     if seg_cnt is None and want_cnt:
         seg_cnt = torch.empty((U, S), dtype=torch.int32, device=q.device)
     if z_out is None:
         z_out = torch.empty((U, C, d), dtype=torch.float32, device=q.device)
-    if any(x.dtype != q.dtype for x in (k, v, t0, wq, wk, wv, seg_out)):
+    if any(x.dtype != q.dtype for x in (k, v, t0, wq, wk, wv) + ((seg_out,) if seg_out is not None else ())):
         raise TypeError("all inputs and seg_out must share a dtype")
     code = load_library().laser_forward(
         _ptr(q, "q"), _ptr(k, "k"), _ptr(v, "v"), _ptr(t0, "t0"), _ptr(wq, "wq"), _ptr(wk, "wk"), _ptr(wv, "wv"),

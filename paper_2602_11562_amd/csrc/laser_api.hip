@@ -35,8 +35,8 @@ static int segments(int L, int w) { return (int)(((long long)L + w - 1) / w); }
 
 static laser_status validate_sta(const void* q, const void* k, const void* v, const int32_t* lens, int U, int C,
                                  int L, int d_q, int d, int w, float gamma, laser_dtype dt, void* seg_out,
-                                 int32_t* seg_cnt, void* stream, StaArgs* out) {
-  if (!q || !k || !v || !seg_out) return LASER_ERR_NULL;
+                                 int32_t* seg_cnt, void* stream, StaArgs* out, bool seg_required = true) {
+  if (!q || !k || !v || (seg_required && !seg_out)) return LASER_ERR_NULL;
   if (dt != LASER_F32 && dt != LASER_BF16) return LASER_ERR_DTYPE;
   laser_status s = check_dims(U, C, L, d_q, d, w);
   if (s != LASER_OK) return s;
@@ -167,6 +167,26 @@ static laser_status run_gsta_views(GstaArgs& ga, MultiresArgs& ma) {
   return multires_launch(ma);
 }
 
+// The whole path without H' in memory (one GSTA layer): checks, then the fused kernels' arguments
+static laser_status validate_fused(const void* q, const void* k, const void* v, const void* t0, const void* wq,
+                                   const void* wk, const void* wv, const int32_t* lens, int U, int C, int L, int d_q,
+                                   int d, int w, float gamma, laser_dtype dt, int32_t* seg_cnt, float* z_out,
+                                   void* stream, FusedArgs* out) {
+  StaArgs sa;
+  laser_status s = validate_sta(q, k, v, lens, U, C, L, d_q, d, w, gamma, dt, nullptr, seg_cnt, stream, &sa, false);
+  if (s != LASER_OK) return s;
+  if (!t0 || !wq || !wk || !wv || !z_out) return LASER_ERR_NULL;
+  if (sa.S > 4096) return LASER_ERR_SHAPE;   // as for laser_gsta_forward
+  if (!aligned16(t0) || !aligned16(wq) || !aligned16(wk) || !aligned16(wv) || !aligned16(z_out)) return LASER_ERR_ALIGN;
+  *out = FusedArgs{q, k, v, t0, wq, wk, wv, lens, U, C, L, d_q, d, w, sa.S, gamma, dt, seg_cnt, z_out, nullptr,
+                   static_cast<hipStream_t>(stream)};
+  return LASER_OK;
+}
+
+static laser_status run_fused(const FusedArgs& a) {
+  return fused_mfma_supports(a) ? fused_mfma_launch(a) : fused_generic_launch(a);
+}
+
 }  // namespace laser
 
 using namespace laser;
@@ -293,6 +313,15 @@ laser_status laser_forward(const void* q, const void* k, const void* v, const vo
                            const void* wk, const void* wv, const int32_t* lens, int U, int C, int L, int d_q, int d,
                            int w, float gamma, int M, laser_dtype dt, void* seg_out, int32_t* seg_cnt, float* z_out,
                            void* stream) {
+  if (seg_out == nullptr) {   // H' not wanted: the fused kernels, every workgroup walking a whole history
+    FusedArgs fa;
+    const laser_status fs = validate_fused(q, k, v, t0, wq, wk, wv, lens, U, C, L, d_q, d, w, gamma, dt, seg_cnt, z_out,
+                                           stream, &fa);
+    if (fs != LASER_OK) return fs;
+    if (M <= 0 || M > 64) return LASER_ERR_SHAPE;
+    if (M != 1) return LASER_ERR_UNSUPPORTED;   // a second layer reads every segment vector again
+    return run_fused(fa);
+  }
   StaArgs sa;
   GstaArgs ga;
   laser_status s = validate_sta(q, k, v, lens, U, C, L, d_q, d, w, gamma, dt, seg_out, seg_cnt, stream, &sa);
@@ -303,6 +332,29 @@ laser_status laser_forward(const void* q, const void* k, const void* v, const vo
   s = run_sta(sa, LASER_STA_AUTO);
   if (s != LASER_OK) return s;
   return run_gsta(ga, LASER_GSTA_AUTO);
+}
+
+size_t laser_forward_fused_work_bytes(int U, int C, int L, int d_q, int d, int w, laser_dtype dt) {
+  if (check_dims(U, C, L, d_q, d, w) != LASER_OK || (dt != LASER_F32 && dt != LASER_BF16)) return 0;
+  FusedArgs a{};
+  a.U = U; a.C = C; a.L = L; a.d_q = d_q; a.d = d; a.w = w; a.S = segments(L, w); a.gamma = 1.0f; a.dt = dt;
+  return fused_work_bytes(a);
+}
+
+laser_status laser_forward_fused(const void* q, const void* k, const void* v, const void* t0, const void* wq,
+                                 const void* wk, const void* wv, const int32_t* lens, int U, int C, int L, int d_q,
+                                 int d, int w, float gamma, laser_dtype dt, int32_t* seg_cnt, float* z_out, void* work,
+                                 size_t work_bytes, void* stream) {
+  FusedArgs fa;
+  const laser_status s = validate_fused(q, k, v, t0, wq, wk, wv, lens, U, C, L, d_q, d, w, gamma, dt, seg_cnt, z_out,
+                                        stream, &fa);
+  if (s != LASER_OK) return s;
+  if (work != nullptr) {
+    if (!aligned16(work)) return LASER_ERR_ALIGN;
+    if (work_bytes < fused_work_bytes(fa)) return LASER_ERR_SHAPE;
+    fa.work = static_cast<float*>(work);
+  }
+  return run_fused(fa);
 }
 
 laser_status laser_multires_forward(const void* seg, const int32_t* lens, int U, int C, int L, int d, int w, int r,

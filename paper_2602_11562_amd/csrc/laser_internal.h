@@ -159,6 +159,29 @@ bool gsta_backward_supports(const GstaBwdArgs& a);
 size_t gsta_backward_work_bytes(int U, int C, int d, int M);
 laser_status gsta_backward_launch(const GstaBwdArgs& a);
 
+struct FusedArgs {         // the whole path with one GSTA layer and H' never stored: z [U,C,d] fp32 from q, k, v, t0, weights
+  const void* q;
+  const void* k;
+  const void* v;
+  const void* t0;
+  const void* wq;
+  const void* wk;
+  const void* wv;
+  const int32_t* lens;
+  int U, C, L, d_q, d, w, S;
+  float gamma;
+  laser_dtype dt;
+  int32_t* seg_cnt;        // may be nullptr
+  float* z_out;
+  float* work;             // partial results of the runs of a user's history; nullptr = one run per user
+  hipStream_t stream;
+};
+bool fused_generic_supports(const FusedArgs& a);
+laser_status fused_generic_launch(const FusedArgs& a);
+bool fused_mfma_supports(const FusedArgs& a);
+size_t fused_work_bytes(const FusedArgs& a);   // what fused_mfma_launch wants in a.work to cut histories into runs (0: nothing)
+laser_status fused_mfma_launch(const FusedArgs& a);
+
 // Each launcher returns LASER_ERR_UNSUPPORTED (launching nothing) when the shape is outside its range.
 bool sta_generic_supports(const StaArgs& a);
 laser_status sta_generic_launch(const StaArgs& a);

@@ -54,6 +54,12 @@ int main() {
   EXPECT(laser_forward_multires(A, A, A, A, A, A, A, nullptr, 2, 3, 64, 16, 16, 8, 1.0f, 1, bf, A, nullptr, F, BIG, A, A, nullptr), LASER_ERR_SHAPE);
   EXPECT(laser_gsta_forward_multires(A, A, A, A, A, nullptr, 2, 3, 64, 16, 8, 1, bf, F, -1, A, A, nullptr), LASER_ERR_SHAPE);
 
+  EXPECT(laser_forward(A, A, A, A, A, A, A, nullptr, 2, 3, 64, 16, 16, 8, 1.0f, 2, bf, nullptr, nullptr, F, nullptr), LASER_ERR_UNSUPPORTED);
+  EXPECT(laser_forward_fused(A, A, A, A, A, A, A, nullptr, BIG, BIG, BIG, 16, 16, 1, 1.0f, bf, nullptr, F, nullptr, 0, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_forward_fused(A, A, A, A, A, A, A, nullptr, 32, 256, 4096, 128, 128, 128, 1.0f, bf, nullptr, F, A, 1024, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_forward_fused_work_bytes(BIG, BIG, BIG, 1024, 1024, 1, bf) == 0, 1);
+  EXPECT(laser_forward_fused_work_bytes(1 << 20, 9, 1 << 10, 8, 64, 1 << 10, bf) == 0, 1);
+
   // views, FFN, projections, folded form
   EXPECT(laser_multires_forward(A, nullptr, 2, 3, 64, 16, 8, 9, bf, A, A, nullptr), LASER_ERR_SHAPE);
   EXPECT(laser_multires_forward(A, nullptr, BIG, BIG, 64, 16, 8, 2, bf, A, A, nullptr), LASER_ERR_SHAPE);

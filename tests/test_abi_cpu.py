@@ -87,10 +87,37 @@ def test_forward_validates_both_stages_before_launching(lib):
     f = lib.laser_forward
     ok_tail = (None, 2, 3, 64, 16, 16, 8, 1.0)
     assert f(A, A, A, None, A, A, A, *ok_tail, 1, 1, A, None, A, None) == 1      # t0 NULL
-    assert f(A, A, A, A, A, A, A, *ok_tail, 1, 1, None, None, A, None) == 1      # seg_out NULL
+    # seg_out NULL asks for the fused path (H' never stored): one layer only, and validated like everything else
+    assert f(A, A, A, A, A, A, A, *ok_tail, 2, 1, None, None, A, None) == 4      # seg_out NULL with two layers
+    assert f(A, A, A, None, A, A, A, *ok_tail, 1, 1, None, None, A, None) == 1   # seg_out NULL, t0 NULL
+    assert f(A, A, A, A, A, A, A, *ok_tail, 1, 1, None, None, None, None) == 1   # seg_out NULL, z_out NULL
+    assert f(A, A, A, A, A, A, A + 8, *ok_tail, 1, 1, None, None, A, None) == 6  # seg_out NULL, wv misaligned
+    assert f(A, A, A, A, A, A, A, *ok_tail, 0, 1, None, None, A, None) == 2      # seg_out NULL, M = 0
     assert f(A, A, A, A, A, A, A, *ok_tail, 1, 1, A, None, None, None) == 1      # z_out NULL
     assert f(A, A, A, A, A, A, A, *ok_tail, 0, 1, A, None, A, None) == 2         # M = 0
     assert f(A, A, A, A, A, A, A, *ok_tail, 1, 3, A, None, A, None) == 3         # dtype
+
+
+def test_fused_forward_argument_validation(lib):
+    NULL, SHAPE, DTYPE, ALIGN = 1, 2, 3, 6
+    wb = lib.laser_forward_fused_work_bytes
+    # 32 users x 256 candidates, L = 4096, w = 128, d = 128, bf16: two candidate tiles of four waves per user, four
+    # runs of eight segments; per (tile of 32 candidates, run) 66 rows of 64 floats
+    assert wb(32, 256, 4096, 128, 128, 128, 1) == 32 * 2 * 4 * 4 * 66 * 64 * 4
+    assert wb(4096, 1, 4096, 64, 64, 256, 1) == 0          # enough users: whole histories, no scratch
+    assert wb(1, 16, 1024, 64, 64, 64, 0) == 0             # fp32 storage: the generic kernel, one run per user
+    assert wb(0, 16, 1024, 64, 64, 64, 1) == 0 and wb(1, 16, 1024, 64, 12, 64, 1) == 0   # invalid sizes
+    f = lambda q=A, t0=A, wv=A, lens=None, U=2, C=3, L=64, dq=16, d=16, w=8, gamma=1.0, dt=1, cnt=None, z=A, work=None, \
+        nbytes=0: lib.laser_forward_fused(q, A, A, t0, A, A, wv, lens, U, C, L, dq, d, w, ctypes.c_float(gamma), dt, cnt,
+                                          z, work, ctypes.c_size_t(nbytes), None)
+    for kw in ({"q": None}, {"t0": None}, {"wv": None}, {"z": None}):
+        assert f(**kw) == NULL, kw
+    assert f(dt=4) == DTYPE
+    for kw in ({"U": 0}, {"C": 0}, {"w": 0}, {"d": 12}, {"gamma": 0.0}, {"L": 8192, "w": 1}):
+        assert f(**kw) == SHAPE, kw
+    assert f(wv=A + 8) == ALIGN and f(z=A + 4) == ALIGN and f(lens=A + 2) == ALIGN and f(cnt=A + 1) == ALIGN
+    assert f(work=A + 8, nbytes=1 << 30) == ALIGN
+    assert f(U=32, C=256, L=4096, dq=128, d=128, w=128, work=A, nbytes=1024) == SHAPE   # scratch too small
 
 
 def test_kernel_names(lib):
