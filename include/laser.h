@@ -118,8 +118,8 @@ laser_status laser_sta_forward_heads(const void* q, const void* k, const void* v
                                      laser_sta_variant variant);
 
 /*
- * The ablation variant of paper Sec. 4.4.1, in which the sigmoid aggregation of STA is replaced by the conventional
- * softmax:  seg_out[u,c,i,:] = sum_j softmax_j(dot(q[u,c,:], k[u,j,:]) / gamma) * v[u,j,:], the softmax taken over the
+ * The ablation variant of paper Sec. 4.4.1 / Table 4, STA with a softmax over the items in the place of its sigmoid
+ * gates:  seg_out[u,c,i,:] = sum_j softmax_j(dot(q[u,c,:], k[u,j,:]) / gamma) * v[u,j,:], the softmax taken over the
  * valid items j of segment i (per head on the head's own columns, as in laser_sta_forward_heads); segments without a
  * valid item give zeros. Arguments, layouts, limits and errors as for laser_sta_forward_heads. Kernels: the streaming
  * kernel for short segments (C <= 8, bf16, w below one step of its long form), the matrix-core kernel (C >= 9, bf16,

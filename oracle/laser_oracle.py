@@ -136,8 +136,8 @@ def sta_pair_heads(Q: np.ndarray, K: np.ndarray, V: np.ndarray, length: int, w: 
 
 def sta_pair_softmax(Q: np.ndarray, K: np.ndarray, V: np.ndarray, length: int, w: int, gamma: float,
                      heads: int = 1) -> np.ndarray:
-    """H' [S, d] of one (user, candidate) in the ablation variant of Sec. 4.4.1, where the sigmoid aggregation of
-    Sec. 3.4.2 is replaced by the conventional softmax: s_i = softmax(Q K_i^T / gamma) V_i.
+    """H' [S, d] of one (user, candidate) in the ablation variant of Sec. 4.4.1 / Table 4: a softmax over the items
+    takes the place of the sigmoid gates of Sec. 3.4.2, s_i = softmax(Q K_i^T / gamma) V_i.
 
     Reading: the softmax runs over the valid items of segment i (the window STA aggregates over), per head on the
     head's own columns as in sta_pair_heads; a segment without a valid item gives zeros.
