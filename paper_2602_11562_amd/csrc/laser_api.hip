@@ -183,7 +183,11 @@ static laser_status validate_fused(const void* q, const void* k, const void* v, 
   return LASER_OK;
 }
 
+// Scratch the fused kernels want in a.work to cut histories into runs (0: whole histories per workgroup)
+static size_t fused_need_bytes(const FusedArgs& a) { return fused_stream_supports(a) ? 0 : fused_work_bytes(a); }
+
 static laser_status run_fused(const FusedArgs& a) {
+  if (fused_stream_supports(a)) return fused_stream_launch(a);
   return fused_mfma_supports(a) ? fused_mfma_launch(a) : fused_generic_launch(a);
 }
 
@@ -338,7 +342,7 @@ size_t laser_forward_fused_work_bytes(int U, int C, int L, int d_q, int d, int w
   if (check_dims(U, C, L, d_q, d, w) != LASER_OK || (dt != LASER_F32 && dt != LASER_BF16)) return 0;
   FusedArgs a{};
   a.U = U; a.C = C; a.L = L; a.d_q = d_q; a.d = d; a.w = w; a.S = segments(L, w); a.gamma = 1.0f; a.dt = dt;
-  return fused_work_bytes(a);
+  return fused_need_bytes(a);
 }
 
 laser_status laser_forward_fused(const void* q, const void* k, const void* v, const void* t0, const void* wq,
@@ -351,7 +355,7 @@ laser_status laser_forward_fused(const void* q, const void* k, const void* v, co
   if (s != LASER_OK) return s;
   if (work != nullptr) {
     if (!aligned16(work)) return LASER_ERR_ALIGN;
-    if (work_bytes < fused_work_bytes(fa)) return LASER_ERR_SHAPE;
+    if (work_bytes < fused_need_bytes(fa)) return LASER_ERR_SHAPE;
     fa.work = static_cast<float*>(work);
   }
   return run_fused(fa);

@@ -181,6 +181,8 @@ laser_status fused_generic_launch(const FusedArgs& a);
 bool fused_mfma_supports(const FusedArgs& a);
 size_t fused_work_bytes(const FusedArgs& a);   // what fused_mfma_launch wants in a.work to cut histories into runs (0: nothing)
 laser_status fused_mfma_launch(const FusedArgs& a);
+bool fused_stream_supports(const FusedArgs& a);   // few candidates per user: the streaming kernel with the layer as its epilogue
+laser_status fused_stream_launch(const FusedArgs& a);
 
 // Each launcher returns LASER_ERR_UNSUPPORTED (launching nothing) when the shape is outside its range.
 bool sta_generic_supports(const StaArgs& a);

@@ -27,7 +27,21 @@ __device__ __forceinline__ void unpack8(const u32x4& r, float (&x)[8]) {
   }
 }
 
-template <int DQ, int D, int CMAX, int HEADS>
+// FUSED (the whole path with one GSTA layer and H' never stored; a workgroup then walks a whole user): every finished
+// segment vector, still fp32 in the reduction buffer, goes through the online softmax of the layer of Sec. 3.4.3
+// instead of to memory: r = W_k (t0 W_q)^T log2(e) / sqrt(d) per candidate first, then per segment the score
+// H'_i . r, the running maximum and denominator, and the weighted sum P in LDS; z = t0 + (P / l) W_v at the end. The
+// state is C <= 8 vectors per workgroup, and the layer's products are a few thousand multiply-adds per candidate, so
+// they run on the vector ALUs from weights read through the caches.
+struct StreamFusedTail {
+  const unsigned short* t0;   // [P, D]
+  const unsigned short* wq;   // [D, D] each
+  const unsigned short* wk;
+  const unsigned short* wv;
+  float* z;                   // [P, D]
+};
+
+template <int DQ, int D, int CMAX, int HEADS, bool FUSED = false>
 __global__ __launch_bounds__(256) void sta_stream_kernel(const unsigned short* __restrict__ q,
                                                          const unsigned short* __restrict__ k,
                                                          const unsigned short* __restrict__ v,
@@ -36,7 +50,7 @@ __global__ __launch_bounds__(256) void sta_stream_kernel(const unsigned short* _
                                                          int w, int S, int spg, int groups, int users, int classes,
                                                          float neg_scale_log2e,
                                                          unsigned short* __restrict__ seg_out,
-                                                         int32_t* __restrict__ seg_cnt) {
+                                                         int32_t* __restrict__ seg_cnt, StreamFusedTail ft) {
   constexpr int LQ = DQ / 8, LV = D / 8;           // lanes per K row / V row
   constexpr int RQ = 64 / LQ, RV = 64 / LV;        // rows per wave-wide load
   constexpr int IPC = RQ > RV ? RQ : RV;           // items per chunk
@@ -48,6 +62,9 @@ __global__ __launch_bounds__(256) void sta_stream_kernel(const unsigned short* _
   static_assert(LQ % HEADS == 0 && LV % HEADS == 0, "a head's columns must fill whole 16-byte lanes");
   __shared__ float red[4][CMAX][D];
   __shared__ float gs[4][CMAX][HEADS][IPC];
+  constexpr int FC = FUSED ? CMAX : 1, FD = FUSED ? D : 1;
+  __shared__ float f_r[FC][FD], f_p[FC][FD], f_h[FC][FD];   // r, the weighted sum P, the segment vector just finished
+  __shared__ float f_dot[FC][2], f_cw[FC][2], f_ml[FC][2];  // partial scores; (rescale, weight); (maximum, denominator)
 
   // Longest histories first. Workgroups start in index order and a long history keeps its workgroup busy many times
   // longer than a short one, so the launch would end with a few late starters of long users running alone. With
@@ -81,6 +98,30 @@ __global__ __launch_bounds__(256) void sta_stream_kernel(const unsigned short* _
   }
   const unsigned short* kU = k + (size_t)u * L * DQ;
   const unsigned short* vU = v + (size_t)u * L * D;
+  if constexpr (FUSED) {
+    for (int e = tid; e < C * D; e += 256) {   // q' = t0 W_q
+      const int c = e / D, col = e - c * D;
+      float s = 0.0f;
+#pragma unroll 8
+      for (int a = 0; a < D; ++a) s = fmaf(bf16_bits_to_f32(ft.t0[(pb + c) * D + a]), bf16_bits_to_f32(ft.wq[a * D + col]), s);
+      f_h[c][col] = s;
+      f_p[c][col] = 0.0f;
+    }
+    if (tid < C) {
+      f_ml[tid][0] = -1.0e30f;
+      f_ml[tid][1] = 0.0f;
+    }
+    __syncthreads();
+    const float rscale = 1.4426950408889634f / sqrtf((float)D);
+    for (int e = tid; e < C * D; e += 256) {   // r = W_k q'^T
+      const int c = e / D, row = e - c * D;
+      float s = 0.0f;
+#pragma unroll 8
+      for (int a = 0; a < D; ++a) s = fmaf(bf16_bits_to_f32(ft.wk[row * D + a]), f_h[c][a], s);
+      f_r[c][row] = s * rscale;
+    }
+    __syncthreads();
+  }
 
   const int i_beg = grp * spg;
   const int i_end = (grp + 1) * spg < S ? (grp + 1) * spg : S;
@@ -181,10 +222,36 @@ __global__ __launch_bounds__(256) void sta_stream_kernel(const unsigned short* _
       }
     }
     __syncthreads();
-    for (int e = tid; e < C * D; e += 256) {
-      const int c = e / D, col = e - c * D;
-      const float s = ((red[0][c][col] + red[1][c][col]) + red[2][c][col]) + red[3][c][col];
-      seg_out[((pb + c) * S + i) * D + col] = f32_to_bf16_bits(s);
+    if constexpr (FUSED) {
+      // the segment vector meets r: 64 consecutive components of one candidate per wave and round
+      for (int e = tid; e < C * D; e += 256) {
+        const int c = e / D, col = e - c * D;
+        const float s = ((red[0][c][col] + red[1][c][col]) + red[2][c][col]) + red[3][c][col];
+        f_h[c][col] = s;
+        const float part = wave_sum(s * f_r[c][col]);
+        if (lane == 0) f_dot[c][col >> 6] = part;
+      }
+      __syncthreads();
+      if (tid < C) {   // online softmax over the segments, base 2
+        const float e2 = D > 64 ? f_dot[tid][0] + f_dot[tid][1] : f_dot[tid][0];
+        const float m_old = f_ml[tid][0], m_new = fmaxf(m_old, e2);
+        const float corr = __builtin_amdgcn_exp2f(m_old - m_new), wgt = __builtin_amdgcn_exp2f(e2 - m_new);
+        f_ml[tid][0] = m_new;
+        f_ml[tid][1] = fmaf(f_ml[tid][1], corr, wgt);
+        f_cw[tid][0] = corr;
+        f_cw[tid][1] = wgt;
+      }
+      __syncthreads();
+      for (int e = tid; e < C * D; e += 256) {
+        const int c = e / D, col = e - c * D;
+        f_p[c][col] = fmaf(f_cw[c][1], f_h[c][col], f_p[c][col] * f_cw[c][0]);
+      }
+    } else {
+      for (int e = tid; e < C * D; e += 256) {
+        const int c = e / D, col = e - c * D;
+        const float s = ((red[0][c][col] + red[1][c][col]) + red[2][c][col]) + red[3][c][col];
+        seg_out[((pb + c) * S + i) * D + col] = f32_to_bf16_bits(s);
+      }
     }
     __syncthreads();   // the reduction buffer is reused by the next segment
   };
@@ -214,6 +281,18 @@ __global__ __launch_bounds__(256) void sta_stream_kernel(const unsigned short* _
       cbase = nbase;
       chi = nhi;
     }
+  }
+  if constexpr (FUSED) {   // z = t0 + (P / l) W_v (no valid segment: l = 0 and z = t0)
+    __syncthreads();
+    for (int e = tid; e < C * D; e += 256) {
+      const int c = e / D, col = e - c * D;
+      const float l = f_ml[c][1], inv = l > 0.0f ? 1.0f / l : 0.0f;
+      float o = 0.0f;
+#pragma unroll 8
+      for (int a = 0; a < D; ++a) o = fmaf(f_p[c][a], bf16_bits_to_f32(ft.wv[a * D + col]), o);
+      ft.z[(pb + c) * D + col] = bf16_bits_to_f32(ft.t0[(pb + c) * D + col]) + o * inv;
+    }
+    return;
   }
   // empty segments of the run: exact zeros
   for (int e = tid; e < (i_end - i_ne) * C * D; e += 256) {
@@ -539,13 +618,56 @@ static void launch_c(const StaArgs& a, float nsl) {
       hipLaunchKernelGGL((sta_stream_kernel<DQ, D, CM, HEADS>), dim3(blocks * classes), dim3(256), 0, a.stream,    \
                          (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v,       \
                          a.lens, a.cand_off, a.P, a.C, a.L, a.w, a.S, spg, groups, a.U, classes, nsl,               \
-                         (unsigned short*)a.seg_out, a.seg_cnt);                                                     \
+                         (unsigned short*)a.seg_out, a.seg_cnt, StreamFusedTail{});                                  \
   } while (0)
   if (a.C <= 1) LASER_STREAM_LAUNCH(1);
   else if (a.C <= 2) LASER_STREAM_LAUNCH(2);
   else if (a.C <= 4) LASER_STREAM_LAUNCH(4);
   else LASER_STREAM_LAUNCH(8);
 #undef LASER_STREAM_LAUNCH
+}
+
+// The fused form (FusedArgs: the whole path, H' never stored): the long-segment kernel, a whole user per workgroup
+bool fused_stream_supports(const FusedArgs& a) {
+  if (a.dt != LASER_BF16 || a.C > 8) return false;
+  if (!(a.d_q == 32 || a.d_q == 64 || a.d_q == 128) || !(a.d == 64 || a.d == 128)) return false;
+  const int lq = a.d_q / 8, lv = a.d / 8;
+  const int ipc = (64 / lq) > (64 / lv) ? (64 / lq) : (64 / lv);
+  if (a.w < 4 * 4 * ipc) return false;   // short segments go wave by wave (another kernel, not fused)
+  return (long long)a.U * 4 <= 0x7fffffffLL;
+}
+
+template <int DQ, int D>
+static void fused_stream_launch_c(const FusedArgs& a, float nsl) {
+  const unsigned blocks = (unsigned)a.U;   // a workgroup walks a whole user: spg = S, one group
+  const int classes = (a.lens != nullptr && blocks >= 4096) ? 4 : 1;   // longest histories first, as above
+  const StreamFusedTail ft{(const unsigned short*)a.t0, (const unsigned short*)a.wq, (const unsigned short*)a.wk,
+                           (const unsigned short*)a.wv, a.z_out};
+#define LASER_FUSED_STREAM(CM)                                                                                       \
+  hipLaunchKernelGGL((sta_stream_kernel<DQ, D, CM, 1, true>), dim3(blocks * classes), dim3(256), 0, a.stream,        \
+                     (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens,     \
+                     (const int32_t*)nullptr, 0, a.C, a.L, a.w, a.S, a.S, 1, a.U, classes, nsl,                      \
+                     (unsigned short*)nullptr, a.seg_cnt, ft)
+  if (a.C <= 1) LASER_FUSED_STREAM(1);
+  else if (a.C <= 2) LASER_FUSED_STREAM(2);
+  else if (a.C <= 4) LASER_FUSED_STREAM(4);
+  else LASER_FUSED_STREAM(8);
+#undef LASER_FUSED_STREAM
+}
+
+laser_status fused_stream_launch(const FusedArgs& a) {
+  if (!fused_stream_supports(a)) return LASER_ERR_UNSUPPORTED;
+  const float nsl = -1.4426950408889634f / a.gamma;
+  switch (a.d_q * 1000 + a.d) {
+    case 32064: fused_stream_launch_c<32, 64>(a, nsl); break;
+    case 32128: fused_stream_launch_c<32, 128>(a, nsl); break;
+    case 64064: fused_stream_launch_c<64, 64>(a, nsl); break;
+    case 64128: fused_stream_launch_c<64, 128>(a, nsl); break;
+    case 128064: fused_stream_launch_c<128, 64>(a, nsl); break;
+    case 128128: fused_stream_launch_c<128, 128>(a, nsl); break;
+    default: return LASER_ERR_UNSUPPORTED;
+  }
+  return launch_status();
 }
 
 laser_status sta_stream_launch(const StaArgs& a) {

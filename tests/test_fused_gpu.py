@@ -23,7 +23,7 @@ REDUCED = {
     "cfg1": C["cfg1_tiny_f32"],                                            # fp32: the generic fused kernel
     "cfg2": C["cfg2_bf16"].replace(U=6),                                   # 64 candidates, d = 64: two waves
     "cfg3": C["cfg3_high_fanout"].replace(U=2, L=1024 + 128),              # 256 candidates, d = 128: two tiles of four waves
-    "cfg4": C["cfg4_low_fanout"].replace(U=48),                            # one candidate per user
+    "cfg4": C["cfg4_low_fanout"].replace(U=48),                            # one candidate per user: the streaming kernel
 }
 def _spec(dtype, U, Cn, L, d, dq, w, seed):
     return WorkloadSpec(f"fused_edge_{seed}", dtype, U=U, C=Cn, L=L, d=d, d_q=dq, w=w, M=1, lens_kind="full", seed=seed)
@@ -36,6 +36,12 @@ EDGE = {
     "one_segment": (_spec("bf16", 2, 16, 96, 64, 128, 128, 34), None),                 # w > L
     "odd_widths_f32": (_spec("f32", 3, 5, 130, 48, 24, 16, 35), [130, 50, 0]),         # the generic kernel
     "bf16_other_widths": (_spec("bf16", 2, 6, 90, 96, 40, 32, 36), [90, 33]),          # bf16 on the generic kernel
+    # few candidates per user with long segments: the streaming kernel with the layer as its epilogue
+    "stream_three_candidates": (_spec("bf16", 5, 3, 1500, 128, 64, 300, 37), [1500, 301, 300, 7, 0]),
+    "stream_eight_candidates": (_spec("bf16", 3, 8, 700, 64, 128, 128, 38), [700, 129, 128]),
+    "stream_two_wide": (_spec("bf16", 2, 2, 520, 128, 128, 256, 39), [520, 257]),
+    # few candidates with short segments: not the streaming form (the matrix-core kernel takes them)
+    "few_candidates_short_segments": (_spec("bf16", 3, 2, 200, 64, 64, 10, 40), [200, 95, 0]),
 }
 
 
