@@ -237,15 +237,6 @@ __global__ __launch_bounds__(64 * NW) void fused_mfma_kernel(const unsigned shor
     return e;
   };
 
-  Stage<DQ, D, NT> st;
-  int ci = seg_lo, ct0 = seg_lo * w, chi = seg_ne > seg_lo ? seg_end(seg_lo) : 0;   // current tile
-  int buf = 0;
-  if (seg_ne > seg_lo) {
-    st.load(kU, vU, ct0, chi, tid);
-    st.store(smem, smem + KBYTES, tid);
-  }
-  __syncthreads();
-
   f32x16 acc[DB], pacc[DB];
 #pragma unroll
   for (int db = 0; db < DB; ++db)
@@ -256,94 +247,146 @@ __global__ __launch_bounds__(64 * NW) void fused_mfma_kernel(const unsigned shor
     }
   float sm_m = FUSED_NEG, sm_l = 0.0f;
 
-  while (ci < seg_ne) {
-    int ni = ci, nt0 = ct0 + TI, nhi = chi;
-    if (nt0 >= chi) {
-      ni = ci + 1;
-      nt0 = ni * w;
-      nhi = ni < seg_ne ? seg_end(ni) : 0;
+  // per-lane LDS offsets that do not change: K operand row (block 0) and the transpose-load source
+  const int koff = l32 * KP + h * 16;
+  const int voff = (h * 4 + ((lane & 15) >> 2)) * VP + ((l32 & 16) + 4 * (lane & 3)) * 2;
+  auto score = [&](const unsigned char* Ks, int ib) {   // Sc^T of block ib: 32 items x 32 candidates
+    f32x16 sc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sc[r] = 0.0f;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(Ks + ib * 32 * KP + koff + ks * 32);
+      sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], sc, 0, 0, 0);
     }
-    const bool has_next = ni < seg_ne;
-    unsigned char* Ks = smem + buf * (KBYTES + VBYTES);
-    unsigned char* Vs = Ks + KBYTES;
-    // (in flight during the products below; with no next tile the current one is read again, in bounds and unused)
-    if (NBUF == 2) st.load(kU, vU, has_next ? nt0 : ct0, has_next ? nhi : chi, tid);
-
+    return sc;
+  };
+  auto aggregate = [&](const unsigned char* Vs, int ib, const bf16x8 (&p)[2]) {   // acc^T += V^T . P^T
 #pragma unroll
-    for (int ib = 0; ib < TI / 32; ++ib) {
-      if (ct0 + ib * 32 < chi) {   // uniform: otherwise the rest of the tile is padding (zero rows)
-        f32x16 sc;
+    for (int s = 0; s < 2; ++s)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sc[r] = 0.0f;
-#pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) {
-          const bf16x8 ka = *reinterpret_cast<const bf16x8*>(Ks + (ib * 32 + l32) * KP + (ks * 16 + h * 8) * 2);
-          sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[ks], sc, 0, 0, 0);
-        }
-        bf16x8 p[2];
-#pragma unroll
-        for (int s = 0; s < 2; ++s)
-#pragma unroll
-          for (int e = 0; e < 8; ++e) p[s][e] = (__bf16)gate(sc[s * 8 + e], neg_scale_log2e);
-#pragma unroll
-        for (int s = 0; s < 2; ++s) {
-          const int item0 = ib * 32 + s * 16 + h * 4;
-#pragma unroll
-          for (int db = 0; db < DB; ++db) {
-            const int dc0 = db * 32 + (l32 & 16);
-            const int i16 = lane & 15;
-            const unsigned char* src = Vs + (item0 + (i16 >> 2)) * VP + (dc0 + 4 * (i16 & 3)) * 2;
-            const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(src));
-            const s16x4 hi4 =
-                __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(src + 8 * VP));
-            const s16x8 both = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
-            acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), p[s], acc[db], 0, 0, 0);
-          }
-        }
+      for (int db = 0; db < DB; ++db) {
+        const unsigned char* src = Vs + (ib * 32 + s * 16) * VP + voff + db * 64;
+        const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(src));
+        const s16x4 hi4 =
+            __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(src + 8 * VP));
+        const s16x8 both = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), p[s], acc[db], 0, 0, 0);
       }
+  };
+  auto gates = [&](const f32x16& sc, bf16x8 (&p)[2]) {
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) p[s][e] = (__bf16)gate(sc[s * 8 + e], neg_scale_log2e);
+  };
+  // a finished segment's vector enters the layer's online softmax (base 2: rr carries log2 e / sqrt d)
+  auto segment_done = [&]() {
+    float e2 = 0.0f;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) e2 = fmaf(acc[db][r], rr[db][r], e2);
+    {   // the other half of the candidate's components sits in lane ^ 32
+      const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(e2), __float_as_uint(e2), false, false);
+      e2 = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
     }
-
-    if (NBUF == 2 && has_next)
-      st.store(smem + (buf ^ 1) * (KBYTES + VBYTES), smem + (buf ^ 1) * (KBYTES + VBYTES) + KBYTES, tid);
-    if (ni != ci) {
-      // ---- segment finished: its vector enters the layer's online softmax (base 2: rr carries log2 e / sqrt d)
-      float e2 = 0.0f;
+    const float m_new = fmaxf(sm_m, e2);
+    const float corr = __builtin_amdgcn_exp2f(sm_m - m_new);   // exactly 0 at the first segment
+    const float wgt = __builtin_amdgcn_exp2f(e2 - m_new);
+    sm_l = fmaf(sm_l, corr, wgt);
+    sm_m = m_new;
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
+    for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) e2 = fmaf(acc[db][r], rr[db][r], e2);
-      {   // the other half of the candidate's components sits in lane ^ 32
-        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(e2), __float_as_uint(e2), false, false);
-        e2 = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+      for (int r = 0; r < 16; ++r) {
+        pacc[db][r] = fmaf(wgt, acc[db][r], pacc[db][r] * corr);
+        acc[db][r] = 0.0f;
       }
-      const float m_new = fmaxf(sm_m, e2);
-      const float corr = __builtin_amdgcn_exp2f(sm_m - m_new);   // exactly 0 at the first segment
-      const float wgt = __builtin_amdgcn_exp2f(e2 - m_new);
-      sm_l = fmaf(sm_l, corr, wgt);
-      sm_m = m_new;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          pacc[db][r] = fmaf(wgt, acc[db][r], pacc[db][r] * corr);
-          acc[db][r] = 0.0f;
-        }
-    }
+  };
 
-    if (NBUF == 2) {
+  Stage<DQ, D, NT> st;
+  int ci = seg_lo, ct0 = seg_lo * w, chi = seg_ne > seg_lo ? seg_end(seg_lo) : 0;   // current tile
+  int buf = 0;
+  if (seg_ne > seg_lo) {
+    st.load(kU, vU, ct0, chi, tid);
+    st.store(smem, smem + KBYTES, tid);
+  }
+  __syncthreads();
+
+  if constexpr (NBUF == 2 && D == 64) {
+    // The two 32-item blocks of a tile software-pipelined inside the wave: the score chain of one block runs beside
+    // the gates of the other, the aggregation of a block beside the gates of the next. Every tile is computed in
+    // full (its padding rows are zeros in LDS). (Measured: 64 users x 64 candidates, d = 64: 29.1 -> 26.9 us for the
+    // whole fused path; with d = 128, at 383 registers and one wave per SIMD, the same order is slower, 60 against
+    // 51 us for 32 users x 256 candidates, and the plain order below is kept.)
+    f32x16 sc0;
+    if (seg_ne > seg_lo) sc0 = score(smem, 0);
+    while (ci < seg_ne) {
+      int ni = ci, nt0 = ct0 + TI, nhi = chi;
+      if (nt0 >= chi) {
+        ni = ci + 1;
+        nt0 = ni * w;
+        nhi = ni < seg_ne ? seg_end(ni) : 0;
+      }
+      const bool has_next = ni < seg_ne;
+      const unsigned char* Ks = smem + buf * (KBYTES + VBYTES);
+      const unsigned char* Vs = Ks + KBYTES;
+      unsigned char* nKs = smem + (buf ^ 1) * (KBYTES + VBYTES);
+      st.load(kU, vU, has_next ? nt0 : ct0, has_next ? nhi : chi, tid);   // lands during the products below
+      bf16x8 p0[2], p1[2];
+      const f32x16 sc1 = score(Ks, 1);
+      gates(sc0, p0);
+      aggregate(Vs, 0, p0);
+      gates(sc1, p1);
+      aggregate(Vs, 1, p1);
+      if (has_next) st.store(nKs, nKs + KBYTES, tid);
+      if (ni != ci) segment_done();
       __syncthreads();
       buf ^= 1;
-    } else {
-      __syncthreads();   // everyone is done reading the tile
-      if (has_next) {
-        st.load(kU, vU, nt0, nhi, tid);
-        st.store(smem, smem + KBYTES, tid);
-      }
-      __syncthreads();
+      if (has_next) sc0 = score(nKs, 0);
+      ci = ni;
+      ct0 = nt0;
+      chi = nhi;
     }
-    ci = ni;
-    ct0 = nt0;
-    chi = nhi;
+  } else {
+    while (ci < seg_ne) {
+      int ni = ci, nt0 = ct0 + TI, nhi = chi;
+      if (nt0 >= chi) {
+        ni = ci + 1;
+        nt0 = ni * w;
+        nhi = ni < seg_ne ? seg_end(ni) : 0;
+      }
+      const bool has_next = ni < seg_ne;
+      const unsigned char* Ks = smem + buf * (KBYTES + VBYTES);
+      // (in flight during the products below; with no next tile the current one is read again, in bounds and unused)
+      if (NBUF == 2) st.load(kU, vU, has_next ? nt0 : ct0, has_next ? nhi : chi, tid);
+#pragma unroll
+      for (int ib = 0; ib < TI / 32; ++ib) {
+        if (ct0 + ib * 32 < chi) {   // uniform: otherwise the rest of the tile is padding (zero rows)
+          bf16x8 p[2];
+          gates(score(Ks, ib), p);
+          aggregate(Ks + KBYTES, ib, p);
+        }
+      }
+      if (NBUF == 2 && has_next)
+        st.store(smem + (buf ^ 1) * (KBYTES + VBYTES), smem + (buf ^ 1) * (KBYTES + VBYTES) + KBYTES, tid);
+      if (ni != ci) segment_done();
+      if (NBUF == 2) {
+        __syncthreads();
+        buf ^= 1;
+      } else {
+        __syncthreads();   // everyone is done reading the tile
+        if (has_next) {
+          st.load(kU, vU, nt0, nhi, tid);
+          st.store(smem, smem + KBYTES, tid);
+        }
+        __syncthreads();
+      }
+      ci = ni;
+      ct0 = nt0;
+      chi = nhi;
+    }
   }
 
   if (sruns == 1) {   // the whole history was walked here: finish the pairs (the tile buffers become W_v's)
@@ -363,21 +406,21 @@ __global__ __launch_bounds__(64 * NW) void fused_mfma_kernel(const unsigned shor
   }
 }
 
-// Runs of a pair merged in run order (fixed order: reproducible), then z = t0 + (P / l) W_v. One wave per tile of
-// 32 candidates, NWF of them per (user, candidate tile) as in the kernel that wrote the partial results.
+// The runs of a pair merged in a fixed order (reproducible), then z = t0 + (P / l) W_v. One workgroup per tile of 32
+// candidates (tiles numbered as by the kernel that wrote the partial results: nwf of them per (user, candidate
+// tile)); wave v merges runs v, v + NWM, ... in ascending order, the waves' results meet in LDS and wave 0 merges
+// them in wave order and finishes the pairs. All waves park W_v meanwhile.
 template <int D, int NWM>
 __global__ __launch_bounds__(64 * NWM) void fused_merge_kernel(const float* __restrict__ part,
                                                                const unsigned short* __restrict__ t0,
                                                                const unsigned short* __restrict__ wv, int C,
-                                                               int ctiles, int nwf, int sruns, long long tiles,
-                                                               float* __restrict__ z) {
-  constexpr int VP = VPitch<D>::v, DB = D / 32;
+                                                               int ctiles, int nwf, int sruns, float* __restrict__ z) {
+  constexpr int VP = VPitch<D>::v, DB = D / 32, ROWS = part_rows<D>();
   __shared__ __attribute__((aligned(16))) unsigned char Wvl[D * VP];
+  __shared__ float mix[NWM][ROWS][64];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   WeightsLds<D>::template park<64 * NWM>(Wvl, VP, wv, tid);
-  long long tile = (long long)blockIdx.x * NWM + wave;
-  const bool live = tile < tiles;
-  if (!live) tile = tiles - 1;   // keeps the wave in the barrier and the products; it stores nothing
+  const long long tile = blockIdx.x;
   const int wv_in = (int)(tile % nwf);
   const long long uc = tile / nwf;
   const int ct = (int)(uc % ctiles);
@@ -390,9 +433,7 @@ __global__ __launch_bounds__(64 * NWM) void fused_merge_kernel(const float* __re
 #pragma unroll
     for (int r = 0; r < 16; ++r) pacc[db][r] = 0.0f;
   float m = FUSED_NEG, l = 0.0f;
-  for (int s = 0; s < sruns; ++s) {
-    const float* src = part + (((size_t)tile * sruns + s) * part_rows<D>()) * 64 + lane;
-    const float ms = src[(D / 2) * 64], ls = src[(D / 2 + 1) * 64];
+  auto absorb = [&](float ms, float ls, auto&& prow) {   // (m, l, P) <- (m, l, P) merged with (ms, ls, prow(.))
     const float m_new = fmaxf(m, ms);
     const float corr = __builtin_amdgcn_exp2f(m - m_new), ws = __builtin_amdgcn_exp2f(ms - m_new);
     l = fmaf(l, corr, ls * ws);
@@ -400,10 +441,26 @@ __global__ __launch_bounds__(64 * NWM) void fused_merge_kernel(const float* __re
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) pacc[db][r] = fmaf(src[(db * 16 + r) * 64], ws, pacc[db][r] * corr);
+      for (int r = 0; r < 16; ++r) pacc[db][r] = fmaf(prow(db * 16 + r), ws, pacc[db][r] * corr);
+  };
+  for (int s = wave; s < sruns; s += NWM) {
+    const float* src = part + (((size_t)tile * sruns + s) * ROWS) * 64 + lane;
+    absorb(src[(D / 2) * 64], src[(D / 2 + 1) * 64], [&](int row) { return src[row * 64]; });
+  }
+  if (wave > 0) {
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mix[wave][db * 16 + r][lane] = pacc[db][r];
+    mix[wave][D / 2][lane] = m;
+    mix[wave][D / 2 + 1][lane] = l;
   }
   __syncthreads();
-  finish_pairs<D>(pacc, l, t0, (size_t)u * C, cbase, live ? C : 0, Wvl, VP, lane, z);
+  if (wave == 0) {
+    for (int o = 1; o < NWM; ++o)
+      absorb(mix[o][D / 2][lane], mix[o][D / 2 + 1][lane], [&](int row) { return mix[o][row][lane]; });
+    finish_pairs<D>(pacc, l, t0, (size_t)u * C, cbase, C, Wvl, VP, lane, z);
+  }
 }
 
 // ---------------------------------------------------------------------------------------------- generic kernel
@@ -670,14 +727,14 @@ laser_status fused_mfma_launch(const FusedArgs& a) {
   if (launch_status() != LASER_OK) return LASER_ERR_LAUNCH;
   if (sruns == 1) return LASER_OK;
   const long long tiles = (long long)a.U * ctiles * nw;
-  constexpr int NWM = 4;
-  const unsigned mblocks = (unsigned)((tiles + NWM - 1) / NWM);
+  if (tiles > 0x7fffffffLL) return LASER_ERR_SHAPE;
+  constexpr int NWM = 4;   // a workgroup per tile: four waves share the runs and the parking of W_v
   if (a.d == 64)
-    hipLaunchKernelGGL((fused_merge_kernel<64, NWM>), dim3(mblocks), dim3(64 * NWM), 0, a.stream, a.work,
-                       (const unsigned short*)a.t0, (const unsigned short*)a.wv, a.C, ctiles, nw, sruns, tiles, a.z_out);
+    hipLaunchKernelGGL((fused_merge_kernel<64, NWM>), dim3((unsigned)tiles), dim3(64 * NWM), 0, a.stream, a.work,
+                       (const unsigned short*)a.t0, (const unsigned short*)a.wv, a.C, ctiles, nw, sruns, a.z_out);
   else
-    hipLaunchKernelGGL((fused_merge_kernel<128, NWM>), dim3(mblocks), dim3(64 * NWM), 0, a.stream, a.work,
-                       (const unsigned short*)a.t0, (const unsigned short*)a.wv, a.C, ctiles, nw, sruns, tiles, a.z_out);
+    hipLaunchKernelGGL((fused_merge_kernel<128, NWM>), dim3((unsigned)tiles), dim3(64 * NWM), 0, a.stream, a.work,
+                       (const unsigned short*)a.t0, (const unsigned short*)a.wv, a.C, ctiles, nw, sruns, a.z_out);
   return launch_status();
 }
 
