@@ -227,6 +227,25 @@ def paper_setting_ranking(laser, torch, event_time):
         ffn(i)
         gsta_views(i)
 
+    def ffn_gsta(i):   # FFN + LayerNorm and GSTA from one pass over H' (the transformed rows written in place)
+        laser.laser_ffn_gsta_forward(seg, t, *g3, lens, w1, b1, w2, b2, ln_g, ln_b, L, w, 1e-5, seg_out=seg, z_out=z)
+
+    def ffn_gsta_z_only(i):
+        laser.laser_ffn_gsta_forward(seg, t, *g3, lens, w1, b1, w2, b2, ln_g, ln_b, L, w, 1e-5, z_out=z, want_seg=False)
+
+    def head_one_pass(i):   # the head without the two other views: z from one pass over H'
+        laser.laser_project_q_forward(t, Wq, q_out=Q)
+        laser.laser_project_kv_forward(H, Wk, Wv, k_out=K, v_out=V)
+        sta()(i)
+        ffn_gsta_z_only(i)
+
+    def head_two_calls(i):
+        laser.laser_project_q_forward(t, Wq, q_out=Q)
+        laser.laser_project_kv_forward(H, Wk, Wv, k_out=K, v_out=V)
+        sta()(i)
+        ffn(i)
+        laser.laser_gsta_forward(seg, t, *g3, lens, L, w, z_out=z)
+
     chain(0)
     out = {"U": U, "C": C, "L": L, "w": w, "heads": heads, "d_q": dq, "d": d,
            "kv_projection_ms": event_time(lambda i: laser.laser_project_kv_forward(H, Wk, Wv, k_out=K, v_out=V)),
@@ -240,6 +259,10 @@ def paper_setting_ranking(laser, torch, event_time):
     out["views_ms"] = event_time(views)
     out["gsta_with_views_ms"] = event_time(gsta_views)
     out["full_head_ms"] = event_time(full_head)
+    out["ffn_then_gsta_one_pass_ms"] = event_time(ffn_gsta)
+    out["ffn_then_gsta_one_pass_z_only_ms"] = event_time(ffn_gsta_z_only)
+    out["head_z_two_calls_ms"] = event_time(head_two_calls)
+    out["head_z_one_pass_ms"] = event_time(head_one_pass)
     out["pairs_per_s_full_head"] = U * C / (out["full_head_ms"] * 1e-3)
     nvalid = int(lens.sum())
     # STA alone: valid K and V rows, the queries, H' written once
@@ -444,6 +467,31 @@ def main() -> int:
                "gbps": ffn_b / (ffn_ms * 1e-3) / 1e9, "tflops": ffn_f / (ffn_ms * 1e-3) / 1e12,
                "bound": "hbm" if t_h >= t_m else "mfma",
                "frac": (t_h if t_h >= t_m else t_m) / (ffn_ms * 1e-3)}
+        if spec.M == 1:
+            # FFN + LayerNorm and GSTA behind it: the two calls in a row (the transformed H' written and read back)
+            # against laser_ffn_gsta_forward (one pass over H', transformed rows not wanted)
+            def two_calls(i):
+                dw, seg, cnt, z = sets[i % copies]
+                laser.laser_segment_ffn_forward(seg, dw.lens, w1, b1, w2, b2, ln_g, ln_b, spec.L, spec.w, 1e-5,
+                                                seg_out=outs2[i % copies])
+                laser.laser_gsta_forward(outs2[i % copies], dw.t0, dw.wq, dw.wk, dw.wv, dw.lens, spec.L, spec.w, z_out=z)
+
+            def one_pass(i):
+                dw, seg, cnt, z = sets[i % copies]
+                laser.laser_ffn_gsta_forward(seg, dw.t0, dw.wq, dw.wk, dw.wv, dw.lens, w1, b1, w2, b2, ln_g, ln_b,
+                                             spec.L, spec.w, 1e-5, z_out=z, want_seg=False)
+
+            two_ms = event_time(two_calls)
+            try:
+                one_ms = event_time(one_pass)
+            except laser.LaserError:
+                one_ms = None
+            # least traffic of FFN + GSTA when only z is wanted: valid segment vectors read once, t0 and z, the weights
+            fg_b = (nvalid * spec.C * spec.d + spec.pairs * spec.d + (2 * args.ffn + 3 * spec.d) * spec.d) * esz \
+                + spec.pairs * spec.d * 4
+            ffn["then_gsta"] = {"two_calls_ms": two_ms, "one_pass_ms": one_ms, "one_pass_algorithmic_bytes": fg_b,
+                                "one_pass_frac_of_hbm_peak": None if one_ms is None else
+                                fg_b / (one_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
     project = None
     if args.project > 0:

@@ -260,6 +260,24 @@ laser_status laser_segment_ffn_forward_variant(const void* seg, const int32_t* l
                                                void* seg_out, void* stream, laser_ffn_variant variant);
 
 /*
+ * The segment feed-forward step followed by GSTA (paper Sec. 3.4.2, the FFN + LayerNorm equation, then Sec. 3.4.3):
+ * z = GSTA(t0; s) with s = LN(FFN(H') + H') as laser_segment_ffn_forward defines it, rounded to dt once as if it
+ * were stored. Arguments as for laser_segment_ffn_forward (seg, lens, w1 .. ln_b, d_ff, eps) and laser_gsta_forward
+ * (t0, wq, wk, wv, M, z_out); all pointers are device pointers, caller-owned, aligned as there.
+ * seg_out [U,C,S,d] dt receives s (fully overwritten, zeros for segments without a valid item); it may be seg itself,
+ * and it may be NULL when s is not wanted. bf16, d = 128, d_ff in {64, 128}, M = 1: one pass over H', s is scored
+ * and pooled while it is on chip, z_out holds intermediate values until the last of three launches has run. Any
+ * other shape: laser_segment_ffn_forward into seg_out, then laser_gsta_forward on it, and LASER_ERR_UNSUPPORTED if
+ * seg_out is NULL. Results agree with those two calls in a row up to the order of fp32 sums.
+ * Errors: those of the two entry points (seg_out may be NULL), everything validated before the first launch.
+ */
+laser_status laser_ffn_gsta_forward(const void* seg, const void* t0, const void* wq, const void* wk, const void* wv,
+                                    const int32_t* lens, const void* w1, const float* b1, const void* w2,
+                                    const float* b2, const float* ln_g, const float* ln_b, int U, int C, int L, int d,
+                                    int d_ff, int w, int M, float eps, laser_dtype dt, void* seg_out, float* z_out,
+                                    void* stream);
+
+/*
  * Multi-resolution feature fusion (paper Sec. 3.4.4): besides the global context z, the representation holds
  * max_pool(H') and the r most recent segments s_1 .. s_r. Both are taken from a stored H':
  *   pool_out   [U,C,d]   dt   component-wise maximum over the segment vectors of the pair that hold at least one

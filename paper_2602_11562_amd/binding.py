@@ -26,7 +26,7 @@ EXPORTS = [
     "laser_segment_ffn_forward_ragged", "laser_gsta_forward", "laser_gsta_forward_variant",
     "laser_forward", "laser_forward_fused", "laser_forward_fused_work_bytes", "laser_multires_forward", "laser_forward_multires", "laser_gsta_forward_multires",
     "laser_sta_kernel_name",
-    "laser_gsta_kernel_name", "laser_segment_ffn_forward", "laser_segment_ffn_forward_variant",
+    "laser_gsta_kernel_name", "laser_segment_ffn_forward", "laser_segment_ffn_forward_variant", "laser_ffn_gsta_forward",
     "laser_gsta_kernel_name_layers", "laser_project_q_forward", "laser_project_q_forward_variant",
     "laser_project_kv_forward", "laser_project_kv_forward_variant", "laser_fold_query_weights",
     "laser_project_heads_forward", "laser_sta_folded_forward", "laser_sta_backward", "laser_sta_backward_bf16", "laser_sta_backward_static", "laser_sta_backward_work_bytes", "laser_gsta_backward",
@@ -84,6 +84,9 @@ def load_library() -> ctypes.CDLL:
     lib.laser_segment_ffn_forward.restype = i32
     lib.laser_segment_ffn_forward_variant.argtypes = lib.laser_segment_ffn_forward.argtypes + [i32]
     lib.laser_segment_ffn_forward_variant.restype = i32
+    lib.laser_ffn_gsta_forward.argtypes = [vp, vp, vp, vp, vp, ip, vp, fp, vp, fp, fp, fp, i32, i32, i32, i32, i32, i32,
+                                           i32, f32, i32, vp, vp, vp]
+    lib.laser_ffn_gsta_forward.restype = i32
     lib.laser_project_q_forward.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp]
     lib.laser_project_q_forward_variant.argtypes = lib.laser_project_q_forward.argtypes + [i32]
     lib.laser_project_kv_forward.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp]
@@ -598,6 +601,38 @@ def laser_gsta_forward_multires(seg, t0, wq, wk, wv, lens, L: int, w: int, r: in
         int(r), _ptr(pool_out, "pool_out"), _ptr(recent_out, "recent_out"), _stream(stream))
     _check(code, "laser_gsta_forward_multires")
     return z_out, pool_out, recent_out
+
+
+def laser_ffn_gsta_forward(seg, t0, wq, wk, wv, lens, w1, b1, w2, b2, ln_g, ln_b, L: int, w: int, eps: float = 1e-5,
+                           seg_out=None, z_out=None, stream=None, want_seg: bool = True):
+    """seg [U,C,S,d] -> (s = LN(FFN(seg) + seg) [U,C,S,d] or None, z = GSTA(t0; s) [U,C,d] fp32). want_seg=False
+    passes a null seg_out (s is not written); seg_out may be seg itself."""
+    torch = _torch()
+    U, C, S, d = seg.shape
+    d_ff = w1.shape[1]
+    M = wq.shape[0]
+    if S != -(-L // w):
+        raise ValueError("seg.shape[2] must be ceil(L / w)")
+    if tuple(w1.shape) != (d, d_ff) or tuple(w2.shape) != (d_ff, d):
+        raise ValueError("w1 must be [d, d_ff] and w2 [d_ff, d]")
+    if tuple(b1.shape) != (d_ff,) or any(tuple(x.shape) != (d,) for x in (b2, ln_g, ln_b)):
+        raise ValueError("b1 must be [d_ff]; b2, ln_g, ln_b must be [d]")
+    if tuple(t0.shape) != (U, C, d) or any(tuple(x.shape) != (M, d, d) for x in (wq, wk, wv)):
+        raise ValueError("t0 / weight shapes disagree with seg")
+    if any(x.dtype != seg.dtype for x in (t0, wq, wk, wv, w1, w2)):
+        raise TypeError("seg, t0 and the weight matrices must share a dtype")
+    if seg_out is None and want_seg:
+        seg_out = torch.empty_like(seg)
+    if z_out is None:
+        z_out = torch.empty((U, C, d), dtype=torch.float32, device=seg.device)
+    code = load_library().laser_ffn_gsta_forward(
+        _ptr(seg, "seg"), _ptr(t0, "t0"), _ptr(wq, "wq"), _ptr(wk, "wk"), _ptr(wv, "wv"),
+        _ptr(lens, "lens", torch.int32), _ptr(w1, "w1"), _ptr(b1, "b1", torch.float32), _ptr(w2, "w2"),
+        _ptr(b2, "b2", torch.float32), _ptr(ln_g, "ln_g", torch.float32), _ptr(ln_b, "ln_b", torch.float32), U, C,
+        int(L), d, d_ff, int(w), M, float(eps), _dt(seg), _ptr(seg_out, "seg_out", seg.dtype),
+        _ptr(z_out, "z_out", torch.float32), _stream(stream))
+    _check(code, "laser_ffn_gsta_forward")
+    return seg_out, z_out
 
 
 def laser_multires_forward(seg, lens, L: int, w: int, r: int, pool_out=None, recent_out=None, stream=None,

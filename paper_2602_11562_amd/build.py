@@ -20,7 +20,7 @@ LIB = os.path.join(HERE, "liblaser.so")
 OBJDIR = os.path.join(HERE, "_build")
 
 SOURCES = ["laser_api.hip", "sta_generic.hip", "sta_mfma.hip", "sta_stream.hip", "gsta_generic.hip",
-           "gsta_tiled.hip", "fused_forward.hip", "multires.hip", "segment_ffn.hip", "project.hip", "sta_backward.hip", "gsta_backward.hip"]
+           "gsta_tiled.hip", "fused_forward.hip", "multires.hip", "segment_ffn.hip", "ffn_gsta.hip", "project.hip", "sta_backward.hip", "gsta_backward.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

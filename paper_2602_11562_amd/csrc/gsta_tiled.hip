@@ -231,7 +231,9 @@ __global__ __launch_bounds__(GT_THREADS) void gsta_tiled_kernel(const unsigned s
     __syncthreads();
 
     // step 3: one pair per wave at a time; its H' block goes through registers once
-    if (layer > 0) {
+    // (H' is the same in every layer, Sec. 3.4.3: when the ring holds all of the wave's blocks they stay where they
+    // are; otherwise the first ones are requested again, from the caches)
+    if (layer > 0 && PPW > DEPTH) {
 #pragma unroll
       for (int dd = 0; dd < DEPTH; ++dd) load_pair(wave + dd * GT_WAVES, nvs[dd], hring[dd]);
     }
@@ -987,6 +989,34 @@ laser_status gsta_split_launch(const GstaArgs& a) {
   if (!gsta_split_supports(a)) return LASER_ERR_UNSUPPORTED;
   if (a.d == 64) launch_split<64>(a);
   else launch_split<128>(a);
+  return launch_status();
+}
+
+// The outer two launches of the split form on their own, for a caller that produces p itself between them
+// (ffn_gsta.hip): r = (t0 W_q) W_k^T / sqrt(d) into the z rows, and z = t0 + p W_v from the z rows. bf16, d in {64, 128}.
+laser_status gsta_r_launch(const GstaArgs& a) {
+  if (a.dt != LASER_BF16 || !(a.d == 64 || a.d == 128)) return LASER_ERR_UNSUPPORTED;
+  const int P = gsta_pairs(a);
+  const unsigned tiles = (unsigned)((P + GT_ROWS - 1) / GT_ROWS);
+  if (a.d == 64)
+    hipLaunchKernelGGL((gsta_r_kernel<64>), dim3(tiles), dim3(GS_THREADS), 0, a.stream, (const unsigned short*)a.t0,
+                       (const unsigned short*)a.wq, (const unsigned short*)a.wk, P, a.z_out);
+  else
+    hipLaunchKernelGGL((gsta_r_kernel<128>), dim3(tiles), dim3(GS_THREADS), 0, a.stream, (const unsigned short*)a.t0,
+                       (const unsigned short*)a.wq, (const unsigned short*)a.wk, P, a.z_out);
+  return launch_status();
+}
+
+laser_status gsta_out_launch(const GstaArgs& a) {
+  if (a.dt != LASER_BF16 || !(a.d == 64 || a.d == 128)) return LASER_ERR_UNSUPPORTED;
+  const int P = gsta_pairs(a);
+  const unsigned tiles = (unsigned)((P + GT_ROWS - 1) / GT_ROWS);
+  if (a.d == 64)
+    hipLaunchKernelGGL((gsta_out_kernel<64>), dim3(tiles), dim3(GS_THREADS), 0, a.stream, (const unsigned short*)a.t0,
+                       (const unsigned short*)a.wv, P, a.z_out);
+  else
+    hipLaunchKernelGGL((gsta_out_kernel<128>), dim3(tiles), dim3(GS_THREADS), 0, a.stream, (const unsigned short*)a.t0,
+                       (const unsigned short*)a.wv, P, a.z_out);
   return launch_status();
 }
 

@@ -83,8 +83,9 @@ static laser_status validate_multires(const void* seg, const int32_t* lens, int 
 
 static laser_status validate_ffn(const void* seg, const int32_t* lens, const void* w1, const float* b1, const void* w2,
                                  const float* b2, const float* ln_g, const float* ln_b, int U, int C, int L, int d,
-                                 int d_ff, int w, float eps, laser_dtype dt, void* seg_out, void* stream, FfnArgs* out) {
-  if (!seg || !w1 || !b1 || !w2 || !b2 || !ln_g || !ln_b || !seg_out) return LASER_ERR_NULL;
+                                 int d_ff, int w, float eps, laser_dtype dt, void* seg_out, void* stream, FfnArgs* out,
+                                 bool seg_out_required = true) {
+  if (!seg || !w1 || !b1 || !w2 || !b2 || !ln_g || !ln_b || (seg_out_required && !seg_out)) return LASER_ERR_NULL;
   if (dt != LASER_F32 && dt != LASER_BF16) return LASER_ERR_DTYPE;
   laser_status s = check_dims(U, C, L, d, d, w);
   if (s != LASER_OK) return s;
@@ -441,6 +442,27 @@ laser_status laser_segment_ffn_forward_variant(const void* seg, const int32_t* l
   if (variant < LASER_FFN_AUTO || variant > LASER_FFN_MFMA) return LASER_ERR_UNSUPPORTED;
   if (variant == LASER_FFN_AUTO) variant = segment_ffn_mfma_supports(a) ? LASER_FFN_MFMA : LASER_FFN_GENERIC;
   return variant == LASER_FFN_MFMA ? segment_ffn_mfma_launch(a) : segment_ffn_generic_launch(a);
+}
+
+laser_status laser_ffn_gsta_forward(const void* seg, const void* t0, const void* wq, const void* wk, const void* wv,
+                                    const int32_t* lens, const void* w1, const float* b1, const void* w2,
+                                    const float* b2, const float* ln_g, const float* ln_b, int U, int C, int L, int d,
+                                    int d_ff, int w, int M, float eps, laser_dtype dt, void* seg_out, float* z_out,
+                                    void* stream) {
+  FfnArgs fa;
+  GstaArgs ga;
+  laser_status s = validate_ffn(seg, lens, w1, b1, w2, b2, ln_g, ln_b, U, C, L, d, d_ff, w, eps, dt, seg_out, stream,
+                                &fa, false);
+  if (s != LASER_OK) return s;
+  s = validate_gsta(seg, t0, wq, wk, wv, lens, U, C, L, d, w, M, dt, z_out, stream, &ga);
+  if (s != LASER_OK) return s;
+  if (ffn_gsta_fused_supports(fa, ga)) return ffn_gsta_fused_launch(fa, ga);
+  // no kernel takes both steps for this shape: the two launches, through the transformed H'
+  if (!seg_out) return LASER_ERR_UNSUPPORTED;
+  s = segment_ffn_mfma_supports(fa) ? segment_ffn_mfma_launch(fa) : segment_ffn_generic_launch(fa);
+  if (s != LASER_OK) return s;
+  ga.seg = seg_out;
+  return run_gsta(ga, LASER_GSTA_AUTO);
 }
 
 laser_status laser_segment_ffn_forward(const void* seg, const int32_t* lens, const void* w1, const float* b1,

@@ -198,6 +198,11 @@ bool gsta_tiled_supports(const GstaArgs& a);
 laser_status gsta_tiled_launch(const GstaArgs& a);
 bool gsta_split_supports(const GstaArgs& a);
 laser_status gsta_split_launch(const GstaArgs& a);
+laser_status gsta_r_launch(const GstaArgs& a);     // first launch of the split form alone: r into the z rows
+laser_status gsta_out_launch(const GstaArgs& a);   // its last launch alone: z = t0 + p W_v from the z rows
+// FFN + LayerNorm feeding one GSTA layer from a single pass over H' (ffn_gsta.hip); f.seg_out may be null
+bool ffn_gsta_fused_supports(const FfnArgs& f, const GstaArgs& g);
+laser_status ffn_gsta_fused_launch(const FfnArgs& f, const GstaArgs& g);
 bool gsta_one_supports(const GstaArgs& a);
 laser_status gsta_one_launch(const GstaArgs& a);
 int gsta_one_max_recent(int d);   // largest r whose recent_out the one-kernel form writes itself
