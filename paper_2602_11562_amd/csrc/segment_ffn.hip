@@ -137,10 +137,11 @@ laser_status segment_ffn_generic_launch(const FfnArgs& a) {
 namespace laser {
 
 // ------------------------------------------------------------------------------------------ matrix-core form
-// The tile itself (operand scheme, weights parked in LDS, products, LayerNorm statistics) is in segment_ffn_tile.h.
-// Here the rows are the flat [pairs * S] row space of H' in tiles of 32; normalised rows are rounded and leave
-// through a wave-private LDS patch as whole 256-byte rows. 256 workgroups of 8 waves walk the row tiles with a grid
-// stride. In place is safe: a wave has its 32 rows in registers before it writes them.
+// The tile itself (operand scheme, weights and rows fetched straight into LDS, products, LayerNorm statistics) is in
+// segment_ffn_tile.h. Here the rows are the flat [pairs * S] row space of H' in tiles of 32; 256 workgroups of 8
+// waves walk the tiles with a grid stride, each wave with the rows of its next tile in flight while it multiplies.
+// Normalised rows are rounded and leave through the wave's LDS patch as whole 256-byte rows. In place is safe: a
+// wave's requests for a tile are complete before it writes that tile, and no other wave touches it.
 template <int DFF>
 __global__ __launch_bounds__(FM_THREADS) void segment_ffn_mfma_kernel(
     const unsigned short* seg, const int32_t* __restrict__ lens, const unsigned short* __restrict__ w1,
@@ -149,54 +150,79 @@ __global__ __launch_bounds__(FM_THREADS) void segment_ffn_mfma_kernel(
     long long rows, int C, int L, int w, int S, float eps,
     unsigned short* out) {
   constexpr int D = FM_D, KSTEPS = D / 16, DB = D / 32, OP = FM_OP;
+  __shared__ __attribute__((aligned(1024))) unsigned char W1L[FM_W1B];
   __shared__ __attribute__((aligned(1024))) unsigned char W2L[DFF * FM_ROWB];
-  __shared__ __attribute__((aligned(16))) unsigned char W1T[DFF * FM_W1P];
-  __shared__ __attribute__((aligned(16))) unsigned char patch[FM_WAVES * FM_ROWS * OP];
+  __shared__ __attribute__((aligned(1024))) unsigned char patch[FM_WAVES * FM_PATCH];
   __shared__ __attribute__((aligned(16))) float vecs[DFF + 3 * D];             // b1, b2, ln_g, ln_b
-  __shared__ int rowok[FM_WAVES][FM_ROWS];
 
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  ffn_park_weights<DFF>(W1T, W2L, vecs, w1, w2, b1, b2, ln_g, ln_b, tid);
+  unsigned char* opatch = patch + wave * FM_PATCH;
+  const unsigned land = __builtin_amdgcn_readfirstlane(ffn_lds_addr(opatch));
+  const long long ntiles = (rows + FM_ROWS - 1) / FM_ROWS;
+  const long long stride = (long long)gridDim.x * FM_WAVES;
+  long long t = (long long)blockIdx.x * FM_WAVES + wave;
+  // rows of tile tt into the landing area (rows past the end repeat the last one; never stored)
+  auto fetch_tile = [&](long long tt) {
+    const long long r0 = tt * FM_ROWS;
+    const long long left = rows - r0 - 1;
+    ffn_fetch_rows(seg + (size_t)r0 * D, left < FM_ROWS - 1 ? (int)left : FM_ROWS - 1, land, lane);
+  };
+  ffn_park_weights<DFF>(__builtin_amdgcn_readfirstlane(ffn_lds_addr(W1L)), __builtin_amdgcn_readfirstlane(ffn_lds_addr(W2L)),
+                        vecs, w1, w2, b1, b2, ln_g, ln_b, tid);
+  if (t < ntiles) fetch_tile(t);
+  ffn_wait_fetches();
   __syncthreads();
   const float* b1s = vecs;
   const float* b2s = vecs + DFF;
   const float* gs = vecs + DFF + D;
   const float* bs = vecs + DFF + 2 * D;
   FfnLane ln;
-  ln.init(W1T, lane);
-  unsigned char* opatch = patch + wave * FM_ROWS * OP;
+  ln.init(lane);
   constexpr int LPR = D / 8, RPI = 64 / LPR;
   const unsigned char* opr = opatch + (lane / LPR) * OP + (lane % LPR) * 16;
 
-  const long long ntiles = (rows + FM_ROWS - 1) / FM_ROWS;
-  for (long long t = (long long)blockIdx.x * FM_WAVES + wave; t < ntiles; t += (long long)gridDim.x * FM_WAVES) {
-    const long long r0 = t * FM_ROWS;
-    // the wave's rows as the B operand (rows past the end repeat the last one; never stored)
-    bf16x8 xreg[KSTEPS];
-    {
-      const long long r = (r0 + l32) < rows ? (r0 + l32) : (rows - 1);
-      const unsigned short* xr = seg + (size_t)r * D + h * 8;
-#pragma unroll
-      for (int ks = 0; ks < KSTEPS; ++ks) xreg[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(xr + ks * 16));
+  // Does this lane's row of tile tt belong to a segment with a valid item: first item of the segment and the user's
+  // valid length. The length of the next tile's row is requested ahead of that tile's fetch and compared after the
+  // products (a vector load awaited while the fetch is in flight would wait for the fetch as well).
+  struct RowLen { long long first; int len; };
+  auto row_len = [&](long long tt) {
+    const long long r = tt * FM_ROWS + l32;
+    RowLen o{1, 0};
+    if (r < rows) {   // (rows < 2^31: 32-bit division)
+      const unsigned pr = (unsigned)r / (unsigned)S;
+      o.first = (long long)((unsigned)r - pr * (unsigned)S) * w;
+      o.len = valid_len(lens, pair_user(cand_off, U, C, (int)pr), L);
     }
-    if (lane < FM_ROWS) {   // which rows belong to a segment with a valid item
-      const long long r = r0 + lane;
-      int ok = 0;
-      if (r < rows) {
-        const int i = (int)(r % S);
-        const int u = pair_user(cand_off, U, C, (int)(r / S));
-        ok = (long long)i * w < valid_len(lens, u, L);
-      }
-      rowok[wave][lane] = ok;
+    return o;
+  };
+  bf16x8 xreg[KSTEPS];
+  bool ok = false;
+  if (t < ntiles) {
+    ffn_read_rows(opatch, l32, h, xreg);
+    const RowLen rl = row_len(t);
+    ok = rl.first < rl.len;
+  }
+  for (; t < ntiles; t += stride) {
+    const long long r0 = t * FM_ROWS;
+    const bool more = t + stride < ntiles;
+    RowLen nxt{1, 0};
+    if (more) {
+      nxt = row_len(t + stride);
+      fetch_tile(t + stride);   // the patch is idle: the previous tile's rows have left it
     }
     f32x16 acc[DB];
-    ffn_tile_products<DFF>(xreg, ln, W2L, b1s, b2s, h, acc);
-    // ---- LayerNorm over d, gain, bias: two multiply-adds per value
+    ffn_tile_products<DFF>(xreg, ln, W1L, W2L, b1s, b2s, l32, h, acc);
+    if (more) {   // the next tile's rows move into the registers of this one's before the patch is written
+      ffn_wait_fetches();
+      ffn_read_rows(opatch, l32, h, xreg);
+    }
+    // ---- LayerNorm over d, gain, bias: two multiply-adds per value; rows of segments without a valid item are zeros
     float rstd, nmr;
     ffn_row_stats(acc, eps, rstd, nmr);
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+    for (int db = 0; db < DB; ++db) {
+      __builtin_amdgcn_sched_barrier(0);   // a column block at a time (register pressure)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const f32x4 gg = *reinterpret_cast<const f32x4*>(gs + db * 32 + 8 * g + 4 * h);
@@ -204,16 +230,19 @@ __global__ __launch_bounds__(FM_THREADS) void segment_ffn_mfma_kernel(
         bf16x4 o;
 #pragma unroll
         for (int e = 0; e < 4; ++e) o[e] = (__bf16)fmaf(fmaf(acc[db][4 * g + e], rstd, nmr), gg[e], bb[e]);
-        *reinterpret_cast<u32x2*>(opatch + l32 * OP + (db * 32 + g * 8 + h * 4) * 2) = __builtin_bit_cast(u32x2, o);
+        u32x2 bits = __builtin_bit_cast(u32x2, o);
+        if (!ok) bits = u32x2{0u, 0u};
+        *reinterpret_cast<u32x2*>(opatch + l32 * OP + (db * 32 + g * 8 + h * 4) * 2) = bits;
       }
+    }
     // ---- rows leave as whole 256-byte rows (LDS operations of a wave execute in order: no barrier needed)
 #pragma unroll
     for (int b = 0; b < FM_ROWS / RPI; ++b) {
       const int rr = b * RPI + lane / LPR;
-      u32x4 val = *reinterpret_cast<const u32x4*>(opr + b * RPI * OP);
-      if (!rowok[wave][rr]) val = u32x4{0u, 0u, 0u, 0u};
+      const u32x4 val = *reinterpret_cast<const u32x4*>(opr + b * RPI * OP);
       if (r0 + rr < rows) *reinterpret_cast<u32x4*>(out + (size_t)(r0 + rr) * D + (lane % LPR) * 8) = val;
     }
+    ok = nxt.first < nxt.len;
   }
 }
 
