@@ -24,6 +24,7 @@
 namespace laser {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -808,61 +809,88 @@ __global__ __launch_bounds__(GT_THREADS) void gsta_one_kernel(const unsigned sho
         }
       }
     }
-    float rs[8];
+    // r of the pair, this lane's eight components, as two bf16 pairs per two components: r = hi + lo up to 2^-17 of
+    // its size, so that a score is two dot products of packed pairs (v_dot2c_f32_bf16) per stored word instead of
+    // two conversions and two multiply-adds
+    bf16x2 rhi[4], rlo[4];
     {
       const f32x4 a = *reinterpret_cast<const f32x4*>(bufA + pi * FP + gl * 8);
       const f32x4 b = *reinterpret_cast<const f32x4*>(bufA + pi * FP + gl * 8 + 4);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) { rs[e] = a[e]; rs[4 + e] = b[e]; }
+      for (int e = 0; e < 4; ++e) {
+        const float r0 = e < 2 ? a[2 * e] : b[2 * e - 4], r1 = e < 2 ? a[2 * e + 1] : b[2 * e - 3];
+        rhi[e] = bf16x2{(__bf16)r0, (__bf16)r1};
+        rlo[e] = bf16x2{(__bf16)(r0 - (float)rhi[e][0]), (__bf16)(r1 - (float)rhi[e][1])};
+      }
     }
-    // Two passes over the register-resident block instead of a running maximum: the rows' scores are independent
-    // of each other (eight dot products in flight instead of one chain of dependent rescalings), and the weighted
-    // sum then needs no rescaling. Rows of empty segments count as zeros whatever they hold.
-    float sd[ROWS];
+    // Rows of empty segments count as zeros whatever they hold: replaced once, for both passes
+    // (words kept as scalars: cast to a bf16 pair straight out of a four-word vector, the compiler's lowering picked
+    // the vector's first word for all four)
+    unsigned int hs[ROWS][4];
 #pragma unroll
     for (int j = 0; j < ROWS; ++j) {
       const bool ok = (j * RPW + grp) < nv;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) hs[j][e] = ok ? hcur[j][e] : 0u;
+    }
+    // Two passes over the register-resident block instead of a running maximum: the rows' scores are independent
+    // of each other (eight dot products in flight instead of one chain of dependent rescalings), and the weighted
+    // sum then needs no rescaling: the maximum is taken over the whole pair (the four lane groups hold their own in
+    // all their lanes: four scalar reads) before the second pass.
+    float sd[ROWS];
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j) {
       float sdot = 0.0f;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const unsigned int pk = ok ? hcur[j][e] : 0u;
-        sdot = fmaf(__uint_as_float(pk << 16), rs[2 * e], sdot);
-        sdot = fmaf(__uint_as_float(pk & 0xffff0000u), rs[2 * e + 1], sdot);
+        const bf16x2 x = __builtin_bit_cast(bf16x2, hs[j][e]);
+        sdot = __builtin_amdgcn_fdot2_f32_bf16(x, rhi[e], sdot, false);
+        sdot = __builtin_amdgcn_fdot2_f32_bf16(x, rlo[e], sdot, false);
       }
       sdot = row_sum<LPR>(sdot);
-      sd[j] = ok ? sdot : -INFINITY;
+      sd[j] = (j * RPW + grp) < nv ? sdot : -INFINITY;
     }
     float m = sd[0];
 #pragma unroll
     for (int j = 1; j < ROWS; ++j) m = fmaxf(m, sd[j]);
-    const float mref = (m == -INFINITY) ? 0.0f : m;   // no valid row in this lane group
+    if constexpr (LPR == 16) {
+      const int mb = __float_as_int(m);
+      m = fmaxf(fmaxf(__int_as_float(__builtin_amdgcn_readlane(mb, 0)), __int_as_float(__builtin_amdgcn_readlane(mb, 16))),
+                fmaxf(__int_as_float(__builtin_amdgcn_readlane(mb, 32)), __int_as_float(__builtin_amdgcn_readlane(mb, 48))));
+    } else {
+#pragma unroll
+      for (int off = LPR; off < 64; off <<= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+    }
+    const float mref = (m == -INFINITY) ? 0.0f : m;   // no valid row in this pair
     float den = 0.0f;
     float pacc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) pacc[e] = 0.0f;
 #pragma unroll
     for (int j = 0; j < ROWS; ++j) {
-      const bool ok = (j * RPW + grp) < nv;
-      const float a = ok ? __expf(sd[j] - mref) : 0.0f;
+      const float a = __expf(sd[j] - mref);   // 0 for the rows of empty segments (their score is -inf)
       den += a;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const unsigned int pk = ok ? hcur[j][e] : 0u;
+        const unsigned int pk = hs[j][e];
         pacc[2 * e] = fmaf(a, __uint_as_float(pk << 16), pacc[2 * e]);
         pacc[2 * e + 1] = fmaf(a, __uint_as_float(pk & 0xffff0000u), pacc[2 * e + 1]);
       }
     }
+    // sums over the lane groups (the same reference in all of them: plain additions), the upper half first
+    // (lane ^ 32 by v_permlane32_swap, no LDS round trip)
+    auto add_other = [&](float x, int off) {
+      if (off == 32) {
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+        return __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+      }
+      return x + __shfl_xor(x, off, 64);
+    };
 #pragma unroll
-    for (int off = LPR; off < 64; off <<= 1) {
-      const float m_o = __shfl_xor(m, off, 64);
-      const float den_o = __shfl_xor(den, off, 64);
-      const float M2 = fmaxf(m, m_o);
-      const float f = (m == M2) ? 1.0f : __expf(m - M2);
-      const float f_o = (m_o == M2) ? 1.0f : __expf(m_o - M2);
-      den = den * f + den_o * f_o;
+    for (int off = 32; off >= LPR; off >>= 1) {
+      den = add_other(den, off);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) pacc[e] = pacc[e] * f + __shfl_xor(pacc[e], off, 64) * f_o;
-      m = M2;
+      for (int e = 0; e < 8; ++e) pacc[e] = add_other(pacc[e], off);
     }
     if (grp == 0) {
       const float inv = nv > 0 ? 1.0f / den : 0.0f;
