@@ -57,9 +57,19 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 
 template <int D> struct WPitch { static constexpr int v = (D * 2) % 256 == 64 ? D * 2 : D * 2 + 64; };
 
-// [32 x D] (LDS, fp32, pitch FP) times W^T with W bf16 [D][D] in global memory -> 32 x 32 block `nb`:
-// out[p][n] = sum_k X[p][k] W[n][k]. The B operand (k contiguous per lane) is one 16-byte load per step.
-// same product with the B operands already in registers (loaded early by the caller)
+// B operand of X.W^T: lane n needs W[n][k] for 8 consecutive k: one 16-byte load per k-step
+template <int D>
+__device__ __forceinline__ void load_b_rows(const unsigned short* __restrict__ W, int nb, int l32, int h,
+                                            bf16x8 (&b)[D / 16]) {
+  const int n = nb * 32 + l32;
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks)
+    b[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(W + (size_t)n * D + ks * 16 + h * 8));
+}
+
+// [32 x D] (LDS, fp32, pitch FP) times W^T with W bf16 [D][D] -> a 32 x 32 block: out[p][n] = sum_k X[p][k] W[n][k],
+// with the B operands (k contiguous per lane: one 16-byte load per step, load_b_rows) already in registers,
+// requested early by the caller
 template <int D>
 __device__ __forceinline__ f32x16 tile_gemm_breg(const float* X, int FP, const bf16x8 (&b)[D / 16], int l32, int h) {
   f32x16 acc;
@@ -70,24 +80,6 @@ __device__ __forceinline__ f32x16 tile_gemm_breg(const float* X, int FP, const b
     const HiLo a = split8(X + l32 * FP + ks * 16 + h * 8);
     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.hi, b[ks], acc, 0, 0, 0);
     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.lo, b[ks], acc, 0, 0, 0);
-  }
-  return acc;
-}
-
-template <int D>
-__device__ __forceinline__ f32x16 tile_gemm_wt(const float* X, int FP, const unsigned short* __restrict__ W, int nb,
-                                               int l32, int h) {
-  f32x16 acc;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
-  const int n = nb * 32 + l32;
-  // partial unroll: a full unroll makes the scheduler hoist every operand load and costs ~100 registers
-#pragma unroll 2
-  for (int ks = 0; ks < D / 16; ++ks) {
-    const bf16x8 b = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(W + (size_t)n * D + ks * 16 + h * 8));
-    const HiLo a = split8(X + l32 * FP + ks * 16 + h * 8);
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.hi, b, acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.lo, b, acc, 0, 0, 0);
   }
   return acc;
 }
@@ -176,6 +168,10 @@ __global__ __launch_bounds__(GT_THREADS) void gsta_tiled_kernel(const unsigned s
 
   WStage<D> ws;
   ws.load(wq, tid);
+  // W_k of the layer as the B operand of step 2, straight from memory in operand order and a layer ahead: requested
+  // inside the product it put a round trip to L2 into every layer's chain
+  bf16x8 bk[D / 16];
+  if (wave < DB) load_b_rows<D>(wk, wave, l32, h, bk);
 
   // valid segments of the wave's pairs (independent loads, one round trip)
   int nvs[PPW];
@@ -212,7 +208,6 @@ __global__ __launch_bounds__(GT_THREADS) void gsta_tiled_kernel(const unsigned s
   }
 
   for (int layer = 0; layer < M; ++layer) {
-    const unsigned short* Wk = wk + (size_t)layer * D * D;
     const unsigned short* Wv = wv + (size_t)layer * D * D;
 
     ws.store(Wl, tid);                                 // W_q of this layer
@@ -225,8 +220,9 @@ __global__ __launch_bounds__(GT_THREADS) void gsta_tiled_kernel(const unsigned s
     __syncthreads();
     ws.load(Wv, tid);                                  // W_v: in flight during step 2, W_q is no longer needed
     if (wave < DB) {                                   // step 2: r = q' W_k^T / sqrt(d)
-      const f32x16 rr = tile_gemm_wt<D>(bufB, FP, Wk, wave, l32, h);
+      const f32x16 rr = tile_gemm_breg<D>(bufB, FP, bk, l32, h);
       store_acc(bufA, FP, rr, wave, l32, h, scale);
+      if (layer + 1 < M) load_b_rows<D>(wk + (size_t)(layer + 1) * D * D, wave, l32, h, bk);
     }
     ws.store(Wl, tid);
     __syncthreads();
@@ -355,16 +351,6 @@ __device__ __forceinline__ void load_b_cols(const unsigned short* __restrict__ W
   for (int ks = 0; ks < D / 16; ++ks)
 #pragma unroll
     for (int i = 0; i < 8; ++i) b[ks][i] = __builtin_bit_cast(__bf16, W[(size_t)(ks * 16 + h * 8 + i) * D + n]);
-}
-
-// B operand of X.W^T: lane n needs W[n][k] for 8 consecutive k: one 16-byte load per k-step
-template <int D>
-__device__ __forceinline__ void load_b_rows(const unsigned short* __restrict__ W, int nb, int l32, int h,
-                                            bf16x8 (&b)[D / 16]) {
-  const int n = nb * 32 + l32;
-#pragma unroll
-  for (int ks = 0; ks < D / 16; ++ks)
-    b[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(W + (size_t)n * D + ks * 16 + h * 8));
 }
 
 template <int D>
