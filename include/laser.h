@@ -278,6 +278,21 @@ laser_status laser_ffn_gsta_forward(const void* seg, const void* t0, const void*
                                     void* stream);
 
 /*
+ * laser_ffn_gsta_forward with the two other views of Sec. 3.4.4 taken from the transformed rows s (the complete head
+ * on a stored H'): pool_out [U,C,d] dt, recent_out [U,C,r,d] dt and r as for laser_multires_forward, everything else
+ * as for laser_ffn_gsta_forward, everything validated before the first launch. Where that entry point makes one pass
+ * over H' the views come from the same pass; otherwise laser_segment_ffn_forward into seg_out (required then), then
+ * laser_gsta_forward_multires on it. z_out, pool_out and recent_out agree with those two calls in a row: the views
+ * bit for bit, z_out up to the order of fp32 sums.
+ */
+laser_status laser_ffn_gsta_forward_multires(const void* seg, const void* t0, const void* wq, const void* wk,
+                                             const void* wv, const int32_t* lens, const void* w1, const float* b1,
+                                             const void* w2, const float* b2, const float* ln_g, const float* ln_b,
+                                             int U, int C, int L, int d, int d_ff, int w, int M, float eps,
+                                             laser_dtype dt, void* seg_out, float* z_out, int r, void* pool_out,
+                                             void* recent_out, void* stream);
+
+/*
  * Multi-resolution feature fusion (paper Sec. 3.4.4): besides the global context z, the representation holds
  * max_pool(H') and the r most recent segments s_1 .. s_r. Both are taken from a stored H':
  *   pool_out   [U,C,d]   dt   component-wise maximum over the segment vectors of the pair that hold at least one

@@ -26,7 +26,7 @@ EXPORTS = [
     "laser_segment_ffn_forward_ragged", "laser_gsta_forward", "laser_gsta_forward_variant",
     "laser_forward", "laser_forward_fused", "laser_forward_fused_work_bytes", "laser_multires_forward", "laser_forward_multires", "laser_gsta_forward_multires",
     "laser_sta_kernel_name",
-    "laser_gsta_kernel_name", "laser_segment_ffn_forward", "laser_segment_ffn_forward_variant", "laser_ffn_gsta_forward",
+    "laser_gsta_kernel_name", "laser_segment_ffn_forward", "laser_segment_ffn_forward_variant", "laser_ffn_gsta_forward", "laser_ffn_gsta_forward_multires",
     "laser_gsta_kernel_name_layers", "laser_project_q_forward", "laser_project_q_forward_variant",
     "laser_project_kv_forward", "laser_project_kv_forward_variant", "laser_fold_query_weights",
     "laser_project_heads_forward", "laser_sta_folded_forward", "laser_sta_backward", "laser_sta_backward_bf16", "laser_sta_backward_static", "laser_sta_backward_work_bytes", "laser_gsta_backward",
@@ -87,6 +87,8 @@ def load_library() -> ctypes.CDLL:
     lib.laser_ffn_gsta_forward.argtypes = [vp, vp, vp, vp, vp, ip, vp, fp, vp, fp, fp, fp, i32, i32, i32, i32, i32, i32,
                                            i32, f32, i32, vp, vp, vp]
     lib.laser_ffn_gsta_forward.restype = i32
+    lib.laser_ffn_gsta_forward_multires.argtypes = lib.laser_ffn_gsta_forward.argtypes[:-1] + [i32, vp, vp, vp]
+    lib.laser_ffn_gsta_forward_multires.restype = i32
     lib.laser_project_q_forward.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp]
     lib.laser_project_q_forward_variant.argtypes = lib.laser_project_q_forward.argtypes + [i32]
     lib.laser_project_kv_forward.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp]
@@ -604,9 +606,11 @@ def laser_gsta_forward_multires(seg, t0, wq, wk, wv, lens, L: int, w: int, r: in
 
 
 def laser_ffn_gsta_forward(seg, t0, wq, wk, wv, lens, w1, b1, w2, b2, ln_g, ln_b, L: int, w: int, eps: float = 1e-5,
-                           seg_out=None, z_out=None, stream=None, want_seg: bool = True):
+                           seg_out=None, z_out=None, stream=None, want_seg: bool = True, r: Optional[int] = None,
+                           pool_out=None, recent_out=None):
     """seg [U,C,S,d] -> (s = LN(FFN(seg) + seg) [U,C,S,d] or None, z = GSTA(t0; s) [U,C,d] fp32). want_seg=False
-    passes a null seg_out (s is not written); seg_out may be seg itself."""
+    passes a null seg_out (s is not written); seg_out may be seg itself. With r (an int >= 0) the call is
+    laser_ffn_gsta_forward_multires and returns (s or None, z, pool [U,C,d], recent [U,C,r,d] or None)."""
     torch = _torch()
     U, C, S, d = seg.shape
     d_ff = w1.shape[1]
@@ -625,6 +629,20 @@ def laser_ffn_gsta_forward(seg, t0, wq, wk, wv, lens, w1, b1, w2, b2, ln_g, ln_b
         seg_out = torch.empty_like(seg)
     if z_out is None:
         z_out = torch.empty((U, C, d), dtype=torch.float32, device=seg.device)
+    if r is not None:
+        if pool_out is None:
+            pool_out = torch.empty((U, C, d), dtype=seg.dtype, device=seg.device)
+        if recent_out is None and r > 0:
+            recent_out = torch.empty((U, C, r, d), dtype=seg.dtype, device=seg.device)
+        code = load_library().laser_ffn_gsta_forward_multires(
+            _ptr(seg, "seg"), _ptr(t0, "t0"), _ptr(wq, "wq"), _ptr(wk, "wk"), _ptr(wv, "wv"),
+            _ptr(lens, "lens", torch.int32), _ptr(w1, "w1"), _ptr(b1, "b1", torch.float32), _ptr(w2, "w2"),
+            _ptr(b2, "b2", torch.float32), _ptr(ln_g, "ln_g", torch.float32), _ptr(ln_b, "ln_b", torch.float32), U, C,
+            int(L), d, d_ff, int(w), M, float(eps), _dt(seg), _ptr(seg_out, "seg_out", seg.dtype),
+            _ptr(z_out, "z_out", torch.float32), int(r), _ptr(pool_out, "pool_out", seg.dtype),
+            _ptr(recent_out, "recent_out", seg.dtype), _stream(stream))
+        _check(code, "laser_ffn_gsta_forward_multires")
+        return seg_out, z_out, pool_out, recent_out
     code = load_library().laser_ffn_gsta_forward(
         _ptr(seg, "seg"), _ptr(t0, "t0"), _ptr(wq, "wq"), _ptr(wk, "wk"), _ptr(wv, "wv"),
         _ptr(lens, "lens", torch.int32), _ptr(w1, "w1"), _ptr(b1, "b1", torch.float32), _ptr(w2, "w2"),

@@ -26,14 +26,19 @@
 
 namespace laser {
 
-template <int DFF>
+// MR: also the two other views of Sec. 3.4.4 of the transformed rows: pool [P, D] bf16, the component-wise maximum
+// over the segments that hold a valid item (zeros when there is none), taken in the weighted-sum loop from the same
+// words (rows past the last valid segment are copies of it, so they leave the maximum alone); recent [P, r, D] bf16,
+// the first r rows as they would be stored. Either may be null.
+template <int DFF, bool MR>
 __global__ __launch_bounds__(FM_THREADS) void ffn_pool_kernel(
     const unsigned short* seg, const int32_t* __restrict__ lens, const unsigned short* __restrict__ w1,
     const float* __restrict__ b1, const unsigned short* __restrict__ w2, const float* __restrict__ b2,
     const float* __restrict__ ln_g, const float* __restrict__ ln_b, const int32_t* __restrict__ cand_off, int U, int P,
     int C, int L, int w, int S, float eps,
     unsigned short* out,   // s rows [P, S, D], may be null (not wanted), may be seg
-    float* z) {            // [P, D]: r on entry, p on exit
+    float* z,              // [P, D]: r on entry, p on exit
+    unsigned* pool, unsigned short* recent, int r) {
   constexpr int D = FM_D, KSTEPS = D / 16, DB = D / 32, OP = FM_OP;
   constexpr int RVB = 1024;   // bytes per copy of r: the 512 bytes twice (a fetch moves 16 bytes per lane, 64 lanes)
   __shared__ __attribute__((aligned(1024))) unsigned char W1L[FM_W1B];
@@ -89,7 +94,10 @@ __global__ __launch_bounds__(FM_THREADS) void ffn_pool_kernel(
     const int nvn = prn < P ? valid_segments(prn) : 0;
     unsigned short* O = out ? out + (size_t)pr * S * D : nullptr;
     const float* rw = reinterpret_cast<const float*>(rmine + rb * RVB);
+    unsigned short* R = (MR && recent) ? recent + (size_t)pr * r * D : nullptr;
+    const int nr = R ? r : 0;
     float m = -INFINITY, den = 0.0f, p0 = 0.0f, p1 = 0.0f;
+    float mx0 = -INFINITY, mx1 = -INFINITY;
     for (int i0 = 0; i0 < nv; i0 += FM_ROWS) {
       // the next tile with a valid segment: of this pair, else the first of the next pair (with its r)
       const bool same = i0 + FM_ROWS < nv;
@@ -162,6 +170,10 @@ __global__ __launch_bounds__(FM_THREADS) void ffn_pool_kernel(
         const unsigned wd = *reinterpret_cast<const unsigned*>(pcol + row * OP);
         p0 = fmaf(ar, __uint_as_float(wd << 16), p0);
         p1 = fmaf(ar, __uint_as_float(wd & 0xffff0000u), p1);
+        if (MR) {
+          mx0 = fmaxf(mx0, __uint_as_float(wd << 16));
+          mx1 = fmaxf(mx1, __uint_as_float(wd & 0xffff0000u));
+        }
       }
       if (O) {   // rows leave as whole 256-byte rows (LDS operations of a wave execute in order: no barrier needed)
 #pragma unroll
@@ -172,6 +184,27 @@ __global__ __launch_bounds__(FM_THREADS) void ffn_pool_kernel(
           if (ii < S) *reinterpret_cast<u32x4*>(O + (size_t)ii * D + (lane % LPR) * 8) = val;
         }
       }
+      if (MR && i0 < nr) {   // the same rows into the most recent segments' view
+#pragma unroll
+        for (int b = 0; b < FM_ROWS / RPI; ++b) {
+          const int ii = i0 + b * RPI + lane / LPR;
+          u32x4 val = *reinterpret_cast<const u32x4*>(opr + b * RPI * OP);
+          if (ii >= nv) val = u32x4{0u, 0u, 0u, 0u};
+          if (ii < nr) *reinterpret_cast<u32x4*>(R + (size_t)ii * D + (lane % LPR) * 8) = val;
+        }
+      }
+    }
+    if (MR && nr > 0) {   // its rows in the tiles without a valid segment: zeros
+      for (int i0 = ((nv + FM_ROWS - 1) / FM_ROWS) * FM_ROWS; i0 < nr; i0 += FM_ROWS) {
+#pragma unroll
+        for (int b = 0; b < FM_ROWS / RPI; ++b) {
+          const int ii = i0 + b * RPI + lane / LPR;
+          if (ii < nr) *reinterpret_cast<u32x4*>(R + (size_t)ii * D + (lane % LPR) * 8) = u32x4{0u, 0u, 0u, 0u};
+        }
+      }
+    }
+    if (MR && pool) {   // maxima of stored values: their bits pass through
+      pool[(size_t)pr * (D / 2) + lane] = nv > 0 ? ((__float_as_uint(mx0) >> 16) | (__float_as_uint(mx1) & 0xffff0000u)) : 0u;
     }
     if (O) {   // the rows of the tiles without a valid segment: zeros
       for (int i0 = ((nv + FM_ROWS - 1) / FM_ROWS) * FM_ROWS; i0 < S; i0 += FM_ROWS) {
@@ -195,6 +228,7 @@ __global__ __launch_bounds__(FM_THREADS) void ffn_pool_kernel(
   }
 }
 
+// (the views come from the same pass: g.pool_out, g.recent_out and g.r as for the GSTA launchers)
 bool ffn_gsta_fused_supports(const FfnArgs& f, const GstaArgs& g) {
   if (f.dt != LASER_BF16 || g.dt != LASER_BF16) return false;
   if (f.d != 128 || g.d != 128 || !(f.d_ff == 64 || f.d_ff == 128)) return false;
@@ -208,13 +242,14 @@ laser_status ffn_gsta_fused_launch(const FfnArgs& f, const GstaArgs& g) {
   const int P = f.cand_off ? f.P : f.U * f.C;
   long long blocks = ((long long)P + FM_WAVES - 1) / FM_WAVES;
   if (blocks > 256) blocks = 256;   // one workgroup per compute unit (LDS), each wave walking several pairs
-#define LASER_FFN_POOL(FF)                                                                                            \
-  hipLaunchKernelGGL((ffn_pool_kernel<FF>), dim3((unsigned)blocks), dim3(FM_THREADS), 0, f.stream,                    \
+  const bool views = g.pool_out != nullptr || g.recent_out != nullptr;
+#define LASER_FFN_POOL(FF, MRF)                                                                                       \
+  hipLaunchKernelGGL((ffn_pool_kernel<FF, MRF>), dim3((unsigned)blocks), dim3(FM_THREADS), 0, f.stream,               \
                      (const unsigned short*)f.seg, f.lens, (const unsigned short*)f.w1, f.b1,                        \
                      (const unsigned short*)f.w2, f.b2, f.ln_g, f.ln_b, f.cand_off, f.U, P, f.C, f.L, f.w, f.S, f.eps, \
-                     (unsigned short*)f.seg_out, g.z_out)
-  if (f.d_ff == 64) LASER_FFN_POOL(64);
-  else LASER_FFN_POOL(128);
+                     (unsigned short*)f.seg_out, g.z_out, (unsigned*)g.pool_out, (unsigned short*)g.recent_out, g.r)
+  if (f.d_ff == 64) { if (views) LASER_FFN_POOL(64, true); else LASER_FFN_POOL(64, false); }
+  else { if (views) LASER_FFN_POOL(128, true); else LASER_FFN_POOL(128, false); }
 #undef LASER_FFN_POOL
   s = launch_status();
   if (s != LASER_OK) return s;

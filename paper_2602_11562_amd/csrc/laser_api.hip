@@ -465,6 +465,36 @@ laser_status laser_ffn_gsta_forward(const void* seg, const void* t0, const void*
   return run_gsta(ga, LASER_GSTA_AUTO);
 }
 
+laser_status laser_ffn_gsta_forward_multires(const void* seg, const void* t0, const void* wq, const void* wk,
+                                             const void* wv, const int32_t* lens, const void* w1, const float* b1,
+                                             const void* w2, const float* b2, const float* ln_g, const float* ln_b,
+                                             int U, int C, int L, int d, int d_ff, int w, int M, float eps,
+                                             laser_dtype dt, void* seg_out, float* z_out, int r, void* pool_out,
+                                             void* recent_out, void* stream) {
+  FfnArgs fa;
+  GstaArgs ga;
+  MultiresArgs ma;
+  laser_status s = validate_ffn(seg, lens, w1, b1, w2, b2, ln_g, ln_b, U, C, L, d, d_ff, w, eps, dt, seg_out, stream,
+                                &fa, false);
+  if (s != LASER_OK) return s;
+  s = validate_gsta(seg, t0, wq, wk, wv, lens, U, C, L, d, w, M, dt, z_out, stream, &ga);
+  if (s != LASER_OK) return s;
+  s = validate_multires(seg, lens, U, C, L, d, w, r, dt, pool_out, recent_out, stream, &ma);
+  if (s != LASER_OK) return s;
+  if (ffn_gsta_fused_supports(fa, ga)) {
+    ga.pool_out = pool_out;
+    ga.recent_out = recent_out;
+    ga.r = r;
+    return ffn_gsta_fused_launch(fa, ga);
+  }
+  if (!seg_out) return LASER_ERR_UNSUPPORTED;
+  s = segment_ffn_mfma_supports(fa) ? segment_ffn_mfma_launch(fa) : segment_ffn_generic_launch(fa);
+  if (s != LASER_OK) return s;
+  ga.seg = seg_out;
+  ma.seg = seg_out;
+  return run_gsta_views(ga, ma);
+}
+
 laser_status laser_segment_ffn_forward(const void* seg, const int32_t* lens, const void* w1, const float* b1,
                                        const void* w2, const float* b2, const float* ln_g, const float* ln_b, int U,
                                        int C, int L, int d, int d_ff, int w, float eps, laser_dtype dt, void* seg_out,

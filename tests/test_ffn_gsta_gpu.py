@@ -137,6 +137,53 @@ def test_ffn_gsta_one_pass(name):
     assert torch.equal(s_c.view(torch.int16), s_out.view(torch.int16))
 
 
+@pytest.mark.parametrize("name", list(FUSED) + ["two_layers", "d64"])
+@pytest.mark.parametrize("r", [0, 1, 5, "all"])
+def test_ffn_gsta_with_views(name, r):
+    """laser_ffn_gsta_forward_multires: z as without the views (same bits), max-pool and the most recent rows equal to
+    those of laser_gsta_forward_multires on the stored transformed rows (bit for bit: copies and maxima of the same
+    stored values) and to the checker's views of its own rounded rows wherever those rows agree."""
+    import torch
+    table = FUSED if name in FUSED else UNFUSED
+    dtype, U, C, L, w, d, dff, M, lens, sharp = table[name]
+    cs = _case(dtype, U, C, L, w, d, dff, M, lens, seed=1000 + len(name) * 7 + d, sharp=sharp)
+    Hs, cnt = _poison_empty_rows(cs, dtype, L, w)
+    rr = cs["S"] if r == "all" else min(r, cs["S"])
+    print(f"case {name} r {rr}", flush=True)
+    seg = to_device(Hs)
+    dev = {k: to_device(cs[k]) for k in ("lens", "W1s", "b1", "W2s", "b2", "g", "b", "t0s", "wqs", "wks", "wvs")}
+    args = (dev["t0s"], dev["wqs"], dev["wks"], dev["wvs"], dev["lens"], dev["W1s"], dev["b1"], dev["W2s"], dev["b2"],
+            dev["g"], dev["b"], L, w, 1e-5)
+    s_a, z_a = laser.laser_ffn_gsta_forward(seg, *args)
+    s_b, z_b, pool, recent = laser.laser_ffn_gsta_forward(seg, *args, r=rr)
+    z2, pool2, recent2 = laser.laser_gsta_forward_multires(s_a, dev["t0s"], dev["wqs"], dev["wks"], dev["wvs"], dev["lens"],
+                                                           L, w, rr)
+    torch.cuda.synchronize()
+    assert torch.equal(z_a.view(torch.int32), z_b.view(torch.int32))
+    assert torch.equal(s_a.view(torch.int16), s_b.view(torch.int16))
+    assert torch.equal(pool.view(torch.int16), pool2.view(torch.int16))
+    if rr > 0:
+        assert torch.equal(recent.view(torch.int16), recent2.view(torch.int16))
+    else:
+        assert recent is None
+    # the checker's views of the stored rows (exact operations on stored values)
+    pool_ref, recent_ref = oracle.multires_forward(to_host_f64(s_a), cnt, rr)
+    assert np.array_equal(to_host_f64(pool), pool_ref)
+    if rr > 0:
+        assert np.array_equal(to_host_f64(recent), recent_ref)
+    if name in FUSED:   # rows not wanted: the views and z from the same pass, same bits
+        zp = torch.full_like(z_a, float("nan"))
+        none, z_c, pool_c, recent_c = laser.laser_ffn_gsta_forward(seg, *args, r=rr, want_seg=False, z_out=zp,
+                                                                   pool_out=torch.full_like(pool, float("nan")),
+                                                                   recent_out=None if rr == 0 else torch.full_like(recent, float("nan")))
+        torch.cuda.synchronize()
+        assert none is None
+        assert torch.equal(z_a.view(torch.int32), z_c.view(torch.int32))
+        assert torch.equal(pool.view(torch.int16), pool_c.view(torch.int16))
+        if rr > 0:
+            assert torch.equal(recent.view(torch.int16), recent_c.view(torch.int16))
+
+
 @pytest.mark.parametrize("name", list(UNFUSED))
 def test_ffn_gsta_two_launches_behind_the_same_entry_point(name):
     cs, seg, z, s_out, call = _run(name, UNFUSED)
