@@ -223,3 +223,19 @@ def test_ffn_gsta_full_size_high_fanout():
         worst = max(worst, vec_rel_err(zh[u:u + 1, c:c + 1], z_ref))
     print(f"full size against the checker (96 pairs): z {worst:.3e}", flush=True)
     assert worst <= 2e-2
+
+
+def test_ffn_gsta_without_lengths_and_with_a_single_pair():
+    """lens = NULL means every item is valid; one pair leaves seven waves of the workgroup without work."""
+    import torch
+    for (U, C, L, w, dff) in ((1, 1, 320, 8, 128), (2, 3, 96, 8, 64)):
+        cs = _case("bf16", U, C, L, w, 128, dff, 1, [L] * U, seed=31 + C)
+        cnt = oracle.segment_counts(cs["lens"], L, w)
+        s_ref = oracle.segment_ffn_forward(cs["Hv"], cnt, cs["W1v"], cs["b1"], cs["W2v"], cs["b2"], cs["g"], cs["b"], 1e-5)
+        z_ref = oracle.gsta_forward(_round_like_storage(s_ref, "bf16"), cs["t0v"], cs["wqv"], cs["wkv"], cs["wvv"], cnt)
+        dev = {k: to_device(cs[k]) for k in ("Hs", "W1s", "b1", "W2s", "b2", "g", "b", "t0s", "wqs", "wks", "wvs")}
+        s_out, z = laser.laser_ffn_gsta_forward(dev["Hs"], dev["t0s"], dev["wqs"], dev["wks"], dev["wvs"], None, dev["W1s"],
+                                                dev["b1"], dev["W2s"], dev["b2"], dev["g"], dev["b"], L, w, 1e-5)
+        torch.cuda.synchronize()
+        assert vec_rel_err(to_host_f64(s_out), s_ref) <= 2e-2
+        assert vec_rel_err(to_host_f64(z), z_ref) <= 2e-2
