@@ -239,3 +239,42 @@ def test_ffn_gsta_without_lengths_and_with_a_single_pair():
         torch.cuda.synchronize()
         assert vec_rel_err(to_host_f64(s_out), s_ref) <= 2e-2
         assert vec_rel_err(to_host_f64(z), z_ref) <= 2e-2
+
+
+def test_ffn_gsta_seeded_random_shapes():
+    """Twenty-four seeded shapes (users, candidates, segment counts from one tile's worth to several, ragged lengths with
+    empty histories, both hidden sizes, with and without the views): every z and every transformed row against the
+    checker, the views against the checker's views of the stored rows."""
+    import torch
+    rng = np.random.default_rng(20260211)
+    worst = 0.0
+    for case in range(24):
+        U, C = int(rng.integers(1, 5)), int(rng.integers(1, 41))
+        w = int(rng.choice([1, 3, 8, 10, 16]))
+        S = int(rng.choice([1, 2, 7, 31, 32, 33, 40, 64, 65, 100, 130]))
+        L = S * w - int(rng.integers(0, w))            # last segment short
+        dff = int(rng.choice([64, 128]))
+        lens = [int(x) for x in rng.integers(0, L + 1, size=U)]
+        if case % 5 == 0:
+            lens[0] = L
+        r = int(rng.integers(0, S + 1)) if case % 2 == 0 else None
+        print(f"case {case}: U {U} C {C} L {L} w {w} S {S} d_ff {dff} lens {lens} r {r}", flush=True)
+        cs = _case("bf16", U, C, L, w, 128, dff, 1, lens, seed=500 + case)
+        assert cs["S"] == S
+        Hs, cnt = _poison_empty_rows(cs, "bf16", L, w)
+        s_ref = oracle.segment_ffn_forward(cs["Hv"], cnt, cs["W1v"], cs["b1"], cs["W2v"], cs["b2"], cs["g"], cs["b"], 1e-5)
+        z_ref = oracle.gsta_forward(_round_like_storage(s_ref, "bf16"), cs["t0v"], cs["wqv"], cs["wkv"], cs["wvv"], cnt)
+        dev = {k: to_device(cs[k]) for k in ("lens", "W1s", "b1", "W2s", "b2", "g", "b", "t0s", "wqs", "wks", "wvs")}
+        out = laser.laser_ffn_gsta_forward(to_device(Hs), dev["t0s"], dev["wqs"], dev["wks"], dev["wvs"], dev["lens"],
+                                           dev["W1s"], dev["b1"], dev["W2s"], dev["b2"], dev["g"], dev["b"], L, w, 1e-5, r=r)
+        torch.cuda.synchronize()
+        s_out, z = out[0], out[1]
+        err_s, err_z = vec_rel_err(to_host_f64(s_out), s_ref), vec_rel_err(to_host_f64(z), z_ref)
+        worst = max(worst, err_s, err_z)
+        assert err_s <= 2e-2 and err_z <= 2e-2, (case, err_s, err_z)
+        if r is not None:
+            pool_ref, recent_ref = oracle.multires_forward(to_host_f64(s_out), cnt, r)
+            assert np.array_equal(to_host_f64(out[2]), pool_ref), case
+            if r > 0:
+                assert np.array_equal(to_host_f64(out[3]), recent_ref), case
+    print(f"worst vector-relative error {worst:.3e}", flush=True)
