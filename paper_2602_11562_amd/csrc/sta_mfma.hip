@@ -868,23 +868,23 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
     for (int ks = 1; ks < KSTEPS; ++ks) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[ks], sc, 0, 0, 0);
     return sc;
   };
-  f32x16 sc_cur;
+  f32x16 scA, scB;   // scores of the tile in work and of the next one: the two swap roles every step (no copy)
   u32x4 p0, p1;   // gates of items 0..15 / 16..31 of the current tile, rounded to bf16 pairs: B operands of the
                   // aggregation
   if (any) {
-    sc_cur = scores();
+    scA = scores();
     read_k(1);
     // gates of items 0..15 of the first tile, up to the rounding of the last pair (done by the first slot of
     // the loop, as for every later tile)
 #pragma unroll
-    for (int i = 0; i < 8; ++i) sc_cur[i] = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(sc_cur[i] * neg_scale_log2e));
+    for (int i = 0; i < 8; ++i) scA[i] = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(scA[i] * neg_scale_log2e));
 #pragma unroll
     for (int j = 0; j < 3; ++j) {
-      const bf16x2 c = {(__bf16)sc_cur[2 * j], (__bf16)sc_cur[2 * j + 1]};
+      const bf16x2 c = {(__bf16)scA[2 * j], (__bf16)scA[2 * j + 1]};
       p0[j] = __builtin_bit_cast(unsigned, c);
     }
   }
-  while (cur.seg < seg_ne) {
+  auto step = [&](f32x16& sc_cur, f32x16& sc_nxt) __attribute__((always_inline)) {
     const Cur nxt = advance(cur);
     const bool has_next = nxt.seg < seg_ne;
     const bool has_next2 = has_next && advance(nxt).seg < seg_ne;
@@ -906,7 +906,6 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
     // an exp2 or reciprocal. Nothing may be moved across the slot borders. After the last tile the score MFMAs run
     // on whatever the K registers hold and their result is dropped; in a partial tile the gates of the rows past
     // the end (copies of the last valid row) are cleared after rounding.
-    f32x16 sc_nxt;
     const int nvt = cur.hi - cur.t0;
     const bool first = cur.t0 == cur.seg * w;
     auto clear_past_end = [&](u32x4& bits, int half) {
@@ -1008,7 +1007,11 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
     ++done;
     cbuf = nbuf;
     cur = nxt;
-    if (has_next) sc_cur = sc_nxt;
+  };
+  while (cur.seg < seg_ne) {
+    step(scA, scB);
+    if (cur.seg >= seg_ne) break;
+    step(scB, scA);
   }
   if (out_seg >= 0) flush_units(out_seg, out_units, FU - out_units);
 
