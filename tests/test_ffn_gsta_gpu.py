@@ -76,6 +76,11 @@ FUSED = {
     "one_segment": ("bf16", 2, 70, 64, 64, 128, 64, 1, [64, 1], 1.0),                            # S = 1
     "sharp_softmax": ("bf16", 2, 19, 1024, 16, 128, 128, 1, [1024, 700], 40.0),                  # S = 64, peaked weights
     "many_pairs": ("bf16", 9, 257, 256, 32, 128, 128, 1, [256, 1, 256, 33, 200, 64, 0, 255, 97], 1.0),  # every wave walks pairs
+    # more than 2048 pairs: a wave walks several, and its tiles of 32 rows hold the last rows of one pair and the
+    # first of the next (S = 5: two whole pairs; S = 20: 20 + 12, 8 + 20, ...; S = 100: 96 + 4 | 28 + ...)
+    "packed_tiles_5": ("bf16", 6, 800, 60, 12, 128, 128, 1, [60, 13, 60, 0, 35, 59], 1.0),
+    "packed_tiles_20": ("bf16", 5, 1000, 200, 10, 128, 64, 1, [200, 200, 95, 0, 151], 1.0),
+    "packed_tiles_100": ("bf16", 3, 750, 1000, 10, 128, 128, 1, [1000, 1000, 637], 1.0),
 }
 UNFUSED = {
     "f32": ("f32", 2, 7, 512, 64, 64, 128, 1, [512, 65], 1.0),
@@ -278,3 +283,43 @@ def test_ffn_gsta_seeded_random_shapes():
             if r > 0:
                 assert np.array_equal(to_host_f64(out[3]), recent_ref), case
     print(f"worst vector-relative error {worst:.3e}", flush=True)
+
+
+def test_ffn_gsta_seeded_random_shapes_many_pairs():
+    """Eight seeded shapes with several thousand pairs, so that every wave walks two to five of them and packs their
+    valid rows into shared tiles (pairs of different users, hence of different valid lengths, meet in a tile): z, the
+    transformed rows and the views against the checker."""
+    import torch
+    rng = np.random.default_rng(20260212)
+    for case in range(8):
+        U = int(rng.integers(2, 7))
+        C = int(rng.integers(2100 // U + 1, 6000 // U))
+        w = int(rng.choice([4, 10]))
+        S = int(rng.choice([3, 7, 16, 20, 33, 50]))
+        L = S * w - int(rng.integers(0, w))
+        dff = int(rng.choice([64, 128]))
+        lens = [int(x) for x in rng.integers(0, L + 1, size=U)]
+        lens[case % U] = L
+        r = int(rng.integers(0, S + 1)) if case % 2 == 0 else None
+        print(f"case {case}: U {U} C {C} L {L} w {w} S {S} d_ff {dff} lens {lens} r {r}", flush=True)
+        cs = _case("bf16", U, C, L, w, 128, dff, 1, lens, seed=900 + case)
+        Hs, cnt = _poison_empty_rows(cs, "bf16", L, w)
+        s_ref = oracle.segment_ffn_forward(cs["Hv"], cnt, cs["W1v"], cs["b1"], cs["W2v"], cs["b2"], cs["g"], cs["b"], 1e-5)
+        z_ref = oracle.gsta_forward(_round_like_storage(s_ref, "bf16"), cs["t0v"], cs["wqv"], cs["wkv"], cs["wvv"], cnt)
+        dev = {k: to_device(cs[k]) for k in ("lens", "W1s", "b1", "W2s", "b2", "g", "b", "t0s", "wqs", "wks", "wvs")}
+        out = laser.laser_ffn_gsta_forward(to_device(Hs), dev["t0s"], dev["wqs"], dev["wks"], dev["wvs"], dev["lens"],
+                                           dev["W1s"], dev["b1"], dev["W2s"], dev["b2"], dev["g"], dev["b"], L, w, 1e-5, r=r)
+        torch.cuda.synchronize()
+        s_out, z = out[0], out[1]
+        err_s, err_z = vec_rel_err(to_host_f64(s_out), s_ref), vec_rel_err(to_host_f64(z), z_ref)
+        assert err_s <= 2e-2 and err_z <= 2e-2, (case, err_s, err_z)
+        # every pair on its own as well: a vector-relative error over the whole batch would hide one wrong pair
+        zh = to_host_f64(z).reshape(-1, 128)
+        zr = np.asarray(z_ref).reshape(-1, 128)
+        per_pair = np.linalg.norm(zh - zr, axis=1) / np.maximum(np.linalg.norm(zr, axis=1), 1e-30)
+        assert per_pair.max() <= 2e-2, (case, int(per_pair.argmax()), float(per_pair.max()))
+        if r is not None:
+            pool_ref, recent_ref = oracle.multires_forward(to_host_f64(s_out), cnt, r)
+            assert np.array_equal(to_host_f64(out[2]), pool_ref), case
+            if r > 0:
+                assert np.array_equal(to_host_f64(out[3]), recent_ref), case
