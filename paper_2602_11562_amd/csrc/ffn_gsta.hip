@@ -5,23 +5,24 @@
 //
 // Three launches, the outer two shared with the split form of GSTA (gsta_tiled.hip):
 //   gsta_r_kernel     r = (t0 W_q) W_k^T / sqrt(d)   tiles of 32 pairs, MFMA                       -> z rows
-//   ffn_pool_kernel   below: a wave per pair          H' rows -> s rows (on chip), z rows (r) -> z rows (p)
+//   ffn_pool_kernel   below: a wave walks pairs       H' rows -> s rows (on chip), z rows (r) -> z rows (p)
 //   gsta_out_kernel   z = t0 + p W_v                  tiles of 32 pairs, MFMA             z rows -> z rows
 // with p = sum_i a_i s_i, a = softmax over the segments that hold a valid item of r . s_i (the attention equation
 // with its products re-associated, which is exact).
 //
-// ffn_pool_kernel: the FFN tile of segment_ffn_tile.h on the rows of one pair at a time (tiles of 32 rows over the
-// pair's first nv segments, the ones that hold a valid item; rows past them repeat the last one and count as empty;
-// the rows of the remaining segments are never read). A wave walks pairs with a grid stride; the rows of its next
-// tile, of this pair or the next, and the next pair's r are in flight while it multiplies. After LayerNorm a lane
-// holds, in the accumulator layout, 64 of the 128 components of row l32: the rounded values (what a stored s would
-// hold) are multiplied with the same components of r, read from a wave-private LDS copy, and one exchange with
-// lane ^ 32 gives the row's score. Maximum and sum over the tile's rows are wave reductions; tiles of a pair are
-// merged with the running maximum (online softmax). The weighted sum over rows is taken from the LDS patch the
-// rounded rows are parked in: lane l owns components 2 l and 2 l + 1 and reads one word per row, with the row's
-// weight from v_readlane. Rows of segments without a valid item are never read (whatever H' holds there is not
-// trusted): inside a tile they are copies of the last valid row with weight zero, and they leave as zeros.
-// p / sum of weights replaces r in the pair's z row.
+// ffn_pool_kernel: the FFN tile of segment_ffn_tile.h on the valid rows (the first nv segments, the ones that hold a
+// valid item) of the pairs a wave walks with a grid stride, one pair after the other, cut into tiles of 32 as one
+// stream: a tile holds rows of one pair, or the last rows of one followed by the first of the next, so that only the
+// wave's last tile is padded (with copies of its last row, which count as empty). The rows of the remaining segments
+// are never read (whatever H' holds there is not trusted): they, and the results of a pair without any valid
+// segment, are written by a pass of their own before the first tile. The rows of the wave's next tile and r of the
+// pairs that start in it are in flight while it multiplies. After LayerNorm a lane holds, in the accumulator layout,
+// 64 of the 128 components of row l32: the rounded values (what a stored s would hold) are multiplied with the same
+// components of its pair's r, read from a wave-private LDS copy, and one exchange with lane ^ 32 gives the row's
+// score. Maximum and sum over the rows of a pair in the tile are wave reductions; tiles of a pair are merged with the
+// running maximum (online softmax). The weighted sum over rows is taken from the LDS patch the rounded rows are
+// parked in: lane l owns components 2 l and 2 l + 1 and reads one word per row, with the row's weight from
+// v_readlane. p / sum of weights replaces r in the pair's z row.
 #include "segment_ffn_tile.h"
 
 namespace laser {
@@ -77,12 +78,25 @@ __global__ __launch_bounds__(FM_THREADS) void ffn_pool_kernel(
     const int n = (valid_len(lens, pair_user(cand_off, U, C, p), L) + w - 1) / w;
     return __builtin_amdgcn_readfirstlane(n < S ? n : S);
   };
-  // the wave's first pair at or after its k-th that has a valid segment (nvk > 0), else nvk = 0
+  constexpr int LPR = D / 8, RPI = 64 / LPR;
+  const int nr = (MR && recent) ? (r < S ? r : S) : 0;
+  // The wave's first pair at or after its k-th that has a valid segment (nvk > 0), else nvk = 0. Every pair of the
+  // wave is looked at here exactly once, in order, and gets what the tiles never touch: the rows of its segments
+  // without a valid item leave as zeros, and a pair without any has p = 0 and a pooled maximum of zeros.
   auto next_pair = [&](int k, int& nvk) {
     nvk = 0;
     while (pr0 + k * stride < P) {
-      nvk = valid_segments(pr0 + k * stride);
+      const int p = pr0 + k * stride;
+      nvk = valid_segments(p);
+      if (out)
+        for (int i = nvk + lane / LPR; i < S; i += RPI)
+          *reinterpret_cast<u32x4*>(out + ((size_t)p * S + i) * D + (lane % LPR) * 8) = u32x4{0u, 0u, 0u, 0u};
+      if (MR && recent)
+        for (int i = nvk + lane / LPR; i < nr; i += RPI)
+          *reinterpret_cast<u32x4*>(recent + ((size_t)p * r + i) * D + (lane % LPR) * 8) = u32x4{0u, 0u, 0u, 0u};
       if (nvk > 0) break;
+      if (MR && pool) pool[(size_t)p * (D / 2) + lane] = 0u;
+      *reinterpret_cast<f32x2*>(z + (size_t)p * D + 2 * lane) = f32x2{0.0f, 0.0f};
       ++k;
     }
     return k;
@@ -140,24 +154,6 @@ __global__ __launch_bounds__(FM_THREADS) void ffn_pool_kernel(
                         vecs, w1, w2, b1, b2, ln_g, ln_b, tid);
   if (cur.some) fetch_tile(cur);
 
-  constexpr int LPR = D / 8, RPI = 64 / LPR;
-  const int nr = (MR && recent) ? (r < S ? r : S) : 0;
-  // What the tiles never touch, while the first fetches are under way: the rows of the segments without a valid
-  // item leave as zeros, and a pair without any has p = 0 and a pooled maximum of zeros.
-  for (int k = 0; pr0 + k * stride < P; ++k) {
-    const int p = pr0 + k * stride;
-    const int nvk = valid_segments(p);
-    if (out)
-      for (int i = nvk + lane / LPR; i < S; i += RPI)
-        *reinterpret_cast<u32x4*>(out + ((size_t)p * S + i) * D + (lane % LPR) * 8) = u32x4{0u, 0u, 0u, 0u};
-    if (MR && recent)
-      for (int i = nvk + lane / LPR; i < nr; i += RPI)
-        *reinterpret_cast<u32x4*>(recent + ((size_t)p * r + i) * D + (lane % LPR) * 8) = u32x4{0u, 0u, 0u, 0u};
-    if (nvk == 0) {
-      if (MR && pool) pool[(size_t)p * (D / 2) + lane] = 0u;
-      *reinterpret_cast<f32x2*>(z + (size_t)p * D + 2 * lane) = f32x2{0.0f, 0.0f};
-    }
-  }
   ffn_wait_fetches();
   __syncthreads();
   const float* b1s = vecs;
@@ -285,21 +281,31 @@ __global__ __launch_bounds__(FM_THREADS) void ffn_pool_kernel(
         }
       }
     }
-    // rows on their way out, as whole 256-byte rows: tile row j is row a0 + j of A or row j - na of B
-    if (out != nullptr || (MR && cur.a0 < nr) || (MR && nb > 0 && nr > 0)) {
-      const unsigned dBrows = (unsigned)(cur.kB - cur.kA) * (unsigned)stride;   // pairs between A and B
-#pragma unroll
-      for (int b = 0; b < FM_ROWS / RPI; ++b) {
+    // rows on their way out, as whole 256-byte rows: tile row j is row a0 + j of A or row j - na of B. Without the
+    // transformed rows wanted, only the tile rows that belong to the first r of their pair leave (jr: one past the
+    // last of them), four at a time.
+    {
+      const unsigned dBpairs = (unsigned)(cur.kB - cur.kA) * (unsigned)stride;   // pairs between A and B
+      auto rows_out = [&](int b) {
         const int j = b * RPI + lane / LPR;
         const u32x4 val = *reinterpret_cast<const u32x4*>(opr + b * RPI * OP);
         const bool jb = j >= na;
         const int i = jb ? j - na : cur.a0 + j;              // segment index inside its pair
-        const unsigned pj = jb ? dBrows : 0u;                // pair, counted from A
+        const unsigned pj = jb ? dBpairs : 0u;               // pair, counted from A
         if (j < ntot) {
           if (out) *reinterpret_cast<u32x4*>(out + ((size_t)pA * S + (size_t)pj * S + i) * D + (lane % LPR) * 8) = val;
           if (MR && i < nr)
             *reinterpret_cast<u32x4*>(recent + ((size_t)pA * r + (size_t)pj * r + i) * D + (lane % LPR) * 8) = val;
         }
+      };
+      if (out) {
+#pragma unroll
+        for (int b = 0; b < FM_ROWS / RPI; ++b) rows_out(b);
+      } else if (MR) {
+        int jr = nr == 0 ? 0 : (nb > 0 ? na + nr : nr - cur.a0);
+        jr = jr < ntot ? jr : ntot;
+#pragma unroll 1
+        for (int b = 0; b * RPI < jr; ++b) rows_out(b);
       }
     }
     if (nb > 0) {   // A ended; B's sums become the running ones, unless B ended here too
