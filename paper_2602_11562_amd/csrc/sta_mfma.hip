@@ -695,11 +695,10 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
   const int seg_hi = (seg_lo + spw) < S ? (seg_lo + spw) : S;
   int seg_ne = seg_lo;
   while (seg_ne < seg_hi && seg_ne * w < n) ++seg_ne;
+  const int item_end = n < L ? n : L;   // one past the user's last valid item
   auto seg_end = [&](int i) {
-    int e = i * w + w;
-    if (e > L) e = L;
-    if (e > n) e = n;
-    return e;
+    const int e = i * w + w;
+    return e < item_end ? e : item_end;
   };
 
   auto issue_tile = [&](int t0, int hi, int buf) {   // requires t0 < hi
@@ -768,32 +767,44 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
   const bool all_rows = cbase + CW <= C;
   // A finished segment leaves in FU units of two row groups (eight rows, 2 KB per wave), a few per step: all
   // waves of a compute unit storing whole patches in the same step saturate its store path for most of a step
-  // while it idles in the others. flush_units(seg, from, n) stores units from .. from+n-1.
+  // while it idles in the others.
   constexpr int FU = CW / RPI / 2;
   const size_t unit_stride = (size_t)2 * RPI * S * (D * 2);   // bytes between the first rows of two units in H'
-  auto flush_units = [&](int seg, int from, int n) {
+  // where the next unit of the parked segment comes from and goes to (set when a segment is parked, advanced per
+  // unit: recomputed from the unit number in every step they cost a dozen scalar instructions)
+  unsigned char* fl_dst = oU;
+  const unsigned char* fl_src = opr;
+  int fl_row = cbase + lane / LPR;
+  auto flush_units = [&](int n) {   // the next n units of the parked segment
     // scalar work per unit is kept to two 64-bit additions: a wave issues one instruction every few cycles,
     // whatever its kind, and the other wave of the SIMD is at the same point of the same step
-    unsigned char* dst = oU + (size_t)seg * (D * 2) + (size_t)from * unit_stride;
-    const unsigned char* src = opr + from * (2 * RPI * OP);
-    int row = cbase + from * (2 * RPI) + lane / LPR;
 #pragma unroll 1
     for (int b = 0; b < n; ++b) {
-      const u32x4 v0 = *reinterpret_cast<const u32x4*>(src);
-      const u32x4 v1 = *reinterpret_cast<const u32x4*>(src + RPI * OP);
-      if (all_rows || row < C) {
-        // (the s_nop: a store of more than 8 bytes reads its data registers for two more cycles after issue; the
-        // compiler pads its own stores against a following register write, but cannot see into this one)
-        if (NTS) asm volatile("global_store_dwordx4 %0, %1, %2 nt\n\ts_nop 1" ::"v"(ooff), "v"(v0), "s"(dst) : "memory");
-        else asm volatile("global_store_dwordx4 %0, %1, %2\n\ts_nop 1" ::"v"(ooff), "v"(v0), "s"(dst) : "memory");
+      const u32x4 v0 = *reinterpret_cast<const u32x4*>(fl_src);
+      const u32x4 v1 = *reinterpret_cast<const u32x4*>(fl_src + RPI * OP);
+      // (the s_nop: a store of more than 8 bytes reads its data registers for two more cycles after issue; the
+      // compiler pads its own stores against a following register write, but cannot see into this one)
+      if (all_rows) {
+        if (NTS) {
+          asm volatile("global_store_dwordx4 %0, %1, %2 nt\n\ts_nop 1" ::"v"(ooff), "v"(v0), "s"(fl_dst) : "memory");
+          asm volatile("global_store_dwordx4 %0, %1, %2 nt\n\ts_nop 1" ::"v"(ooff2), "v"(v1), "s"(fl_dst) : "memory");
+        } else {
+          asm volatile("global_store_dwordx4 %0, %1, %2\n\ts_nop 1" ::"v"(ooff), "v"(v0), "s"(fl_dst) : "memory");
+          asm volatile("global_store_dwordx4 %0, %1, %2\n\ts_nop 1" ::"v"(ooff2), "v"(v1), "s"(fl_dst) : "memory");
+        }
+      } else {
+        if (fl_row < C) {
+          if (NTS) asm volatile("global_store_dwordx4 %0, %1, %2 nt\n\ts_nop 1" ::"v"(ooff), "v"(v0), "s"(fl_dst) : "memory");
+          else asm volatile("global_store_dwordx4 %0, %1, %2\n\ts_nop 1" ::"v"(ooff), "v"(v0), "s"(fl_dst) : "memory");
+        }
+        if (fl_row + RPI < C) {
+          if (NTS) asm volatile("global_store_dwordx4 %0, %1, %2 nt\n\ts_nop 1" ::"v"(ooff2), "v"(v1), "s"(fl_dst) : "memory");
+          else asm volatile("global_store_dwordx4 %0, %1, %2\n\ts_nop 1" ::"v"(ooff2), "v"(v1), "s"(fl_dst) : "memory");
+        }
       }
-      if (all_rows || row + RPI < C) {
-        if (NTS) asm volatile("global_store_dwordx4 %0, %1, %2 nt\n\ts_nop 1" ::"v"(ooff2), "v"(v1), "s"(dst) : "memory");
-        else asm volatile("global_store_dwordx4 %0, %1, %2\n\ts_nop 1" ::"v"(ooff2), "v"(v1), "s"(dst) : "memory");
-      }
-      dst += unit_stride;
-      src += 2 * RPI * OP;
-      row += 2 * RPI;
+      fl_dst += unit_stride;
+      fl_src += 2 * RPI * OP;
+      fl_row += 2 * RPI;
     }
   };
 
@@ -949,11 +960,11 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
       // waits sit behind a branch, and ahead of the score MFMAs they made the compiler wait for every operand
       // read in flight. The stores still have most of a step to complete before the next fetch wait.
       if (out_seg >= 0) {   // an equal share in every step that is left before the patch is needed again
-        const int steps_left = (nvt + DT_TI - 1) / DT_TI;
+        const int steps_left = (int)((unsigned)(nvt + DT_TI - 1) / DT_TI);
         const int left = FU - out_units;   // n = ceil(left / steps_left), left <= FU = 4, without a division
         static_assert(FU == 4, "the share below is written out for four units");
         const int n = steps_left >= left ? 1 : (steps_left == 1 ? left : 2);
-        flush_units(out_seg, out_units, n);
+        flush_units(n);
         out_units += n;
         if (out_units == FU) out_seg = -1;
       }
@@ -1002,6 +1013,9 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
         }
       out_seg = cur.seg;
       out_units = 0;
+      fl_dst = oU + (size_t)cur.seg * (D * 2);
+      fl_src = opr;
+      fl_row = cbase + lane / LPR;
     }
     if (wave >= NW / 2) issue_next();
     ++done;
@@ -1013,7 +1027,7 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
     if (cur.seg >= seg_ne) break;
     step(scB, scA);
   }
-  if (out_seg >= 0) flush_units(out_seg, out_units, FU - out_units);
+  if (out_seg >= 0) flush_units(FU - out_units);
 
   if (seg_ne < seg_hi) {   // empty segments of the run: exact zeros
     const int ncand = (C - ct * (CW * NW)) < CW * NW ? (C - ct * (CW * NW)) : CW * NW;
@@ -1096,6 +1110,19 @@ static void launch_nw(const StaArgs& a, int nw, int spw, int ctiles, int sruns, 
                        (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens,
                        a.cand_off, a.P, a.C, a.L, a.w, a.S, spw, ctiles, sruns, nsl, (unsigned short*)a.seg_out, a.seg_cnt);
   }
+  else if (nw == 4 && DQ == 128 && D == 128 && tuning_int("LASER_STA_NODMA", 0) == 0) {
+    // 65 to 128 candidates: the same kernel with four waves, one workgroup per compute unit (LDS) and one wave per
+    // SIMD; its deep prefetch needs several segments per workgroup to pay (see sta_mfma_launch)
+    const unsigned blocks = (unsigned)((long long)a.U * ctiles * sruns);
+    if (a.reread)
+      hipLaunchKernelGGL((sta_mfma_dma_kernel<4, false>), dim3(blocks), dim3(256), 0, a.stream,
+                         (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens,
+                         a.cand_off, a.P, a.C, a.L, a.w, a.S, spw, ctiles, sruns, nsl, (unsigned short*)a.seg_out, a.seg_cnt);
+    else
+      hipLaunchKernelGGL((sta_mfma_dma_kernel<4, true>), dim3(blocks), dim3(256), 0, a.stream,
+                         (const unsigned short*)a.q, (const unsigned short*)a.k, (const unsigned short*)a.v, a.lens,
+                         a.cand_off, a.P, a.C, a.L, a.w, a.S, spw, ctiles, sruns, nsl, (unsigned short*)a.seg_out, a.seg_cnt);
+  }
   else if (nw == 4) launch_one<DQ, D, 4, 1>(a, spw, ctiles, sruns, nsl);
   else if (nw == 2) launch_one<DQ, D, 2, 1>(a, spw, ctiles, sruns, nsl);
   else launch_one<DQ, D, 1, 1>(a, spw, ctiles, sruns, nsl);
@@ -1112,6 +1139,16 @@ laser_status sta_mfma_launch(const StaArgs& a) {
   const long long want = 2048 / nw;
   int spw = 1;
   while (spw < 8 && (long long)a.U * ctiles * ((a.S + 2 * spw - 1) / (2 * spw)) >= want) spw *= 2;
+  // the direct-to-LDS kernels take a compute unit's LDS per workgroup: as many segments per workgroup as bring the
+  // launch down to one round of 256 workgroups, eight at most (16 users x 128 candidates x 40 segments: 640
+  // workgroups of one segment 32.9 us in the register-staged form, 224 of three segments 26.8 us in this one)
+  const bool direct = a.heads == 1 && !a.softmax && a.d_q == 128 && a.d == 128 && (nw == 8 || nw == 4) &&
+                      tuning_int("LASER_STA_NODMA", 0) == 0;
+  if (direct) {
+    const long long per_seg = (long long)a.U * ctiles * a.S;
+    spw = (int)((per_seg + 255) / 256 < 8 ? (per_seg + 255) / 256 : 8);
+    if (spw < 1) spw = 1;
+  }
   const int spw_forced = tuning_int("LASER_STA_SPW", 0);   // tuning builds only
   if (spw_forced >= 1 && spw_forced <= 64) spw = spw_forced;
   const int sruns = (a.S + spw - 1) / spw;

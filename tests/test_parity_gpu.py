@@ -153,6 +153,10 @@ EDGE_SPECS = {
     "many_candidates_ragged": _spec("bf16", 5, 200, 1000, 128, 128, 100, 1, 2011),   # w not a multiple of the tile
     "many_candidates_small_w": _spec("bf16", 2, 130, 300, 128, 128, 10, 1, 2012),    # segments shorter than a tile
     "many_candidates_two_tiles": _spec("bf16", 3, 257, 512, 128, 128, 128, 1, 2013),  # two candidate tiles per user
+    # 65 to 128 candidates with d_q = d = 128: the same kernel with four waves
+    "four_waves_ragged": _spec("bf16", 5, 100, 1000, 128, 128, 100, 1, 2018),
+    "four_waves_small_w": _spec("bf16", 2, 96, 300, 128, 128, 10, 1, 2019),
+    "four_waves_runs_of_segments": _spec("bf16", 8, 80, 2048, 128, 128, 32, 1, 2020),   # two segments per workgroup
     # short segments with few candidates per user: the wave-per-segment streaming form (C = 1 is how the paper's
     # own training batches look: one target per sample, Sec. 4.1.2)
     "paper_default_one_target": _spec("bf16", 6, 1, 1000, 128, 32, 10, 2, 2014),
@@ -169,6 +173,9 @@ EDGE_LENS = {
     "many_candidates_ragged": [1000, 333, 0, 37, 32],
     "many_candidates_small_w": [300, 95],
     "many_candidates_two_tiles": [512, 1, 200],
+    "four_waves_ragged": [1000, 333, 0, 37, 32],
+    "four_waves_small_w": [300, 95],
+    "four_waves_runs_of_segments": [2048, 2047, 1000, 33, 32, 0, 1500, 64],
     "paper_default_one_target": [1000, 995, 10, 9, 0, 123],
     "short_segments_three_candidates": [500, 49, 24],
     "short_segments_wide_keys": [203, 6],
