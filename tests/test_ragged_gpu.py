@@ -19,6 +19,8 @@ laser = pytest.importorskip("paper_2602_11562_amd")
 CASES = {
     # dtype, L, d_q, d, w, M, C_max, counts per user, lens per user
     "matrix_core_direct_to_lds": ("bf16", 1024 + 128, 128, 128, 128, 1, 256, [256, 100, 0, 33], [1152, 700, 1152, 129]),
+    "matrix_core_direct_to_lds_four_waves": ("bf16", 1024 + 128, 128, 128, 128, 1, 128, [128, 65, 0, 33, 1],
+                                             [1152, 700, 1152, 129, 1000]),
     "matrix_core_eight_waves": ("bf16", 640, 64, 128, 64, 1, 200, [200, 1, 129], [640, 65, 300]),
     "matrix_core_two_waves": ("bf16", 512, 64, 64, 64, 2, 64, [64, 33, 1, 0, 17], [512, 100, 64, 512, 0]),
     "streaming_long_segments": ("bf16", 1024, 64, 64, 256, 1, 8, [1, 8, 0, 3], [1024, 300, 1024, 257]),
