@@ -835,10 +835,16 @@ __global__ __launch_bounds__(64 * NW) void sta_mfma_dma_kernel(const unsigned sh
       fbuf = 1;
     }
 #pragma unroll 1
-    for (int a = fetched; a < DT_AHEAD; ++a) issue_next();
+    for (int a = fetched; a < 2; ++a) issue_next();
   }
   if (srun == 0 && ct == 0) write_seg_cnt(seg_cnt, u, n, L, w, S, tid, NT);
   wait_tile(1);   // tiles 0 and 1, and the queries, which are older (with nothing requested: everything)
+  // the other tiles of the head start are requested only now: in the first microseconds every workgroup of the
+  // launch asks for its queries and first tiles at once, and what is asked for later arrives sooner
+  if (any) {
+#pragma unroll 1
+    for (int a = fetched; a < DT_AHEAD; ++a) issue_next();
+  }
   __syncthreads();
 
   bf16x8 qreg[KSTEPS], ka[KSTEPS], va[2][DB];
