@@ -67,6 +67,15 @@ int main() {
   EXPECT(laser_segment_ffn_forward(A, nullptr, A, F, A, F, F, F, 2, 3, 64, 16, BIG, 8, 1e-5f, bf, A, nullptr), LASER_ERR_SHAPE);
   EXPECT(laser_segment_ffn_forward_variant(A, nullptr, A, F, A, F, F, F, 2, 3, 64, 16, 32, 8, 1e-5f, bf, A, nullptr, (laser_ffn_variant)9), LASER_ERR_UNSUPPORTED);
   EXPECT(laser_segment_ffn_forward_ragged(A, nullptr, I, A, F, A, F, F, F, 3, 8, 25, 64, 16, 32, 8, 1e-5f, bf, A, nullptr), LASER_ERR_SHAPE);
+  // FFN + LayerNorm feeding GSTA: missing argument, bad shape, and the cases in which no kernel takes both steps
+  // and there is no seg_out to put the rows between them (d = 64; two layers); 32 GB of H' are refused as a shape
+  // (the one-pass kernel's 32-bit row offsets are covered by that limit)
+  EXPECT(laser_ffn_gsta_forward(A, A, A, A, A, nullptr, A, F, nullptr, F, F, F, 2, 3, 64, 128, 128, 8, 1, 1e-5f, bf, A, F, nullptr), LASER_ERR_NULL);
+  EXPECT(laser_ffn_gsta_forward(A, A, A, A, A, nullptr, A, F, A, F, F, F, 2, 3, 64, 128, BIG, 8, 1, 1e-5f, bf, A, F, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_ffn_gsta_forward(A, A, A, A, A, nullptr, A, F, A, F, F, F, 2, 3, 64, 64, 64, 8, 1, 1e-5f, bf, nullptr, F, nullptr), LASER_ERR_UNSUPPORTED);
+  EXPECT(laser_ffn_gsta_forward(A, A, A, A, A, nullptr, A, F, A, F, F, F, 2, 3, 64, 128, 128, 8, 2, 1e-5f, bf, nullptr, F, nullptr), LASER_ERR_UNSUPPORTED);
+  EXPECT(laser_ffn_gsta_forward(A, A, A, A, A, nullptr, A, F, A, F, F, F, 4096, 256, 2048, 128, 128, 16, 1, 1e-5f, bf, nullptr, F, nullptr), LASER_ERR_SHAPE);
+  EXPECT(laser_ffn_gsta_forward_multires(A, A, A, A, A, nullptr, A, F, A, F, F, F, 2, 3, 64, 128, 128, 8, 1, 1e-5f, bf, A, F, 9, A, A, nullptr), LASER_ERR_SHAPE);
   EXPECT(laser_project_q_forward(A, A, BIG, BIG, 16, 8, bf, A, nullptr), LASER_ERR_SHAPE);
   EXPECT(laser_project_q_forward(A, A, 2, 3, BIG, 8, bf, A, nullptr), LASER_ERR_SHAPE);
   EXPECT(laser_project_kv_forward(A, A, A, 2, 64, 16, BIG, 16, bf, A, A, nullptr), LASER_ERR_SHAPE);
